@@ -1,0 +1,172 @@
+"""Seeded synthetic inputs for the int4 decoder-layer workloads.
+
+This module serves BOTH the CPU oracle's tests and the HIP path's tests and
+benchmark, so it holds none of the layer's arithmetic: it only draws random
+tensors, turns fp32 weights into the packed storage format the layer consumes
+(that is input preparation, the inverse of nothing the layer computes -- the
+layer only ever *decodes*), and names the workload shapes.
+
+Everything is a pure function of (seed, tensor id): the generator is numpy's
+counter-based Philox keyed with those two integers, so any tensor can be
+regenerated alone, on any machine, without materialising the whole model.
+
+Stand-in statement: the paper evaluates trained Llama-family checkpoints
+(Sec. 5.1, Sec. 5.3); none is available here, so weights are random
+N(0, 0.02^2), activations and pre-filled cache entries N(0, 1), norm weights
+1 + 0.1 N(0, 1) -- same shapes, dtypes and storage format as the real thing.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Dict, Tuple
+
+import numpy as np
+
+GROUP = 32          # quantisation group along k
+NIBBLES = 8         # codes per uint32 word
+
+
+@dataclass(frozen=True)
+class LayerShape:
+    name: str
+    hidden: int
+    n_heads: int
+    n_kv_heads: int
+    head_dim: int
+    ffn: int
+    rms_eps: float = 1e-5
+    rope_base: float = 10000.0
+    n_layers: int = 1
+    vocab: int = 32000
+
+    @property
+    def qkv_rows(self) -> int:
+        return (self.n_heads + 2 * self.n_kv_heads) * self.head_dim
+
+    def matrices(self) -> Dict[str, Tuple[int, int]]:
+        """name -> (m, k) of the four quantised matrices of one layer."""
+        H, F = self.hidden, self.ffn
+        return {"wqkv": (self.qkv_rows, H), "wo": (H, self.n_heads * self.head_dim),
+                "wgu": (2 * F, H), "wdown": (H, F)}
+
+    def params_per_layer(self) -> int:
+        return sum(m * k for m, k in self.matrices().values())
+
+    def packed_bytes_per_layer(self) -> int:
+        return sum(m * (k // 2) + m * ((k + GROUP - 1) // GROUP) * 2 for m, k in self.matrices().values())
+
+    def kv_bytes_per_token(self) -> int:
+        return 2 * self.n_kv_heads * self.head_dim * 2
+
+
+TINY = LayerShape("tiny", hidden=256, n_heads=4, n_kv_heads=4, head_dim=64, ffn=688)
+LLAMA7B = LayerShape("llama2-7b", hidden=4096, n_heads=32, n_kv_heads=32, head_dim=128, ffn=11008, n_layers=32)
+LLAMA70B = LayerShape("llama2-70b", hidden=8192, n_heads=64, n_kv_heads=8, head_dim=128, ffn=28672, n_layers=80)
+
+# tensor-id space: (layer * 16 + slot) for weights, fixed bases for the rest
+_SLOT = {"wqkv": 0, "wo": 1, "wgu": 2, "wdown": 3, "norm_attn": 4, "norm_ffn": 5}
+TID_X = 1 << 20          # + call index
+TID_KV = 2 << 20         # + layer * 2 + {0: K, 1: V}
+TID_LENS = 3 << 20
+TID_EMBED = 4 << 20
+TID_LMHEAD = (4 << 20) + 1
+TID_FINAL_NORM = (4 << 20) + 2
+TID_IDS = (4 << 20) + 3
+
+
+def rng(seed: int, tensor_id: int) -> np.random.Generator:
+    return np.random.Generator(np.random.Philox(key=[int(seed), int(tensor_id)]))
+
+
+def normal_f32(seed: int, tensor_id: int, shape, std: float = 1.0, mean: float = 0.0) -> np.ndarray:
+    a = rng(seed, tensor_id).standard_normal(size=shape, dtype=np.float32)
+    if std != 1.0:
+        a *= np.float32(std)
+    if mean != 0.0:
+        a += np.float32(mean)
+    return a
+
+
+def normal_f16_bits(seed: int, tensor_id: int, shape, std: float = 1.0, mean: float = 0.0) -> np.ndarray:
+    """fp16 tensor returned as its uint16 bit patterns (the wire format of every fp16 buffer)."""
+    return normal_f32(seed, tensor_id, shape, std, mean).astype(np.float16).view(np.uint16)
+
+
+def f16_bits_to_f32(bits: np.ndarray) -> np.ndarray:
+    return np.ascontiguousarray(bits).view(np.float16).astype(np.float32)
+
+
+def pack_codes(codes: np.ndarray) -> np.ndarray:
+    """codes uint8 [m,k] in 0..15 -> uint32 [m,k/8]; element c%8 goes to bits 4*(c%8)..+3."""
+    m, k = codes.shape
+    assert k % NIBBLES == 0
+    c = codes.reshape(m, k // NIBBLES, NIBBLES).astype(np.uint32)
+    word = np.zeros((m, k // NIBBLES), dtype=np.uint32)
+    for j in range(NIBBLES):
+        word |= c[:, :, j] << np.uint32(4 * j)
+    return word
+
+
+def quantize_q4(w: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+    """Symmetric int4, group 32 along k (last group short if k % 32 != 0).
+
+    Per group: scale = fp16(max|w| / 7); codes = clamp(rint(w / scale), -7, 7) + 8,
+    an all-zero group (scale 0) gets code 8 everywhere.  Returns
+    (qweight uint32 [m,k/8], scales uint16 bits [m,ceil(k/32)])."""
+    w = np.ascontiguousarray(w, dtype=np.float32)
+    m, k = w.shape
+    assert k % NIBBLES == 0
+    G = (k + GROUP - 1) // GROUP
+    pad = G * GROUP - k
+    wp = np.pad(w, ((0, 0), (0, pad))) if pad else w
+    grp = wp.reshape(m, G, GROUP)
+    amax = np.abs(grp).max(axis=2)
+    s16 = (amax / np.float32(7.0)).astype(np.float16)
+    s32 = s16.astype(np.float32)
+    safe = np.where(s32 > 0, s32, np.float32(1.0))
+    q = np.rint(grp / safe[:, :, None])
+    q = np.clip(q, -7, 7)
+    q = np.where((s32 > 0)[:, :, None], q, 0.0)
+    codes = (q + 8).astype(np.uint8).reshape(m, G * GROUP)[:, :k]
+    return pack_codes(np.ascontiguousarray(codes)), s16.view(np.uint16)
+
+
+def qmat(seed: int, tensor_id: int, m: int, k: int, std: float = 0.02) -> Tuple[np.ndarray, np.ndarray]:
+    """One random quantised matrix; generated in row slabs to bound host memory."""
+    qs, ss = [], []
+    g = rng(seed, tensor_id)
+    slab = max(1, (1 << 25) // k)
+    for r0 in range(0, m, slab):
+        rows = min(slab, m - r0)
+        w = g.standard_normal(size=(rows, k), dtype=np.float32) * np.float32(std)
+        q, s = quantize_q4(w)
+        qs.append(q), ss.append(s)
+    return np.concatenate(qs, axis=0), np.concatenate(ss, axis=0)
+
+
+def layer_weights(shape: LayerShape, seed: int, layer: int = 0) -> Dict[str, np.ndarray]:
+    """Host arrays of one layer: '<mat>.q' uint32, '<mat>.s' uint16, 'norm_attn'/'norm_ffn' uint16."""
+    out: Dict[str, np.ndarray] = {}
+    for name, (m, k) in shape.matrices().items():
+        q, s = qmat(seed, layer * 16 + _SLOT[name], m, k)
+        out[name + ".q"], out[name + ".s"] = q, s
+    for name in ("norm_attn", "norm_ffn"):
+        out[name] = normal_f16_bits(seed, layer * 16 + _SLOT[name], (shape.hidden,), std=0.1, mean=1.0)
+    return out
+
+
+def activations(shape: LayerShape, seed: int, call: int, n: int) -> np.ndarray:
+    """fp16 bits [n, hidden], N(0,1)."""
+    return normal_f16_bits(seed, TID_X + call, (n, shape.hidden))
+
+
+def kv_prefill(shape: LayerShape, seed: int, slots: int, capacity: int, layer: int = 0):
+    """Two fp16-bit caches [slots, capacity, g, d] filled with N(0,1) everywhere (callers
+    treat only entries below each sequence's past length as meaningful)."""
+    dims = (slots, capacity, shape.n_kv_heads, shape.head_dim)
+    return (normal_f16_bits(seed, TID_KV + 2 * layer, dims), normal_f16_bits(seed, TID_KV + 2 * layer + 1, dims))
+
+
+def uniform_lengths(seed: int, count: int, lo: int, hi: int, stream: int = 0) -> np.ndarray:
+    """count integers uniform in [lo, hi] inclusive."""
+    return rng(seed, TID_LENS + stream).integers(lo, hi + 1, size=count, dtype=np.int32)
