@@ -1,0 +1,178 @@
+/*
+ * relax_mi355.h -- C ABI of the MI355X (gfx950) implementation of the
+ * dynamic-shape int4 Llama-style decoder layer behind the LLM results of
+ * "Relax: Composable Abstractions for End-to-End Dynamic Machine Learning"
+ * (arXiv 2311.02103).
+ *
+ * Calling rules, each taken from the paper's statement of the problem:
+ *   - Destination-passing style (Sec. 3.3): the caller owns and passes every
+ *     output, the KV cache and the workspace; the library allocates nothing
+ *     and keeps no hidden state between calls.
+ *   - Symbolic dimensions are ordinary runtime integers passed next to the
+ *     tensors (Sec. 3.3, the extra symbolic arguments of call_tir; Sec. 4.1,
+ *     the extra parameter bound to n).  n (rows in the call), L (KV length)
+ *     and B (sequences) may change on every call; ONE compiled library serves
+ *     every value -- nothing is specialised, rebuilt or cached per shape
+ *     (Sec. 5.1: compiled once for arbitrary batch size and sequence length).
+ *     Only the static model dimensions in relax_layer_dims are treated as
+ *     constants of a model (Sec. 3.3: specialise static dims, keep n dynamic).
+ *   - Scratch memory of the kernels (split-L attention partials, staging) is
+ *     lifted to one caller-provided workspace sized from upper bounds on the
+ *     symbolic dims (Sec. 4.3 upper-bound planning, Sec. 4.4 workspace
+ *     lifting): relax_workspace_bytes(dims, n_max, L_max, B_max).
+ *   - Shape constraints are checked at the function boundary and reported as
+ *     error codes (Sec. 3.2 match_cast runtime checks, Sec. 4.1 boundary
+ *     checks).  All checks run on the host BEFORE anything is enqueued: a call
+ *     that returns an error has written nothing.
+ *   - The int4 decode never materialises a dense weight matrix: it is fused
+ *     into the consuming matmul (Sec. 4.2, decode_q4 case study); a matrix-
+ *     vector kernel serves small n, an MFMA GEMM serves large n, chosen from
+ *     the runtime value of n inside the same entry point (Sec. 5.1).
+ *
+ * Memory spaces: every pointer is a DEVICE pointer unless its comment says
+ * "host".  fp16 tensors are passed as uint16_t bit patterns.  All work is
+ * enqueued on `stream` (a hipStream_t passed as void*; NULL = default stream)
+ * and is asynchronous; the return value reports validation / launch errors.
+ *
+ * Storage format of a quantised matrix W[m,k] (k % 8 == 0):
+ *   q : uint32 [m, k/8]        element c of row r is nibble c%8 (bits
+ *                              4*(c%8)..+3) of word q[r*(k/8) + c/8];
+ *                              code u in 0..15 stands for the integer u-8
+ *   s : fp16   [m, ceil(k/32)] one scale per 32 consecutive c (last group
+ *                              short when k % 32 != 0)
+ *   W[r,c] = (u - 8) * s[r, c/32]
+ */
+#ifndef RELAX_MI355_H
+#define RELAX_MI355_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t relax_status;
+enum {
+    RELAX_OK              =  0,
+    RELAX_ERR_NULL        = -1,   /* a required pointer is NULL                          */
+    RELAX_ERR_SHAPE       = -2,   /* n<1, k%8!=0, sum(q_lens)!=n, L_b<q_len_b, h%g!=0... */
+    RELAX_ERR_CAPACITY    = -3,   /* L_b > kv_capacity, slot out of range                */
+    RELAX_ERR_WORKSPACE   = -4,   /* ws_bytes below relax_workspace_bytes(...)           */
+    RELAX_ERR_UNSUPPORTED = -5,   /* head_dim not in {64,128}, group != 32, k too large  */
+    RELAX_ERR_HIP         = -6    /* the HIP runtime reported a launch error             */
+};
+
+typedef void *relax_stream;       /* hipStream_t */
+
+/* Static dimensions of a layer (constants of a model, not symbolic).                    */
+typedef struct {
+    int32_t hidden;               /* H                                                   */
+    int32_t n_heads;              /* h  query heads                                      */
+    int32_t n_kv_heads;           /* g  KV heads, h % g == 0                             */
+    int32_t head_dim;             /* d  in {64, 128}                                     */
+    int32_t ffn;                  /* F                                                   */
+    int32_t group;                /* quantisation group, must be 32                      */
+    float   rms_eps;
+    float   rope_base;
+    int32_t kv_capacity;          /* L_cap: positions per cache slot                     */
+    int32_t kv_slots;             /* number of cache slots                               */
+} relax_layer_dims;
+
+/* A quantised matrix in the storage format described at the top.                        */
+typedef struct {
+    const uint32_t *q;            /* [m, k/8]                                            */
+    const uint16_t *s;            /* [m, ceil(k/32)] fp16                                */
+    int32_t m, k;
+} relax_qmat;
+
+typedef struct {
+    relax_qmat wqkv;              /* rows [Wq (h*d) ; Wk (g*d) ; Wv (g*d)], k = H        */
+    relax_qmat wo;                /* [H, h*d]                                            */
+    relax_qmat wgu;               /* rows [gate (F) ; up (F)], k = H                     */
+    relax_qmat wdown;             /* [H, F]                                              */
+    const uint16_t *norm_attn;    /* [H] fp16                                            */
+    const uint16_t *norm_ffn;     /* [H] fp16                                            */
+} relax_layer_weights;
+
+/* KV cache of one layer.  K holds keys AFTER rotary embedding.                          */
+typedef struct {
+    uint16_t *k;                  /* [kv_slots, kv_capacity, g, d] fp16                  */
+    uint16_t *v;                  /* [kv_slots, kv_capacity, g, d] fp16                  */
+    const float *rope;            /* [kv_capacity, d/2, 2] (cos, sin) of pos*base^(-2t/d),
+                                     filled once by relax_rope_table_init                */
+} relax_kv_cache;
+
+/* The ragged batch of one call.  Rows of a sequence are contiguous and in order; row i
+ * of sequence b sits at position kv_lens[b] - q_lens[b] + i.  A prefill of one sequence
+ * is (B=1, {n}, {L}); a batched decode step is (B=n, {1,...}, {L_b}).                   */
+typedef struct {
+    int32_t B;
+    const int32_t *q_lens;        /* host [B], each >= 1, sum == n                       */
+    const int32_t *kv_lens;       /* host [B], L_b AFTER this call's rows are appended   */
+    const int32_t *slots;         /* host [B] cache slot per sequence; NULL: slot b = b  */
+} relax_seqs;
+
+/* Bytes of workspace that any call with n <= n_max, every L_b <= L_max and B <= B_max
+ * needs (Sec. 4.3: static plan from upper bounds; Sec. 4.4: lifted kernel scratch).
+ * Returns 0 if dims is NULL or inconsistent.                                            */
+size_t relax_workspace_bytes(const relax_layer_dims *dims, int32_t n_max, int32_t L_max, int32_t B_max);
+
+/* Bytes of the rotary table for these dims, and the call that fills it on the device
+ * (angles, cos and sin evaluated in fp64, stored as fp32).  Pairing is half-split:
+ * element t < d/2 rotates with element t + d/2 at frequency base^(-2t/d).               */
+size_t       relax_rope_table_bytes(const relax_layer_dims *dims);
+relax_status relax_rope_table_init(const relax_layer_dims *dims, float *table, relax_stream stream);
+
+/* out[i,r] = sum_c x[i,c] * W[r,c] with W decoded on the fly (Sec. 4.2 fused decode;
+ * Sec. 5.1 matrix-vector kernel at small n, GEMM otherwise -- picked from n at run time).
+ * x [n,k] fp16, out [n,m] fp16, fp32 accumulation.  ws may be NULL when ws_bytes == 0
+ * is enough (it is for this call today; the argument is part of the lifted-workspace
+ * convention).  Errors: NULL, SHAPE (n<1, m<1, k<8, k%8), UNSUPPORTED (k > 65536).      */
+relax_status relax_dequant_matmul(const uint16_t *x, const relax_qmat *w, uint16_t *out, int32_t n,
+                                  void *ws, size_t ws_bytes, relax_stream stream);
+
+/* Two optional parts (the norm and the rotary step are separated by the QKV matmul, so
+ * they cannot be one pass; either part is skipped when its first pointer is NULL):
+ *  part 1  y[i,:] = x[i,:] * rsqrt(mean(x[i,:]^2) + eps) * w      x,y [n,H] fp16, w [H]
+ *  part 2  rotary embedding in place on the q and k columns of qkv [n,(h+2g)d] fp16
+ *          (row layout [q | k | v]) at each row's position, then K[slot][pos] = k,
+ *          V[slot][pos] = v.  Needs dims, cache (with rope table) and seqs.
+ * Errors: NULL, SHAPE, CAPACITY, UNSUPPORTED as listed in the enum.                     */
+relax_status relax_rmsnorm_rope(const uint16_t *x, const uint16_t *w, uint16_t *y, int32_t n, int32_t H,
+                                float eps, uint16_t *qkv, const relax_layer_dims *dims,
+                                const relax_kv_cache *cache, const relax_seqs *seqs, relax_stream stream);
+
+/* Causal attention over the cache (Sec. 4.2, the fused attention operator; KV length is
+ * symbolic).  q [n,h,d] fp16 (already rotated), out [n,h,d] fp16.  Row i of sequence b
+ * attends to cache positions 0..pos_i of its slot, which must already hold this call's
+ * keys/values; nothing beyond pos_i is read.  Query head j uses KV head j / (h/g).
+ * softmax scale 1/sqrt(d), fp32 softmax.  Decode rows are split along L over many
+ * workgroups and merged from the workspace.                                             */
+relax_status relax_attention(const uint16_t *q, const relax_kv_cache *cache, const relax_seqs *seqs,
+                             const relax_layer_dims *dims, uint16_t *out, int32_t n,
+                             void *ws, size_t ws_bytes, relax_stream stream);
+
+/* The whole layer on n rows:
+ *   xn = RMSNorm(x; norm_attn); qkv = xn Wqkv^T; rotary(q,k); append k,v;
+ *   a = attention(q); x1 = x + a Wo^T;
+ *   gu = RMSNorm(x1; norm_ffn) Wgu^T; act = silu(gate) * up; out = x1 + act Wdown^T
+ * x, out [n,H] fp16 (out may alias x).  The cache is updated at positions
+ * kv_lens[b]-q_lens[b] .. kv_lens[b]-1 of each sequence's slot.                         */
+relax_status relax_decoder_layer(const relax_layer_dims *dims, const relax_layer_weights *weights,
+                                 const uint16_t *x, const relax_kv_cache *cache, const relax_seqs *seqs,
+                                 uint16_t *out, int32_t n, void *ws, size_t ws_bytes, relax_stream stream);
+
+/* Test exports for the bit-exactness requirement on decoding and indexing: the same
+ * device decode routine the matmul kernels use, written out densely.
+ * relax_unpack_int4: out int8 [m,k] in -8..7.  relax_dequantize: out fp32 [m,k].        */
+relax_status relax_unpack_int4(const relax_qmat *w, int8_t *out, relax_stream stream);
+relax_status relax_dequantize(const relax_qmat *w, float *out, relax_stream stream);
+
+/* Build identity of the loaded binary (one binary serves every shape).                  */
+const char *relax_build_id(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,231 @@
+"""ctypes binding of librelax_mi355.so: argument marshalling only.
+
+Every function has the name and argument order of its C declaration in
+include/relax_mi355.h and returns the C status code.  Tensors are torch CUDA
+tensors (PyTorch is used for device memory and streams, nothing else) or raw
+integer device addresses; fp16 buffers may be torch.float16 or torch.uint16/int16.
+There is no fallback: if the HIP library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional, Sequence, Union
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "librelax_mi355.so")
+
+OK, ERR_NULL, ERR_SHAPE, ERR_CAPACITY, ERR_WORKSPACE, ERR_UNSUPPORTED, ERR_HIP = 0, -1, -2, -3, -4, -5, -6
+STATUS_NAMES = {0: "RELAX_OK", -1: "RELAX_ERR_NULL", -2: "RELAX_ERR_SHAPE", -3: "RELAX_ERR_CAPACITY",
+                -4: "RELAX_ERR_WORKSPACE", -5: "RELAX_ERR_UNSUPPORTED", -6: "RELAX_ERR_HIP"}
+
+
+class RelaxError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        super().__init__("%s returned %s" % (where, STATUS_NAMES.get(status, status)))
+        self.status = status
+
+
+def check(status: int, where: str = "relax call") -> None:
+    if status != OK:
+        raise RelaxError(status, where)
+
+
+class LayerDims(C.Structure):
+    _fields_ = [("hidden", C.c_int32), ("n_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("ffn", C.c_int32), ("group", C.c_int32), ("rms_eps", C.c_float), ("rope_base", C.c_float),
+                ("kv_capacity", C.c_int32), ("kv_slots", C.c_int32)]
+
+
+class QMatC(C.Structure):
+    _fields_ = [("q", C.c_void_p), ("s", C.c_void_p), ("m", C.c_int32), ("k", C.c_int32)]
+
+
+class LayerWeightsC(C.Structure):
+    _fields_ = [("wqkv", QMatC), ("wo", QMatC), ("wgu", QMatC), ("wdown", QMatC),
+                ("norm_attn", C.c_void_p), ("norm_ffn", C.c_void_p)]
+
+
+class KVCacheC(C.Structure):
+    _fields_ = [("k", C.c_void_p), ("v", C.c_void_p), ("rope", C.c_void_p)]
+
+
+class SeqsC(C.Structure):
+    _fields_ = [("B", C.c_int32), ("q_lens", C.POINTER(C.c_int32)), ("kv_lens", C.POINTER(C.c_int32)),
+                ("slots", C.POINTER(C.c_int32))]
+
+
+_lib = None
+
+_SIGNATURES = {
+    "relax_build_id": (C.c_char_p, []),
+    "relax_workspace_bytes": (C.c_size_t, [C.POINTER(LayerDims), C.c_int32, C.c_int32, C.c_int32]),
+    "relax_rope_table_bytes": (C.c_size_t, [C.POINTER(LayerDims)]),
+    "relax_rope_table_init": (C.c_int32, [C.POINTER(LayerDims), C.c_void_p, C.c_void_p]),
+    "relax_dequant_matmul": (C.c_int32, [C.c_void_p, C.POINTER(QMatC), C.c_void_p, C.c_int32, C.c_void_p, C.c_size_t,
+                                         C.c_void_p]),
+    "relax_rmsnorm_rope": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_void_p,
+                                       C.POINTER(LayerDims), C.POINTER(KVCacheC), C.POINTER(SeqsC), C.c_void_p]),
+    "relax_attention": (C.c_int32, [C.c_void_p, C.POINTER(KVCacheC), C.POINTER(SeqsC), C.POINTER(LayerDims), C.c_void_p,
+                                    C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "relax_decoder_layer": (C.c_int32, [C.POINTER(LayerDims), C.POINTER(LayerWeightsC), C.c_void_p, C.POINTER(KVCacheC),
+                                        C.POINTER(SeqsC), C.c_void_p, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "relax_unpack_int4": (C.c_int32, [C.POINTER(QMatC), C.c_void_p, C.c_void_p]),
+    "relax_dequantize": (C.c_int32, [C.POINTER(QMatC), C.c_void_p, C.c_void_p]),
+}
+EXPORTS = tuple(_SIGNATURES)
+
+
+def lib():
+    """Loads the HIP library; raises (never falls back) when it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError("librelax_mi355.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                              "(or python paper_2311_02103_amd/build.py) first")
+        handle = C.CDLL(LIB_PATH)
+        for name, (res, args) in _SIGNATURES.items():
+            fn = getattr(handle, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = handle
+    return _lib
+
+
+Ptr = Union[None, int, "torch.Tensor"]  # noqa: F821
+
+
+def _ptr(t: Ptr) -> Optional[int]:
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    if not t.is_contiguous():
+        raise ValueError("tensor must be contiguous")
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        if torch.cuda.is_available():
+            return torch.cuda.current_stream().cuda_stream or None
+        return None
+    if isinstance(stream, int):
+        return stream or None
+    return stream.cuda_stream or None
+
+
+def _ref(obj):
+    return None if obj is None else C.byref(obj)
+
+
+@dataclass
+class QMat:
+    """A quantised matrix on the device: q int32/uint32 [m,k/8], s fp16 [m,ceil(k/32)]."""
+    q: Ptr
+    s: Ptr
+    m: int
+    k: int
+
+    def c(self) -> QMatC:
+        return QMatC(_ptr(self.q), _ptr(self.s), self.m, self.k)
+
+
+@dataclass
+class LayerWeights:
+    wqkv: QMat
+    wo: QMat
+    wgu: QMat
+    wdown: QMat
+    norm_attn: Ptr
+    norm_ffn: Ptr
+
+    def c(self) -> LayerWeightsC:
+        return LayerWeightsC(self.wqkv.c(), self.wo.c(), self.wgu.c(), self.wdown.c(), _ptr(self.norm_attn),
+                             _ptr(self.norm_ffn))
+
+
+@dataclass
+class KVCache:
+    k: Ptr
+    v: Ptr
+    rope: Ptr
+
+    def c(self) -> KVCacheC:
+        return KVCacheC(_ptr(self.k), _ptr(self.v), _ptr(self.rope))
+
+
+class Seqs:
+    """Host-side ragged descriptor; kv_lens are lengths AFTER this call's rows are appended."""
+
+    def __init__(self, q_lens: Sequence[int], kv_lens: Sequence[int], slots: Optional[Sequence[int]] = None):
+        arr = lambda v: (C.c_int32 * len(v))(*[int(e) for e in v])
+        self.B = len(q_lens)
+        self._q, self._kv = arr(q_lens), arr(kv_lens)
+        self._sl = None if slots is None else arr(slots)
+
+    def c(self) -> SeqsC:
+        ip = C.POINTER(C.c_int32)
+        return SeqsC(self.B, C.cast(self._q, ip), C.cast(self._kv, ip), None if self._sl is None else C.cast(self._sl, ip))
+
+
+def make_dims(hidden, n_heads, n_kv_heads, head_dim, ffn, kv_capacity, kv_slots=1, rms_eps=1e-5, rope_base=10000.0,
+              group=32) -> LayerDims:
+    return LayerDims(hidden, n_heads, n_kv_heads, head_dim, ffn, group, rms_eps, rope_base, kv_capacity, kv_slots)
+
+
+def relax_build_id() -> str:
+    return lib().relax_build_id().decode()
+
+
+def relax_workspace_bytes(dims: Optional[LayerDims], n_max: int, L_max: int, B_max: int) -> int:
+    return int(lib().relax_workspace_bytes(_ref(dims), n_max, L_max, B_max))
+
+
+def relax_rope_table_bytes(dims: Optional[LayerDims]) -> int:
+    return int(lib().relax_rope_table_bytes(_ref(dims)))
+
+
+def relax_rope_table_init(dims: Optional[LayerDims], table: Ptr, stream=None) -> int:
+    return lib().relax_rope_table_init(_ref(dims), _ptr(table), _stream(stream))
+
+
+def relax_dequant_matmul(x: Ptr, w: Optional[QMat], out: Ptr, n: int, ws: Ptr = None, ws_bytes: int = 0, stream=None) -> int:
+    wc = None if w is None else w.c()
+    return lib().relax_dequant_matmul(_ptr(x), _ref(wc), _ptr(out), n, _ptr(ws), ws_bytes, _stream(stream))
+
+
+def relax_rmsnorm_rope(x: Ptr, w: Ptr, y: Ptr, n: int, H: int, eps: float, qkv: Ptr = None,
+                       dims: Optional[LayerDims] = None, cache: Optional[KVCache] = None, seqs: Optional[Seqs] = None,
+                       stream=None) -> int:
+    cc = None if cache is None else cache.c()
+    sc = None if seqs is None else seqs.c()
+    return lib().relax_rmsnorm_rope(_ptr(x), _ptr(w), _ptr(y), n, H, eps, _ptr(qkv), _ref(dims), _ref(cc), _ref(sc),
+                                    _stream(stream))
+
+
+def relax_attention(q: Ptr, cache: Optional[KVCache], seqs: Optional[Seqs], dims: Optional[LayerDims], out: Ptr, n: int,
+                    ws: Ptr, ws_bytes: int, stream=None) -> int:
+    cc = None if cache is None else cache.c()
+    sc = None if seqs is None else seqs.c()
+    return lib().relax_attention(_ptr(q), _ref(cc), _ref(sc), _ref(dims), _ptr(out), n, _ptr(ws), ws_bytes, _stream(stream))
+
+
+def relax_decoder_layer(dims: Optional[LayerDims], weights: Optional[LayerWeights], x: Ptr, cache: Optional[KVCache],
+                        seqs: Optional[Seqs], out: Ptr, n: int, ws: Ptr, ws_bytes: int, stream=None) -> int:
+    wc = None if weights is None else weights.c()
+    cc = None if cache is None else cache.c()
+    sc = None if seqs is None else seqs.c()
+    return lib().relax_decoder_layer(_ref(dims), _ref(wc), _ptr(x), _ref(cc), _ref(sc), _ptr(out), n, _ptr(ws), ws_bytes,
+                                     _stream(stream))
+
+
+def relax_unpack_int4(w: Optional[QMat], out: Ptr, stream=None) -> int:
+    wc = None if w is None else w.c()
+    return lib().relax_unpack_int4(_ref(wc), _ptr(out), _stream(stream))
+
+
+def relax_dequantize(w: Optional[QMat], out: Ptr, stream=None) -> int:
+    wc = None if w is None else w.c()
+    return lib().relax_dequantize(_ref(wc), _ptr(out), _stream(stream))

@@ -1,0 +1,285 @@
+// C ABI of librelax_mi355.so: argument checks (all on the host, before anything is enqueued),
+// the workspace plan, and the launch sequence of each exported call.  See include/relax_mi355.h
+// for the contract and for the passages of the paper each rule comes from.
+#include <vector>
+
+#include "relax_common.h"
+
+using namespace relax;
+
+namespace {
+
+inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+// Static plan of the lifted workspace (Sec. 4.3 upper bounds, Sec. 4.4 lifting).  Offsets are a
+// pure function of (dims, n, L, B); a call sized by upper bounds covers every smaller call.
+struct WsPlan {
+    size_t table, partials, qbuf, attn, x1, act, xn, qkv, total;
+};
+
+WsPlan plan_ws(const relax_layer_dims &dm, int32_t n, int32_t L, int32_t B)
+{
+    WsPlan p;
+    size_t off = 0;
+    const size_t hd = (size_t)dm.n_heads * dm.head_dim;
+    const size_t qkvw = (size_t)(dm.n_heads + 2 * dm.n_kv_heads) * dm.head_dim;
+    p.table = off;    off += align256(sizeof(int32_t) * 4 * (size_t)(B > 1 ? B : 1));
+    p.partials = off; off += align256(sizeof(float) * attn_partial_floats(dm, n, L));
+    p.qbuf = off;     off += align256(2 * (size_t)n * hd);
+    p.attn = off;     off += align256(2 * (size_t)n * hd);
+    p.x1 = off;       off += align256(4 * (size_t)n * dm.hidden);
+    p.act = off;      off += align256(2 * (size_t)n * dm.ffn);
+    p.xn = off;       off += align256(2 * (size_t)n * dm.hidden);
+    p.qkv = off;      off += align256(2 * (size_t)n * qkvw);
+    p.total = off;
+    return p;
+}
+
+relax_status check_dims(const relax_layer_dims *dm)
+{
+    if (!dm) return RELAX_ERR_NULL;
+    if (dm->hidden < 8 || dm->n_heads < 1 || dm->n_kv_heads < 1 || dm->ffn < 8 || dm->kv_capacity < 1 || dm->kv_slots < 1)
+        return RELAX_ERR_SHAPE;
+    if (dm->n_heads % dm->n_kv_heads != 0 || dm->head_dim % 2 != 0) return RELAX_ERR_SHAPE;
+    if (dm->head_dim != 64 && dm->head_dim != 128) return RELAX_ERR_UNSUPPORTED;
+    if (dm->group != kGroup) return RELAX_ERR_UNSUPPORTED;
+    return RELAX_OK;
+}
+
+relax_status check_qmat(const relax_qmat *w)
+{
+    if (!w || !w->q || !w->s) return RELAX_ERR_NULL;
+    if (w->m < 1 || w->k < 8 || w->k % 8 != 0) return RELAX_ERR_SHAPE;
+    if (w->k > kMaxK) return RELAX_ERR_UNSUPPORTED;
+    return RELAX_OK;
+}
+
+// Validates the ragged descriptor against n and the cache, and builds the kernel-side table.
+// host_table receives the [4][B] image for batches that do not fit the inline arrays.
+relax_status build_seqs(const relax_seqs *sq, const relax_layer_dims &dm, int32_t n, SeqTable &st, int32_t &L_max,
+                        std::vector<int32_t> &host_table)
+{
+    if (!sq || !sq->q_lens || !sq->kv_lens) return RELAX_ERR_NULL;
+    if (n < 1 || sq->B < 1) return RELAX_ERR_SHAPE;
+    long long total = 0;
+    L_max = 0;
+    for (int b = 0; b < sq->B; ++b) {
+        if (sq->q_lens[b] < 1 || sq->kv_lens[b] < sq->q_lens[b]) return RELAX_ERR_SHAPE;
+        total += sq->q_lens[b];
+    }
+    if (total != n) return RELAX_ERR_SHAPE;
+    for (int b = 0; b < sq->B; ++b) {
+        const int32_t slot = sq->slots ? sq->slots[b] : b;
+        if (sq->kv_lens[b] > dm.kv_capacity || slot < 0 || slot >= dm.kv_slots) return RELAX_ERR_CAPACITY;
+        if (sq->kv_lens[b] > L_max) L_max = sq->kv_lens[b];
+    }
+    st.B = sq->B;
+    st.n = n;
+    st.dev = nullptr;
+    const bool inl = sq->B <= kInlineSeqs;
+    if (!inl) host_table.assign(4 * (size_t)sq->B, 0);
+    int32_t start = 0;
+    for (int b = 0; b < sq->B; ++b) {
+        const int32_t slot = sq->slots ? sq->slots[b] : b;
+        if (inl) {
+            st.q_start[b] = start, st.q_len[b] = sq->q_lens[b], st.kv_len[b] = sq->kv_lens[b], st.slot[b] = slot;
+        } else {
+            host_table[b] = start;
+            host_table[sq->B + b] = sq->q_lens[b];
+            host_table[2 * (size_t)sq->B + b] = sq->kv_lens[b];
+            host_table[3 * (size_t)sq->B + b] = slot;
+        }
+        start += sq->q_lens[b];
+    }
+    if (inl)
+        for (int b = sq->B; b < kInlineSeqs; ++b) st.q_start[b] = st.q_len[b] = st.kv_len[b] = st.slot[b] = 0;
+    return RELAX_OK;
+}
+
+// Large batches: the descriptor goes to the device table at the front of the workspace.  The
+// host image is pageable, so wait for the copy before it goes out of scope.
+relax_status upload_table(SeqTable &st, const std::vector<int32_t> &host_table, void *ws, const WsPlan &pl, hipStream_t stream)
+{
+    if (host_table.empty()) return RELAX_OK;
+    int32_t *dev = reinterpret_cast<int32_t *>(static_cast<char *>(ws) + pl.table);
+    if (hipMemcpyAsync(dev, host_table.data(), host_table.size() * sizeof(int32_t), hipMemcpyHostToDevice, stream) != hipSuccess)
+        return RELAX_ERR_HIP;
+    if (hipStreamSynchronize(stream) != hipSuccess) return RELAX_ERR_HIP;
+    st.dev = dev;
+    return RELAX_OK;
+}
+
+inline relax_status hip_status(hipError_t e) { return e == hipSuccess ? RELAX_OK : RELAX_ERR_HIP; }
+
+}  // namespace
+
+extern "C" {
+
+const char *relax_build_id(void) { return "relax_mi355 gfx950 " __DATE__ " " __TIME__; }
+
+size_t relax_workspace_bytes(const relax_layer_dims *dims, int32_t n_max, int32_t L_max, int32_t B_max)
+{
+    if (check_dims(dims) != RELAX_OK || n_max < 1 || L_max < 1 || B_max < 1) return 0;
+    return plan_ws(*dims, n_max, L_max, B_max).total;
+}
+
+size_t relax_rope_table_bytes(const relax_layer_dims *dims)
+{
+    if (check_dims(dims) != RELAX_OK) return 0;
+    return sizeof(float) * 2 * (size_t)dims->kv_capacity * (size_t)(dims->head_dim / 2);
+}
+
+relax_status relax_rope_table_init(const relax_layer_dims *dims, float *table, relax_stream stream)
+{
+    relax_status rc = check_dims(dims);
+    if (rc != RELAX_OK) return rc;
+    if (!table) return RELAX_ERR_NULL;
+    return hip_status(launch_rope_table(*dims, table, static_cast<hipStream_t>(stream)));
+}
+
+relax_status relax_dequant_matmul(const uint16_t *x, const relax_qmat *w, uint16_t *out, int32_t n, void *ws, size_t ws_bytes,
+                                  relax_stream stream)
+{
+    (void)ws, (void)ws_bytes;
+    if (!x || !out) return RELAX_ERR_NULL;
+    relax_status rc = check_qmat(w);
+    if (rc != RELAX_OK) return rc;
+    if (n < 1) return RELAX_ERR_SHAPE;
+    GemvArgs a = {};
+    a.x = x, a.q = w->q, a.s = w->s, a.m = w->m, a.k = w->k, a.n = n, a.out_f16 = out;
+    return hip_status(launch_gemv(a, X_F16, EPI_F16, static_cast<hipStream_t>(stream)));
+}
+
+relax_status relax_rmsnorm_rope(const uint16_t *x, const uint16_t *w, uint16_t *y, int32_t n, int32_t H, float eps, uint16_t *qkv,
+                                const relax_layer_dims *dims, const relax_kv_cache *cache, const relax_seqs *seqs,
+                                relax_stream stream)
+{
+    hipStream_t st_ = static_cast<hipStream_t>(stream);
+    if (!x && !qkv) return RELAX_ERR_NULL;
+    if (n < 1) return RELAX_ERR_SHAPE;
+    SeqTable st = {};
+    std::vector<int32_t> host_table;
+    if (x) {
+        if (!w || !y) return RELAX_ERR_NULL;
+        if (H < 1) return RELAX_ERR_SHAPE;
+    }
+    if (qkv) {
+        relax_status rc = check_dims(dims);
+        if (rc != RELAX_OK) return rc;
+        if (!cache || !cache->k || !cache->v || !cache->rope) return RELAX_ERR_NULL;
+        int32_t L_max = 0;
+        rc = build_seqs(seqs, *dims, n, st, L_max, host_table);
+        if (rc != RELAX_OK) return rc;
+        if (!host_table.empty()) return RELAX_ERR_UNSUPPORTED;   // this call takes no workspace: B <= 16 only
+    }
+    if (x) {
+        relax_status rc = hip_status(launch_rmsnorm(x, w, y, n, H, eps, st_));
+        if (rc != RELAX_OK) return rc;
+    }
+    if (qkv) return hip_status(launch_rope_append(qkv, *dims, *cache, st, st_));
+    return RELAX_OK;
+}
+
+relax_status relax_attention(const uint16_t *q, const relax_kv_cache *cache, const relax_seqs *seqs, const relax_layer_dims *dims,
+                             uint16_t *out, int32_t n, void *ws, size_t ws_bytes, relax_stream stream)
+{
+    hipStream_t st_ = static_cast<hipStream_t>(stream);
+    relax_status rc = check_dims(dims);
+    if (rc != RELAX_OK) return rc;
+    if (!q || !out || !cache || !cache->k || !cache->v || !ws) return RELAX_ERR_NULL;
+    SeqTable st = {};
+    std::vector<int32_t> host_table;
+    int32_t L_max = 0;
+    rc = build_seqs(seqs, *dims, n, st, L_max, host_table);
+    if (rc != RELAX_OK) return rc;
+    const WsPlan pl = plan_ws(*dims, n, L_max, seqs->B);
+    if (ws_bytes < pl.qbuf) return RELAX_ERR_WORKSPACE;          // table + partials
+    rc = upload_table(st, host_table, ws, pl, st_);
+    if (rc != RELAX_OK) return rc;
+    float *partials = reinterpret_cast<float *>(static_cast<char *>(ws) + pl.partials);
+    return hip_status(launch_attention(q, *cache, *dims, st, L_max, out, partials, st_));
+}
+
+relax_status relax_decoder_layer(const relax_layer_dims *dims, const relax_layer_weights *wt, const uint16_t *x,
+                                 const relax_kv_cache *cache, const relax_seqs *seqs, uint16_t *out, int32_t n, void *ws,
+                                 size_t ws_bytes, relax_stream stream)
+{
+    hipStream_t st_ = static_cast<hipStream_t>(stream);
+    relax_status rc = check_dims(dims);
+    if (rc != RELAX_OK) return rc;
+    if (!wt || !x || !out || !ws || !cache || !cache->k || !cache->v || !cache->rope || !wt->norm_attn || !wt->norm_ffn)
+        return RELAX_ERR_NULL;
+    const relax_qmat *mats[4] = {&wt->wqkv, &wt->wo, &wt->wgu, &wt->wdown};
+    for (const relax_qmat *mq : mats) {
+        rc = check_qmat(mq);
+        if (rc != RELAX_OK) return rc;
+    }
+    const relax_layer_dims &dm = *dims;
+    const int32_t hd = dm.n_heads * dm.head_dim, qkvw = (dm.n_heads + 2 * dm.n_kv_heads) * dm.head_dim;
+    if (wt->wqkv.m != qkvw || wt->wqkv.k != dm.hidden || wt->wo.m != dm.hidden || wt->wo.k != hd ||
+        wt->wgu.m != 2 * dm.ffn || wt->wgu.k != dm.hidden || wt->wdown.m != dm.hidden || wt->wdown.k != dm.ffn)
+        return RELAX_ERR_SHAPE;
+    SeqTable st = {};
+    std::vector<int32_t> host_table;
+    int32_t L_max = 0;
+    rc = build_seqs(seqs, dm, n, st, L_max, host_table);
+    if (rc != RELAX_OK) return rc;
+    const WsPlan pl = plan_ws(dm, n, L_max, seqs->B);
+    if (ws_bytes < pl.total) return RELAX_ERR_WORKSPACE;
+    rc = upload_table(st, host_table, ws, pl, st_);
+    if (rc != RELAX_OK) return rc;
+
+    char *base = static_cast<char *>(ws);
+    float *partials = reinterpret_cast<float *>(base + pl.partials);
+    uint16_t *qbuf = reinterpret_cast<uint16_t *>(base + pl.qbuf);
+    uint16_t *attn = reinterpret_cast<uint16_t *>(base + pl.attn);
+    float *x1 = reinterpret_cast<float *>(base + pl.x1);
+    uint16_t *act = reinterpret_cast<uint16_t *>(base + pl.act);
+
+    // 1. RMSNorm -> QKV matvec -> rotary embedding -> q to workspace, k/v appended to the cache
+    GemvArgs a = {};
+    a.x = x, a.norm_w = wt->norm_attn, a.eps = dm.rms_eps;
+    a.q = wt->wqkv.q, a.s = wt->wqkv.s, a.m = wt->wqkv.m, a.k = wt->wqkv.k, a.n = n;
+    a.out_f16 = qbuf, a.kcache = cache->k, a.vcache = cache->v, a.rope = cache->rope;
+    a.h = dm.n_heads, a.g = dm.n_kv_heads, a.d = dm.head_dim, a.kv_capacity = dm.kv_capacity, a.seqs = st;
+    if (launch_gemv(a, X_F16_NORM, EPI_ROPE_KV, st_) != hipSuccess) return RELAX_ERR_HIP;
+
+    // 2. attention over the cache
+    if (launch_attention(qbuf, *cache, dm, st, L_max, attn, partials, st_) != hipSuccess) return RELAX_ERR_HIP;
+
+    // 3. output projection + residual: x1 = x + attn Wo^T (fp32 residual stream in the workspace)
+    GemvArgs o = {};
+    o.x = attn, o.q = wt->wo.q, o.s = wt->wo.s, o.m = wt->wo.m, o.k = wt->wo.k, o.n = n;
+    o.out_f32 = x1, o.resid = x;
+    if (launch_gemv(o, X_F16, EPI_RESID_F32, st_) != hipSuccess) return RELAX_ERR_HIP;
+
+    // 4. RMSNorm -> gate/up matvec -> SwiGLU
+    GemvArgs f = {};
+    f.x = x1, f.norm_w = wt->norm_ffn, f.eps = dm.rms_eps;
+    f.q = wt->wgu.q, f.s = wt->wgu.s, f.m = wt->wgu.m, f.k = wt->wgu.k, f.n = n;
+    f.out_f16 = act;
+    if (launch_gemv(f, X_F32_NORM, EPI_SWIGLU, st_) != hipSuccess) return RELAX_ERR_HIP;
+
+    // 5. down projection + residual
+    GemvArgs dn = {};
+    dn.x = act, dn.q = wt->wdown.q, dn.s = wt->wdown.s, dn.m = wt->wdown.m, dn.k = wt->wdown.k, dn.n = n;
+    dn.out_f16 = out, dn.resid = x1;
+    if (launch_gemv(dn, X_F16, EPI_RESID_F16, st_) != hipSuccess) return RELAX_ERR_HIP;
+    return RELAX_OK;
+}
+
+relax_status relax_unpack_int4(const relax_qmat *w, int8_t *out, relax_stream stream)
+{
+    if (!w || !w->q || !out) return RELAX_ERR_NULL;
+    if (w->m < 1 || w->k < 8 || w->k % 8 != 0) return RELAX_ERR_SHAPE;
+    return hip_status(launch_unpack(*w, out, static_cast<hipStream_t>(stream)));
+}
+
+relax_status relax_dequantize(const relax_qmat *w, float *out, relax_stream stream)
+{
+    if (!w || !w->q || !w->s || !out) return RELAX_ERR_NULL;
+    if (w->m < 1 || w->k < 8 || w->k % 8 != 0) return RELAX_ERR_SHAPE;
+    return hip_status(launch_dequantize(*w, out, static_cast<hipStream_t>(stream)));
+}
+
+}  // extern "C"

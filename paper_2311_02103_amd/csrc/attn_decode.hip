@@ -1,0 +1,219 @@
+// Attention over a KV cache of symbolic length, split along L ("flash-decoding" shape):
+// the paper treats attention as one fused operator whose KV length is a runtime value
+// (Relax, Sec. 4.2 custom attention pattern; Sec. 5.1 dynamic sequence length).  A decode row
+// reads L * g * d * 2 * 2 bytes of cache and does almost no arithmetic, so the kernel is a
+// streaming read: L is cut into chunks across workgroups so that 256 CUs have work even at
+// batch 1, every K/V byte is loaded once with 16-byte loads (all query heads of a KV head are
+// served by the same load), and each workgroup leaves an un-normalised partial (running max,
+// running sum, accumulator) in the caller's workspace (Sec. 4.4: kernel scratch lifted to the
+// caller).  A second small kernel merges the partials of a (row, head) with the usual
+// max-rescaling.  Scores, softmax and accumulation are fp32.
+#include "relax_common.h"
+
+namespace relax {
+
+AttnPlan attn_plan(int32_t n, int32_t g, int32_t L_max)
+{
+    long long total = (long long)n * g * (L_max > 0 ? L_max : 1);
+    long long c = (total + 1023) / 1024;
+    c = ((c + 63) / 64) * 64;
+    if (c < 64) c = 64;
+    if (c > 512) c = 512;
+    AttnPlan p;
+    p.chunk = (int32_t)c;
+    p.splits = (L_max + p.chunk - 1) / p.chunk;
+    if (p.splits < 1) p.splits = 1;
+    return p;
+}
+
+// Upper bound over every (n <= n_max, L <= L_max) of n*h*splits*(d+2) floats; see attn_plan:
+// unclamped chunks give at most 1024/(n g) + 1 splits, chunks clamped at 512 give ceil(L/512).
+size_t attn_partial_floats(const relax_layer_dims &dm, int32_t n_max, int32_t L_max)
+{
+    const size_t h = dm.n_heads, rep = dm.n_heads / dm.n_kv_heads;
+    size_t a = rep * 1024 + (size_t)n_max * h;
+    size_t b = (size_t)n_max * h * (size_t)((L_max + 511) / 512);
+    return (a > b ? a : b) * (size_t)(dm.head_dim + 2);
+}
+
+__device__ inline void unpack8(const uint4 &raw, float *f)
+{
+    const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        f[2 * j] = h2f((uint16_t)(w[j] & 0xFFFFu));
+        f[2 * j + 1] = h2f((uint16_t)(w[j] >> 16));
+    }
+}
+
+// merge state b into state a (running max m, running sum l, accumulator acc[8])
+__device__ inline void merge_state(float &ma, float &la, float *acca, float mb, float lb, const float *accb)
+{
+    const float mn = fmaxf(ma, mb);
+    const float sa = (ma == -INFINITY) ? 0.0f : __expf(ma - mn);
+    const float sb = (mb == -INFINITY) ? 0.0f : __expf(mb - mn);
+    la = la * sa + lb * sb;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acca[e] = acca[e] * sa + accb[e] * sb;
+    ma = mn;
+}
+
+// grid: x = KV head * (rep/REP) + head sub-group, y = split along L, z = row of the call
+template <int D, int REP>
+__global__ __launch_bounds__(256) void attn_split_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict__ kc,
+                                                         const uint16_t *__restrict__ vc, float *__restrict__ part, SeqTable st,
+                                                         int h, int g, int cap, int chunk, int splits)
+{
+    constexpr int LPT = D / 8;        // lanes that share one token (each owns 8 of its d elements)
+    constexpr int TPW = kWave / LPT;  // tokens per wavefront step
+    __shared__ float sm[4 * REP * (D + 2)];
+
+    const int i = blockIdx.z, split = blockIdx.y;
+    const RowInfo ri = row_info(st, i);
+    const int L = ri.pos + 1;
+    const int t_begin = split * chunk;
+    if (t_begin >= L) return;                                  // uniform for the workgroup
+    const int t_end = min(L, t_begin + chunk);
+
+    const int rep = h / g, subs = rep / REP;
+    const int kvh = blockIdx.x / subs, head0 = kvh * rep + (blockIdx.x - kvh * subs) * REP;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int sub = lane / LPT, e0 = (lane % LPT) * 8;
+    const float inv_sqrt_d = 1.0f / sqrtf((float)D);
+
+    float qf[REP][8], acc[REP][8], m[REP], l[REP];
+#pragma unroll
+    for (int r = 0; r < REP; ++r) {
+        unpack8(*(const uint4 *)(q + ((size_t)i * h + head0 + r) * D + e0), qf[r]);
+        m[r] = -INFINITY;
+        l[r] = 0.0f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[r][e] = 0.0f;
+    }
+
+    const size_t slot_base = (size_t)ri.slot * cap;
+    for (int t = t_begin + wave * TPW + sub; t < t_end; t += 4 * TPW) {
+        const size_t at = ((slot_base + t) * g + kvh) * D + e0;
+        float kf[8], vf[8];
+        unpack8(*(const uint4 *)(kc + at), kf);
+        unpack8(*(const uint4 *)(vc + at), vf);
+#pragma unroll
+        for (int r = 0; r < REP; ++r) {
+            float dot = 0.0f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) dot += qf[r][e] * kf[e];
+#pragma unroll
+            for (int off = LPT / 2; off >= 1; off >>= 1) dot += __shfl_xor(dot, off, kWave);
+            const float s = dot * inv_sqrt_d;
+            const float mn = fmaxf(m[r], s);
+            const float ca = __expf(m[r] - mn);                // m = -inf on the first token: exp(-inf) = 0
+            const float p = __expf(s - mn);
+            l[r] = l[r] * ca + p;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[r][e] = acc[r][e] * ca + p * vf[e];
+            m[r] = mn;
+        }
+    }
+
+    // merge the TPW token groups of the wavefront (lanes that own the same 8 elements)
+#pragma unroll
+    for (int r = 0; r < REP; ++r) {
+#pragma unroll
+        for (int off = LPT; off < kWave; off <<= 1) {
+            float mb = __shfl_xor(m[r], off, kWave), lb = __shfl_xor(l[r], off, kWave), accb[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) accb[e] = __shfl_xor(acc[r][e], off, kWave);
+            merge_state(m[r], l[r], acc[r], mb, lb, accb);
+        }
+        if (lane < LPT) {
+            float *dst = sm + (wave * REP + r) * (D + 2);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) dst[e0 + e] = acc[r][e];
+            if (lane == 0) {
+                dst[D] = m[r];
+                dst[D + 1] = l[r];
+            }
+        }
+    }
+    __syncthreads();
+
+    // merge the four wavefronts and write the partial of (row, head, split)
+    for (int idx = tid; idx < REP * D; idx += 256) {
+        const int r = idx / D, e = idx - r * D;
+        float mm = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) mm = fmaxf(mm, sm[(w * REP + r) * (D + 2) + D]);
+        float num = 0.0f, den = 0.0f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const float *src = sm + (w * REP + r) * (D + 2);
+            const float sc = (src[D] == -INFINITY) ? 0.0f : __expf(src[D] - mm);
+            num += src[e] * sc;
+            den += src[D + 1] * sc;
+        }
+        float *dst = part + (((size_t)i * h + head0 + r) * splits + split) * (D + 2);
+        dst[e] = num;
+        if (e == 0) {
+            dst[D] = mm;
+            dst[D + 1] = den;
+        }
+    }
+}
+
+// one workgroup of D threads per (row, head): out = sum_s acc_s e^(m_s - M) / sum_s l_s e^(m_s - M)
+template <int D>
+__global__ void attn_merge_kernel(const float *__restrict__ part, uint16_t *__restrict__ out, SeqTable st, int h, int chunk,
+                                  int splits)
+{
+    const int i = blockIdx.x / h, e = threadIdx.x;
+    const RowInfo ri = row_info(st, i);
+    const int used = (ri.pos + chunk) / chunk;                 // ceil((pos+1)/chunk)
+    const float *src = part + (size_t)blockIdx.x * splits * (D + 2);
+    float mm = -INFINITY;
+    for (int s = 0; s < used; ++s) mm = fmaxf(mm, src[s * (D + 2) + D]);
+    float num = 0.0f, den = 0.0f;
+    for (int s = 0; s < used; ++s) {
+        const float sc = __expf(src[s * (D + 2) + D] - mm);
+        num += src[s * (D + 2) + e] * sc;
+        den += src[s * (D + 2) + D + 1] * sc;
+    }
+    out[(size_t)blockIdx.x * D + e] = f2h(num / den);
+}
+
+template <int D, int REP>
+static hipError_t launch_split(const uint16_t *q, const relax_kv_cache &cache, const relax_layer_dims &dm, const SeqTable &st,
+                               const AttnPlan &pl, float *partials, hipStream_t stream)
+{
+    const int rep = dm.n_heads / dm.n_kv_heads;
+    dim3 grid(dm.n_kv_heads * (rep / REP), pl.splits, st.n);
+    hipLaunchKernelGGL((attn_split_kernel<D, REP>), grid, dim3(256), 0, stream, q, cache.k, cache.v, partials, st, dm.n_heads,
+                       dm.n_kv_heads, dm.kv_capacity, pl.chunk, pl.splits);
+    return hipGetLastError();
+}
+
+template <int D>
+static hipError_t launch_d(const uint16_t *q, const relax_kv_cache &cache, const relax_layer_dims &dm, const SeqTable &st,
+                           const AttnPlan &pl, uint16_t *out, float *partials, hipStream_t stream)
+{
+    const int rep = dm.n_heads / dm.n_kv_heads;
+    hipError_t e;
+    if (rep % 8 == 0) e = launch_split<D, 8>(q, cache, dm, st, pl, partials, stream);
+    else if (rep % 4 == 0) e = launch_split<D, 4>(q, cache, dm, st, pl, partials, stream);
+    else if (rep % 2 == 0) e = launch_split<D, 2>(q, cache, dm, st, pl, partials, stream);
+    else e = launch_split<D, 1>(q, cache, dm, st, pl, partials, stream);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((attn_merge_kernel<D>), dim3(st.n * dm.n_heads), dim3(D), 0, stream, partials, out, st, dm.n_heads,
+                       pl.chunk, pl.splits);
+    return hipGetLastError();
+}
+
+hipError_t launch_attention(const uint16_t *q, const relax_kv_cache &cache, const relax_layer_dims &dm, const SeqTable &st,
+                            int32_t L_max, uint16_t *out, float *partials, hipStream_t stream)
+{
+    const AttnPlan pl = attn_plan(st.n, dm.n_kv_heads, L_max);
+    if (dm.head_dim == 128) return launch_d<128>(q, cache, dm, st, pl, out, partials, stream);
+    if (dm.head_dim == 64) return launch_d<64>(q, cache, dm, st, pl, out, partials, stream);
+    return hipErrorInvalidValue;
+}
+
+}  // namespace relax

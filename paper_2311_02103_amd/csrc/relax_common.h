@@ -1,0 +1,125 @@
+// Internal definitions shared by the HIP translation units of librelax_mi355.so.
+// Not part of the C ABI (include/relax_mi355.h is).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <stdint.h>
+
+#include "relax_mi355.h"
+
+namespace relax {
+
+constexpr int kWave = 64;            // CDNA wavefront
+constexpr int kGroup = 32;           // quantisation group along k
+constexpr int kMaxK = 28672;         // x row (fp16) + per-group terms must fit 64 KB of LDS
+constexpr int kInlineSeqs = 16;      // ragged descriptors up to this many sequences ride in kernel arguments
+
+// The ragged batch as the kernels see it.  The symbolic values (n, B, every L_b) are plain
+// kernel arguments (Sec. 3.3: symbolic values travel as extra scalar arguments); a batch
+// with more than kInlineSeqs sequences is copied to a device table in the workspace, the
+// device-side analogue of the runtime shape heap of Sec. 4.7.
+struct SeqTable {
+    int32_t B;
+    int32_t n;
+    const int32_t *dev;              // [4][B]: q_start, q_len, kv_len, slot; nullptr -> inline arrays
+    int32_t q_start[kInlineSeqs];
+    int32_t q_len[kInlineSeqs];
+    int32_t kv_len[kInlineSeqs];
+    int32_t slot[kInlineSeqs];
+};
+
+struct RowInfo {
+    int32_t seq, pos, slot;
+};
+
+// row of the call -> (sequence, position in its cache slot, slot)
+__device__ inline RowInfo row_info(const SeqTable &st, int32_t row)
+{
+    RowInfo r;
+    if (st.dev) {
+        const int32_t *qs = st.dev, *ql = st.dev + st.B, *kl = st.dev + 2 * st.B, *sl = st.dev + 3 * st.B;
+        int b = 0;
+        while (b + 1 < st.B && row >= qs[b] + ql[b]) ++b;
+        r.seq = b;
+        r.pos = kl[b] - ql[b] + (row - qs[b]);
+        r.slot = sl[b];
+    } else {
+        int b = 0;
+#pragma unroll
+        for (int j = 0; j < kInlineSeqs - 1; ++j)
+            if (j + 1 < st.B && row >= st.q_start[j] + st.q_len[j]) b = j + 1;
+        r.seq = b;
+        r.pos = st.kv_len[b] - st.q_len[b] + (row - st.q_start[b]);
+        r.slot = st.slot[b];
+    }
+    return r;
+}
+
+__device__ inline float wave_sum(float v)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, kWave);
+    return v;
+}
+
+__device__ inline float wave_max(float v)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, kWave));
+    return v;
+}
+
+__device__ inline float h2f(uint16_t bits) { return __half2float(__ushort_as_half(bits)); }
+__device__ inline uint16_t f2h(float v) { return __half_as_ushort(__float2half_rn(v)); }
+
+// Decode of one stored code: nibble e of a word -> integer in -8..7 (offset-binary).
+__device__ inline int decode_code(uint32_t word, int e) { return (int)((word >> (4 * e)) & 0xFu) - 8; }
+
+inline int groups_of(int k) { return (k + kGroup - 1) / kGroup; }
+
+// ---- launchers (defined in the .hip files), all asynchronous on `stream` --------------------------------------
+
+enum XMode { X_F16 = 0, X_F16_NORM = 1, X_F32_NORM = 2 };
+enum Epilogue { EPI_F16 = 0, EPI_ROPE_KV = 1, EPI_RESID_F32 = 2, EPI_RESID_F16 = 3, EPI_SWIGLU = 4 };
+
+struct GemvArgs {
+    // input rows
+    const void *x;                   // [n,k] fp16 (X_F16, X_F16_NORM) or fp32 (X_F32_NORM)
+    const uint16_t *norm_w;          // [k] fp16, norm modes only
+    float eps;
+    // matrix
+    const uint32_t *q;
+    const uint16_t *s;
+    int32_t m, k, n;
+    // epilogue
+    uint16_t *out_f16;               // EPI_F16: [n,m]; EPI_ROPE_KV: q buffer [n,h*d]; EPI_RESID_F16: out [n,m]; EPI_SWIGLU: act [n,F]
+    float *out_f32;                  // EPI_RESID_F32: x1 [n,m]
+    const void *resid;               // EPI_RESID_F32: x fp16 [n,m]; EPI_RESID_F16: x1 fp32 [n,m]
+    // EPI_ROPE_KV
+    uint16_t *kcache, *vcache;
+    const float *rope;
+    int32_t h, g, d, kv_capacity;
+    SeqTable seqs;
+};
+
+hipError_t launch_gemv(const GemvArgs &a, int xmode, int epi, hipStream_t stream);
+
+hipError_t launch_rmsnorm(const uint16_t *x, const uint16_t *w, uint16_t *y, int n, int H, float eps, hipStream_t stream);
+hipError_t launch_rope_append(uint16_t *qkv, const relax_layer_dims &dm, const relax_kv_cache &cache,
+                              const SeqTable &st, hipStream_t stream);
+hipError_t launch_rope_table(const relax_layer_dims &dm, float *table, hipStream_t stream);
+hipError_t launch_unpack(const relax_qmat &w, int8_t *out, hipStream_t stream);
+hipError_t launch_dequantize(const relax_qmat &w, float *out, hipStream_t stream);
+
+// Split-L attention: chunk length and split count are pure functions of the runtime shape.
+struct AttnPlan {
+    int32_t chunk;                   // tokens per split
+    int32_t splits;                  // grid extent along L (rows with fewer tokens leave the tail idle)
+};
+AttnPlan attn_plan(int32_t n, int32_t g, int32_t L_max);
+size_t attn_partial_floats(const relax_layer_dims &dm, int32_t n_max, int32_t L_max);
+hipError_t launch_attention(const uint16_t *q, const relax_kv_cache &cache, const relax_layer_dims &dm,
+                            const SeqTable &st, int32_t L_max, uint16_t *out, float *partials, hipStream_t stream);
+
+}  // namespace relax

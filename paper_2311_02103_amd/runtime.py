@@ -1,0 +1,66 @@
+"""Device-side bookkeeping around the C ABI: torch tensors that own the weights, the KV cache,
+the rotary table and the workspace of one layer.  Allocation and host->device copies only."""
+from __future__ import annotations
+
+from typing import Dict, Optional, Sequence
+
+import numpy as np
+import torch
+
+from . import binding as rx
+
+
+def to_device(a: np.ndarray, device="cuda") -> torch.Tensor:
+    """numpy uint16 (fp16 bits) -> torch.float16, uint32 -> int32 (same bits), others as is."""
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16)).to(device).view(torch.float16)
+    if a.dtype == np.uint32:
+        return torch.from_numpy(a.view(np.int32)).to(device)
+    return torch.from_numpy(a).to(device)
+
+
+def f16_bits(t: torch.Tensor) -> np.ndarray:
+    """torch.float16 tensor -> numpy uint16 bit patterns on the host."""
+    return t.detach().contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+class DeviceLayer:
+    """One decoder layer resident on the GPU, sized by upper bounds (n_max, L_max = kv_capacity, B_max)."""
+
+    def __init__(self, host_weights: Dict[str, np.ndarray], *, hidden: int, n_heads: int, n_kv_heads: int, head_dim: int,
+                 ffn: int, kv_capacity: int, kv_slots: int = 1, n_max: int = 1, B_max: Optional[int] = None,
+                 rms_eps: float = 1e-5, rope_base: float = 10000.0, device="cuda", share_from: "DeviceLayer" = None):
+        self.device = device
+        self.dims = rx.make_dims(hidden, n_heads, n_kv_heads, head_dim, ffn, kv_capacity, kv_slots, rms_eps, rope_base)
+        mats = {"wqkv": ((n_heads + 2 * n_kv_heads) * head_dim, hidden), "wo": (hidden, n_heads * head_dim),
+                "wgu": (2 * ffn, hidden), "wdown": (hidden, ffn)}
+        self.t = {k: to_device(v, device) for k, v in host_weights.items()}
+        self.weights = rx.LayerWeights(*(rx.QMat(self.t[n + ".q"], self.t[n + ".s"], *mats[n]) for n in mats),
+                                       self.t["norm_attn"], self.t["norm_ffn"])
+        self.n_max, self.B_max = n_max, (B_max if B_max is not None else max(kv_slots, 1))
+        if share_from is not None:          # layers of one model share cache geometry, rope table and workspace
+            self.rope, self.ws, self.ws_bytes = share_from.rope, share_from.ws, share_from.ws_bytes
+        else:
+            self.rope = torch.empty(rx.relax_rope_table_bytes(self.dims) // 4, dtype=torch.float32, device=device)
+            rx.check(rx.relax_rope_table_init(self.dims, self.rope), "relax_rope_table_init")
+            self.ws_bytes = rx.relax_workspace_bytes(self.dims, n_max, kv_capacity, self.B_max)
+            self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device=device)
+        shape = (kv_slots, kv_capacity, n_kv_heads, head_dim)
+        self.k = torch.zeros(shape, dtype=torch.float16, device=device)
+        self.v = torch.zeros(shape, dtype=torch.float16, device=device)
+        self.cache = rx.KVCache(self.k, self.v, self.rope)
+
+    def load_cache(self, k_bits: np.ndarray, v_bits: np.ndarray) -> None:
+        self.k.copy_(to_device(k_bits, self.device).view(self.k.shape))
+        self.v.copy_(to_device(v_bits, self.device).view(self.v.shape))
+
+    def forward(self, x: torch.Tensor, q_lens: Sequence[int], kv_lens: Sequence[int], slots=None,
+                out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        n = x.shape[0]
+        if out is None:
+            out = torch.empty_like(x)
+        seqs = rx.Seqs(q_lens, kv_lens, slots)
+        rx.check(rx.relax_decoder_layer(self.dims, self.weights, x, self.cache, seqs, out, n, self.ws, self.ws_bytes),
+                 "relax_decoder_layer")
+        return out

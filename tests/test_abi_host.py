@@ -1,0 +1,123 @@
+"""Host-side contract of the C ABI: the library loads without a GPU, exports every declared symbol,
+and every shape / pointer check fires before anything is enqueued (Relax Sec. 3.2 / 4.1: shape
+constraints are checked at the function boundary and raise errors)."""
+import os
+import re
+
+import pytest
+
+from paper_2311_02103_amd import binding as rx
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+P = 0x10000   # a non-null fake device address: every call below must fail validation before touching it
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "relax_mi355.h")).read()
+    declared = set(re.findall(r"\b(relax_[a-z0-9_]+)\s*\(", header))
+    declared -= {"relax_status", "relax_stream"}
+    assert declared == set(rx.EXPORTS), declared ^ set(rx.EXPORTS)
+    lib = rx.lib()
+    for name in declared:
+        assert getattr(lib, name) is not None
+    assert "gfx950" in rx.relax_build_id()
+
+
+def dims(**kw):
+    base = dict(hidden=256, n_heads=4, n_kv_heads=4, head_dim=64, ffn=688, kv_capacity=64, kv_slots=2)
+    base.update(kw)
+    return rx.make_dims(**base)
+
+
+def weights(d, **kw):
+    H, F = d.hidden, d.ffn
+    hd, qkvw = d.n_heads * d.head_dim, (d.n_heads + 2 * d.n_kv_heads) * d.head_dim
+    m = dict(wqkv=rx.QMat(P, P, qkvw, H), wo=rx.QMat(P, P, H, hd), wgu=rx.QMat(P, P, 2 * F, H), wdown=rx.QMat(P, P, H, F))
+    m.update(kw)
+    return rx.LayerWeights(m["wqkv"], m["wo"], m["wgu"], m["wdown"], P, P)
+
+
+def test_workspace_query():
+    d = dims()
+    small, big = rx.relax_workspace_bytes(d, 1, 64, 1), rx.relax_workspace_bytes(d, 37, 64, 2)
+    assert 0 < small < big
+    assert rx.relax_workspace_bytes(None, 1, 1, 1) == 0
+    assert rx.relax_workspace_bytes(dims(head_dim=96), 1, 1, 1) == 0
+    assert rx.relax_workspace_bytes(d, 0, 64, 1) == 0
+    assert rx.relax_rope_table_bytes(d) == 64 * 32 * 2 * 4
+    # monotone in every symbolic upper bound
+    prev = 0
+    for n in (1, 2, 17, 128, 2048):
+        cur = rx.relax_workspace_bytes(dims(hidden=4096, n_heads=32, n_kv_heads=32, head_dim=128, ffn=11008,
+                                            kv_capacity=4096), n, 4096, 1)
+        assert cur >= prev
+        prev = cur
+
+
+def test_dequant_matmul_checks():
+    assert rx.relax_dequant_matmul(None, rx.QMat(P, P, 8, 64), P, 1) == rx.ERR_NULL
+    assert rx.relax_dequant_matmul(P, None, P, 1) == rx.ERR_NULL
+    assert rx.relax_dequant_matmul(P, rx.QMat(None, P, 8, 64), P, 1) == rx.ERR_NULL
+    assert rx.relax_dequant_matmul(P, rx.QMat(P, P, 8, 64), None, 1) == rx.ERR_NULL
+    assert rx.relax_dequant_matmul(P, rx.QMat(P, P, 8, 64), P, 0) == rx.ERR_SHAPE
+    assert rx.relax_dequant_matmul(P, rx.QMat(P, P, 8, 60), P, 1) == rx.ERR_SHAPE       # k % 8
+    assert rx.relax_dequant_matmul(P, rx.QMat(P, P, 0, 64), P, 1) == rx.ERR_SHAPE
+    assert rx.relax_dequant_matmul(P, rx.QMat(P, P, 8, 1 << 20), P, 1) == rx.ERR_UNSUPPORTED
+
+
+def test_decoder_layer_checks():
+    d = dims()
+    w = weights(d)
+    ws_bytes = rx.relax_workspace_bytes(d, 8, 64, 2)
+    call = lambda dd, ww, sq, n, x=P, ws=P, wsb=ws_bytes, cache=rx.KVCache(P, P, P): \
+        rx.relax_decoder_layer(dd, ww, x, cache, sq, P, n, ws, wsb)
+    ok_seq = rx.Seqs([3], [3])
+    assert call(None, w, ok_seq, 3) == rx.ERR_NULL
+    assert call(d, None, ok_seq, 3) == rx.ERR_NULL
+    assert call(d, w, None, 3) == rx.ERR_NULL
+    assert call(d, w, ok_seq, 3, x=None) == rx.ERR_NULL
+    assert call(d, w, ok_seq, 3, cache=rx.KVCache(P, P, None)) == rx.ERR_NULL
+    assert call(d, w, ok_seq, 3, ws=None) == rx.ERR_NULL
+    assert call(d, w, ok_seq, 0) == rx.ERR_SHAPE
+    assert call(d, w, ok_seq, 4) == rx.ERR_SHAPE                          # sum q_lens != n
+    assert call(d, w, rx.Seqs([3], [2]), 3) == rx.ERR_SHAPE              # L < q_len
+    assert call(d, w, rx.Seqs([3, 0], [3, 0]), 3) == rx.ERR_SHAPE        # empty sequence
+    assert call(d, w, rx.Seqs([3], [65]), 3) == rx.ERR_CAPACITY          # L > capacity
+    assert call(d, w, rx.Seqs([1, 1, 1], [1, 1, 1]), 3) == rx.ERR_CAPACITY   # third slot does not exist
+    assert call(d, w, rx.Seqs([3], [3], slots=[2]), 3) == rx.ERR_CAPACITY
+    assert call(d, w, rx.Seqs([3], [3], slots=[-1]), 3) == rx.ERR_CAPACITY
+    assert call(dims(n_kv_heads=3), w, ok_seq, 3) == rx.ERR_SHAPE        # h % g
+    assert call(dims(head_dim=96), w, ok_seq, 3) == rx.ERR_UNSUPPORTED
+    assert call(dims(group=64), w, ok_seq, 3) == rx.ERR_UNSUPPORTED
+    assert call(d, weights(d, wo=rx.QMat(P, P, 256, 128)), ok_seq, 3) == rx.ERR_SHAPE    # matrix does not fit dims
+    assert call(d, weights(d, wdown=rx.QMat(P, P, 256, 684)), ok_seq, 3) == rx.ERR_SHAPE  # k % 8
+    assert call(d, w, rx.Seqs([8], [64]), 8, wsb=ws_bytes - 1) == rx.ERR_WORKSPACE
+    assert call(d, w, rx.Seqs([8], [64]), 8, wsb=0) == rx.ERR_WORKSPACE
+
+
+def test_attention_and_norm_rope_checks():
+    d = dims()
+    c = rx.KVCache(P, P, P)
+    s = rx.Seqs([2], [5])
+    assert rx.relax_attention(None, c, s, d, P, 2, P, 1 << 20) == rx.ERR_NULL
+    assert rx.relax_attention(P, c, None, d, P, 2, P, 1 << 20) == rx.ERR_NULL
+    assert rx.relax_attention(P, c, s, d, P, 3, P, 1 << 20) == rx.ERR_SHAPE
+    assert rx.relax_attention(P, c, rx.Seqs([2], [70]), d, P, 2, P, 1 << 20) == rx.ERR_CAPACITY
+    assert rx.relax_attention(P, c, s, d, P, 2, P, 16) == rx.ERR_WORKSPACE
+    assert rx.relax_rmsnorm_rope(None, None, None, 1, 256, 1e-5) == rx.ERR_NULL
+    assert rx.relax_rmsnorm_rope(P, None, P, 1, 256, 1e-5) == rx.ERR_NULL
+    assert rx.relax_rmsnorm_rope(P, P, P, 0, 256, 1e-5) == rx.ERR_SHAPE
+    assert rx.relax_rmsnorm_rope(None, None, None, 2, 256, 1e-5, qkv=P, dims=d, cache=rx.KVCache(P, P, None), seqs=s) == rx.ERR_NULL
+    assert rx.relax_rmsnorm_rope(None, None, None, 2, 256, 1e-5, qkv=P, dims=d, cache=c, seqs=rx.Seqs([1], [5])) == rx.ERR_SHAPE
+    assert rx.relax_unpack_int4(rx.QMat(P, P, 4, 12), P) == rx.ERR_SHAPE
+    assert rx.relax_dequantize(rx.QMat(P, None, 4, 16), P) == rx.ERR_NULL
+    assert rx.relax_rope_table_init(d, None) == rx.ERR_NULL
+
+
+def test_no_product_module_touches_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2311_02103_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.lower(), os.path.join(dirpath, f)

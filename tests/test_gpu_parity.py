@@ -1,0 +1,286 @@
+"""Parity of the HIP path against the CPU oracle, element by element, through the C ABI.
+
+Bar: bit-exact for int4 decoding / indexing and for integer-valued contractions; within
+|gpu - ref| <= 1e-2 + 2e-2 |ref| for fp16 results against the fp32 oracle."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads as wl
+from helpers import assert_close, device_layer, f32_cache, oracle_dims, oracle_weights
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def rx():
+    if not torch.cuda.is_available():
+        pytest.skip("needs a GPU")
+    from paper_2311_02103_amd import binding
+    binding.lib()                      # raises if the HIP library is not built: no fallback exists
+    return binding
+
+
+def dev(a):
+    from paper_2311_02103_amd.runtime import to_device
+    return to_device(a)
+
+
+def host_bits(t):
+    from paper_2311_02103_amd.runtime import f16_bits
+    return f16_bits(t)
+
+
+def gpu_matmul(rx, x_bits, q, s, m, k):
+    n = x_bits.shape[0]
+    out = torch.empty((n, m), dtype=torch.float16, device="cuda")
+    rx.check(rx.relax_dequant_matmul(dev(x_bits), rx.QMat(dev(q), dev(s), m, k), out, n), "relax_dequant_matmul")
+    torch.cuda.synchronize()
+    return host_bits(out)
+
+
+# ------------------------------------------------------------------------- decode exports: bit-exact
+@pytest.mark.parametrize("m,k", [(5, 8), (33, 688), (64, 4096), (3, 11008)])
+def test_unpack_and_dequantize_bit_exact(rx, m, k):
+    r = np.random.RandomState(m * 7 + k)
+    q = r.randint(0, 2 ** 32, size=(m, k // 8), dtype=np.uint64).astype(np.uint32)
+    s = (r.randn(m, (k + 31) // 32) * 0.01).astype(np.float16).view(np.uint16)
+    qm = rx.QMat(dev(q), dev(s), m, k)
+    codes = torch.empty((m, k), dtype=torch.int8, device="cuda")
+    dense = torch.empty((m, k), dtype=torch.float32, device="cuda")
+    rx.check(rx.relax_unpack_int4(qm, codes), "relax_unpack_int4")
+    rx.check(rx.relax_dequantize(qm, dense), "relax_dequantize")
+    torch.cuda.synchronize()
+    assert np.array_equal(codes.cpu().numpy(), oracle.unpack_int4(q, m, k))
+    assert np.array_equal(dense.cpu().numpy().view(np.uint32), oracle.dequantize(q, s, m, k).view(np.uint32))
+
+
+# ------------------------------------------------------------------------- matvec: exact cases
+@pytest.mark.parametrize("m,k,n", [(40, 256, 2), (65, 688, 3), (130, 4096, 1), (37, 11008, 2)])
+def test_selector_matrix_bitwise(rx, m, k, n):
+    # row r holds +1 (code 9) only at column (7r+3) mod k, scale 1  =>  out[i,r] = x[i,(7r+3) mod k].
+    # x is integer-valued (every partial sum is exactly representable), so any (r,c) -> word / nibble /
+    # scale-group indexing slip shows as a wrong integer; with N(0,1) x the result must still match to fp16 rounding.
+    codes = np.full((m, k), 8, dtype=np.uint8)
+    cols = (7 * np.arange(m) + 3) % k
+    codes[np.arange(m), cols] = 9
+    q = wl.pack_codes(codes)
+    s = np.full((m, (k + 31) // 32), np.float16(1.0)).view(np.uint16)
+    xi = ((np.arange(n)[:, None] * 5 + np.arange(k)[None, :] * 37) % 15 - 7).astype(np.float32)
+    got = gpu_matmul(rx, xi.astype(np.float16).view(np.uint16), q, s, m, k).view(np.float16).astype(np.float32)
+    assert np.array_equal(got, xi[:, cols])
+    assert np.array_equal(got, oracle.dequant_matmul(xi, q, s, m, k))
+    x = wl.normal_f16_bits(1, 77, (n, k))
+    got = gpu_matmul(rx, x, q, s, m, k).view(np.float16).astype(np.float32)
+    ref = oracle.dequant_matmul(wl.f16_bits_to_f32(x), q, s, m, k)
+    assert np.array_equal(ref, wl.f16_bits_to_f32(x)[:, cols])
+    assert np.abs(got - ref).max() <= 4e-3          # scale 1.0 here: ~150x the scale of real weights
+
+
+@pytest.mark.parametrize("m,k,n", [(33, 688, 5), (64, 4096, 2), (31, 2048, 1), (16, 11008, 1)])
+def test_integer_valued_matmul_bitwise(rx, m, k, n):
+    r = np.random.RandomState(k + m)
+    codes = r.randint(0, 16, size=(m, k)).astype(np.uint8)
+    sc = r.choice([1.0, 2.0], size=(m, (k + 31) // 32)).astype(np.float16)
+    # sparse small-integer x keeps |out| <= 2048 so the fp16 result is exact
+    x = np.zeros((n, k), dtype=np.float32)
+    hot = r.choice(k, size=24, replace=False)
+    x[:, hot] = r.randint(-3, 4, size=(n, 24))
+    xb = x.astype(np.float16).view(np.uint16)
+    q, s = wl.pack_codes(codes), sc.view(np.uint16)
+    ref = oracle.dequant_matmul(x, q, s, m, k)
+    assert np.abs(ref).max() <= 2048
+    got = gpu_matmul(rx, xb, q, s, m, k).view(np.float16).astype(np.float32)
+    assert np.array_equal(got, ref)
+
+
+# ------------------------------------------------------------------------- matvec: random data, tolerance
+@pytest.mark.parametrize("m,k,n", [(768, 256, 37), (256, 256, 1), (1376, 256, 4), (256, 688, 37), (257, 688, 1),
+                                   (1024, 4096, 1), (515, 4096, 17), (640, 11008, 1), (96, 11008, 3), (9, 8192, 2),
+                                   (2, 28672, 1), (1, 64, 1)])
+def test_dequant_matmul_random(rx, m, k, n):
+    q, s = wl.qmat(3, m * 131 + k, m, k)
+    x = wl.normal_f16_bits(3, m + k + n, (n, k))
+    ref = oracle.dequant_matmul(wl.f16_bits_to_f32(x), q, s, m, k)
+    got = gpu_matmul(rx, x, q, s, m, k).view(np.float16).astype(np.float32)
+    assert_close(got, ref, "dequant_matmul m=%d k=%d n=%d" % (m, k, n))
+    # well inside the bar: fp32 accumulation, one fp16 rounding of the result
+    assert np.abs(got - ref).max() <= 2e-3 * max(1.0, np.abs(ref).max())
+
+
+def test_dequant_matmul_rows_are_independent(rx):
+    m, k, n = 300, 4096, 5
+    q, s = wl.qmat(4, 1, m, k)
+    x = wl.normal_f16_bits(4, 2, (n, k))
+    full = gpu_matmul(rx, x, q, s, m, k)
+    for i in range(n):
+        assert np.array_equal(gpu_matmul(rx, x[i:i + 1], q, s, m, k)[0], full[i])
+
+
+# ------------------------------------------------------------------------- RMSNorm / rotary + append
+def test_rmsnorm_and_rope_append(rx):
+    shape = wl.TINY
+    cap, n = 64, 6
+    dims = rx.make_dims(shape.hidden, shape.n_heads, shape.n_kv_heads, shape.head_dim, shape.ffn, cap, 2)
+    od = oracle_dims(shape, cap)
+    x = wl.normal_f16_bits(5, 1, (n, shape.hidden))
+    w = wl.normal_f16_bits(5, 2, (shape.hidden,), std=0.1, mean=1.0)
+    y = torch.empty((n, shape.hidden), dtype=torch.float16, device="cuda")
+    rx.check(rx.relax_rmsnorm_rope(dev(x), dev(w), y, n, shape.hidden, shape.rms_eps))
+    torch.cuda.synchronize()
+    assert_close(host_bits(y).view(np.float16), oracle.rmsnorm(wl.f16_bits_to_f32(x), w, shape.rms_eps), "rmsnorm")
+
+    qkv = wl.normal_f16_bits(5, 3, (n, shape.qkv_rows))
+    rope = torch.empty(rx.relax_rope_table_bytes(dims) // 4, dtype=torch.float32, device="cuda")
+    rx.check(rx.relax_rope_table_init(dims, rope))
+    kc = torch.full((2, cap, shape.n_kv_heads, shape.head_dim), float("nan"), dtype=torch.float16, device="cuda")
+    vc = torch.full_like(kc, float("nan"))
+    seqs_q, seqs_kv, slots = [2, 4], [40, 4], [1, 0]
+    dq = dev(qkv)
+    rx.check(rx.relax_rmsnorm_rope(None, None, None, n, shape.hidden, shape.rms_eps, qkv=dq, dims=dims,
+                                   cache=rx.KVCache(kc, vc, rope), seqs=rx.Seqs(seqs_q, seqs_kv, slots)))
+    torch.cuda.synchronize()
+    Ko = np.full((2, cap, shape.n_kv_heads, shape.head_dim), np.nan, np.float32)
+    Vo = Ko.copy()
+    ref = oracle.rope_append(wl.f16_bits_to_f32(qkv), od, Ko, Vo, oracle.Seqs(seqs_q, seqs_kv, slots))
+    assert_close(host_bits(dq).view(np.float16), ref, "rope qkv", atol=4e-3, rtol=2e-3)
+    Kg, Vg = host_bits(kc).view(np.float16).astype(np.float32), host_bits(vc).view(np.float16).astype(np.float32)
+    assert np.array_equal(np.isnan(Kg), np.isnan(Ko)) and np.array_equal(np.isnan(Vg), np.isnan(Vo))   # only the new rows
+    mask = ~np.isnan(Ko)
+    assert_close(Kg[mask], Ko[mask], "appended K", atol=4e-3, rtol=2e-3)
+    assert np.array_equal(Vg[mask], Vo[mask])
+    # the table itself: (cos, sin) of pos * base^(-2t/d) against float64
+    tab = rope.cpu().numpy().reshape(cap, shape.head_dim // 2, 2)
+    ang = np.arange(cap)[:, None] * shape.rope_base ** (-2.0 * np.arange(shape.head_dim // 2) / shape.head_dim)[None, :]
+    assert np.abs(tab[:, :, 0] - np.cos(ang)).max() < 1e-7 and np.abs(tab[:, :, 1] - np.sin(ang)).max() < 1e-7
+
+
+# ------------------------------------------------------------------------- attention
+def run_attention(rx, h, g, d, cap, slots, q_lens, kv_lens, slot_ids, seed, poison=True):
+    n = int(np.sum(q_lens))
+    dims = rx.make_dims(h * d, h, g, d, 64, cap, slots)
+    od = oracle.Dims(h * d, h, g, d, 64, kv_capacity=cap)
+    kb, vb = (wl.normal_f16_bits(seed, 10 + j, (slots, cap, g, d)) for j in (0, 1))
+    qb = wl.normal_f16_bits(seed, 12, (n, h, d))
+    kc, vc = dev(kb).clone(), dev(vb).clone()
+    if poison:      # nothing beyond each row's position may be read: poison the cache above every sequence's length
+        for b, sl in enumerate(slot_ids):
+            kc[sl, kv_lens[b]:] = float("nan")
+            vc[sl, kv_lens[b]:] = float("nan")
+    ws_bytes = rx.relax_workspace_bytes(dims, n, int(max(kv_lens)), len(q_lens))
+    ws = torch.full((ws_bytes,), 0xFF, dtype=torch.uint8, device="cuda")       # NaN-pattern garbage in the scratch
+    out = torch.empty((n, h, d), dtype=torch.float16, device="cuda")
+    rx.check(rx.relax_attention(dev(qb), rx.KVCache(kc, vc, None), rx.Seqs(q_lens, kv_lens, slot_ids), dims, out, n, ws,
+                                ws_bytes), "relax_attention")
+    torch.cuda.synchronize()
+    ref = oracle.attention(wl.f16_bits_to_f32(qb), f32_cache(kb), f32_cache(vb), od, oracle.Seqs(q_lens, kv_lens, slot_ids))
+    return host_bits(out).view(np.float16).astype(np.float32), ref
+
+
+@pytest.mark.parametrize("L", [1, 2, 63, 64, 65, 257, 1000, 4096])
+def test_decode_attention_lengths(rx, L):
+    got, ref = run_attention(rx, 32, 32, 128, 4096, 1, [1], [L], [0], seed=20 + L)
+    assert_close(got, ref, "decode attention L=%d" % L, atol=2e-3, rtol=1e-2)
+
+
+@pytest.mark.parametrize("h,g,d", [(4, 4, 64), (8, 2, 64), (64, 8, 128), (6, 3, 128), (5, 5, 128), (12, 1, 64)])
+def test_decode_attention_head_layouts(rx, h, g, d):
+    got, ref = run_attention(rx, h, g, d, 600, 3, [1, 1, 1], [600, 1, 77], [2, 0, 1], seed=h * 10 + g)
+    assert_close(got, ref, "attention h=%d g=%d d=%d" % (h, g, d), atol=2e-3, rtol=1e-2)
+
+
+def test_attention_ragged_prefill_rows_and_many_sequences(rx):
+    got, ref = run_attention(rx, 8, 4, 64, 128, 4, [5, 1, 37, 2], [9, 128, 37, 66], [3, 1, 0, 2], seed=31)
+    assert_close(got, ref, "ragged attention", atol=2e-3, rtol=1e-2)
+    B = 21                                         # more sequences than ride in kernel arguments: device table path
+    kv = [int(v) for v in wl.uniform_lengths(32, B, 1, 300)]
+    got, ref = run_attention(rx, 8, 8, 64, 300, B, [1] * B, kv, list(range(B))[::-1], seed=32)
+    assert_close(got, ref, "21-sequence decode", atol=2e-3, rtol=1e-2)
+
+
+# ------------------------------------------------------------------------- whole layer
+def run_schedule(rx, shape, seed, cap, calls, slots=1, prefill_bits=None, n_max=None):
+    """calls: list of (q_lens, kv_lens, slot_ids).  Returns per-call (gpu fp32, oracle fp32) and both caches."""
+    w = wl.layer_weights(shape, seed)
+    n_max = n_max or max(int(np.sum(c[0])) for c in calls)
+    layer = device_layer(shape, w, cap, slots=slots, n_max=n_max, B_max=max(len(c[0]) for c in calls))
+    od, ow = oracle_dims(shape, cap), oracle_weights(shape, w)
+    cshape = (slots, cap, shape.n_kv_heads, shape.head_dim)
+    if prefill_bits is not None:
+        layer.load_cache(*prefill_bits)
+        Ko, Vo = f32_cache(prefill_bits[0]).reshape(cshape), f32_cache(prefill_bits[1]).reshape(cshape)
+    else:
+        Ko, Vo = np.zeros(cshape, np.float32), np.zeros(cshape, np.float32)
+    outs = []
+    for ci, (ql, kl, sl) in enumerate(calls):
+        n = int(np.sum(ql))
+        x = wl.activations(shape, seed, ci, n)
+        y = layer.forward(dev(x), ql, kl, sl)
+        torch.cuda.synchronize()
+        ref = oracle.decoder_layer(od, ow, x, Ko, Vo, oracle.Seqs(ql, kl, sl))
+        outs.append((host_bits(y).view(np.float16).astype(np.float32), ref))
+    Kg = host_bits(layer.k).view(np.float16).astype(np.float32)
+    Vg = host_bits(layer.v).view(np.float16).astype(np.float32)
+    return outs, (Kg, Vg), (Ko, Vo)
+
+
+def test_tiny_layer_prefill_then_sixteen_decode_steps(rx):
+    # workload 1: prefill n=37, then decode L=38..53, seed 0
+    calls = [([37], [37], None)] + [([1], [L], None) for L in range(38, 54)]
+    outs, (Kg, Vg), (Ko, Vo) = run_schedule(rx, wl.TINY, 0, 64, calls)
+    for ci, (g, r) in enumerate(outs):
+        assert_close(g, r, "tiny layer call %d" % ci)
+    assert_close(Kg[:, :53], Ko[:, :53], "K cache", atol=5e-3, rtol=5e-3)
+    assert_close(Vg[:, :53], Vo[:, :53], "V cache", atol=5e-3, rtol=5e-3)
+    assert np.all(Kg[:, 53:] == 0) and np.all(Vg[:, 53:] == 0)               # nothing written beyond L
+
+
+def test_tiny_layer_prefill_equals_sequential_decode_on_gpu(rx):
+    shape, n = wl.TINY, 9
+    w = wl.layer_weights(shape, 7)
+    a = device_layer(shape, w, 16, n_max=n)
+    b = device_layer(shape, w, 16, n_max=n)
+    x = dev(wl.activations(shape, 7, 0, n))
+    full = a.forward(x, [n], [n])
+    steps = torch.cat([b.forward(x[i:i + 1], [1], [i + 1]) for i in range(n)])
+    torch.cuda.synchronize()
+    assert_close(host_bits(steps).view(np.float16), host_bits(full).view(np.float16).astype(np.float32), "prefill vs decode")
+
+
+def test_tiny_layer_ragged_batch(rx):
+    calls = [([3, 5, 1], [3, 5, 1], [2, 0, 1]), ([1, 1, 1], [4, 6, 2], [2, 0, 1]), ([2, 1], [8, 3], [0, 1])]
+    outs, _, _ = run_schedule(rx, wl.TINY, 3, 32, calls, slots=3)
+    for ci, (g, r) in enumerate(outs):
+        assert_close(g, r, "ragged call %d" % ci)
+
+
+def test_layer_zero_projections_return_input(rx):
+    # zero Wo and Wdown: both residual branches vanish and the layer is the identity.  The fast matvec removes the
+    # decode offset per group in fp32 (sum x (1024+u) - 1032 sum x), so a zero matrix gives ~1e-6, not a bitwise 0.
+    shape = wl.TINY
+    w = wl.layer_weights(shape, 9)
+    w["wo.q"] = np.full_like(w["wo.q"], 0x88888888)
+    w["wdown.q"] = np.full_like(w["wdown.q"], 0x88888888)
+    layer = device_layer(shape, w, 8, n_max=4)
+    x = wl.activations(shape, 9, 0, 4)
+    y = layer.forward(dev(x), [4], [4])
+    torch.cuda.synchronize()
+    assert_close(host_bits(y).view(np.float16), wl.f16_bits_to_f32(x), "identity layer", atol=1e-4, rtol=1e-3)
+
+
+@pytest.mark.parametrize("L", [1, 300, 4096])
+def test_llama7b_layer_decode(rx, L):
+    shape, cap = wl.LLAMA7B, 4096
+    pre = wl.kv_prefill(shape, 1, 1, cap)
+    outs, (Kg, Vg), (Ko, Vo) = run_schedule(rx, shape, 1, cap, [([1], [L], None)], prefill_bits=pre)
+    g, r = outs[0]
+    assert_close(g, r, "7B decode layer L=%d" % L)
+    assert_close(Kg[0, L - 1], Ko[0, L - 1], "appended K", atol=5e-3, rtol=5e-3)
+    assert_close(Vg[0, L - 1], Vo[0, L - 1], "appended V", atol=5e-3, rtol=5e-3)
+
+
+def test_llama7b_layer_prefill_17(rx):
+    outs, _, _ = run_schedule(rx, wl.LLAMA7B, 2, 64, [([17], [17], None)])
+    assert_close(*outs[0], "7B prefill n=17")
