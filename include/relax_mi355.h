@@ -163,11 +163,19 @@ relax_status relax_decoder_layer(const relax_layer_dims *dims, const relax_layer
                                  const uint16_t *x, const relax_kv_cache *cache, const relax_seqs *seqs,
                                  uint16_t *out, int32_t n, void *ws, size_t ws_bytes, relax_stream stream);
 
-/* Test exports for the bit-exactness requirement on decoding and indexing: the same
- * device decode routine the matmul kernels use, written out densely.
+/* Test exports for the bit-exactness requirement on decoding and indexing: the device
+ * decode of (word, nibble, scale group) written out densely, one element per thread.
  * relax_unpack_int4: out int8 [m,k] in -8..7.  relax_dequantize: out fp32 [m,k].        */
 relax_status relax_unpack_int4(const relax_qmat *w, int8_t *out, relax_stream stream);
 relax_status relax_dequantize(const relax_qmat *w, float *out, relax_stream stream);
+
+/* Measurement aid: the next relax_decoder_layer call on this host thread records `start`
+ * before and `stop` after the launch of one of its steps (0 QKV matvec/GEMM, 1 attention,
+ * 2 output projection, 3 gate/up, 4 down projection) on the call's stream; the setting is
+ * consumed by that one call.  start/stop are hipEvent_t handles owned by the caller;
+ * step < 0 or NULL events clear the setting.  Lets a benchmark time one kernel of the
+ * fused layer with HIP events on the stream the kernel really runs on.                  */
+void relax_profile_step_events(void *start, void *stop, int32_t step);
 
 /* Build identity of the loaded binary (one binary serves every shape).                  */
 const char *relax_build_id(void);

@@ -60,6 +60,7 @@ _lib = None
 
 _SIGNATURES = {
     "relax_build_id": (C.c_char_p, []),
+    "relax_profile_step_events": (None, [C.c_void_p, C.c_void_p, C.c_int32]),
     "relax_workspace_bytes": (C.c_size_t, [C.POINTER(LayerDims), C.c_int32, C.c_int32, C.c_int32]),
     "relax_rope_table_bytes": (C.c_size_t, [C.POINTER(LayerDims)]),
     "relax_rope_table_init": (C.c_int32, [C.POINTER(LayerDims), C.c_void_p, C.c_void_p]),
@@ -229,3 +230,8 @@ def relax_unpack_int4(w: Optional[QMat], out: Ptr, stream=None) -> int:
 def relax_dequantize(w: Optional[QMat], out: Ptr, stream=None) -> int:
     wc = None if w is None else w.c()
     return lib().relax_dequantize(_ref(wc), _ptr(out), _stream(stream))
+
+
+def relax_profile_step_events(start: Optional[int], stop: Optional[int], step: int) -> None:
+    """start / stop: raw hipEvent_t handles (e.g. torch.cuda.Event(enable_timing=True).cuda_event after a record)."""
+    lib().relax_profile_step_events(start, stop, step)

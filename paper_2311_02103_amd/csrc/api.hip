@@ -111,9 +111,34 @@ relax_status upload_table(SeqTable &st, const std::vector<int32_t> &host_table, 
 
 inline relax_status hip_status(hipError_t e) { return e == hipSuccess ? RELAX_OK : RELAX_ERR_HIP; }
 
+// One-shot measurement hook (relax_profile_step_events): events around one step of the next layer call.
+thread_local hipEvent_t g_prof_start = nullptr, g_prof_stop = nullptr;
+thread_local int g_prof_step = -1;
+
+struct StepTimer {
+    hipEvent_t start, stop;
+    int step;
+    hipStream_t stream;
+    explicit StepTimer(hipStream_t s) : start(g_prof_start), stop(g_prof_stop), step(g_prof_step), stream(s)
+    {
+        g_prof_start = g_prof_stop = nullptr;
+        g_prof_step = -1;
+    }
+    void before(int s) const { if (s == step && start) (void)hipEventRecord(start, stream); }
+    void after(int s) const { if (s == step && stop) (void)hipEventRecord(stop, stream); }
+};
+
 }  // namespace
 
 extern "C" {
+
+void relax_profile_step_events(void *start, void *stop, int32_t step)
+{
+    const bool on = start && stop && step >= 0;
+    g_prof_start = on ? static_cast<hipEvent_t>(start) : nullptr;
+    g_prof_stop = on ? static_cast<hipEvent_t>(stop) : nullptr;
+    g_prof_step = on ? step : -1;
+}
 
 const char *relax_build_id(void) { return "relax_mi355 gfx950 " __DATE__ " " __TIME__; }
 
@@ -229,6 +254,7 @@ relax_status relax_decoder_layer(const relax_layer_dims *dims, const relax_layer
     rc = upload_table(st, host_table, ws, pl, st_);
     if (rc != RELAX_OK) return rc;
 
+    const StepTimer timer(st_);
     char *base = static_cast<char *>(ws);
     float *partials = reinterpret_cast<float *>(base + pl.partials);
     uint16_t *qbuf = reinterpret_cast<uint16_t *>(base + pl.qbuf);
@@ -242,29 +268,39 @@ relax_status relax_decoder_layer(const relax_layer_dims *dims, const relax_layer
     a.q = wt->wqkv.q, a.s = wt->wqkv.s, a.m = wt->wqkv.m, a.k = wt->wqkv.k, a.n = n;
     a.out_f16 = qbuf, a.kcache = cache->k, a.vcache = cache->v, a.rope = cache->rope;
     a.h = dm.n_heads, a.g = dm.n_kv_heads, a.d = dm.head_dim, a.kv_capacity = dm.kv_capacity, a.seqs = st;
+    timer.before(0);
     if (launch_gemv(a, X_F16_NORM, EPI_ROPE_KV, st_) != hipSuccess) return RELAX_ERR_HIP;
+    timer.after(0);
 
     // 2. attention over the cache
+    timer.before(1);
     if (launch_attention(qbuf, *cache, dm, st, L_max, attn, partials, st_) != hipSuccess) return RELAX_ERR_HIP;
+    timer.after(1);
 
     // 3. output projection + residual: x1 = x + attn Wo^T (fp32 residual stream in the workspace)
     GemvArgs o = {};
     o.x = attn, o.q = wt->wo.q, o.s = wt->wo.s, o.m = wt->wo.m, o.k = wt->wo.k, o.n = n;
     o.out_f32 = x1, o.resid = x;
+    timer.before(2);
     if (launch_gemv(o, X_F16, EPI_RESID_F32, st_) != hipSuccess) return RELAX_ERR_HIP;
+    timer.after(2);
 
     // 4. RMSNorm -> gate/up matvec -> SwiGLU
     GemvArgs f = {};
     f.x = x1, f.norm_w = wt->norm_ffn, f.eps = dm.rms_eps;
     f.q = wt->wgu.q, f.s = wt->wgu.s, f.m = wt->wgu.m, f.k = wt->wgu.k, f.n = n;
     f.out_f16 = act;
+    timer.before(3);
     if (launch_gemv(f, X_F32_NORM, EPI_SWIGLU, st_) != hipSuccess) return RELAX_ERR_HIP;
+    timer.after(3);
 
     // 5. down projection + residual
     GemvArgs dn = {};
     dn.x = act, dn.q = wt->wdown.q, dn.s = wt->wdown.s, dn.m = wt->wdown.m, dn.k = wt->wdown.k, dn.n = n;
     dn.out_f16 = out, dn.resid = x1;
+    timer.before(4);
     if (launch_gemv(dn, X_F16, EPI_RESID_F16, st_) != hipSuccess) return RELAX_ERR_HIP;
+    timer.after(4);
     return RELAX_OK;
 }
 

@@ -64,3 +64,25 @@ class DeviceLayer:
         rx.check(rx.relax_decoder_layer(self.dims, self.weights, x, self.cache, seqs, out, n, self.ws, self.ws_bytes),
                  "relax_decoder_layer")
         return out
+
+    def prepare(self, x: torch.Tensor, q_lens: Sequence[int], kv_lens: Sequence[int], slots=None,
+                out: Optional[torch.Tensor] = None, stream=None):
+        """Marshal one relax_decoder_layer call once; the returned closure only crosses the C boundary.
+        The symbolic values (n, every L_b) are still plain arguments of that C call."""
+        import ctypes as C
+        n = x.shape[0]
+        out = torch.empty_like(x) if out is None else out
+        seqs = rx.Seqs(q_lens, kv_lens, slots)
+        keep = (seqs, self.weights.c(), self.cache.c(), seqs.c(), x, out)
+        fn = rx.lib().relax_decoder_layer
+        args = (C.byref(self.dims), C.byref(keep[1]), x.data_ptr(), C.byref(keep[2]), C.byref(keep[3]), out.data_ptr(), n,
+                self.ws.data_ptr(), self.ws_bytes)
+
+        def call(stream_handle=None):
+            rc = fn(*args, stream_handle if stream_handle is not None else rx._stream(stream))
+            if rc != 0:
+                raise rx.RelaxError(rc, "relax_decoder_layer")
+            return out
+
+        call.keep = keep
+        return call

@@ -17,6 +17,7 @@ N(0, 0.02^2), activations and pre-filled cache entries N(0, 1), norm weights
 """
 from __future__ import annotations
 
+from concurrent.futures import ThreadPoolExecutor
 from dataclasses import dataclass
 from typing import Dict, Tuple
 
@@ -131,17 +132,23 @@ def quantize_q4(w: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
     return pack_codes(np.ascontiguousarray(codes)), s16.view(np.uint16)
 
 
+def _qmat_slab(seed: int, tensor_id: int, slab: int, rows: int, k: int, std: float):
+    # every slab has its own Philox counter block, so the result does not depend on how slabs are scheduled
+    g = np.random.Generator(np.random.Philox(key=[int(seed), int(tensor_id)], counter=[0, 0, int(slab) + 1, 0]))
+    w = g.standard_normal(size=(rows, k), dtype=np.float32) * np.float32(std)
+    return quantize_q4(w)
+
+
 def qmat(seed: int, tensor_id: int, m: int, k: int, std: float = 0.02) -> Tuple[np.ndarray, np.ndarray]:
-    """One random quantised matrix; generated in row slabs to bound host memory."""
-    qs, ss = [], []
-    g = rng(seed, tensor_id)
-    slab = max(1, (1 << 25) // k)
-    for r0 in range(0, m, slab):
-        rows = min(slab, m - r0)
-        w = g.standard_normal(size=(rows, k), dtype=np.float32) * np.float32(std)
-        q, s = quantize_q4(w)
-        qs.append(q), ss.append(s)
-    return np.concatenate(qs, axis=0), np.concatenate(ss, axis=0)
+    """One random quantised matrix N(0, std^2); generated in row slabs (bounded host memory, threads)."""
+    slab_rows = max(1, (1 << 22) // k)
+    jobs = [(seed, tensor_id, i, min(slab_rows, m - r0), k, std) for i, r0 in enumerate(range(0, m, slab_rows))]
+    if len(jobs) == 1:
+        parts = [_qmat_slab(*jobs[0])]
+    else:
+        with ThreadPoolExecutor(max_workers=min(8, len(jobs))) as pool:
+            parts = list(pool.map(lambda j: _qmat_slab(*j), jobs))
+    return np.concatenate([p[0] for p in parts], axis=0), np.concatenate([p[1] for p in parts], axis=0)
 
 
 def layer_weights(shape: LayerShape, seed: int, layer: int = 0) -> Dict[str, np.ndarray]:
