@@ -19,7 +19,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_HBM_GBS = 8000.0
-STEP_NAMES = ["qkv_matvec", "attention", "o_proj_matvec", "gate_up_matvec", "down_matvec"]
+STEP_NAMES = ["qkv_matvec", "attention", "o_proj_matvec", "gate_up_matvec", "down_matvec", "fused_decode_layer"]
 
 
 def main():
@@ -32,6 +32,8 @@ def main():
                     help="graph: the 64-call schedule is captured once in a HIP graph and replayed (Sec. 4.5 of the paper)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the CPU-oracle baseline leg (0 = skip)")
     ap.add_argument("--no-kernel-timing", action="store_true")
+    ap.add_argument("--path", choices=["fused", "stepwise"], default="stepwise",
+                    help="fused: one persistent kernel per layer call (default); stepwise: the six-kernel path")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus %d is not supported" % args.gpus,
@@ -46,6 +48,7 @@ def main():
     from paper_2311_02103_amd.runtime import DeviceLayer, f16_bits, to_device
 
     rx.lib()
+    rx.check(rx.relax_set_option("fused_decode", 1 if args.path == "fused" else 0))
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
     torch.cuda.set_device(0)
@@ -118,9 +121,13 @@ def main():
 
     # ---- per-kernel timing of the same steps with HIP events on the launch stream (eager launches) --------------
     kernel_ms = {}
+    kvb_call = lambda c: shape.packed_bytes_per_layer() + kvb * Ls[c] + kvb + 6 * shape.hidden * 2
+    timed_bytes = {}
     if not args.no_kernel_timing:
         nk = min(args.steps, 256)
-        for step_id, name in enumerate(STEP_NAMES):
+        step_ids = [5] if args.path == "fused" else [0, 1, 2, 3, 4]
+        for step_id in step_ids:
+            name = STEP_NAMES[step_id]
             evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(nk)]
             for a, b in evs:                        # materialise the hipEvent handles
                 a.record(stream), b.record(stream)
@@ -130,12 +137,23 @@ def main():
                 calls[i % ncalls](sh)
             stream.synchronize()
             kernel_ms[name] = float(np.mean([a.elapsed_time(b) for a, b in evs]))
+            timed_bytes[name] = float(np.mean([kvb_call(i % ncalls) for i in range(nk)]))
     m, k = shape.matrices()["wgu"]
     gu_bytes = m * (k // 2) + m * (k // 32) * 2 + shape.hidden * 4 + shape.hidden * 2 + shape.ffn * 2
     roofline = None
-    if "gate_up_matvec" in kernel_ms:
+    traffic = None
+    if args.path == "fused" and "fused_decode_layer" in kernel_ms:
+        tpath = os.path.join(ROOT, "profiles", "traffic_fused_decode_layer_7b.json")
+        if os.path.exists(tpath):
+            traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
+        nbytes, ms = timed_bytes["fused_decode_layer"], kernel_ms["fused_decode_layer"]
+        ach = nbytes / (ms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "kernel": "decode_layer_kernel<128,1> (whole layer: 113.84 MB packed weights + 16 KB*L KV "
+                                                "+ activations per launch)",
+                    "achieved": round(ach, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(ach / PEAK_HBM_GBS, 4),
+                    "traffic": traffic, "algorithmic_bytes_per_launch": int(nbytes), "avg_launch_ms": round(ms, 5)}
+    elif "gate_up_matvec" in kernel_ms:
         ach = gu_bytes / (kernel_ms["gate_up_matvec"] * 1e-3) / 1e9
-        traffic = None
         tpath = os.path.join(ROOT, "profiles", "traffic_gate_up_matvec_7b.json")
         if os.path.exists(tpath):
             traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
@@ -184,7 +202,7 @@ def main():
         "config": {"workload": "configs[1]: one Llama-2-7B-shaped int4-g32 decoder layer, decode only, batch 1, n=1, "
                                "L~U{1..4096} over 64 seeded calls; 1 step = 1 token through 1 layer (a 32-layer model "
                                "does 32 such steps per token); %d rotating weight sets" % args.sets,
-                   "mode": args.mode, "mean_L": round(mean_L, 1), "build_id": rx.relax_build_id(),
+                   "mode": args.mode, "path": args.path, "mean_L": round(mean_L, 1), "build_id": rx.relax_build_id(),
                    "setup_s": round(setup_s, 1)},
         "layer_hbm": {"algorithmic_bytes_per_step": int(layer_bytes), "achieved_GBps": round(layer_gbs, 1),
                       "frac_of_peak": round(layer_gbs / PEAK_HBM_GBS, 4)},

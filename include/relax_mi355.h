@@ -118,6 +118,25 @@ typedef struct {
  * Returns 0 if dims is NULL or inconsistent.                                            */
 size_t relax_workspace_bytes(const relax_layer_dims *dims, int32_t n_max, int32_t L_max, int32_t B_max);
 
+/* The front of the workspace holds the state of the persistent fused decode kernel: an epoch counter and
+ * the exchange buffers whose 8-byte words carry {value, epoch}.  It must be zeroed once before the first
+ * call that uses the workspace -- relax_workspace_init does that (one small kernel on `stream`) -- and is
+ * then maintained by the calls themselves (every call bumps the epoch).  Call it again after
+ * relax_workspace_error reported a failure.
+ * relax_workspace_error copies the sticky failure flag of the fused kernel to the host (synchronous): it
+ * is set when a bounded wait for another workgroup's data ran out (the kernel then finishes without
+ * hanging and its output is invalid), which means the GPU could not keep one workgroup per CU resident
+ * -- e.g. another kernel was occupying CUs.                                                          */
+relax_status relax_workspace_init(const relax_layer_dims *dims, void *ws, size_t ws_bytes, relax_stream stream);
+relax_status relax_workspace_error(const relax_layer_dims *dims, const void *ws, int32_t *flag_host);
+
+/* Tuning / test switch.  "fused_decode" (default 0): when 1, a call with n == 1 and B == 1 whose matrices
+ * allow it (k % 32 == 0, 16-byte aligned, everything fits LDS) runs as ONE persistent kernel whose steps are
+ * chained by published {value, epoch} words instead of kernel boundaries; 0 uses the step-by-step kernels
+ * that serve every shape (the fused kernel is correct but currently slower: each step transition costs a
+ * memory round trip under full HBM load).  Unknown name: RELAX_ERR_UNSUPPORTED.                        */
+relax_status relax_set_option(const char *name, int32_t value);
+
 /* Bytes of the rotary table for these dims, and the call that fills it on the device
  * (angles, cos and sin evaluated in fp64, stored as fp32).  Pairing is half-split:
  * element t < d/2 rotates with element t + d/2 at frequency base^(-2t/d).               */
@@ -171,11 +190,17 @@ relax_status relax_dequantize(const relax_qmat *w, float *out, relax_stream stre
 
 /* Measurement aid: the next relax_decoder_layer call on this host thread records `start`
  * before and `stop` after the launch of one of its steps (0 QKV matvec/GEMM, 1 attention,
- * 2 output projection, 3 gate/up, 4 down projection) on the call's stream; the setting is
+ * 2 output projection, 3 gate/up, 4 down projection, 5 the fused single-launch decode
+ * layer) on the call's stream; the setting is
  * consumed by that one call.  start/stop are hipEvent_t handles owned by the caller;
  * step < 0 or NULL events clear the setting.  Lets a benchmark time one kernel of the
  * fused layer with HIP events on the stream the kernel really runs on.                  */
 void relax_profile_step_events(void *start, void *stop, int32_t step);
+
+/* Measurement aid: when set to a device buffer of 16 uint64 per CU, every workgroup of the fused decode kernel
+ * stamps the 100 MHz wall clock into its 16 slots at each step boundary (kernel start, then the end of: staging A, step A, attention items, merge,
+ * staging C, step C, staging D, step D, staging E, step E).  NULL switches it off (default).                                                          */
+void relax_profile_trace_buffer(void *dev_u64x16);
 
 /* Build identity of the loaded binary (one binary serves every shape).                  */
 const char *relax_build_id(void);

@@ -9,5 +9,6 @@ from . import binding  # noqa: F401
 from .binding import (  # noqa: F401
     KVCache, LayerDims, LayerWeights, QMat, RelaxError, Seqs, check, make_dims,
     relax_attention, relax_build_id, relax_decoder_layer, relax_dequant_matmul, relax_dequantize,
-    relax_rmsnorm_rope, relax_rope_table_bytes, relax_rope_table_init, relax_unpack_int4, relax_workspace_bytes,
+    relax_rmsnorm_rope, relax_rope_table_bytes, relax_rope_table_init, relax_set_option, relax_unpack_int4, relax_workspace_bytes, relax_workspace_error,
+    relax_workspace_init,
 )

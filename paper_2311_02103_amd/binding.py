@@ -60,6 +60,10 @@ _lib = None
 
 _SIGNATURES = {
     "relax_build_id": (C.c_char_p, []),
+    "relax_set_option": (C.c_int32, [C.c_char_p, C.c_int32]),
+    "relax_profile_trace_buffer": (None, [C.c_void_p]),
+    "relax_workspace_init": (C.c_int32, [C.POINTER(LayerDims), C.c_void_p, C.c_size_t, C.c_void_p]),
+    "relax_workspace_error": (C.c_int32, [C.POINTER(LayerDims), C.c_void_p, C.POINTER(C.c_int32)]),
     "relax_profile_step_events": (None, [C.c_void_p, C.c_void_p, C.c_int32]),
     "relax_workspace_bytes": (C.c_size_t, [C.POINTER(LayerDims), C.c_int32, C.c_int32, C.c_int32]),
     "relax_rope_table_bytes": (C.c_size_t, [C.POINTER(LayerDims)]),
@@ -235,3 +239,22 @@ def relax_dequantize(w: Optional[QMat], out: Ptr, stream=None) -> int:
 def relax_profile_step_events(start: Optional[int], stop: Optional[int], step: int) -> None:
     """start / stop: raw hipEvent_t handles (e.g. torch.cuda.Event(enable_timing=True).cuda_event after a record)."""
     lib().relax_profile_step_events(start, stop, step)
+
+
+def relax_set_option(name: str, value: int) -> int:
+    return lib().relax_set_option(name.encode(), value)
+
+
+def relax_workspace_init(dims: Optional[LayerDims], ws: Ptr, ws_bytes: int, stream=None) -> int:
+    return lib().relax_workspace_init(_ref(dims), _ptr(ws), ws_bytes, _stream(stream))
+
+
+def relax_workspace_error(dims: Optional[LayerDims], ws: Ptr) -> int:
+    """Returns the sticky failure flag of the fused kernel (0 = fine); raises on a call error."""
+    flag = C.c_int32(0)
+    check(lib().relax_workspace_error(_ref(dims), _ptr(ws), C.byref(flag)), "relax_workspace_error")
+    return flag.value
+
+
+def relax_profile_trace_buffer(buf: Ptr) -> None:
+    lib().relax_profile_trace_buffer(_ptr(buf))

@@ -1,6 +1,7 @@
 // C ABI of librelax_mi355.so: argument checks (all on the host, before anything is enqueued),
 // the workspace plan, and the launch sequence of each exported call.  See include/relax_mi355.h
 // for the contract and for the passages of the paper each rule comes from.
+#include <cstring>
 #include <vector>
 
 #include "relax_common.h"
@@ -14,7 +15,7 @@ inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 // Static plan of the lifted workspace (Sec. 4.3 upper bounds, Sec. 4.4 lifting).  Offsets are a
 // pure function of (dims, n, L, B); a call sized by upper bounds covers every smaller call.
 struct WsPlan {
-    size_t table, partials, qbuf, attn, x1, act, xn, qkv, total;
+    size_t sync, f_q, f_knew, f_vnew, f_attn, f_x1, f_act, f_part, f_end, table, partials, qbuf, attn, x1, act, xn, qkv, total;
 };
 
 WsPlan plan_ws(const relax_layer_dims &dm, int32_t n, int32_t L, int32_t B)
@@ -23,6 +24,19 @@ WsPlan plan_ws(const relax_layer_dims &dm, int32_t n, int32_t L, int32_t B)
     size_t off = 0;
     const size_t hd = (size_t)dm.n_heads * dm.head_dim;
     const size_t qkvw = (size_t)(dm.n_heads + 2 * dm.n_kv_heads) * dm.head_dim;
+    // the sync area sits at offset 0 and depends on the static dims only: it has to stay zero from call to call
+    p.sync = off;     off += align256(decode_layer_sync_bytes(dm));
+    // exchange buffers of the fused decode kernel (n = 1): 8-byte {value, epoch} words for q, the new k/v row,
+    // attention output, x1, SwiGLU output and the split-L partials; they depend on the static dims only as well
+    const size_t gd = (size_t)dm.n_kv_heads * dm.head_dim;
+    p.f_q = off;      off += align256(8 * hd);
+    p.f_knew = off;   off += align256(8 * gd);
+    p.f_vnew = off;   off += align256(8 * gd);
+    p.f_attn = off;   off += align256(8 * hd);
+    p.f_x1 = off;     off += align256(8 * (size_t)dm.hidden);
+    p.f_act = off;    off += align256(8 * (size_t)dm.ffn);
+    p.f_part = off;   off += align256(8 * (size_t)dm.n_heads * kFusedMaxSplits * (size_t)(dm.head_dim + 2));
+    p.f_end = off;
     p.table = off;    off += align256(sizeof(int32_t) * 4 * (size_t)(B > 1 ? B : 1));
     p.partials = off; off += align256(sizeof(float) * attn_partial_floats(dm, n, L));
     p.qbuf = off;     off += align256(2 * (size_t)n * hd);
@@ -128,9 +142,61 @@ struct StepTimer {
     void after(int s) const { if (s == step && stop) (void)hipEventRecord(stop, stream); }
 };
 
+// Tuning / test switches (relax_set_option).
+int g_opt_fused_decode = 0;
+unsigned long long *g_trace = nullptr;      // relax_profile_trace_buffer
+
+// CU count of the current device (the fused kernel launches exactly one workgroup per CU).
+int device_cus()
+{
+    static int cus[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
+    if (cus[dev] == 0) {
+        int v = 0;
+        if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+        cus[dev] = v;
+    }
+    return cus[dev];
+}
+
 }  // namespace
 
 extern "C" {
+
+void relax_profile_trace_buffer(void *dev_u64x16) { g_trace = static_cast<unsigned long long *>(dev_u64x16); }
+
+relax_status relax_set_option(const char *name, int32_t value)
+{
+    if (!name) return RELAX_ERR_NULL;
+    if (std::strcmp(name, "fused_decode") == 0) {
+        g_opt_fused_decode = value;
+        return RELAX_OK;
+    }
+    return RELAX_ERR_UNSUPPORTED;
+}
+
+relax_status relax_workspace_init(const relax_layer_dims *dims, void *ws, size_t ws_bytes, relax_stream stream)
+{
+    relax_status rc = check_dims(dims);
+    if (rc != RELAX_OK) return rc;
+    if (!ws) return RELAX_ERR_NULL;
+    const size_t span = plan_ws(*dims, 1, 1, 1).f_end;        // sync area + exchange buffers
+    if (ws_bytes < span) return RELAX_ERR_WORKSPACE;
+    return hip_status(launch_sync_clear(ws, span, static_cast<hipStream_t>(stream)));
+}
+
+relax_status relax_workspace_error(const relax_layer_dims *dims, const void *ws, int32_t *flag_host)
+{
+    relax_status rc = check_dims(dims);
+    if (rc != RELAX_OK) return rc;
+    if (!ws || !flag_host) return RELAX_ERR_NULL;
+    uint32_t v = 0;
+    if (hipMemcpy(&v, static_cast<const char *>(ws) + decode_layer_error_offset(), sizeof(v), hipMemcpyDeviceToHost) != hipSuccess)
+        return RELAX_ERR_HIP;
+    *flag_host = (int32_t)v;
+    return RELAX_OK;
+}
 
 void relax_profile_step_events(void *start, void *stop, int32_t step)
 {
@@ -172,6 +238,7 @@ relax_status relax_dequant_matmul(const uint16_t *x, const relax_qmat *w, uint16
     if (n < 1) return RELAX_ERR_SHAPE;
     GemvArgs a = {};
     a.x = x, a.q = w->q, a.s = w->s, a.m = w->m, a.k = w->k, a.n = n, a.out_f16 = out;
+    a.trace = g_trace;
     return hip_status(launch_gemv(a, X_F16, EPI_F16, static_cast<hipStream_t>(stream)));
 }
 
@@ -256,6 +323,35 @@ relax_status relax_decoder_layer(const relax_layer_dims *dims, const relax_layer
 
     const StepTimer timer(st_);
     char *base = static_cast<char *>(ws);
+
+    // Runtime dispatch on the symbolic shape (Sec. 5.1): a single decode row takes the persistent fused kernel.
+    if (g_opt_fused_decode && n == 1 && seqs->B == 1) {
+        const int cus = device_cus();
+        if (decode_layer_eligible(dm, *wt, n, seqs->B, cus)) {
+            DecodeLayerArgs fa = {};
+            fa.wqkv = {wt->wqkv.q, wt->wqkv.s, wt->wqkv.m, wt->wqkv.k};
+            fa.wo = {wt->wo.q, wt->wo.s, wt->wo.m, wt->wo.k};
+            fa.wgu = {wt->wgu.q, wt->wgu.s, wt->wgu.m, wt->wgu.k};
+            fa.wdown = {wt->wdown.q, wt->wdown.s, wt->wdown.m, wt->wdown.k};
+            fa.norm_attn = wt->norm_attn, fa.norm_ffn = wt->norm_ffn, fa.x = x, fa.out = out;
+            fa.kcache = cache->k, fa.vcache = cache->v, fa.rope = cache->rope;
+            fa.H = dm.hidden, fa.h = dm.n_heads, fa.g = dm.n_kv_heads, fa.d = dm.head_dim, fa.F = dm.ffn, fa.cap = dm.kv_capacity;
+            fa.eps = dm.rms_eps;
+            fa.pos = st.kv_len[0] - 1, fa.slot = st.slot[0];
+            fa.sync = reinterpret_cast<uint32_t *>(base + pl.sync);
+            typedef unsigned long long u64;
+            fa.q_ll = reinterpret_cast<u64 *>(base + pl.f_q), fa.knew_ll = reinterpret_cast<u64 *>(base + pl.f_knew);
+            fa.vnew_ll = reinterpret_cast<u64 *>(base + pl.f_vnew), fa.attn_ll = reinterpret_cast<u64 *>(base + pl.f_attn);
+            fa.x1_ll = reinterpret_cast<u64 *>(base + pl.f_x1), fa.act_ll = reinterpret_cast<u64 *>(base + pl.f_act);
+            fa.part_ll = reinterpret_cast<u64 *>(base + pl.f_part);
+            fa.trace = g_trace;
+            timer.before(5);
+            if (launch_decode_layer(fa, cus, st_) != hipSuccess) return RELAX_ERR_HIP;
+            timer.after(5);
+            return RELAX_OK;
+        }
+    }
+
     float *partials = reinterpret_cast<float *>(base + pl.partials);
     uint16_t *qbuf = reinterpret_cast<uint16_t *>(base + pl.qbuf);
     uint16_t *attn = reinterpret_cast<uint16_t *>(base + pl.attn);

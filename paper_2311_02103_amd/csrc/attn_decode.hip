@@ -160,23 +160,35 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const uint16_t *__restr
     }
 }
 
-// one workgroup of D threads per (row, head): out = sum_s acc_s e^(m_s - M) / sum_s l_s e^(m_s - M)
+// one workgroup of D threads per (row, head): out = sum_s acc_s e^(m_s - M) / sum_s l_s e^(m_s - M).
+// The per-split scales are computed once (thread s owns split s) and shared through LDS; the accumulator loads of
+// a thread are independent of each other, so they are all in flight together.
 template <int D>
 __global__ void attn_merge_kernel(const float *__restrict__ part, uint16_t *__restrict__ out, SeqTable st, int h, int chunk,
                                   int splits)
 {
+    extern __shared__ float scale[];                           // [splits] e^(m_s - M), then [1] 1 / denominator
     const int i = blockIdx.x / h, e = threadIdx.x;
     const RowInfo ri = row_info(st, i);
     const int used = (ri.pos + chunk) / chunk;                 // ceil((pos+1)/chunk)
     const float *src = part + (size_t)blockIdx.x * splits * (D + 2);
+    for (int s = e; s < used; s += D) scale[s] = src[s * (D + 2) + D];
+    __syncthreads();
     float mm = -INFINITY;
-    for (int s = 0; s < used; ++s) mm = fmaxf(mm, src[s * (D + 2) + D]);
+    for (int s = 0; s < used; ++s) mm = fmaxf(mm, scale[s]);
+    __syncthreads();
+    for (int s = e; s < used; s += D) scale[s] = __expf(scale[s] - mm);
+    __syncthreads();
     float num = 0.0f, den = 0.0f;
-    for (int s = 0; s < used; ++s) {
-        const float sc = __expf(src[s * (D + 2) + D] - mm);
-        num += src[s * (D + 2) + e] * sc;
-        den += src[s * (D + 2) + D + 1] * sc;
+    int s = 0;
+    for (; s + 8 <= used; s += 8) {
+        float a8[8], l8[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) a8[j] = src[(s + j) * (D + 2) + e], l8[j] = src[(s + j) * (D + 2) + D + 1];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) num += a8[j] * scale[s + j], den += l8[j] * scale[s + j];
     }
+    for (; s < used; ++s) num += src[s * (D + 2) + e] * scale[s], den += src[s * (D + 2) + D + 1] * scale[s];
     out[(size_t)blockIdx.x * D + e] = f2h(num / den);
 }
 
@@ -202,7 +214,7 @@ static hipError_t launch_d(const uint16_t *q, const relax_kv_cache &cache, const
     else if (rep % 2 == 0) e = launch_split<D, 2>(q, cache, dm, st, pl, partials, stream);
     else e = launch_split<D, 1>(q, cache, dm, st, pl, partials, stream);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((attn_merge_kernel<D>), dim3(st.n * dm.n_heads), dim3(D), 0, stream, partials, out, st, dm.n_heads,
+    hipLaunchKernelGGL((attn_merge_kernel<D>), dim3(st.n * dm.n_heads), dim3(D), sizeof(float) * (size_t)pl.splits, stream, partials, out, st, dm.n_heads,
                        pl.chunk, pl.splits);
     return hipGetLastError();
 }

@@ -16,26 +16,12 @@
 // accumulates in fp32.  The offsets are removed per group with two precomputed sums of x:
 //   sum x (u-8) = [sum_A x (1024+u)] + [sum_B x (1024+16u)]/16 - (1032 sum_A x + 72 sum_B x).
 // Every quantity is an exact small multiple of the inputs, so integer-valued test cases stay exact.
-#include "relax_common.h"
+#include <algorithm>
+#include <cstdlib>
+
+#include "q4_device.h"
 
 namespace relax {
-
-typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
-
-__device__ inline float dot2(uint32_t a_bits, uint32_t b_bits, float acc)
-{
-    return __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, a_bits), __builtin_bit_cast(half2_t, b_bits), acc, false);
-}
-
-// position of element e (0..7) of a word inside the staged 8-element x packet [x0 x4 x1 x5 x2 x6 x3 x7]
-__device__ inline int packet_pos(int e) { return ((e & 3) << 1) | (e >> 2); }
-
-// LDS offset (in halfs) of x element c in the fast-path layout: [chunk of 2048][word j of the group][lane][8]
-__device__ inline int fast_off(int c)
-{
-    int chunk = c >> 11, lane = (c & 2047) >> 5, j = (c & 31) >> 3, e = c & 7;
-    return ((((chunk << 2) + j) << 6) + lane) * 8 + packet_pos(e);
-}
 
 template <int EPI>
 __device__ inline int unit_count(const GemvArgs &a)
@@ -156,17 +142,7 @@ __global__ __launch_bounds__(512) void gemv_q4_kernel(GemvArgs a)
     }
     __syncthreads();
     if (FAST) {
-        for (int gi = tid; gi < G; gi += blockDim.x) {
-            int chunk = gi >> 6, ln = gi & 63;
-            float sa = 0.0f, sb = 0.0f;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const uint16_t *p = xs + ((((chunk << 2) + j) << 6) + ln) * 8;
-                sa += h2f(p[0]) + h2f(p[1]) + h2f(p[4]) + h2f(p[5]);
-                sb += h2f(p[2]) + h2f(p[3]) + h2f(p[6]) + h2f(p[7]);
-            }
-            corr[gi] = 1032.0f * sa + 72.0f * sb;
-        }
+        for (int gi = tid; gi < G; gi += blockDim.x) corr[gi] = group_corr(xs, gi);
         __syncthreads();
     }
 
@@ -200,20 +176,7 @@ __global__ __launch_bounds__(512) void gemv_q4_kernel(GemvArgs a)
                         sc[r] = h2f(a.s[(size_t)rows[r] * G + gi]);
                     }
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        const uint32_t ww[4] = {wv[r].x, wv[r].y, wv[r].z, wv[r].w};
-                        float accA = 0.0f, accB = 0.0f;
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            const uint32_t w = ww[j], w8 = w >> 8;
-                            const uint32_t xw[4] = {xv[j].x, xv[j].y, xv[j].z, xv[j].w};
-                            accA = dot2((w & 0x000F000Fu) | 0x64006400u, xw[0], accA);
-                            accB = dot2((w & 0x00F000F0u) | 0x64006400u, xw[1], accB);
-                            accA = dot2((w8 & 0x000F000Fu) | 0x64006400u, xw[2], accA);
-                            accB = dot2((w8 & 0x00F000F0u) | 0x64006400u, xw[3], accB);
-                        }
-                        tot[r] += sc[r] * (accA + accB * 0.0625f - cr);
-                    }
+                    for (int r = 0; r < 4; ++r) tot[r] += sc[r] * group_dot(wv[r], xv, cr);
                 }
             }
         } else {
@@ -241,20 +204,272 @@ __global__ __launch_bounds__(512) void gemv_q4_kernel(GemvArgs a)
     }
 }
 
+// ---- streaming kernel for the fast layout (k % 32 == 0, 16-byte aligned rows) -----------------------------------------
+//
+// Persistent shape: a few workgroups per CU, six wavefronts each; every wavefront walks tiles of four matrix
+// rows (two units the epilogue consumes together) in trips of 4 rows x 2 chunks of 2048 columns = 8 KB, with
+// two trips in flight (double buffer, branch-free so that consuming one trip never waits for the next one).
+// The first two trips are requested BEFORE the x row is staged -- weights do not depend on x -- and the
+// workgroup barriers of the staging fence LDS only, so those loads stay in flight across them.  Sums of a
+// tile go to LDS; after the loop lane j finishes the wavefront's j-th tile (loads and stores of the
+// epilogue never interleave with the weight stream).
+constexpr int kSThreads = 256, kSWaves = kSThreads / kWave, kSMaxTiles = 16;
+
+template <int EPI>
+__device__ __forceinline__ void stream_tile_rows(const GemvArgs &a, int tile, int *rows)
+{
+    if (EPI == EPI_ROPE_KV) {
+        const int d4 = a.d >> 2, nqk = (a.h + a.g) * d4;
+        if (tile < nqk) {
+            const int j = tile / d4, t = (tile - j * d4) * 2;
+            rows[0] = j * a.d + t, rows[1] = rows[0] + (a.d >> 1), rows[2] = rows[0] + 1, rows[3] = rows[1] + 1;
+        } else {
+            rows[0] = (a.h + a.g) * a.d + 4 * (tile - nqk);
+            rows[1] = rows[0] + 1, rows[2] = rows[0] + 2, rows[3] = rows[0] + 3;
+        }
+    } else if (EPI == EPI_SWIGLU) {
+        const int F = a.m >> 1;
+        rows[0] = 2 * tile, rows[1] = rows[0] + F, rows[2] = rows[0] + 1, rows[3] = rows[1] + 1;
+    } else {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) rows[r] = min(4 * tile + r, a.m - 1);
+    }
+}
+
+template <int EPI>
+__device__ __forceinline__ void stream_epilogue(const GemvArgs &a, int i, const RowInfo &ri, int tile, const float *v)
+{
+    const size_t base = (size_t)i * a.m;
+    if (EPI == EPI_F16 || EPI == EPI_RESID_F32 || EPI == EPI_RESID_F16) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int row = 4 * tile + r;
+            if (row < a.m) {
+                if (EPI == EPI_F16) a.out_f16[base + row] = f2h(v[r]);
+                else if (EPI == EPI_RESID_F32) a.out_f32[base + row] = h2f(((const uint16_t *)a.resid)[base + row]) + v[r];
+                else a.out_f16[base + row] = f2h(((const float *)a.resid)[base + row] + v[r]);
+            }
+        }
+    } else if (EPI == EPI_SWIGLU) {
+        const int F = a.m >> 1;
+        uint16_t *dst = a.out_f16 + (size_t)i * F + 2 * tile;
+        dst[0] = f2h(v[0] / (1.0f + expf(-v[0])) * v[1]);
+        dst[1] = f2h(v[2] / (1.0f + expf(-v[2])) * v[3]);
+    } else {  // EPI_ROPE_KV
+        const int d4 = a.d >> 2, hd2 = a.d >> 1, nqk = (a.h + a.g) * d4;
+        const size_t tok = ((size_t)ri.slot * a.kv_capacity + ri.pos) * (size_t)(a.g * a.d);
+        if (tile < nqk) {
+            const int j = tile / d4, t = (tile - j * d4) * 2;
+            const float4 cs = *(const float4 *)(a.rope + ((size_t)ri.pos * hd2 + t) * 2);       // cos_t sin_t cos_t+1 sin_t+1
+            const float p0 = v[0] * cs.x - v[1] * cs.y, q0 = v[0] * cs.y + v[1] * cs.x;
+            const float p1 = v[2] * cs.z - v[3] * cs.w, q1 = v[2] * cs.w + v[3] * cs.z;
+            uint16_t *dst = (j < a.h) ? a.out_f16 + (size_t)i * (a.h * a.d) + (size_t)j * a.d + t
+                                      : a.kcache + tok + (size_t)(j - a.h) * a.d + t;
+            dst[0] = f2h(p0), dst[1] = f2h(p1), dst[hd2] = f2h(q0), dst[hd2 + 1] = f2h(q1);
+        } else {
+            uint16_t *dst = a.vcache + tok + 4 * (size_t)(tile - nqk);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) dst[r] = f2h(v[r]);
+        }
+    }
+}
+
+template <int XMODE, int EPI, int PX>
+__global__ __launch_bounds__(kSThreads) void gemv_q4_stream_kernel(GemvArgs a)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    __shared__ float red[kSWaves];
+    const int k = a.k, G = k >> 5, nchunks = (k + 2047) >> 11, kpad = nchunks << 11;
+    uint16_t *xs = (uint16_t *)smem;
+    float *corr = (float *)(smem + (size_t)kpad * 2);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    float *res = corr + ((G + 63) & ~63) + wave * (kSMaxTiles * 4);
+    const int i = blockIdx.y;
+    const DLMat M = {a.q, a.s, a.m, a.k};
+    const int ntiles = (EPI == EPI_ROPE_KV || EPI == EPI_SWIGLU) ? (a.m >> 2) : ((a.m + 3) >> 2);
+    const int nsub = (nchunks + 1) >> 1;
+    const int W = gridDim.x * kSWaves, wave_global = blockIdx.x * kSWaves + wave;
+    const int mine = wave_global < ntiles ? (ntiles - wave_global + W - 1) / W : 0;
+    const int nsu = mine * nsub;
+    auto stamp = [&](int s) {
+        if (a.trace && tid == 0 && blockIdx.y == 0) a.trace[blockIdx.x * 8 + s] = wall_clock64();
+    };
+    stamp(0);
+
+    auto target = [&](int su, int *rows, int &chunk0) {
+        const bool live = su < nsu;
+        const int j = su / nsub, sub = su - j * nsub;
+        stream_tile_rows<EPI>(a, live ? wave_global + j * W : 0, rows);
+        chunk0 = live ? sub * 2 : 0;
+    };
+    // ---- loads in the order they are needed: memory operations of a wavefront complete in order, so the x row (and
+    //      the norm weights) go out first and the two weight trips right behind them -------------------------------
+    const size_t xbase = (size_t)i * k;
+    constexpr int PN = 4;                   // passes of 256 threads x 8 elements: PN covers 8192 (norm modes), PX the plain row
+    float vals[XMODE != X_F16 ? PN : 1][8];
+    uint4 wnr[XMODE != X_F16 ? PN : 1];
+    uint4 xraw[XMODE == X_F16 ? PX : 1];
+    if (XMODE != X_F16) {
+#pragma unroll
+        for (int p = 0; p < PN; ++p) {
+            const int c8 = min(tid + p * kSThreads, (k >> 3) - 1);
+            if (XMODE == X_F32_NORM) {
+                const float4 lo = *(const float4 *)((const float *)a.x + xbase + c8 * 8), hi = *(const float4 *)((const float *)a.x + xbase + c8 * 8 + 4);
+                vals[p][0] = lo.x, vals[p][1] = lo.y, vals[p][2] = lo.z, vals[p][3] = lo.w;
+                vals[p][4] = hi.x, vals[p][5] = hi.y, vals[p][6] = hi.z, vals[p][7] = hi.w;
+            } else {
+                const uint4 raw = *(const uint4 *)((const uint16_t *)a.x + xbase + c8 * 8);
+                const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) vals[p][2 * j] = h2f((uint16_t)(w[j] & 0xFFFFu)), vals[p][2 * j + 1] = h2f((uint16_t)(w[j] >> 16));
+            }
+            wnr[p] = *(const uint4 *)(a.norm_w + c8 * 8);
+        }
+    } else {
+#pragma unroll
+        for (int p = 0; p < PX; ++p) {
+            const int c8 = min(tid + p * kSThreads, (k >> 3) - 1);
+            xraw[p] = *(const uint4 *)((const uint16_t *)a.x + xbase + c8 * 8);
+        }
+    }
+    Slot s0, s1;
+    {
+        int rows[4], chunk0;
+        target(0, rows, chunk0);
+        slot_load(s0, M, rows, chunk0, 0, lane);
+        target(1, rows, chunk0);
+        slot_load(s1, M, rows, chunk0, 0, lane);
+    }
+
+    stamp(1);
+    // ---- stage the (optionally RMS-normalised) x row in LDS as fp16 in the packet order [x0 x4 x1 x5 x2 x6 x3 x7] ----
+    auto put8 = [&](int c8, const float *y) {
+        const uint32_t o0 = (uint32_t)f2h(y[0]) | ((uint32_t)f2h(y[4]) << 16), o1 = (uint32_t)f2h(y[1]) | ((uint32_t)f2h(y[5]) << 16);
+        const uint32_t o2 = (uint32_t)f2h(y[2]) | ((uint32_t)f2h(y[6]) << 16), o3 = (uint32_t)f2h(y[3]) | ((uint32_t)f2h(y[7]) << 16);
+        *(uint4 *)(xs + fast_off(c8 * 8)) = make_uint4(o0, o1, o2, o3);
+    };
+    if (XMODE != X_F16) {
+        float ss = 0.0f;
+#pragma unroll
+        for (int p = 0; p < PN; ++p)
+            if ((tid + p * kSThreads) * 8 < k) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) ss += vals[p][e] * vals[p][e];
+            }
+        ss = wave_sum(ss);
+        if (lane == 0) red[wave] = ss;
+        wg_barrier();
+        float tot = 0.0f;
+#pragma unroll
+        for (int w = 0; w < kSWaves; ++w) tot += red[w];
+        const float inv = 1.0f / sqrtf(tot / (float)k + a.eps);
+#pragma unroll
+        for (int p = 0; p < PN; ++p) {
+            const int c8 = tid + p * kSThreads;
+            if (c8 * 8 < kpad) {
+                const uint32_t w[4] = {wnr[p].x, wnr[p].y, wnr[p].z, wnr[p].w};
+                float y[8];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    y[2 * j] = c8 * 8 < k ? vals[p][2 * j] * inv * h2f((uint16_t)(w[j] & 0xFFFFu)) : 0.0f;
+                    y[2 * j + 1] = c8 * 8 < k ? vals[p][2 * j + 1] * inv * h2f((uint16_t)(w[j] >> 16)) : 0.0f;
+                }
+                put8(c8, y);
+            }
+        }
+    } else {
+#pragma unroll
+        for (int p = 0; p < PX; ++p) {
+            const int c8 = tid + p * kSThreads;
+            if (c8 * 8 < kpad) {
+                const uint32_t w[4] = {xraw[p].x, xraw[p].y, xraw[p].z, xraw[p].w};
+                float y[8];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    y[2 * j] = c8 * 8 < k ? h2f((uint16_t)(w[j] & 0xFFFFu)) : 0.0f;
+                    y[2 * j + 1] = c8 * 8 < k ? h2f((uint16_t)(w[j] >> 16)) : 0.0f;
+                }
+                put8(c8, y);
+            }
+        }
+    }
+    wg_barrier();
+    for (int gi = tid; gi < G; gi += kSThreads) corr[gi] = group_corr(xs, gi);
+    wg_barrier();
+
+    stamp(2);
+    RowInfo ri = {0, 0, 0};
+    if (EPI == EPI_ROPE_KV) ri = row_info(a.seqs, i);
+
+    // ---- trips ------------------------------------------------------------------------------------------------
+    float acc8[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc8[e] = 0.0f;
+    auto trip = [&](Slot &s, int su) {
+        const int j = su / nsub, sub = su - j * nsub;
+        slot_consume(s, M, xs, corr, sub * 2, 0, lane, su < nsu, acc8);
+        int rows[4], chunk0;
+        target(su + 2, rows, chunk0);
+        slot_load(s, M, rows, chunk0, 0, lane);
+        if (su < nsu && sub == nsub - 1) {
+            float v[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) v[r] = wave_sum(acc8[r] + acc8[r + 4]);
+            if (lane == 0) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) res[j * 4 + r] = v[r];
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc8[e] = 0.0f;
+        }
+    };
+#pragma unroll 1
+    for (int su = 0; su < nsu; su += 2) {
+        trip(s0, su);
+        trip(s1, su + 1);
+    }
+    stamp(3);
+    if (lane < mine) {
+        float v[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) v[r] = res[lane * 4 + r];
+        stream_epilogue<EPI>(a, i, ri, wave_global + lane * W, v);
+    }
+    stamp(4);
+}
+
 template <int XMODE, int EPI>
 static hipError_t launch_t(const GemvArgs &a, hipStream_t stream)
 {
     const int k = a.k, G = groups_of(k);
-    const bool fast = (k % kGroup == 0) && ((k / 8) % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.q) & 15) == 0);
+    const bool fast = (k % kGroup == 0) && ((k / 8) % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.q) & 15) == 0) &&
+                      ((reinterpret_cast<uintptr_t>(a.x) & 15) == 0) && ((reinterpret_cast<uintptr_t>(a.norm_w) & 15) == 0);
     const int threads = 512, nwaves = threads / kWave;
     int U = (EPI == EPI_SWIGLU) ? a.m / 2 : (a.m + 1) / 2;
     int gx = (U + 2 * nwaves - 1) / (2 * nwaves);
     if (gx > 1024) gx = 1024;
     if (gx < 1) gx = 1;
     dim3 grid(gx, a.n), block(threads);
-    if (fast) {
-        size_t lds = (size_t)((k + 2047) / 2048) * 2048 * 2 + (size_t)G * 4;
-        hipLaunchKernelGGL((gemv_q4_kernel<XMODE, EPI, true>), grid, block, lds, stream, a);
+    if (fast && (XMODE == X_F16 ? k <= 14 * kSThreads * 8 : k <= 4 * kSThreads * 8)) {
+        const int ntiles = (EPI == EPI_ROPE_KV || EPI == EPI_SWIGLU) ? a.m / 4 : (a.m + 3) / 4;
+        const size_t lds = (size_t)((k + 2047) / 2048) * 2048 * 2 + (size_t)((G + 63) / 64 * 64) * 4 + kSWaves * kSMaxTiles * 4 * 4;
+        const bool small_k = k <= 6 * kSThreads * 8;
+        auto kern = small_k ? gemv_q4_stream_kernel<XMODE, EPI, 6> : gemv_q4_stream_kernel<XMODE, EPI, 14>;
+        // workgroups that are resident at the same time (CUs x occupancy): the grid never exceeds it, so that every
+        // workgroup starts at once and each wavefront keeps streaming until its share is done
+        static int resident[2] = {0, 0};
+        if (resident[small_k] == 0) {
+            int dev = 0, cus = 0, occ = 0;
+            if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) cus = 256;
+            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, kern, kSThreads, 40 * 1024) != hipSuccess || occ < 1) occ = 1;
+            const char *env = getenv("RELAX_GEMV_BPC");            // tuning aid: workgroups per CU
+            const int want = env ? atoi(env) : 1;
+            resident[small_k] = cus * std::max(1, std::min(occ, want));
+        }
+        int sgx = std::max(1, resident[small_k] / std::min(a.n, 8));
+        sgx = std::min(sgx, (ntiles + kSWaves - 1) / kSWaves);
+        sgx = std::max(sgx, (ntiles + kSWaves * kSMaxTiles - 1) / (kSWaves * kSMaxTiles));
+        hipLaunchKernelGGL(kern, dim3(sgx, a.n), dim3(kSThreads), lds, stream, a);
     } else {
         size_t lds = (size_t)k * 2;
         hipLaunchKernelGGL((gemv_q4_kernel<XMODE, EPI, false>), grid, block, lds, stream, a);

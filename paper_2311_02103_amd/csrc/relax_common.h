@@ -101,6 +101,7 @@ struct GemvArgs {
     const float *rope;
     int32_t h, g, d, kv_capacity;
     SeqTable seqs;
+    unsigned long long *trace;       // optional measurement aid: [workgroup][8] wall-clock stamps
 };
 
 hipError_t launch_gemv(const GemvArgs &a, int xmode, int epi, hipStream_t stream);
@@ -121,5 +122,38 @@ AttnPlan attn_plan(int32_t n, int32_t g, int32_t L_max);
 size_t attn_partial_floats(const relax_layer_dims &dm, int32_t n_max, int32_t L_max);
 hipError_t launch_attention(const uint16_t *q, const relax_kv_cache &cache, const relax_layer_dims &dm,
                             const SeqTable &st, int32_t L_max, uint16_t *out, float *partials, hipStream_t stream);
+
+// ---- persistent fused decode layer (decode_layer.hip) -----------------------------------------------------------
+struct DLMat {
+    const uint32_t *q;
+    const uint16_t *s;
+    int32_t m, k;
+};
+
+struct DecodeLayerArgs {
+    DLMat wqkv, wo, wgu, wdown;
+    const uint16_t *norm_attn, *norm_ffn;
+    const uint16_t *x;
+    uint16_t *out;
+    uint16_t *kcache, *vcache;
+    const float *rope;
+    int32_t H, h, g, d, F, cap;
+    float eps;
+    int32_t pos, slot;                 // the single row of the call: its position and cache slot
+    uint32_t *sync;                    // epoch counter, exit counter, error flag
+    // exchange buffers in the workspace: one 8-byte word {fp32 value, epoch tag} per element
+    unsigned long long *q_ll, *knew_ll, *vnew_ll, *part_ll, *attn_ll, *x1_ll, *act_ll;
+    int32_t splits, chunk;             // attention plan (pure function of L and the CU count)
+    int32_t nblocks;
+    int32_t lds_corr, lds_raw, lds_wn, lds_attn, lds_res;
+    unsigned long long *trace;         // optional: [workgroup][16] stamps of the 100 MHz wall clock at step boundaries
+};
+
+constexpr int kFusedMaxSplits = 64;
+size_t decode_layer_sync_bytes(const relax_layer_dims &dm);
+size_t decode_layer_error_offset();
+hipError_t launch_sync_clear(void *base, size_t bytes, hipStream_t stream);
+bool decode_layer_eligible(const relax_layer_dims &dm, const relax_layer_weights &w, int n, int B, int n_cus);
+hipError_t launch_decode_layer(DecodeLayerArgs &a, int n_cus, hipStream_t stream);
 
 }  // namespace relax

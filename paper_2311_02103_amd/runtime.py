@@ -46,6 +46,7 @@ class DeviceLayer:
             rx.check(rx.relax_rope_table_init(self.dims, self.rope), "relax_rope_table_init")
             self.ws_bytes = rx.relax_workspace_bytes(self.dims, n_max, kv_capacity, self.B_max)
             self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device=device)
+            rx.check(rx.relax_workspace_init(self.dims, self.ws, self.ws_bytes), "relax_workspace_init")
         shape = (kv_slots, kv_capacity, n_kv_heads, head_dim)
         self.k = torch.zeros(shape, dtype=torch.float16, device=device)
         self.v = torch.zeros(shape, dtype=torch.float16, device=device)
