@@ -236,6 +236,9 @@ relax_status relax_dequant_matmul(const uint16_t *x, const relax_qmat *w, uint16
     relax_status rc = check_qmat(w);
     if (rc != RELAX_OK) return rc;
     if (n < 1) return RELAX_ERR_SHAPE;
+    // runtime dispatch on the symbolic n (Sec. 5.1): matrix-vector kernel for a few rows, MFMA GEMM otherwise
+    if (n >= kGemmMinN && gemm_mfma_eligible(*w, x, EPI_F16))
+        return hip_status(launch_gemm_mfma(x, *w, n, EPI_F16, out, nullptr, nullptr, static_cast<hipStream_t>(stream)));
     GemvArgs a = {};
     a.x = x, a.q = w->q, a.s = w->s, a.m = w->m, a.k = w->k, a.n = n, a.out_f16 = out;
     a.trace = g_trace;
@@ -289,7 +292,7 @@ relax_status relax_attention(const uint16_t *q, const relax_kv_cache *cache, con
     rc = upload_table(st, host_table, ws, pl, st_);
     if (rc != RELAX_OK) return rc;
     float *partials = reinterpret_cast<float *>(static_cast<char *>(ws) + pl.partials);
-    return hip_status(launch_attention(q, *cache, *dims, st, L_max, out, partials, st_));
+    return hip_status(launch_attention(q, dims->n_heads * dims->head_dim, *cache, *dims, st, L_max, out, partials, st_));
 }
 
 relax_status relax_decoder_layer(const relax_layer_dims *dims, const relax_layer_weights *wt, const uint16_t *x,
@@ -353,6 +356,34 @@ relax_status relax_decoder_layer(const relax_layer_dims *dims, const relax_layer
     }
 
     float *partials = reinterpret_cast<float *>(base + pl.partials);
+
+    // Large n: MFMA GEMMs with the light steps as separate kernels (same entry point, same binary).
+    if (n >= kGemmMinN && gemm_mfma_eligible(wt->wqkv, x, EPI_F16) && gemm_mfma_eligible(wt->wo, x, EPI_RESID_F32) &&
+        gemm_mfma_eligible(wt->wgu, x, EPI_SWIGLU) && gemm_mfma_eligible(wt->wdown, x, EPI_RESID_F16)) {
+        uint16_t *xn = reinterpret_cast<uint16_t *>(base + pl.xn), *qkv = reinterpret_cast<uint16_t *>(base + pl.qkv);
+        uint16_t *attn_o = reinterpret_cast<uint16_t *>(base + pl.attn), *act_o = reinterpret_cast<uint16_t *>(base + pl.act);
+        float *x1f = reinterpret_cast<float *>(base + pl.x1);
+        timer.before(0);
+        if (launch_rmsnorm(x, wt->norm_attn, xn, n, dm.hidden, dm.rms_eps, st_) != hipSuccess) return RELAX_ERR_HIP;
+        if (launch_gemm_mfma(xn, wt->wqkv, n, EPI_F16, qkv, nullptr, nullptr, st_) != hipSuccess) return RELAX_ERR_HIP;
+        if (launch_rope_append(qkv, dm, *cache, st, st_) != hipSuccess) return RELAX_ERR_HIP;
+        timer.after(0);
+        timer.before(1);
+        if (launch_attention(qkv, qkvw, *cache, dm, st, L_max, attn_o, partials, st_) != hipSuccess) return RELAX_ERR_HIP;
+        timer.after(1);
+        timer.before(2);
+        if (launch_gemm_mfma(attn_o, wt->wo, n, EPI_RESID_F32, nullptr, x1f, x, st_) != hipSuccess) return RELAX_ERR_HIP;
+        timer.after(2);
+        timer.before(3);
+        if (launch_rmsnorm_f32(x1f, wt->norm_ffn, xn, n, dm.hidden, dm.rms_eps, st_) != hipSuccess) return RELAX_ERR_HIP;
+        if (launch_gemm_mfma(xn, wt->wgu, n, EPI_SWIGLU, act_o, nullptr, nullptr, st_) != hipSuccess) return RELAX_ERR_HIP;
+        timer.after(3);
+        timer.before(4);
+        if (launch_gemm_mfma(act_o, wt->wdown, n, EPI_RESID_F16, out, nullptr, x1f, st_) != hipSuccess) return RELAX_ERR_HIP;
+        timer.after(4);
+        return RELAX_OK;
+    }
+
     uint16_t *qbuf = reinterpret_cast<uint16_t *>(base + pl.qbuf);
     uint16_t *attn = reinterpret_cast<uint16_t *>(base + pl.attn);
     float *x1 = reinterpret_cast<float *>(base + pl.x1);
@@ -370,7 +401,7 @@ relax_status relax_decoder_layer(const relax_layer_dims *dims, const relax_layer
 
     // 2. attention over the cache
     timer.before(1);
-    if (launch_attention(qbuf, *cache, dm, st, L_max, attn, partials, st_) != hipSuccess) return RELAX_ERR_HIP;
+    if (launch_attention(qbuf, hd, *cache, dm, st, L_max, attn, partials, st_) != hipSuccess) return RELAX_ERR_HIP;
     timer.after(1);
 
     // 3. output projection + residual: x1 = x + attn Wo^T (fp32 residual stream in the workspace)

@@ -62,7 +62,7 @@ __device__ inline void merge_state(float &ma, float &la, float *acca, float mb, 
 template <int D, int REP>
 __global__ __launch_bounds__(256) void attn_split_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict__ kc,
                                                          const uint16_t *__restrict__ vc, float *__restrict__ part, SeqTable st,
-                                                         int h, int g, int cap, int chunk, int splits)
+                                                         int h, int g, int cap, int chunk, int splits, int q_stride)
 {
     constexpr int LPT = D / 8;        // lanes that share one token (each owns 8 of its d elements)
     constexpr int TPW = kWave / LPT;  // tokens per wavefront step
@@ -84,7 +84,7 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const uint16_t *__restr
     float qf[REP][8], acc[REP][8], m[REP], l[REP];
 #pragma unroll
     for (int r = 0; r < REP; ++r) {
-        unpack8(*(const uint4 *)(q + ((size_t)i * h + head0 + r) * D + e0), qf[r]);
+        unpack8(*(const uint4 *)(q + (size_t)i * q_stride + (size_t)(head0 + r) * D + e0), qf[r]);
         m[r] = -INFINITY;
         l[r] = 0.0f;
 #pragma unroll
@@ -193,38 +193,38 @@ __global__ void attn_merge_kernel(const float *__restrict__ part, uint16_t *__re
 }
 
 template <int D, int REP>
-static hipError_t launch_split(const uint16_t *q, const relax_kv_cache &cache, const relax_layer_dims &dm, const SeqTable &st,
+static hipError_t launch_split(const uint16_t *q, int q_stride, const relax_kv_cache &cache, const relax_layer_dims &dm, const SeqTable &st,
                                const AttnPlan &pl, float *partials, hipStream_t stream)
 {
     const int rep = dm.n_heads / dm.n_kv_heads;
     dim3 grid(dm.n_kv_heads * (rep / REP), pl.splits, st.n);
     hipLaunchKernelGGL((attn_split_kernel<D, REP>), grid, dim3(256), 0, stream, q, cache.k, cache.v, partials, st, dm.n_heads,
-                       dm.n_kv_heads, dm.kv_capacity, pl.chunk, pl.splits);
+                       dm.n_kv_heads, dm.kv_capacity, pl.chunk, pl.splits, q_stride);
     return hipGetLastError();
 }
 
 template <int D>
-static hipError_t launch_d(const uint16_t *q, const relax_kv_cache &cache, const relax_layer_dims &dm, const SeqTable &st,
+static hipError_t launch_d(const uint16_t *q, int q_stride, const relax_kv_cache &cache, const relax_layer_dims &dm, const SeqTable &st,
                            const AttnPlan &pl, uint16_t *out, float *partials, hipStream_t stream)
 {
     const int rep = dm.n_heads / dm.n_kv_heads;
     hipError_t e;
-    if (rep % 8 == 0) e = launch_split<D, 8>(q, cache, dm, st, pl, partials, stream);
-    else if (rep % 4 == 0) e = launch_split<D, 4>(q, cache, dm, st, pl, partials, stream);
-    else if (rep % 2 == 0) e = launch_split<D, 2>(q, cache, dm, st, pl, partials, stream);
-    else e = launch_split<D, 1>(q, cache, dm, st, pl, partials, stream);
+    if (rep % 8 == 0) e = launch_split<D, 8>(q, q_stride, cache, dm, st, pl, partials, stream);
+    else if (rep % 4 == 0) e = launch_split<D, 4>(q, q_stride, cache, dm, st, pl, partials, stream);
+    else if (rep % 2 == 0) e = launch_split<D, 2>(q, q_stride, cache, dm, st, pl, partials, stream);
+    else e = launch_split<D, 1>(q, q_stride, cache, dm, st, pl, partials, stream);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL((attn_merge_kernel<D>), dim3(st.n * dm.n_heads), dim3(D), sizeof(float) * (size_t)pl.splits, stream, partials, out, st, dm.n_heads,
                        pl.chunk, pl.splits);
     return hipGetLastError();
 }
 
-hipError_t launch_attention(const uint16_t *q, const relax_kv_cache &cache, const relax_layer_dims &dm, const SeqTable &st,
+hipError_t launch_attention(const uint16_t *q, int32_t q_stride, const relax_kv_cache &cache, const relax_layer_dims &dm, const SeqTable &st,
                             int32_t L_max, uint16_t *out, float *partials, hipStream_t stream)
 {
     const AttnPlan pl = attn_plan(st.n, dm.n_kv_heads, L_max);
-    if (dm.head_dim == 128) return launch_d<128>(q, cache, dm, st, pl, out, partials, stream);
-    if (dm.head_dim == 64) return launch_d<64>(q, cache, dm, st, pl, out, partials, stream);
+    if (dm.head_dim == 128) return launch_d<128>(q, q_stride, cache, dm, st, pl, out, partials, stream);
+    if (dm.head_dim == 64) return launch_d<64>(q, q_stride, cache, dm, st, pl, out, partials, stream);
     return hipErrorInvalidValue;
 }
 

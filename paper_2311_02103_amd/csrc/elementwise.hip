@@ -8,26 +8,40 @@
 namespace relax {
 
 // y[i,:] = x[i,:] * rsqrt(mean(x[i,:]^2) + eps) * w ; one workgroup per row, fp32 reduction.
-__global__ __launch_bounds__(256) void rmsnorm_kernel(const uint16_t *x, const uint16_t *w, uint16_t *y, int H, float eps)
+template <typename T>
+__device__ inline float load_as_float(const T *p, size_t i);
+template <>
+__device__ inline float load_as_float<uint16_t>(const uint16_t *p, size_t i) { return h2f(p[i]); }
+template <>
+__device__ inline float load_as_float<float>(const float *p, size_t i) { return p[i]; }
+
+template <typename T>
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const T *x, const uint16_t *w, uint16_t *y, int H, float eps)
 {
     __shared__ float red[4];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const size_t base = (size_t)blockIdx.x * H;
     float ss = 0.0f;
     for (int c = tid; c < H; c += 256) {
-        float v = h2f(x[base + c]);
+        float v = load_as_float<T>(x, base + c);
         ss += v * v;
     }
     ss = wave_sum(ss);
     if (lane == 0) red[wave] = ss;
     __syncthreads();
     const float inv = 1.0f / sqrtf((red[0] + red[1] + red[2] + red[3]) / (float)H + eps);
-    for (int c = tid; c < H; c += 256) y[base + c] = f2h(h2f(x[base + c]) * inv * h2f(w[c]));
+    for (int c = tid; c < H; c += 256) y[base + c] = f2h(load_as_float<T>(x, base + c) * inv * h2f(w[c]));
 }
 
 hipError_t launch_rmsnorm(const uint16_t *x, const uint16_t *w, uint16_t *y, int n, int H, float eps, hipStream_t stream)
 {
-    hipLaunchKernelGGL(rmsnorm_kernel, dim3(n), dim3(256), 0, stream, x, w, y, H, eps);
+    hipLaunchKernelGGL(rmsnorm_kernel<uint16_t>, dim3(n), dim3(256), 0, stream, x, w, y, H, eps);
+    return hipGetLastError();
+}
+
+hipError_t launch_rmsnorm_f32(const float *x, const uint16_t *w, uint16_t *y, int n, int H, float eps, hipStream_t stream)
+{
+    hipLaunchKernelGGL(rmsnorm_kernel<float>, dim3(n), dim3(256), 0, stream, x, w, y, H, eps);
     return hipGetLastError();
 }
 

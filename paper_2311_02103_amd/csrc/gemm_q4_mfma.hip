@@ -1,0 +1,364 @@
+// Fused int4-decode GEMM for large n (prefill): out[i,r] = sum_c x[i,c] * (u(r,c) - 8) * s[r, c/32].
+//
+// At large n the contraction is dense and MFMA-bound (Relax, Sec. 5.1: library-grade GEMM for batch sizes
+// other than 1; Sec. 4.2: the 4-bit decode stays fused into the matmul).  Mapping for gfx950:
+//   - v_mfma_f32_32x32x16_f16, fp32 accumulate.  A workgroup is four wavefronts (2 x 2), one per SIMD, so a
+//     wavefront may use all 512 registers of its lane: its tile is 128 weight rows x 128 x-rows = 16 MFMA tiles
+//     = 256 accumulator registers, and every 16-byte LDS fragment read feeds four MFMAs.
+//   - Both operands go through LDS in 64-wide k blocks, double buffered with ONE LDS-only barrier per block
+//     (global loads of the next block stay in flight across it).  The packed weights are decoded on the way in,
+//     once per workgroup: a thread loads 32 bytes of codes and the two group scales of one weight row, turns
+//     them into 64 fp16 values and writes them to LDS.  Decode = merge the nibbles into the mantissa of fp16
+//     1024.0, remove the offset exactly (1024+u-1032, (1024+16u)/16-72), multiply by the group scale: 13
+//     packed-fp16 VALU ops per 8 weights, which the scheduler places between the MFMAs of the current block.
+//   - Each 8-wide k packet is kept in LDS in the order [e0 e4 e1 e5 e2 e6 e3 e7] -- the nibble pairs the decode
+//     produces; the x tile is permuted the same way when it is staged.  The order of k inside an MFMA is free
+//     as long as A and B agree.  Rows are padded to 144 bytes: 16-byte reads and writes of consecutive rows hit
+//     distinct banks.
+//   - For the gate/up matrix a workgroup tile is 128 gate rows + the 128 matching up rows and a wavefront owns
+//     matching fragments of both, so SwiGLU is an element-wise epilogue on the accumulators.
+//   - n, m need not be multiples of the tile: rows are clamped on load and masked on store (one binary for
+//     every n: 17, 511, 2048 ...).  k must be a multiple of 128 (else the matvec path serves the call).
+//     Narrower tiles (64 weight rows per wavefront; 32 or 64 x-rows per wavefront) are picked by the launcher
+//     when the wide one would leave CUs idle.
+#include "relax_common.h"
+
+namespace relax {
+
+namespace {
+
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef float float16_t __attribute__((ext_vector_type(16)));
+
+constexpr int BK = 64;                  // k per main-loop step
+constexpr int kPitch = BK + 8;          // LDS row pitch in halfs (144 bytes)
+constexpr int kThreadsG = 256;
+
+__device__ __forceinline__ uint32_t pk_add(uint32_t a, uint32_t b)
+{
+    return __builtin_bit_cast(uint32_t, __builtin_bit_cast(half2_t, a) + __builtin_bit_cast(half2_t, b));
+}
+__device__ __forceinline__ uint32_t pk_mul(uint32_t a, uint32_t b)
+{
+    return __builtin_bit_cast(uint32_t, __builtin_bit_cast(half2_t, a) * __builtin_bit_cast(half2_t, b));
+}
+__device__ __forceinline__ uint32_t pk_fma(uint32_t a, uint32_t b, uint32_t c)
+{
+    half2_t r = __builtin_elementwise_fma(__builtin_bit_cast(half2_t, a), __builtin_bit_cast(half2_t, b), __builtin_bit_cast(half2_t, c));
+    return __builtin_bit_cast(uint32_t, r);
+}
+
+// (w & mask) | bits as one VALU op (mask from a scalar register, bits from a vector register: the encoding
+// takes no literal and only one scalar source)
+__device__ __forceinline__ uint32_t and_or(uint32_t w, uint32_t mask, uint32_t bits)
+{
+    uint32_t r;
+    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(w), "s"(mask), "v"(bits));
+    return r;
+}
+
+// one packed word (8 codes, elements 0..7) and its group scale (fp16 pair s,s) -> 8 fp16 weights in the packet
+// order [e0 e4 e1 e5 e2 e6 e3 e7]; every step is exact except the final multiply by the scale
+__device__ __forceinline__ half8_t decode_word(uint32_t w, uint32_t s2)
+{
+    const uint32_t w8 = w >> 8;
+    const uint32_t a0 = and_or(w, 0x000F000Fu, 0x64006400u);   // 1024 + u   : e0, e4
+    const uint32_t a1 = and_or(w, 0x00F000F0u, 0x64006400u);   // 1024 + 16u : e1, e5
+    const uint32_t a2 = and_or(w8, 0x000F000Fu, 0x64006400u);  // e2, e6
+    const uint32_t a3 = and_or(w8, 0x00F000F0u, 0x64006400u);  // e3, e7
+    const uint32_t kNeg1032 = 0xE408E408u, kSixteenth = 0x2C002C00u, kNeg72 = 0xD480D480u;
+    uint4 r;
+    r.x = pk_mul(pk_add(a0, kNeg1032), s2);
+    r.y = pk_mul(pk_fma(a1, kSixteenth, kNeg72), s2);
+    r.z = pk_mul(pk_add(a2, kNeg1032), s2);
+    r.w = pk_mul(pk_fma(a3, kSixteenth, kNeg72), s2);
+    return __builtin_bit_cast(half8_t, r);
+}
+
+struct GemmArgs {
+    const uint16_t *x;       // [n,k] fp16
+    const uint32_t *q;       // [m,k/8]
+    const uint16_t *s;       // [m,k/32]
+    int32_t n, m, k;
+    int32_t epi;
+    int32_t tiles_m;         // weight-row tiles of the launch (the grid is one-dimensional: tiles_m * x-row tiles)
+    uint16_t *out_f16;       // EPI_F16: [n,m]; EPI_RESID_F16: [n,m]; EPI_SWIGLU: [n,m/2]
+    float *out_f32;          // EPI_RESID_F32: [n,m]
+    const void *resid;       // EPI_RESID_F32: fp16 [n,m]; EPI_RESID_F16: fp32 [n,m]
+};
+
+// One-dimensional grid of tiles_m * (x-row tiles) workgroups.  Wavefront w owns MF fragments of 32 weight rows (w & 1 picks which)
+// and NF fragments of 32 x-rows (w >> 1 picks which) of the workgroup tile of 64 MF weight rows x 64 NF x-rows.
+// LDS row r of the weight tile is weight row m0 + r, except for EPI_SWIGLU: rows [0, 32 MF) are gate rows
+// g0 + r and rows [32 MF, 64 MF) the up rows F + g0 + (r - 32 MF).
+template <int EPI, int MF, int NF>
+__global__ __launch_bounds__(kThreadsG) void gemm_q4_mfma_kernel(GemmArgs a)
+{
+    constexpr int BM = 64 * MF, BN = 64 * NF;
+    constexpr int W = 2 * MF;                             // packed words a thread decodes per k block (8 or 4)
+    constexpr int TPR = 8 / W;                            // threads per weight row
+    constexpr int XP = 2 * NF;                            // 16-byte x packets a thread stages per k block
+    constexpr int kABuf = BM * kPitch, kBBuf = BN * kPitch;
+    extern __shared__ __align__(16) uint16_t lds[];       // A[2][BM][kPitch], B[2][BN][kPitch]
+    uint16_t *const As = lds, *const Bs = lds + 2 * kABuf;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int row32 = lane & 31, hf = lane >> 5;
+    const int wm = wave & 1, wn = wave >> 1;
+    // Workgroups are handed to the 8 XCDs round-robin by linear id, and each XCD has its own L2.  Renumber them so
+    // that an XCD owns a contiguous run of tiles (consecutive weight-row tiles of one x-row tile): the x tile a
+    // workgroup streams is then fetched into one L2 instead of eight.
+    const int nb = gridDim.x, xcd = blockIdx.x & 7, idx = blockIdx.x >> 3;
+    const int tile = xcd * (nb >> 3) + min(xcd, nb & 7) + idx;
+    const int tile_m = tile % a.tiles_m, tile_n = tile / a.tiles_m;
+    const int n0 = tile_n * BN;
+    const int kw = a.k >> 3, G = a.k >> 5;
+    const int F = a.m >> 1;
+
+    // ---- staging roles ----
+    const int arow = tid / TPR, aword0 = (tid % TPR) * W;
+    int grow;
+    if (EPI == EPI_SWIGLU) {
+        const int g0 = tile_m * (BM / 2);
+        grow = arow < BM / 2 ? min(g0 + arow, F - 1) : F + min(g0 + arow - BM / 2, F - 1);
+    } else {
+        grow = min(tile_m * BM + arow, a.m - 1);
+    }
+    const uint32_t *qsrc = a.q + (size_t)grow * kw + aword0;
+    const uint16_t *ssrc = a.s + (size_t)grow * G + (aword0 >> 2);
+    const uint16_t *xsrc[XP];
+#pragma unroll
+    for (int p = 0; p < XP; ++p) {
+        const int pk = tid + p * kThreadsG;
+        xsrc[p] = a.x + (size_t)min(n0 + (pk >> 3), a.n - 1) * a.k + (pk & 7) * 8;
+    }
+
+    // Staged registers of one k block: packed codes + scales of this thread's weight row part, and its x packets.
+    struct Stage {
+        uint4 wq[W / 4];
+        uint32_t wsc;
+        uint4 xr[XP];
+    };
+    const int nkb = a.k / BK;
+    auto stage_load = [&](Stage &S, int kb) {             // kb is clamped: the tail re-reads the last block (never consumed)
+        kb = min(kb, nkb - 1);
+#pragma unroll
+        for (int i = 0; i < W / 4; ++i) S.wq[i] = *(const uint4 *)(qsrc + kb * (BK / 8) + i * 4);
+        if (W == 8) S.wsc = *(const uint32_t *)(ssrc + kb * (BK / 32));
+        else S.wsc = ssrc[kb * (BK / 32)];
+#pragma unroll
+        for (int p = 0; p < XP; ++p) S.xr[p] = *(const uint4 *)(xsrc[p] + kb * BK);
+    };
+    // quarter `part` (0..3) of the decode + LDS write of a staged block
+    auto stage_store = [&](const Stage &S, int buf, int part) {
+        uint16_t *ad = As + buf * kABuf + arow * kPitch + aword0 * 8;
+#pragma unroll
+        for (int i = 0; i < W; ++i) {
+            if (i * 4 / W != part) continue;
+            const uint4 &wv = S.wq[i >> 2];
+            const uint32_t word = (i & 3) == 0 ? wv.x : (i & 3) == 1 ? wv.y : (i & 3) == 2 ? wv.z : wv.w;
+            const uint32_t sc = (W == 8 && i >= 4) ? (S.wsc >> 16) : (S.wsc & 0xFFFFu);
+            *(half8_t *)(ad + i * 8) = decode_word(word, sc | (sc << 16));
+        }
+        uint16_t *bd = Bs + buf * kBBuf;
+#pragma unroll
+        for (int p = 0; p < XP; ++p) {
+            if (p * 4 / XP != part) continue;
+            const int pk = tid + p * kThreadsG;
+            // [x0 x1 | x2 x3 | x4 x5 | x6 x7] -> [x0 x4 | x1 x5 | x2 x6 | x3 x7]
+            uint4 o;
+            o.x = __builtin_amdgcn_perm(S.xr[p].z, S.xr[p].x, 0x05040100u);
+            o.y = __builtin_amdgcn_perm(S.xr[p].z, S.xr[p].x, 0x07060302u);
+            o.z = __builtin_amdgcn_perm(S.xr[p].w, S.xr[p].y, 0x05040100u);
+            o.w = __builtin_amdgcn_perm(S.xr[p].w, S.xr[p].y, 0x07060302u);
+            *(uint4 *)(bd + (pk >> 3) * kPitch + (pk & 7) * 8) = o;
+        }
+    };
+    // LDS-only workgroup barrier: the global loads of later k blocks stay in flight across it
+    auto lds_barrier = [&]() {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+    };
+
+    // ---- MFMA roles ----
+    int afrag_off[MF];                                    // offset of this lane's fragment rows inside a weight tile
+#pragma unroll
+    for (int f = 0; f < MF; ++f) {
+        int rb;
+        if (EPI == EPI_SWIGLU) rb = (f / (MF / 2)) * (BM / 2) + (wm * (MF / 2) + f % (MF / 2)) * 32;
+        else rb = (wm * MF + f) * 32;
+        afrag_off[f] = (rb + row32) * kPitch + hf * 8;
+    }
+    const int bfrag_off = (wn * NF * 32 + row32) * kPitch + hf * 8;
+
+    float16_t acc[MF][NF];
+#pragma unroll
+    for (int f = 0; f < MF; ++f)
+#pragma unroll
+        for (int j = 0; j < NF; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[f][j][v] = 0.0f;
+
+    // One k block: MFMAs on LDS buffer `buf` while the staged block S is decoded into the other buffer.  The
+    // fragments of k step ks+1 are requested before the MFMAs of step ks are issued, and a quarter of the decode
+    // is placed next to each step's MFMAs; the scheduling fences keep the compiler from undoing either.
+    auto block = [&](int buf, const Stage &S) {
+        const uint16_t *ab = As + buf * kABuf, *bb = Bs + buf * kBBuf + bfrag_off;
+        half8_t af[2][MF], bf[2][NF];
+#pragma unroll
+        for (int f = 0; f < MF; ++f) af[0][f] = *(const half8_t *)(ab + afrag_off[f]);
+#pragma unroll
+        for (int j = 0; j < NF; ++j) bf[0][j] = *(const half8_t *)(bb + j * 32 * kPitch);
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+            const int cur = ks & 1, nxt = cur ^ 1;
+            if (ks + 1 < BK / 16) {
+#pragma unroll
+                for (int f = 0; f < MF; ++f) af[nxt][f] = *(const half8_t *)(ab + afrag_off[f] + (ks + 1) * 16);
+#pragma unroll
+                for (int j = 0; j < NF; ++j) bf[nxt][j] = *(const half8_t *)(bb + j * 32 * kPitch + (ks + 1) * 16);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int j = 0; j < NF; ++j)
+#pragma unroll
+                for (int f = 0; f < MF; ++f)
+                    acc[f][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[cur][f], bf[cur][j], acc[f][j], 0, 0, 0);
+            stage_store(S, buf ^ 1, ks);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    // Software pipeline over k blocks, two register stages deep: the global loads of block kb+2 are issued at the
+    // top of block kb and consumed (decoded into LDS) during block kb+1, a full block of MFMAs later.
+    Stage S0, S1;
+    stage_load(S0, 0);
+#pragma unroll
+    for (int part = 0; part < 4; ++part) stage_store(S0, 0, part);
+    lds_barrier();
+    stage_load(S1, 1);
+    for (int kb = 0; kb < nkb; kb += 2) {                 // nkb is even (k % 128 == 0)
+        stage_load(S0, kb + 2);
+        block(0, S1);                                     // MFMAs on buffer 0 (block kb), block kb+1 -> buffer 1
+        lds_barrier();
+        stage_load(S1, kb + 3);
+        block(1, S0);                                     // MFMAs on buffer 1 (block kb+1), block kb+2 -> buffer 0
+        lds_barrier();
+    }
+
+    // ---- epilogue.  acc[f][j][v]: tile row of fragment f + 8 (v/4) + 4 (lane/32) + v%4, x row n0 + 32 (NF wn + j) + lane%32 ----
+#pragma unroll
+    for (int j = 0; j < NF; ++j) {
+        const int xrow = n0 + (wn * NF + j) * 32 + row32;
+        if (xrow >= a.n) continue;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const int off = b * 8 + hf * 4;
+            if (EPI == EPI_SWIGLU) {
+#pragma unroll
+                for (int f = 0; f < MF / 2; ++f) {
+                    const int g = tile_m * (BM / 2) + (wm * (MF / 2) + f) * 32 + off;
+                    if (g < F) {                                 // F % 4 == 0 is checked by the launcher
+                        uint16_t o[4];
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            const float gte = acc[f][j][b * 4 + r], up = acc[f + MF / 2][j][b * 4 + r];
+                            o[r] = f2h(gte / (1.0f + __expf(-gte)) * up);
+                        }
+                        *(uint2 *)(a.out_f16 + (size_t)xrow * F + g) = make_uint2(o[0] | ((uint32_t)o[1] << 16), o[2] | ((uint32_t)o[3] << 16));
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int f = 0; f < MF; ++f) {
+                    const int r0 = tile_m * BM + (wm * MF + f) * 32 + off;
+                    if (r0 < a.m) {                              // m % 4 == 0 is checked by the launcher
+                        const size_t at = (size_t)xrow * a.m + r0;
+                        float v[4];
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) v[r] = acc[f][j][b * 4 + r];
+                        if (EPI == EPI_RESID_F32) {
+                            const uint2 xx = *(const uint2 *)((const uint16_t *)a.resid + at);
+                            float4 o;
+                            o.x = h2f((uint16_t)(xx.x & 0xFFFFu)) + v[0], o.y = h2f((uint16_t)(xx.x >> 16)) + v[1];
+                            o.z = h2f((uint16_t)(xx.y & 0xFFFFu)) + v[2], o.w = h2f((uint16_t)(xx.y >> 16)) + v[3];
+                            *(float4 *)(a.out_f32 + at) = o;
+                        } else {
+                            if (EPI == EPI_RESID_F16) {
+                                const float4 rr = *(const float4 *)((const float *)a.resid + at);
+                                v[0] += rr.x, v[1] += rr.y, v[2] += rr.z, v[3] += rr.w;
+                            }
+                            *(uint2 *)(a.out_f16 + at) =
+                                make_uint2(f2h(v[0]) | ((uint32_t)f2h(v[1]) << 16), f2h(v[2]) | ((uint32_t)f2h(v[3]) << 16));
+                        }
+                    }
+                }
+            }
+        }
+    }
+}
+
+template <int MF, int NF>
+hipError_t launch_tile(const GemmArgs &a_in, hipStream_t stream)
+{
+    constexpr int BM = 64 * MF, BN = 64 * NF;
+    const int rows = a_in.epi == EPI_SWIGLU ? a_in.m / 2 : a_in.m, per_block = a_in.epi == EPI_SWIGLU ? BM / 2 : BM;
+    GemmArgs a = a_in;
+    a.tiles_m = (rows + per_block - 1) / per_block;
+    dim3 grid(a.tiles_m * ((a.n + BN - 1) / BN));
+    const size_t lds = 2 * (size_t)(BM + BN) * kPitch * sizeof(uint16_t);    // up to 147456 bytes: one workgroup per CU
+    static bool attr_done = false;
+    if (!attr_done) {
+        const void *ks[4] = {(const void *)gemm_q4_mfma_kernel<EPI_F16, MF, NF>, (const void *)gemm_q4_mfma_kernel<EPI_RESID_F32, MF, NF>,
+                             (const void *)gemm_q4_mfma_kernel<EPI_RESID_F16, MF, NF>, (const void *)gemm_q4_mfma_kernel<EPI_SWIGLU, MF, NF>};
+        for (const void *kf : ks)
+            if (hipFuncSetAttribute(kf, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) return hipErrorInvalidValue;
+        attr_done = true;
+    }
+    switch (a.epi) {
+    case EPI_F16: hipLaunchKernelGGL((gemm_q4_mfma_kernel<EPI_F16, MF, NF>), grid, dim3(kThreadsG), lds, stream, a); break;
+    case EPI_RESID_F32: hipLaunchKernelGGL((gemm_q4_mfma_kernel<EPI_RESID_F32, MF, NF>), grid, dim3(kThreadsG), lds, stream, a); break;
+    case EPI_RESID_F16: hipLaunchKernelGGL((gemm_q4_mfma_kernel<EPI_RESID_F16, MF, NF>), grid, dim3(kThreadsG), lds, stream, a); break;
+    case EPI_SWIGLU: hipLaunchKernelGGL((gemm_q4_mfma_kernel<EPI_SWIGLU, MF, NF>), grid, dim3(kThreadsG), lds, stream, a); break;
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+}  // namespace
+
+// Whether the MFMA path can serve this matrix (k in whole 128-blocks, 16-byte aligned rows, 4-row store granules).
+bool gemm_mfma_eligible(const relax_qmat &w, const void *x, int epi)
+{
+    if (w.k % (2 * BK) != 0) return false;
+    if ((reinterpret_cast<uintptr_t>(w.q) & 15) != 0 || (reinterpret_cast<uintptr_t>(w.s) & 3) != 0) return false;
+    if ((reinterpret_cast<uintptr_t>(x) & 15) != 0) return false;
+    if (epi == EPI_SWIGLU) return w.m % 8 == 0;
+    return w.m % 4 == 0;
+}
+
+// Tile choice for n > 128: 256 x 256 or 128 x 256 (weight rows x x-rows), whichever wastes less of the last
+// round of workgroups over the 256 CUs (one workgroup per CU); ties go to the wider tile.  Small n takes
+// narrower x tiles.
+hipError_t launch_gemm_mfma(const uint16_t *x, const relax_qmat &w, int n, int epi, uint16_t *out_f16, float *out_f32, const void *resid,
+                            hipStream_t stream)
+{
+    GemmArgs a;
+    a.x = x, a.q = w.q, a.s = w.s, a.n = n, a.m = w.m, a.k = w.k, a.epi = epi;
+    a.out_f16 = out_f16, a.out_f32 = out_f32, a.resid = resid;
+    const long rows = epi == EPI_SWIGLU ? w.m / 2 : w.m;
+    const long rdiv = epi == EPI_SWIGLU ? 2 : 1;
+    auto blocks = [&](int mf, int nf) { return ((rows + 64 * mf / rdiv - 1) / (64 * mf / rdiv)) * (long)((n + 64 * nf - 1) / (64 * nf)); };
+    const long kCUs = 256;
+    if (n > 128) {
+        auto fill = [&](long b) { return (double)b / (double)(((b + kCUs - 1) / kCUs) * kCUs); };
+        if (fill(blocks(4, 4)) >= fill(blocks(2, 4))) return launch_tile<4, 4>(a, stream);
+        return launch_tile<2, 4>(a, stream);
+    }
+    if (n > 64) return launch_tile<2, 2>(a, stream);
+    return launch_tile<2, 1>(a, stream);
+}
+
+}  // namespace relax

@@ -107,6 +107,13 @@ struct GemvArgs {
 hipError_t launch_gemv(const GemvArgs &a, int xmode, int epi, hipStream_t stream);
 
 hipError_t launch_rmsnorm(const uint16_t *x, const uint16_t *w, uint16_t *y, int n, int H, float eps, hipStream_t stream);
+hipError_t launch_rmsnorm_f32(const float *x, const uint16_t *w, uint16_t *y, int n, int H, float eps, hipStream_t stream);
+
+// MFMA GEMM for large n (gemm_q4_mfma.hip)
+constexpr int kGemmMinN = 16;        // rows from which the MFMA GEMM replaces one matvec pass per row
+bool gemm_mfma_eligible(const relax_qmat &w, const void *x, int epi);
+hipError_t launch_gemm_mfma(const uint16_t *x, const relax_qmat &w, int n, int epi, uint16_t *out_f16, float *out_f32, const void *resid,
+                            hipStream_t stream);
 hipError_t launch_rope_append(uint16_t *qkv, const relax_layer_dims &dm, const relax_kv_cache &cache,
                               const SeqTable &st, hipStream_t stream);
 hipError_t launch_rope_table(const relax_layer_dims &dm, float *table, hipStream_t stream);
@@ -120,7 +127,7 @@ struct AttnPlan {
 };
 AttnPlan attn_plan(int32_t n, int32_t g, int32_t L_max);
 size_t attn_partial_floats(const relax_layer_dims &dm, int32_t n_max, int32_t L_max);
-hipError_t launch_attention(const uint16_t *q, const relax_kv_cache &cache, const relax_layer_dims &dm,
+hipError_t launch_attention(const uint16_t *q, int32_t q_stride, const relax_kv_cache &cache, const relax_layer_dims &dm,
                             const SeqTable &st, int32_t L_max, uint16_t *out, float *partials, hipStream_t stream);
 
 // ---- persistent fused decode layer (decode_layer.hip) -----------------------------------------------------------
