@@ -90,6 +90,8 @@ relax_status build_seqs(const relax_seqs *sq, const relax_layer_dims &dm, int32_
     st.B = sq->B;
     st.n = n;
     st.dev = nullptr;
+    st.q_max = 0;
+    for (int b = 0; b < sq->B; ++b) st.q_max = sq->q_lens[b] > st.q_max ? sq->q_lens[b] : st.q_max;
     const bool inl = sq->B <= kInlineSeqs;
     if (!inl) host_table.assign(4 * (size_t)sq->B, 0);
     int32_t start = 0;

@@ -222,6 +222,7 @@ static hipError_t launch_d(const uint16_t *q, int q_stride, const relax_kv_cache
 hipError_t launch_attention(const uint16_t *q, int32_t q_stride, const relax_kv_cache &cache, const relax_layer_dims &dm, const SeqTable &st,
                             int32_t L_max, uint16_t *out, float *partials, hipStream_t stream)
 {
+    if (st.q_max >= kPrefillMinQ && attn_prefill_supported(dm)) return launch_attention_prefill(q, q_stride, cache, dm, st, out, stream);
     const AttnPlan pl = attn_plan(st.n, dm.n_kv_heads, L_max);
     if (dm.head_dim == 128) return launch_d<128>(q, q_stride, cache, dm, st, pl, out, partials, stream);
     if (dm.head_dim == 64) return launch_d<64>(q, q_stride, cache, dm, st, pl, out, partials, stream);

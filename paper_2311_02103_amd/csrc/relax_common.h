@@ -22,6 +22,7 @@ constexpr int kInlineSeqs = 16;      // ragged descriptors up to this many seque
 struct SeqTable {
     int32_t B;
     int32_t n;
+    int32_t q_max;                   // longest q_len of the call (host-side dispatch: decode vs prefill attention)
     const int32_t *dev;              // [4][B]: q_start, q_len, kv_len, slot; nullptr -> inline arrays
     int32_t q_start[kInlineSeqs];
     int32_t q_len[kInlineSeqs];
@@ -129,6 +130,12 @@ AttnPlan attn_plan(int32_t n, int32_t g, int32_t L_max);
 size_t attn_partial_floats(const relax_layer_dims &dm, int32_t n_max, int32_t L_max);
 hipError_t launch_attention(const uint16_t *q, int32_t q_stride, const relax_kv_cache &cache, const relax_layer_dims &dm,
                             const SeqTable &st, int32_t L_max, uint16_t *out, float *partials, hipStream_t stream);
+
+// Causal MFMA attention for calls with many rows per sequence (attn_prefill.hip)
+constexpr int kPrefillMinQ = 16;     // longest q_len from which launch_attention takes the MFMA kernel
+bool attn_prefill_supported(const relax_layer_dims &dm);
+hipError_t launch_attention_prefill(const uint16_t *q, int32_t q_stride, const relax_kv_cache &cache, const relax_layer_dims &dm,
+                                    const SeqTable &st, uint16_t *out, hipStream_t stream);
 
 // ---- persistent fused decode layer (decode_layer.hip) -----------------------------------------------------------
 struct DLMat {

@@ -200,6 +200,51 @@ def test_attention_ragged_prefill_rows_and_many_sequences(rx):
     assert_close(got, ref, "21-sequence decode", atol=2e-3, rtol=1e-2)
 
 
+@pytest.mark.parametrize("h,g,d,q_lens,kv_lens", [
+    (4, 4, 128, [16], [16]),                      # smallest call that takes the MFMA kernel
+    (4, 2, 128, [129], [129]),                    # one full q tile + one row; crosses a 64-token KV tile
+    (2, 2, 64, [300], [300]),                     # head dim 64, several q tiles and KV tiles, ragged tails
+    (4, 1, 128, [70], [333]),                     # chunked prefill: 263 cached tokens before the call's rows
+    (8, 4, 64, [40, 1, 200, 17], [40, 90, 200, 64]),   # mixed batch: a decode row among prefills, different pasts
+])
+def test_prefill_attention_mfma(rx, h, g, d, q_lens, kv_lens):
+    B = len(q_lens)
+    got, ref = run_attention(rx, h, g, d, max(kv_lens) + 5, B, q_lens, kv_lens, list(range(B))[::-1], seed=40 + h + sum(q_lens))
+    assert_close(got, ref, "prefill attention h=%d g=%d d=%d q=%s" % (h, g, d, q_lens), atol=2e-3, rtol=1e-2)
+
+
+def test_prefill_attention_many_sequences_device_table(rx):
+    B = 19                                        # more sequences than ride in kernel arguments
+    q = [int(v) for v in wl.uniform_lengths(41, B, 1, 70)]
+    q[3] = 33
+    past = [int(v) for v in wl.uniform_lengths(42, B, 1, 50)]
+    kv = [a + b - 1 for a, b in zip(q, past)]
+    got, ref = run_attention(rx, 4, 2, 64, 128, B, q, kv, list(range(B)), seed=43)
+    assert_close(got, ref, "19-sequence prefill", atol=2e-3, rtol=1e-2)
+
+
+def test_prefill_attention_7b_2048_sampled_rows(rx):
+    """Full cfg-3 shape (h=g=32, d=128, n=L=2048): the oracle computes sampled query rows one by one."""
+    h = g = 32
+    d, n, cap = 128, 2048, 2048
+    dims = rx.make_dims(h * d, h, g, d, 64, cap, 1)
+    od = oracle.Dims(h * d, h, g, d, 64, kv_capacity=cap)
+    kb, vb = (wl.normal_f16_bits(50, 10 + j, (1, cap, g, d)) for j in (0, 1))
+    qb = wl.normal_f16_bits(50, 12, (n, h, d))
+    ws_bytes = rx.relax_workspace_bytes(dims, n, n, 1)
+    ws = torch.full((ws_bytes,), 0xFF, dtype=torch.uint8, device="cuda")
+    out = torch.empty((n, h, d), dtype=torch.float16, device="cuda")
+    rx.check(rx.relax_attention(dev(qb), rx.KVCache(dev(kb), dev(vb), None), rx.Seqs([n], [n], [0]), dims, out, n, ws, ws_bytes))
+    torch.cuda.synchronize()
+    got = host_bits(out).view(np.float16).astype(np.float32)
+    assert np.isfinite(got).all()
+    Kf, Vf = f32_cache(kb), f32_cache(vb)
+    for row in (0, 1, 63, 64, 127, 128, 1000, 1983, 2047):
+        # the same row as a decode call on the same cache: q_len 1, kv_len row+1
+        ref = oracle.attention(wl.f16_bits_to_f32(qb[row:row + 1]), Kf, Vf, od, oracle.Seqs([1], [row + 1], [0]))
+        assert_close(got[row:row + 1], ref, "prefill attention row %d" % row, atol=2e-3, rtol=1e-2)
+
+
 # ------------------------------------------------------------------------- whole layer
 def run_schedule(rx, shape, seed, cap, calls, slots=1, prefill_bits=None, n_max=None):
     """calls: list of (q_lens, kv_lens, slot_ids).  Returns per-call (gpu fp32, oracle fp32) and both caches."""
