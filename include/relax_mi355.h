@@ -182,6 +182,42 @@ relax_status relax_decoder_layer(const relax_layer_dims *dims, const relax_layer
                                  const uint16_t *x, const relax_kv_cache *cache, const relax_seqs *seqs,
                                  uint16_t *out, int32_t n, void *ws, size_t ws_bytes, relax_stream stream);
 
+/* A stack of decoder layers with its embedding and output head (the end-to-end LLM of
+ * Sec. 5.1: the layer above repeated, between a token-embedding gather and a final
+ * RMSNorm + unquantised fp16 vocabulary projection).  `layers` is a HOST array of
+ * n_layers weight structs (their pointers are device pointers); embedding and lm_head
+ * are device fp16 [vocab, hidden], norm_final device fp16 [hidden].  n_layers may be 0. */
+typedef struct {
+    relax_layer_dims dims;
+    int32_t n_layers, vocab;
+    const relax_layer_weights *layers;
+    const uint16_t *embedding;
+    const uint16_t *norm_final;
+    const uint16_t *lm_head;
+} relax_model;
+
+/* Bytes of workspace for relax_model_step over every call with n <= n_max rows,
+ * B <= B_max sequences, kv_lens <= L_max: the layer workspace (shared by all layers,
+ * which run one after another), two [n_max, hidden] fp16 activation buffers, the
+ * normalised last rows and [B_max, vocab] fp16 logits.  The front of it is the same
+ * sync area as in relax_workspace_bytes: call relax_workspace_init on it once.
+ * Returns 0 for invalid arguments.                                                      */
+size_t relax_model_workspace_bytes(const relax_model *model, int32_t n_max, int32_t L_max, int32_t B_max);
+
+/* One step of the whole model on n rows (prefill, decode or a ragged mix, as described
+ * by seqs):  x = E[ids];  x = layer_l(x) for l = 0..n_layers-1, layer l using caches[l]
+ * (a HOST array of n_layers cache structs with the dims' capacity and slots);
+ * y_b = RMSNorm(x[last row of sequence b]; norm_final);  logits[b,:] = y_b lm_head^T
+ * (fp32 accumulation, stored fp16);  next_ids[b] = lowest index among the maxima of
+ * logits[b,:] as stored (greedy decoding, the paper's generation protocol).
+ * ids: device int32 [n].  logits: device fp16 [B, vocab] or NULL (then they stay in the
+ * workspace).  next_ids: device int32 [B] or NULL.  An id outside [0, vocab) is read as
+ * id 0 and raises bit 1 of the flag relax_workspace_error reports.
+ * Errors as relax_decoder_layer; hidden must be a multiple of 8.                        */
+relax_status relax_model_step(const relax_model *model, const int32_t *ids, const relax_kv_cache *caches,
+                              const relax_seqs *seqs, uint16_t *logits, int32_t *next_ids, int32_t n,
+                              void *ws, size_t ws_bytes, relax_stream stream);
+
 /* Test exports for the bit-exactness requirement on decoding and indexing: the device
  * decode of (word, nibble, scale group) written out densely, one element per thread.
  * relax_unpack_int4: out int8 [m,k] in -8..7.  relax_dequantize: out fp32 [m,k].        */

@@ -285,3 +285,22 @@ def decoder_layer(dims: Dims, w: LayerWeights, x, kcache: np.ndarray, vcache: np
     if rc != 0:
         raise ValueError("oracle_decoder_layer: inconsistent descriptor")
     return (out, tapd) if taps else out
+
+
+def model_step(dims: Dims, layers: Sequence[LayerWeights], embedding_bits: np.ndarray, norm_final_bits: np.ndarray,
+               lm_head_bits: np.ndarray, ids: np.ndarray, kcaches: Sequence[np.ndarray], vcaches: Sequence[np.ndarray],
+               seqs: Seqs):
+    """One step of the layer stack (Relax, Sec. 5.1, end-to-end LLM; Llama-style wrapper):
+    x = E[ids] (fp16 table, exact in fp32); x = layer_l(x) with the residual stream kept in fp32;
+    y_b = RMSNorm(x[last row of sequence b]; w_final); logits[b] = y_b . W_lm^T (fp16 weights, fp32 sums);
+    greedy id = lowest index among the maxima.  Caches (one fp32 pair per layer) are updated in place.
+
+    Returns (logits fp32 [B, V], ids int32 [B])."""
+    emb = np.ascontiguousarray(embedding_bits).view(np.float16)
+    x = emb[np.asarray(ids, dtype=np.int64)].astype(np.float32)
+    for l, w in enumerate(layers):
+        x = decoder_layer(dims, w, x, kcaches[l], vcaches[l], seqs)
+    last = np.cumsum(np.asarray(seqs.q, dtype=np.int64)) - 1
+    y = rmsnorm(np.ascontiguousarray(x[last]), norm_final_bits, dims.rms_eps)
+    logits = half_matmul(y, lm_head_bits)
+    return logits, argmax(logits)

@@ -56,6 +56,11 @@ class SeqsC(C.Structure):
                 ("slots", C.POINTER(C.c_int32))]
 
 
+class ModelC(C.Structure):
+    _fields_ = [("dims", LayerDims), ("n_layers", C.c_int32), ("vocab", C.c_int32), ("layers", C.POINTER(LayerWeightsC)),
+                ("embedding", C.c_void_p), ("norm_final", C.c_void_p), ("lm_head", C.c_void_p)]
+
+
 _lib = None
 
 _SIGNATURES = {
@@ -76,6 +81,9 @@ _SIGNATURES = {
                                     C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]),
     "relax_decoder_layer": (C.c_int32, [C.POINTER(LayerDims), C.POINTER(LayerWeightsC), C.c_void_p, C.POINTER(KVCacheC),
                                         C.POINTER(SeqsC), C.c_void_p, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "relax_model_workspace_bytes": (C.c_size_t, [C.POINTER(ModelC), C.c_int32, C.c_int32, C.c_int32]),
+    "relax_model_step": (C.c_int32, [C.POINTER(ModelC), C.c_void_p, C.POINTER(KVCacheC), C.POINTER(SeqsC), C.c_void_p,
+                                     C.c_void_p, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]),
     "relax_unpack_int4": (C.c_int32, [C.POINTER(QMatC), C.c_void_p, C.c_void_p]),
     "relax_dequantize": (C.c_int32, [C.POINTER(QMatC), C.c_void_p, C.c_void_p]),
 }
@@ -224,6 +232,35 @@ def relax_decoder_layer(dims: Optional[LayerDims], weights: Optional[LayerWeight
     sc = None if seqs is None else seqs.c()
     return lib().relax_decoder_layer(_ref(dims), _ref(wc), _ptr(x), _ref(cc), _ref(sc), _ptr(out), n, _ptr(ws), ws_bytes,
                                      _stream(stream))
+
+
+class Model:
+    """Host-side image of relax_model: keeps the C arrays (layer weight structs) alive."""
+
+    def __init__(self, dims: LayerDims, layers: Sequence[LayerWeights], vocab: int, embedding: Ptr, norm_final: Ptr, lm_head: Ptr):
+        self.dims, self.vocab, self.n_layers = dims, vocab, len(layers)
+        self._layers = (LayerWeightsC * max(1, len(layers)))(*[lw.c() for lw in layers])
+        self._keep = (layers, embedding, norm_final, lm_head)
+        self._c = ModelC(dims, len(layers), vocab, C.cast(self._layers, C.POINTER(LayerWeightsC)) if layers else None,
+                         _ptr(embedding), _ptr(norm_final), _ptr(lm_head))
+
+    def c(self) -> ModelC:
+        return self._c
+
+
+def relax_model_workspace_bytes(model: Optional[Model], n_max: int, L_max: int, B_max: int) -> int:
+    return int(lib().relax_model_workspace_bytes(None if model is None else C.byref(model.c()), n_max, L_max, B_max))
+
+
+def relax_model_step(model: Optional[Model], ids: Ptr, caches: Optional[Sequence[KVCache]], seqs: Optional[Seqs], logits: Ptr,
+                     next_ids: Ptr, n: int, ws: Ptr, ws_bytes: int, stream=None) -> int:
+    sc = None if seqs is None else seqs.c()
+    carr = None
+    if caches is not None:
+        carr = (KVCacheC * max(1, len(caches)))(*[c.c() for c in caches])
+    return lib().relax_model_step(None if model is None else C.byref(model.c()), _ptr(ids),
+                                  None if carr is None else C.cast(carr, C.POINTER(KVCacheC)), _ref(sc), _ptr(logits),
+                                  _ptr(next_ids), n, _ptr(ws), ws_bytes, _stream(stream))
 
 
 def relax_unpack_int4(w: Optional[QMat], out: Ptr, stream=None) -> int:

@@ -297,42 +297,38 @@ relax_status relax_attention(const uint16_t *q, const relax_kv_cache *cache, con
     return hip_status(launch_attention(q, dims->n_heads * dims->head_dim, *cache, *dims, st, L_max, out, partials, st_));
 }
 
-relax_status relax_decoder_layer(const relax_layer_dims *dims, const relax_layer_weights *wt, const uint16_t *x,
-                                 const relax_kv_cache *cache, const relax_seqs *seqs, uint16_t *out, int32_t n, void *ws,
-                                 size_t ws_bytes, relax_stream stream)
+}  // extern "C"
+
+namespace {
+
+// Shape checks of one layer's weights against the static dims.
+relax_status check_layer(const relax_layer_dims &dm, const relax_layer_weights *wt)
 {
-    hipStream_t st_ = static_cast<hipStream_t>(stream);
-    relax_status rc = check_dims(dims);
-    if (rc != RELAX_OK) return rc;
-    if (!wt || !x || !out || !ws || !cache || !cache->k || !cache->v || !cache->rope || !wt->norm_attn || !wt->norm_ffn)
-        return RELAX_ERR_NULL;
+    if (!wt || !wt->norm_attn || !wt->norm_ffn) return RELAX_ERR_NULL;
     const relax_qmat *mats[4] = {&wt->wqkv, &wt->wo, &wt->wgu, &wt->wdown};
     for (const relax_qmat *mq : mats) {
-        rc = check_qmat(mq);
+        const relax_status rc = check_qmat(mq);
         if (rc != RELAX_OK) return rc;
     }
-    const relax_layer_dims &dm = *dims;
     const int32_t hd = dm.n_heads * dm.head_dim, qkvw = (dm.n_heads + 2 * dm.n_kv_heads) * dm.head_dim;
     if (wt->wqkv.m != qkvw || wt->wqkv.k != dm.hidden || wt->wo.m != dm.hidden || wt->wo.k != hd ||
         wt->wgu.m != 2 * dm.ffn || wt->wgu.k != dm.hidden || wt->wdown.m != dm.hidden || wt->wdown.k != dm.ffn)
         return RELAX_ERR_SHAPE;
-    SeqTable st = {};
-    std::vector<int32_t> host_table;
-    int32_t L_max = 0;
-    rc = build_seqs(seqs, dm, n, st, L_max, host_table);
-    if (rc != RELAX_OK) return rc;
-    const WsPlan pl = plan_ws(dm, n, L_max, seqs->B);
-    if (ws_bytes < pl.total) return RELAX_ERR_WORKSPACE;
-    rc = upload_table(st, host_table, ws, pl, st_);
-    if (rc != RELAX_OK) return rc;
+    return RELAX_OK;
+}
 
+// Enqueues one decoder layer.  Everything has been validated; st is the kernel-side ragged descriptor (its device
+// table, if any, already uploaded); base/pl are the layer workspace and its plan.
+relax_status layer_enqueue(const relax_layer_dims &dm, const relax_layer_weights *wt, const uint16_t *x, const relax_kv_cache *cache,
+                           const SeqTable &st, int32_t L_max, uint16_t *out, int32_t n, char *base, const WsPlan &pl, hipStream_t st_)
+{
+    const int32_t hd = dm.n_heads * dm.head_dim, qkvw = (dm.n_heads + 2 * dm.n_kv_heads) * dm.head_dim;
     const StepTimer timer(st_);
-    char *base = static_cast<char *>(ws);
 
     // Runtime dispatch on the symbolic shape (Sec. 5.1): a single decode row takes the persistent fused kernel.
-    if (g_opt_fused_decode && n == 1 && seqs->B == 1) {
+    if (g_opt_fused_decode && n == 1 && st.B == 1) {
         const int cus = device_cus();
-        if (decode_layer_eligible(dm, *wt, n, seqs->B, cus)) {
+        if (decode_layer_eligible(dm, *wt, n, st.B, cus)) {
             DecodeLayerArgs fa = {};
             fa.wqkv = {wt->wqkv.q, wt->wqkv.s, wt->wqkv.m, wt->wqkv.k};
             fa.wo = {wt->wo.q, wt->wo.s, wt->wo.m, wt->wo.k};
@@ -430,6 +426,109 @@ relax_status relax_decoder_layer(const relax_layer_dims *dims, const relax_layer
     timer.before(4);
     if (launch_gemv(dn, X_F16, EPI_RESID_F16, st_) != hipSuccess) return RELAX_ERR_HIP;
     timer.after(4);
+    return RELAX_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+relax_status relax_decoder_layer(const relax_layer_dims *dims, const relax_layer_weights *wt, const uint16_t *x,
+                                 const relax_kv_cache *cache, const relax_seqs *seqs, uint16_t *out, int32_t n, void *ws,
+                                 size_t ws_bytes, relax_stream stream)
+{
+    hipStream_t st_ = static_cast<hipStream_t>(stream);
+    relax_status rc = check_dims(dims);
+    if (rc != RELAX_OK) return rc;
+    if (!wt || !x || !out || !ws || !cache || !cache->k || !cache->v || !cache->rope) return RELAX_ERR_NULL;
+    const relax_layer_dims &dm = *dims;
+    rc = check_layer(dm, wt);
+    if (rc != RELAX_OK) return rc;
+    SeqTable st = {};
+    std::vector<int32_t> host_table;
+    int32_t L_max = 0;
+    rc = build_seqs(seqs, dm, n, st, L_max, host_table);
+    if (rc != RELAX_OK) return rc;
+    const WsPlan pl = plan_ws(dm, n, L_max, seqs->B);
+    if (ws_bytes < pl.total) return RELAX_ERR_WORKSPACE;
+    rc = upload_table(st, host_table, ws, pl, st_);
+    if (rc != RELAX_OK) return rc;
+    return layer_enqueue(dm, wt, x, cache, st, L_max, out, n, static_cast<char *>(ws), pl, st_);
+}
+
+// Workspace of a model step: [layer workspace][xa][xb][normalised last rows][logits]
+struct ModelPlan {
+    WsPlan layer;
+    size_t xa, xb, xn, logits, total;
+};
+
+static ModelPlan plan_model(const relax_model &m, int32_t n, int32_t L, int32_t B)
+{
+    ModelPlan p;
+    p.layer = plan_ws(m.dims, n, L, B);
+    size_t off = p.layer.total;
+    p.xa = off;     off += align256(2 * (size_t)n * m.dims.hidden);
+    p.xb = off;     off += align256(2 * (size_t)n * m.dims.hidden);
+    p.xn = off;     off += align256(2 * (size_t)B * m.dims.hidden);
+    p.logits = off; off += align256(2 * (size_t)B * m.vocab);
+    p.total = off;
+    return p;
+}
+
+static relax_status check_model(const relax_model *m)
+{
+    if (!m) return RELAX_ERR_NULL;
+    const relax_status rc = check_dims(&m->dims);
+    if (rc != RELAX_OK) return rc;
+    if (m->n_layers < 0 || m->vocab < 1 || m->dims.hidden % 8 != 0) return RELAX_ERR_SHAPE;
+    if (!m->embedding || !m->norm_final || !m->lm_head || (m->n_layers > 0 && !m->layers)) return RELAX_ERR_NULL;
+    return RELAX_OK;
+}
+
+size_t relax_model_workspace_bytes(const relax_model *model, int32_t n_max, int32_t L_max, int32_t B_max)
+{
+    if (check_model(model) != RELAX_OK || n_max < 1 || L_max < 1 || B_max < 1) return 0;
+    return plan_model(*model, n_max, L_max, B_max).total;
+}
+
+relax_status relax_model_step(const relax_model *model, const int32_t *ids, const relax_kv_cache *caches, const relax_seqs *seqs,
+                              uint16_t *logits, int32_t *next_ids, int32_t n, void *ws, size_t ws_bytes, relax_stream stream)
+{
+    hipStream_t st_ = static_cast<hipStream_t>(stream);
+    relax_status rc = check_model(model);
+    if (rc != RELAX_OK) return rc;
+    if (!ids || !ws || (model->n_layers > 0 && !caches)) return RELAX_ERR_NULL;
+    const relax_layer_dims &dm = model->dims;
+    for (int l = 0; l < model->n_layers; ++l) {
+        rc = check_layer(dm, &model->layers[l]);
+        if (rc != RELAX_OK) return rc;
+        if (!caches[l].k || !caches[l].v || !caches[l].rope) return RELAX_ERR_NULL;
+    }
+    SeqTable st = {};
+    std::vector<int32_t> host_table;
+    int32_t L_max = 0;
+    rc = build_seqs(seqs, dm, n, st, L_max, host_table);
+    if (rc != RELAX_OK) return rc;
+    const ModelPlan mp = plan_model(*model, n, L_max, seqs->B);
+    if (ws_bytes < mp.total) return RELAX_ERR_WORKSPACE;
+    rc = upload_table(st, host_table, ws, mp.layer, st_);
+    if (rc != RELAX_OK) return rc;
+
+    char *base = static_cast<char *>(ws);
+    uint16_t *cur = reinterpret_cast<uint16_t *>(base + mp.xa), *nxt = reinterpret_cast<uint16_t *>(base + mp.xb);
+    uint32_t *err = reinterpret_cast<uint32_t *>(base + decode_layer_error_offset());
+    if (launch_embed(ids, model->embedding, cur, n, dm.hidden, model->vocab, err, st_) != hipSuccess) return RELAX_ERR_HIP;
+    for (int l = 0; l < model->n_layers; ++l) {
+        rc = layer_enqueue(dm, &model->layers[l], cur, &caches[l], st, L_max, nxt, n, base, mp.layer, st_);
+        if (rc != RELAX_OK) return rc;
+        uint16_t *t = cur;
+        cur = nxt, nxt = t;
+    }
+    uint16_t *xn = reinterpret_cast<uint16_t *>(base + mp.xn);
+    uint16_t *lg = logits ? logits : reinterpret_cast<uint16_t *>(base + mp.logits);
+    if (launch_final_norm(cur, model->norm_final, xn, st, dm.hidden, dm.rms_eps, st_) != hipSuccess) return RELAX_ERR_HIP;
+    if (launch_lm_head(xn, model->lm_head, lg, seqs->B, dm.hidden, model->vocab, device_cus(), st_) != hipSuccess) return RELAX_ERR_HIP;
+    if (next_ids && launch_argmax(lg, next_ids, seqs->B, model->vocab, st_) != hipSuccess) return RELAX_ERR_HIP;
     return RELAX_OK;
 }
 

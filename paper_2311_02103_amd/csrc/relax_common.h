@@ -137,6 +137,12 @@ bool attn_prefill_supported(const relax_layer_dims &dm);
 hipError_t launch_attention_prefill(const uint16_t *q, int32_t q_stride, const relax_kv_cache &cache, const relax_layer_dims &dm,
                                     const SeqTable &st, uint16_t *out, hipStream_t stream);
 
+// Model wrapper steps (model_head.hip)
+hipError_t launch_embed(const int32_t *ids, const uint16_t *E, uint16_t *x, int n, int H, int V, uint32_t *err, hipStream_t stream);
+hipError_t launch_final_norm(const uint16_t *x, const uint16_t *w, uint16_t *y, const SeqTable &st, int H, float eps, hipStream_t stream);
+hipError_t launch_lm_head(const uint16_t *xn, const uint16_t *W, uint16_t *logits, int B, int H, int V, int n_cus, hipStream_t stream);
+hipError_t launch_argmax(const uint16_t *logits, int32_t *ids, int B, int V, hipStream_t stream);
+
 // ---- persistent fused decode layer (decode_layer.hip) -----------------------------------------------------------
 struct DLMat {
     const uint32_t *q;

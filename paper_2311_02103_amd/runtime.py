@@ -87,3 +87,56 @@ class DeviceLayer:
 
         call.keep = keep
         return call
+
+
+class DeviceModel:
+    """A stack of decoder layers with embedding, final norm and fp16 LM head resident on the GPU.
+
+    layer_weights: one host dict per layer (as DeviceLayer takes); a dict may appear several times in the list
+    (weight sharing between layers keeps big synthetic models small on the host) -- its device copy is shared too,
+    each layer still has its own KV cache."""
+
+    def __init__(self, layer_weights: Sequence[Dict[str, np.ndarray]], embedding_bits: np.ndarray, norm_final_bits: np.ndarray,
+                 lm_head_bits: np.ndarray, *, hidden: int, n_heads: int, n_kv_heads: int, head_dim: int, ffn: int,
+                 kv_capacity: int, kv_slots: int = 1, n_max: int = 1, B_max: Optional[int] = None, rms_eps: float = 1e-5,
+                 rope_base: float = 10000.0, device="cuda"):
+        self.device = device
+        self.dims = rx.make_dims(hidden, n_heads, n_kv_heads, head_dim, ffn, kv_capacity, kv_slots, rms_eps, rope_base)
+        self.vocab = int(embedding_bits.shape[0])
+        mats = {"wqkv": ((n_heads + 2 * n_kv_heads) * head_dim, hidden), "wo": (hidden, n_heads * head_dim),
+                "wgu": (2 * ffn, hidden), "wdown": (hidden, ffn)}
+        uploaded = {}
+        self.layers = []
+        for hw in layer_weights:
+            if id(hw) not in uploaded:
+                t = {k: to_device(v, device) for k, v in hw.items()}
+                uploaded[id(hw)] = (t, rx.LayerWeights(*(rx.QMat(t[n + ".q"], t[n + ".s"], *mats[n]) for n in mats),
+                                                       t["norm_attn"], t["norm_ffn"]))
+            self.layers.append(uploaded[id(hw)][1])
+        self._tensors = uploaded
+        self.embedding = to_device(embedding_bits, device)
+        self.norm_final = to_device(norm_final_bits, device)
+        self.lm_head = to_device(lm_head_bits, device)
+        self.model = rx.Model(self.dims, self.layers, self.vocab, self.embedding, self.norm_final, self.lm_head)
+        self.n_max, self.B_max = n_max, (B_max if B_max is not None else max(kv_slots, 1))
+        self.rope = torch.empty(rx.relax_rope_table_bytes(self.dims) // 4, dtype=torch.float32, device=device)
+        rx.check(rx.relax_rope_table_init(self.dims, self.rope), "relax_rope_table_init")
+        self.ws_bytes = rx.relax_model_workspace_bytes(self.model, n_max, kv_capacity, self.B_max)
+        self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device=device)
+        rx.check(rx.relax_workspace_init(self.dims, self.ws, self.ws_bytes), "relax_workspace_init")
+        shape = (kv_slots, kv_capacity, n_kv_heads, head_dim)
+        self.k = [torch.zeros(shape, dtype=torch.float16, device=device) for _ in self.layers]
+        self.v = [torch.zeros(shape, dtype=torch.float16, device=device) for _ in self.layers]
+        self.caches = [rx.KVCache(k, v, self.rope) for k, v in zip(self.k, self.v)]
+
+    def step(self, ids: torch.Tensor, q_lens: Sequence[int], kv_lens: Sequence[int], slots=None,
+             logits: Optional[torch.Tensor] = None, next_ids: Optional[torch.Tensor] = None, stream=None):
+        """ids: int32 [n] on the device.  Returns (logits fp16 [B,V], next_ids int32 [B])."""
+        B = len(q_lens)
+        if logits is None:
+            logits = torch.empty((B, self.vocab), dtype=torch.float16, device=self.device)
+        if next_ids is None:
+            next_ids = torch.empty((B,), dtype=torch.int32, device=self.device)
+        rx.check(rx.relax_model_step(self.model, ids, self.caches, rx.Seqs(q_lens, kv_lens, slots), logits, next_ids,
+                                     int(ids.shape[0]), self.ws, self.ws_bytes, stream), "relax_model_step")
+        return logits, next_ids

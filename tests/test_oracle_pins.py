@@ -368,7 +368,7 @@ def _empty_cache(dims, slots=1):
 def _layer_f64(dims, lw, xbits, K, V, seqs):
     """Independent float64 composition with numpy/scipy library routines (tiny shapes only)."""
     H, h, g, d, F = dims.hidden, dims.n_heads, dims.n_kv_heads, dims.head_dim, dims.ffn
-    x = xbits.view(np.float16).astype(np.float64)
+    x = xbits.view(np.float16).astype(np.float64) if xbits.dtype == np.uint16 else np.asarray(xbits, np.float64)
     dq = lambda m: oracle.dequantize(m.q, m.s, m.m, m.k).astype(np.float64)
     nw = lambda b: b.view(np.float16).astype(np.float64)
 
@@ -467,3 +467,92 @@ def test_layer_rejects_inconsistent_descriptors():
 def test_argmax_takes_lowest_index_among_maxima():
     lg = np.array([[0.0, 3.0, 3.0, -1.0], [5.0, 5.0, 5.0, 5.0], [-2.0, -1.0, -3.0, -1.0]], np.float32)
     assert oracle.argmax(lg).tolist() == [1, 0, 1]
+
+
+# ------------------------------------------------------------------------- model wrapper (Sec. 5.1, end-to-end LLM)
+def _tiny_model(n_layers, vocab=97, seed=7, cap=32):
+    shape = wl.TINY
+    dims = oracle.Dims(shape.hidden, shape.n_heads, shape.n_kv_heads, shape.head_dim, shape.ffn, shape.rms_eps, shape.rope_base, cap)
+    mats = shape.matrices()
+    layers = []
+    for l in range(n_layers):
+        w = wl.layer_weights(shape, seed, layer=l)
+        layers.append(oracle.LayerWeights(*(oracle.QMat(w[n + ".q"], w[n + ".s"], *mats[n]) for n in ("wqkv", "wo", "wgu", "wdown")),
+                                          w["norm_attn"], w["norm_ffn"]))
+    return shape, dims, layers, wl.model_tensors(shape, seed, vocab)
+
+
+def _caches(dims, n_layers, slots):
+    shp = (slots, dims.kv_capacity, dims.n_kv_heads, dims.head_dim)
+    return [np.zeros(shp, np.float32) for _ in range(n_layers)], [np.zeros(shp, np.float32) for _ in range(n_layers)]
+
+
+def test_model_without_layers_closed_form_and_tied_head_returns_the_input_token():
+    shape, dims, _, mt = _tiny_model(0)
+    V, H = mt["embedding"].shape
+    # (a) constant embedding rows c_v * 1, unit norm weight: y = c/sqrt(c^2+eps) * 1, logits[v'] = y * sum_c W[v',c]
+    cvals = (0.25 + 0.125 * np.arange(V)).astype(np.float16)
+    emb = np.repeat(cvals[:, None], H, axis=1).view(np.uint16)
+    ones = np.ones(H, np.float16).view(np.uint16)
+    ids = np.array([3, 50, 96], np.int32)
+    logits, _ = oracle.model_step(dims, [], emb, ones, mt["lm_head"], ids, [], [], oracle.Seqs([1, 1, 1], [1, 1, 1]))
+    c = cvals[ids].astype(np.float64)
+    rowsum = wl.f16_bits_to_f32(mt["lm_head"]).astype(np.float64).sum(axis=1)
+    want = (c / np.sqrt(c * c + dims.rms_eps))[:, None] * rowsum[None, :]
+    assert np.abs(logits - want).max() < 1e-5
+    # (b) LM head tied to a random embedding: <e_id/rms, e_v> is largest at v = id, so greedy returns the input token
+    ids = wl.token_ids(7, 9, V)
+    _, nxt = oracle.model_step(dims, [], mt["embedding"], ones, mt["embedding"], ids, [], [], oracle.Seqs([1] * 9, [1] * 9))
+    assert nxt.tolist() == ids.tolist()
+
+
+def test_model_reads_the_last_row_of_each_sequence_and_batches_like_separate_calls():
+    shape, dims, layers, mt = _tiny_model(2)
+    V = mt["embedding"].shape[0]
+    ids = wl.token_ids(8, 5 + 1 + 3, V)
+    q = [5, 1, 3]
+    K, Vc = _caches(dims, 2, 3)
+    # sequence 1 is a decode row with 4 cached tokens: give every layer's slot 1 a past
+    past = [wl.f16_bits_to_f32(wl.normal_f16_bits(8, 100 + l, (4, dims.n_kv_heads, dims.head_dim))) for l in range(4)]
+    for l in range(2):
+        K[l][1, :4], Vc[l][1, :4] = past[2 * l], past[2 * l + 1]
+    logits, nxt = oracle.model_step(dims, layers, mt["embedding"], mt["norm_final"], mt["lm_head"], ids, K, Vc,
+                                    oracle.Seqs(q, [5, 5, 3]))
+    assert logits.shape == (3, V) and nxt.shape == (3,)
+    # the same three sequences, each in a call of its own (slot 0 of fresh caches)
+    start = 0
+    for b, (ql, kl) in enumerate(zip(q, [5, 5, 3])):
+        Kb, Vb = _caches(dims, 2, 1)
+        if b == 1:
+            for l in range(2):
+                Kb[l][0, :4], Vb[l][0, :4] = past[2 * l], past[2 * l + 1]
+        lg, nb = oracle.model_step(dims, layers, mt["embedding"], mt["norm_final"], mt["lm_head"], ids[start:start + ql], Kb, Vb,
+                                   oracle.Seqs([ql], [kl]))
+        assert np.array_equal(lg[0], logits[b]) and nb[0] == nxt[b]
+        # and the layer caches hold the same appended rows
+        for l in range(2):
+            assert np.array_equal(Kb[l][0, :kl], K[l][b, :kl])
+        start += ql
+    # a prefill's logits belong to its LAST row: dropping the first rows' successors changes them
+    lg_short, _ = oracle.model_step(dims, layers, mt["embedding"], mt["norm_final"], mt["lm_head"], ids[:4], *_caches(dims, 2, 1),
+                                    oracle.Seqs([4], [4]))
+    assert np.abs(lg_short[0] - logits[0]).max() > 1e-4
+
+
+def test_model_stack_equals_layer_by_layer_float64_composition():
+    """Two layers + head against the float64 layer composition used to pin the single layer."""
+    shape, dims, layers, mt = _tiny_model(2, vocab=61)
+    ids = wl.token_ids(9, 6, 61)
+    K, Vc = _caches(dims, 2, 1)
+    logits, _ = oracle.model_step(dims, layers, mt["embedding"], mt["norm_final"], mt["lm_head"], ids, K, Vc, oracle.Seqs([6], [6]))
+    x = mt["embedding"][ids]                                    # fp16 bits: the first layer sees exact fp16 values
+    seqs = oracle.Seqs([6], [6])
+    x64 = None
+    for l in range(2):
+        zero = np.zeros((1, dims.kv_capacity, dims.n_kv_heads, dims.head_dim))
+        x64, _, _ = _layer_f64(dims, layers[l], x if l == 0 else x64, zero, zero.copy(), seqs)
+    wf = wl.f16_bits_to_f32(mt["norm_final"]).astype(np.float64)
+    last = x64[-1]
+    y = last / np.sqrt(np.mean(last * last) + dims.rms_eps) * wf
+    want = wl.f16_bits_to_f32(mt["lm_head"]).astype(np.float64) @ y
+    assert np.abs(logits[0] - want).max() < 2e-4 * max(1.0, np.abs(want).max())

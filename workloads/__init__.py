@@ -177,3 +177,15 @@ def kv_prefill(shape: LayerShape, seed: int, slots: int, capacity: int, layer: i
 def uniform_lengths(seed: int, count: int, lo: int, hi: int, stream: int = 0) -> np.ndarray:
     """count integers uniform in [lo, hi] inclusive."""
     return rng(seed, TID_LENS + stream).integers(lo, hi + 1, size=count, dtype=np.int32)
+
+
+def model_tensors(shape: LayerShape, seed: int, vocab: int) -> Dict[str, np.ndarray]:
+    """Embedding and LM head fp16 bits [vocab, hidden], N(0, 0.02^2); final norm weight fp16 bits [hidden], 1 + 0.1 N(0,1)."""
+    return {"embedding": normal_f16_bits(seed, TID_EMBED, (vocab, shape.hidden), std=0.02),
+            "lm_head": normal_f16_bits(seed, TID_LMHEAD, (vocab, shape.hidden), std=0.02),
+            "norm_final": normal_f16_bits(seed, TID_FINAL_NORM, (shape.hidden,), std=0.1, mean=1.0)}
+
+
+def token_ids(seed: int, count: int, vocab: int, stream: int = 0) -> np.ndarray:
+    """count token ids uniform in [0, vocab)."""
+    return rng(seed, TID_IDS + 16 * stream).integers(0, vocab, size=count, dtype=np.int32)
