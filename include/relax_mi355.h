@@ -144,10 +144,14 @@ size_t       relax_rope_table_bytes(const relax_layer_dims *dims);
 relax_status relax_rope_table_init(const relax_layer_dims *dims, float *table, relax_stream stream);
 
 /* out[i,r] = sum_c x[i,c] * W[r,c] with W decoded on the fly (Sec. 4.2 fused decode;
- * Sec. 5.1 matrix-vector kernel at small n, GEMM otherwise -- picked from n at run time).
- * x [n,k] fp16, out [n,m] fp16, fp32 accumulation.  ws may be NULL when ws_bytes == 0
- * is enough (it is for this call today; the argument is part of the lifted-workspace
- * convention).  Errors: NULL, SHAPE (n<1, m<1, k<8, k%8), UNSUPPORTED (k > 65536).      */
+ * Sec. 5.1: the kernel is picked from the symbolic n at run time -- matrix-vector kernel
+ * for one row, split-K MFMA kernel for a few rows, tiled MFMA GEMM for many).
+ * x [n,k] fp16, out [n,m] fp16, fp32 accumulation.  The few-row kernel keeps its split-K
+ * partial tiles in ws (Sec. 4.4, lifted workspace): relax_matmul_workspace_bytes(w, n_max)
+ * is enough for every n <= n_max; with ws == NULL or fewer bytes the call still succeeds
+ * through the other two kernels.  Errors: NULL, SHAPE (n<1, m<1, k<8, k%8),
+ * UNSUPPORTED (k > 28672).                                                              */
+size_t       relax_matmul_workspace_bytes(const relax_qmat *w, int32_t n_max);
 relax_status relax_dequant_matmul(const uint16_t *x, const relax_qmat *w, uint16_t *out, int32_t n,
                                   void *ws, size_t ws_bytes, relax_stream stream);
 

@@ -73,6 +73,7 @@ _SIGNATURES = {
     "relax_workspace_bytes": (C.c_size_t, [C.POINTER(LayerDims), C.c_int32, C.c_int32, C.c_int32]),
     "relax_rope_table_bytes": (C.c_size_t, [C.POINTER(LayerDims)]),
     "relax_rope_table_init": (C.c_int32, [C.POINTER(LayerDims), C.c_void_p, C.c_void_p]),
+    "relax_matmul_workspace_bytes": (C.c_size_t, [C.POINTER(QMatC), C.c_int32]),
     "relax_dequant_matmul": (C.c_int32, [C.c_void_p, C.POINTER(QMatC), C.c_void_p, C.c_int32, C.c_void_p, C.c_size_t,
                                          C.c_void_p]),
     "relax_rmsnorm_rope": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_void_p,
@@ -202,6 +203,11 @@ def relax_rope_table_bytes(dims: Optional[LayerDims]) -> int:
 
 def relax_rope_table_init(dims: Optional[LayerDims], table: Ptr, stream=None) -> int:
     return lib().relax_rope_table_init(_ref(dims), _ptr(table), _stream(stream))
+
+
+def relax_matmul_workspace_bytes(w: Optional[QMat], n_max: int) -> int:
+    wc = None if w is None else w.c()
+    return int(lib().relax_matmul_workspace_bytes(_ref(wc), n_max))
 
 
 def relax_dequant_matmul(x: Ptr, w: Optional[QMat], out: Ptr, n: int, ws: Ptr = None, ws_bytes: int = 0, stream=None) -> int:

@@ -15,7 +15,7 @@ inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 // Static plan of the lifted workspace (Sec. 4.3 upper bounds, Sec. 4.4 lifting).  Offsets are a
 // pure function of (dims, n, L, B); a call sized by upper bounds covers every smaller call.
 struct WsPlan {
-    size_t sync, f_q, f_knew, f_vnew, f_attn, f_x1, f_act, f_part, f_end, table, partials, qbuf, attn, x1, act, xn, qkv, total;
+    size_t sync, f_q, f_knew, f_vnew, f_attn, f_x1, f_act, f_part, f_end, table, partials, qbuf, attn, x1, act, xn, qkv, skinny, total;
 };
 
 WsPlan plan_ws(const relax_layer_dims &dm, int32_t n, int32_t L, int32_t B)
@@ -45,6 +45,15 @@ WsPlan plan_ws(const relax_layer_dims &dm, int32_t n, int32_t L, int32_t B)
     p.act = off;      off += align256(2 * (size_t)n * dm.ffn);
     p.xn = off;       off += align256(2 * (size_t)n * dm.hidden);
     p.qkv = off;      off += align256(2 * (size_t)n * qkvw);
+    // split-K partial tiles of the few-row matmul: the largest of the four matrices, at most kSkinnyMaxN rows
+    {
+        const int ns = n < kSkinnyMaxN ? n : kSkinnyMaxN;
+        size_t fl = gemm_skinny_partial_floats((int)qkvw, dm.hidden, ns);
+        const size_t f2 = gemm_skinny_partial_floats(dm.hidden, (int)hd, ns), f3 = gemm_skinny_partial_floats(2 * dm.ffn, dm.hidden, ns),
+                     f4 = gemm_skinny_partial_floats(dm.hidden, dm.ffn, ns);
+        fl = fl > f2 ? fl : f2, fl = fl > f3 ? fl : f3, fl = fl > f4 ? fl : f4;
+        p.skinny = off;   off += align256(sizeof(float) * fl);
+    }
     p.total = off;
     return p;
 }
@@ -230,15 +239,26 @@ relax_status relax_rope_table_init(const relax_layer_dims *dims, float *table, r
     return hip_status(launch_rope_table(*dims, table, static_cast<hipStream_t>(stream)));
 }
 
+size_t relax_matmul_workspace_bytes(const relax_qmat *w, int32_t n_max)
+{
+    if (check_qmat(w) != RELAX_OK || n_max < 1) return 0;
+    const int ns = n_max < kSkinnyMaxN ? n_max : kSkinnyMaxN;
+    return align256(sizeof(float) * gemm_skinny_partial_floats(w->m, w->k, ns));
+}
+
 relax_status relax_dequant_matmul(const uint16_t *x, const relax_qmat *w, uint16_t *out, int32_t n, void *ws, size_t ws_bytes,
                                   relax_stream stream)
 {
-    (void)ws, (void)ws_bytes;
     if (!x || !out) return RELAX_ERR_NULL;
     relax_status rc = check_qmat(w);
     if (rc != RELAX_OK) return rc;
     if (n < 1) return RELAX_ERR_SHAPE;
-    // runtime dispatch on the symbolic n (Sec. 5.1): matrix-vector kernel for a few rows, MFMA GEMM otherwise
+    // runtime dispatch on the symbolic n (Sec. 5.1): matrix-vector kernel for one row, split-K MFMA kernel for a few
+    // (when the caller brought the workspace for its partial tiles), tiled MFMA GEMM otherwise
+    if (n >= kSkinnyMinN && n <= kSkinnyMaxN && ws && gemm_skinny_eligible(*w, x, n, EPI_F16) &&
+        (reinterpret_cast<uintptr_t>(ws) & 15) == 0 && ws_bytes >= sizeof(float) * gemm_skinny_partial_floats(w->m, w->k, n))
+        return hip_status(launch_gemm_skinny(x, *w, n, EPI_F16, out, nullptr, nullptr, static_cast<float *>(ws),
+                                             static_cast<hipStream_t>(stream)));
     if (n >= kGemmMinN && gemm_mfma_eligible(*w, x, EPI_F16))
         return hip_status(launch_gemm_mfma(x, *w, n, EPI_F16, out, nullptr, nullptr, static_cast<hipStream_t>(stream)));
     GemvArgs a = {};
@@ -355,29 +375,39 @@ relax_status layer_enqueue(const relax_layer_dims &dm, const relax_layer_weights
 
     float *partials = reinterpret_cast<float *>(base + pl.partials);
 
-    // Large n: MFMA GEMMs with the light steps as separate kernels (same entry point, same binary).
-    if (n >= kGemmMinN && gemm_mfma_eligible(wt->wqkv, x, EPI_F16) && gemm_mfma_eligible(wt->wo, x, EPI_RESID_F32) &&
-        gemm_mfma_eligible(wt->wgu, x, EPI_SWIGLU) && gemm_mfma_eligible(wt->wdown, x, EPI_RESID_F16)) {
+    // More than one row: matrix path (same entry point, same binary) -- the matmuls run on MFMA, as the split-K
+    // few-row kernel up to kSkinnyMaxN rows and as the tiled GEMM above, with the light steps as separate kernels.
+    float *skinny_ws = reinterpret_cast<float *>(base + pl.skinny);
+    auto mat_ok = [&](const relax_qmat &wq, const void *xin, int epi) {
+        return (n <= kSkinnyMaxN && gemm_skinny_eligible(wq, xin, n, epi)) || (n >= kGemmMinN && gemm_mfma_eligible(wq, xin, epi));
+    };
+    auto matmul = [&](const uint16_t *xin, const relax_qmat &wq, int epi, uint16_t *o16, float *o32, const void *resid) {
+        if (n <= kSkinnyMaxN && gemm_skinny_eligible(wq, xin, n, epi))
+            return launch_gemm_skinny(xin, wq, n, epi, o16, o32, resid, skinny_ws, st_);
+        return launch_gemm_mfma(xin, wq, n, epi, o16, o32, resid, st_);
+    };
+    if (n >= kSkinnyMinN && mat_ok(wt->wqkv, x, EPI_F16) && mat_ok(wt->wo, x, EPI_RESID_F32) && mat_ok(wt->wgu, x, EPI_SWIGLU) &&
+        mat_ok(wt->wdown, x, EPI_RESID_F16)) {
         uint16_t *xn = reinterpret_cast<uint16_t *>(base + pl.xn), *qkv = reinterpret_cast<uint16_t *>(base + pl.qkv);
         uint16_t *attn_o = reinterpret_cast<uint16_t *>(base + pl.attn), *act_o = reinterpret_cast<uint16_t *>(base + pl.act);
         float *x1f = reinterpret_cast<float *>(base + pl.x1);
         timer.before(0);
         if (launch_rmsnorm(x, wt->norm_attn, xn, n, dm.hidden, dm.rms_eps, st_) != hipSuccess) return RELAX_ERR_HIP;
-        if (launch_gemm_mfma(xn, wt->wqkv, n, EPI_F16, qkv, nullptr, nullptr, st_) != hipSuccess) return RELAX_ERR_HIP;
+        if (matmul(xn, wt->wqkv, EPI_F16, qkv, nullptr, nullptr) != hipSuccess) return RELAX_ERR_HIP;
         if (launch_rope_append(qkv, dm, *cache, st, st_) != hipSuccess) return RELAX_ERR_HIP;
         timer.after(0);
         timer.before(1);
         if (launch_attention(qkv, qkvw, *cache, dm, st, L_max, attn_o, partials, st_) != hipSuccess) return RELAX_ERR_HIP;
         timer.after(1);
         timer.before(2);
-        if (launch_gemm_mfma(attn_o, wt->wo, n, EPI_RESID_F32, nullptr, x1f, x, st_) != hipSuccess) return RELAX_ERR_HIP;
+        if (matmul(attn_o, wt->wo, EPI_RESID_F32, nullptr, x1f, x) != hipSuccess) return RELAX_ERR_HIP;
         timer.after(2);
         timer.before(3);
         if (launch_rmsnorm_f32(x1f, wt->norm_ffn, xn, n, dm.hidden, dm.rms_eps, st_) != hipSuccess) return RELAX_ERR_HIP;
-        if (launch_gemm_mfma(xn, wt->wgu, n, EPI_SWIGLU, act_o, nullptr, nullptr, st_) != hipSuccess) return RELAX_ERR_HIP;
+        if (matmul(xn, wt->wgu, EPI_SWIGLU, act_o, nullptr, nullptr) != hipSuccess) return RELAX_ERR_HIP;
         timer.after(3);
         timer.before(4);
-        if (launch_gemm_mfma(act_o, wt->wdown, n, EPI_RESID_F16, out, nullptr, x1f, st_) != hipSuccess) return RELAX_ERR_HIP;
+        if (matmul(act_o, wt->wdown, EPI_RESID_F16, out, nullptr, x1f) != hipSuccess) return RELAX_ERR_HIP;
         timer.after(4);
         return RELAX_OK;
     }

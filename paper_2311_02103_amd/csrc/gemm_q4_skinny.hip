@@ -1,0 +1,339 @@
+// Fused int4-decode matmul for a few rows (2 <= n <= 64: batched decode, short prefills):
+//   out[i,r] = sum_c x[i,c] * (u(r,c) - 8) * s[r, c/32].
+//
+// With few rows the contraction is still bound by the one pass over the packed weights (Relax, Sec. 5.1:
+// batch sizes between the matrix-vector case and the compute-bound GEMM), but every weight now meets n
+// activations, so the products go to the matrix cores.  Mapping for gfx950:
+//   - v_mfma_f32_32x32x16_f16 with the weights as the A operand straight from global memory: lane l of a
+//     wavefront owns weight row (l % 32) and one half (l / 32) of each 256-wide k round, i.e. 64 contiguous bytes
+//     of packed codes per round (four 16-byte loads) and four group scales; each word is decoded in registers
+//     (the exact offset-removal decode of the large-n GEMM) into the eight fp16 values of one MFMA k step.
+//     Nothing of the weight stream goes through LDS; loads run two rounds ahead of their use.
+//   - The order of k inside an MFMA is free as long as A and B agree: k step s of half hf pairs word 16 hf + s of
+//     the round with the matching 8-wide x packet.  The x chunk of a round (n rows x 256) is staged in LDS once per
+//     workgroup, each packet in the order [x0 x4 x1 x5 x2 x6 x3 x7] of the decode, and shared by the four
+//     wavefronts (four 32-row blocks of weight rows).  Columns of the 32-wide MFMA tile beyond n are never stored.
+//   - m x k is cut into workgroup tasks of 128 weight rows x one k range (split-K) so that the grid fills 256 CUs
+//     several times over even when m is small; every task writes its fp32 partial tile to the workspace and a small
+//     finishing kernel adds the partials IN A FIXED ORDER and applies the epilogue (plain fp16, residual adds,
+//     SwiGLU).  No atomics: results are reproducible run to run.
+#include "relax_common.h"
+
+namespace relax {
+
+namespace {
+
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef float float16_t __attribute__((ext_vector_type(16)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+
+constexpr int kRound = 256;                  // k per round
+constexpr int kXPitch = kRound + 8;          // LDS row pitch of the x chunk in halfs (528 bytes)
+constexpr int kRowsPerBlock = 128;           // 4 wavefronts x 32 weight rows
+constexpr int kMaxRounds = 16;               // rounds per task at most (the task's scales sit in LDS: 128 rows x 16 bytes per round)
+
+__device__ __forceinline__ uint32_t pk_add(uint32_t a, uint32_t b)
+{
+    return __builtin_bit_cast(uint32_t, __builtin_bit_cast(half2_t, a) + __builtin_bit_cast(half2_t, b));
+}
+__device__ __forceinline__ uint32_t pk_mul(uint32_t a, uint32_t b)
+{
+    return __builtin_bit_cast(uint32_t, __builtin_bit_cast(half2_t, a) * __builtin_bit_cast(half2_t, b));
+}
+__device__ __forceinline__ uint32_t pk_fma(uint32_t a, uint32_t b, uint32_t c)
+{
+    half2_t r = __builtin_elementwise_fma(__builtin_bit_cast(half2_t, a), __builtin_bit_cast(half2_t, b), __builtin_bit_cast(half2_t, c));
+    return __builtin_bit_cast(uint32_t, r);
+}
+// (w & mask) | bits as one VALU op (mask from a scalar register, bits from a vector register)
+__device__ __forceinline__ uint32_t and_or(uint32_t w, uint32_t mask, uint32_t bits)
+{
+    uint32_t r;
+    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(w), "s"(mask), "v"(bits));
+    return r;
+}
+// one packed word and its group scale (fp16 pair s,s) -> 8 fp16 weights in the order [e0 e4 e1 e5 e2 e6 e3 e7];
+// exact up to the final multiply: 1024+u-1032, (1024+16u)/16-72
+__device__ __forceinline__ half8_t decode_word(uint32_t w, uint32_t s2)
+{
+    const uint32_t w8 = w >> 8;
+    const uint32_t a0 = and_or(w, 0x000F000Fu, 0x64006400u), a1 = and_or(w, 0x00F000F0u, 0x64006400u);
+    const uint32_t a2 = and_or(w8, 0x000F000Fu, 0x64006400u), a3 = and_or(w8, 0x00F000F0u, 0x64006400u);
+    const uint32_t kNeg1032 = 0xE408E408u, kSixteenth = 0x2C002C00u, kNeg72 = 0xD480D480u;
+    u32x4_t r;
+    r.x = pk_mul(pk_add(a0, kNeg1032), s2);
+    r.y = pk_mul(pk_fma(a1, kSixteenth, kNeg72), s2);
+    r.z = pk_mul(pk_add(a2, kNeg1032), s2);
+    r.w = pk_mul(pk_fma(a3, kSixteenth, kNeg72), s2);
+    return __builtin_bit_cast(half8_t, r);
+}
+
+struct SkinnyArgs {
+    const uint16_t *x;       // [n,k] fp16
+    const uint32_t *q;       // [m,k/8]
+    const uint16_t *s;       // [m,k/32]
+    float *partial;          // [splits][n][m] fp32
+    int32_t n, m, k;
+    int32_t rounds_per_split;
+};
+
+// grid: x = 128-row tile of weight rows, y = k split.  NF = 32-wide column blocks of the MFMA tile, XR = x rows kept
+// in LDS (n <= XR <= 32 NF).  MFMA columns beyond n compute on whatever the LDS rows hold (for XR = 16 the lanes of
+// columns 16..31 re-read rows 0..15) and are never stored: a column of the result depends on its own x row only.
+template <int NF, int XR>
+__global__ __launch_bounds__(256) void skinny_q4_kernel(SkinnyArgs a)
+{
+    constexpr int XP = XR / 8;                            // 16-byte x packets a thread stages per round (XR rows x 32 packets / 256)
+    constexpr int kXBuf = XR * kXPitch;
+    extern __shared__ __align__(16) uint16_t lds[];       // x chunks [2][XR][kXPitch], then the scale tile [128][sc_pitch]
+    uint16_t *const xs = lds, *const scs = lds + 2 * kXBuf;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int row32 = lane & 31, hf = lane >> 5;
+    const int kw = a.k >> 3, G = a.k >> 5;
+    const int total_rounds = a.k / kRound;
+    const int r_begin = blockIdx.y * a.rounds_per_split, r_end = min(total_rounds, r_begin + a.rounds_per_split);
+    const int nr = r_end - r_begin;                       // >= 1 by construction of the grid
+    const int sc_pitch = a.rounds_per_split * 8 + 8;      // halfs per row of the scale tile (+16 bytes: rows start in different banks)
+
+    // ---- group scales of the whole task, once: 128 rows x (8 nr) fp16, 16-byte packets, coalesced along each row ----
+    // (per-round 8-byte loads would touch every 128-byte line of the scale rows eight rounds in a row)
+    u32x4_t screg[kMaxRounds / 2];
+#pragma unroll
+    for (int i = 0; i < kMaxRounds / 2; ++i) {
+        const int pk = tid + i * 256, row = pk / a.rounds_per_split, rr = pk - row * a.rounds_per_split;
+        const int grow = min(blockIdx.x * kRowsPerBlock + min(row, kRowsPerBlock - 1), a.m - 1);
+        screg[i] = *(const u32x4_t *)(a.s + (size_t)grow * G + (size_t)(r_begin + min(rr, nr - 1)) * (kRound / 32));
+    }
+
+    const int wrow = min(blockIdx.x * kRowsPerBlock + wave * 32 + row32, a.m - 1);
+    const uint32_t *qsrc = a.q + (size_t)wrow * kw + (size_t)r_begin * (kRound / 8) + hf * 16;
+    // x staging roles: packet pk = tid + p * 256 -> x row pk / 32, packet pk % 32 of the round
+    const uint16_t *xsrc[XP];
+    bool xon[XP];
+#pragma unroll
+    for (int p = 0; p < XP; ++p) {
+        const int pk = tid + p * 256, xr = pk >> 5;
+        xon[p] = xr < a.n;
+        xsrc[p] = a.x + (size_t)min(xr, a.n - 1) * a.k + (size_t)r_begin * kRound + (pk & 31) * 8;
+    }
+
+    // Registers of one round in flight: the thread's share of the x chunk and the lane's 64 bytes of codes.
+    // Memory operations of a wavefront complete in order, so x goes first: the chunk is needed one round before the codes.
+    struct Stage {
+        u32x4_t x[XP];
+        u32x4_t w[4];
+    };
+    auto stage_load = [&](Stage &S, int r) {              // r relative to r_begin, clamped: the tail re-reads the last round
+        r = min(r, nr - 1);
+#pragma unroll
+        for (int p = 0; p < XP; ++p) S.x[p] = *(const u32x4_t *)(xsrc[p] + (size_t)r * kRound);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) S.w[i] = *(const u32x4_t *)(qsrc + (size_t)r * (kRound / 8) + i * 4);
+    };
+    auto x_store = [&](const Stage &S, int buf) {
+#pragma unroll
+        for (int p = 0; p < XP; ++p) {
+            if (!xon[p]) continue;
+            const int pk = tid + p * 256;
+            // [x0 x1 | x2 x3 | x4 x5 | x6 x7] -> [x0 x4 | x1 x5 | x2 x6 | x3 x7]
+            u32x4_t o;
+            o.x = __builtin_amdgcn_perm(S.x[p].z, S.x[p].x, 0x05040100u);
+            o.y = __builtin_amdgcn_perm(S.x[p].z, S.x[p].x, 0x07060302u);
+            o.z = __builtin_amdgcn_perm(S.x[p].w, S.x[p].y, 0x05040100u);
+            o.w = __builtin_amdgcn_perm(S.x[p].w, S.x[p].y, 0x07060302u);
+            *(u32x4_t *)(xs + buf * kXBuf + (pk >> 5) * kXPitch + (pk & 31) * 8) = o;
+        }
+    };
+    auto lds_barrier = [&]() {                            // LDS only: global loads stay in flight across it
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+    };
+
+    float16_t acc[NF];
+#pragma unroll
+    for (int j = 0; j < NF; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[j][v] = 0.0f;
+
+    // one round: 16 k steps; word 16 hf + s of the lane's 64 bytes against x packet 16 hf + s of the chunk
+    const uint16_t *sc_lane = scs + (wave * 32 + row32) * sc_pitch + hf * 4;
+    auto round = [&](const Stage &S, int r, int buf) {
+        const uint16_t *xb = xs + buf * kXBuf + (row32 & (XR - 1)) * kXPitch + hf * 128;
+        // the four group scales of the lane's half, each duplicated into both halves of a register
+        const u32x2_t sc = *(const u32x2_t *)(sc_lane + r * 8);
+        const uint32_t s2[4] = {__builtin_amdgcn_perm(sc.x, sc.x, 0x01000100u), __builtin_amdgcn_perm(sc.x, sc.x, 0x03020302u),
+                                __builtin_amdgcn_perm(sc.y, sc.y, 0x01000100u), __builtin_amdgcn_perm(sc.y, sc.y, 0x03020302u)};
+#pragma unroll
+        for (int s = 0; s < 16; ++s) {
+            const u32x4_t &wv = S.w[s >> 2];
+            const uint32_t word = (s & 3) == 0 ? wv.x : (s & 3) == 1 ? wv.y : (s & 3) == 2 ? wv.z : wv.w;
+            const half8_t af = decode_word(word, s2[s >> 2]);
+#pragma unroll
+            for (int j = 0; j < NF; ++j) {
+                const half8_t bf = *(const half8_t *)(xb + (XR > 32 ? j * 32 * kXPitch : 0) + s * 8);
+                acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af, bf, acc[j], 0, 0, 0);
+            }
+        }
+    };
+
+    // Software pipeline, three register stages: everything of round r+2 is requested at the top of round r; the x chunk
+    // of round r+1 moves from registers to LDS at the end of round r.  The loop has one exit: rounds past the end of
+    // the k range still load (clamped), store and synchronise, but skip the arithmetic.
+    Stage S0, S1, S2;
+    stage_load(S0, 0);
+    stage_load(S1, 1);
+#pragma unroll
+    for (int i = 0; i < kMaxRounds / 2; ++i) {
+        const int pk = tid + i * 256, row = pk / a.rounds_per_split, rr = pk - row * a.rounds_per_split;
+        if (row < kRowsPerBlock) *(u32x4_t *)(scs + row * sc_pitch + rr * 8) = screg[i];
+    }
+    x_store(S0, 0);
+    lds_barrier();
+    for (int r = 0; r < nr; r += 3) {
+        stage_load(S2, r + 2);
+        round(S0, r, r & 1);
+        x_store(S1, (r + 1) & 1);
+        lds_barrier();
+        stage_load(S0, r + 3);
+        if (r + 1 < nr) round(S1, r + 1, (r + 1) & 1);
+        x_store(S2, (r + 2) & 1);
+        lds_barrier();
+        stage_load(S1, r + 4);
+        if (r + 2 < nr) round(S2, r + 2, (r + 2) & 1);
+        x_store(S0, (r + 3) & 1);
+        lds_barrier();
+    }
+
+    // partial[split][i][row]: register v of column block j is weight row 8 (v/4) + 4 hf + v%4, x row 32 j + row32
+    const int row0 = blockIdx.x * kRowsPerBlock + wave * 32;
+#pragma unroll
+    for (int j = 0; j < NF; ++j) {
+        const int i = j * 32 + row32;
+        if (i >= a.n) continue;
+        float *dst = a.partial + ((size_t)blockIdx.y * a.n + i) * a.m;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const int r = row0 + b * 8 + hf * 4;
+            if (r < a.m)                                   // m % 4 == 0 is checked by the launcher
+                *(float4_t *)(dst + r) = float4_t{acc[j][b * 4], acc[j][b * 4 + 1], acc[j][b * 4 + 2], acc[j][b * 4 + 3]};
+        }
+    }
+}
+
+// out = epilogue(sum over splits, in order, of partial[s][i][r]); one thread per 4 consecutive r (SwiGLU: 4 gate columns)
+template <int EPI>
+__global__ __launch_bounds__(256) void skinny_finish_kernel(const float *__restrict__ partial, int splits, int n, int m,
+                                                            uint16_t *__restrict__ out_f16, float *__restrict__ out_f32,
+                                                            const void *__restrict__ resid)
+{
+    const int width = EPI == EPI_SWIGLU ? m / 2 : m;
+    const size_t idx = ((size_t)blockIdx.x * 256 + threadIdx.x) * 4;
+    if (idx >= (size_t)n * width) return;
+    const int i = (int)(idx / width), r = (int)(idx - (size_t)i * width);
+    float4_t sum = {0.0f, 0.0f, 0.0f, 0.0f}, sum2 = {0.0f, 0.0f, 0.0f, 0.0f};
+    for (int s = 0; s < splits; ++s) {
+        const float *p = partial + ((size_t)s * n + i) * m + r;
+        sum += *(const float4_t *)p;
+        if (EPI == EPI_SWIGLU) sum2 += *(const float4_t *)(p + width);
+    }
+    const size_t at = (size_t)i * width + r;
+    float v[4] = {sum.x, sum.y, sum.z, sum.w};
+    if (EPI == EPI_RESID_F32) {
+        const u32x2_t xx = *(const u32x2_t *)((const uint16_t *)resid + at);
+        *(float4_t *)(out_f32 + at) = float4_t{h2f((uint16_t)(xx.x & 0xFFFFu)) + v[0], h2f((uint16_t)(xx.x >> 16)) + v[1],
+                                               h2f((uint16_t)(xx.y & 0xFFFFu)) + v[2], h2f((uint16_t)(xx.y >> 16)) + v[3]};
+        return;
+    }
+    if (EPI == EPI_RESID_F16) {
+        const float4_t rr = *(const float4_t *)((const float *)resid + at);
+        v[0] += rr.x, v[1] += rr.y, v[2] += rr.z, v[3] += rr.w;
+    }
+    if (EPI == EPI_SWIGLU) {
+        const float u[4] = {sum2.x, sum2.y, sum2.z, sum2.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = v[e] / (1.0f + __expf(-v[e])) * u[e];
+    }
+    *(u32x2_t *)(out_f16 + at) = u32x2_t{f2h(v[0]) | ((uint32_t)f2h(v[1]) << 16), f2h(v[2]) | ((uint32_t)f2h(v[3]) << 16)};
+}
+
+struct SkinnyPlan {
+    int tiles_m, splits, rounds_per_split;
+};
+
+// Split count: enough tasks for about four workgroups per CU, no k range shorter than 4 rounds (unless k itself is),
+// none longer than kMaxRounds.
+SkinnyPlan skinny_plan(int m, int k)
+{
+    SkinnyPlan p;
+    p.tiles_m = (m + kRowsPerBlock - 1) / kRowsPerBlock;
+    const int rounds = k / kRound;
+    int splits = (1024 + p.tiles_m - 1) / p.tiles_m;
+    const int max_splits = rounds >= 4 ? rounds / 4 : 1, min_splits = (rounds + kMaxRounds - 1) / kMaxRounds;
+    splits = splits > max_splits ? max_splits : splits;
+    splits = splits < min_splits ? min_splits : splits;
+    p.rounds_per_split = (rounds + splits - 1) / splits;
+    p.splits = (rounds + p.rounds_per_split - 1) / p.rounds_per_split;
+    return p;
+}
+
+template <int NF, int XR>
+hipError_t launch_skinny(const SkinnyArgs &a, dim3 grid, hipStream_t stream)
+{
+    const size_t lds = (size_t)2 * XR * kXPitch * sizeof(uint16_t) + (size_t)kRowsPerBlock * (a.rounds_per_split * 8 + 8) * sizeof(uint16_t);
+    static bool attr_done = false;
+    if (!attr_done) {
+        if (hipFuncSetAttribute((const void *)skinny_q4_kernel<NF, XR>, hipFuncAttributeMaxDynamicSharedMemorySize, 112 * 1024) != hipSuccess)
+            return hipErrorInvalidValue;
+        attr_done = true;
+    }
+    hipLaunchKernelGGL((skinny_q4_kernel<NF, XR>), grid, dim3(256), lds, stream, a);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+bool gemm_skinny_eligible(const relax_qmat &w, const void *x, int n, int epi)
+{
+    if (n < 1 || n > kSkinnyMaxN) return false;
+    if (w.k % kRound != 0) return false;
+    if ((reinterpret_cast<uintptr_t>(w.q) & 15) != 0 || (reinterpret_cast<uintptr_t>(w.s) & 15) != 0) return false;
+    if ((reinterpret_cast<uintptr_t>(x) & 15) != 0) return false;
+    return epi == EPI_SWIGLU ? w.m % 8 == 0 : w.m % 4 == 0;
+}
+
+// fp32 elements of workspace the partial tiles of one matmul need
+size_t gemm_skinny_partial_floats(int m, int k, int n)
+{
+    if (k % kRound != 0) return 0;
+    return (size_t)skinny_plan(m, k).splits * (size_t)n * (size_t)m;
+}
+
+hipError_t launch_gemm_skinny(const uint16_t *x, const relax_qmat &w, int n, int epi, uint16_t *out_f16, float *out_f32, const void *resid,
+                              float *partial, hipStream_t stream)
+{
+    const SkinnyPlan pl = skinny_plan(w.m, w.k);
+    SkinnyArgs a;
+    a.x = x, a.q = w.q, a.s = w.s, a.partial = partial, a.n = n, a.m = w.m, a.k = w.k, a.rounds_per_split = pl.rounds_per_split;
+    dim3 grid(pl.tiles_m, pl.splits);
+    hipError_t e;
+    if (n <= 16) e = launch_skinny<1, 16>(a, grid, stream);
+    else if (n <= 32) e = launch_skinny<1, 32>(a, grid, stream);
+    else e = launch_skinny<2, 64>(a, grid, stream);
+    if (e != hipSuccess) return e;
+    const int width = epi == EPI_SWIGLU ? w.m / 2 : w.m;
+    const unsigned fb = (unsigned)(((size_t)n * width / 4 + 255) / 256);
+    switch (epi) {
+    case EPI_F16: hipLaunchKernelGGL(skinny_finish_kernel<EPI_F16>, dim3(fb), dim3(256), 0, stream, partial, pl.splits, n, w.m, out_f16, out_f32, resid); break;
+    case EPI_RESID_F32: hipLaunchKernelGGL(skinny_finish_kernel<EPI_RESID_F32>, dim3(fb), dim3(256), 0, stream, partial, pl.splits, n, w.m, out_f16, out_f32, resid); break;
+    case EPI_RESID_F16: hipLaunchKernelGGL(skinny_finish_kernel<EPI_RESID_F16>, dim3(fb), dim3(256), 0, stream, partial, pl.splits, n, w.m, out_f16, out_f32, resid); break;
+    case EPI_SWIGLU: hipLaunchKernelGGL(skinny_finish_kernel<EPI_SWIGLU>, dim3(fb), dim3(256), 0, stream, partial, pl.splits, n, w.m, out_f16, out_f32, resid); break;
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+}  // namespace relax

@@ -115,6 +115,13 @@ constexpr int kGemmMinN = 16;        // rows from which the MFMA GEMM replaces o
 bool gemm_mfma_eligible(const relax_qmat &w, const void *x, int epi);
 hipError_t launch_gemm_mfma(const uint16_t *x, const relax_qmat &w, int n, int epi, uint16_t *out_f16, float *out_f32, const void *resid,
                             hipStream_t stream);
+// MFMA matmul for a few rows, split-K with partial tiles in the workspace (gemm_q4_skinny.hip)
+constexpr int kSkinnyMinN = 2;       // rows from which the layer takes the matrix path (norm, matmuls, rope as separate launches)
+constexpr int kSkinnyMaxN = 64;      // rows up to which the skinny kernel replaces the tiled GEMM
+bool gemm_skinny_eligible(const relax_qmat &w, const void *x, int n, int epi);
+size_t gemm_skinny_partial_floats(int m, int k, int n);
+hipError_t launch_gemm_skinny(const uint16_t *x, const relax_qmat &w, int n, int epi, uint16_t *out_f16, float *out_f32, const void *resid,
+                              float *partial, hipStream_t stream);
 hipError_t launch_rope_append(uint16_t *qkv, const relax_layer_dims &dm, const relax_kv_cache &cache,
                               const SeqTable &st, hipStream_t stream);
 hipError_t launch_rope_table(const relax_layer_dims &dm, float *table, hipStream_t stream);

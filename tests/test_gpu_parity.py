@@ -33,10 +33,16 @@ def host_bits(t):
     return f16_bits(t)
 
 
-def gpu_matmul(rx, x_bits, q, s, m, k):
+def gpu_matmul(rx, x_bits, q, s, m, k, with_ws=False):
+    """with_ws: bring the workspace that lets a few-row call take the split-K MFMA kernel."""
     n = x_bits.shape[0]
     out = torch.empty((n, m), dtype=torch.float16, device="cuda")
-    rx.check(rx.relax_dequant_matmul(dev(x_bits), rx.QMat(dev(q), dev(s), m, k), out, n), "relax_dequant_matmul")
+    qm = rx.QMat(dev(q), dev(s), m, k)
+    ws, ws_bytes = None, 0
+    if with_ws:
+        ws_bytes = rx.relax_matmul_workspace_bytes(qm, n)
+        ws = torch.full((max(ws_bytes, 16),), 0xFF, dtype=torch.uint8, device="cuda")       # NaN-pattern garbage
+    rx.check(rx.relax_dequant_matmul(dev(x_bits), qm, out, n, ws, ws_bytes), "relax_dequant_matmul")
     torch.cuda.synchronize()
     return host_bits(out)
 
@@ -405,6 +411,50 @@ def test_gemm_random_against_oracle_and_matvec_path(rx, m, k, n):
     # the same rows through the matrix-vector kernel (n below the dispatch threshold): both paths meet the same bar
     rows = gpu_matmul(rx, x[:3], q, s, m, k).view(np.float16).astype(np.float32)
     assert_close(rows, ref[:3], "matvec rows")
+
+
+# ------------------------------------------------------------------------- few-row split-K MFMA kernel (2 <= n <= 64, k % 256 == 0)
+@pytest.mark.parametrize("m,k,n", [(128, 256, 2), (100, 512, 5), (260, 1024, 16), (512, 4096, 32), (132, 11008, 33), (1024, 2048, 64)])
+def test_skinny_integer_valued_bitwise(rx, m, k, n):
+    r = np.random.RandomState(m + k + n)
+    codes = r.randint(0, 16, size=(m, k)).astype(np.uint8)
+    sc = r.choice([1.0, 2.0], size=(m, k // 32)).astype(np.float16)
+    x = np.zeros((n, k), dtype=np.float32)
+    for i in range(n):                                   # sparse small-integer rows keep |out| <= 2048: exact in fp16
+        hot = r.choice(k, size=20, replace=False)
+        x[i, hot] = r.randint(-3, 4, size=20)
+    q, s = wl.pack_codes(codes), sc.view(np.uint16)
+    ref = oracle.dequant_matmul(x, q, s, m, k)
+    assert np.abs(ref).max() <= 2048
+    got = gpu_matmul(rx, x.astype(np.float16).view(np.uint16), q, s, m, k, with_ws=True).view(np.float16).astype(np.float32)
+    assert np.array_equal(got, ref)
+
+
+@pytest.mark.parametrize("m,k,n", [(768, 256, 3), (4096, 4096, 16), (8192, 8192, 16), (512, 28672, 7), (12288, 4096, 40), (1000, 1024, 64)])
+def test_skinny_random_against_oracle_and_reproducible(rx, m, k, n):
+    q, s = wl.qmat(8, m * 7 + k, m, k)
+    x = wl.normal_f16_bits(8, n, (n, k))
+    ref = oracle.dequant_matmul(wl.f16_bits_to_f32(x), q, s, m, k)
+    got = gpu_matmul(rx, x, q, s, m, k, with_ws=True)
+    assert_close(got.view(np.float16).astype(np.float32), ref, "skinny m=%d k=%d n=%d" % (m, k, n))
+    assert np.abs(got.view(np.float16).astype(np.float32) - ref).max() <= 3e-3 * max(1.0, np.abs(ref).max())
+    # partial tiles are summed in a fixed order: a second run gives the same bits
+    assert np.array_equal(got, gpu_matmul(rx, x, q, s, m, k, with_ws=True))
+
+
+def test_mid_layer_batched_decode_through_the_few_row_kernel(rx):
+    """Ragged batches of 2..16 decode rows (and a 40-row mixed call) on the mid-size layer: the matrix path with the
+    split-K kernel, norm / rope / attention as separate launches."""
+    B = 16
+    past = [int(v) for v in wl.uniform_lengths(33, B, 1, 90)]
+    kb, vb = wl.kv_prefill(FAST_MID, 33, B, 128)
+    calls = [([1] * B, [p + 1 for p in past], list(range(B))),
+             ([1, 1], [past[3] + 2, past[7] + 2], [3, 7]),
+             ([1] * 5, [past[b] + (3 if b in (3, 7) else 2) for b in (0, 3, 5, 7, 9)], [0, 3, 5, 7, 9]),
+             ([20, 1, 19], [past[1] + 21, past[2] + 2, past[4] + 20], [1, 2, 4])]
+    outs, (Kg, Vg), (Ko, Vo) = run_schedule(rx, FAST_MID, 33, 128, calls, slots=B, prefill_bits=(kb, vb))
+    for i, (got, ref) in enumerate(outs):
+        assert_close(got, ref, "batched call %d" % i)
 
 
 def test_mid_layer_prefill_and_decode_through_gemm_and_matvec(rx):
