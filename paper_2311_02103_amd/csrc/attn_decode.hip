@@ -209,7 +209,8 @@ static hipError_t launch_d(const uint16_t *q, int q_stride, const relax_kv_cache
 {
     const int rep = dm.n_heads / dm.n_kv_heads;
     hipError_t e;
-    if (rep % 8 == 0) e = launch_split<D, 8>(q, q_stride, cache, dm, st, pl, partials, stream);
+    if (attn_gqa_supported(dm)) e = launch_attention_gqa_split(q, q_stride, cache, dm, st, pl, partials, stream);   // MFMA kernel for grouped heads
+    else if (rep % 8 == 0) e = launch_split<D, 8>(q, q_stride, cache, dm, st, pl, partials, stream);
     else if (rep % 4 == 0) e = launch_split<D, 4>(q, q_stride, cache, dm, st, pl, partials, stream);
     else if (rep % 2 == 0) e = launch_split<D, 2>(q, q_stride, cache, dm, st, pl, partials, stream);
     else e = launch_split<D, 1>(q, q_stride, cache, dm, st, pl, partials, stream);

@@ -138,6 +138,11 @@ size_t attn_partial_floats(const relax_layer_dims &dm, int32_t n_max, int32_t L_
 hipError_t launch_attention(const uint16_t *q, int32_t q_stride, const relax_kv_cache &cache, const relax_layer_dims &dm,
                             const SeqTable &st, int32_t L_max, uint16_t *out, float *partials, hipStream_t stream);
 
+// MFMA split kernel for grouped-query decode rows (attn_gqa.hip); partials in the format of the scalar split kernel
+bool attn_gqa_supported(const relax_layer_dims &dm);
+hipError_t launch_attention_gqa_split(const uint16_t *q, int32_t q_stride, const relax_kv_cache &cache, const relax_layer_dims &dm,
+                                      const SeqTable &st, const AttnPlan &pl, float *partials, hipStream_t stream);
+
 // Causal MFMA attention for calls with many rows per sequence (attn_prefill.hip)
 constexpr int kPrefillMinQ = 16;     // longest q_len from which launch_attention takes the MFMA kernel
 bool attn_prefill_supported(const relax_layer_dims &dm);
