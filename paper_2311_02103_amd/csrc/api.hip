@@ -402,8 +402,8 @@ relax_status layer_enqueue(const relax_layer_dims &dm, const relax_layer_weights
         timer.before(2);
         if (matmul(attn_o, wt->wo, EPI_RESID_F32, nullptr, x1f, x) != hipSuccess) return RELAX_ERR_HIP;
         timer.after(2);
-        timer.before(3);
         if (launch_rmsnorm_f32(x1f, wt->norm_ffn, xn, n, dm.hidden, dm.rms_eps, st_) != hipSuccess) return RELAX_ERR_HIP;
+        timer.before(3);                                  // step 3 brackets the gate/up matmul alone (the dominant kernel)
         if (matmul(xn, wt->wgu, EPI_SWIGLU, act_o, nullptr, nullptr) != hipSuccess) return RELAX_ERR_HIP;
         timer.after(3);
         timer.before(4);
