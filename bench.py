@@ -285,9 +285,13 @@ def bench_model(args, np, torch, wl, rx, big):
         shape, nl, distinct, B, cap, seed = wl.LLAMA7B, 32, args.sets, 1, 512, 3
         steps = args.steps = args.steps or 256
         warmup = args.warmup = 8 if args.warmup is None else args.warmup
+    if args.layers:
+        nl = args.layers
     t_setup = time.time()
+    print("bench: generating %d weight sets of the %s layer shape on the host" % (distinct, shape.name), file=sys.stderr, flush=True)
     host = [wl.layer_weights(shape, seed, layer=l) for l in range(distinct)]
     mt = wl.model_tensors(shape, seed, V)
+    print("bench: host tensors ready after %.0f s, building the device model (%d layers)" % (time.time() - t_setup, nl), file=sys.stderr, flush=True)
     n_max = B if big else 128
     dev = DeviceModel([host[l % distinct] for l in range(nl)], mt["embedding"], mt["norm_final"], mt["lm_head"], hidden=shape.hidden,
                       n_heads=shape.n_heads, n_kv_heads=shape.n_kv_heads, head_dim=shape.head_dim, ffn=shape.ffn, kv_capacity=cap,
@@ -303,6 +307,7 @@ def bench_model(args, np, torch, wl, rx, big):
             dev.v[l].normal_()
         ids = torch.from_numpy(wl.token_ids(seed, B, V)).cuda()
         setup_s = time.time() - t_setup
+        print("bench: device model and KV caches ready after %.0f s" % setup_s, file=sys.stderr, flush=True)
         step = lambda s: dev.step(ids if s == 0 else nxt, [1] * B, [k + s for k in kv], logits=logits, next_ids=nxt)
         for s in range(warmup):
             step(s)
@@ -314,9 +319,9 @@ def bench_model(args, np, torch, wl, rx, big):
         elapsed = time.perf_counter() - t0
         kv_bytes = shape.kv_bytes_per_token() * float(sum(kv) + B * (warmup + steps / 2.0)) * nl
         tokens = B * steps
-        desc = ("configs[4]: Llama-2-70B-shaped GQA model (hidden 8192, 64/8 heads x 128, FFN 28672), 80 layers (%d distinct int4-g32 "
+        desc = ("configs[4]: Llama-2-70B-shaped GQA model (hidden 8192, 64/8 heads x 128, FFN 28672), %d layers (%d distinct int4-g32 "
                 "weight sets cycled, 1.9 GB: more than the last-level cache), vocab 32000, batched decode of 16 sequences, "
-                "L_b~U{100..8000} (sum %d), kv_capacity 8192; 1 step = 1 relax_model_step = 16 tokens" % (distinct, sum(kv)))
+                "L_b~U{100..8000} (sum %d), kv_capacity 8192; 1 step = 1 relax_model_step = 16 tokens" % (nl, distinct, sum(kv)))
         metric = "decode tokens/s (70B-shaped int4 GQA model, batch 16)"
     else:
         prompt = torch.from_numpy(wl.token_ids(seed, 128, V)).cuda()
@@ -332,9 +337,9 @@ def bench_model(args, np, torch, wl, rx, big):
         elapsed = time.perf_counter() - t0
         kv_bytes = shape.kv_bytes_per_token() * (129 + warmup + steps / 2.0) * nl
         tokens = steps
-        desc = ("configs[3]: 32-layer Llama-2-7B-shaped model (%d distinct int4-g32 weight sets cycled), fp16 embedding and LM head, "
+        desc = ("configs[3]: %d-layer Llama-2-7B-shaped model (%d distinct int4-g32 weight sets cycled), fp16 embedding and LM head, "
                 "vocab 32000, 128-token random-id prompt, then greedy decode at batch 1 (next id fed back on the device); "
-                "1 step = 1 relax_model_step = 1 token" % distinct)
+                "1 step = 1 relax_model_step = 1 token" % (nl, distinct))
         metric = "decode tokens/s (7B-shaped int4 model, batch 1)"
     ms_per_step = elapsed * 1e3 / steps
     step_bytes = weight_bytes + kv_bytes
@@ -399,11 +404,15 @@ def main():
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", choices=["decode_layer", "prefill_layer", "model_7b", "batched_70b"], default="decode_layer")
     ap.add_argument("--n", type=int, default=2048, help="rows of the prefill_layer workload")
+    ap.add_argument("--layers", type=int, default=0, help="model workloads: override the layer count (short profiling runs)")
     ap.add_argument("--sets", type=int, default=8, help="distinct weight sets rotated through")
     ap.add_argument("--mode", choices=["graph", "eager"], default="graph",
                     help="decode_layer: the 64-call schedule is captured once in a HIP graph and replayed (Sec. 4.5 of the paper)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the CPU-oracle baseline leg (0 = skip)")
     ap.add_argument("--no-kernel-timing", action="store_true")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="before the workload, copy a 512 MiB buffer four times with a plain device copy kernel: a dispatch of known "
+                         "traffic (512 MiB read, 512 MiB written) that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
     ap.add_argument("--path", choices=["fused", "stepwise"], default="stepwise",
                     help="decode_layer: stepwise = one kernel per step (default); fused = the experimental single persistent kernel")
     args = ap.parse_args()
@@ -420,6 +429,13 @@ def main():
     rx.lib()                                        # raises when the HIP library is not built: there is no fallback
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.pmc_calibration:
+        src = torch.full((128 * 1024 * 1024,), 1.0, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     if args.workload == "decode_layer":
         bench_decode_layer(args, np, torch, wl, rx)
     elif args.workload == "prefill_layer":

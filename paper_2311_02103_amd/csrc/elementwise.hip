@@ -8,12 +8,24 @@
 namespace relax {
 
 // y[i,:] = x[i,:] * rsqrt(mean(x[i,:]^2) + eps) * w ; one workgroup per row, fp32 reduction.
-template <typename T>
-__device__ inline float load_as_float(const T *p, size_t i);
-template <>
-__device__ inline float load_as_float<uint16_t>(const uint16_t *p, size_t i) { return h2f(p[i]); }
-template <>
-__device__ inline float load_as_float<float>(const float *p, size_t i) { return p[i]; }
+// The row is read once, eight elements per thread and pass (16-byte loads for fp16, 2 x 16 bytes for fp32), and
+// stays in registers between the reduction and the scaling (up to kNormPasses * 2048 columns; longer rows re-read).
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
+constexpr int kNormPasses = 4;
+
+__device__ inline void load8(const uint16_t *p, float *v)
+{
+    const u32x4_t raw = *(const u32x4_t *)p;
+    const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) v[2 * j] = h2f((uint16_t)(w[j] & 0xFFFFu)), v[2 * j + 1] = h2f((uint16_t)(w[j] >> 16));
+}
+__device__ inline void load8(const float *p, float *v)
+{
+    const float4_t a = *(const float4_t *)p, b = *(const float4_t *)(p + 4);
+    v[0] = a.x, v[1] = a.y, v[2] = a.z, v[3] = a.w, v[4] = b.x, v[5] = b.y, v[6] = b.z, v[7] = b.w;
+}
 
 template <typename T>
 __global__ __launch_bounds__(256) void rmsnorm_kernel(const T *x, const uint16_t *w, uint16_t *y, int H, float eps)
@@ -21,16 +33,54 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const T *x, const uint16_t
     __shared__ float red[4];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const size_t base = (size_t)blockIdx.x * H;
+    const bool vec = (H & 7) == 0 && H <= kNormPasses * 2048 && ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(y) |
+                                                                  reinterpret_cast<uintptr_t>(w)) & 15) == 0;
+    float v[kNormPasses][8];
     float ss = 0.0f;
-    for (int c = tid; c < H; c += 256) {
-        float v = load_as_float<T>(x, base + c);
-        ss += v * v;
+    if (vec) {
+#pragma unroll
+        for (int p = 0; p < kNormPasses; ++p) {
+            const int c = (p * 256 + tid) * 8;
+            if (c < H) {
+                load8(x + base + c, v[p]);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) ss += v[p][e] * v[p][e];
+            }
+        }
+    } else {
+        for (int c = tid; c < H; c += 256) {
+            float t;
+            if (sizeof(T) == 2) t = h2f(((const uint16_t *)x)[base + c]);
+            else t = ((const float *)x)[base + c];
+            ss += t * t;
+        }
     }
     ss = wave_sum(ss);
     if (lane == 0) red[wave] = ss;
     __syncthreads();
     const float inv = 1.0f / sqrtf((red[0] + red[1] + red[2] + red[3]) / (float)H + eps);
-    for (int c = tid; c < H; c += 256) y[base + c] = f2h(load_as_float<T>(x, base + c) * inv * h2f(w[c]));
+    if (vec) {
+#pragma unroll
+        for (int p = 0; p < kNormPasses; ++p) {
+            const int c = (p * 256 + tid) * 8;
+            if (c < H) {
+                float wv[8];
+                load8(w + c, wv);
+                uint32_t o[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    o[j] = f2h(v[p][2 * j] * inv * wv[2 * j]) | ((uint32_t)f2h(v[p][2 * j + 1] * inv * wv[2 * j + 1]) << 16);
+                *(u32x4_t *)(y + base + c) = u32x4_t{o[0], o[1], o[2], o[3]};
+            }
+        }
+    } else {
+        for (int c = tid; c < H; c += 256) {
+            float t;
+            if (sizeof(T) == 2) t = h2f(((const uint16_t *)x)[base + c]);
+            else t = ((const float *)x)[base + c];
+            y[base + c] = f2h(t * inv * h2f(w[c]));
+        }
+    }
 }
 
 hipError_t launch_rmsnorm(const uint16_t *x, const uint16_t *w, uint16_t *y, int n, int H, float eps, hipStream_t stream)
