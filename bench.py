@@ -397,12 +397,52 @@ def bench_model(args, np, torch, wl, rx, big):
           "us_per_layer": round(ms_per_step * 1e3 / nl, 2), "kernel_ms": {k_: round(v, 5) for k_, v in kernel_ms.items()}})
 
 
+# ------------------------------------------------------------------------------------------------ device ceilings
+def bench_ceilings(args, np, torch, wl, rx):
+    """What the device at hand reaches on a plain streaming read (1 GiB, two buffers alternated: more than the
+    last-level cache) and on a bare MFMA loop: the measured-achievable counterparts of the two published peaks."""
+    steps = args.steps = args.steps or 20
+    args.warmup = 2 if args.warmup is None else args.warmup
+    sink = torch.zeros(256 * 1024, dtype=torch.float32, device="cuda")
+    bufs = [torch.full((256 * 1024 * 1024,), 1.0, dtype=torch.float32, device="cuda") for _ in range(2)]
+    nbytes = bufs[0].numel() * 4
+
+    def timed(fn, reps):
+        for i in range(args.warmup):
+            fn(i)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for i in range(reps):
+            fn(i)
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+
+    ms_read = timed(lambda i: rx.check(rx.relax_probe_stream_read(bufs[i % 2], nbytes, sink)), steps)
+    out = {}
+    for name, rnd in (("near_constant_operands", False), ("random_operands", True)):
+        flops = [0]
+
+        def call(i):
+            rc, flops[0] = rx.relax_probe_mfma(sink, 4000, rnd)
+            rx.check(rc)
+        ms = timed(call, 5)
+        out[name] = round(flops[0] / ms / 1e9, 1)
+    ach = nbytes / ms_read / 1e6
+    emit(args, "device ceilings: streaming read GB/s, MFMA loop TFLOP/s", "GB/s", ach, ms_read, "u32x4 loads / f16 MFMA",
+         {"workload": "ceilings: relax_probe_stream_read over 1 GiB (two buffers alternated) and relax_probe_mfma (16 independent "
+                      "32x32x16 f16 MFMAs per wavefront and iteration, 4 wavefronts per CU, 4000 iterations)", "build_id": rx.relax_build_id()},
+         {"bound": "hbm", "kernel": "stream_read_kernel", "achieved": round(ach, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+          "frac": round(ach / PEAK_HBM_GBS, 4), "traffic": None},
+         None, {"mfma_loop_TFLOPs": out, "mfma_published_peak_TFLOPs": PEAK_MFMA_TFLOPS})
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=0, help="timed steps (default: 1280 decode_layer, 50 prefill_layer, 256 model_7b, 8 batched_70b)")
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", choices=["decode_layer", "prefill_layer", "model_7b", "batched_70b"], default="decode_layer")
+    ap.add_argument("--workload", choices=["decode_layer", "prefill_layer", "model_7b", "batched_70b", "ceilings"], default="decode_layer")
     ap.add_argument("--n", type=int, default=2048, help="rows of the prefill_layer workload")
     ap.add_argument("--layers", type=int, default=0, help="model workloads: override the layer count (short profiling runs)")
     ap.add_argument("--sets", type=int, default=8, help="distinct weight sets rotated through")
@@ -440,6 +480,8 @@ def main():
         bench_decode_layer(args, np, torch, wl, rx)
     elif args.workload == "prefill_layer":
         bench_prefill_layer(args, np, torch, wl, rx)
+    elif args.workload == "ceilings":
+        bench_ceilings(args, np, torch, wl, rx)
     else:
         bench_model(args, np, torch, wl, rx, big=args.workload == "batched_70b")
 

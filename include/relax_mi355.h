@@ -222,6 +222,19 @@ relax_status relax_model_step(const relax_model *model, const int32_t *ids, cons
                               const relax_seqs *seqs, uint16_t *logits, int32_t *next_ids, int32_t n,
                               void *ws, size_t ws_bytes, relax_stream stream);
 
+/* Measurement aids for the roofline figures: what the device at hand reaches on a plain
+ * streaming read and on a bare loop of fp16 matrix-core instructions (the published
+ * peaks, 8 TB/s and 2.5 PFLOP/s, are upper bounds of these).  Time them with events.
+ * relax_probe_stream_read: every byte of buf (16-byte aligned, bytes >= 16) is loaded
+ * once with 16-byte loads; sink: one device word.
+ * relax_probe_mfma: one workgroup of four wavefronts per CU, each issuing 16 independent
+ * 32x32x16 fp16 MFMAs per iteration on register operands (random_data != 0: operands
+ * drawn from a hash, which costs clock under the power limit; 0: near-constant
+ * operands); sink: device fp32 [CUs * 256]; *flops receives the operation count of the
+ * launch.                                                                               */
+relax_status relax_probe_stream_read(const void *buf, size_t bytes, uint32_t *sink, relax_stream stream);
+relax_status relax_probe_mfma(float *sink, int32_t iters, int32_t random_data, int64_t *flops, relax_stream stream);
+
 /* Test exports for the bit-exactness requirement on decoding and indexing: the device
  * decode of (word, nibble, scale group) written out densely, one element per thread.
  * relax_unpack_int4: out int8 [m,k] in -8..7.  relax_dequantize: out fp32 [m,k].        */

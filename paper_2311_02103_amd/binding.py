@@ -85,6 +85,8 @@ _SIGNATURES = {
     "relax_model_workspace_bytes": (C.c_size_t, [C.POINTER(ModelC), C.c_int32, C.c_int32, C.c_int32]),
     "relax_model_step": (C.c_int32, [C.POINTER(ModelC), C.c_void_p, C.POINTER(KVCacheC), C.POINTER(SeqsC), C.c_void_p,
                                      C.c_void_p, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "relax_probe_stream_read": (C.c_int32, [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]),
+    "relax_probe_mfma": (C.c_int32, [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_int64), C.c_void_p]),
     "relax_unpack_int4": (C.c_int32, [C.POINTER(QMatC), C.c_void_p, C.c_void_p]),
     "relax_dequantize": (C.c_int32, [C.POINTER(QMatC), C.c_void_p, C.c_void_p]),
 }
@@ -267,6 +269,17 @@ def relax_model_step(model: Optional[Model], ids: Ptr, caches: Optional[Sequence
     return lib().relax_model_step(None if model is None else C.byref(model.c()), _ptr(ids),
                                   None if carr is None else C.cast(carr, C.POINTER(KVCacheC)), _ref(sc), _ptr(logits),
                                   _ptr(next_ids), n, _ptr(ws), ws_bytes, _stream(stream))
+
+
+def relax_probe_stream_read(buf: Ptr, nbytes: int, sink: Ptr, stream=None) -> int:
+    return lib().relax_probe_stream_read(_ptr(buf), nbytes, _ptr(sink), _stream(stream))
+
+
+def relax_probe_mfma(sink: Ptr, iters: int, random_data: bool, stream=None):
+    """Returns (status, floating-point operations of the launch)."""
+    flops = C.c_int64(0)
+    rc = lib().relax_probe_mfma(_ptr(sink), iters, 1 if random_data else 0, C.byref(flops), _stream(stream))
+    return rc, flops.value
 
 
 def relax_unpack_int4(w: Optional[QMat], out: Ptr, stream=None) -> int:

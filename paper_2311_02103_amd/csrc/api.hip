@@ -217,6 +217,22 @@ void relax_profile_step_events(void *start, void *stop, int32_t step)
     g_prof_step = on ? step : -1;
 }
 
+relax_status relax_probe_stream_read(const void *buf, size_t bytes, uint32_t *sink, relax_stream stream)
+{
+    if (!buf || !sink) return RELAX_ERR_NULL;
+    if (bytes < 16 || (reinterpret_cast<uintptr_t>(buf) & 15) != 0) return RELAX_ERR_SHAPE;
+    return hip_status(launch_probe_stream_read(buf, bytes, sink, device_cus(), static_cast<hipStream_t>(stream)));
+}
+
+relax_status relax_probe_mfma(float *sink, int32_t iters, int32_t random_data, int64_t *flops, relax_stream stream)
+{
+    if (!sink || !flops) return RELAX_ERR_NULL;
+    if (iters < 1) return RELAX_ERR_SHAPE;
+    const int cus = device_cus();
+    *flops = (int64_t)cus * 4 * iters * 16 * (2LL * 32 * 32 * 16);
+    return hip_status(launch_probe_mfma(sink, iters, random_data, cus, static_cast<hipStream_t>(stream)));
+}
+
 const char *relax_build_id(void) { return "relax_mi355 gfx950 " __DATE__ " " __TIME__; }
 
 size_t relax_workspace_bytes(const relax_layer_dims *dims, int32_t n_max, int32_t L_max, int32_t B_max)

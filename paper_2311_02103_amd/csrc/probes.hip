@@ -1,0 +1,83 @@
+// Device-ceiling probes behind relax_probe_stream_read / relax_probe_mfma: what a plain streaming read and a bare
+// loop of matrix-core instructions reach on the device at hand, for the roofline figures of the benchmark (the
+// published peaks are 8 TB/s and 2.5 PFLOP/s; a kernel cannot beat what these reach).  Not part of the hot path.
+#include "relax_common.h"
+
+namespace relax {
+
+namespace {
+
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef float float16_t __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+
+// every workgroup walks the buffer with a grid stride, eight independent 16-byte loads per lane in flight
+__global__ __launch_bounds__(256) void stream_read_kernel(const u32x4_t *__restrict__ buf, size_t packets, uint32_t *sink)
+{
+    const size_t stride = (size_t)gridDim.x * 256;
+    size_t at = (size_t)blockIdx.x * 256 + threadIdx.x;
+    u32x4_t acc = {0u, 0u, 0u, 0u};
+    for (; at + 7 * stride < packets; at += 8 * stride) {
+        u32x4_t v[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = buf[at + j * stride];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc ^= v[j];
+    }
+    for (; at < packets; at += stride) acc ^= buf[at];
+    if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9E3779B9u) sink[0] = 1u;      // keeps the loads alive; practically never true
+}
+
+// 16 independent 32x32x16 fp16 MFMAs per iteration and wavefront (a 128 x 128 accumulator tile), operands in registers
+template <int RANDOM>
+__global__ __launch_bounds__(256) void mfma_rate_kernel(float *sink, int iters)
+{
+    const int lane = threadIdx.x & 63;
+    half8_t a[4], b[4];
+#pragma unroll
+    for (int f = 0; f < 4; ++f)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const uint32_t hsh = (uint32_t)(lane * 131 + f * 17 + e + blockIdx.x * 7919) * 2654435761u;
+            a[f][e] = (_Float16)(RANDOM ? ((int)((hsh >> 8) & 0xFFFF) - 32768) / 16384.0f : 0.001f * (lane + f + e));
+            b[f][e] = (_Float16)(RANDOM ? ((int)((hsh >> 12) & 0xFFFF) - 32768) / 16384.0f : 0.002f * (lane + e));
+        }
+    float16_t acc[4][4];
+#pragma unroll
+    for (int f = 0; f < 4; ++f)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[f][j][v] = 0.0f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int f = 0; f < 4; ++f) acc[f][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[f], b[j], acc[f][j], 0, 0, 0);
+    }
+    float s = 0.0f;
+#pragma unroll
+    for (int f = 0; f < 4; ++f)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) s += acc[f][j][v];
+    sink[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
+}
+
+}  // namespace
+
+hipError_t launch_probe_stream_read(const void *buf, size_t bytes, uint32_t *sink, int n_cus, hipStream_t stream)
+{
+    hipLaunchKernelGGL(stream_read_kernel, dim3(n_cus * 8), dim3(256), 0, stream, (const u32x4_t *)buf, bytes / 16, sink);
+    return hipGetLastError();
+}
+
+hipError_t launch_probe_mfma(float *sink, int iters, int random_data, int n_cus, hipStream_t stream)
+{
+    if (random_data) hipLaunchKernelGGL(mfma_rate_kernel<1>, dim3(n_cus), dim3(256), 0, stream, sink, iters);
+    else hipLaunchKernelGGL(mfma_rate_kernel<0>, dim3(n_cus), dim3(256), 0, stream, sink, iters);
+    return hipGetLastError();
+}
+
+}  // namespace relax

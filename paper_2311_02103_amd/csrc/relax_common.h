@@ -155,6 +155,10 @@ hipError_t launch_final_norm(const uint16_t *x, const uint16_t *w, uint16_t *y, 
 hipError_t launch_lm_head(const uint16_t *xn, const uint16_t *W, uint16_t *logits, int B, int H, int V, int n_cus, hipStream_t stream);
 hipError_t launch_argmax(const uint16_t *logits, int32_t *ids, int B, int V, hipStream_t stream);
 
+// Device-ceiling probes (probes.hip)
+hipError_t launch_probe_stream_read(const void *buf, size_t bytes, uint32_t *sink, int n_cus, hipStream_t stream);
+hipError_t launch_probe_mfma(float *sink, int iters, int random_data, int n_cus, hipStream_t stream);
+
 // ---- persistent fused decode layer (decode_layer.hip) -----------------------------------------------------------
 struct DLMat {
     const uint32_t *q;
