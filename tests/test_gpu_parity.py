@@ -349,7 +349,7 @@ def fused_schedule(rx, shape, seed, cap, Ls, fused):
         calls = [([1], [L], None) for L in Ls]
         outs, caches_g, caches_o = run_schedule(rx, shape, seed, cap, calls, prefill_bits=pre)
     finally:
-        rx.check(rx.relax_set_option("fused_decode", 1))
+        rx.check(rx.relax_set_option("fused_decode", 0))        # back to the default
     return outs, caches_g, caches_o
 
 
@@ -469,3 +469,13 @@ def test_mid_layer_prefill_and_decode_through_gemm_and_matvec(rx):
 def test_llama7b_layer_prefill_128(rx):
     outs, _, _ = run_schedule(rx, wl.LLAMA7B, 2, 128, [([128], [128], None)])
     assert_close(*outs[0], "7B prefill n=128")
+
+
+@pytest.mark.parametrize("n", [511, 2048])
+def test_llama7b_layer_prefill_full_sizes(rx, n):
+    """The remaining row counts of the symbolic-n configuration, every row and the whole appended cache against the
+    oracle (511: ragged tiles everywhere; 2048: the size the prefill figures are quoted on)."""
+    outs, (Kg, Vg), (Ko, Vo) = run_schedule(rx, wl.LLAMA7B, 2, n, [([n], [n], None)])
+    assert_close(*outs[0], "7B prefill n=%d" % n)
+    assert_close(Kg[0, :n], Ko[0, :n], "appended K", atol=5e-3, rtol=5e-3)
+    assert_close(Vg[0, :n], Vo[0, :n], "appended V", atol=5e-3, rtol=5e-3)
