@@ -117,37 +117,52 @@ hipError_t launch_rope_table(const relax_layer_dims &dm, float *table, hipStream
 }
 
 // Rotary embedding in place on the q and k columns of qkv, then append k (rotated) and v to the
-// cache at each row's position.  One workgroup per row; a thread owns one rotation pair or one
-// v element pair.
+// cache at each row's position.  One workgroup per (row, slice of the heads); a thread owns eight
+// consecutive rotation pairs of one head (16-byte loads and stores), or eight v elements.
 __global__ __launch_bounds__(256) void rope_append_kernel(uint16_t *qkv, uint16_t *kc, uint16_t *vc, const float *rope, int h,
                                                           int g, int d, int cap, SeqTable st)
 {
     const int i = blockIdx.x;
     const RowInfo ri = row_info(st, i);
-    const int hd2 = d >> 1, width = (h + 2 * g) * d;
+    const int hd2 = d >> 1, width = (h + 2 * g) * d, per_head = hd2 >> 3;
     uint16_t *row = qkv + (size_t)i * width;
     const size_t tok = ((size_t)ri.slot * cap + ri.pos) * (size_t)(g * d);
-    const int nqk = (h + g) * hd2;
-    for (int u = threadIdx.x; u < nqk; u += blockDim.x) {
-        const int j = u / hd2, t = u - j * hd2;
-        const float c = rope[((size_t)ri.pos * hd2 + t) * 2], s = rope[((size_t)ri.pos * hd2 + t) * 2 + 1];
-        const float a = h2f(row[j * d + t]), b = h2f(row[j * d + t + hd2]);
-        const uint16_t oa = f2h(a * c - b * s), ob = f2h(a * s + b * c);
-        row[j * d + t] = oa;
-        row[j * d + t + hd2] = ob;
+    const int items = (h + g) * per_head;                      // d % 16 == 0 for the supported head dims (64, 128)
+    for (int u = blockIdx.y * 256 + threadIdx.x; u < items; u += gridDim.y * 256) {
+        const int j = u / per_head, t0 = (u - j * per_head) * 8;
+        float a[8], b[8];
+        load8(row + j * d + t0, a);
+        load8(row + j * d + t0 + hd2, b);
+        const float *cs = rope + ((size_t)ri.pos * hd2 + t0) * 2;
+        uint32_t oa[4], ob[4];
+#pragma unroll
+        for (int e = 0; e < 8; e += 2) {
+            const float4_t c2 = *(const float4_t *)(cs + e * 2);          // cos, sin of t0 + e and t0 + e + 1
+            oa[e >> 1] = f2h(a[e] * c2.x - b[e] * c2.y) | ((uint32_t)f2h(a[e + 1] * c2.z - b[e + 1] * c2.w) << 16);
+            ob[e >> 1] = f2h(a[e] * c2.y + b[e] * c2.x) | ((uint32_t)f2h(a[e + 1] * c2.w + b[e + 1] * c2.z) << 16);
+        }
+        const u32x4_t va = {oa[0], oa[1], oa[2], oa[3]}, vb = {ob[0], ob[1], ob[2], ob[3]};
+        *(u32x4_t *)(row + j * d + t0) = va;
+        *(u32x4_t *)(row + j * d + t0 + hd2) = vb;
         if (j >= h) {
-            kc[tok + (size_t)(j - h) * d + t] = oa;
-            kc[tok + (size_t)(j - h) * d + t + hd2] = ob;
+            *(u32x4_t *)(kc + tok + (size_t)(j - h) * d + t0) = va;
+            *(u32x4_t *)(kc + tok + (size_t)(j - h) * d + t0 + hd2) = vb;
         }
     }
     const uint16_t *vrow = row + (size_t)(h + g) * d;
-    for (int e = threadIdx.x; e < g * d; e += blockDim.x) vc[tok + e] = vrow[e];
+    for (int e = (blockIdx.y * 256 + threadIdx.x) * 8; e < g * d; e += gridDim.y * 256 * 8)
+        *(u32x4_t *)(vc + tok + e) = *(const u32x4_t *)(vrow + e);
 }
 
 hipError_t launch_rope_append(uint16_t *qkv, const relax_layer_dims &dm, const relax_kv_cache &cache, const SeqTable &st,
                               hipStream_t stream)
 {
-    hipLaunchKernelGGL(rope_append_kernel, dim3(st.n), dim3(256), 0, stream, qkv, cache.k, cache.v, cache.rope, dm.n_heads,
+    if (((reinterpret_cast<uintptr_t>(qkv) | reinterpret_cast<uintptr_t>(cache.k) | reinterpret_cast<uintptr_t>(cache.v) |
+          reinterpret_cast<uintptr_t>(cache.rope)) & 15) != 0 || dm.head_dim % 16 != 0)
+        return hipErrorInvalidValue;                           // the kernel moves 16-byte packets
+    const int items = (dm.n_heads + dm.n_kv_heads) * (dm.head_dim / 16);
+    const int slices = st.n >= 256 ? 1 : (items + 255) / 256;    // few rows: spread a row's heads over several workgroups
+    hipLaunchKernelGGL(rope_append_kernel, dim3(st.n, slices), dim3(256), 0, stream, qkv, cache.k, cache.v, cache.rope, dm.n_heads,
                        dm.n_kv_heads, dm.head_dim, dm.kv_capacity, st);
     return hipGetLastError();
 }

@@ -264,14 +264,14 @@ struct SkinnyPlan {
     int tiles_m, splits, rounds_per_split;
 };
 
-// Split count: enough tasks for about four workgroups per CU, no k range shorter than 4 rounds (unless k itself is),
+// Split count: up to four workgroups per CU (what stays resident at once), no k range shorter than 4 rounds (unless k itself is),
 // none longer than kMaxRounds.
 SkinnyPlan skinny_plan(int m, int k)
 {
     SkinnyPlan p;
     p.tiles_m = (m + kRowsPerBlock - 1) / kRowsPerBlock;
     const int rounds = k / kRound;
-    int splits = (1024 + p.tiles_m - 1) / p.tiles_m;
+    int splits = 1024 / p.tiles_m;                        // at most one resident wave of workgroups (4 per CU): no tail round
     const int max_splits = rounds >= 4 ? rounds / 4 : 1, min_splits = (rounds + kMaxRounds - 1) / kMaxRounds;
     splits = splits > max_splits ? max_splits : splits;
     splits = splits < min_splits ? min_splits : splits;

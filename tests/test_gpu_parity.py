@@ -374,8 +374,12 @@ def test_fused_decode_epoch_bookkeeping_and_no_error(rx):
     layer = device_layer(shape, w, cap)
     layer.load_cache(*wl.kv_prefill(shape, 5, 1, cap))
     x = dev(wl.activations(shape, 5, 0, 1))
-    ys = [host_bits(layer.forward(x, [1], [300])).copy() for _ in range(5)]     # same call five times: same bits
-    torch.cuda.synchronize()
+    rx.check(rx.relax_set_option("fused_decode", 1))
+    try:
+        ys = [host_bits(layer.forward(x, [1], [300])).copy() for _ in range(5)]     # same call five times: same bits
+        torch.cuda.synchronize()
+    finally:
+        rx.check(rx.relax_set_option("fused_decode", 0))        # back to the default
     for y in ys[1:]:
         assert np.array_equal(y, ys[0])
     assert rx.relax_workspace_error(layer.dims, layer.ws) == 0
