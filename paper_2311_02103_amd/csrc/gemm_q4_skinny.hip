@@ -30,8 +30,7 @@ typedef float float4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 
-constexpr int kRound = 256;                  // k per round
-constexpr int kXPitch = kRound + 8;          // LDS row pitch of the x chunk in halfs (528 bytes)
+constexpr int kRound = 256;                  // k granule every matrix has to be a multiple of (a round is 256 or 128 columns)
 constexpr int kRowsPerBlock = 128;           // 4 wavefronts x 32 weight rows
 constexpr int kMaxRounds = 16;               // rounds per task at most (the task's scales sit in LDS: 128 rows x 16 bytes per round)
 
@@ -83,55 +82,58 @@ struct SkinnyArgs {
 // grid: x = 128-row tile of weight rows, y = k split.  NF = 32-wide column blocks of the MFMA tile, XR = x rows kept
 // in LDS (n <= XR <= 32 NF).  MFMA columns beyond n compute on whatever the LDS rows hold (for XR = 16 the lanes of
 // columns 16..31 re-read rows 0..15) and are never stored: a column of the result depends on its own x row only.
-template <int NF, int XR>
+template <int NF, int XR, int KR>
 __global__ __launch_bounds__(256) void skinny_q4_kernel(SkinnyArgs a)
 {
-    constexpr int XP = XR / 8;                            // 16-byte x packets a thread stages per round (XR rows x 32 packets / 256)
+    constexpr int kXPitch = KR + 8;                       // LDS row pitch of the x chunk in halfs (16-byte fragment reads of 32 rows hit distinct banks)
+    constexpr int W = KR / 16;                            // packed words (= MFMA k steps) per lane and round: the lane's half of the round
+    constexpr int XP = XR * (KR / 8) / 256;               // 16-byte x packets a thread stages per round
     constexpr int kXBuf = XR * kXPitch;
     extern __shared__ __align__(16) uint16_t lds[];       // x chunks [2][XR][kXPitch], then the scale tile [128][sc_pitch]
     uint16_t *const xs = lds, *const scs = lds + 2 * kXBuf;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int row32 = lane & 31, hf = lane >> 5;
     const int kw = a.k >> 3, G = a.k >> 5;
-    const int total_rounds = a.k / kRound;
+    const int total_rounds = a.k / KR;
     const int r_begin = blockIdx.y * a.rounds_per_split, r_end = min(total_rounds, r_begin + a.rounds_per_split);
     const int nr = r_end - r_begin;                       // >= 1 by construction of the grid
-    const int sc_pitch = a.rounds_per_split * 8 + 8;      // halfs per row of the scale tile (+16 bytes: rows start in different banks)
+    const int spr = a.rounds_per_split * KR / 256;        // 16-byte scale packets (8 groups = 256 columns) per row of the task
+    const int sc_pitch = spr * 8 + 8;                     // halfs per row of the scale tile (+16 bytes: rows start in different banks)
 
     // ---- group scales of the whole task, once: 128 rows x (8 nr) fp16, 16-byte packets, coalesced along each row ----
     // (per-round 8-byte loads would touch every 128-byte line of the scale rows eight rounds in a row)
     u32x4_t screg[kMaxRounds / 2];
 #pragma unroll
     for (int i = 0; i < kMaxRounds / 2; ++i) {
-        const int pk = tid + i * 256, row = pk / a.rounds_per_split, rr = pk - row * a.rounds_per_split;
+        const int pk = tid + i * 256, row = pk / spr, pp = pk - row * spr;
         const int grow = min(blockIdx.x * kRowsPerBlock + min(row, kRowsPerBlock - 1), a.m - 1);
-        screg[i] = *(const u32x4_t *)(a.s + (size_t)grow * G + (size_t)(r_begin + min(rr, nr - 1)) * (kRound / 32));
+        screg[i] = *(const u32x4_t *)(a.s + (size_t)grow * G + (size_t)r_begin * (KR / 32) + (size_t)min(pp, nr * KR / 256 - 1) * 8);
     }
 
     const int wrow = min(blockIdx.x * kRowsPerBlock + wave * 32 + row32, a.m - 1);
-    const uint32_t *qsrc = a.q + (size_t)wrow * kw + (size_t)r_begin * (kRound / 8) + hf * 16;
-    // x staging roles: packet pk = tid + p * 256 -> x row pk / 32, packet pk % 32 of the round
+    const uint32_t *qsrc = a.q + (size_t)wrow * kw + (size_t)r_begin * (KR / 8) + hf * W;
+    // x staging roles: packet pk = tid + p * 256 -> x row pk / (KR/8), packet pk % (KR/8) of the round
     const uint16_t *xsrc[XP];
     bool xon[XP];
 #pragma unroll
     for (int p = 0; p < XP; ++p) {
-        const int pk = tid + p * 256, xr = pk >> 5;
+        const int pk = tid + p * 256, xr = pk / (KR / 8);
         xon[p] = xr < a.n;
-        xsrc[p] = a.x + (size_t)min(xr, a.n - 1) * a.k + (size_t)r_begin * kRound + (pk & 31) * 8;
+        xsrc[p] = a.x + (size_t)min(xr, a.n - 1) * a.k + (size_t)r_begin * KR + (pk % (KR / 8)) * 8;
     }
 
     // Registers of one round in flight: the thread's share of the x chunk and the lane's 64 bytes of codes.
     // Memory operations of a wavefront complete in order, so x goes first: the chunk is needed one round before the codes.
     struct Stage {
         u32x4_t x[XP];
-        u32x4_t w[4];
+        u32x4_t w[W / 4];
     };
     auto stage_load = [&](Stage &S, int r) {              // r relative to r_begin, clamped: the tail re-reads the last round
         r = min(r, nr - 1);
 #pragma unroll
-        for (int p = 0; p < XP; ++p) S.x[p] = *(const u32x4_t *)(xsrc[p] + (size_t)r * kRound);
+        for (int p = 0; p < XP; ++p) S.x[p] = *(const u32x4_t *)(xsrc[p] + (size_t)r * KR);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) S.w[i] = *(const u32x4_t *)(qsrc + (size_t)r * (kRound / 8) + i * 4);
+        for (int i = 0; i < W / 4; ++i) S.w[i] = *(const u32x4_t *)(qsrc + (size_t)r * (KR / 8) + i * 4);
     };
     auto x_store = [&](const Stage &S, int buf) {
 #pragma unroll
@@ -144,7 +146,7 @@ __global__ __launch_bounds__(256) void skinny_q4_kernel(SkinnyArgs a)
             o.y = __builtin_amdgcn_perm(S.x[p].z, S.x[p].x, 0x07060302u);
             o.z = __builtin_amdgcn_perm(S.x[p].w, S.x[p].y, 0x05040100u);
             o.w = __builtin_amdgcn_perm(S.x[p].w, S.x[p].y, 0x07060302u);
-            *(u32x4_t *)(xs + buf * kXBuf + (pk >> 5) * kXPitch + (pk & 31) * 8) = o;
+            *(u32x4_t *)(xs + buf * kXBuf + (pk / (KR / 8)) * kXPitch + (pk % (KR / 8)) * 8) = o;
         }
     };
     auto lds_barrier = [&]() {                            // LDS only: global loads stay in flight across it
@@ -159,16 +161,18 @@ __global__ __launch_bounds__(256) void skinny_q4_kernel(SkinnyArgs a)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[j][v] = 0.0f;
 
-    // one round: 16 k steps; word 16 hf + s of the lane's 64 bytes against x packet 16 hf + s of the chunk
-    const uint16_t *sc_lane = scs + (wave * 32 + row32) * sc_pitch + hf * 4;
+    // one round: W k steps; word W hf + s of the lane's codes against x packet W hf + s of the chunk
+    const uint16_t *sc_lane = scs + (wave * 32 + row32) * sc_pitch + hf * (W / 4);
     auto round = [&](const Stage &S, int r, int buf) {
-        const uint16_t *xb = xs + buf * kXBuf + (row32 & (XR - 1)) * kXPitch + hf * 128;
-        // the four group scales of the lane's half, each duplicated into both halves of a register
-        const u32x2_t sc = *(const u32x2_t *)(sc_lane + r * 8);
+        const uint16_t *xb = xs + buf * kXBuf + (row32 & (XR - 1)) * kXPitch + hf * (KR / 2);
+        // the group scales of the lane's half (W/4 of them), each duplicated into both halves of a register
+        u32x2_t sc;
+        if (W == 16) sc = *(const u32x2_t *)(sc_lane + r * 8);
+        else sc = u32x2_t{*(const uint32_t *)(sc_lane + r * 4), 0u};
         const uint32_t s2[4] = {__builtin_amdgcn_perm(sc.x, sc.x, 0x01000100u), __builtin_amdgcn_perm(sc.x, sc.x, 0x03020302u),
                                 __builtin_amdgcn_perm(sc.y, sc.y, 0x01000100u), __builtin_amdgcn_perm(sc.y, sc.y, 0x03020302u)};
 #pragma unroll
-        for (int s = 0; s < 16; ++s) {
+        for (int s = 0; s < W; ++s) {
             const u32x4_t &wv = S.w[s >> 2];
             const uint32_t word = (s & 3) == 0 ? wv.x : (s & 3) == 1 ? wv.y : (s & 3) == 2 ? wv.z : wv.w;
             const half8_t af = decode_word(word, s2[s >> 2]);
@@ -188,8 +192,8 @@ __global__ __launch_bounds__(256) void skinny_q4_kernel(SkinnyArgs a)
     stage_load(S1, 1);
 #pragma unroll
     for (int i = 0; i < kMaxRounds / 2; ++i) {
-        const int pk = tid + i * 256, row = pk / a.rounds_per_split, rr = pk - row * a.rounds_per_split;
-        if (row < kRowsPerBlock) *(u32x4_t *)(scs + row * sc_pitch + rr * 8) = screg[i];
+        const int pk = tid + i * 256, row = pk / spr, pp = pk - row * spr;
+        if (row < kRowsPerBlock) *(u32x4_t *)(scs + row * sc_pitch + pp * 8) = screg[i];
     }
     x_store(S0, 0);
     lds_barrier();
@@ -265,32 +269,35 @@ struct SkinnyPlan {
 };
 
 // Split count: up to four workgroups per CU (what stays resident at once), no k range shorter than 4 rounds (unless k itself is),
-// none longer than kMaxRounds.
-SkinnyPlan skinny_plan(int m, int k)
+// none longer than kMaxRounds; with 128-wide rounds every task has an even number of them (its scales come in packets of 256 columns).
+SkinnyPlan skinny_plan(int m, int k, int kr)
 {
     SkinnyPlan p;
     p.tiles_m = (m + kRowsPerBlock - 1) / kRowsPerBlock;
-    const int rounds = k / kRound;
+    const int rounds = k / kr;
     int splits = 1024 / p.tiles_m;                        // at most one resident wave of workgroups (4 per CU): no tail round
     const int max_splits = rounds >= 4 ? rounds / 4 : 1, min_splits = (rounds + kMaxRounds - 1) / kMaxRounds;
     splits = splits > max_splits ? max_splits : splits;
     splits = splits < min_splits ? min_splits : splits;
     p.rounds_per_split = (rounds + splits - 1) / splits;
+    if (kr == 128) p.rounds_per_split = (p.rounds_per_split + 1) & ~1;
     p.splits = (rounds + p.rounds_per_split - 1) / p.rounds_per_split;
     return p;
 }
 
-template <int NF, int XR>
+inline int skinny_round(int n) { return n <= 64 ? 256 : 128; }   // wider x tiles take narrower rounds: the x chunk has to fit LDS twice
+
+template <int NF, int XR, int KR>
 hipError_t launch_skinny(const SkinnyArgs &a, dim3 grid, hipStream_t stream)
 {
-    const size_t lds = (size_t)2 * XR * kXPitch * sizeof(uint16_t) + (size_t)kRowsPerBlock * (a.rounds_per_split * 8 + 8) * sizeof(uint16_t);
+    const size_t lds = (size_t)2 * XR * (KR + 8) * sizeof(uint16_t) + (size_t)kRowsPerBlock * (a.rounds_per_split * KR / 256 * 8 + 8) * sizeof(uint16_t);
     static bool attr_done = false;
     if (!attr_done) {
-        if (hipFuncSetAttribute((const void *)skinny_q4_kernel<NF, XR>, hipFuncAttributeMaxDynamicSharedMemorySize, 112 * 1024) != hipSuccess)
+        if (hipFuncSetAttribute((const void *)skinny_q4_kernel<NF, XR, KR>, hipFuncAttributeMaxDynamicSharedMemorySize, 112 * 1024) != hipSuccess)
             return hipErrorInvalidValue;
         attr_done = true;
     }
-    hipLaunchKernelGGL((skinny_q4_kernel<NF, XR>), grid, dim3(256), lds, stream, a);
+    hipLaunchKernelGGL((skinny_q4_kernel<NF, XR, KR>), grid, dim3(256), lds, stream, a);
     return hipGetLastError();
 }
 
@@ -309,20 +316,26 @@ bool gemm_skinny_eligible(const relax_qmat &w, const void *x, int n, int epi)
 size_t gemm_skinny_partial_floats(int m, int k, int n)
 {
     if (k % kRound != 0) return 0;
-    return (size_t)skinny_plan(m, k).splits * (size_t)n * (size_t)m;
+    size_t worst = 0;                                     // n rows may run with either round size: take the larger plan
+    for (int kr : {256, 128}) {
+        const size_t v = (size_t)skinny_plan(m, k, kr).splits * (size_t)n * (size_t)m;
+        worst = v > worst ? v : worst;
+    }
+    return worst;
 }
 
 hipError_t launch_gemm_skinny(const uint16_t *x, const relax_qmat &w, int n, int epi, uint16_t *out_f16, float *out_f32, const void *resid,
                               float *partial, hipStream_t stream)
 {
-    const SkinnyPlan pl = skinny_plan(w.m, w.k);
+    const SkinnyPlan pl = skinny_plan(w.m, w.k, skinny_round(n));
     SkinnyArgs a;
     a.x = x, a.q = w.q, a.s = w.s, a.partial = partial, a.n = n, a.m = w.m, a.k = w.k, a.rounds_per_split = pl.rounds_per_split;
     dim3 grid(pl.tiles_m, pl.splits);
     hipError_t e;
-    if (n <= 16) e = launch_skinny<1, 16>(a, grid, stream);
-    else if (n <= 32) e = launch_skinny<1, 32>(a, grid, stream);
-    else e = launch_skinny<2, 64>(a, grid, stream);
+    if (n <= 16) e = launch_skinny<1, 16, 256>(a, grid, stream);
+    else if (n <= 32) e = launch_skinny<1, 32, 256>(a, grid, stream);
+    else if (n <= 64) e = launch_skinny<2, 64, 256>(a, grid, stream);
+    else e = launch_skinny<4, 128, 128>(a, grid, stream);
     if (e != hipSuccess) return e;
     const int width = epi == EPI_SWIGLU ? w.m / 2 : w.m;
     const unsigned fb = (unsigned)(((size_t)n * width / 4 + 255) / 256);

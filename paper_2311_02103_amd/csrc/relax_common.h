@@ -117,7 +117,7 @@ hipError_t launch_gemm_mfma(const uint16_t *x, const relax_qmat &w, int n, int e
                             hipStream_t stream);
 // MFMA matmul for a few rows, split-K with partial tiles in the workspace (gemm_q4_skinny.hip)
 constexpr int kSkinnyMinN = 2;       // rows from which the layer takes the matrix path (norm, matmuls, rope as separate launches)
-constexpr int kSkinnyMaxN = 64;      // rows up to which the skinny kernel replaces the tiled GEMM
+constexpr int kSkinnyMaxN = 128;     // rows up to which the few-row kernel replaces the tiled GEMM
 bool gemm_skinny_eligible(const relax_qmat &w, const void *x, int n, int epi);
 size_t gemm_skinny_partial_floats(int m, int k, int n);
 hipError_t launch_gemm_skinny(const uint16_t *x, const relax_qmat &w, int n, int epi, uint16_t *out_f16, float *out_f32, const void *resid,

@@ -418,7 +418,8 @@ def test_gemm_random_against_oracle_and_matvec_path(rx, m, k, n):
 
 
 # ------------------------------------------------------------------------- few-row split-K MFMA kernel (2 <= n <= 64, k % 256 == 0)
-@pytest.mark.parametrize("m,k,n", [(128, 256, 2), (100, 512, 5), (260, 1024, 16), (512, 4096, 32), (132, 11008, 33), (1024, 2048, 64)])
+@pytest.mark.parametrize("m,k,n", [(128, 256, 2), (100, 512, 5), (260, 1024, 16), (512, 4096, 32), (132, 11008, 33), (1024, 2048, 64),
+                                   (260, 512, 65), (512, 4096, 128), (132, 11008, 100)])
 def test_skinny_integer_valued_bitwise(rx, m, k, n):
     r = np.random.RandomState(m + k + n)
     codes = r.randint(0, 16, size=(m, k)).astype(np.uint8)
@@ -434,7 +435,8 @@ def test_skinny_integer_valued_bitwise(rx, m, k, n):
     assert np.array_equal(got, ref)
 
 
-@pytest.mark.parametrize("m,k,n", [(768, 256, 3), (4096, 4096, 16), (8192, 8192, 16), (512, 28672, 7), (12288, 4096, 40), (1000, 1024, 64)])
+@pytest.mark.parametrize("m,k,n", [(768, 256, 3), (4096, 4096, 16), (8192, 8192, 16), (512, 28672, 7), (12288, 4096, 40), (1000, 1024, 64),
+                                   (4096, 4096, 128), (1000, 11008, 97), (768, 256, 65)])
 def test_skinny_random_against_oracle_and_reproducible(rx, m, k, n):
     q, s = wl.qmat(8, m * 7 + k, m, k)
     x = wl.normal_f16_bits(8, n, (n, k))
