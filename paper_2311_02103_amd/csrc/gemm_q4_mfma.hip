@@ -339,9 +339,9 @@ bool gemm_mfma_eligible(const relax_qmat &w, const void *x, int epi)
     return w.m % 4 == 0;
 }
 
-// Tile choice for n > 128: 256 x 256 or 128 x 256 (weight rows x x-rows), whichever wastes less of the last
-// round of workgroups over the 256 CUs (one workgroup per CU); ties go to the wider tile.  Small n takes
-// narrower x tiles.
+// Tile choice for n > 128: 256 x 256, 128 x 256 or 128 x 128 (weight rows x x-rows), whichever leaves the largest
+// useful share of the rounds of workgroups over the 256 CUs (one workgroup per CU); ties go to the wider tile.
+// Small n takes narrower x tiles.
 hipError_t launch_gemm_mfma(const uint16_t *x, const relax_qmat &w, int n, int epi, uint16_t *out_f16, float *out_f32, const void *resid,
                             hipStream_t stream)
 {
@@ -353,9 +353,17 @@ hipError_t launch_gemm_mfma(const uint16_t *x, const relax_qmat &w, int n, int e
     auto blocks = [&](int mf, int nf) { return ((rows + 64 * mf / rdiv - 1) / (64 * mf / rdiv)) * (long)((n + 64 * nf - 1) / (64 * nf)); };
     const long kCUs = 256;
     if (n > 128) {
-        auto fill = [&](long b) { return (double)b / (double)(((b + kCUs - 1) / kCUs) * kCUs); };
-        if (fill(blocks(4, 4)) >= fill(blocks(2, 4))) return launch_tile<4, 4>(a, stream);
-        return launch_tile<2, 4>(a, stream);
+        // useful share of the workgroup rounds: padding rows of ragged tiles and idle CUs of the last round both count as waste;
+        // the 128 x 128 tile pays about a fifth more LDS traffic per MFMA than the two wide ones
+        auto score = [&](int mf, int nf, double tile_eff) {
+            const long b = blocks(mf, nf);
+            const double rounds = (double)((b + kCUs - 1) / kCUs);
+            return tile_eff * (double)rows * (double)n / (rounds * kCUs * (64.0 * mf / rdiv) * (64.0 * nf));
+        };
+        const double s44 = score(4, 4, 1.0), s24 = score(2, 4, 1.0), s22 = score(2, 2, 0.8);
+        if (s44 >= s24 && s44 >= s22) return launch_tile<4, 4>(a, stream);
+        if (s24 >= s22) return launch_tile<2, 4>(a, stream);
+        return launch_tile<2, 2>(a, stream);
     }
     if (n > 64) return launch_tile<2, 2>(a, stream);
     return launch_tile<2, 1>(a, stream);
