@@ -114,6 +114,48 @@ def test_attention_and_norm_rope_checks():
     assert rx.relax_rope_table_init(d, None) == rx.ERR_NULL
 
 
+def test_model_step_and_matmul_workspace_checks():
+    d = dims()
+    w = weights(d)
+    model = lambda **kw: rx.Model(kw.get("d", d), kw.get("layers", [w, w]), kw.get("vocab", 100), kw.get("emb", P), kw.get("norm", P),
+                                  kw.get("head", P))
+    m = model()
+    wsb = rx.relax_model_workspace_bytes(m, 8, 64, 2)
+    assert wsb > rx.relax_workspace_bytes(d, 8, 64, 2)                    # the layer workspace plus activations and logits
+    assert rx.relax_model_workspace_bytes(None, 8, 64, 2) == 0
+    assert rx.relax_model_workspace_bytes(model(vocab=0), 8, 64, 2) == 0
+    assert rx.relax_model_workspace_bytes(m, 0, 64, 2) == 0
+    caches = [rx.KVCache(P, P, P)] * 2
+    seq = rx.Seqs([3], [3])
+    call = lambda mm=m, ids=P, cc=caches, sq=seq, n=3, ws=P, b=wsb: rx.relax_model_step(mm, ids, cc, sq, P, P, n, ws, b)
+    assert call(mm=None) == rx.ERR_NULL
+    assert call(ids=None) == rx.ERR_NULL
+    assert call(cc=None) == rx.ERR_NULL
+    assert call(ws=None) == rx.ERR_NULL
+    assert call(mm=model(emb=None)) == rx.ERR_NULL
+    assert call(mm=model(head=None)) == rx.ERR_NULL
+    assert call(cc=[rx.KVCache(P, P, P), rx.KVCache(P, None, P)]) == rx.ERR_NULL
+    assert call(mm=model(vocab=0)) == rx.ERR_SHAPE
+    assert call(mm=model(d=dims(hidden=252))) == rx.ERR_SHAPE            # hidden % 8
+    assert call(mm=model(layers=[w, weights(d, wo=rx.QMat(P, P, 256, 128))])) == rx.ERR_SHAPE
+    assert call(n=4) == rx.ERR_SHAPE                                      # sum q_lens != n
+    assert call(sq=rx.Seqs([3], [65])) == rx.ERR_CAPACITY
+    assert call(b=wsb - 1) == rx.ERR_WORKSPACE or rx.relax_model_workspace_bytes(m, 3, 3, 1) <= wsb - 1
+    assert call(b=16) == rx.ERR_WORKSPACE
+    # a model without layers needs no caches
+    assert rx.relax_model_step(model(layers=[]), None, None, seq, P, P, 3, P, wsb) == rx.ERR_NULL        # ids still required
+    # few-row matmul workspace: zero for bad arguments, grows with the row bound up to the kernel's limit
+    q = rx.QMat(P, P, 4096, 4096)
+    assert rx.relax_matmul_workspace_bytes(None, 4) == 0 and rx.relax_matmul_workspace_bytes(q, 0) == 0
+    assert 0 < rx.relax_matmul_workspace_bytes(q, 2) < rx.relax_matmul_workspace_bytes(q, 64)
+    assert rx.relax_matmul_workspace_bytes(q, 128) == rx.relax_matmul_workspace_bytes(q, 4096)
+    assert rx.relax_matmul_workspace_bytes(rx.QMat(P, P, 64, 688), 16) == 0      # k not a multiple of 256: the kernel never runs
+    # probes validate before launching
+    assert rx.relax_probe_stream_read(None, 64, P) == rx.ERR_NULL
+    assert rx.relax_probe_stream_read(P + 4, 64, P) == rx.ERR_SHAPE
+    assert rx.relax_probe_mfma(None, 10, False)[0] == rx.ERR_NULL
+
+
 def test_no_product_module_touches_the_oracle():
     pkg = os.path.join(ROOT, "paper_2311_02103_amd")
     for dirpath, _, files in os.walk(pkg):
