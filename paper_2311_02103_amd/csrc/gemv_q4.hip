@@ -405,12 +405,14 @@ __global__ __launch_bounds__(kSThreads) void gemv_q4_stream_kernel(GemvArgs a)
     float acc8[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc8[e] = 0.0f;
-    auto trip = [&](Slot &s, int su) {
+    auto trip = [&](Slot &s, int su, bool prefetch) {
         const int j = su / nsub, sub = su - j * nsub;
         slot_consume(s, M, xs, corr, sub * 2, 0, lane, su < nsu, acc8);
-        int rows[4], chunk0;
-        target(su + 2, rows, chunk0);
-        slot_load(s, M, rows, chunk0, 0, lane);
+        if (prefetch) {                                            // compile-time constant at both call sites
+            int rows[4], chunk0;
+            target(su + 2, rows, chunk0);
+            slot_load(s, M, rows, chunk0, 0, lane);
+        }
         if (su < nsu && sub == nsub - 1) {
             float v[4];
 #pragma unroll
@@ -423,11 +425,17 @@ __global__ __launch_bounds__(kSThreads) void gemv_q4_stream_kernel(GemvArgs a)
             for (int e = 0; e < 8; ++e) acc8[e] = 0.0f;
         }
     };
+    // The last two trips are peeled off the loop and request nothing: a wavefront does not retire before its
+    // outstanding loads have returned, so prefetching past the end would add a memory round trip to every launch.
+    const int nsu_even = (nsu + 1) & ~1;
+    int su = 0;
 #pragma unroll 1
-    for (int su = 0; su < nsu; su += 2) {
-        trip(s0, su);
-        trip(s1, su + 1);
+    for (; su + 2 < nsu_even; su += 2) {
+        trip(s0, su, true);
+        trip(s1, su + 1, true);
     }
+    trip(s0, su, false);
+    trip(s1, su + 1, false);
     stamp(3);
     if (lane < mine) {
         float v[4];
@@ -441,6 +449,8 @@ __global__ __launch_bounds__(kSThreads) void gemv_q4_stream_kernel(GemvArgs a)
 template <int XMODE, int EPI>
 static hipError_t launch_t(const GemvArgs &a, hipStream_t stream)
 {
+    static const bool use_reg = getenv("RELAX_GEMV_OLD") == nullptr;     // tuning aid: the LDS-resident variants below
+    if (use_reg && gemv_reg_eligible(a)) return launch_gemv_reg(a, XMODE, EPI, stream);
     const int k = a.k, G = groups_of(k);
     const bool fast = (k % kGroup == 0) && ((k / 8) % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.q) & 15) == 0) &&
                       ((reinterpret_cast<uintptr_t>(a.x) & 15) == 0) && ((reinterpret_cast<uintptr_t>(a.norm_w) & 15) == 0);

@@ -1,0 +1,424 @@
+// Batch-1 matrix-vector kernel with the x row in registers (Relax, Sec. 4.2 decode_q4 case study: the 4-bit decode
+// fused into the consuming matmul; Sec. 5.1: batch-1 decoding served by a dedicated matrix-vector program).
+//
+// The kernel is bound by HBM, and at the sizes of one decoder layer a launch lasts ~10 us, so what counts besides
+// the stream itself is (a) how few vector instructions a weight costs -- one wavefront per SIMD leaves nothing to
+// hide them behind -- and (b) how short the x-dependent prologue and the tail are:
+//   * one workgroup of four wavefronts per CU; a wavefront walks its units (row pairs the epilogue consumes
+//     together) in slots of R rows, two slots in flight, 16-byte loads (one quantisation group per lane and load,
+//     1 KB contiguous per wavefront);
+//   * the first slots are requested before anything that depends on x; x is staged once per workgroup through LDS
+//     (RMSNorm folded in) and then lives in registers in the packet order of the decode: lane l owns groups
+//     l, l + 64, ... of the row, exactly the groups its weight loads bring, so the loop touches no LDS;
+//   * decode: (w & 0x000F000F) | 0x6400 6400 is the fp16 pair (1024 + u0, 1024 + u4) in one v_and_or_b32, the other
+//     masks give (1024 + 16 u1, 1024 + 16 u5) and, on w >> 8, nibbles 2,6 and 3,7; v_dot2_f32_f16 contracts a pair with
+//     two x values in fp32 and the offsets leave per group through 1032 sum_A x + 72 sum_B x (exact arithmetic on
+//     integer-valued inputs);
+//   * the R row sums of a slot are reduced together with DPP row operations (a transposing reduction: 2 cross-row
+//     exchanges per slot instead of 6 per row);
+//   * inputs of the epilogue (residual values, rotary table entries) are fetched at the very start, results are
+//     parked in LDS and lane j finishes the wavefront's j-th unit after the stream has drained, so no load of the
+//     epilogue ever sits between weight loads (memory operations of a wavefront return in order).
+#include <algorithm>
+#include <cstdlib>
+
+#include "q4_device.h"
+
+namespace relax {
+
+namespace {
+
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+
+constexpr int kRThreads = 256, kRWaves = kRThreads / kWave;
+constexpr int kRMaxUnits = 64;            // units per wavefront: lane j finishes unit j
+
+// (w & mask) | bits as one VALU op (mask from a scalar register, bits from a vector register)
+__device__ __forceinline__ uint32_t and_or(uint32_t w, uint32_t mask, uint32_t bits)
+{
+    uint32_t r;
+    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(w), "s"(mask), "v"(bits));
+    return r;
+}
+
+// sum_c x_c (u_c - 8) of one group: wq = its four words, xv = the lane's 32 x values in packet order
+// ([x0 x4 x1 x5 x2 x6 x3 x7] per word), corr = 1032 sum_A x + 72 sum_B x
+__device__ __forceinline__ float group_dot_r(const u32x4_t &wq, const u32x4_t *xv, float corr)
+{
+    const uint32_t base = 0x64006400u;
+    float accA = 0.0f, accB = 0.0f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const uint32_t w = wq[j], w8 = w >> 8;
+        accA = dot2(and_or(w, 0x000F000Fu, base), xv[j].x, accA);
+        accB = dot2(and_or(w, 0x00F000F0u, base), xv[j].y, accB);
+        accA = dot2(and_or(w8, 0x000F000Fu, base), xv[j].z, accA);
+        accB = dot2(and_or(w8, 0x00F000F0u, base), xv[j].w, accB);
+    }
+    return accA + accB * 0.0625f - corr;
+}
+
+// value of another lane through a DPP control word (all lanes active, full row and bank masks)
+template <int CTRL>
+__device__ __forceinline__ float dpp(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
+}
+constexpr int kQuadXor1 = 0xB1, kQuadXor2 = 0x4E, kRowRor4 = 0x124, kRowRor8 = 0x128;
+
+// four per-lane partial sums (rows 0..3 of a slot) -> lane l holds the wavefront total of row l & 3
+__device__ __forceinline__ float reduce4(float v0, float v1, float v2, float v3, int lane)
+{
+    const bool odd = lane & 1, up = lane & 2;
+    const float p = (odd ? v1 : v0) + dpp<kQuadXor1>(odd ? v0 : v1);
+    const float q = (odd ? v3 : v2) + dpp<kQuadXor1>(odd ? v2 : v3);
+    float r = (up ? q : p) + dpp<kQuadXor2>(up ? p : q);
+    r += dpp<kRowRor4>(r);
+    r += dpp<kRowRor8>(r);
+    r += __shfl_xor(r, 16, kWave);
+    r += __shfl_xor(r, 32, kWave);
+    return r;
+}
+// two partial sums -> lane l holds the total of row l & 1
+__device__ __forceinline__ float reduce2(float v0, float v1, int lane)
+{
+    const bool odd = lane & 1;
+    float r = (odd ? v1 : v0) + dpp<kQuadXor1>(odd ? v0 : v1);
+    r += dpp<kQuadXor2>(r);
+    r += dpp<kRowRor4>(r);
+    r += dpp<kRowRor8>(r);
+    r += __shfl_xor(r, 16, kWave);
+    r += __shfl_xor(r, 32, kWave);
+    return r;
+}
+
+template <int EPI>
+__device__ __forceinline__ int unit_count_r(const GemvArgs &a)
+{
+    return (EPI == EPI_SWIGLU || EPI == EPI_ROPE_KV) ? a.m / 2 : (a.m + 1) / 2;
+}
+
+// unit u -> the two matrix rows whose results the epilogue consumes together
+template <int EPI>
+__device__ __forceinline__ void unit_rows_r(const GemvArgs &a, int u, int &ra, int &rb)
+{
+    if (EPI == EPI_SWIGLU) {
+        ra = u, rb = u + a.m / 2;
+    } else if (EPI == EPI_ROPE_KV) {
+        const int hd2 = a.d >> 1, nqk = (a.h + a.g) * hd2;
+        if (u < nqk) {
+            const int j = u / hd2, t = u - j * hd2;
+            ra = j * a.d + t, rb = ra + hd2;
+        } else {
+            ra = (a.h + a.g) * a.d + 2 * (u - nqk), rb = ra + 1;
+        }
+    } else {
+        ra = 2 * u, rb = min(2 * u + 1, a.m - 1);
+    }
+}
+
+// what the epilogue of unit u reads besides the two sums: fetched before the weight stream starts
+template <int EPI>
+__device__ __forceinline__ float2 epi_fetch(const GemvArgs &a, int i, const RowInfo &ri, int u)
+{
+    float2 pre = make_float2(0.0f, 0.0f);
+    int ra, rb;
+    unit_rows_r<EPI>(a, u, ra, rb);
+    const size_t base = (size_t)i * a.m;
+    if (EPI == EPI_RESID_F32) {
+        const uint16_t *xr = (const uint16_t *)a.resid;
+        pre = make_float2(h2f(xr[base + ra]), h2f(xr[base + rb]));
+    } else if (EPI == EPI_RESID_F16) {
+        const float *xr = (const float *)a.resid;
+        pre = make_float2(xr[base + ra], xr[base + rb]);
+    } else if (EPI == EPI_ROPE_KV) {
+        const int hd2 = a.d >> 1, nqk = (a.h + a.g) * hd2;
+        if (u < nqk) pre = *(const float2 *)(a.rope + ((size_t)ri.pos * hd2 + (u % hd2)) * 2);     // cos, sin
+    }
+    return pre;
+}
+
+template <int EPI>
+__device__ __forceinline__ void epi_store(const GemvArgs &a, int i, const RowInfo &ri, int u, float va, float vb, float2 pre)
+{
+    int ra, rb;
+    unit_rows_r<EPI>(a, u, ra, rb);
+    const size_t base = (size_t)i * a.m;
+    if (EPI == EPI_F16) {
+        a.out_f16[base + ra] = f2h(va);
+        if (2 * u + 1 < a.m) a.out_f16[base + rb] = f2h(vb);
+    } else if (EPI == EPI_RESID_F32) {
+        a.out_f32[base + ra] = pre.x + va;
+        if (2 * u + 1 < a.m) a.out_f32[base + rb] = pre.y + vb;
+    } else if (EPI == EPI_RESID_F16) {
+        a.out_f16[base + ra] = f2h(pre.x + va);
+        if (2 * u + 1 < a.m) a.out_f16[base + rb] = f2h(pre.y + vb);
+    } else if (EPI == EPI_SWIGLU) {
+        a.out_f16[(size_t)i * (a.m / 2) + u] = f2h(va / (1.0f + expf(-va)) * vb);
+    } else {  // EPI_ROPE_KV
+        const int hd2 = a.d >> 1, nqk = (a.h + a.g) * hd2;
+        const size_t tok = ((size_t)ri.slot * a.kv_capacity + ri.pos) * (size_t)(a.g * a.d);
+        if (u < nqk) {
+            const int j = u / hd2, t = u - j * hd2;
+            const float oa = va * pre.x - vb * pre.y, ob = va * pre.y + vb * pre.x;
+            uint16_t *dst = (j < a.h) ? a.out_f16 + (size_t)i * (a.h * a.d) + (size_t)j * a.d + t
+                                      : a.kcache + tok + (size_t)(j - a.h) * a.d + t;
+            dst[0] = f2h(oa), dst[hd2] = f2h(ob);
+        } else {
+            uint16_t *dst = a.vcache + tok + 2 * (size_t)(u - nqk);
+            dst[0] = f2h(va), dst[1] = f2h(vb);
+        }
+    }
+}
+
+template <int NG>
+struct RegShape {
+    static constexpr int R = NG <= 2 ? 4 : 2;                  // rows per slot
+    static constexpr int NSLOT = 2;                            // slots in flight (the schedule of the stream is written for two)
+};
+
+// grid: x = workgroups (at most one per CU and row), y = row of x
+template <int XMODE, int EPI, int NG>
+__global__ __launch_bounds__(kRThreads) void gemv_q4_reg_kernel(GemvArgs a)
+{
+    constexpr int R = RegShape<NG>::R, NSLOT = RegShape<NG>::NSLOT, UPS = R / 2, E = R * NG;
+    __shared__ __align__(16) uint16_t xs[NG * 2048];
+    __shared__ float red[kRWaves];
+    __shared__ float res_all[kRWaves][kRMaxUnits * 2 + 2];
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int i = blockIdx.y;
+    const int k = a.k, G = k >> 5, kw = k >> 3;
+    const int U = unit_count_r<EPI>(a);
+    const int W = gridDim.x * kRWaves, wg = blockIdx.x * kRWaves + wave;
+    const int mine = wg < U ? (U - wg + W - 1) / W : 0;        // <= kRMaxUnits: the launcher sizes the grid for it
+    float *res = res_all[wave];
+    auto stamp = [&](int st) {                                 // optional measurement aid: wall-clock stamps of a workgroup
+        if (a.trace && tid == 0 && blockIdx.y == 0) a.trace[blockIdx.x * 8 + st] = wall_clock64();
+    };
+    stamp(0);
+
+    // ---- what the epilogue reads, then the x row, then the first slots: requested in the order they are needed ----
+    RowInfo ri = {0, 0, 0};
+    if (EPI == EPI_ROPE_KV) ri = row_info(a.seqs, i);
+    float2 pre = make_float2(0.0f, 0.0f);
+    if (lane < mine) pre = epi_fetch<EPI>(a, i, ri, wg + lane * W);
+
+    // pass p of the staging covers chunk p of 2048 columns: thread t holds word t & 3 of group 64 p + (t >> 2)
+    const size_t xbase = (size_t)i * k;
+    u32x4_t xraw[NG], xraw2[XMODE == X_F32_NORM ? NG : 1], wnr[XMODE != X_F16 ? NG : 1];
+#pragma unroll
+    for (int p = 0; p < NG; ++p) {
+        const int c8 = min(p * kRThreads + tid, kw - 1);
+        if (XMODE == X_F32_NORM) {
+            xraw[p] = *(const u32x4_t *)((const float *)a.x + xbase + (size_t)c8 * 8);
+            xraw2[p] = *(const u32x4_t *)((const float *)a.x + xbase + (size_t)c8 * 8 + 4);
+        } else {
+            xraw[p] = *(const u32x4_t *)((const uint16_t *)a.x + xbase + (size_t)c8 * 8);
+        }
+        if (XMODE != X_F16) wnr[p] = *(const u32x4_t *)(a.norm_w + (size_t)c8 * 8);
+    }
+
+    struct Slot {
+        u32x4_t w[E];
+        uint16_t sc[E];
+    };
+    // entry e = rr * NG + c: row rr of the slot (unit j0 + rr / 2, its first or second row), chunk c
+    // The requests of a slot stay together in program order (scheduling barriers on both sides): the wait before a
+    // consume is a count of younger requests, and one request of this slot issued late would make it cover the
+    // other slot as well.
+    auto slot_load = [&](Slot &s, int j0) {
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int uu = 0; uu < UPS; ++uu) {
+            const int u = min(wg + (j0 + uu) * W, U - 1);          // units past the end re-read a valid one and are dropped
+            int rows[2];
+            unit_rows_r<EPI>(a, u, rows[0], rows[1]);
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const uint32_t *qrow = a.q + (size_t)rows[h] * kw;
+                const uint16_t *srow = a.s + (size_t)rows[h] * G;
+#pragma unroll
+                for (int c = 0; c < NG; ++c) {
+                    const int gi = (c == NG - 1) ? min(c * 64 + lane, G - 1) : c * 64 + lane;
+                    s.w[(uu * 2 + h) * NG + c] = *(const u32x4_t *)(qrow + gi * 4);
+                    s.sc[(uu * 2 + h) * NG + c] = srow[gi];
+                }
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    Slot sl[NSLOT];
+#pragma unroll
+    for (int t = 0; t < NSLOT; ++t) slot_load(sl[t], t * UPS);
+    stamp(1);
+
+    // ---- stage the (optionally RMS-normalised) x row in LDS as fp16, packet order [x0 x4 x1 x5 x2 x6 x3 x7] ----
+    float inv = 1.0f;
+    float xf[XMODE != X_F16 ? NG : 1][8];
+    if (XMODE != X_F16) {
+        float ss = 0.0f;
+#pragma unroll
+        for (int p = 0; p < NG; ++p) {
+            const bool on = (p * kRThreads + tid) < kw;
+            if (XMODE == X_F32_NORM) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) xf[p][e] = __uint_as_float(xraw[p][e]), xf[p][4 + e] = __uint_as_float(xraw2[p][e]);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) xf[p][2 * e] = h2f((uint16_t)(xraw[p][e] & 0xFFFFu)), xf[p][2 * e + 1] = h2f((uint16_t)(xraw[p][e] >> 16));
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                xf[p][e] = on ? xf[p][e] : 0.0f;
+                ss += xf[p][e] * xf[p][e];
+            }
+        }
+        ss = wave_sum(ss);
+        if (lane == 0) red[wave] = ss;
+        wg_barrier();
+        float tot = 0.0f;
+#pragma unroll
+        for (int w = 0; w < kRWaves; ++w) tot += red[w];
+        inv = 1.0f / sqrtf(tot / (float)k + a.eps);
+    }
+#pragma unroll
+    for (int p = 0; p < NG; ++p) {
+        u32x4_t o;
+        if (XMODE != X_F16) {
+            uint16_t y[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const uint32_t ww = wnr[p][e >> 1];
+                y[e] = f2h(xf[p][e] * inv * h2f((uint16_t)((e & 1) ? (ww >> 16) : (ww & 0xFFFFu))));
+            }
+            o.x = (uint32_t)y[0] | ((uint32_t)y[4] << 16), o.y = (uint32_t)y[1] | ((uint32_t)y[5] << 16);
+            o.z = (uint32_t)y[2] | ((uint32_t)y[6] << 16), o.w = (uint32_t)y[3] | ((uint32_t)y[7] << 16);
+        } else {
+            const bool on = (p * kRThreads + tid) < kw;
+            const u32x4_t r = xraw[p];
+            o.x = __builtin_amdgcn_perm(r.z, r.x, 0x05040100u), o.y = __builtin_amdgcn_perm(r.z, r.x, 0x07060302u);
+            o.z = __builtin_amdgcn_perm(r.w, r.y, 0x05040100u), o.w = __builtin_amdgcn_perm(r.w, r.y, 0x07060302u);
+            if (!on) o = u32x4_t{0u, 0u, 0u, 0u};
+        }
+        *(u32x4_t *)(xs + (((p * 4 + (tid & 3)) << 6) + (tid >> 2)) * 8) = o;
+    }
+    wg_barrier();
+    // the lane's share of x: group c * 64 + lane of every chunk, and the offset term of each group
+    u32x4_t xv[NG][4];
+    float cr[NG];
+#pragma unroll
+    for (int c = 0; c < NG; ++c) {
+        float sa = 0.0f, sb = 0.0f;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            xv[c][j] = *(const u32x4_t *)(xs + (((c * 4 + j) << 6) + lane) * 8);
+            sa = dot2(xv[c][j].x, 0x3C003C00u, sa), sb = dot2(xv[c][j].y, 0x3C003C00u, sb);
+            sa = dot2(xv[c][j].z, 0x3C003C00u, sa), sb = dot2(xv[c][j].w, 0x3C003C00u, sb);
+        }
+        cr[c] = 1032.0f * sa + 72.0f * sb;
+    }
+    const bool last_on = (NG - 1) * 64 + lane < G;                 // lanes past the last group of the row
+    stamp(2);
+
+    // ---- the stream ------------------------------------------------------------------------------------------
+    auto consume = [&](const Slot &s, int j0) {
+        float acc[R];
+#pragma unroll
+        for (int rr = 0; rr < R; ++rr) acc[rr] = 0.0f;
+#pragma unroll
+        for (int c = 0; c < NG; ++c)
+#pragma unroll
+            for (int rr = 0; rr < R; ++rr) {
+                float scv = h2f(s.sc[rr * NG + c]);
+                if (c == NG - 1) scv = last_on ? scv : 0.0f;
+                acc[rr] += scv * group_dot_r(s.w[rr * NG + c], xv[c], cr[c]);
+            }
+        if (R == 4) {
+            const float r = reduce4(acc[0], acc[1], acc[R > 2 ? 2 : 0], acc[R > 2 ? 3 : 0], lane);
+            if (lane < 4) res[j0 * 2 + lane] = r;
+        } else {
+            const float r = reduce2(acc[0], acc[1], lane);
+            if (lane < 2) res[j0 * 2 + lane] = r;
+        }
+    };
+    // Slots of the wavefront: ns = 2 q + r.  Every path below is straight-line in its loads -- none sits under a
+    // condition that merges back -- so the wait before a consume counts exactly the loads requested after its slot,
+    // and nothing is requested past the end (a wavefront does not retire before its loads have returned).
+    const int ns = (mine + UPS - 1) / UPS, q = ns >> 1;
+    int s = 0;
+#pragma unroll 1
+    for (; s + 2 < 2 * q; s += 2) {                                // refills s + 2, s + 3 <= 2 q - 1 exist
+        consume(sl[0], s * UPS);
+        slot_load(sl[0], (s + 2) * UPS);
+        consume(sl[1], (s + 1) * UPS);
+        slot_load(sl[1], (s + 3) * UPS);
+    }
+    if (q > 0) {
+        if (ns & 1) {
+            consume(sl[0], s * UPS);
+            slot_load(sl[0], (s + 2) * UPS);
+            consume(sl[1], (s + 1) * UPS);
+            consume(sl[0], (s + 2) * UPS);
+        } else {
+            consume(sl[0], s * UPS);
+            consume(sl[1], (s + 1) * UPS);
+        }
+    } else if (ns == 1) {
+        consume(sl[0], 0);
+    }
+
+    stamp(3);
+    // ---- epilogue: lane jj finishes the wavefront's unit jj ----------------------------------------------------
+    if (lane < mine) epi_store<EPI>(a, i, ri, wg + lane * W, res[lane * 2], res[lane * 2 + 1], pre);
+    stamp(4);
+}
+
+template <int XMODE, int EPI, int NG>
+hipError_t launch_ng(const GemvArgs &a, hipStream_t stream)
+{
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v < 1) v = 256;
+        cus = v;
+    }
+    const int U = (EPI == EPI_SWIGLU || EPI == EPI_ROPE_KV) ? a.m / 2 : (a.m + 1) / 2;
+    // one workgroup per CU, shared between the rows of x; never fewer than what keeps a wavefront within kRMaxUnits
+    int gx = std::max(1, cus / std::min(a.n, 8));
+    gx = std::min(gx, (U + kRWaves - 1) / kRWaves);
+    gx = std::max(gx, (U + kRWaves * kRMaxUnits - 1) / (kRWaves * kRMaxUnits));
+    hipLaunchKernelGGL((gemv_q4_reg_kernel<XMODE, EPI, NG>), dim3(gx, a.n), dim3(kRThreads), 0, stream, a);
+    return hipGetLastError();
+}
+
+template <int XMODE, int EPI>
+hipError_t launch_xe(const GemvArgs &a, hipStream_t stream)
+{
+    const int ng = (a.k + 2047) / 2048;
+    if (ng <= 1) return launch_ng<XMODE, EPI, 1>(a, stream);
+    if (ng == 2) return launch_ng<XMODE, EPI, 2>(a, stream);
+    if (ng <= 4) return launch_ng<XMODE, EPI, 4>(a, stream);
+    return launch_ng<XMODE, EPI, 6>(a, stream);
+}
+
+}  // namespace
+
+// rows of 16-byte packets, whole groups, at most 6 chunks of 2048 columns (the x registers of a lane)
+bool gemv_reg_eligible(const GemvArgs &a)
+{
+    const int k = a.k;
+    return k >= 32 && k <= 6 * 2048 && (k % kGroup == 0) && ((reinterpret_cast<uintptr_t>(a.q) & 15) == 0) &&
+           ((reinterpret_cast<uintptr_t>(a.x) & 15) == 0) && ((reinterpret_cast<uintptr_t>(a.norm_w) & 15) == 0) && a.m >= 2;
+}
+
+hipError_t launch_gemv_reg(const GemvArgs &a, int xmode, int epi, hipStream_t stream)
+{
+    if (xmode == X_F16 && epi == EPI_F16) return launch_xe<X_F16, EPI_F16>(a, stream);
+    if (xmode == X_F16_NORM && epi == EPI_ROPE_KV) return launch_xe<X_F16_NORM, EPI_ROPE_KV>(a, stream);
+    if (xmode == X_F16 && epi == EPI_RESID_F32) return launch_xe<X_F16, EPI_RESID_F32>(a, stream);
+    if (xmode == X_F32_NORM && epi == EPI_SWIGLU) return launch_xe<X_F32_NORM, EPI_SWIGLU>(a, stream);
+    if (xmode == X_F16 && epi == EPI_RESID_F16) return launch_xe<X_F16, EPI_RESID_F16>(a, stream);
+    return hipErrorInvalidValue;
+}
+
+}  // namespace relax

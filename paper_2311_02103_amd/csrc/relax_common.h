@@ -106,6 +106,9 @@ struct GemvArgs {
 };
 
 hipError_t launch_gemv(const GemvArgs &a, int xmode, int epi, hipStream_t stream);
+// x-in-registers variant for rows of up to 6 x 2048 columns (gemv_q4_reg.hip); launch_gemv picks it when eligible
+bool gemv_reg_eligible(const GemvArgs &a);
+hipError_t launch_gemv_reg(const GemvArgs &a, int xmode, int epi, hipStream_t stream);
 
 hipError_t launch_rmsnorm(const uint16_t *x, const uint16_t *w, uint16_t *y, int n, int H, float eps, hipStream_t stream);
 hipError_t launch_rmsnorm_f32(const float *x, const uint16_t *w, uint16_t *y, int n, int H, float eps, hipStream_t stream);
