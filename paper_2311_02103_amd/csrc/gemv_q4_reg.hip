@@ -105,19 +105,20 @@ __device__ __forceinline__ void unit_rows_r(const GemvArgs &a, int u, int &ra, i
     if (EPI == EPI_SWIGLU) {
         ra = u, rb = u + a.m / 2;
     } else if (EPI == EPI_ROPE_KV) {
+        // branch-free: the weight loads that follow must not sit under a condition (their count has to be static)
         const int hd2 = a.d >> 1, nqk = (a.h + a.g) * hd2;
-        if (u < nqk) {
-            const int j = u / hd2, t = u - j * hd2;
-            ra = j * a.d + t, rb = ra + hd2;
-        } else {
-            ra = (a.h + a.g) * a.d + 2 * (u - nqk), rb = ra + 1;
-        }
+        const int uq = min(u, nqk - 1), j = uq / hd2, t = uq - j * hd2;
+        const int rq = j * a.d + t, rv = (a.h + a.g) * a.d + 2 * (u - nqk);
+        ra = u < nqk ? rq : rv;
+        rb = u < nqk ? rq + hd2 : rv + 1;
     } else {
         ra = 2 * u, rb = min(2 * u + 1, a.m - 1);
     }
 }
 
-// what the epilogue of unit u reads besides the two sums: fetched before the weight stream starts
+// what the epilogue of unit u reads besides the two sums, as raw bits: requested before the weight stream starts and
+// not touched until the end (any use, even a conversion, would make the wavefront wait for it on the spot).  Every
+// lane requests something valid -- no load under a condition, the count of requests in flight stays static.
 template <int EPI>
 __device__ __forceinline__ float2 epi_fetch(const GemvArgs &a, int i, const RowInfo &ri, int u)
 {
@@ -127,13 +128,14 @@ __device__ __forceinline__ float2 epi_fetch(const GemvArgs &a, int i, const RowI
     const size_t base = (size_t)i * a.m;
     if (EPI == EPI_RESID_F32) {
         const uint16_t *xr = (const uint16_t *)a.resid;
-        pre = make_float2(h2f(xr[base + ra]), h2f(xr[base + rb]));
+        pre = make_float2(__uint_as_float((uint32_t)xr[base + ra]), __uint_as_float((uint32_t)xr[base + rb]));
     } else if (EPI == EPI_RESID_F16) {
         const float *xr = (const float *)a.resid;
         pre = make_float2(xr[base + ra], xr[base + rb]);
     } else if (EPI == EPI_ROPE_KV) {
         const int hd2 = a.d >> 1, nqk = (a.h + a.g) * hd2;
-        if (u < nqk) pre = *(const float2 *)(a.rope + ((size_t)ri.pos * hd2 + (u % hd2)) * 2);     // cos, sin
+        const int t = u < nqk ? u % hd2 : 0;
+        pre = *(const float2 *)(a.rope + ((size_t)ri.pos * hd2 + t) * 2);                          // cos, sin
     }
     return pre;
 }
@@ -148,8 +150,8 @@ __device__ __forceinline__ void epi_store(const GemvArgs &a, int i, const RowInf
         a.out_f16[base + ra] = f2h(va);
         if (2 * u + 1 < a.m) a.out_f16[base + rb] = f2h(vb);
     } else if (EPI == EPI_RESID_F32) {
-        a.out_f32[base + ra] = pre.x + va;
-        if (2 * u + 1 < a.m) a.out_f32[base + rb] = pre.y + vb;
+        a.out_f32[base + ra] = h2f((uint16_t)__float_as_uint(pre.x)) + va;
+        if (2 * u + 1 < a.m) a.out_f32[base + rb] = h2f((uint16_t)__float_as_uint(pre.y)) + vb;
     } else if (EPI == EPI_RESID_F16) {
         a.out_f16[base + ra] = f2h(pre.x + va);
         if (2 * u + 1 < a.m) a.out_f16[base + rb] = f2h(pre.y + vb);
@@ -192,16 +194,21 @@ __global__ __launch_bounds__(kRThreads) void gemv_q4_reg_kernel(GemvArgs a)
     const int W = gridDim.x * kRWaves, wg = blockIdx.x * kRWaves + wave;
     const int mine = wg < U ? (U - wg + W - 1) / W : 0;        // <= kRMaxUnits: the launcher sizes the grid for it
     float *res = res_all[wave];
-    auto stamp = [&](int st) {                                 // optional measurement aid: wall-clock stamps of a workgroup
+    // Measurement aid, compiled in only on request: wall-clock stamps of a workgroup.  A store under a condition
+    // between the requests and their waits makes every later wait a wait for all requests in flight.
+    auto stamp = [&](int st) {
+#ifdef RELAX_GEMV_TRACE
         if (a.trace && tid == 0 && blockIdx.y == 0) a.trace[blockIdx.x * 8 + st] = wall_clock64();
+#else
+        (void)st;
+#endif
     };
     stamp(0);
 
     // ---- what the epilogue reads, then the x row, then the first slots: requested in the order they are needed ----
     RowInfo ri = {0, 0, 0};
     if (EPI == EPI_ROPE_KV) ri = row_info(a.seqs, i);
-    float2 pre = make_float2(0.0f, 0.0f);
-    if (lane < mine) pre = epi_fetch<EPI>(a, i, ri, wg + lane * W);
+    const float2 pre = epi_fetch<EPI>(a, i, ri, min(wg + lane * W, U - 1));
 
     // pass p of the staging covers chunk p of 2048 columns: thread t holds word t & 3 of group 64 p + (t >> 2)
     const size_t xbase = (size_t)i * k;
@@ -235,6 +242,7 @@ __global__ __launch_bounds__(kRThreads) void gemv_q4_reg_kernel(GemvArgs a)
             unit_rows_r<EPI>(a, u, rows[0], rows[1]);
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
+                rows[h] = __builtin_amdgcn_readfirstlane(rows[h]);     // uniform: row bases in scalar registers
                 const uint32_t *qrow = a.q + (size_t)rows[h] * kw;
                 const uint16_t *srow = a.s + (size_t)rows[h] * G;
 #pragma unroll

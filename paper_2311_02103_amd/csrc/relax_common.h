@@ -46,13 +46,21 @@ __device__ inline RowInfo row_info(const SeqTable &st, int32_t row)
         r.pos = kl[b] - ql[b] + (row - qs[b]);
         r.slot = sl[b];
     } else {
-        int b = 0;
+        // static indices only: a dynamic index into the by-value table would go through a flat load of the kernel
+        // arguments, and a flat load in flight turns every later wait of the kernel into a wait for all loads
+        int b = 0, qs = st.q_start[0], ql = st.q_len[0], kl = st.kv_len[0], sl = st.slot[0];
 #pragma unroll
-        for (int j = 0; j < kInlineSeqs - 1; ++j)
-            if (j + 1 < st.B && row >= st.q_start[j] + st.q_len[j]) b = j + 1;
+        for (int j = 0; j < kInlineSeqs - 1; ++j) {
+            const bool adv = j + 1 < st.B && row >= st.q_start[j] + st.q_len[j];
+            b = adv ? j + 1 : b;
+            qs = adv ? st.q_start[j + 1] : qs;
+            ql = adv ? st.q_len[j + 1] : ql;
+            kl = adv ? st.kv_len[j + 1] : kl;
+            sl = adv ? st.slot[j + 1] : sl;
+        }
         r.seq = b;
-        r.pos = st.kv_len[b] - st.q_len[b] + (row - st.q_start[b]);
-        r.slot = st.slot[b];
+        r.pos = kl - ql + (row - qs);
+        r.slot = sl;
     }
     return r;
 }
