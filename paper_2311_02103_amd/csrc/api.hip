@@ -439,6 +439,8 @@ relax_status layer_enqueue(const relax_layer_dims &dm, const relax_layer_weights
     a.q = wt->wqkv.q, a.s = wt->wqkv.s, a.m = wt->wqkv.m, a.k = wt->wqkv.k, a.n = n;
     a.out_f16 = qbuf, a.kcache = cache->k, a.vcache = cache->v, a.rope = cache->rope;
     a.h = dm.n_heads, a.g = dm.n_kv_heads, a.d = dm.head_dim, a.kv_capacity = dm.kv_capacity, a.seqs = st;
+    a.trace = g_trace;
+    if (n == 1 && st.dev == nullptr) a.pos0 = st.kv_len[0] - st.q_len[0] - st.q_start[0], a.slot0 = st.slot[0];
     timer.before(0);
     if (launch_gemv(a, X_F16_NORM, EPI_ROPE_KV, st_) != hipSuccess) return RELAX_ERR_HIP;
     timer.after(0);
@@ -451,7 +453,7 @@ relax_status layer_enqueue(const relax_layer_dims &dm, const relax_layer_weights
     // 3. output projection + residual: x1 = x + attn Wo^T (fp32 residual stream in the workspace)
     GemvArgs o = {};
     o.x = attn, o.q = wt->wo.q, o.s = wt->wo.s, o.m = wt->wo.m, o.k = wt->wo.k, o.n = n;
-    o.out_f32 = x1, o.resid = x;
+    o.out_f32 = x1, o.resid = x, o.trace = g_trace;
     timer.before(2);
     if (launch_gemv(o, X_F16, EPI_RESID_F32, st_) != hipSuccess) return RELAX_ERR_HIP;
     timer.after(2);
@@ -460,7 +462,7 @@ relax_status layer_enqueue(const relax_layer_dims &dm, const relax_layer_weights
     GemvArgs f = {};
     f.x = x1, f.norm_w = wt->norm_ffn, f.eps = dm.rms_eps;
     f.q = wt->wgu.q, f.s = wt->wgu.s, f.m = wt->wgu.m, f.k = wt->wgu.k, f.n = n;
-    f.out_f16 = act;
+    f.out_f16 = act, f.trace = g_trace;
     timer.before(3);
     if (launch_gemv(f, X_F32_NORM, EPI_SWIGLU, st_) != hipSuccess) return RELAX_ERR_HIP;
     timer.after(3);
@@ -468,7 +470,7 @@ relax_status layer_enqueue(const relax_layer_dims &dm, const relax_layer_weights
     // 5. down projection + residual
     GemvArgs dn = {};
     dn.x = act, dn.q = wt->wdown.q, dn.s = wt->wdown.s, dn.m = wt->wdown.m, dn.k = wt->wdown.k, dn.n = n;
-    dn.out_f16 = out, dn.resid = x1;
+    dn.out_f16 = out, dn.resid = x1, dn.trace = g_trace;
     timer.before(4);
     if (launch_gemv(dn, X_F16, EPI_RESID_F16, st_) != hipSuccess) return RELAX_ERR_HIP;
     timer.after(4);

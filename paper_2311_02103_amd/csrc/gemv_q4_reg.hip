@@ -92,6 +92,14 @@ __device__ __forceinline__ float reduce2(float v0, float v1, int lane)
     return r;
 }
 
+// u / hd2 for the rotary row mapping: a shift when half the head dimension is a power of two (the branch is uniform
+// and holds no load)
+__device__ __forceinline__ int div_half_dim(int u, int hd2)
+{
+    if ((hd2 & (hd2 - 1)) == 0) return u >> (31 - __builtin_clz(hd2));
+    return u / hd2;
+}
+
 template <int EPI>
 __device__ __forceinline__ int unit_count_r(const GemvArgs &a)
 {
@@ -107,7 +115,7 @@ __device__ __forceinline__ void unit_rows_r(const GemvArgs &a, int u, int &ra, i
     } else if (EPI == EPI_ROPE_KV) {
         // branch-free: the weight loads that follow must not sit under a condition (their count has to be static)
         const int hd2 = a.d >> 1, nqk = (a.h + a.g) * hd2;
-        const int uq = min(u, nqk - 1), j = uq / hd2, t = uq - j * hd2;
+        const int uq = min(u, nqk - 1), j = div_half_dim(uq, hd2), t = uq - j * hd2;
         const int rq = j * a.d + t, rv = (a.h + a.g) * a.d + 2 * (u - nqk);
         ra = u < nqk ? rq : rv;
         rb = u < nqk ? rq + hd2 : rv + 1;
@@ -134,7 +142,7 @@ __device__ __forceinline__ float2 epi_fetch(const GemvArgs &a, int i, const RowI
         pre = make_float2(xr[base + ra], xr[base + rb]);
     } else if (EPI == EPI_ROPE_KV) {
         const int hd2 = a.d >> 1, nqk = (a.h + a.g) * hd2;
-        const int t = u < nqk ? u % hd2 : 0;
+        const int t = u < nqk ? u - div_half_dim(u, hd2) * hd2 : 0;
         pre = *(const float2 *)(a.rope + ((size_t)ri.pos * hd2 + t) * 2);                          // cos, sin
     }
     return pre;
@@ -161,7 +169,7 @@ __device__ __forceinline__ void epi_store(const GemvArgs &a, int i, const RowInf
         const int hd2 = a.d >> 1, nqk = (a.h + a.g) * hd2;
         const size_t tok = ((size_t)ri.slot * a.kv_capacity + ri.pos) * (size_t)(a.g * a.d);
         if (u < nqk) {
-            const int j = u / hd2, t = u - j * hd2;
+            const int j = div_half_dim(u, hd2), t = u - j * hd2;
             const float oa = va * pre.x - vb * pre.y, ob = va * pre.y + vb * pre.x;
             uint16_t *dst = (j < a.h) ? a.out_f16 + (size_t)i * (a.h * a.d) + (size_t)j * a.d + t
                                       : a.kcache + tok + (size_t)(j - a.h) * a.d + t;
@@ -198,7 +206,7 @@ __global__ __launch_bounds__(kRThreads) void gemv_q4_reg_kernel(GemvArgs a)
     // between the requests and their waits makes every later wait a wait for all requests in flight.
     auto stamp = [&](int st) {
 #ifdef RELAX_GEMV_TRACE
-        if (a.trace && tid == 0 && blockIdx.y == 0) a.trace[blockIdx.x * 8 + st] = wall_clock64();
+        if (a.trace && tid == 0 && blockIdx.y == 0) a.trace[(EPI * 1024 + blockIdx.x) * 8 + st] = wall_clock64();
 #else
         (void)st;
 #endif
@@ -207,8 +215,10 @@ __global__ __launch_bounds__(kRThreads) void gemv_q4_reg_kernel(GemvArgs a)
 
     // ---- what the epilogue reads, then the x row, then the first slots: requested in the order they are needed ----
     RowInfo ri = {0, 0, 0};
-    if (EPI == EPI_ROPE_KV) ri = row_info(a.seqs, i);
-    const float2 pre = epi_fetch<EPI>(a, i, ri, min(wg + lane * W, U - 1));
+    if (EPI == EPI_ROPE_KV) {
+        if (a.n == 1) ri.pos = a.pos0, ri.slot = a.slot0;          // the host resolved the only row: no table walk up front
+        else ri = row_info(a.seqs, i);
+    }
 
     // pass p of the staging covers chunk p of 2048 columns: thread t holds word t & 3 of group 64 p + (t >> 2)
     const size_t xbase = (size_t)i * k;
@@ -258,6 +268,9 @@ __global__ __launch_bounds__(kRThreads) void gemv_q4_reg_kernel(GemvArgs a)
     Slot sl[NSLOT];
 #pragma unroll
     for (int t = 0; t < NSLOT; ++t) slot_load(sl[t], t * UPS);
+    // behind the first slots in program order: its address arithmetic runs while they are in flight
+    const float2 pre = epi_fetch<EPI>(a, i, ri, min(wg + lane * W, U - 1));
+    __builtin_amdgcn_sched_barrier(0);
     stamp(1);
 
     // ---- stage the (optionally RMS-normalised) x row in LDS as fp16, packet order [x0 x4 x1 x5 x2 x6 x3 x7] ----

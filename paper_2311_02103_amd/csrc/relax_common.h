@@ -110,6 +110,7 @@ struct GemvArgs {
     const float *rope;
     int32_t h, g, d, kv_capacity;
     SeqTable seqs;
+    int32_t pos0, slot0;             // position and cache slot of row 0, resolved on the host (what a one-row call needs of seqs)
     unsigned long long *trace;       // optional measurement aid: [workgroup][8] wall-clock stamps
 };
 
