@@ -160,35 +160,213 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const uint16_t *__restr
     }
 }
 
+// ---- split kernel for one query head per KV head (multi-head attention) -----------------------------------------------
+//
+// Same work split and partial format as attn_split_kernel, built for the memory system: a wavefront step is 4 K loads
+// and 4 V loads of 16 bytes per lane (TS tokens), two steps are in flight, and the first two are requested before
+// anything else, so at the usual chunk sizes (a wavefront owns two to eight steps) most of the chunk is already on its
+// way when the first score is computed.  q . k runs on packed fp16 pairs with v_dot2_f32_f16 (exact products, fp32
+// sums) and is reduced over the lanes of a token with DPP row operations; the softmax state advances once per step
+// (one rescale for TS tokens instead of one per token).  The step schedule is straight-line in its loads (no load
+// under a condition that merges back), so a wait counts exactly the loads requested after the step it needs.
+typedef uint32_t u32x4a_t __attribute__((ext_vector_type(4)));
+typedef _Float16 half2a_t __attribute__((ext_vector_type(2)));
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
+}
+
+template <int D>
+__global__ __launch_bounds__(256) void attn_mha_split_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict__ kc,
+                                                             const uint16_t *__restrict__ vc, float *__restrict__ part, SeqTable st,
+                                                             int h, int cap, int chunk, int splits, int q_stride)
+{
+    constexpr int LPT = D / 8;        // lanes that share one token (each owns 8 of its d elements)
+    constexpr int TPW = kWave / LPT;  // tokens per load instruction of a wavefront
+    constexpr int NL = 4;             // K (and V) loads per step
+    constexpr int TS = NL * TPW;      // tokens per wavefront step
+    __shared__ float sm[4 * (D + 2)];
+
+    const int i = blockIdx.z, split = blockIdx.y, head = blockIdx.x;
+    const RowInfo ri = row_info(st, i);
+    const int L = ri.pos + 1;
+    const int t_begin = split * chunk;
+    if (t_begin >= L) return;                                  // uniform for the workgroup
+    const int t_end = min(L, t_begin + chunk);
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int sub = lane / LPT, e0 = (lane % LPT) * 8;
+    const float inv_sqrt_d = 1.0f / sqrtf((float)D);
+
+    // step s of this wavefront covers tokens t_begin + (4 s + wave) TS .. + TS - 1
+    const int first = t_begin + wave * TS;
+    const int ns = first < t_end ? (t_end - first + 4 * TS - 1) / (4 * TS) : 0;
+    const size_t row_stride = (size_t)h * D;                   // one token of the cache, all heads
+    const uint16_t *kbase = kc + ((size_t)ri.slot * cap) * row_stride + (size_t)head * D + e0;
+    const uint16_t *vbase = vc + ((size_t)ri.slot * cap) * row_stride + (size_t)head * D + e0;
+
+    struct Step {
+        u32x4a_t k[NL], v[NL];
+    };
+    auto step_load = [&](Step &sp, int s) {
+        __builtin_amdgcn_sched_barrier(0);
+        const int t0 = first + s * 4 * TS + sub;
+#pragma unroll
+        for (int j = 0; j < NL; ++j) {
+            const size_t at = (size_t)min(t0 + j * TPW, t_end - 1) * row_stride;    // tokens past the end re-read the last one, masked below
+            sp.k[j] = *(const u32x4a_t *)(kbase + at);
+            sp.v[j] = *(const u32x4a_t *)(vbase + at);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    Step sa, sb;
+    step_load(sa, 0);
+    step_load(sb, 1);
+    const u32x4a_t qv = *(const u32x4a_t *)(q + (size_t)i * q_stride + (size_t)head * D + e0);
+
+    float acc[8], m = -INFINITY, l = 0.0f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = 0.0f;
+
+    auto consume = [&](const Step &sp, int s) {
+        const int t0 = first + s * 4 * TS + sub;
+        float sc[NL];
+        float mx = m;
+#pragma unroll
+        for (int j = 0; j < NL; ++j) {
+            float dot = 0.0f;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                const uint32_t kw = sp.k[j][w], qw = qv[w];    // element copies: a bit_cast applied to the subscript itself reads word 0
+                dot = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2a_t, kw), __builtin_bit_cast(half2a_t, qw), dot, false);
+            }
+            dot += dpp_f<0xB1>(dot);                           // lane ^ 1
+            dot += dpp_f<0x4E>(dot);                           // lane ^ 2
+            if (LPT == 16) {
+                dot += dpp_f<0x124>(dot);                      // rotate the row of 16 by 4, then by 8
+                dot += dpp_f<0x128>(dot);
+            } else {
+                dot += dpp_f<0x141>(dot);                      // mirror within the half row of 8
+            }
+            sc[j] = (t0 + j * TPW < t_end) ? dot * inv_sqrt_d : -INFINITY;
+            mx = fmaxf(mx, sc[j]);
+        }
+        const float mref = (mx == -INFINITY) ? 0.0f : mx;      // nothing valid yet: every weight below is exp(-inf) = 0
+        const float ca = __expf(m - mref);
+        float p[NL], psum = 0.0f;
+#pragma unroll
+        for (int j = 0; j < NL; ++j) {
+            p[j] = __expf(sc[j] - mref);
+            psum += p[j];
+        }
+        l = l * ca + psum;
+        m = mx;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] *= ca;
+#pragma unroll
+        for (int j = 0; j < NL; ++j)
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                const uint32_t vw = sp.v[j][w];
+                const half2a_t vv = __builtin_bit_cast(half2a_t, vw);
+                acc[2 * w] += p[j] * (float)vv.x;
+                acc[2 * w + 1] += p[j] * (float)vv.y;
+            }
+    };
+
+    const int nq = ns >> 1;
+    int s = 0;
+#pragma unroll 1
+    for (; s + 2 < 2 * nq; s += 2) {
+        consume(sa, s);
+        step_load(sa, s + 2);
+        consume(sb, s + 1);
+        step_load(sb, s + 3);
+    }
+    if (nq > 0) {
+        if (ns & 1) {
+            consume(sa, s);
+            step_load(sa, s + 2);
+            consume(sb, s + 1);
+            consume(sa, s + 2);
+        } else {
+            consume(sa, s);
+            consume(sb, s + 1);
+        }
+    } else if (ns == 1) {
+        consume(sa, 0);
+    }
+
+    // merge the TPW token groups of the wavefront (lanes that own the same 8 elements)
+#pragma unroll
+    for (int off = LPT; off < kWave; off <<= 1) {
+        float mb = __shfl_xor(m, off, kWave), lb = __shfl_xor(l, off, kWave), accb[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) accb[e] = __shfl_xor(acc[e], off, kWave);
+        merge_state(m, l, acc, mb, lb, accb);
+    }
+    if (lane < LPT) {
+        float *dst = sm + wave * (D + 2);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) dst[e0 + e] = acc[e];
+        if (lane == 0) dst[D] = m, dst[D + 1] = l;
+    }
+    __syncthreads();
+    // merge the four wavefronts and write the partial of (row, head, split)
+    if (tid < D) {
+        const int e = tid;
+        float mm = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) mm = fmaxf(mm, sm[w * (D + 2) + D]);
+        float num = 0.0f, den = 0.0f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const float *src = sm + w * (D + 2);
+            const float scw = (src[D] == -INFINITY) ? 0.0f : __expf(src[D] - mm);
+            num += src[e] * scw;
+            den += src[D + 1] * scw;
+        }
+        float *dst = part + (((size_t)i * h + head) * splits + split) * (D + 2);
+        dst[e] = num;
+        if (e == 0) dst[D] = mm, dst[D + 1] = den;
+    }
+}
+
 // one workgroup of D threads per (row, head): out = sum_s acc_s e^(m_s - M) / sum_s l_s e^(m_s - M).
-// The per-split scales are computed once (thread s owns split s) and shared through LDS; the accumulator loads of
-// a thread are independent of each other, so they are all in flight together.
+// No LDS and no barrier: a thread reads the (m, l) pair of every split itself (the same address for the whole
+// workgroup: one transaction) next to its own accumulator element, 16 splits per round with all loads of a round in
+// flight together, and folds a round in with the usual max-rescaling.
 template <int D>
 __global__ void attn_merge_kernel(const float *__restrict__ part, uint16_t *__restrict__ out, SeqTable st, int h, int chunk,
                                   int splits)
 {
-    extern __shared__ float scale[];                           // [splits] e^(m_s - M), then [1] 1 / denominator
+    constexpr int RS = 16;
     const int i = blockIdx.x / h, e = threadIdx.x;
     const RowInfo ri = row_info(st, i);
     const int used = (ri.pos + chunk) / chunk;                 // ceil((pos+1)/chunk)
     const float *src = part + (size_t)blockIdx.x * splits * (D + 2);
-    for (int s = e; s < used; s += D) scale[s] = src[s * (D + 2) + D];
-    __syncthreads();
-    float mm = -INFINITY;
-    for (int s = 0; s < used; ++s) mm = fmaxf(mm, scale[s]);
-    __syncthreads();
-    for (int s = e; s < used; s += D) scale[s] = __expf(scale[s] - mm);
-    __syncthreads();
-    float num = 0.0f, den = 0.0f;
-    int s = 0;
-    for (; s + 8 <= used; s += 8) {
-        float a8[8], l8[8];
+    float mm = -INFINITY, num = 0.0f, den = 0.0f;
+    for (int s0 = 0; s0 < used; s0 += RS) {
+        float ms[RS], ls[RS], as[RS];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) a8[j] = src[(s + j) * (D + 2) + e], l8[j] = src[(s + j) * (D + 2) + D + 1];
+        for (int j = 0; j < RS; ++j) {
+            const float *p = src + (size_t)min(s0 + j, used - 1) * (D + 2);
+            ms[j] = p[D], ls[j] = p[D + 1], as[j] = p[e];
+        }
+        float mx = mm;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) num += a8[j] * scale[s + j], den += l8[j] * scale[s + j];
+        for (int j = 0; j < RS; ++j) mx = (s0 + j < used) ? fmaxf(mx, ms[j]) : mx;
+        const float mref = (mx == -INFINITY) ? 0.0f : mx;
+        const float c0 = __expf(mm - mref);
+        num *= c0, den *= c0;
+#pragma unroll
+        for (int j = 0; j < RS; ++j) {
+            const float w = (s0 + j < used) ? __expf(ms[j] - mref) : 0.0f;
+            num += as[j] * w, den += ls[j] * w;
+        }
+        mm = mx;
     }
-    for (; s < used; ++s) num += src[s * (D + 2) + e] * scale[s], den += src[s * (D + 2) + D + 1] * scale[s];
     out[(size_t)blockIdx.x * D + e] = f2h(num / den);
 }
 
@@ -210,12 +388,17 @@ static hipError_t launch_d(const uint16_t *q, int q_stride, const relax_kv_cache
     const int rep = dm.n_heads / dm.n_kv_heads;
     hipError_t e;
     if (attn_gqa_supported(dm)) e = launch_attention_gqa_split(q, q_stride, cache, dm, st, pl, partials, stream);   // MFMA kernel for grouped heads
+    else if (rep == 1) {
+        hipLaunchKernelGGL((attn_mha_split_kernel<D>), dim3(dm.n_heads, pl.splits, st.n), dim3(256), 0, stream, q, cache.k, cache.v, partials, st,
+                           dm.n_heads, dm.kv_capacity, pl.chunk, pl.splits, q_stride);
+        e = hipGetLastError();
+    }
     else if (rep % 8 == 0) e = launch_split<D, 8>(q, q_stride, cache, dm, st, pl, partials, stream);
     else if (rep % 4 == 0) e = launch_split<D, 4>(q, q_stride, cache, dm, st, pl, partials, stream);
     else if (rep % 2 == 0) e = launch_split<D, 2>(q, q_stride, cache, dm, st, pl, partials, stream);
     else e = launch_split<D, 1>(q, q_stride, cache, dm, st, pl, partials, stream);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((attn_merge_kernel<D>), dim3(st.n * dm.n_heads), dim3(D), sizeof(float) * (size_t)pl.splits, stream, partials, out, st, dm.n_heads,
+    hipLaunchKernelGGL((attn_merge_kernel<D>), dim3(st.n * dm.n_heads), dim3(D), 0, stream, partials, out, st, dm.n_heads,
                        pl.chunk, pl.splits);
     return hipGetLastError();
 }
