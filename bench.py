@@ -147,7 +147,7 @@ def bench_decode_layer(args, np, torch, wl, rx):
                     "algorithmic_bytes_per_launch": int(layer_bytes), "avg_launch_ms": round(ms, 5)}
     elif "gate_up" in kernel_ms:
         ach = gu_bytes / (kernel_ms["gate_up"] * 1e-3) / 1e9
-        roofline = {"bound": "hbm", "kernel": "gemv_q4_stream_kernel<X_F32_NORM, EPI_SWIGLU> (gate/up matvec, m=22016, k=4096: "
+        roofline = {"bound": "hbm", "kernel": "gemv_q4_reg_kernel<X_F32_NORM, EPI_SWIGLU, 2> (gate/up matvec, m=22016, k=4096: "
                                                 "RMSNorm prologue, SwiGLU epilogue)",
                     "achieved": round(ach, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(ach / PEAK_HBM_GBS, 4),
                     "traffic": traffic_from_profile("traffic_gate_up_matvec_7b.json"), "algorithmic_bytes_per_launch": gu_bytes,
@@ -356,7 +356,7 @@ def bench_model(args, np, torch, wl, rx, big):
     gu_bytes = m * (k // 2) + m * (k // 32) * 2
     ach = gu_bytes / (kernel_ms["gate_up"] * 1e-3) / 1e9
     kernel = ("skinny_q4_kernel<1,16> + skinny_finish_kernel<EPI_SWIGLU> (gate/up, m=57344, k=8192, n=16)" if big else
-              "gemv_q4_stream_kernel<X_F32_NORM, EPI_SWIGLU> (gate/up matvec, m=22016, k=4096)")
+              "gemv_q4_reg_kernel<X_F32_NORM, EPI_SWIGLU, 2> (gate/up matvec, m=22016, k=4096)")
     roofline = {"bound": "hbm", "kernel": kernel, "achieved": round(ach, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                 "frac": round(ach / PEAK_HBM_GBS, 4),
                 "traffic": traffic_from_profile("traffic_gate_up_skinny_70b.json" if big else "traffic_gate_up_matvec_7b.json"),

@@ -445,17 +445,36 @@ relax_status layer_enqueue(const relax_layer_dims &dm, const relax_layer_weights
     if (launch_gemv(a, X_F16_NORM, EPI_ROPE_KV, st_) != hipSuccess) return RELAX_ERR_HIP;
     timer.after(0);
 
-    // 2. attention over the cache
-    timer.before(1);
-    if (launch_attention(qbuf, hd, *cache, dm, st, L_max, attn, partials, st_) != hipSuccess) return RELAX_ERR_HIP;
-    timer.after(1);
+    // 2. attention over the cache.  One row, one query head per KV head: the split kernel alone, with few enough
+    //    splits for the output projection to fold the merge into its own prologue (one launch less per layer).
+    GemvArgs o = {};
+    o.q = wt->wo.q, o.s = wt->wo.s, o.m = wt->wo.m, o.k = wt->wo.k, o.n = n;
+    o.out_f32 = x1, o.resid = x, o.trace = g_trace;
+    bool folded = false;
+    if (n == 1 && st.dev == nullptr && attn_mha_split_supported(dm)) {
+        const int pos = st.kv_len[0] - st.q_len[0] - st.q_start[0], L = pos + 1;
+        int splits = std::min(kAttnMergeSplits, (L + 63) / 64);
+        const int chunk = ((L + splits - 1) / splits + 63) / 64 * 64;
+        splits = (L + chunk - 1) / chunk;
+        o.h = dm.n_heads, o.d = dm.head_dim, o.pos0 = pos;
+        o.part = partials, o.part_splits = splits, o.part_stride = dm.head_dim + 4, o.part_chunk = chunk;
+        folded = (size_t)dm.n_heads * splits * o.part_stride <= attn_partial_floats(dm, 1, 1) && gemv_merge_eligible(o);
+        if (folded) {
+            timer.before(1);
+            if (launch_attention_mha_split(qbuf, hd, *cache, dm, st, chunk, splits, o.part_stride, partials, st_) != hipSuccess) return RELAX_ERR_HIP;
+            timer.after(1);
+        }
+    }
+    if (!folded) {
+        timer.before(1);
+        if (launch_attention(qbuf, hd, *cache, dm, st, L_max, attn, partials, st_) != hipSuccess) return RELAX_ERR_HIP;
+        timer.after(1);
+        o.x = attn;
+    }
 
     // 3. output projection + residual: x1 = x + attn Wo^T (fp32 residual stream in the workspace)
-    GemvArgs o = {};
-    o.x = attn, o.q = wt->wo.q, o.s = wt->wo.s, o.m = wt->wo.m, o.k = wt->wo.k, o.n = n;
-    o.out_f32 = x1, o.resid = x, o.trace = g_trace;
     timer.before(2);
-    if (launch_gemv(o, X_F16, EPI_RESID_F32, st_) != hipSuccess) return RELAX_ERR_HIP;
+    if (launch_gemv(o, folded ? X_ATTN_MERGE : X_F16, EPI_RESID_F32, st_) != hipSuccess) return RELAX_ERR_HIP;
     timer.after(2);
 
     // 4. RMSNorm -> gate/up matvec -> SwiGLU

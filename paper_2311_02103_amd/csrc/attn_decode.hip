@@ -181,7 +181,7 @@ __device__ __forceinline__ float dpp_f(float v)
 template <int D>
 __global__ __launch_bounds__(256) void attn_mha_split_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict__ kc,
                                                              const uint16_t *__restrict__ vc, float *__restrict__ part, SeqTable st,
-                                                             int h, int cap, int chunk, int splits, int q_stride)
+                                                             int h, int cap, int chunk, int splits, int q_stride, int ps)
 {
     constexpr int LPT = D / 8;        // lanes that share one token (each owns 8 of its d elements)
     constexpr int TPW = kWave / LPT;  // tokens per load instruction of a wavefront
@@ -327,7 +327,7 @@ __global__ __launch_bounds__(256) void attn_mha_split_kernel(const uint16_t *__r
             num += src[e] * scw;
             den += src[D + 1] * scw;
         }
-        float *dst = part + (((size_t)i * h + head) * splits + split) * (D + 2);
+        float *dst = part + (((size_t)i * h + head) * splits + split) * ps;          // ps >= D + 2 floats per partial
         dst[e] = num;
         if (e == 0) dst[D] = mm, dst[D + 1] = den;
     }
@@ -390,7 +390,7 @@ static hipError_t launch_d(const uint16_t *q, int q_stride, const relax_kv_cache
     if (attn_gqa_supported(dm)) e = launch_attention_gqa_split(q, q_stride, cache, dm, st, pl, partials, stream);   // MFMA kernel for grouped heads
     else if (rep == 1) {
         hipLaunchKernelGGL((attn_mha_split_kernel<D>), dim3(dm.n_heads, pl.splits, st.n), dim3(256), 0, stream, q, cache.k, cache.v, partials, st,
-                           dm.n_heads, dm.kv_capacity, pl.chunk, pl.splits, q_stride);
+                           dm.n_heads, dm.kv_capacity, pl.chunk, pl.splits, q_stride, D + 2);
         e = hipGetLastError();
     }
     else if (rep % 8 == 0) e = launch_split<D, 8>(q, q_stride, cache, dm, st, pl, partials, stream);
@@ -400,6 +400,26 @@ static hipError_t launch_d(const uint16_t *q, int q_stride, const relax_kv_cache
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL((attn_merge_kernel<D>), dim3(st.n * dm.n_heads), dim3(D), 0, stream, partials, out, st, dm.n_heads,
                        pl.chunk, pl.splits);
+    return hipGetLastError();
+}
+
+// split kernel alone, for a caller that folds the merge into its own prologue (one query head per KV head, decode rows):
+// partial of (row, head, split) at partials + ((row * h + head) * splits + split) * part_stride
+bool attn_mha_split_supported(const relax_layer_dims &dm)
+{
+    return dm.n_heads == dm.n_kv_heads && (dm.head_dim == 128 || dm.head_dim == 64);
+}
+
+hipError_t launch_attention_mha_split(const uint16_t *q, int32_t q_stride, const relax_kv_cache &cache, const relax_layer_dims &dm,
+                                      const SeqTable &st, int32_t chunk, int32_t splits, int32_t part_stride, float *partials, hipStream_t stream)
+{
+    const dim3 grid(dm.n_heads, splits, st.n);
+    if (dm.head_dim == 128)
+        hipLaunchKernelGGL((attn_mha_split_kernel<128>), grid, dim3(256), 0, stream, q, cache.k, cache.v, partials, st, dm.n_heads,
+                           dm.kv_capacity, chunk, splits, q_stride, part_stride);
+    else
+        hipLaunchKernelGGL((attn_mha_split_kernel<64>), grid, dim3(256), 0, stream, q, cache.k, cache.v, partials, st, dm.n_heads,
+                           dm.kv_capacity, chunk, splits, q_stride, part_stride);
     return hipGetLastError();
 }
 

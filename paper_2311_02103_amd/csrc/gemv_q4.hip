@@ -489,6 +489,7 @@ static hipError_t launch_t(const GemvArgs &a, hipStream_t stream)
 
 hipError_t launch_gemv(const GemvArgs &a, int xmode, int epi, hipStream_t stream)
 {
+    if (xmode == X_ATTN_MERGE) return launch_gemv_reg(a, xmode, epi, stream);      // only the x-in-registers kernel folds the merge
     if (xmode == X_F16 && epi == EPI_F16) return launch_t<X_F16, EPI_F16>(a, stream);
     if (xmode == X_F16_NORM && epi == EPI_ROPE_KV) return launch_t<X_F16_NORM, EPI_ROPE_KV>(a, stream);
     if (xmode == X_F16 && epi == EPI_RESID_F32) return launch_t<X_F16, EPI_RESID_F32>(a, stream);

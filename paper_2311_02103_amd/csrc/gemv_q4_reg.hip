@@ -221,19 +221,41 @@ __global__ __launch_bounds__(kRThreads) void gemv_q4_reg_kernel(GemvArgs a)
     }
 
     // pass p of the staging covers chunk p of 2048 columns: thread t holds word t & 3 of group 64 p + (t >> 2)
+    constexpr bool kNorm = (XMODE == X_F16_NORM || XMODE == X_F32_NORM), kMerge = (XMODE == X_ATTN_MERGE);
+    constexpr int MS = kAttnMergeSplits;
     const size_t xbase = (size_t)i * k;
-    u32x4_t xraw[NG], xraw2[XMODE == X_F32_NORM ? NG : 1], wnr[XMODE != X_F16 ? NG : 1];
+    u32x4_t xraw[NG], xraw2[XMODE == X_F32_NORM ? NG : 1], wnr[kNorm ? NG : 1];
+    // X_ATTN_MERGE: x is the attention output, still in split form.  The thread's 8 elements belong to one head; it
+    // reads their accumulators and the (max, sum) pair of every split (splits past the used ones re-read the last)
+    float4 pacc[kMerge ? NG : 1][kMerge ? MS : 1][2];
+    float2 pml[kMerge ? NG : 1][kMerge ? MS : 1];
+    const int used = kMerge ? (a.pos0 + a.part_chunk) / a.part_chunk : 0;      // splits that hold tokens: ceil((pos + 1) / chunk)
+    auto x_loads = [&]() {
 #pragma unroll
     for (int p = 0; p < NG; ++p) {
         const int c8 = min(p * kRThreads + tid, kw - 1);
-        if (XMODE == X_F32_NORM) {
+        if (kMerge) {
+            const int head = (c8 * 8) / a.d, e = c8 * 8 - head * a.d;
+            const float *pb = a.part + ((size_t)i * a.h + head) * (size_t)a.part_splits * a.part_stride;
+#pragma unroll
+            for (int s = 0; s < MS; ++s) {
+                const float *ps = pb + (size_t)min(s, used - 1) * a.part_stride;
+                pacc[p][s][0] = *(const float4 *)(ps + e);
+                pacc[p][s][1] = *(const float4 *)(ps + e + 4);
+                pml[p][s] = *(const float2 *)(ps + a.d);
+            }
+        } else if (XMODE == X_F32_NORM) {
             xraw[p] = *(const u32x4_t *)((const float *)a.x + xbase + (size_t)c8 * 8);
             xraw2[p] = *(const u32x4_t *)((const float *)a.x + xbase + (size_t)c8 * 8 + 4);
         } else {
             xraw[p] = *(const u32x4_t *)((const uint16_t *)a.x + xbase + (size_t)c8 * 8);
         }
-        if (XMODE != X_F16) wnr[p] = *(const u32x4_t *)(a.norm_w + (size_t)c8 * 8);
+        if (kNorm) wnr[p] = *(const u32x4_t *)(a.norm_w + (size_t)c8 * 8);
     }
+    };
+    // The x row goes out ahead of the weights (it is needed first and is small).  The partials of X_ATTN_MERGE are
+    // many requests served by the L2: behind the first slots, so that the weight stream from HBM starts at once.
+    if (!kMerge) x_loads();
 
     struct Slot {
         u32x4_t w[E];
@@ -247,7 +269,9 @@ __global__ __launch_bounds__(kRThreads) void gemv_q4_reg_kernel(GemvArgs a)
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int uu = 0; uu < UPS; ++uu) {
-            const int u = min(wg + (j0 + uu) * W, U - 1);          // units past the end re-read a valid one and are dropped
+            // units past the end re-read the wavefront's own first unit (a different address per wavefront: one shared
+            // address would queue every wavefront of the grid on the same few cache lines) and are dropped
+            const int uj = wg + (j0 + uu) * W, u = uj < U ? uj : min(wg, U - 1);
             int rows[2];
             unit_rows_r<EPI>(a, u, rows[0], rows[1]);
 #pragma unroll
@@ -268,15 +292,16 @@ __global__ __launch_bounds__(kRThreads) void gemv_q4_reg_kernel(GemvArgs a)
     Slot sl[NSLOT];
 #pragma unroll
     for (int t = 0; t < NSLOT; ++t) slot_load(sl[t], t * UPS);
+    if (kMerge) x_loads();
     // behind the first slots in program order: its address arithmetic runs while they are in flight
-    const float2 pre = epi_fetch<EPI>(a, i, ri, min(wg + lane * W, U - 1));
+    const float2 pre = epi_fetch<EPI>(a, i, ri, lane < mine ? wg + lane * W : min(wg, U - 1));
     __builtin_amdgcn_sched_barrier(0);
     stamp(1);
 
     // ---- stage the (optionally RMS-normalised) x row in LDS as fp16, packet order [x0 x4 x1 x5 x2 x6 x3 x7] ----
     float inv = 1.0f;
-    float xf[XMODE != X_F16 ? NG : 1][8];
-    if (XMODE != X_F16) {
+    float xf[kNorm ? NG : 1][8];
+    if (kNorm) {
         float ss = 0.0f;
 #pragma unroll
         for (int p = 0; p < NG; ++p) {
@@ -305,13 +330,34 @@ __global__ __launch_bounds__(kRThreads) void gemv_q4_reg_kernel(GemvArgs a)
 #pragma unroll
     for (int p = 0; p < NG; ++p) {
         u32x4_t o;
-        if (XMODE != X_F16) {
+        if (kNorm) {
             uint16_t y[8];
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const uint32_t ww = wnr[p][e >> 1];
                 y[e] = f2h(xf[p][e] * inv * h2f((uint16_t)((e & 1) ? (ww >> 16) : (ww & 0xFFFFu))));
             }
+            o.x = (uint32_t)y[0] | ((uint32_t)y[4] << 16), o.y = (uint32_t)y[1] | ((uint32_t)y[5] << 16);
+            o.z = (uint32_t)y[2] | ((uint32_t)y[6] << 16), o.w = (uint32_t)y[3] | ((uint32_t)y[7] << 16);
+        } else if (kMerge) {
+            // out = sum_s acc_s e^(m_s - M) / sum_s l_s e^(m_s - M), rounded to fp16 like the stand-alone merge
+            const bool on = (p * kRThreads + tid) < kw;
+            float mm = -INFINITY;
+#pragma unroll
+            for (int s = 0; s < MS; ++s) mm = (s < used) ? fmaxf(mm, pml[p][s].x) : mm;
+            float num[8], den = 0.0f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) num[e] = 0.0f;
+#pragma unroll
+            for (int s = 0; s < MS; ++s) {
+                const float w = (s < used) ? __expf(pml[p][s].x - mm) : 0.0f;
+                den += pml[p][s].y * w;
+                num[0] += pacc[p][s][0].x * w, num[1] += pacc[p][s][0].y * w, num[2] += pacc[p][s][0].z * w, num[3] += pacc[p][s][0].w * w;
+                num[4] += pacc[p][s][1].x * w, num[5] += pacc[p][s][1].y * w, num[6] += pacc[p][s][1].z * w, num[7] += pacc[p][s][1].w * w;
+            }
+            uint16_t y[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) y[e] = on ? f2h(num[e] / den) : (uint16_t)0;
             o.x = (uint32_t)y[0] | ((uint32_t)y[4] << 16), o.y = (uint32_t)y[1] | ((uint32_t)y[5] << 16);
             o.z = (uint32_t)y[2] | ((uint32_t)y[6] << 16), o.w = (uint32_t)y[3] | ((uint32_t)y[7] << 16);
         } else {
@@ -401,7 +447,8 @@ hipError_t launch_ng(const GemvArgs &a, hipStream_t stream)
     if (cus == 0) {
         int dev = 0, v = 0;
         if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v < 1) v = 256;
-        cus = v;
+        const char *env = getenv("RELAX_GEMV_WGS_PER_CU");         // tuning aid
+        cus = v * std::max(1, env ? atoi(env) : 1);
     }
     const int U = (EPI == EPI_SWIGLU || EPI == EPI_ROPE_KV) ? a.m / 2 : (a.m + 1) / 2;
     // one workgroup per CU, shared between the rows of x; never fewer than what keeps a wavefront within kRMaxUnits
@@ -432,11 +479,25 @@ bool gemv_reg_eligible(const GemvArgs &a)
            ((reinterpret_cast<uintptr_t>(a.x) & 15) == 0) && ((reinterpret_cast<uintptr_t>(a.norm_w) & 15) == 0) && a.m >= 2;
 }
 
+// X_ATTN_MERGE: one row, at most two chunks of columns (the split accumulators of a thread live in registers), heads
+// of whole 8-element packets, 16-byte aligned partials with at most kAttnMergeSplits splits
+bool gemv_merge_eligible(const GemvArgs &a)
+{
+    return a.n == 1 && a.k <= 2 * 2048 && a.k >= 32 && (a.k % kGroup == 0) && a.k == a.h * a.d && (a.d % 8 == 0) && a.part != nullptr &&
+           ((reinterpret_cast<uintptr_t>(a.part) & 15) == 0) && (a.part_stride % 4 == 0) && a.part_stride >= a.d + 2 && a.part_chunk > 0 &&
+           a.part_splits >= 1 && a.part_splits <= kAttnMergeSplits && a.pos0 >= 0 && a.pos0 / a.part_chunk < a.part_splits &&
+           ((reinterpret_cast<uintptr_t>(a.q) & 15) == 0) && a.m >= 2;
+}
+
 hipError_t launch_gemv_reg(const GemvArgs &a, int xmode, int epi, hipStream_t stream)
 {
     if (xmode == X_F16 && epi == EPI_F16) return launch_xe<X_F16, EPI_F16>(a, stream);
     if (xmode == X_F16_NORM && epi == EPI_ROPE_KV) return launch_xe<X_F16_NORM, EPI_ROPE_KV>(a, stream);
     if (xmode == X_F16 && epi == EPI_RESID_F32) return launch_xe<X_F16, EPI_RESID_F32>(a, stream);
+    if (xmode == X_ATTN_MERGE && epi == EPI_RESID_F32 && gemv_merge_eligible(a)) {
+        if (a.k <= 2048) return launch_ng<X_ATTN_MERGE, EPI_RESID_F32, 1>(a, stream);
+        return launch_ng<X_ATTN_MERGE, EPI_RESID_F32, 2>(a, stream);
+    }
     if (xmode == X_F32_NORM && epi == EPI_SWIGLU) return launch_xe<X_F32_NORM, EPI_SWIGLU>(a, stream);
     if (xmode == X_F16 && epi == EPI_RESID_F16) return launch_xe<X_F16, EPI_RESID_F16>(a, stream);
     return hipErrorInvalidValue;

@@ -89,12 +89,16 @@ inline int groups_of(int k) { return (k + kGroup - 1) / kGroup; }
 
 // ---- launchers (defined in the .hip files), all asynchronous on `stream` --------------------------------------
 
-enum XMode { X_F16 = 0, X_F16_NORM = 1, X_F32_NORM = 2 };
+enum XMode { X_F16 = 0, X_F16_NORM = 1, X_F32_NORM = 2, X_ATTN_MERGE = 3 };
+constexpr int kAttnMergeSplits = 8;  // splits along L that the matvec prologue of X_ATTN_MERGE folds (one round of loads)
 enum Epilogue { EPI_F16 = 0, EPI_ROPE_KV = 1, EPI_RESID_F32 = 2, EPI_RESID_F16 = 3, EPI_SWIGLU = 4 };
 
 struct GemvArgs {
     // input rows
-    const void *x;                   // [n,k] fp16 (X_F16, X_F16_NORM) or fp32 (X_F32_NORM)
+    const void *x;                   // [n,k] fp16 (X_F16, X_F16_NORM) or fp32 (X_F32_NORM); unused by X_ATTN_MERGE
+    // X_ATTN_MERGE (one row): x = merge of the attention partials [h][part_splits][part_stride] fp32 (d accumulators, max, sum)
+    const float *part;
+    int32_t part_splits, part_stride, part_chunk;
     const uint16_t *norm_w;          // [k] fp16, norm modes only
     float eps;
     // matrix
@@ -117,6 +121,7 @@ struct GemvArgs {
 hipError_t launch_gemv(const GemvArgs &a, int xmode, int epi, hipStream_t stream);
 // x-in-registers variant for rows of up to 6 x 2048 columns (gemv_q4_reg.hip); launch_gemv picks it when eligible
 bool gemv_reg_eligible(const GemvArgs &a);
+bool gemv_merge_eligible(const GemvArgs &a);
 hipError_t launch_gemv_reg(const GemvArgs &a, int xmode, int epi, hipStream_t stream);
 
 hipError_t launch_rmsnorm(const uint16_t *x, const uint16_t *w, uint16_t *y, int n, int H, float eps, hipStream_t stream);
@@ -147,6 +152,9 @@ struct AttnPlan {
 };
 AttnPlan attn_plan(int32_t n, int32_t g, int32_t L_max);
 size_t attn_partial_floats(const relax_layer_dims &dm, int32_t n_max, int32_t L_max);
+bool attn_mha_split_supported(const relax_layer_dims &dm);
+hipError_t launch_attention_mha_split(const uint16_t *q, int32_t q_stride, const relax_kv_cache &cache, const relax_layer_dims &dm,
+                                      const SeqTable &st, int32_t chunk, int32_t splits, int32_t part_stride, float *partials, hipStream_t stream);
 hipError_t launch_attention(const uint16_t *q, int32_t q_stride, const relax_kv_cache &cache, const relax_layer_dims &dm,
                             const SeqTable &st, int32_t L_max, uint16_t *out, float *partials, hipStream_t stream);
 
