@@ -255,6 +255,14 @@ void relax_profile_step_events(void *start, void *stop, int32_t step);
  * staging C, step C, staging D, step D, staging E, step E).  NULL switches it off (default).                                                          */
 void relax_profile_trace_buffer(void *dev_u64x16);
 
+/* Measurement aid: while q_alt / s_alt (device pointers to another packed matrix and its scales, of the shape of
+ * the layer's gate/up matrix) are set, every relax_decoder_layer call with n == 1 launches its gate/up matvec
+ * once more, on those weights, ahead of the real launch (whose result then overwrites it).  Inside a captured
+ * schedule the kernels run back to back, so the duration of that launch there is the difference between the
+ * schedule timed with and without the extra launch -- on weights that are cold like the real ones.  NULL, NULL
+ * switches it off (default).  The caller owns the memory and keeps it alive while set.                         */
+void relax_profile_alt_gate_up(const void *q_alt, const void *s_alt);
+
 /* Build identity of the loaded binary (one binary serves every shape).                  */
 const char *relax_build_id(void);
 

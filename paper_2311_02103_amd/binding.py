@@ -67,6 +67,7 @@ _SIGNATURES = {
     "relax_build_id": (C.c_char_p, []),
     "relax_set_option": (C.c_int32, [C.c_char_p, C.c_int32]),
     "relax_profile_trace_buffer": (None, [C.c_void_p]),
+    "relax_profile_alt_gate_up": (None, [C.c_void_p, C.c_void_p]),
     "relax_workspace_init": (C.c_int32, [C.POINTER(LayerDims), C.c_void_p, C.c_size_t, C.c_void_p]),
     "relax_workspace_error": (C.c_int32, [C.POINTER(LayerDims), C.c_void_p, C.POINTER(C.c_int32)]),
     "relax_profile_step_events": (None, [C.c_void_p, C.c_void_p, C.c_int32]),
@@ -314,3 +315,7 @@ def relax_workspace_error(dims: Optional[LayerDims], ws: Ptr) -> int:
 
 def relax_profile_trace_buffer(buf: Ptr) -> None:
     lib().relax_profile_trace_buffer(_ptr(buf))
+
+
+def relax_profile_alt_gate_up(q_alt: Ptr, s_alt: Ptr) -> None:
+    lib().relax_profile_alt_gate_up(_ptr(q_alt), _ptr(s_alt))

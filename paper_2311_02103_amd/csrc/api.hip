@@ -155,6 +155,8 @@ struct StepTimer {
 
 // Tuning / test switches (relax_set_option).
 int g_opt_fused_decode = 0;
+const uint32_t *g_prof_alt_q = nullptr;      // relax_profile_alt_gate_up: another matrix of the gate/up shape
+const uint16_t *g_prof_alt_s = nullptr;
 unsigned long long *g_trace = nullptr;      // relax_profile_trace_buffer
 
 // CU count of the current device (the fused kernel launches exactly one workgroup per CU).
@@ -176,6 +178,12 @@ int device_cus()
 extern "C" {
 
 void relax_profile_trace_buffer(void *dev_u64x16) { g_trace = static_cast<unsigned long long *>(dev_u64x16); }
+
+void relax_profile_alt_gate_up(const void *q_alt, const void *s_alt)
+{
+    g_prof_alt_q = static_cast<const uint32_t *>(q_alt);
+    g_prof_alt_s = static_cast<const uint16_t *>(s_alt);
+}
 
 relax_status relax_set_option(const char *name, int32_t value)
 {
@@ -483,6 +491,11 @@ relax_status layer_enqueue(const relax_layer_dims &dm, const relax_layer_weights
     f.q = wt->wgu.q, f.s = wt->wgu.s, f.m = wt->wgu.m, f.k = wt->wgu.k, f.n = n;
     f.out_f16 = act, f.trace = g_trace;
     timer.before(3);
+    if (g_prof_alt_q && g_prof_alt_s) {                        // measurement aid: one more launch of the same shape on other weights first
+        GemvArgs f2 = f;
+        f2.q = g_prof_alt_q, f2.s = g_prof_alt_s;
+        if (launch_gemv(f2, X_F32_NORM, EPI_SWIGLU, st_) != hipSuccess) return RELAX_ERR_HIP;
+    }
     if (launch_gemv(f, X_F32_NORM, EPI_SWIGLU, st_) != hipSuccess) return RELAX_ERR_HIP;
     timer.after(3);
 
