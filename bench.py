@@ -460,12 +460,38 @@ def bench_ceilings(args, np, torch, wl, rx):
         ms = timed(call, 5)
         out[name] = round(flops[0] / ms / 1e9, 1)
     ach = nbytes / ms_read / 1e6
+    # Chain of dependent launches that only stream (one stream, captured in a graph, every launch on memory that has
+    # not been touched for 2 GiB): what a launch of the decode layer costs before any arithmetic, as a fixed part per
+    # launch plus bytes over a streaming rate.
+    stream = torch.cuda.Stream()
+    chain = {}
+    for mb in (0, 12, 48, 96):
+        nb, nl = max(mb << 20, 4096), 48
+        ptrs = [bufs[j % 2].data_ptr() + ((j // 2) * (96 << 20)) % (nbytes - (96 << 20)) for j in range(nl)]
+        with torch.cuda.stream(stream):
+            rx.check(rx.relax_probe_stream_read(ptrs[0], nb, sink, stream=stream))
+        stream.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=stream):
+            for j in range(nl):
+                rx.check(rx.relax_probe_stream_read(ptrs[j], nb, sink, stream=stream))
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        with torch.cuda.stream(stream):
+            g.replay()
+            a.record(stream)
+            for _ in range(10):
+                g.replay()
+            b.record(stream)
+        stream.synchronize()
+        chain["%d MB" % mb] = round(a.elapsed_time(b) * 1e3 / (10 * nl), 2)
+    slope = (96 - 48) * (1 << 20) / ((chain["96 MB"] - chain["48 MB"]) * 1e-6) / 1e9
+    chain_out = {"us_per_dependent_launch": chain, "fixed_us": chain["0 MB"], "slope_GBps": round(slope, 1)}
     emit(args, "device ceilings: streaming read GB/s, MFMA loop TFLOP/s", "GB/s", ach, ms_read, "u32x4 loads / f16 MFMA",
          {"workload": "ceilings: relax_probe_stream_read over 1 GiB (two buffers alternated) and relax_probe_mfma (16 independent "
                       "32x32x16 f16 MFMAs per wavefront and iteration, 4 wavefronts per CU, 4000 iterations)", "build_id": rx.relax_build_id()},
          {"bound": "hbm", "kernel": "stream_read_kernel", "achieved": round(ach, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
           "frac": round(ach / PEAK_HBM_GBS, 4), "traffic": None},
-         None, {"mfma_loop_TFLOPs": out, "mfma_published_peak_TFLOPs": PEAK_MFMA_TFLOPS})
+         None, {"mfma_loop_TFLOPs": out, "mfma_published_peak_TFLOPs": PEAK_MFMA_TFLOPS, "stream_chain": chain_out})
 
 
 def main():

@@ -269,9 +269,11 @@ __global__ __launch_bounds__(kRThreads) void gemv_q4_reg_kernel(GemvArgs a)
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int uu = 0; uu < UPS; ++uu) {
-            // units past the end re-read the wavefront's own first unit (a different address per wavefront: one shared
-            // address would queue every wavefront of the grid on the same few cache lines) and are dropped
-            const int uj = wg + (j0 + uu) * W, u = uj < U ? uj : min(wg, U - 1);
+            // units past the end re-read the unit before them -- the other half of the same slot, still on its way or
+            // in the L2, and a different address per wavefront (one shared address would queue every wavefront of
+            // the grid on the same few cache lines) -- and are dropped
+            const int uj = wg + (j0 + uu) * W, ub = wg + max(j0 + uu - 1, 0) * W;
+            const int u = uj < U ? uj : (ub < U ? ub : min(wg, U - 1));
             int rows[2];
             unit_rows_r<EPI>(a, u, rows[0], rows[1]);
 #pragma unroll
