@@ -394,10 +394,11 @@ __global__ __launch_bounds__(kRThreads) void gemv_q4_reg_kernel(GemvArgs a)
         float acc[R];
 #pragma unroll
         for (int rr = 0; rr < R; ++rr) acc[rr] = 0.0f;
+        // in the order the requests went out (row by row): every group is used as soon as it has arrived
 #pragma unroll
-        for (int c = 0; c < NG; ++c)
+        for (int rr = 0; rr < R; ++rr)
 #pragma unroll
-            for (int rr = 0; rr < R; ++rr) {
+            for (int c = 0; c < NG; ++c) {
                 float scv = h2f(s.sc[rr * NG + c]);
                 if (c == NG - 1) scv = last_on ? scv : 0.0f;
                 acc[rr] += scv * group_dot_r(s.w[rr * NG + c], xv[c], cr[c]);
