@@ -465,7 +465,7 @@ relax_status layer_enqueue(const relax_layer_dims &dm, const relax_layer_weights
         const int chunk = ((L + splits - 1) / splits + 63) / 64 * 64;
         splits = (L + chunk - 1) / chunk;
         o.h = dm.n_heads, o.d = dm.head_dim, o.pos0 = pos;
-        o.part = partials, o.part_splits = splits, o.part_stride = dm.head_dim + 4, o.part_chunk = chunk;
+        o.part = partials, o.part_splits = splits, o.part_stride = dm.head_dim / 2 + 4, o.part_chunk = chunk;
         folded = (size_t)dm.n_heads * splits * o.part_stride <= attn_partial_floats(dm, 1, 1) && gemv_merge_eligible(o);
         if (folded) {
             timer.before(1);

@@ -178,7 +178,7 @@ __device__ __forceinline__ float dpp_f(float v)
     return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
 }
 
-template <int D>
+template <int D, bool HALF>
 __global__ __launch_bounds__(256) void attn_mha_split_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict__ kc,
                                                              const uint16_t *__restrict__ vc, float *__restrict__ part, SeqTable st,
                                                              int h, int cap, int chunk, int splits, int q_stride, int ps)
@@ -327,9 +327,15 @@ __global__ __launch_bounds__(256) void attn_mha_split_kernel(const uint16_t *__r
             num += src[e] * scw;
             den += src[D + 1] * scw;
         }
-        float *dst = part + (((size_t)i * h + head) * splits + split) * ps;          // ps >= D + 2 floats per partial
-        dst[e] = num;
-        if (e == 0) dst[D] = mm, dst[D + 1] = den;
+        float *dst = part + (((size_t)i * h + head) * splits + split) * ps;          // ps floats per partial
+        if (HALF) {
+            // for a reader that folds the merge into its prologue: out_s = acc_s / l_s as fp16 (D halfs), then (m_s, l_s)
+            reinterpret_cast<uint16_t *>(dst)[e] = f2h(num / den);                       // den > 0: the split holds at least one token
+            if (e == 0) dst[D / 2] = mm, dst[D / 2 + 1] = den;
+        } else {
+            dst[e] = num;                                                                // ps >= D + 2
+            if (e == 0) dst[D] = mm, dst[D + 1] = den;
+        }
     }
 }
 
@@ -389,7 +395,7 @@ static hipError_t launch_d(const uint16_t *q, int q_stride, const relax_kv_cache
     hipError_t e;
     if (attn_gqa_supported(dm)) e = launch_attention_gqa_split(q, q_stride, cache, dm, st, pl, partials, stream);   // MFMA kernel for grouped heads
     else if (rep == 1) {
-        hipLaunchKernelGGL((attn_mha_split_kernel<D>), dim3(dm.n_heads, pl.splits, st.n), dim3(256), 0, stream, q, cache.k, cache.v, partials, st,
+        hipLaunchKernelGGL((attn_mha_split_kernel<D, false>), dim3(dm.n_heads, pl.splits, st.n), dim3(256), 0, stream, q, cache.k, cache.v, partials, st,
                            dm.n_heads, dm.kv_capacity, pl.chunk, pl.splits, q_stride, D + 2);
         e = hipGetLastError();
     }
@@ -404,7 +410,8 @@ static hipError_t launch_d(const uint16_t *q, int q_stride, const relax_kv_cache
 }
 
 // split kernel alone, for a caller that folds the merge into its own prologue (one query head per KV head, decode rows):
-// partial of (row, head, split) at partials + ((row * h + head) * splits + split) * part_stride
+// partial of (row, head, split) at partials + ((row * h + head) * splits + split) * part_stride floats, in the half
+// format: head_dim normalised outputs acc / l as fp16, then (max, sum) as fp32 at float index head_dim / 2; part_stride >= head_dim / 2 + 2
 bool attn_mha_split_supported(const relax_layer_dims &dm)
 {
     return dm.n_heads == dm.n_kv_heads && (dm.head_dim == 128 || dm.head_dim == 64);
@@ -415,10 +422,10 @@ hipError_t launch_attention_mha_split(const uint16_t *q, int32_t q_stride, const
 {
     const dim3 grid(dm.n_heads, splits, st.n);
     if (dm.head_dim == 128)
-        hipLaunchKernelGGL((attn_mha_split_kernel<128>), grid, dim3(256), 0, stream, q, cache.k, cache.v, partials, st, dm.n_heads,
+        hipLaunchKernelGGL((attn_mha_split_kernel<128, true>), grid, dim3(256), 0, stream, q, cache.k, cache.v, partials, st, dm.n_heads,
                            dm.kv_capacity, chunk, splits, q_stride, part_stride);
     else
-        hipLaunchKernelGGL((attn_mha_split_kernel<64>), grid, dim3(256), 0, stream, q, cache.k, cache.v, partials, st, dm.n_heads,
+        hipLaunchKernelGGL((attn_mha_split_kernel<64, true>), grid, dim3(256), 0, stream, q, cache.k, cache.v, partials, st, dm.n_heads,
                            dm.kv_capacity, chunk, splits, q_stride, part_stride);
     return hipGetLastError();
 }

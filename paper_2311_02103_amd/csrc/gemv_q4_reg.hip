@@ -227,7 +227,7 @@ __global__ __launch_bounds__(kRThreads) void gemv_q4_reg_kernel(GemvArgs a)
     u32x4_t xraw[NG], xraw2[XMODE == X_F32_NORM ? NG : 1], wnr[kNorm ? NG : 1];
     // X_ATTN_MERGE: x is the attention output, still in split form.  The thread's 8 elements belong to one head; it
     // reads their accumulators and the (max, sum) pair of every split (splits past the used ones re-read the last)
-    float4 pacc[kMerge ? NG : 1][kMerge ? MS : 1][2];
+    u32x4_t pacc[kMerge ? NG : 1][kMerge ? MS : 1];            // 8 normalised outputs of the split, fp16
     float2 pml[kMerge ? NG : 1][kMerge ? MS : 1];
     const int used = kMerge ? (a.pos0 + a.part_chunk) / a.part_chunk : 0;      // splits that hold tokens: ceil((pos + 1) / chunk)
     auto x_loads = [&]() {
@@ -240,9 +240,8 @@ __global__ __launch_bounds__(kRThreads) void gemv_q4_reg_kernel(GemvArgs a)
 #pragma unroll
             for (int s = 0; s < MS; ++s) {
                 const float *ps = pb + (size_t)min(s, used - 1) * a.part_stride;
-                pacc[p][s][0] = *(const float4 *)(ps + e);
-                pacc[p][s][1] = *(const float4 *)(ps + e + 4);
-                pml[p][s] = *(const float2 *)(ps + a.d);
+                pacc[p][s] = *(const u32x4_t *)((const uint16_t *)ps + e);
+                pml[p][s] = *(const float2 *)(ps + (a.d >> 1));
             }
         } else if (XMODE == X_F32_NORM) {
             xraw[p] = *(const u32x4_t *)((const float *)a.x + xbase + (size_t)c8 * 8);
@@ -352,10 +351,14 @@ __global__ __launch_bounds__(kRThreads) void gemv_q4_reg_kernel(GemvArgs a)
             for (int e = 0; e < 8; ++e) num[e] = 0.0f;
 #pragma unroll
             for (int s = 0; s < MS; ++s) {
-                const float w = (s < used) ? __expf(pml[p][s].x - mm) : 0.0f;
-                den += pml[p][s].y * w;
-                num[0] += pacc[p][s][0].x * w, num[1] += pacc[p][s][0].y * w, num[2] += pacc[p][s][0].z * w, num[3] += pacc[p][s][0].w * w;
-                num[4] += pacc[p][s][1].x * w, num[5] += pacc[p][s][1].y * w, num[6] += pacc[p][s][1].z * w, num[7] += pacc[p][s][1].w * w;
+                // the split kernel left out_s = acc_s / l_s (fp16) and (m_s, l_s): weight of the split = l_s e^(m_s - M)
+                const float w = (s < used) ? __expf(pml[p][s].x - mm) * pml[p][s].y : 0.0f;
+                den += w;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t ow = pacc[p][s][j];
+                    num[2 * j] += w * h2f((uint16_t)(ow & 0xFFFFu)), num[2 * j + 1] += w * h2f((uint16_t)(ow >> 16));
+                }
             }
             uint16_t y[8];
 #pragma unroll
@@ -487,7 +490,7 @@ bool gemv_reg_eligible(const GemvArgs &a)
 bool gemv_merge_eligible(const GemvArgs &a)
 {
     return a.n == 1 && a.k <= 2 * 2048 && a.k >= 32 && (a.k % kGroup == 0) && a.k == a.h * a.d && (a.d % 8 == 0) && a.part != nullptr &&
-           ((reinterpret_cast<uintptr_t>(a.part) & 15) == 0) && (a.part_stride % 4 == 0) && a.part_stride >= a.d + 2 && a.part_chunk > 0 &&
+           ((reinterpret_cast<uintptr_t>(a.part) & 15) == 0) && (a.part_stride % 4 == 0) && a.part_stride >= a.d / 2 + 2 && a.part_chunk > 0 &&
            a.part_splits >= 1 && a.part_splits <= kAttnMergeSplits && a.pos0 >= 0 && a.pos0 / a.part_chunk < a.part_splits &&
            ((reinterpret_cast<uintptr_t>(a.q) & 15) == 0) && a.m >= 2;
 }

@@ -96,7 +96,8 @@ enum Epilogue { EPI_F16 = 0, EPI_ROPE_KV = 1, EPI_RESID_F32 = 2, EPI_RESID_F16 =
 struct GemvArgs {
     // input rows
     const void *x;                   // [n,k] fp16 (X_F16, X_F16_NORM) or fp32 (X_F32_NORM); unused by X_ATTN_MERGE
-    // X_ATTN_MERGE (one row): x = merge of the attention partials [h][part_splits][part_stride] fp32 (d accumulators, max, sum)
+    // X_ATTN_MERGE (one row): x = merge of the attention partials [h][part_splits][part_stride floats]: d normalised outputs
+    // as fp16, then (max, sum) as fp32 at float index d / 2
     const float *part;
     int32_t part_splits, part_stride, part_chunk;
     const uint16_t *norm_w;          // [k] fp16, norm modes only
