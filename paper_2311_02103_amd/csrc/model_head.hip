@@ -47,6 +47,52 @@ __global__ __launch_bounds__(256) void final_norm_kernel(const uint16_t *__restr
     }
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const size_t base = (size_t)row * H;
+    // rows of whole 16-byte packets, at most kNormPasses per thread: the row stays in registers between the two passes
+    constexpr int kNormPasses = 4;
+    const bool vec = (H % 8 == 0) && H <= 256 * 8 * kNormPasses && ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(w) |
+                                                                     reinterpret_cast<uintptr_t>(y)) & 15) == 0;
+    if (vec) {
+        uint4 xr[kNormPasses], wr[kNormPasses];
+        float ss = 0.0f;
+#pragma unroll
+        for (int p = 0; p < kNormPasses; ++p) {
+            const int c8 = tid + p * 256;
+            xr[p] = wr[p] = make_uint4(0u, 0u, 0u, 0u);
+            if (c8 * 8 < H) {
+                xr[p] = *(const uint4 *)(x + base + (size_t)c8 * 8);
+                wr[p] = *(const uint4 *)(w + (size_t)c8 * 8);
+            }
+        }
+#pragma unroll
+        for (int p = 0; p < kNormPasses; ++p) {
+            const uint32_t xw[4] = {xr[p].x, xr[p].y, xr[p].z, xr[p].w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float a = h2f((uint16_t)(xw[j] & 0xFFFFu)), c = h2f((uint16_t)(xw[j] >> 16));
+                ss += a * a + c * c;
+            }
+        }
+        ss = wave_sum(ss);
+        if (lane == 0) red[wave] = ss;
+        __syncthreads();
+        const float inv = 1.0f / sqrtf((red[0] + red[1] + red[2] + red[3]) / (float)H + eps);
+#pragma unroll
+        for (int p = 0; p < kNormPasses; ++p) {
+            const int c8 = tid + p * 256;
+            if (c8 * 8 < H) {
+                const uint32_t xw[4] = {xr[p].x, xr[p].y, xr[p].z, xr[p].w}, ww[4] = {wr[p].x, wr[p].y, wr[p].z, wr[p].w};
+                uint32_t o[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint16_t lo = f2h(h2f((uint16_t)(xw[j] & 0xFFFFu)) * inv * h2f((uint16_t)(ww[j] & 0xFFFFu)));
+                    const uint16_t hi = f2h(h2f((uint16_t)(xw[j] >> 16)) * inv * h2f((uint16_t)(ww[j] >> 16)));
+                    o[j] = (uint32_t)lo | ((uint32_t)hi << 16);
+                }
+                *(uint4 *)(y + (size_t)b * H + (size_t)c8 * 8) = make_uint4(o[0], o[1], o[2], o[3]);
+            }
+        }
+        return;
+    }
     float ss = 0.0f;
     for (int c = tid; c < H; c += 256) {
         const float v = h2f(x[base + c]);
@@ -116,9 +162,31 @@ __global__ __launch_bounds__(1024) void argmax_kernel(const uint16_t *__restrict
     const uint16_t *row = logits + (size_t)blockIdx.x * V;
     float best = -INFINITY;
     int idx = 0x7FFFFFFF;
-    for (int c = threadIdx.x; c < V; c += 1024) {
-        const float v = h2f(row[c]);
+    auto take = [&](float v, int c) {
         if (v > best || (v == best && c < idx)) best = v, idx = c;
+    };
+    if (V % 8 == 0 && (reinterpret_cast<uintptr_t>(logits) & 15) == 0) {
+        // 16-byte packets, four of them in flight per thread and round
+        const int packets = V >> 3;
+        for (int p0 = threadIdx.x; p0 < packets; p0 += 4 * 1024) {
+            uint4 raw[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) raw[j] = *(const uint4 *)(row + (size_t)min(p0 + j * 1024, packets - 1) * 8);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int pk = p0 + j * 1024;
+                if (pk < packets) {
+                    const uint32_t wv[4] = {raw[j].x, raw[j].y, raw[j].z, raw[j].w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        take(h2f((uint16_t)(wv[e] & 0xFFFFu)), pk * 8 + 2 * e);
+                        take(h2f((uint16_t)(wv[e] >> 16)), pk * 8 + 2 * e + 1);
+                    }
+                }
+            }
+        }
+    } else {
+        for (int c = threadIdx.x; c < V; c += 1024) take(h2f(row[c]), c);
     }
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) {
