@@ -192,6 +192,7 @@ template <int XMODE, int EPI, int NG>
 __global__ __launch_bounds__(kRThreads) void gemv_q4_reg_kernel(GemvArgs a)
 {
     constexpr int R = RegShape<NG>::R, NSLOT = RegShape<NG>::NSLOT, UPS = R / 2, E = R * NG;
+    constexpr int kFirstRagged = NG >= 4 ? NG - 2 : NG - 1;        // first chunk of 2048 columns that a row may end in
     __shared__ __align__(16) uint16_t xs[NG * 2048];
     __shared__ float red[kRWaves];
     __shared__ float res_all[kRWaves][kRMaxUnits * 2 + 2];
@@ -282,7 +283,8 @@ __global__ __launch_bounds__(kRThreads) void gemv_q4_reg_kernel(GemvArgs a)
                 const uint16_t *srow = a.s + (size_t)rows[h] * G;
 #pragma unroll
                 for (int c = 0; c < NG; ++c) {
-                    const int gi = (c == NG - 1) ? min(c * 64 + lane, G - 1) : c * 64 + lane;
+                    // chunks that can reach past the row (NG = 4, 6 also serve rows one chunk shorter) are clamped
+                    const int gi = (c >= kFirstRagged) ? min(c * 64 + lane, G - 1) : c * 64 + lane;
                     s.w[(uu * 2 + h) * NG + c] = *(const u32x4_t *)(qrow + gi * 4);
                     s.sc[(uu * 2 + h) * NG + c] = srow[gi];
                 }
@@ -389,7 +391,9 @@ __global__ __launch_bounds__(kRThreads) void gemv_q4_reg_kernel(GemvArgs a)
         }
         cr[c] = 1032.0f * sa + 72.0f * sb;
     }
-    const bool last_on = (NG - 1) * 64 + lane < G;                 // lanes past the last group of the row
+    bool chunk_on[NG];                                             // lanes past the last group of the row contribute nothing
+#pragma unroll
+    for (int c = 0; c < NG; ++c) chunk_on[c] = c * 64 + lane < G;
     stamp(2);
 
     // ---- the stream ------------------------------------------------------------------------------------------
@@ -403,7 +407,7 @@ __global__ __launch_bounds__(kRThreads) void gemv_q4_reg_kernel(GemvArgs a)
 #pragma unroll
             for (int c = 0; c < NG; ++c) {
                 float scv = h2f(s.sc[rr * NG + c]);
-                if (c == NG - 1) scv = last_on ? scv : 0.0f;
+                if (c >= kFirstRagged) scv = chunk_on[c] ? scv : 0.0f;
                 acc[rr] += scv * group_dot_r(s.w[rr * NG + c], xv[c], cr[c]);
             }
         if (R == 4) {

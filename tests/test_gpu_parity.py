@@ -105,7 +105,9 @@ def test_integer_valued_matmul_bitwise(rx, m, k, n):
 # ------------------------------------------------------------------------- matvec: random data, tolerance
 @pytest.mark.parametrize("m,k,n", [(768, 256, 37), (256, 256, 1), (1376, 256, 4), (256, 688, 37), (257, 688, 1),
                                    (1024, 4096, 1), (515, 4096, 17), (640, 11008, 1), (96, 11008, 3), (9, 8192, 2),
-                                   (2, 28672, 1), (1, 64, 1)])
+                                   (2, 28672, 1), (1, 64, 1),
+                                   # rows that end in the first / second-to-last chunk of 2048 columns of the register-resident matvec
+                                   (131, 2080, 1), (200, 4192, 1), (64, 8224, 1), (77, 2080, 3), (37, 10272, 1)])
 def test_dequant_matmul_random(rx, m, k, n):
     q, s = wl.qmat(3, m * 131 + k, m, k)
     x = wl.normal_f16_bits(3, m + k + n, (n, k))
