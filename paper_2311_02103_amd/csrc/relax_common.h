@@ -38,7 +38,11 @@ struct RowInfo {
 __device__ inline RowInfo row_info(const SeqTable &st, int32_t row)
 {
     RowInfo r;
-    if (st.dev) {
+    if (st.B == 1 && !st.dev) {                                // one sequence (batch-1 decode, a single prefill): no walk
+        r.seq = 0;
+        r.pos = st.kv_len[0] - st.q_len[0] + (row - st.q_start[0]);
+        r.slot = st.slot[0];
+    } else if (st.dev) {
         const int32_t *qs = st.dev, *ql = st.dev + st.B, *kl = st.dev + 2 * st.B, *sl = st.dev + 3 * st.B;
         int b = 0;
         while (b + 1 < st.B && row >= qs[b] + ql[b]) ++b;
