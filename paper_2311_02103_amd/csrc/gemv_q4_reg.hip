@@ -79,6 +79,17 @@ __device__ __forceinline__ float reduce4(float v0, float v1, float v2, float v3,
     r += __shfl_xor(r, 32, kWave);
     return r;
 }
+// one partial sum -> every lane holds the total
+__device__ __forceinline__ float reduce1(float v)
+{
+    float r = v + dpp<kQuadXor1>(v);
+    r += dpp<kQuadXor2>(r);
+    r += dpp<kRowRor4>(r);
+    r += dpp<kRowRor8>(r);
+    r += __shfl_xor(r, 16, kWave);
+    r += __shfl_xor(r, 32, kWave);
+    return r;
+}
 // two partial sums -> lane l holds the total of row l & 1
 __device__ __forceinline__ float reduce2(float v0, float v1, int lane)
 {
@@ -183,7 +194,9 @@ __device__ __forceinline__ void epi_store(const GemvArgs &a, int i, const RowInf
 
 template <int NG>
 struct RegShape {
-    static constexpr int R = NG <= 2 ? 4 : 2;                  // rows per slot
+    // rows per slot: 8 requests of 16 bytes per lane and slot for short rows; long rows keep 96 registers of x, so
+    // their slots are one row (6 requests) -- with two rows the kernel needed 382 registers and spilled to AGPRs
+    static constexpr int R = NG <= 2 ? 4 : (NG <= 4 ? 2 : 1);
     static constexpr int NSLOT = 2;                            // slots in flight (the schedule of the stream is written for two)
 };
 
@@ -191,11 +204,11 @@ struct RegShape {
 template <int XMODE, int EPI, int NG>
 __global__ __launch_bounds__(kRThreads) void gemv_q4_reg_kernel(GemvArgs a)
 {
-    constexpr int R = RegShape<NG>::R, NSLOT = RegShape<NG>::NSLOT, UPS = R / 2, E = R * NG;
+    constexpr int R = RegShape<NG>::R, NSLOT = RegShape<NG>::NSLOT, E = R * NG;
     constexpr int kFirstRagged = NG >= 4 ? NG - 2 : NG - 1;        // first chunk of 2048 columns that a row may end in
     __shared__ __align__(16) uint16_t xs[NG * 2048];
     __shared__ float red[kRWaves];
-    __shared__ float res_all[kRWaves][kRMaxUnits * 2 + 2];
+    __shared__ float res_all[kRWaves][kRMaxUnits * 2 + 4];     // one sum per row of the wavefront (+ the dead rows of a last slot)
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int i = blockIdx.y;
     const int k = a.k, G = k >> 5, kw = k >> 3;
@@ -265,36 +278,35 @@ __global__ __launch_bounds__(kRThreads) void gemv_q4_reg_kernel(GemvArgs a)
     // The requests of a slot stay together in program order (scheduling barriers on both sides): the wait before a
     // consume is a count of younger requests, and one request of this slot issued late would make it cover the
     // other slot as well.
-    auto slot_load = [&](Slot &s, int j0) {
+    // The rows of a wavefront in sequence: row t is row t & 1 of its unit t >> 1; slot si holds rows si R .. si R + R - 1.
+    auto slot_load = [&](Slot &s, int si) {
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int uu = 0; uu < UPS; ++uu) {
+        for (int rr = 0; rr < R; ++rr) {
             // units past the end re-read the unit before them -- the other half of the same slot, still on its way or
             // in the L2, and a different address per wavefront (one shared address would queue every wavefront of
             // the grid on the same few cache lines) -- and are dropped
-            const int uj = wg + (j0 + uu) * W, ub = wg + max(j0 + uu - 1, 0) * W;
+            const int t = si * R + rr, j = t >> 1;
+            const int uj = wg + j * W, ub = wg + max(j - 1, 0) * W;
             const int u = uj < U ? uj : (ub < U ? ub : min(wg, U - 1));
             int rows[2];
             unit_rows_r<EPI>(a, u, rows[0], rows[1]);
+            const int row = __builtin_amdgcn_readfirstlane((t & 1) ? rows[1] : rows[0]);     // uniform: row bases in scalar registers
+            const uint32_t *qrow = a.q + (size_t)row * kw;
+            const uint16_t *srow = a.s + (size_t)row * G;
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                rows[h] = __builtin_amdgcn_readfirstlane(rows[h]);     // uniform: row bases in scalar registers
-                const uint32_t *qrow = a.q + (size_t)rows[h] * kw;
-                const uint16_t *srow = a.s + (size_t)rows[h] * G;
-#pragma unroll
-                for (int c = 0; c < NG; ++c) {
-                    // chunks that can reach past the row (NG = 4, 6 also serve rows one chunk shorter) are clamped
-                    const int gi = (c >= kFirstRagged) ? min(c * 64 + lane, G - 1) : c * 64 + lane;
-                    s.w[(uu * 2 + h) * NG + c] = *(const u32x4_t *)(qrow + gi * 4);
-                    s.sc[(uu * 2 + h) * NG + c] = srow[gi];
-                }
+            for (int c = 0; c < NG; ++c) {
+                // chunks that can reach past the row (NG = 4, 6 also serve rows one chunk shorter) are clamped
+                const int gi = (c >= kFirstRagged) ? min(c * 64 + lane, G - 1) : c * 64 + lane;
+                s.w[rr * NG + c] = *(const u32x4_t *)(qrow + gi * 4);
+                s.sc[rr * NG + c] = srow[gi];
             }
         }
         __builtin_amdgcn_sched_barrier(0);
     };
     Slot sl[NSLOT];
 #pragma unroll
-    for (int t = 0; t < NSLOT; ++t) slot_load(sl[t], t * UPS);
+    for (int t = 0; t < NSLOT; ++t) slot_load(sl[t], t);
     if (kMerge) x_loads();
     // behind the first slots in program order: its address arithmetic runs while they are in flight
     const float2 pre = epi_fetch<EPI>(a, i, ri, lane < mine ? wg + lane * W : min(wg, U - 1));
@@ -410,35 +422,39 @@ __global__ __launch_bounds__(kRThreads) void gemv_q4_reg_kernel(GemvArgs a)
                 if (c >= kFirstRagged) scv = chunk_on[c] ? scv : 0.0f;
                 acc[rr] += scv * group_dot_r(s.w[rr * NG + c], xv[c], cr[c]);
             }
+        // res[t] = sum of the wavefront's row t
         if (R == 4) {
-            const float r = reduce4(acc[0], acc[1], acc[R > 2 ? 2 : 0], acc[R > 2 ? 3 : 0], lane);
-            if (lane < 4) res[j0 * 2 + lane] = r;
-        } else {
-            const float r = reduce2(acc[0], acc[1], lane);
+            const float r = reduce4(acc[0], acc[R > 1 ? 1 : 0], acc[R > 2 ? 2 : 0], acc[R > 2 ? 3 : 0], lane);
+            if (lane < 4) res[j0 * 4 + lane] = r;
+        } else if (R == 2) {
+            const float r = reduce2(acc[0], acc[R > 1 ? 1 : 0], lane);
             if (lane < 2) res[j0 * 2 + lane] = r;
+        } else {
+            const float r = reduce1(acc[0]);
+            if (lane == 0) res[j0] = r;
         }
     };
     // Slots of the wavefront: ns = 2 q + r.  Every path below is straight-line in its loads -- none sits under a
     // condition that merges back -- so the wait before a consume counts exactly the loads requested after its slot,
     // and nothing is requested past the end (a wavefront does not retire before its loads have returned).
-    const int ns = (mine + UPS - 1) / UPS, q = ns >> 1;
+    const int ns = (2 * mine + R - 1) / R, q = ns >> 1;
     int s = 0;
 #pragma unroll 1
     for (; s + 2 < 2 * q; s += 2) {                                // refills s + 2, s + 3 <= 2 q - 1 exist
-        consume(sl[0], s * UPS);
-        slot_load(sl[0], (s + 2) * UPS);
-        consume(sl[1], (s + 1) * UPS);
-        slot_load(sl[1], (s + 3) * UPS);
+        consume(sl[0], s);
+        slot_load(sl[0], s + 2);
+        consume(sl[1], s + 1);
+        slot_load(sl[1], s + 3);
     }
     if (q > 0) {
         if (ns & 1) {
-            consume(sl[0], s * UPS);
-            slot_load(sl[0], (s + 2) * UPS);
-            consume(sl[1], (s + 1) * UPS);
-            consume(sl[0], (s + 2) * UPS);
+            consume(sl[0], s);
+            slot_load(sl[0], s + 2);
+            consume(sl[1], s + 1);
+            consume(sl[0], s + 2);
         } else {
-            consume(sl[0], s * UPS);
-            consume(sl[1], (s + 1) * UPS);
+            consume(sl[0], s);
+            consume(sl[1], s + 1);
         }
     } else if (ns == 1) {
         consume(sl[0], 0);
