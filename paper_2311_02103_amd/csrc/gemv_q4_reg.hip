@@ -192,19 +192,24 @@ __device__ __forceinline__ void epi_store(const GemvArgs &a, int i, const RowInf
     }
 }
 
+constexpr int kRSlots = 2;                // slots in flight (the schedule of the stream is written for two)
+
+// Rows per slot, R.  Small slots shorten what is left to compute after the last byte has arrived and let the
+// arithmetic follow the stream more closely; large ones keep more bytes in flight.  Measured on the 7B layer: two rows
+// for rows of up to 4096 columns (four rows: +3 us per layer; one row: +2.7 us), except when a wavefront owns four
+// rows or fewer (the output projection: one row per slot is 0.6 us faster); one row for long rows, whose lanes keep
+// up to 96 registers of x (with two rows the kernel needed 382 registers and spilled to AGPRs: +1.5 us).
 template <int NG>
-struct RegShape {
-    // rows per slot: 8 requests of 16 bytes per lane and slot for short rows; long rows keep 96 registers of x, so
-    // their slots are one row (6 requests) -- with two rows the kernel needed 382 registers and spilled to AGPRs
-    static constexpr int R = NG <= 2 ? 4 : (NG <= 4 ? 2 : 1);
-    static constexpr int NSLOT = 2;                            // slots in flight (the schedule of the stream is written for two)
-};
+constexpr int rows_per_slot(bool few_rows)
+{
+    return NG > 4 ? 1 : (NG <= 2 && few_rows ? 1 : 2);
+}
 
 // grid: x = workgroups (at most one per CU and row), y = row of x
-template <int XMODE, int EPI, int NG>
+template <int XMODE, int EPI, int NG, int R>
 __global__ __launch_bounds__(kRThreads) void gemv_q4_reg_kernel(GemvArgs a)
 {
-    constexpr int R = RegShape<NG>::R, NSLOT = RegShape<NG>::NSLOT, E = R * NG;
+    constexpr int NSLOT = kRSlots, E = R * NG;
     constexpr int kFirstRagged = NG >= 4 ? NG - 2 : NG - 1;        // first chunk of 2048 columns that a row may end in
     __shared__ __align__(16) uint16_t xs[NG * 2048];
     __shared__ float red[kRWaves];
@@ -481,7 +486,11 @@ hipError_t launch_ng(const GemvArgs &a, hipStream_t stream)
     int gx = std::max(1, cus / std::min(a.n, 8));
     gx = std::min(gx, (U + kRWaves - 1) / kRWaves);
     gx = std::max(gx, (U + kRWaves * kRMaxUnits - 1) / (kRWaves * kRMaxUnits));
-    hipLaunchKernelGGL((gemv_q4_reg_kernel<XMODE, EPI, NG>), dim3(gx, a.n), dim3(kRThreads), 0, stream, a);
+    const bool few_rows = 2 * ((U + gx * kRWaves - 1) / (gx * kRWaves)) <= 4;      // rows a wavefront owns
+    if (rows_per_slot<NG>(few_rows) == 1)
+        hipLaunchKernelGGL((gemv_q4_reg_kernel<XMODE, EPI, NG, 1>), dim3(gx, a.n), dim3(kRThreads), 0, stream, a);
+    else
+        hipLaunchKernelGGL((gemv_q4_reg_kernel<XMODE, EPI, NG, 2>), dim3(gx, a.n), dim3(kRThreads), 0, stream, a);
     return hipGetLastError();
 }
 
