@@ -21,6 +21,7 @@
 //     epilogue ever sits between weight loads (memory operations of a wavefront return in order).
 #include <algorithm>
 #include <cstdlib>
+#include <type_traits>
 
 #include "q4_device.h"
 
@@ -439,30 +440,46 @@ __global__ __launch_bounds__(kRThreads) void gemv_q4_reg_kernel(GemvArgs a)
             if (lane == 0) res[j0] = r;
         }
     };
-    // Slots of the wavefront: ns = 2 q + r.  Every path below is straight-line in its loads -- none sits under a
-    // condition that merges back -- so the wait before a consume counts exactly the loads requested after its slot,
-    // and nothing is requested past the end (a wavefront does not retire before its loads have returned).
-    const int ns = (2 * mine + R - 1) / R, q = ns >> 1;
+    // Slots of the wavefront: ns of them, NSLOT in flight.  Every path below is straight-line in its loads -- none
+    // sits under a condition that merges back -- so the wait before a consume counts exactly the loads requested after
+    // its slot, and nothing is requested past the end (a wavefront does not retire before its loads have returned).
+    // Steady state: a step consumes a slot and refills it, NSLOT steps per trip.  What is left after the last full
+    // trip, NSLOT + extra slots, runs through the variant of the tail written for that `extra`: `extra` more steps
+    // with a refill, then one consume for every slot still in flight, in order.
+    const int ns = (2 * mine + R - 1) / R;
     int s = 0;
 #pragma unroll 1
-    for (; s + 2 < 2 * q; s += 2) {                                // refills s + 2, s + 3 <= 2 q - 1 exist
-        consume(sl[0], s);
-        slot_load(sl[0], s + 2);
-        consume(sl[1], s + 1);
-        slot_load(sl[1], s + 3);
-    }
-    if (q > 0) {
-        if (ns & 1) {
-            consume(sl[0], s);
-            slot_load(sl[0], s + 2);
-            consume(sl[1], s + 1);
-            consume(sl[0], s + 2);
-        } else {
-            consume(sl[0], s);
-            consume(sl[1], s + 1);
+    for (; s + 2 * NSLOT <= ns; s += NSLOT) {                      // refills up to slot s + 2 NSLOT - 1 exist
+#pragma unroll
+        for (int t = 0; t < NSLOT; ++t) {
+            consume(sl[t], s + t);
+            slot_load(sl[t], s + t + NSLOT);
         }
-    } else if (ns == 1) {
-        consume(sl[0], 0);
+    }
+    auto tail = [&](auto extra_c) {
+        constexpr int EXTRA = decltype(extra_c)::value;
+#pragma unroll
+        for (int t = 0; t < EXTRA; ++t) {
+            consume(sl[t], s + t);
+            slot_load(sl[t], s + t + NSLOT);
+        }
+#pragma unroll
+        for (int t = EXTRA; t < NSLOT; ++t) consume(sl[t], s + t);
+#pragma unroll
+        for (int t = 0; t < EXTRA; ++t) consume(sl[t], s + t + NSLOT);
+    };
+    const int left = ns - s;                                       // 0 .. 2 NSLOT - 1
+    if (left >= NSLOT) {
+        const int extra = left - NSLOT;
+        if (extra == 0) tail(std::integral_constant<int, 0>{});
+        else if (extra == 1) tail(std::integral_constant<int, 1>{});
+        else if (NSLOT > 2 && extra == 2) tail(std::integral_constant<int, (NSLOT > 2 ? 2 : 0)>{});
+        else if (NSLOT > 3) tail(std::integral_constant<int, (NSLOT > 3 ? 3 : 0)>{});
+    } else {
+        // fewer slots than are in flight (tiny matrices): the slots past the end hold re-read rows and are skipped
+#pragma unroll
+        for (int t = 0; t < NSLOT - 1; ++t)
+            if (t < left) consume(sl[t], t);
     }
 
     stamp(3);
