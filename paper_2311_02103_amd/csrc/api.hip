@@ -462,7 +462,7 @@ relax_status layer_enqueue(const relax_layer_dims &dm, const relax_layer_weights
     if (n == 1 && st.dev == nullptr && attn_mha_split_supported(dm)) {
         const int pos = st.kv_len[0] - st.q_len[0] - st.q_start[0], L = pos + 1;
         int splits = std::min(kAttnMergeSplits, (L + 63) / 64);
-        const int chunk = ((L + splits - 1) / splits + 63) / 64 * 64;
+        const int chunk = ((L + splits - 1) / splits + 31) / 32 * 32;     // whole wavefront steps (16 or 32 tokens), all splits used
         splits = (L + chunk - 1) / chunk;
         o.h = dm.n_heads, o.d = dm.head_dim, o.pos0 = pos;
         o.part = partials, o.part_splits = splits, o.part_stride = dm.head_dim / 2 + 4, o.part_chunk = chunk;

@@ -323,7 +323,7 @@ def test_layer_zero_projections_return_input(rx):
     assert_close(host_bits(y).view(np.float16), wl.f16_bits_to_f32(x), "identity layer", atol=1e-4, rtol=1e-3)
 
 
-@pytest.mark.parametrize("L", [1, 300, 4096])
+@pytest.mark.parametrize("L", [1, 300, 449, 2231, 4096])      # 449: first length with 8 splits; 2231: ragged last step of every split
 def test_llama7b_layer_decode(rx, L):
     shape, cap = wl.LLAMA7B, 4096
     pre = wl.kv_prefill(shape, 1, 1, cap)
