@@ -4,9 +4,10 @@
 // The kernel is bound by HBM, and at the sizes of one decoder layer a launch lasts ~10 us, so what counts besides
 // the stream itself is (a) how few vector instructions a weight costs -- one wavefront per SIMD leaves nothing to
 // hide them behind -- and (b) how short the x-dependent prologue and the tail are:
-//   * one workgroup of four wavefronts per CU; a wavefront walks its units (row pairs the epilogue consumes
-//     together) in slots of R rows, two slots in flight, 16-byte loads (one quantisation group per lane and load,
-//     1 KB contiguous per wavefront);
+//   * one workgroup of four wavefronts per CU; a wavefront walks the rows of its units (row pairs the epilogue
+//     consumes together) in slots of one or two rows, two slots in flight, 16-byte loads (one quantisation group per
+//     lane and load, 1 KB contiguous per wavefront).  Small slots: what a wavefront still has to compute when its last
+//     byte arrives is the arithmetic of the slots in flight;
 //   * the first slots are requested before anything that depends on x; x is staged once per workgroup through LDS
 //     (RMSNorm folded in) and then lives in registers in the packet order of the decode: lane l owns groups
 //     l, l + 64, ... of the row, exactly the groups its weight loads bring, so the loop touches no LDS;
@@ -14,8 +15,8 @@
 //     masks give (1024 + 16 u1, 1024 + 16 u5) and, on w >> 8, nibbles 2,6 and 3,7; v_dot2_f32_f16 contracts a pair with
 //     two x values in fp32 and the offsets leave per group through 1032 sum_A x + 72 sum_B x (exact arithmetic on
 //     integer-valued inputs);
-//   * the R row sums of a slot are reduced together with DPP row operations (a transposing reduction: 2 cross-row
-//     exchanges per slot instead of 6 per row);
+//   * the row sums of a slot are reduced together with DPP row operations (for two rows a transposing reduction;
+//     2 LDS-crossbar exchanges per slot instead of 6 per row);
 //   * inputs of the epilogue (residual values, rotary table entries) are fetched at the very start, results are
 //     parked in LDS and lane j finishes the wavefront's j-th unit after the stream has drained, so no load of the
 //     epilogue ever sits between weight loads (memory operations of a wavefront return in order).
@@ -67,19 +68,6 @@ __device__ __forceinline__ float dpp(float v)
 }
 constexpr int kQuadXor1 = 0xB1, kQuadXor2 = 0x4E, kRowRor4 = 0x124, kRowRor8 = 0x128;
 
-// four per-lane partial sums (rows 0..3 of a slot) -> lane l holds the wavefront total of row l & 3
-__device__ __forceinline__ float reduce4(float v0, float v1, float v2, float v3, int lane)
-{
-    const bool odd = lane & 1, up = lane & 2;
-    const float p = (odd ? v1 : v0) + dpp<kQuadXor1>(odd ? v0 : v1);
-    const float q = (odd ? v3 : v2) + dpp<kQuadXor1>(odd ? v2 : v3);
-    float r = (up ? q : p) + dpp<kQuadXor2>(up ? p : q);
-    r += dpp<kRowRor4>(r);
-    r += dpp<kRowRor8>(r);
-    r += __shfl_xor(r, 16, kWave);
-    r += __shfl_xor(r, 32, kWave);
-    return r;
-}
 // one partial sum -> every lane holds the total
 __device__ __forceinline__ float reduce1(float v)
 {
@@ -429,10 +417,8 @@ __global__ __launch_bounds__(kRThreads) void gemv_q4_reg_kernel(GemvArgs a)
                 acc[rr] += scv * group_dot_r(s.w[rr * NG + c], xv[c], cr[c]);
             }
         // res[t] = sum of the wavefront's row t
-        if (R == 4) {
-            const float r = reduce4(acc[0], acc[R > 1 ? 1 : 0], acc[R > 2 ? 2 : 0], acc[R > 2 ? 3 : 0], lane);
-            if (lane < 4) res[j0 * 4 + lane] = r;
-        } else if (R == 2) {
+        static_assert(R == 1 || R == 2, "slots of one or two rows");
+        if (R == 2) {
             const float r = reduce2(acc[0], acc[R > 1 ? 1 : 0], lane);
             if (lane < 2) res[j0 * 2 + lane] = r;
         } else {
