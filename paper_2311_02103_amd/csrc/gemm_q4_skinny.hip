@@ -268,14 +268,14 @@ struct SkinnyPlan {
     int tiles_m, splits, rounds_per_split;
 };
 
-// Split count: up to four workgroups per CU (what stays resident at once), no k range shorter than 4 rounds (unless k itself is),
+// Split count: about one workgroup per CU when the row tiles alone do not give that many, no k range shorter than 4 rounds (unless k itself is),
 // none longer than kMaxRounds; with 128-wide rounds every task has an even number of them (its scales come in packets of 256 columns).
 SkinnyPlan skinny_plan(int m, int k, int kr)
 {
     SkinnyPlan p;
     p.tiles_m = (m + kRowsPerBlock - 1) / kRowsPerBlock;
     const int rounds = k / kr;
-    int splits = 1024 / p.tiles_m;                        // at most one resident wave of workgroups (4 per CU): no tail round
+    int splits = 256 / p.tiles_m;                         // about one workgroup per CU: more of them in flight measured slower (7B and 70B shapes, 16 and 64 rows)
     const int max_splits = rounds >= 4 ? rounds / 4 : 1, min_splits = (rounds + kMaxRounds - 1) / kMaxRounds;
     splits = splits > max_splits ? max_splits : splits;
     splits = splits < min_splits ? min_splits : splits;
