@@ -134,7 +134,12 @@ relax_status relax_workspace_error(const relax_layer_dims *dims, const void *ws,
  * allow it (k % 32 == 0, 16-byte aligned, everything fits LDS) runs as ONE persistent kernel whose steps are
  * chained by published {value, epoch} words instead of kernel boundaries; 0 uses the step-by-step kernels
  * that serve every shape (the fused kernel is correct but currently slower: each step transition costs a
- * memory round trip under full HBM load).  Unknown name: RELAX_ERR_UNSUPPORTED.                        */
+ * memory round trip under full HBM load).
+ * "fuse_finish" (default 1): in the few-row path (2 <= n <= 128: batched decode, short prefills) the finishing
+ * pass of a split-K matmul also does the light step that follows it (rotary embedding + KV append after QKV,
+ * the RMSNorm after the output projection, and in relax_model_step the first RMSNorm of the next layer after
+ * the down projection: Sec. 4.2 operator fusion); 0 runs them as launches of their own.  Results are identical
+ * bit for bit either way.  Unknown name: RELAX_ERR_UNSUPPORTED.                                          */
 relax_status relax_set_option(const char *name, int32_t value);
 
 /* Bytes of the rotary table for these dims, and the call that fills it on the device

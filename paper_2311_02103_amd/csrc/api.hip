@@ -155,6 +155,7 @@ struct StepTimer {
 
 // Tuning / test switches (relax_set_option).
 int g_opt_fused_decode = 0;
+int g_opt_fuse_finish = 1;                   // few-row path: light steps folded into the finishing pass of the split-K matmuls
 const uint32_t *g_prof_alt_q = nullptr;      // relax_profile_alt_gate_up: another matrix of the gate/up shape
 const uint16_t *g_prof_alt_s = nullptr;
 unsigned long long *g_trace = nullptr;      // relax_profile_trace_buffer
@@ -190,6 +191,10 @@ relax_status relax_set_option(const char *name, int32_t value)
     if (!name) return RELAX_ERR_NULL;
     if (std::strcmp(name, "fused_decode") == 0) {
         g_opt_fused_decode = value;
+        return RELAX_OK;
+    }
+    if (std::strcmp(name, "fuse_finish") == 0) {
+        g_opt_fuse_finish = value;
         return RELAX_OK;
     }
     return RELAX_ERR_UNSUPPORTED;
@@ -363,9 +368,13 @@ relax_status check_layer(const relax_layer_dims &dm, const relax_layer_weights *
 
 // Enqueues one decoder layer.  Everything has been validated; st is the kernel-side ragged descriptor (its device
 // table, if any, already uploaded); base/pl are the layer workspace and its plan.
+// next_norm (optional): the RMSNorm weights of the layer that follows; when the few-row path can, it leaves RMSNorm(out) * next_norm in the
+// workspace and sets *xn_done, and the next call passes xn_ready to skip its own first RMSNorm.
 relax_status layer_enqueue(const relax_layer_dims &dm, const relax_layer_weights *wt, const uint16_t *x, const relax_kv_cache *cache,
-                           const SeqTable &st, int32_t L_max, uint16_t *out, int32_t n, char *base, const WsPlan &pl, hipStream_t st_)
+                           const SeqTable &st, int32_t L_max, uint16_t *out, int32_t n, char *base, const WsPlan &pl, hipStream_t st_,
+                           const uint16_t *next_norm = nullptr, bool xn_ready = false, bool *xn_done = nullptr)
 {
+    if (xn_done) *xn_done = false;
     const int32_t hd = dm.n_heads * dm.head_dim, qkvw = (dm.n_heads + 2 * dm.n_kv_heads) * dm.head_dim;
     const StepTimer timer(st_);
 
@@ -415,23 +424,44 @@ relax_status layer_enqueue(const relax_layer_dims &dm, const relax_layer_weights
         uint16_t *xn = reinterpret_cast<uint16_t *>(base + pl.xn), *qkv = reinterpret_cast<uint16_t *>(base + pl.qkv);
         uint16_t *attn_o = reinterpret_cast<uint16_t *>(base + pl.attn), *act_o = reinterpret_cast<uint16_t *>(base + pl.act);
         float *x1f = reinterpret_cast<float *>(base + pl.x1);
+        // few rows: the finishing pass of a split-K matmul also does the light step that follows it (rotary + append, RMSNorm)
+        hipError_t fuse_err = hipSuccess;
+        auto fused = [&](const uint16_t *xin, const relax_qmat &wq, int epi, uint16_t *o16, float *o32, const void *resid, const SkinnyFuse &f) {
+            if (!g_opt_fuse_finish || n > kSkinnyMaxN || !gemm_skinny_eligible(wq, xin, n, epi) || !gemm_skinny_fuse_ok(wq, epi, f)) return false;
+            fuse_err = launch_gemm_skinny(xin, wq, n, epi, o16, o32, resid, skinny_ws, st_, &f);
+            return true;
+        };
         timer.before(0);
-        if (launch_rmsnorm(x, wt->norm_attn, xn, n, dm.hidden, dm.rms_eps, st_) != hipSuccess) return RELAX_ERR_HIP;
-        if (matmul(xn, wt->wqkv, EPI_F16, qkv, nullptr, nullptr) != hipSuccess) return RELAX_ERR_HIP;
-        if (launch_rope_append(qkv, dm, *cache, st, st_) != hipSuccess) return RELAX_ERR_HIP;
+        if (!xn_ready && launch_rmsnorm(x, wt->norm_attn, xn, n, dm.hidden, dm.rms_eps, st_) != hipSuccess) return RELAX_ERR_HIP;
+        SkinnyFuse fq = {};
+        fq.dm = &dm, fq.cache = cache, fq.st = &st;
+        if (!fused(xn, wt->wqkv, EPI_F16, qkv, nullptr, nullptr, fq)) {
+            if (matmul(xn, wt->wqkv, EPI_F16, qkv, nullptr, nullptr) != hipSuccess) return RELAX_ERR_HIP;
+            if (launch_rope_append(qkv, dm, *cache, st, st_) != hipSuccess) return RELAX_ERR_HIP;
+        }
+        if (fuse_err != hipSuccess) return RELAX_ERR_HIP;
         timer.after(0);
         timer.before(1);
         if (launch_attention(qkv, qkvw, *cache, dm, st, L_max, attn_o, partials, st_) != hipSuccess) return RELAX_ERR_HIP;
         timer.after(1);
         timer.before(2);
-        if (matmul(attn_o, wt->wo, EPI_RESID_F32, nullptr, x1f, x) != hipSuccess) return RELAX_ERR_HIP;
+        SkinnyFuse fo = {};
+        fo.norm_w = wt->norm_ffn, fo.xn = xn, fo.eps = dm.rms_eps;
+        const bool o_fused = fused(attn_o, wt->wo, EPI_RESID_F32, nullptr, x1f, x, fo);
+        if (!o_fused && matmul(attn_o, wt->wo, EPI_RESID_F32, nullptr, x1f, x) != hipSuccess) return RELAX_ERR_HIP;
+        if (fuse_err != hipSuccess) return RELAX_ERR_HIP;
         timer.after(2);
-        if (launch_rmsnorm_f32(x1f, wt->norm_ffn, xn, n, dm.hidden, dm.rms_eps, st_) != hipSuccess) return RELAX_ERR_HIP;
+        if (!o_fused && launch_rmsnorm_f32(x1f, wt->norm_ffn, xn, n, dm.hidden, dm.rms_eps, st_) != hipSuccess) return RELAX_ERR_HIP;
         timer.before(3);                                  // step 3 brackets the gate/up matmul alone (the dominant kernel)
         if (matmul(xn, wt->wgu, EPI_SWIGLU, act_o, nullptr, nullptr) != hipSuccess) return RELAX_ERR_HIP;
         timer.after(3);
         timer.before(4);
-        if (matmul(act_o, wt->wdown, EPI_RESID_F16, out, nullptr, x1f) != hipSuccess) return RELAX_ERR_HIP;
+        SkinnyFuse fd = {};
+        fd.norm_w = next_norm, fd.xn = xn, fd.eps = dm.rms_eps;
+        const bool d_fused = next_norm && xn_done && fused(act_o, wt->wdown, EPI_RESID_F16, out, nullptr, x1f, fd);
+        if (!d_fused && matmul(act_o, wt->wdown, EPI_RESID_F16, out, nullptr, x1f) != hipSuccess) return RELAX_ERR_HIP;
+        if (fuse_err != hipSuccess) return RELAX_ERR_HIP;
+        if (d_fused) *xn_done = true;
         timer.after(4);
         return RELAX_OK;
     }
@@ -598,9 +628,13 @@ relax_status relax_model_step(const relax_model *model, const int32_t *ids, cons
     uint16_t *cur = reinterpret_cast<uint16_t *>(base + mp.xa), *nxt = reinterpret_cast<uint16_t *>(base + mp.xb);
     uint32_t *err = reinterpret_cast<uint32_t *>(base + decode_layer_error_offset());
     if (launch_embed(ids, model->embedding, cur, n, dm.hidden, model->vocab, err, st_) != hipSuccess) return RELAX_ERR_HIP;
+    bool xn_ready = false;
     for (int l = 0; l < model->n_layers; ++l) {
-        rc = layer_enqueue(dm, &model->layers[l], cur, &caches[l], st, L_max, nxt, n, base, mp.layer, st_);
+        const uint16_t *next_norm = l + 1 < model->n_layers ? model->layers[l + 1].norm_attn : nullptr;
+        bool xn_done = false;
+        rc = layer_enqueue(dm, &model->layers[l], cur, &caches[l], st, L_max, nxt, n, base, mp.layer, st_, next_norm, xn_ready, &xn_done);
         if (rc != RELAX_OK) return rc;
+        xn_ready = xn_done;
         uint16_t *t = cur;
         cur = nxt, nxt = t;
     }

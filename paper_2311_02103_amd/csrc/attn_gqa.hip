@@ -54,9 +54,9 @@ __global__ __launch_bounds__(256) void attn_gqa_kernel(const uint16_t *__restric
     half8_t qf[KS];
     {
         const int head = kvh * rep + min(col, rep - 1);
-        const uint16_t *src = q + (size_t)i * q_stride + (size_t)head * D + hf * (D / 2);
+        const uint16_t *src = q + (size_t)i * q_stride + (size_t)head * D + hf * 8;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) qf[ks] = *(const half8_t *)(src + ks * 8);
+        for (int ks = 0; ks < KS; ++ks) qf[ks] = *(const half8_t *)(src + ks * 16);
     }
 
     float16_t O[DB];
@@ -73,9 +73,9 @@ __global__ __launch_bounds__(256) void attn_gqa_kernel(const uint16_t *__restric
     // registers of one tile in flight: the lane's run of its K row (KS packets) and its share of the V tile
     u32x4_t kreg[KS], vreg[VPK];
     auto tile_load = [&](int t0) {                             // rows are clamped to the split: masked later
-        const size_t krow = ((slot_base + min(t0 + col, t_end - 1)) * g + kvh) * D + hf * (D / 2);
+        const size_t krow = ((slot_base + min(t0 + col, t_end - 1)) * g + kvh) * D + hf * 8;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) kreg[ks] = *(const u32x4_t *)(kc + krow + ks * 8);
+        for (int ks = 0; ks < KS; ++ks) kreg[ks] = *(const u32x4_t *)(kc + krow + ks * 16);
 #pragma unroll
         for (int p = 0; p < VPK; ++p) {
             const int pk = lane + p * 64, r = pk / (D / 8), c = pk % (D / 8);

@@ -28,10 +28,10 @@ __device__ inline void load8(const float *p, float *v)
 }
 
 template <typename T>
-__global__ __launch_bounds__(256) void rmsnorm_kernel(const T *x, const uint16_t *w, uint16_t *y, int H, float eps)
+__global__ __launch_bounds__(1024) void rmsnorm_kernel(const T *x, const uint16_t *w, uint16_t *y, int H, float eps)
 {
-    __shared__ float red[4];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    __shared__ float red[16];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, NT = blockDim.x;
     const size_t base = (size_t)blockIdx.x * H;
     const bool vec = (H & 7) == 0 && H <= kNormPasses * 2048 && ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(y) |
                                                                   reinterpret_cast<uintptr_t>(w)) & 15) == 0;
@@ -40,7 +40,7 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const T *x, const uint16_t
     if (vec) {
 #pragma unroll
         for (int p = 0; p < kNormPasses; ++p) {
-            const int c = (p * 256 + tid) * 8;
+            const int c = (p * NT + tid) * 8;
             if (c < H) {
                 load8(x + base + c, v[p]);
 #pragma unroll
@@ -48,7 +48,7 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const T *x, const uint16_t
             }
         }
     } else {
-        for (int c = tid; c < H; c += 256) {
+        for (int c = tid; c < H; c += NT) {
             float t;
             if (sizeof(T) == 2) t = h2f(((const uint16_t *)x)[base + c]);
             else t = ((const float *)x)[base + c];
@@ -58,11 +58,11 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const T *x, const uint16_t
     ss = wave_sum(ss);
     if (lane == 0) red[wave] = ss;
     __syncthreads();
-    const float inv = 1.0f / sqrtf((red[0] + red[1] + red[2] + red[3]) / (float)H + eps);
+    const float inv = 1.0f / sqrtf(block_total(red, NT >> 6) / (float)H + eps);
     if (vec) {
 #pragma unroll
         for (int p = 0; p < kNormPasses; ++p) {
-            const int c = (p * 256 + tid) * 8;
+            const int c = (p * NT + tid) * 8;
             if (c < H) {
                 float wv[8];
                 load8(w + c, wv);
@@ -74,7 +74,7 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const T *x, const uint16_t
             }
         }
     } else {
-        for (int c = tid; c < H; c += 256) {
+        for (int c = tid; c < H; c += NT) {
             float t;
             if (sizeof(T) == 2) t = h2f(((const uint16_t *)x)[base + c]);
             else t = ((const float *)x)[base + c];
@@ -85,13 +85,13 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const T *x, const uint16_t
 
 hipError_t launch_rmsnorm(const uint16_t *x, const uint16_t *w, uint16_t *y, int n, int H, float eps, hipStream_t stream)
 {
-    hipLaunchKernelGGL(rmsnorm_kernel<uint16_t>, dim3(n), dim3(256), 0, stream, x, w, y, H, eps);
+    hipLaunchKernelGGL(rmsnorm_kernel<uint16_t>, dim3(n), dim3(norm_block_threads(H)), 0, stream, x, w, y, H, eps);
     return hipGetLastError();
 }
 
 hipError_t launch_rmsnorm_f32(const float *x, const uint16_t *w, uint16_t *y, int n, int H, float eps, hipStream_t stream)
 {
-    hipLaunchKernelGGL(rmsnorm_kernel<float>, dim3(n), dim3(256), 0, stream, x, w, y, H, eps);
+    hipLaunchKernelGGL(rmsnorm_kernel<float>, dim3(n), dim3(norm_block_threads(H)), 0, stream, x, w, y, H, eps);
     return hipGetLastError();
 }
 

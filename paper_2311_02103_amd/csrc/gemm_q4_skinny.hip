@@ -228,6 +228,161 @@ __global__ __launch_bounds__(256) void skinny_q4_kernel(SkinnyArgs a)
     }
 }
 
+// ---- at most 16 rows: free-running wavefronts ----
+// The x slice of the workgroup's k range (16 rows x at most 4096 columns) sits in LDS for the whole kernel, so the
+// loop has no workgroup barrier: every wavefront streams its own 16-row blocks of the weight matrix, a stage of
+// 16 rows x 512 bytes (1024 columns) at a time with kStages of them in flight, straight into the A operand of
+// v_mfma_f32_16x16x32_f16 (lane = weight row l % 16 and quarter l / 16 of each 512-column block: four 16-byte loads
+// = four scale groups and one 8-byte scale load per block).  The tile has exactly 16 columns, none wasted on 16 rows.
+struct Rows16Args {
+    const uint16_t *x;       // [n,k] fp16
+    const uint32_t *q;       // [m,k/8]
+    const uint16_t *s;       // [m,k/32]
+    float *partial;          // [splits][n][m] fp32
+    int32_t n, m, k;
+    int32_t sps;             // stages (1024 columns) per k split
+    int32_t bpw;             // 16-row blocks per wavefront
+};
+
+constexpr int kStageCols = 1024;
+constexpr int kMaxSps = 4;                   // 16 rows x 4096 columns of x in LDS
+
+// grid: x = workgroup of the split (4 wavefronts x bpw blocks), y = k split
+template <int NSTG, int WAVES>
+__global__ __launch_bounds__(64 * WAVES) void rows16_q4_kernel(Rows16Args a)
+{
+    extern __shared__ __align__(16) uint16_t lds[];       // x slice [16][P]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int r16 = lane & 15, kb = lane >> 4;
+    const int kw = a.k >> 3, G = a.k >> 5;
+    const int k0 = blockIdx.y * a.sps * kStageCols;
+    const int kcols = min(a.k - k0, a.sps * kStageCols);  // columns of this split: a multiple of 256
+    const int nst = (kcols + kStageCols - 1) / kStageCols;
+    const int P = a.sps * kStageCols + 8;                 // row pitch in halfs: 16 rows x 16 bytes cover all banks
+    const int blocks = (a.m + 15) >> 4;
+    const int b0 = (blockIdx.x * WAVES + wave) * a.bpw;
+    const int nblk = max(0, min(blocks, b0 + a.bpw) - b0);
+    const int T = nblk * nst;                             // stages of this wavefront
+
+    // registers of one stage: per 512-column block the lane's 64 bytes of codes (4 groups) and their 4 scales
+    struct Stage {
+        u32x4_t w[8];
+        u32x2_t sc[2];
+    };
+    // stage t = (block b0 + t / nst, columns k0 + 1024 (t % nst) ...).  Addresses are clamped into the matrix; what a
+    // clamped load brings meets zeros of the x slice (columns) or lands in rows / stages that are never stored.
+    auto stage_load = [&](Stage &S, int u, int ks) {
+        const int row = min(min(b0 + u, blocks - 1) * 16 + r16, a.m - 1);
+        const uint32_t *qrow = a.q + (size_t)row * kw + (k0 >> 3);
+        const uint16_t *srow = a.s + (size_t)row * G + (k0 >> 5);
+#pragma unroll
+        for (int jq = 0; jq < 2; ++jq) {
+            int col = ks * kStageCols + jq * 512 + kb * 128;             // first of the lane's 128 columns
+            if (col >= kcols) col = ks * kStageCols + (kb & 1) * 128;   // beyond the split: re-read the stage's first 256 columns
+#if defined(RELAX_R16_STRIP) && RELAX_R16_STRIP == 2
+            S.sc[jq] = u32x2_t{(uint32_t)(size_t)srow, 0u};
+#else
+            S.sc[jq] = *(const u32x2_t *)(srow + (col >> 5));
+#endif
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) S.w[jq * 4 + jj] = *(const u32x4_t *)(qrow + (col >> 3) + jj * 4);
+        }
+    };
+
+    Stage st[NSTG];
+    {
+        int u = 0, ks = 0;
+#pragma unroll
+        for (int i = 0; i < NSTG; ++i) {
+            stage_load(st[i], u, ks);
+            if (++ks == nst) ks = 0, ++u;
+        }
+    }
+
+    // ---- x slice to LDS: 16-byte packets in the order [x0 x4 x1 x5 x2 x6 x3 x7] of the decode, zeros beyond the split ----
+    {
+        const int ppr = nst * (kStageCols / 8);           // packets per row
+        const int total = a.n * ppr;
+        for (int base = 0; base < total; base += 8 * 64 * WAVES) {           // eight packets per thread in flight
+            u32x4_t v[8];
+            int at[8];
+            bool live[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int id = base + j * 64 * WAVES + tid, idc = min(id, total - 1);
+                const int i = idc / ppr, col = (idc - i * ppr) * 8;
+                at[j] = id < total ? i * P + col : -1;
+                live[j] = col < kcols;
+                v[j] = *(const u32x4_t *)(a.x + (size_t)i * a.k + k0 + min(col, kcols - 8));
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                if (at[j] < 0) continue;
+                u32x4_t o;
+                o.x = __builtin_amdgcn_perm(v[j].z, v[j].x, 0x05040100u);
+                o.y = __builtin_amdgcn_perm(v[j].z, v[j].x, 0x07060302u);
+                o.z = __builtin_amdgcn_perm(v[j].w, v[j].y, 0x05040100u);
+                o.w = __builtin_amdgcn_perm(v[j].w, v[j].y, 0x07060302u);
+                if (!live[j]) o = u32x4_t{0u, 0u, 0u, 0u};
+                *(u32x4_t *)(lds + at[j]) = o;
+            }
+        }
+    }
+    __syncthreads();
+
+    float4_t acc[2] = {{0.0f, 0.0f, 0.0f, 0.0f}, {0.0f, 0.0f, 0.0f, 0.0f}};
+    const uint16_t *xb = lds + r16 * P + kb * 128;
+    uint32_t dummy = 0;
+    auto consume = [&](const Stage &S, int ks) {
+#ifdef RELAX_R16_STRIP
+#pragma unroll
+        for (int j = 0; j < 8; ++j) dummy ^= S.w[j].x ^ S.w[j].y ^ S.w[j].z ^ S.w[j].w;
+        dummy ^= S.sc[0].x ^ S.sc[0].y ^ S.sc[1].x ^ S.sc[1].y;
+        return;
+#endif
+#pragma unroll
+        for (int jq = 0; jq < 2; ++jq) {
+            const uint32_t s2[4] = {__builtin_amdgcn_perm(S.sc[jq].x, S.sc[jq].x, 0x01000100u), __builtin_amdgcn_perm(S.sc[jq].x, S.sc[jq].x, 0x03020302u),
+                                    __builtin_amdgcn_perm(S.sc[jq].y, S.sc[jq].y, 0x01000100u), __builtin_amdgcn_perm(S.sc[jq].y, S.sc[jq].y, 0x03020302u)};
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) {
+                const u32x4_t wv = S.w[jq * 4 + jj];
+                const uint32_t word[4] = {wv.x, wv.y, wv.z, wv.w};
+#pragma unroll
+                for (int wd = 0; wd < 4; ++wd) {
+                    const half8_t af = decode_word(word[wd], s2[jj]);
+                    const half8_t bf = *(const half8_t *)(xb + ks * kStageCols + jq * 512 + jj * 32 + wd * 8);
+                    acc[wd & 1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(af, bf, acc[wd & 1], 0, 0, 0);
+                }
+            }
+        }
+    };
+    // the block's tile: lane holds weight rows 4 (l / 16) .. + 4 of the block for x row l % 16
+    auto flush = [&](int u) {
+        const int row = (b0 + u) * 16 + kb * 4;
+        if (r16 < a.n && row < a.m)                        // m % 4 == 0 is checked by the launcher
+            *(float4_t *)(a.partial + ((size_t)blockIdx.y * a.n + r16) * a.m + row) = acc[0] + acc[1] + (float)dummy;
+        acc[0] = acc[1] = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
+    };
+
+    int u = 0, ks = 0;                                    // (block, stage) of the stage to consume next
+    int lu = 0, lks = 0;                                  // ... of the stage to load next
+#pragma unroll
+    for (int i = 0; i < NSTG; ++i)
+        if (++lks == nst) lks = 0, ++lu;
+    for (int t = 0; t < T; t += NSTG) {
+#pragma unroll
+        for (int i = 0; i < NSTG; ++i) {
+            if (t + i < T) {
+                consume(st[i], ks);
+                if (++ks == nst) flush(u), ks = 0, ++u;
+            }
+            stage_load(st[i], min(lu, max(nblk, 1) - 1), lks);
+            if (++lks == nst) lks = 0, ++lu;
+        }
+    }
+}
+
 // out = epilogue(sum over splits, in order, of partial[s][i][r]); one thread per 4 consecutive r (SwiGLU: 4 gate columns)
 template <int EPI>
 __global__ __launch_bounds__(256) void skinny_finish_kernel(const float *__restrict__ partial, int splits, int n, int m,
@@ -262,6 +417,144 @@ __global__ __launch_bounds__(256) void skinny_finish_kernel(const float *__restr
         for (int e = 0; e < 4; ++e) v[e] = v[e] / (1.0f + __expf(-v[e])) * u[e];
     }
     *(u32x2_t *)(out_f16 + at) = u32x2_t{f2h(v[0]) | ((uint32_t)f2h(v[1]) << 16), f2h(v[2]) | ((uint32_t)f2h(v[3]) << 16)};
+}
+
+// ---- finishing kernels that also do the light step that follows the matmul in the layer (Sec. 4.2: the element-wise
+// ---- neighbours of a matmul fold into it; here into its finishing pass, one launch less each) ----
+
+__device__ __forceinline__ void sum_splits8(const float *partial, int splits, size_t split_stride, size_t at, float *v)
+{
+    float4_t a = {0.0f, 0.0f, 0.0f, 0.0f}, b = {0.0f, 0.0f, 0.0f, 0.0f};
+    int s = 0;
+    for (; s + 4 <= splits; s += 4) {                      // four splits in flight, added in order
+        float4_t ta[4], tb[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const float *p = partial + (size_t)(s + u) * split_stride + at;
+            ta[u] = *(const float4_t *)p, tb[u] = *(const float4_t *)(p + 4);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) a += ta[u], b += tb[u];
+    }
+    for (; s < splits; ++s) {
+        const float *p = partial + (size_t)s * split_stride + at;
+        a += *(const float4_t *)p;
+        b += *(const float4_t *)(p + 4);
+    }
+    v[0] = a.x, v[1] = a.y, v[2] = a.z, v[3] = a.w, v[4] = b.x, v[5] = b.y, v[6] = b.z, v[7] = b.w;
+}
+__device__ __forceinline__ void unpack8h(const u32x4_t raw, float *v)
+{
+    const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) v[2 * j] = h2f((uint16_t)(w[j] & 0xFFFFu)), v[2 * j + 1] = h2f((uint16_t)(w[j] >> 16));
+}
+__device__ __forceinline__ u32x4_t pack8h(const float *v)
+{
+    return u32x4_t{f2h(v[0]) | ((uint32_t)f2h(v[1]) << 16), f2h(v[2]) | ((uint32_t)f2h(v[3]) << 16),
+                   f2h(v[4]) | ((uint32_t)f2h(v[5]) << 16), f2h(v[6]) | ((uint32_t)f2h(v[7]) << 16)};
+}
+
+constexpr int kFuseNormPasses = 4;           // rows of up to 4 x 2048 columns stay in registers between the sum and the scaling
+
+// Residual epilogue + RMSNorm of the result, one workgroup per row (m <= 8192, m % 8 == 0):
+//   EPI_RESID_F32: y = x(fp16 resid) + sum -> out_f32;             xn = RMSNorm(y) * norm_w
+//   EPI_RESID_F16: y = fp16(sum + resid(fp32)) -> out_f16;         xn = RMSNorm(y) * norm_w (of the rounded values: what the next layer reads)
+// Same arithmetic, element by element and in the same order, as the plain finishing kernel followed by the row-norm kernel.
+template <int EPI>
+__global__ __launch_bounds__(1024) void skinny_finish_norm_kernel(const float *__restrict__ partial, int splits, int n, int m,
+                                                                 uint16_t *__restrict__ out_f16, float *__restrict__ out_f32,
+                                                                 const void *__restrict__ resid, const uint16_t *__restrict__ norm_w,
+                                                                 uint16_t *__restrict__ xn, float eps)
+{
+    __shared__ float red[16];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, i = blockIdx.x, T = blockDim.x;
+    const size_t base = (size_t)i * m, split_stride = (size_t)n * m;
+    float v[kFuseNormPasses][8];
+    float ss = 0.0f;
+#pragma unroll
+    for (int p = 0; p < kFuseNormPasses; ++p) {
+        const int c = (p * T + tid) * 8;
+        if (c < m) {
+            sum_splits8(partial, splits, split_stride, base + c, v[p]);
+            if (EPI == EPI_RESID_F32) {
+                float xr[8];
+                unpack8h(*(const u32x4_t *)((const uint16_t *)resid + base + c), xr);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[p][e] = xr[e] + v[p][e];
+                *(float4_t *)(out_f32 + base + c) = float4_t{v[p][0], v[p][1], v[p][2], v[p][3]};
+                *(float4_t *)(out_f32 + base + c + 4) = float4_t{v[p][4], v[p][5], v[p][6], v[p][7]};
+            } else {
+                const float4_t r0 = *(const float4_t *)((const float *)resid + base + c), r1 = *(const float4_t *)((const float *)resid + base + c + 4);
+                v[p][0] += r0.x, v[p][1] += r0.y, v[p][2] += r0.z, v[p][3] += r0.w;
+                v[p][4] += r1.x, v[p][5] += r1.y, v[p][6] += r1.z, v[p][7] += r1.w;
+                const u32x4_t o = pack8h(v[p]);
+                *(u32x4_t *)(out_f16 + base + c) = o;
+                unpack8h(o, v[p]);
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) ss += v[p][e] * v[p][e];
+        }
+    }
+    ss = wave_sum(ss);
+    if (lane == 0) red[wave] = ss;
+    __syncthreads();
+    const float inv = 1.0f / sqrtf(block_total(red, T >> 6) / (float)m + eps);
+#pragma unroll
+    for (int p = 0; p < kFuseNormPasses; ++p) {
+        const int c = (p * T + tid) * 8;
+        if (c < m) {
+            float wv[8], o[8];
+            unpack8h(*(const u32x4_t *)(norm_w + c), wv);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = v[p][e] * inv * wv[e];
+            *(u32x4_t *)(xn + base + c) = pack8h(o);
+        }
+    }
+}
+
+// Plain fp16 epilogue of the QKV matmul + rotary embedding of the q and k heads + append of k (rotated) and v to the
+// cache at each row's position.  grid (row, slice of the heads); a thread owns eight consecutive rotation pairs of one
+// head, or eight v elements.  q goes to its place in qkv (the attention kernel reads it there), k and v to the cache only.
+__global__ __launch_bounds__(256) void skinny_finish_rope_kernel(const float *__restrict__ partial, int splits, int n, int m,
+                                                                 uint16_t *__restrict__ qkv, uint16_t *__restrict__ kc, uint16_t *__restrict__ vc,
+                                                                 const float *__restrict__ rope, int h, int g, int d, int cap, SeqTable st)
+{
+    const int i = blockIdx.x;
+    const RowInfo ri = row_info(st, i);
+    const int hd2 = d >> 1, per_head = hd2 >> 3;
+    const size_t base = (size_t)i * m, split_stride = (size_t)n * m;
+    const size_t tok = ((size_t)ri.slot * cap + ri.pos) * (size_t)(g * d);
+    const int items = (h + g) * per_head;
+    for (int u = blockIdx.y * 256 + threadIdx.x; u < items; u += gridDim.y * 256) {
+        const int j = u / per_head, t0 = (u - j * per_head) * 8;
+        float a[8], b[8];
+        sum_splits8(partial, splits, split_stride, base + j * d + t0, a);
+        sum_splits8(partial, splits, split_stride, base + j * d + t0 + hd2, b);
+        unpack8h(pack8h(a), a);                            // the fp16 rounding of the plain epilogue comes first
+        unpack8h(pack8h(b), b);
+        const float *cs = rope + ((size_t)ri.pos * hd2 + t0) * 2;
+        float oa[8], ob[8];
+#pragma unroll
+        for (int e = 0; e < 8; e += 2) {
+            const float4_t c2 = *(const float4_t *)(cs + e * 2);          // cos, sin of t0 + e and t0 + e + 1
+            oa[e] = a[e] * c2.x - b[e] * c2.y, oa[e + 1] = a[e + 1] * c2.z - b[e + 1] * c2.w;
+            ob[e] = a[e] * c2.y + b[e] * c2.x, ob[e + 1] = a[e + 1] * c2.w + b[e + 1] * c2.z;
+        }
+        const u32x4_t va = pack8h(oa), vb = pack8h(ob);
+        if (j < h) {
+            *(u32x4_t *)(qkv + base + j * d + t0) = va;
+            *(u32x4_t *)(qkv + base + j * d + t0 + hd2) = vb;
+        } else {
+            *(u32x4_t *)(kc + tok + (size_t)(j - h) * d + t0) = va;
+            *(u32x4_t *)(kc + tok + (size_t)(j - h) * d + t0 + hd2) = vb;
+        }
+    }
+    for (int e = (blockIdx.y * 256 + threadIdx.x) * 8; e < g * d; e += gridDim.y * 256 * 8) {
+        float v[8];
+        sum_splits8(partial, splits, split_stride, base + (size_t)(h + g) * d + e, v);
+        *(u32x4_t *)(vc + tok + e) = pack8h(v);
+    }
 }
 
 struct SkinnyPlan {
@@ -301,6 +594,48 @@ hipError_t launch_skinny(const SkinnyArgs &a, dim3 grid, hipStream_t stream)
     return hipGetLastError();
 }
 
+struct Rows16Plan {
+    int sps, splits, wgs, bpw;
+};
+
+// k splits of sps stages, wgs workgroups per split (about one workgroup per CU in all), bpw blocks per wavefront.  The cost of a candidate
+// is what its busiest wavefront does, in stages: its blocks (codes, plus the partial tile it writes per block) and the start of a workgroup
+// (the x slice grows with sps); fewer, longer splits win ties (fewer partial tiles to add up).
+Rows16Plan rows16_plan(int m, int k, int waves)
+{
+    const int blocks = (m + 15) / 16, total = (k + kStageCols - 1) / kStageCols, cus = 256;
+    static const int force_sps = getenv("RELAX_R16_SPS") ? atoi(getenv("RELAX_R16_SPS")) : 0;
+    static const int force_cus = getenv("RELAX_R16_CUS") ? atoi(getenv("RELAX_R16_CUS")) : 0;
+    Rows16Plan best = {};
+    double best_cost = 1e30;
+    for (int sps = kMaxSps; sps >= 1; --sps) {
+        if (force_sps && sps != force_sps) continue;
+        Rows16Plan p;
+        p.sps = sps;
+        p.splits = (total + sps - 1) / sps;
+        p.wgs = std::max(1, (force_cus ? force_cus : cus) / p.splits);
+        p.bpw = (blocks + waves * p.wgs - 1) / (waves * p.wgs);
+        p.wgs = (blocks + waves * p.bpw - 1) / (waves * p.bpw);
+        const double cost = p.bpw * (sps + 0.25) + 1.5 + 0.25 * sps;
+        if (cost < best_cost) best_cost = cost, best = p;
+    }
+    return best;
+}
+
+template <int NSTG, int WAVES>
+hipError_t launch_rows16(const Rows16Args &a, dim3 grid, hipStream_t stream)
+{
+    const size_t lds = (size_t)16 * (a.sps * kStageCols + 8) * sizeof(uint16_t);
+    static bool attr_done = false;
+    if (!attr_done) {
+        if (hipFuncSetAttribute((const void *)rows16_q4_kernel<NSTG, WAVES>, hipFuncAttributeMaxDynamicSharedMemorySize, 16 * (kMaxSps * kStageCols + 8) * 2) != hipSuccess)
+            return hipErrorInvalidValue;
+        attr_done = true;
+    }
+    hipLaunchKernelGGL((rows16_q4_kernel<NSTG, WAVES>), grid, dim3(64 * WAVES), lds, stream, a);
+    return hipGetLastError();
+}
+
 }  // namespace
 
 bool gemm_skinny_eligible(const relax_qmat &w, const void *x, int n, int epi)
@@ -321,29 +656,73 @@ size_t gemm_skinny_partial_floats(int m, int k, int n)
         const size_t v = (size_t)skinny_plan(m, k, kr).splits * (size_t)n * (size_t)m;
         worst = v > worst ? v : worst;
     }
+    if (n <= 16) {
+        const size_t v = (size_t)std::max(rows16_plan(m, k, 4).splits, rows16_plan(m, k, 8).splits) * (size_t)n * (size_t)m;
+        worst = v > worst ? v : worst;
+    }
     return worst;
 }
 
+bool gemm_skinny_fuse_ok(const relax_qmat &w, int epi, const SkinnyFuse &f)
+{
+    if (epi == EPI_RESID_F32 || epi == EPI_RESID_F16)
+        return f.norm_w && f.xn && w.m % 8 == 0 && w.m <= kFuseNormPasses * 2048 &&
+               ((reinterpret_cast<uintptr_t>(f.norm_w) | reinterpret_cast<uintptr_t>(f.xn)) & 15) == 0;
+    if (epi == EPI_F16)
+        return f.dm && f.cache && f.st && f.dm->head_dim % 16 == 0 && w.m == (f.dm->n_heads + 2 * f.dm->n_kv_heads) * f.dm->head_dim &&
+               ((reinterpret_cast<uintptr_t>(f.cache->k) | reinterpret_cast<uintptr_t>(f.cache->v) | reinterpret_cast<uintptr_t>(f.cache->rope)) & 15) == 0;
+    return false;
+}
+
 hipError_t launch_gemm_skinny(const uint16_t *x, const relax_qmat &w, int n, int epi, uint16_t *out_f16, float *out_f32, const void *resid,
-                              float *partial, hipStream_t stream)
+                              float *partial, hipStream_t stream, const SkinnyFuse *fuse)
 {
     const SkinnyPlan pl = skinny_plan(w.m, w.k, skinny_round(n));
     SkinnyArgs a;
     a.x = x, a.q = w.q, a.s = w.s, a.partial = partial, a.n = n, a.m = w.m, a.k = w.k, a.rounds_per_split = pl.rounds_per_split;
     dim3 grid(pl.tiles_m, pl.splits);
     hipError_t e;
-    if (n <= 16) e = launch_skinny<1, 16, 256>(a, grid, stream);
+    int splits = pl.splits;
+    static const bool old16 = getenv("RELAX_ROWS16") == nullptr;
+    static const int nstg = getenv("RELAX_R16_NSTG") ? atoi(getenv("RELAX_R16_NSTG")) : 4;
+    if (n <= 16 && !old16) {
+        static const int waves = getenv("RELAX_R16_WAVES") ? atoi(getenv("RELAX_R16_WAVES")) : 8;
+        const Rows16Plan rp = rows16_plan(w.m, w.k, waves);
+        Rows16Args ra;
+        ra.x = x, ra.q = w.q, ra.s = w.s, ra.partial = partial, ra.n = n, ra.m = w.m, ra.k = w.k, ra.sps = rp.sps, ra.bpw = rp.bpw;
+        splits = rp.splits;
+        const dim3 g16(rp.wgs, rp.splits);
+        if (waves == 4) e = nstg == 3 ? launch_rows16<3, 4>(ra, g16, stream) : nstg == 2 ? launch_rows16<2, 4>(ra, g16, stream) : launch_rows16<4, 4>(ra, g16, stream);
+        else e = nstg == 3 ? launch_rows16<3, 8>(ra, g16, stream) : nstg == 2 ? launch_rows16<2, 8>(ra, g16, stream) : launch_rows16<4, 8>(ra, g16, stream);
+    }
+    else if (n <= 16) e = launch_skinny<1, 16, 256>(a, grid, stream);
     else if (n <= 32) e = launch_skinny<1, 32, 256>(a, grid, stream);
     else if (n <= 64) e = launch_skinny<2, 64, 256>(a, grid, stream);
     else e = launch_skinny<4, 128, 128>(a, grid, stream);
     if (e != hipSuccess) return e;
+    if (fuse) {                                           // the caller checked gemm_skinny_fuse_ok
+        if (epi == EPI_RESID_F32)
+            hipLaunchKernelGGL(skinny_finish_norm_kernel<EPI_RESID_F32>, dim3(n), dim3(norm_block_threads(w.m)), 0, stream, partial, splits, n, w.m, out_f16, out_f32, resid,
+                               fuse->norm_w, fuse->xn, fuse->eps);
+        else if (epi == EPI_RESID_F16)
+            hipLaunchKernelGGL(skinny_finish_norm_kernel<EPI_RESID_F16>, dim3(n), dim3(norm_block_threads(w.m)), 0, stream, partial, splits, n, w.m, out_f16, out_f32, resid,
+                               fuse->norm_w, fuse->xn, fuse->eps);
+        else if (epi == EPI_F16) {
+            const relax_layer_dims &dm = *fuse->dm;
+            const int items = (dm.n_heads + dm.n_kv_heads) * (dm.head_dim / 16);
+            hipLaunchKernelGGL(skinny_finish_rope_kernel, dim3(n, (items + 255) / 256), dim3(256), 0, stream, partial, splits, n, w.m, out_f16, fuse->cache->k,
+                               fuse->cache->v, fuse->cache->rope, dm.n_heads, dm.n_kv_heads, dm.head_dim, dm.kv_capacity, *fuse->st);
+        }
+        else return hipErrorInvalidValue;
+        return hipGetLastError();
+    }
     const int width = epi == EPI_SWIGLU ? w.m / 2 : w.m;
     const unsigned fb = (unsigned)(((size_t)n * width / 4 + 255) / 256);
     switch (epi) {
-    case EPI_F16: hipLaunchKernelGGL(skinny_finish_kernel<EPI_F16>, dim3(fb), dim3(256), 0, stream, partial, pl.splits, n, w.m, out_f16, out_f32, resid); break;
-    case EPI_RESID_F32: hipLaunchKernelGGL(skinny_finish_kernel<EPI_RESID_F32>, dim3(fb), dim3(256), 0, stream, partial, pl.splits, n, w.m, out_f16, out_f32, resid); break;
-    case EPI_RESID_F16: hipLaunchKernelGGL(skinny_finish_kernel<EPI_RESID_F16>, dim3(fb), dim3(256), 0, stream, partial, pl.splits, n, w.m, out_f16, out_f32, resid); break;
-    case EPI_SWIGLU: hipLaunchKernelGGL(skinny_finish_kernel<EPI_SWIGLU>, dim3(fb), dim3(256), 0, stream, partial, pl.splits, n, w.m, out_f16, out_f32, resid); break;
+    case EPI_F16: hipLaunchKernelGGL(skinny_finish_kernel<EPI_F16>, dim3(fb), dim3(256), 0, stream, partial, splits, n, w.m, out_f16, out_f32, resid); break;
+    case EPI_RESID_F32: hipLaunchKernelGGL(skinny_finish_kernel<EPI_RESID_F32>, dim3(fb), dim3(256), 0, stream, partial, splits, n, w.m, out_f16, out_f32, resid); break;
+    case EPI_RESID_F16: hipLaunchKernelGGL(skinny_finish_kernel<EPI_RESID_F16>, dim3(fb), dim3(256), 0, stream, partial, splits, n, w.m, out_f16, out_f32, resid); break;
+    case EPI_SWIGLU: hipLaunchKernelGGL(skinny_finish_kernel<EPI_SWIGLU>, dim3(fb), dim3(256), 0, stream, partial, splits, n, w.m, out_f16, out_f32, resid); break;
     default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

@@ -129,6 +129,15 @@ bool gemv_reg_eligible(const GemvArgs &a);
 bool gemv_merge_eligible(const GemvArgs &a);
 hipError_t launch_gemv_reg(const GemvArgs &a, int xmode, int epi, hipStream_t stream);
 
+// Workgroup size of the row-norm kernels (one workgroup per row, eight elements per thread and pass) and the order in which the
+// per-wavefront sums of squares are added: shared by the stand-alone kernels and the finishing pass that folds the norm in.
+inline int norm_block_threads(int H) { return H >= 8192 ? 1024 : H >= 4096 ? 512 : 256; }
+__device__ inline float block_total(const float *red, int waves)
+{
+    float t = 0.0f;
+    for (int w = 0; w < waves; ++w) t += red[w];
+    return t;
+}
 hipError_t launch_rmsnorm(const uint16_t *x, const uint16_t *w, uint16_t *y, int n, int H, float eps, hipStream_t stream);
 hipError_t launch_rmsnorm_f32(const float *x, const uint16_t *w, uint16_t *y, int n, int H, float eps, hipStream_t stream);
 
@@ -142,8 +151,20 @@ constexpr int kSkinnyMinN = 2;       // rows from which the layer takes the matr
 constexpr int kSkinnyMaxN = 128;     // rows up to which the few-row kernel replaces the tiled GEMM
 bool gemm_skinny_eligible(const relax_qmat &w, const void *x, int n, int epi);
 size_t gemm_skinny_partial_floats(int m, int k, int n);
+// Optional light step folded into the finishing pass of the few-row matmul (one launch less):
+//   residual epilogues: also xn = RMSNorm(result) * norm_w (what the next matmul of the layer, or of the next layer, reads);
+//   EPI_F16 on a QKV matrix: rotary embedding of q and k, k and v appended to the cache (q alone is written to out_f16).
+struct SkinnyFuse {
+    const uint16_t *norm_w;
+    uint16_t *xn;
+    float eps;
+    const relax_layer_dims *dm;
+    const relax_kv_cache *cache;
+    const SeqTable *st;
+};
+bool gemm_skinny_fuse_ok(const relax_qmat &w, int epi, const SkinnyFuse &f);
 hipError_t launch_gemm_skinny(const uint16_t *x, const relax_qmat &w, int n, int epi, uint16_t *out_f16, float *out_f32, const void *resid,
-                              float *partial, hipStream_t stream);
+                              float *partial, hipStream_t stream, const SkinnyFuse *fuse = nullptr);
 hipError_t launch_rope_append(uint16_t *qkv, const relax_layer_dims &dm, const relax_kv_cache &cache,
                               const SeqTable &st, hipStream_t stream);
 hipError_t launch_rope_table(const relax_layer_dims &dm, float *table, hipStream_t stream);

@@ -133,3 +133,34 @@ def test_70b_shape_batched_decode_one_layer(rx):
     dev.v[0].copy_(torch.from_numpy(vb.view(np.int16)).view(torch.float16).cuda())
     Ko, Vo = [f32_cache(kb)], [f32_cache(vb)]
     check_step(dev, od, ol, mt, wl.token_ids(17, B, V), [1] * B, kv, list(range(B)), Ko, Vo, "70B-shape batched decode")
+
+
+def test_few_row_path_with_and_without_folded_finishing_steps(rx):
+    """The few-row matrix path folds rotary + append and the RMSNorms into the finishing pass of its split-K matmuls
+    (and the first RMSNorm of a layer into the last finishing pass of the layer before).  The folded kernels repeat the
+    arithmetic of the separate ones element by element, so logits, picks and caches must be identical bit for bit."""
+    shape, V, nl, B, cap = wl.LLAMA7B, 3000, 3, 5, 64
+    dev, od, ol, mt = build_models(shape, nl, V, seed=21, cap=cap, slots=B, n_max=32, B_max=B, distinct_layers=2)
+    q = [int(v) for v in wl.uniform_lengths(21, B, 1, 6)]
+    ids = torch.from_numpy(wl.token_ids(21, sum(q), V)).cuda()
+    results = []
+    try:
+        for folded in (0, 1):
+            rx.check(rx.relax_set_option("fuse_finish", folded))
+            for l in range(nl):
+                dev.k[l].zero_()
+                dev.v[l].zero_()
+            lg1, nx1 = dev.step(ids, q, q, list(range(B)))
+            lg1, nx1 = lg1.clone(), nx1.clone()
+            lg2, nx2 = dev.step(nx1, [1] * B, [a + 1 for a in q], list(range(B)))
+            torch.cuda.synchronize()
+            results.append((lg1.cpu(), nx1.cpu(), lg2.clone().cpu(), nx2.clone().cpu(), [k.clone().cpu() for k in dev.k], [v.clone().cpu() for v in dev.v]))
+    finally:
+        rx.check(rx.relax_set_option("fuse_finish", 1))      # back to the default
+    a, b = results
+    for name, x, y in (("prefill logits", a[0], b[0]), ("prefill picks", a[1], b[1]), ("decode logits", a[2], b[2]), ("decode picks", a[3], b[3])):
+        assert torch.equal(x.view(torch.int16) if x.dtype == torch.float16 else x, y.view(torch.int16) if y.dtype == torch.float16 else y), name
+    for l in range(nl):
+        assert torch.equal(a[4][l].view(torch.int16), b[4][l].view(torch.int16)), "K cache layer %d" % l
+        assert torch.equal(a[5][l].view(torch.int16), b[5][l].view(torch.int16)), "V cache layer %d" % l
+    assert float(a[0].float().abs().max()) > 0 and torch.isfinite(a[2].float()).all()
