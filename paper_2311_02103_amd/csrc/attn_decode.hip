@@ -12,14 +12,13 @@
 
 namespace relax {
 
-static int clampv() { static int v = getenv("RELAX_ATTN_CLAMP") ? atoi(getenv("RELAX_ATTN_CLAMP")) : 512; return v; }
 AttnPlan attn_plan(int32_t n, int32_t g, int32_t L_max)
 {
     long long total = (long long)n * g * (L_max > 0 ? L_max : 1);
     long long c = (total + 1023) / 1024;
     c = ((c + 63) / 64) * 64;
     if (c < 64) c = 64;
-    if (c > clampv()) c = clampv();
+    if (c > 512) c = 512;
     AttnPlan p;
     p.chunk = (int32_t)c;
     p.splits = (L_max + p.chunk - 1) / p.chunk;
@@ -33,7 +32,7 @@ size_t attn_partial_floats(const relax_layer_dims &dm, int32_t n_max, int32_t L_
 {
     const size_t h = dm.n_heads, rep = dm.n_heads / dm.n_kv_heads;
     size_t a = rep * 1024 + (size_t)n_max * h;
-    size_t b = (size_t)n_max * h * (size_t)((L_max + clampv() - 1) / clampv());
+    size_t b = (size_t)n_max * h * (size_t)((L_max + 511) / 512);
     return (a > b ? a : b) * (size_t)(dm.head_dim + 2);
 }
 

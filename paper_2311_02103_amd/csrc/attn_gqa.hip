@@ -29,7 +29,7 @@ constexpr int kGqaMaxRep = 16;       // query heads per KV head this kernel serv
 
 // grid: x = KV head, y = split along L, z = row of the call
 template <int D>
-__global__ __launch_bounds__(256) void attn_gqa_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict__ kc,
+__global__ __launch_bounds__(256, 2) void attn_gqa_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict__ kc,
                                                        const uint16_t *__restrict__ vc, float *__restrict__ part, SeqTable st,
                                                        int h, int g, int cap, int chunk, int splits, int q_stride)
 {
@@ -50,14 +50,17 @@ __global__ __launch_bounds__(256) void attn_gqa_kernel(const uint16_t *__restric
     const int col = lane & 31, hf = lane >> 5;
     const float scale = 1.0f / sqrtf((float)D);
 
-    // ---- Q fragments: lane owns head (col) of the group, 8 d-values per k step out of its half of the head dimension ----
-    half8_t qf[KS];
-    {
+    // ---- Q fragments: lane owns head (col) of the group; k step ks pairs d = 16 ks + 8 hf .. + 8 of K and Q.
+    // The same for every wavefront and every tile: kept in LDS (KS x 64 lanes x 16 bytes), not in registers, so that
+    // two workgroups fit a CU ----
+    __shared__ __align__(16) uint16_t q_lds[KS * 64 * 8];
+    if (wave == 0) {
         const int head = kvh * rep + min(col, rep - 1);
         const uint16_t *src = q + (size_t)i * q_stride + (size_t)head * D + hf * 8;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) qf[ks] = *(const half8_t *)(src + ks * 16);
+        for (int ks = 0; ks < KS; ++ks) *(half8_t *)(q_lds + (ks * 64 + lane) * 8) = *(const half8_t *)(src + ks * 16);
     }
+    __syncthreads();
 
     float16_t O[DB];
 #pragma unroll
@@ -91,7 +94,7 @@ __global__ __launch_bounds__(256) void attn_gqa_kernel(const uint16_t *__restric
 #pragma unroll
         for (int v = 0; v < 16; ++v) S[v] = 0.0f;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) S = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8_t, kreg[ks]), qf[ks], S, 0, 0, 0);
+        for (int ks = 0; ks < KS; ++ks) S = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8_t, kreg[ks]), *(const half8_t *)(q_lds + (ks * 64 + lane) * 8), S, 0, 0, 0);
 #pragma unroll
         for (int p = 0; p < VPK; ++p) {
             const int pk = lane + p * 64, r = pk / (D / 8), c = pk % (D / 8);
