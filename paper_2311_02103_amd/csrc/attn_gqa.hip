@@ -5,9 +5,9 @@
 //
 // A workgroup is one (row, KV head, split along L); each of its four wavefronts walks its own 32-token tiles with no
 // workgroup barrier in the loop:
-//   S^T[t, head] = K[t, :] . Q[head, :]   A operand = the K tile straight from global memory (lane = token t % 32,
-//                                          half l / 32 of the head dimension: one contiguous run per lane), B operand
-//                                          = the query heads, held in registers for the whole kernel;
+//   S^T[t, head] = K[t, :] . Q[head, :]   A operand = the K tile straight from global memory (lane = token t % 32;
+//                                          k step ks takes d = 16 ks + 8 (l / 32) .. + 8), B operand = the query
+//                                          heads in the same order, read from LDS (written once per workgroup);
 //   online softmax per column (= per head) inside a lane plus one exchange with lane ^ 32;
 //   O^T[d, head] += V^T[d, t] . P^T[t, head]   A operand = the V tile, staged in a wavefront-private LDS region and
 //                                          read with the LDS transpose read of gfx950 (lane r of a 16-lane block
