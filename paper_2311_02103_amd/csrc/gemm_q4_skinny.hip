@@ -228,161 +228,6 @@ __global__ __launch_bounds__(256) void skinny_q4_kernel(SkinnyArgs a)
     }
 }
 
-// ---- at most 16 rows: free-running wavefronts ----
-// The x slice of the workgroup's k range (16 rows x at most 4096 columns) sits in LDS for the whole kernel, so the
-// loop has no workgroup barrier: every wavefront streams its own 16-row blocks of the weight matrix, a stage of
-// 16 rows x 512 bytes (1024 columns) at a time with kStages of them in flight, straight into the A operand of
-// v_mfma_f32_16x16x32_f16 (lane = weight row l % 16 and quarter l / 16 of each 512-column block: four 16-byte loads
-// = four scale groups and one 8-byte scale load per block).  The tile has exactly 16 columns, none wasted on 16 rows.
-struct Rows16Args {
-    const uint16_t *x;       // [n,k] fp16
-    const uint32_t *q;       // [m,k/8]
-    const uint16_t *s;       // [m,k/32]
-    float *partial;          // [splits][n][m] fp32
-    int32_t n, m, k;
-    int32_t sps;             // stages (1024 columns) per k split
-    int32_t bpw;             // 16-row blocks per wavefront
-};
-
-constexpr int kStageCols = 1024;
-constexpr int kMaxSps = 4;                   // 16 rows x 4096 columns of x in LDS
-
-// grid: x = workgroup of the split (4 wavefronts x bpw blocks), y = k split
-template <int NSTG, int WAVES>
-__global__ __launch_bounds__(64 * WAVES) void rows16_q4_kernel(Rows16Args a)
-{
-    extern __shared__ __align__(16) uint16_t lds[];       // x slice [16][P]
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int r16 = lane & 15, kb = lane >> 4;
-    const int kw = a.k >> 3, G = a.k >> 5;
-    const int k0 = blockIdx.y * a.sps * kStageCols;
-    const int kcols = min(a.k - k0, a.sps * kStageCols);  // columns of this split: a multiple of 256
-    const int nst = (kcols + kStageCols - 1) / kStageCols;
-    const int P = a.sps * kStageCols + 8;                 // row pitch in halfs: 16 rows x 16 bytes cover all banks
-    const int blocks = (a.m + 15) >> 4;
-    const int b0 = (blockIdx.x * WAVES + wave) * a.bpw;
-    const int nblk = max(0, min(blocks, b0 + a.bpw) - b0);
-    const int T = nblk * nst;                             // stages of this wavefront
-
-    // registers of one stage: per 512-column block the lane's 64 bytes of codes (4 groups) and their 4 scales
-    struct Stage {
-        u32x4_t w[8];
-        u32x2_t sc[2];
-    };
-    // stage t = (block b0 + t / nst, columns k0 + 1024 (t % nst) ...).  Addresses are clamped into the matrix; what a
-    // clamped load brings meets zeros of the x slice (columns) or lands in rows / stages that are never stored.
-    auto stage_load = [&](Stage &S, int u, int ks) {
-        const int row = min(min(b0 + u, blocks - 1) * 16 + r16, a.m - 1);
-        const uint32_t *qrow = a.q + (size_t)row * kw + (k0 >> 3);
-        const uint16_t *srow = a.s + (size_t)row * G + (k0 >> 5);
-#pragma unroll
-        for (int jq = 0; jq < 2; ++jq) {
-            int col = ks * kStageCols + jq * 512 + kb * 128;             // first of the lane's 128 columns
-            if (col >= kcols) col = ks * kStageCols + (kb & 1) * 128;   // beyond the split: re-read the stage's first 256 columns
-#if defined(RELAX_R16_STRIP) && RELAX_R16_STRIP == 2
-            S.sc[jq] = u32x2_t{(uint32_t)(size_t)srow, 0u};
-#else
-            S.sc[jq] = *(const u32x2_t *)(srow + (col >> 5));
-#endif
-#pragma unroll
-            for (int jj = 0; jj < 4; ++jj) S.w[jq * 4 + jj] = *(const u32x4_t *)(qrow + (col >> 3) + jj * 4);
-        }
-    };
-
-    Stage st[NSTG];
-    {
-        int u = 0, ks = 0;
-#pragma unroll
-        for (int i = 0; i < NSTG; ++i) {
-            stage_load(st[i], u, ks);
-            if (++ks == nst) ks = 0, ++u;
-        }
-    }
-
-    // ---- x slice to LDS: 16-byte packets in the order [x0 x4 x1 x5 x2 x6 x3 x7] of the decode, zeros beyond the split ----
-    {
-        const int ppr = nst * (kStageCols / 8);           // packets per row
-        const int total = a.n * ppr;
-        for (int base = 0; base < total; base += 8 * 64 * WAVES) {           // eight packets per thread in flight
-            u32x4_t v[8];
-            int at[8];
-            bool live[8];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int id = base + j * 64 * WAVES + tid, idc = min(id, total - 1);
-                const int i = idc / ppr, col = (idc - i * ppr) * 8;
-                at[j] = id < total ? i * P + col : -1;
-                live[j] = col < kcols;
-                v[j] = *(const u32x4_t *)(a.x + (size_t)i * a.k + k0 + min(col, kcols - 8));
-            }
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                if (at[j] < 0) continue;
-                u32x4_t o;
-                o.x = __builtin_amdgcn_perm(v[j].z, v[j].x, 0x05040100u);
-                o.y = __builtin_amdgcn_perm(v[j].z, v[j].x, 0x07060302u);
-                o.z = __builtin_amdgcn_perm(v[j].w, v[j].y, 0x05040100u);
-                o.w = __builtin_amdgcn_perm(v[j].w, v[j].y, 0x07060302u);
-                if (!live[j]) o = u32x4_t{0u, 0u, 0u, 0u};
-                *(u32x4_t *)(lds + at[j]) = o;
-            }
-        }
-    }
-    __syncthreads();
-
-    float4_t acc[2] = {{0.0f, 0.0f, 0.0f, 0.0f}, {0.0f, 0.0f, 0.0f, 0.0f}};
-    const uint16_t *xb = lds + r16 * P + kb * 128;
-    uint32_t dummy = 0;
-    auto consume = [&](const Stage &S, int ks) {
-#ifdef RELAX_R16_STRIP
-#pragma unroll
-        for (int j = 0; j < 8; ++j) dummy ^= S.w[j].x ^ S.w[j].y ^ S.w[j].z ^ S.w[j].w;
-        dummy ^= S.sc[0].x ^ S.sc[0].y ^ S.sc[1].x ^ S.sc[1].y;
-        return;
-#endif
-#pragma unroll
-        for (int jq = 0; jq < 2; ++jq) {
-            const uint32_t s2[4] = {__builtin_amdgcn_perm(S.sc[jq].x, S.sc[jq].x, 0x01000100u), __builtin_amdgcn_perm(S.sc[jq].x, S.sc[jq].x, 0x03020302u),
-                                    __builtin_amdgcn_perm(S.sc[jq].y, S.sc[jq].y, 0x01000100u), __builtin_amdgcn_perm(S.sc[jq].y, S.sc[jq].y, 0x03020302u)};
-#pragma unroll
-            for (int jj = 0; jj < 4; ++jj) {
-                const u32x4_t wv = S.w[jq * 4 + jj];
-                const uint32_t word[4] = {wv.x, wv.y, wv.z, wv.w};
-#pragma unroll
-                for (int wd = 0; wd < 4; ++wd) {
-                    const half8_t af = decode_word(word[wd], s2[jj]);
-                    const half8_t bf = *(const half8_t *)(xb + ks * kStageCols + jq * 512 + jj * 32 + wd * 8);
-                    acc[wd & 1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(af, bf, acc[wd & 1], 0, 0, 0);
-                }
-            }
-        }
-    };
-    // the block's tile: lane holds weight rows 4 (l / 16) .. + 4 of the block for x row l % 16
-    auto flush = [&](int u) {
-        const int row = (b0 + u) * 16 + kb * 4;
-        if (r16 < a.n && row < a.m)                        // m % 4 == 0 is checked by the launcher
-            *(float4_t *)(a.partial + ((size_t)blockIdx.y * a.n + r16) * a.m + row) = acc[0] + acc[1] + (float)dummy;
-        acc[0] = acc[1] = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
-    };
-
-    int u = 0, ks = 0;                                    // (block, stage) of the stage to consume next
-    int lu = 0, lks = 0;                                  // ... of the stage to load next
-#pragma unroll
-    for (int i = 0; i < NSTG; ++i)
-        if (++lks == nst) lks = 0, ++lu;
-    for (int t = 0; t < T; t += NSTG) {
-#pragma unroll
-        for (int i = 0; i < NSTG; ++i) {
-            if (t + i < T) {
-                consume(st[i], ks);
-                if (++ks == nst) flush(u), ks = 0, ++u;
-            }
-            stage_load(st[i], min(lu, max(nblk, 1) - 1), lks);
-            if (++lks == nst) lks = 0, ++lu;
-        }
-    }
-}
-
 // out = epilogue(sum over splits, in order, of partial[s][i][r]); one thread per 4 consecutive r (SwiGLU: 4 gate columns)
 template <int EPI>
 __global__ __launch_bounds__(256) void skinny_finish_kernel(const float *__restrict__ partial, int splits, int n, int m,
@@ -594,48 +439,6 @@ hipError_t launch_skinny(const SkinnyArgs &a, dim3 grid, hipStream_t stream)
     return hipGetLastError();
 }
 
-struct Rows16Plan {
-    int sps, splits, wgs, bpw;
-};
-
-// k splits of sps stages, wgs workgroups per split (about one workgroup per CU in all), bpw blocks per wavefront.  The cost of a candidate
-// is what its busiest wavefront does, in stages: its blocks (codes, plus the partial tile it writes per block) and the start of a workgroup
-// (the x slice grows with sps); fewer, longer splits win ties (fewer partial tiles to add up).
-Rows16Plan rows16_plan(int m, int k, int waves)
-{
-    const int blocks = (m + 15) / 16, total = (k + kStageCols - 1) / kStageCols, cus = 256;
-    static const int force_sps = getenv("RELAX_R16_SPS") ? atoi(getenv("RELAX_R16_SPS")) : 0;
-    static const int force_cus = getenv("RELAX_R16_CUS") ? atoi(getenv("RELAX_R16_CUS")) : 0;
-    Rows16Plan best = {};
-    double best_cost = 1e30;
-    for (int sps = kMaxSps; sps >= 1; --sps) {
-        if (force_sps && sps != force_sps) continue;
-        Rows16Plan p;
-        p.sps = sps;
-        p.splits = (total + sps - 1) / sps;
-        p.wgs = std::max(1, (force_cus ? force_cus : cus) / p.splits);
-        p.bpw = (blocks + waves * p.wgs - 1) / (waves * p.wgs);
-        p.wgs = (blocks + waves * p.bpw - 1) / (waves * p.bpw);
-        const double cost = p.bpw * (sps + 0.25) + 1.5 + 0.25 * sps;
-        if (cost < best_cost) best_cost = cost, best = p;
-    }
-    return best;
-}
-
-template <int NSTG, int WAVES>
-hipError_t launch_rows16(const Rows16Args &a, dim3 grid, hipStream_t stream)
-{
-    const size_t lds = (size_t)16 * (a.sps * kStageCols + 8) * sizeof(uint16_t);
-    static bool attr_done = false;
-    if (!attr_done) {
-        if (hipFuncSetAttribute((const void *)rows16_q4_kernel<NSTG, WAVES>, hipFuncAttributeMaxDynamicSharedMemorySize, 16 * (kMaxSps * kStageCols + 8) * 2) != hipSuccess)
-            return hipErrorInvalidValue;
-        attr_done = true;
-    }
-    hipLaunchKernelGGL((rows16_q4_kernel<NSTG, WAVES>), grid, dim3(64 * WAVES), lds, stream, a);
-    return hipGetLastError();
-}
-
 }  // namespace
 
 bool gemm_skinny_eligible(const relax_qmat &w, const void *x, int n, int epi)
@@ -654,10 +457,6 @@ size_t gemm_skinny_partial_floats(int m, int k, int n)
     size_t worst = 0;                                     // n rows may run with either round size: take the larger plan
     for (int kr : {256, 128}) {
         const size_t v = (size_t)skinny_plan(m, k, kr).splits * (size_t)n * (size_t)m;
-        worst = v > worst ? v : worst;
-    }
-    if (n <= 16) {
-        const size_t v = (size_t)std::max(rows16_plan(m, k, 4).splits, rows16_plan(m, k, 8).splits) * (size_t)n * (size_t)m;
         worst = v > worst ? v : worst;
     }
     return worst;
@@ -682,20 +481,8 @@ hipError_t launch_gemm_skinny(const uint16_t *x, const relax_qmat &w, int n, int
     a.x = x, a.q = w.q, a.s = w.s, a.partial = partial, a.n = n, a.m = w.m, a.k = w.k, a.rounds_per_split = pl.rounds_per_split;
     dim3 grid(pl.tiles_m, pl.splits);
     hipError_t e;
-    int splits = pl.splits;
-    static const bool old16 = getenv("RELAX_ROWS16") == nullptr;
-    static const int nstg = getenv("RELAX_R16_NSTG") ? atoi(getenv("RELAX_R16_NSTG")) : 4;
-    if (n <= 16 && !old16) {
-        static const int waves = getenv("RELAX_R16_WAVES") ? atoi(getenv("RELAX_R16_WAVES")) : 8;
-        const Rows16Plan rp = rows16_plan(w.m, w.k, waves);
-        Rows16Args ra;
-        ra.x = x, ra.q = w.q, ra.s = w.s, ra.partial = partial, ra.n = n, ra.m = w.m, ra.k = w.k, ra.sps = rp.sps, ra.bpw = rp.bpw;
-        splits = rp.splits;
-        const dim3 g16(rp.wgs, rp.splits);
-        if (waves == 4) e = nstg == 3 ? launch_rows16<3, 4>(ra, g16, stream) : nstg == 2 ? launch_rows16<2, 4>(ra, g16, stream) : launch_rows16<4, 4>(ra, g16, stream);
-        else e = nstg == 3 ? launch_rows16<3, 8>(ra, g16, stream) : nstg == 2 ? launch_rows16<2, 8>(ra, g16, stream) : launch_rows16<4, 8>(ra, g16, stream);
-    }
-    else if (n <= 16) e = launch_skinny<1, 16, 256>(a, grid, stream);
+    const int splits = pl.splits;
+    if (n <= 16) e = launch_skinny<1, 16, 256>(a, grid, stream);
     else if (n <= 32) e = launch_skinny<1, 32, 256>(a, grid, stream);
     else if (n <= 64) e = launch_skinny<2, 64, 256>(a, grid, stream);
     else e = launch_skinny<4, 128, 128>(a, grid, stream);
