@@ -214,6 +214,8 @@ def test_attention_ragged_prefill_rows_and_many_sequences(rx):
     (2, 2, 64, [300], [300]),                     # head dim 64, several q tiles and KV tiles, ragged tails
     (4, 1, 128, [70], [333]),                     # chunked prefill: 263 cached tokens before the call's rows
     (8, 4, 64, [40, 1, 200, 17], [40, 90, 200, 64]),   # mixed batch: a decode row among prefills, different pasts
+    (4, 4, 128, [150], [155]),                    # 5 cached tokens: the 32-token sub-tiles no longer line up with the 32-query groups, so
+                                                  # a wavefront's second KV group meets sub-tiles that are masked entirely for its first queries
 ])
 def test_prefill_attention_mfma(rx, h, g, d, q_lens, kv_lens):
     B = len(q_lens)
