@@ -85,13 +85,13 @@ __global__ __launch_bounds__(1024) void rmsnorm_kernel(const T *x, const uint16_
 
 hipError_t launch_rmsnorm(const uint16_t *x, const uint16_t *w, uint16_t *y, int n, int H, float eps, hipStream_t stream)
 {
-    hipLaunchKernelGGL(rmsnorm_kernel<uint16_t>, dim3(n), dim3(norm_block_threads(H)), 0, stream, x, w, y, H, eps);
+    hipLaunchKernelGGL(rmsnorm_kernel<uint16_t>, dim3(n), dim3(norm_block_threads(H, n)), 0, stream, x, w, y, H, eps);
     return hipGetLastError();
 }
 
 hipError_t launch_rmsnorm_f32(const float *x, const uint16_t *w, uint16_t *y, int n, int H, float eps, hipStream_t stream)
 {
-    hipLaunchKernelGGL(rmsnorm_kernel<float>, dim3(n), dim3(norm_block_threads(H)), 0, stream, x, w, y, H, eps);
+    hipLaunchKernelGGL(rmsnorm_kernel<float>, dim3(n), dim3(norm_block_threads(H, n)), 0, stream, x, w, y, H, eps);
     return hipGetLastError();
 }
 

@@ -489,10 +489,10 @@ hipError_t launch_gemm_skinny(const uint16_t *x, const relax_qmat &w, int n, int
     if (e != hipSuccess) return e;
     if (fuse) {                                           // the caller checked gemm_skinny_fuse_ok
         if (epi == EPI_RESID_F32)
-            hipLaunchKernelGGL(skinny_finish_norm_kernel<EPI_RESID_F32>, dim3(n), dim3(norm_block_threads(w.m)), 0, stream, partial, splits, n, w.m, out_f16, out_f32, resid,
+            hipLaunchKernelGGL(skinny_finish_norm_kernel<EPI_RESID_F32>, dim3(n), dim3(norm_block_threads(w.m, n)), 0, stream, partial, splits, n, w.m, out_f16, out_f32, resid,
                                fuse->norm_w, fuse->xn, fuse->eps);
         else if (epi == EPI_RESID_F16)
-            hipLaunchKernelGGL(skinny_finish_norm_kernel<EPI_RESID_F16>, dim3(n), dim3(norm_block_threads(w.m)), 0, stream, partial, splits, n, w.m, out_f16, out_f32, resid,
+            hipLaunchKernelGGL(skinny_finish_norm_kernel<EPI_RESID_F16>, dim3(n), dim3(norm_block_threads(w.m, n)), 0, stream, partial, splits, n, w.m, out_f16, out_f32, resid,
                                fuse->norm_w, fuse->xn, fuse->eps);
         else if (epi == EPI_F16) {
             const relax_layer_dims &dm = *fuse->dm;

@@ -131,7 +131,8 @@ hipError_t launch_gemv_reg(const GemvArgs &a, int xmode, int epi, hipStream_t st
 
 // Workgroup size of the row-norm kernels (one workgroup per row, eight elements per thread and pass) and the order in which the
 // per-wavefront sums of squares are added: shared by the stand-alone kernels and the finishing pass that folds the norm in.
-inline int norm_block_threads(int H) { return H >= 8192 ? 1024 : H >= 4096 ? 512 : 256; }
+// (few rows: a row per workgroup leaves most CUs idle, so the workgroup is as wide as the row allows; many rows: 256 threads)
+inline int norm_block_threads(int H, int n) { return n > 128 ? 256 : H >= 8192 ? 1024 : H >= 4096 ? 512 : 256; }
 __device__ inline float block_total(const float *red, int waves)
 {
     float t = 0.0f;
