@@ -68,6 +68,7 @@ def emit(args, metric, unit, value, ms_per_step, dtype, config, roofline, cpu, e
 def bench_decode_layer(args, np, torch, wl, rx):
     from paper_2311_02103_amd.runtime import DeviceLayer, f16_bits, to_device
     rx.check(rx.relax_set_option("fused_decode", 1 if args.path == "fused" else 0))
+    args.mode = args.mode or "graph"
     dev = "cuda:0"
     shape, cap, seed, ncalls = wl.LLAMA7B, 4096, 1, 64
     steps = args.steps = args.steps or 1280
@@ -308,6 +309,7 @@ def bench_prefill_layer(args, np, torch, wl, rx):
 def bench_model(args, np, torch, wl, rx, big):
     from paper_2311_02103_amd.runtime import DeviceModel
     V = 32000
+    args.mode = args.mode or "eager"
     if big:
         shape, nl, distinct, B, cap, seed = wl.LLAMA70B, 80, min(args.sets, 4), 16, 8192, 4
         steps = args.steps = args.steps or 8
@@ -358,14 +360,51 @@ def bench_model(args, np, torch, wl, rx, big):
         prompt = torch.from_numpy(wl.token_ids(seed, 128, V)).cuda()
         setup_s = time.time() - t_setup
         dev.step(prompt, [128], [128], logits=logits, next_ids=nxt)
-        for s in range(warmup):
-            dev.step(nxt, [1], [129 + s], logits=logits, next_ids=nxt)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for s in range(warmup, warmup + steps):
-            dev.step(nxt, [1], [129 + s], logits=logits, next_ids=nxt)
-        torch.cuda.synchronize()
-        elapsed = time.perf_counter() - t0
+        if args.mode == "graph":
+            # Graph offloading (Sec. 4.5) over a device-resident descriptor (the shape heap of Sec. 4.7): a decode step -- a
+            # one-element add that advances kv_len in the table, then relax_model_step, which reads the token from the buffer
+            # it writes the next one to -- is captured, args.graph_steps times in a row, and replayed; the host passes only
+            # the bound.  Nothing in the graph depends on the position, so the same graph serves every token.
+            table = torch.tensor([[0], [1], [128], [0]], dtype=torch.int32, device="cuda")
+            one = torch.ones((), dtype=torch.int32, device="cuda")
+            gstream = torch.cuda.Stream()
+
+            def graph_body():
+                table[2].add_(one)
+                dev.step(nxt, [1], [cap], logits=logits, next_ids=nxt, stream=gstream, device_table=table)
+
+            gs = max(1, args.graph_steps)
+            if steps % gs != 0:
+                raise SystemExit("bench: --steps must be a multiple of --graph-steps")
+            with torch.cuda.stream(gstream):
+                graph_body()                              # everything touched once before capture (this is decode step 0)
+            gstream.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=gstream):
+                for _ in range(gs):
+                    graph_body()
+            wrep = (max(warmup, 1) - 1 + gs - 1) // gs
+            with torch.cuda.stream(gstream):
+                for s in range(wrep):
+                    graph.replay()
+            gstream.synchronize()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            with torch.cuda.stream(gstream):
+                for s in range(steps // gs):
+                    graph.replay()
+            gstream.synchronize()
+            elapsed = time.perf_counter() - t0
+            assert int(table[2].item()) == 128 + 1 + wrep * gs + steps
+        else:
+            for s in range(warmup):
+                dev.step(nxt, [1], [129 + s], logits=logits, next_ids=nxt)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for s in range(warmup, warmup + steps):
+                dev.step(nxt, [1], [129 + s], logits=logits, next_ids=nxt)
+            torch.cuda.synchronize()
+            elapsed = time.perf_counter() - t0
         kv_bytes = shape.kv_bytes_per_token() * (129 + warmup + steps / 2.0) * nl
         tokens = steps
         desc = ("configs[3]: %d-layer Llama-2-7B-shaped model (%d distinct int4-g32 weight sets cycled), fp16 embedding and LM head, "
@@ -421,7 +460,8 @@ def bench_model(args, np, torch, wl, rx, big):
                          "workload is covered by the teacher-forced tests, not here)" % (done, B, t_cpu, t_head, nl)}
 
     emit(args, metric, "tokens/s", tokens / elapsed, ms_per_step, "f16 (int4 weights, f32 accumulate)",
-         {"workload": desc, "build_id": rx.relax_build_id(), "setup_s": round(setup_s, 1), "launch": "eager (one C call per step)"},
+         {"workload": desc, "build_id": rx.relax_build_id(), "setup_s": round(setup_s, 1), "launch": ("hipGraph of %d decode steps (descriptor on the device), captured once and replayed" % max(1, args.graph_steps) if (not big and args.mode == "graph")
+                                                                                     else "eager (one C call per step)")},
          roofline, cpu,
          {"model_hbm": {"algorithmic_bytes_per_step": int(step_bytes), "weights_and_head_bytes": int(weight_bytes), "kv_bytes": int(kv_bytes),
                         "achieved_GBps": round(model_gbs, 1), "frac_of_peak": round(model_gbs / PEAK_HBM_GBS, 4)},
@@ -503,8 +543,11 @@ def main():
     ap.add_argument("--n", type=int, default=2048, help="rows of the prefill_layer workload")
     ap.add_argument("--layers", type=int, default=0, help="model workloads: override the layer count (short profiling runs)")
     ap.add_argument("--sets", type=int, default=8, help="distinct weight sets rotated through")
-    ap.add_argument("--mode", choices=["graph", "eager"], default="graph",
-                    help="decode_layer: the 64-call schedule is captured once in a HIP graph and replayed (Sec. 4.5 of the paper)")
+    ap.add_argument("--mode", choices=["graph", "eager"], default=None,
+                    help="decode_layer (default graph): the 64-call schedule is captured once in a HIP graph and replayed (Sec. 4.5 of "
+                         "the paper); model_7b (default eager, the faster of the two there): graph = --graph-steps decode steps captured "
+                         "once over a device-resident descriptor and replayed")
+    ap.add_argument("--graph-steps", type=int, default=8, help="model_7b, graph mode: decode steps captured in the one graph that is replayed")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the CPU-oracle baseline leg (0 = skip)")
     ap.add_argument("--no-kernel-timing", action="store_true")
     ap.add_argument("--pmc-calibration", action="store_true",

@@ -111,6 +111,18 @@ typedef struct {
     const int32_t *q_lens;        /* host [B], each >= 1, sum == n                       */
     const int32_t *kv_lens;       /* host [B], L_b AFTER this call's rows are appended   */
     const int32_t *slots;         /* host [B] cache slot per sequence; NULL: slot b = b  */
+    const int32_t *device_table;  /* NULL, or device [4][B] int32: q_start, q_len, kv_len, slot per sequence
+                                     (q_start = first row of the sequence in the call).  The device-side form
+                                     of the descriptor -- the runtime shape heap of Sec. 4.7 -- for callers that
+                                     capture a call in a graph and replay it (Sec. 4.5 graph offloading): when
+                                     set, the kernels read positions and slots THERE, at run time, and the host
+                                     arrays above only shape the launch: B, q_lens and n must be exact, kv_lens
+                                     must be upper bounds of what the table will ever hold while the captured
+                                     call is replayed (they size the attention plan; the capacity check is made
+                                     on them), slots are ignored.  The caller owns the table, keeps it alive
+                                     and consistent (kv_len >= q_len, within the bounds) and updates it between
+                                     replays, e.g. with a one-thread kernel in the same graph; the call then does
+                                     no host-to-device copy and no synchronisation.                          */
 } relax_seqs;
 
 /* Bytes of workspace that any call with n <= n_max, every L_b <= L_max and B <= B_max

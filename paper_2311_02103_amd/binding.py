@@ -53,7 +53,7 @@ class KVCacheC(C.Structure):
 
 class SeqsC(C.Structure):
     _fields_ = [("B", C.c_int32), ("q_lens", C.POINTER(C.c_int32)), ("kv_lens", C.POINTER(C.c_int32)),
-                ("slots", C.POINTER(C.c_int32))]
+                ("slots", C.POINTER(C.c_int32)), ("device_table", C.c_void_p)]
 
 
 class ModelC(C.Structure):
@@ -174,17 +174,20 @@ class KVCache:
 
 
 class Seqs:
-    """Host-side ragged descriptor; kv_lens are lengths AFTER this call's rows are appended."""
+    """Host-side ragged descriptor; kv_lens are lengths AFTER this call's rows are appended.  device_table: optional
+    device int32 [4][B] (q_start, q_len, kv_len, slot) that the kernels read instead; kv_lens are then upper bounds."""
 
-    def __init__(self, q_lens: Sequence[int], kv_lens: Sequence[int], slots: Optional[Sequence[int]] = None):
+    def __init__(self, q_lens: Sequence[int], kv_lens: Sequence[int], slots: Optional[Sequence[int]] = None, device_table: Ptr = None):
         arr = lambda v: (C.c_int32 * len(v))(*[int(e) for e in v])
         self.B = len(q_lens)
         self._q, self._kv = arr(q_lens), arr(kv_lens)
         self._sl = None if slots is None else arr(slots)
+        self._table = device_table
 
     def c(self) -> SeqsC:
         ip = C.POINTER(C.c_int32)
-        return SeqsC(self.B, C.cast(self._q, ip), C.cast(self._kv, ip), None if self._sl is None else C.cast(self._sl, ip))
+        return SeqsC(self.B, C.cast(self._q, ip), C.cast(self._kv, ip), None if self._sl is None else C.cast(self._sl, ip),
+                     _ptr(self._table))
 
 
 def make_dims(hidden, n_heads, n_kv_heads, head_dim, ffn, kv_capacity, kv_slots=1, rms_eps=1e-5, rope_base=10000.0,

@@ -101,6 +101,14 @@ relax_status build_seqs(const relax_seqs *sq, const relax_layer_dims &dm, int32_
     st.dev = nullptr;
     st.q_max = 0;
     for (int b = 0; b < sq->B; ++b) st.q_max = sq->q_lens[b] > st.q_max ? sq->q_lens[b] : st.q_max;
+    if (sq->device_table) {
+        // The caller keeps the descriptor on the device (Sec. 4.7 shape heap): kernels read positions and slots there at run
+        // time; the host values above served the checks and serve the launch shapes and plans (kv_lens as upper bounds).
+        if ((reinterpret_cast<uintptr_t>(sq->device_table) & 3) != 0) return RELAX_ERR_SHAPE;
+        st.dev = sq->device_table;
+        for (int b = 0; b < kInlineSeqs; ++b) st.q_start[b] = st.q_len[b] = st.kv_len[b] = st.slot[b] = 0;
+        return RELAX_OK;
+    }
     const bool inl = sq->B <= kInlineSeqs;
     if (!inl) host_table.assign(4 * (size_t)sq->B, 0);
     int32_t start = 0;
@@ -479,6 +487,7 @@ relax_status layer_enqueue(const relax_layer_dims &dm, const relax_layer_weights
     a.h = dm.n_heads, a.g = dm.n_kv_heads, a.d = dm.head_dim, a.kv_capacity = dm.kv_capacity, a.seqs = st;
     a.trace = g_trace;
     if (n == 1 && st.dev == nullptr) a.pos0 = st.kv_len[0] - st.q_len[0] - st.q_start[0], a.slot0 = st.slot[0];
+    else a.pos0 = -1;                                          // rows find their position in the descriptor
     timer.before(0);
     if (launch_gemv(a, X_F16_NORM, EPI_ROPE_KV, st_) != hipSuccess) return RELAX_ERR_HIP;
     timer.after(0);
@@ -489,12 +498,14 @@ relax_status layer_enqueue(const relax_layer_dims &dm, const relax_layer_weights
     o.q = wt->wo.q, o.s = wt->wo.s, o.m = wt->wo.m, o.k = wt->wo.k, o.n = n;
     o.out_f32 = x1, o.resid = x, o.trace = g_trace;
     bool folded = false;
-    if (n == 1 && st.dev == nullptr && attn_mha_split_supported(dm)) {
-        const int pos = st.kv_len[0] - st.q_len[0] - st.q_start[0], L = pos + 1;
-        int splits = std::min(kAttnMergeSplits, (L + 63) / 64);
-        const int chunk = ((L + splits - 1) / splits + 31) / 32 * 32;     // whole wavefront steps (16 or 32 tokens), all splits used
-        splits = (L + chunk - 1) / chunk;
-        o.h = dm.n_heads, o.d = dm.head_dim, o.pos0 = pos;
+    if (n == 1 && attn_mha_split_supported(dm)) {
+        int splits = kAttnMergeSplits, chunk = 0, pos = -1;              // device-resident descriptor: every slice launched, plan on the device
+        if (st.dev == nullptr) {
+            pos = st.kv_len[0] - st.q_len[0] - st.q_start[0];
+            chunk = attn_fold_chunk(pos + 1, kAttnMergeSplits);          // whole wavefront steps (16 or 32 tokens), all splits used
+            splits = (pos + chunk) / chunk;
+        }
+        o.h = dm.n_heads, o.d = dm.head_dim, o.pos0 = pos, o.seqs = st;
         o.part = partials, o.part_splits = splits, o.part_stride = dm.head_dim / 2 + 4, o.part_chunk = chunk;
         folded = (size_t)dm.n_heads * splits * o.part_stride <= attn_partial_floats(dm, 1, 1) && gemv_merge_eligible(o);
         if (folded) {

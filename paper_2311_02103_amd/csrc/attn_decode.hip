@@ -192,6 +192,7 @@ __global__ __launch_bounds__(256) void attn_mha_split_kernel(const uint16_t *__r
     const int i = blockIdx.z, split = blockIdx.y, head = blockIdx.x;
     const RowInfo ri = row_info(st, i);
     const int L = ri.pos + 1;
+    if (chunk <= 0) chunk = attn_fold_chunk(L, splits);        // device-resident descriptor: the plan follows the L read here
     const int t_begin = split * chunk;
     if (t_begin >= L) return;                                  // uniform for the workgroup
     const int t_end = min(L, t_begin + chunk);

@@ -195,7 +195,9 @@ constexpr int rows_per_slot(bool few_rows)
 }
 
 // grid: x = workgroups (at most one per CU and row), y = row of x
-template <int XMODE, int EPI, int NG, int R>
+// DEV: the position of the (single) row comes from the device-resident descriptor a.seqs.dev instead of a.pos0 / a.slot0
+// (a captured launch is then valid for later positions too); only the two variants that need a position have it.
+template <int XMODE, int EPI, int NG, int R, bool DEV = false>
 __global__ __launch_bounds__(kRThreads) void gemv_q4_reg_kernel(GemvArgs a)
 {
     constexpr int NSLOT = kRSlots, E = R * NG;
@@ -224,7 +226,8 @@ __global__ __launch_bounds__(kRThreads) void gemv_q4_reg_kernel(GemvArgs a)
     // ---- what the epilogue reads, then the x row, then the first slots: requested in the order they are needed ----
     RowInfo ri = {0, 0, 0};
     if (EPI == EPI_ROPE_KV) {
-        if (a.n == 1) ri.pos = a.pos0, ri.slot = a.slot0;          // the host resolved the only row: no table walk up front
+        if (DEV) ri = row_info(a.seqs, i);                         // scalar loads of the descriptor
+        else if (a.n == 1) ri.pos = a.pos0, ri.slot = a.slot0;     // the host resolved the only row: no table walk up front
         else ri = row_info(a.seqs, i);
     }
 
@@ -237,7 +240,13 @@ __global__ __launch_bounds__(kRThreads) void gemv_q4_reg_kernel(GemvArgs a)
     // reads their accumulators and the (max, sum) pair of every split (splits past the used ones re-read the last)
     u32x4_t pacc[kMerge ? NG : 1][kMerge ? MS : 1];            // 8 normalised outputs of the split, fp16
     float2 pml[kMerge ? NG : 1][kMerge ? MS : 1];
-    const int used = kMerge ? (a.pos0 + a.part_chunk) / a.part_chunk : 0;      // splits that hold tokens: ceil((pos + 1) / chunk)
+    int used = 0;                                              // splits that hold tokens: ceil((pos + 1) / chunk)
+    if (kMerge && DEV) {
+        const int pos = row_info(a.seqs, 0).pos;
+        used = pos / attn_fold_chunk(pos + 1, a.part_splits) + 1;
+    } else if (kMerge) {
+        used = (a.pos0 + a.part_chunk) / a.part_chunk;
+    }
     auto x_loads = [&]() {
 #pragma unroll
     for (int p = 0; p < NG; ++p) {
@@ -490,10 +499,18 @@ hipError_t launch_ng(const GemvArgs &a, hipStream_t stream)
     gx = std::min(gx, (U + kRWaves - 1) / kRWaves);
     gx = std::max(gx, (U + kRWaves * kRMaxUnits - 1) / (kRWaves * kRMaxUnits));
     const bool few_rows = 2 * ((U + gx * kRWaves - 1) / (gx * kRWaves)) <= 4;      // rows a wavefront owns
-    if (rows_per_slot<NG>(few_rows) == 1)
-        hipLaunchKernelGGL((gemv_q4_reg_kernel<XMODE, EPI, NG, 1>), dim3(gx, a.n), dim3(kRThreads), 0, stream, a);
-    else
-        hipLaunchKernelGGL((gemv_q4_reg_kernel<XMODE, EPI, NG, 2>), dim3(gx, a.n), dim3(kRThreads), 0, stream, a);
+    constexpr bool kHasPos = EPI == EPI_ROPE_KV || XMODE == X_ATTN_MERGE;
+    const bool one = rows_per_slot<NG>(few_rows) == 1;
+    if constexpr (kHasPos) {
+        if (a.n == 1 && a.pos0 < 0) {                              // position from the device-resident descriptor
+            if (a.seqs.dev == nullptr) return hipErrorInvalidValue;
+            if (one) hipLaunchKernelGGL((gemv_q4_reg_kernel<XMODE, EPI, NG, 1, true>), dim3(gx, a.n), dim3(kRThreads), 0, stream, a);
+            else hipLaunchKernelGGL((gemv_q4_reg_kernel<XMODE, EPI, NG, 2, true>), dim3(gx, a.n), dim3(kRThreads), 0, stream, a);
+            return hipGetLastError();
+        }
+    }
+    if (one) hipLaunchKernelGGL((gemv_q4_reg_kernel<XMODE, EPI, NG, 1>), dim3(gx, a.n), dim3(kRThreads), 0, stream, a);
+    else hipLaunchKernelGGL((gemv_q4_reg_kernel<XMODE, EPI, NG, 2>), dim3(gx, a.n), dim3(kRThreads), 0, stream, a);
     return hipGetLastError();
 }
 
@@ -522,8 +539,10 @@ bool gemv_reg_eligible(const GemvArgs &a)
 bool gemv_merge_eligible(const GemvArgs &a)
 {
     return a.n == 1 && a.k <= 2 * 2048 && a.k >= 32 && (a.k % kGroup == 0) && a.k == a.h * a.d && (a.d % 8 == 0) && a.part != nullptr &&
-           ((reinterpret_cast<uintptr_t>(a.part) & 15) == 0) && (a.part_stride % 4 == 0) && a.part_stride >= a.d / 2 + 2 && a.part_chunk > 0 &&
-           a.part_splits >= 1 && a.part_splits <= kAttnMergeSplits && a.pos0 >= 0 && a.pos0 / a.part_chunk < a.part_splits &&
+           ((reinterpret_cast<uintptr_t>(a.part) & 15) == 0) && (a.part_stride % 4 == 0) && a.part_stride >= a.d / 2 + 2 &&
+           a.part_splits >= 1 && a.part_splits <= kAttnMergeSplits &&
+           (a.pos0 < 0 ? a.seqs.dev != nullptr                       // position and split plan from the device-resident descriptor
+                       : a.part_chunk > 0 && a.pos0 / a.part_chunk < a.part_splits) &&
            ((reinterpret_cast<uintptr_t>(a.q) & 15) == 0) && a.m >= 2;
 }
 

@@ -95,6 +95,16 @@ inline int groups_of(int k) { return (k + kGroup - 1) / kGroup; }
 
 enum XMode { X_F16 = 0, X_F16_NORM = 1, X_F32_NORM = 2, X_ATTN_MERGE = 3 };
 constexpr int kAttnMergeSplits = 8;  // splits along L that the matvec prologue of X_ATTN_MERGE folds (one round of loads)
+// Split plan of the folded form for one decode row with L cached tokens: at most max_splits chunks of whole wavefront steps
+// (32 tokens), none shorter than 64 tokens unless L is.  The host evaluates it when it knows L; with a device-resident
+// descriptor both kernels evaluate it from the L they read (the launch then always has max_splits slices).
+__host__ __device__ inline int attn_fold_chunk(int L, int max_splits)
+{
+    int sp = (L + 63) / 64;
+    sp = sp > max_splits ? max_splits : sp;
+    sp = sp < 1 ? 1 : sp;
+    return ((L + sp - 1) / sp + 31) / 32 * 32;
+}
 enum Epilogue { EPI_F16 = 0, EPI_ROPE_KV = 1, EPI_RESID_F32 = 2, EPI_RESID_F16 = 3, EPI_SWIGLU = 4 };
 
 struct GemvArgs {

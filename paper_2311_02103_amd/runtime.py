@@ -57,12 +57,12 @@ class DeviceLayer:
         self.v.copy_(to_device(v_bits, self.device).view(self.v.shape))
 
     def forward(self, x: torch.Tensor, q_lens: Sequence[int], kv_lens: Sequence[int], slots=None,
-                out: Optional[torch.Tensor] = None) -> torch.Tensor:
+                out: Optional[torch.Tensor] = None, device_table: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
         n = x.shape[0]
         if out is None:
             out = torch.empty_like(x)
-        seqs = rx.Seqs(q_lens, kv_lens, slots)
-        rx.check(rx.relax_decoder_layer(self.dims, self.weights, x, self.cache, seqs, out, n, self.ws, self.ws_bytes),
+        seqs = rx.Seqs(q_lens, kv_lens, slots, device_table)
+        rx.check(rx.relax_decoder_layer(self.dims, self.weights, x, self.cache, seqs, out, n, self.ws, self.ws_bytes, stream),
                  "relax_decoder_layer")
         return out
 
@@ -130,13 +130,15 @@ class DeviceModel:
         self.caches = [rx.KVCache(k, v, self.rope) for k, v in zip(self.k, self.v)]
 
     def step(self, ids: torch.Tensor, q_lens: Sequence[int], kv_lens: Sequence[int], slots=None,
-             logits: Optional[torch.Tensor] = None, next_ids: Optional[torch.Tensor] = None, stream=None):
-        """ids: int32 [n] on the device.  Returns (logits fp16 [B,V], next_ids int32 [B])."""
+             logits: Optional[torch.Tensor] = None, next_ids: Optional[torch.Tensor] = None, stream=None,
+             device_table: Optional[torch.Tensor] = None):
+        """ids: int32 [n] on the device.  Returns (logits fp16 [B,V], next_ids int32 [B]).  With device_table (int32 [4][B] on
+        the device: q_start, q_len, kv_len, slot) the kernels read positions there and kv_lens are upper bounds."""
         B = len(q_lens)
         if logits is None:
             logits = torch.empty((B, self.vocab), dtype=torch.float16, device=self.device)
         if next_ids is None:
             next_ids = torch.empty((B,), dtype=torch.int32, device=self.device)
-        rx.check(rx.relax_model_step(self.model, ids, self.caches, rx.Seqs(q_lens, kv_lens, slots), logits, next_ids,
+        rx.check(rx.relax_model_step(self.model, ids, self.caches, rx.Seqs(q_lens, kv_lens, slots, device_table), logits, next_ids,
                                      int(ids.shape[0]), self.ws, self.ws_bytes, stream), "relax_model_step")
         return logits, next_ids
