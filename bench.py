@@ -468,6 +468,30 @@ def bench_model(args, np, torch, wl, rx, big):
           "us_per_layer": round(ms_per_step * 1e3 / nl, 2), "kernel_ms": {k_: round(v, 5) for k_, v in kernel_ms.items()}})
 
 
+# ------------------------------------------------------------------------------------------------ memory plan
+def bench_memory_plan(args, wl, rx):
+    """The shape of the paper's activation-memory experiment (Sec. 5: prefill of 128..1024 tokens, decode at batch 1..64,
+    with and without static planning), on the layer workspace of this library: bytes of the intermediates when every
+    tensor and every kernel workspace has its own allocation, against the plan of Alg. 3 (relax_workspace_plan)."""
+    args.steps, args.warmup = args.steps or 1, args.warmup or 0
+    table = {}
+    for shape in (wl.LLAMA7B, wl.LLAMA70B):
+        cap = 8192
+        dims = rx.make_dims(shape.hidden, shape.n_heads, shape.n_kv_heads, shape.head_dim, shape.ffn, cap, 64)
+        rows = []
+        for kind, cases in (("prefill", [(n, n, 1) for n in (128, 256, 512, 1024)]), ("decode", [(b, 4096, b) for b in (1, 16, 32, 64)])):
+            for n, L, B in cases:
+                rc, entries, planned, unplanned = rx.relax_workspace_plan(dims, n, L, B)
+                rx.check(rc, "relax_workspace_plan")
+                rows.append({"case": "%s n=%d L=%d B=%d" % (kind, n, L, B), "unplanned_bytes": unplanned, "planned_bytes": planned,
+                             "ratio": round(planned / unplanned, 4), "storages": len({e["storage"] for e in entries}), "tensors": len(entries)})
+        table[shape.name] = rows
+    head = table[wl.LLAMA7B.name][3]
+    emit(args, "planned / unplanned activation bytes of one layer call (7B shape, prefill of 1024 tokens)", "ratio", head["ratio"], 0.0,
+         "bytes", {"workload": "§8(f) item 2: dynamic shape-aware memory planning (Alg. 3) of the layer workspace; host-only, nothing is timed",
+                   "build_id": rx.relax_build_id()}, None, None, {"higher_is_better": False, "memory_plan": table})
+
+
 # ------------------------------------------------------------------------------------------------ device ceilings
 def bench_ceilings(args, np, torch, wl, rx):
     """What the device at hand reaches on a plain streaming read (1 GiB, two buffers alternated: more than the
@@ -539,7 +563,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=0, help="timed steps (default: 1280 decode_layer, 50 prefill_layer, 256 model_7b, 8 batched_70b)")
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", choices=["decode_layer", "prefill_layer", "model_7b", "batched_70b", "ceilings"], default="decode_layer")
+    ap.add_argument("--workload", choices=["decode_layer", "prefill_layer", "model_7b", "batched_70b", "ceilings", "memory_plan"],
+                    default="decode_layer")
     ap.add_argument("--n", type=int, default=2048, help="rows of the prefill_layer workload")
     ap.add_argument("--layers", type=int, default=0, help="model workloads: override the layer count (short profiling runs)")
     ap.add_argument("--sets", type=int, default=8, help="distinct weight sets rotated through")
@@ -567,6 +592,9 @@ def main():
     from paper_2311_02103_amd import binding as rx
 
     rx.lib()                                        # raises when the HIP library is not built: there is no fallback
+    if args.workload == "memory_plan":              # host-only: the plan is a pure function of the shapes
+        bench_memory_plan(args, wl, rx)
+        return
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     if args.pmc_calibration:

@@ -130,6 +130,29 @@ typedef struct {
  * Returns 0 if dims is NULL or inconsistent.                                            */
 size_t relax_workspace_bytes(const relax_layer_dims *dims, int32_t n_max, int32_t L_max, int32_t B_max);
 
+/* The memory plan behind relax_workspace_bytes (Sec. 4.3, Alg. 3: dynamic shape-aware memory planning).  The
+ * intermediates of a layer call -- xn, qkv, the attention output and partials, x1, act and the workspace lifted
+ * out of the few-row matmul -- are walked in program order; an allocation reuses a free storage when its size
+ * provably fits for every value of the symbols (c1*n bytes into c2*n bytes when c1 <= c2; an opaque expression of
+ * (n, L, B) only into the same expression), otherwise a new storage is opened; a storage returns to the pool after
+ * the last use of its tensor.  The reuse structure therefore does not depend on n, L, B, every storage grows with
+ * them, and the plan at upper bounds covers every smaller call.
+ * relax_workspace_plan reports that plan for one (n, L, B): one entry per tensor (operations of the layer:
+ * 1 QKV + rotary + append, 2 attention, 3 output projection, 4 second norm, 5 gate/up, 6 down), `offset` in bytes
+ * from the start of the workspace, and the bytes of the planned region with and without reuse (every storage,
+ * resp. tensor, rounded up to 256 bytes; the fixed front part of the workspace -- fused-kernel state and the
+ * descriptor table -- is in neither).  entries may be NULL (sizes only); capacity < *count: RELAX_ERR_WORKSPACE.
+ * Host-only: nothing is enqueued.                                                                                */
+typedef struct {
+    char name[24];
+    int32_t first_op, last_op;    /* the tensor is allocated in front of first_op and dead after last_op          */
+    int32_t storage;              /* index of the storage it lives in; tensors with equal storage share memory    */
+    int32_t pinned;               /* 1: live for the whole call and across the layers of relax_model_step (xn)    */
+    uint64_t offset, bytes, storage_bytes;
+} relax_plan_entry;
+relax_status relax_workspace_plan(const relax_layer_dims *dims, int32_t n, int32_t L, int32_t B, relax_plan_entry *entries,
+                                  int32_t capacity, int32_t *count, size_t *planned_bytes, size_t *unplanned_bytes);
+
 /* The front of the workspace holds the state of the persistent fused decode kernel: an epoch counter and
  * the exchange buffers whose 8-byte words carry {value, epoch}.  It must be zeroed once before the first
  * call that uses the workspace -- relax_workspace_init does that (one small kernel on `stream`) -- and is

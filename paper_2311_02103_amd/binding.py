@@ -56,6 +56,11 @@ class SeqsC(C.Structure):
                 ("slots", C.POINTER(C.c_int32)), ("device_table", C.c_void_p)]
 
 
+class PlanEntryC(C.Structure):
+    _fields_ = [("name", C.c_char * 24), ("first_op", C.c_int32), ("last_op", C.c_int32), ("storage", C.c_int32), ("pinned", C.c_int32),
+                ("offset", C.c_uint64), ("bytes", C.c_uint64), ("storage_bytes", C.c_uint64)]
+
+
 class ModelC(C.Structure):
     _fields_ = [("dims", LayerDims), ("n_layers", C.c_int32), ("vocab", C.c_int32), ("layers", C.POINTER(LayerWeightsC)),
                 ("embedding", C.c_void_p), ("norm_final", C.c_void_p), ("lm_head", C.c_void_p)]
@@ -72,6 +77,8 @@ _SIGNATURES = {
     "relax_workspace_error": (C.c_int32, [C.POINTER(LayerDims), C.c_void_p, C.POINTER(C.c_int32)]),
     "relax_profile_step_events": (None, [C.c_void_p, C.c_void_p, C.c_int32]),
     "relax_workspace_bytes": (C.c_size_t, [C.POINTER(LayerDims), C.c_int32, C.c_int32, C.c_int32]),
+    "relax_workspace_plan": (C.c_int32, [C.POINTER(LayerDims), C.c_int32, C.c_int32, C.c_int32, C.POINTER(PlanEntryC), C.c_int32,
+                                         C.POINTER(C.c_int32), C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]),
     "relax_rope_table_bytes": (C.c_size_t, [C.POINTER(LayerDims)]),
     "relax_rope_table_init": (C.c_int32, [C.POINTER(LayerDims), C.c_void_p, C.c_void_p]),
     "relax_matmul_workspace_bytes": (C.c_size_t, [C.POINTER(QMatC), C.c_int32]),
@@ -201,6 +208,19 @@ def relax_build_id() -> str:
 
 def relax_workspace_bytes(dims: Optional[LayerDims], n_max: int, L_max: int, B_max: int) -> int:
     return int(lib().relax_workspace_bytes(_ref(dims), n_max, L_max, B_max))
+
+
+def relax_workspace_plan(dims: Optional[LayerDims], n: int, L: int, B: int, capacity: int = 32):
+    """(status, entries, planned_bytes, unplanned_bytes); entries are dicts of the C struct's fields."""
+    arr = (PlanEntryC * capacity)()
+    count, planned, unplanned = C.c_int32(0), C.c_size_t(0), C.c_size_t(0)
+    rc = lib().relax_workspace_plan(_ref(dims), n, L, B, arr, capacity, C.byref(count), C.byref(planned), C.byref(unplanned))
+    entries = []
+    if rc == 0:
+        for e in arr[:count.value]:
+            entries.append({"name": e.name.decode(), "first_op": e.first_op, "last_op": e.last_op, "storage": e.storage, "pinned": e.pinned,
+                            "offset": e.offset, "bytes": e.bytes, "storage_bytes": e.storage_bytes})
+    return rc, entries, planned.value, unplanned.value
 
 
 def relax_rope_table_bytes(dims: Optional[LayerDims]) -> int:

@@ -12,10 +12,80 @@ namespace {
 
 inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
+// ---- Dynamic shape-aware memory planning (Sec. 4.3, Alg. 3) over the intermediates of one layer call ----------------------
+// The layer is a fixed sequence of destination-passing operations; every intermediate has a symbolic size in the rows n
+// of the call (a monomial c * n bytes) or an opaque expression of (n, L, B) (the workspaces lifted out of the attention
+// and few-row matmul kernels, Sec. 4.4).  Tensors are walked in program order: an allocation first asks the pool for a free
+// storage that PROVABLY fits whatever the symbols are (c1 * n into c2 * n when c1 <= c2; an opaque expression only into
+// the same expression), smallest such first, else opens a new storage; after the last use of a tensor its storage goes
+// back to the pool.  Reuse therefore never depends on the values of n, L, B: the storage structure is the same for every
+// call, every storage size grows with the symbols, and a workspace sized at the upper bounds (n_max, L_max, B_max) covers
+// every smaller call -- the static plan of Sec. 4.3.
+enum PlanTensorId { T_XN, T_QKV, T_MMWS1, T_PART, T_ATTN, T_X1, T_MMWS3, T_ACT, T_MMWS5, T_MMWS6, T_COUNT };
+const char *const kPlanNames[T_COUNT] = {"xn", "qkv", "matmul_ws.qkv", "attn_partials", "attn_out", "x1", "matmul_ws.o", "act", "matmul_ws.gate_up",
+                                         "matmul_ws.down"};
+struct SymBytes {
+    uint64_t per_row;                // > 0: the tensor is per_row * n bytes
+    int opaque;                      // per_row == 0: number of the opaque expression
+    size_t value;                    // bytes at this call's (n, L, B)
+};
+struct PlanTensor {
+    SymBytes size;
+    int first_op, last_op;           // operations of the layer: 1 QKV (+ rotary, append), 2 attention, 3 output projection, 4 second norm, 5 gate/up, 6 down
+    int storage;
+};
+struct MemPlan {
+    PlanTensor t[T_COUNT];
+    SymBytes storage_size[T_COUNT];
+    size_t storage_off[T_COUNT];
+    int n_storages;
+    size_t planned, unplanned;       // bytes with and without reuse (every storage / tensor rounded up to 256 bytes)
+};
+
+inline bool provably_fits(const SymBytes &want, const SymBytes &have)
+{
+    if (want.per_row > 0 && have.per_row > 0) return want.per_row <= have.per_row;
+    if (want.per_row == 0 && have.per_row == 0) return want.opaque == have.opaque;
+    return false;
+}
+
+void plan_memory(MemPlan &mp, int n_ops)
+{
+    bool is_free[T_COUNT] = {};
+    mp.n_storages = 0;
+    mp.unplanned = 0;
+    for (int op = 0; op <= n_ops; ++op) {
+        for (int id = 0; id < T_COUNT; ++id) {                     // allocations in front of the operation, in declaration order
+            PlanTensor &t = mp.t[id];
+            if (t.first_op != op) continue;
+            mp.unplanned += align256(t.size.value);
+            int best = -1;
+            for (int s = 0; s < mp.n_storages; ++s) {
+                if (!is_free[s] || !provably_fits(t.size, mp.storage_size[s])) continue;
+                if (best < 0 || mp.storage_size[s].value < mp.storage_size[best].value) best = s;
+            }
+            if (best < 0) {
+                best = mp.n_storages++;
+                mp.storage_size[best] = t.size;
+            }
+            is_free[best] = false;
+            t.storage = best;
+        }
+        for (int id = 0; id < T_COUNT; ++id)                       // tensors dead after the operation
+            if (mp.t[id].last_op == op) is_free[mp.t[id].storage] = true;
+    }
+    mp.planned = 0;
+    for (int s = 0; s < mp.n_storages; ++s) {
+        mp.storage_off[s] = mp.planned;
+        mp.planned += align256(mp.storage_size[s].value);
+    }
+}
+
 // Static plan of the lifted workspace (Sec. 4.3 upper bounds, Sec. 4.4 lifting).  Offsets are a
 // pure function of (dims, n, L, B); a call sized by upper bounds covers every smaller call.
 struct WsPlan {
-    size_t sync, f_q, f_knew, f_vnew, f_attn, f_x1, f_act, f_part, f_end, table, partials, qbuf, attn, x1, act, xn, qkv, skinny, total;
+    size_t sync, f_q, f_knew, f_vnew, f_attn, f_x1, f_act, f_part, f_end, table, partials, partials_end, qbuf, attn, x1, act, xn, qkv, skinny, total;
+    MemPlan mem;
 };
 
 WsPlan plan_ws(const relax_layer_dims &dm, int32_t n, int32_t L, int32_t B)
@@ -38,23 +108,36 @@ WsPlan plan_ws(const relax_layer_dims &dm, int32_t n, int32_t L, int32_t B)
     p.f_part = off;   off += align256(8 * (size_t)dm.n_heads * kFusedMaxSplits * (size_t)(dm.head_dim + 2));
     p.f_end = off;
     p.table = off;    off += align256(sizeof(int32_t) * 4 * (size_t)(B > 1 ? B : 1));
-    p.partials = off; off += align256(sizeof(float) * attn_partial_floats(dm, n, L));
-    p.qbuf = off;     off += align256(2 * (size_t)n * hd);
-    p.attn = off;     off += align256(2 * (size_t)n * hd);
-    p.x1 = off;       off += align256(4 * (size_t)n * dm.hidden);
-    p.act = off;      off += align256(2 * (size_t)n * dm.ffn);
-    p.xn = off;       off += align256(2 * (size_t)n * dm.hidden);
-    p.qkv = off;      off += align256(2 * (size_t)n * qkvw);
-    // split-K partial tiles of the few-row matmul: the largest of the four matrices, at most kSkinnyMaxN rows
-    {
-        const int ns = n < kSkinnyMaxN ? n : kSkinnyMaxN;
-        size_t fl = gemm_skinny_partial_floats((int)qkvw, dm.hidden, ns);
-        const size_t f2 = gemm_skinny_partial_floats(dm.hidden, (int)hd, ns), f3 = gemm_skinny_partial_floats(2 * dm.ffn, dm.hidden, ns),
-                     f4 = gemm_skinny_partial_floats(dm.hidden, dm.ffn, ns);
-        fl = fl > f2 ? fl : f2, fl = fl > f3 ? fl : f3, fl = fl > f4 ? fl : f4;
-        p.skinny = off;   off += align256(sizeof(float) * fl);
-    }
-    p.total = off;
+
+    // The intermediates of the layer, their sizes and live ranges.  xn is pinned for the whole call (allocated in front of
+    // operation 0, never recycled): relax_model_step hands the next layer's normalised input over in it.  q of the one-row
+    // path lives in the front of the qkv tensor.  The split-K partial tiles of the few-row matmul are one lifted workspace
+    // (the largest of the four matrices, at most kSkinnyMaxN rows), allocated and released around each matmul.
+    const int ns = n < kSkinnyMaxN ? n : kSkinnyMaxN;
+    size_t fl = gemm_skinny_partial_floats((int)qkvw, dm.hidden, ns);
+    const size_t f2 = gemm_skinny_partial_floats(dm.hidden, (int)hd, ns), f3 = gemm_skinny_partial_floats(2 * dm.ffn, dm.hidden, ns),
+                 f4 = gemm_skinny_partial_floats(dm.hidden, dm.ffn, ns);
+    fl = fl > f2 ? fl : f2, fl = fl > f3 ? fl : f3, fl = fl > f4 ? fl : f4;
+    const SymBytes mmws = {0, 1, sizeof(float) * fl};
+    auto rows = [&](size_t per_row) { return SymBytes{per_row, 0, per_row * (size_t)n}; };
+    MemPlan &mp = p.mem;
+    const int kNever = 1 << 20;
+    mp.t[T_XN] = {rows(2 * (size_t)dm.hidden), 0, kNever, -1};
+    mp.t[T_QKV] = {rows(2 * qkvw), 1, 2, -1};
+    mp.t[T_MMWS1] = {mmws, 1, 1, -1};
+    mp.t[T_PART] = {SymBytes{0, 2, sizeof(float) * attn_partial_floats(dm, n, L)}, 2, 3, -1};
+    mp.t[T_ATTN] = {rows(2 * hd), 2, 3, -1};
+    mp.t[T_X1] = {rows(4 * (size_t)dm.hidden), 3, 6, -1};
+    mp.t[T_MMWS3] = {mmws, 3, 3, -1};
+    mp.t[T_ACT] = {rows(2 * (size_t)dm.ffn), 5, 6, -1};
+    mp.t[T_MMWS5] = {mmws, 5, 5, -1};
+    mp.t[T_MMWS6] = {mmws, 6, 6, -1};
+    plan_memory(mp, 6);
+    auto at = [&](int id) { return off + mp.storage_off[mp.t[id].storage]; };
+    p.xn = at(T_XN), p.qkv = at(T_QKV), p.qbuf = p.qkv, p.partials = at(T_PART), p.attn = at(T_ATTN), p.x1 = at(T_X1), p.act = at(T_ACT);
+    p.skinny = at(T_MMWS1);                                        // the four requests are the same expression: same storage every time
+    p.partials_end = p.partials + align256(mp.t[T_PART].size.value);
+    p.total = off + mp.planned;
     return p;
 }
 
@@ -262,6 +345,35 @@ size_t relax_workspace_bytes(const relax_layer_dims *dims, int32_t n_max, int32_
     return plan_ws(*dims, n_max, L_max, B_max).total;
 }
 
+relax_status relax_workspace_plan(const relax_layer_dims *dims, int32_t n, int32_t L, int32_t B, relax_plan_entry *entries, int32_t capacity,
+                                  int32_t *count, size_t *planned_bytes, size_t *unplanned_bytes)
+{
+    const relax_status rc = check_dims(dims);
+    if (rc != RELAX_OK) return rc;
+    if (n < 1 || L < 1 || B < 1) return RELAX_ERR_SHAPE;
+    const WsPlan pl = plan_ws(*dims, n, L, B);
+    const size_t base = pl.total - pl.mem.planned;               // the planned region follows the fixed front part
+    if (count) *count = T_COUNT;
+    if (planned_bytes) *planned_bytes = pl.mem.planned;
+    if (unplanned_bytes) *unplanned_bytes = pl.mem.unplanned;
+    if (entries) {
+        if (capacity < T_COUNT) return RELAX_ERR_WORKSPACE;
+        for (int id = 0; id < T_COUNT; ++id) {
+            relax_plan_entry &e = entries[id];
+            std::memset(&e, 0, sizeof(e));
+            std::strncpy(e.name, kPlanNames[id], sizeof(e.name) - 1);
+            e.first_op = pl.mem.t[id].first_op;
+            e.last_op = pl.mem.t[id].last_op > 6 ? 6 : pl.mem.t[id].last_op;
+            e.storage = pl.mem.t[id].storage;
+            e.pinned = pl.mem.t[id].last_op > 6;
+            e.offset = base + pl.mem.storage_off[pl.mem.t[id].storage];
+            e.bytes = pl.mem.t[id].size.value;
+            e.storage_bytes = pl.mem.storage_size[pl.mem.t[id].storage].value;
+        }
+    }
+    return RELAX_OK;
+}
+
 size_t relax_rope_table_bytes(const relax_layer_dims *dims)
 {
     if (check_dims(dims) != RELAX_OK) return 0;
@@ -347,7 +459,7 @@ relax_status relax_attention(const uint16_t *q, const relax_kv_cache *cache, con
     rc = build_seqs(seqs, *dims, n, st, L_max, host_table);
     if (rc != RELAX_OK) return rc;
     const WsPlan pl = plan_ws(*dims, n, L_max, seqs->B);
-    if (ws_bytes < pl.qbuf) return RELAX_ERR_WORKSPACE;          // table + partials
+    if (ws_bytes < pl.partials_end) return RELAX_ERR_WORKSPACE;   // table + partials
     rc = upload_table(st, host_table, ws, pl, st_);
     if (rc != RELAX_OK) return rc;
     float *partials = reinterpret_cast<float *>(static_cast<char *>(ws) + pl.partials);
