@@ -468,6 +468,48 @@ def bench_model(args, np, torch, wl, rx, big):
           "us_per_layer": round(ms_per_step * 1e3 / nl, 2), "kernel_ms": {k_: round(v, 5) for k_, v in kernel_ms.items()}})
 
 
+# ------------------------------------------------------------------------------------------------ batch sweep
+def bench_batch_sweep(args, np, torch, wl, rx):
+    """One 7B-shaped layer call on n decode rows (n sequences, one row each, 256 cached tokens each) against n: where the
+    runtime dispatch on the symbolic row count (Sec. 5.1) changes kernels -- matvec kernels for one row (and two rows of a
+    model this small), the few-row MFMA kernel up to 128 rows (64 for the tall gate/up matrix), the tiled GEMM above."""
+    from paper_2311_02103_amd.runtime import DeviceLayer, to_device
+    shape, seed, cap, L = wl.LLAMA7B, 6, 320, 256
+    ns = [1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64, 65, 96, 128, 129, 192, 256]
+    steps = args.steps = args.steps or 60
+    warmup = args.warmup = 10 if args.warmup is None else args.warmup
+    sets = max(1, min(args.sets, 3))                # three sets = 342 MB of weights: more than the last-level cache
+    layers = []
+    for s_ in range(sets):
+        layers.append(DeviceLayer(wl.layer_weights(shape, seed, layer=s_), hidden=shape.hidden, n_heads=shape.n_heads,
+                                  n_kv_heads=shape.n_kv_heads, head_dim=shape.head_dim, ffn=shape.ffn, kv_capacity=cap,
+                                  kv_slots=max(ns), n_max=max(ns), B_max=max(ns), share_from=layers[0] if layers else None))
+        layers[-1].k.normal_()
+        layers[-1].v.normal_()
+    stream = torch.cuda.Stream()
+    rows = []
+    for n in ns:
+        x = to_device(wl.activations(shape, seed, n, n))
+        out = torch.empty_like(x)
+        calls = [lay.prepare(x, [1] * n, [L] * n, out=out) for lay in layers]
+        for i in range(warmup):
+            calls[i % sets](stream.cuda_stream)
+        stream.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            calls[i % sets](stream.cuda_stream)
+        stream.synchronize()
+        us = (time.perf_counter() - t0) * 1e6 / steps
+        matmuls = ("matvec per row" if n <= 2 else "few-row MFMA" if n <= 64 else
+                   "few-row MFMA, tiled GEMM for gate/up" if n <= 128 else "tiled GEMM")
+        rows.append({"n": n, "us_per_call": round(us, 1), "layer_tokens_per_s": round(n / us * 1e6, 0), "matmul_kernels": matmuls})
+    best = max(rows, key=lambda r: r["layer_tokens_per_s"])
+    emit(args, "layer-tokens/s of one 7B-shaped int4 layer call against the number of decode rows (best point)", "tokens/s",
+         best["layer_tokens_per_s"], best["us_per_call"] / 1e3, "f16 (int4 weights, f32 accumulate)",
+         {"workload": "batch sweep (§8(f) item 3, int4 part): n decode rows, one per sequence, L = 256, %d rotating weight sets" % sets,
+          "build_id": rx.relax_build_id()}, None, None, {"batch_sweep": rows})
+
+
 # ------------------------------------------------------------------------------------------------ memory plan
 def bench_memory_plan(args, wl, rx):
     """The shape of the paper's activation-memory experiment (Sec. 5: prefill of 128..1024 tokens, decode at batch 1..64,
@@ -563,7 +605,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=0, help="timed steps (default: 1280 decode_layer, 50 prefill_layer, 256 model_7b, 8 batched_70b)")
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", choices=["decode_layer", "prefill_layer", "model_7b", "batched_70b", "ceilings", "memory_plan"],
+    ap.add_argument("--workload", choices=["decode_layer", "prefill_layer", "model_7b", "batched_70b", "ceilings", "memory_plan", "batch_sweep"],
                     default="decode_layer")
     ap.add_argument("--n", type=int, default=2048, help="rows of the prefill_layer workload")
     ap.add_argument("--layers", type=int, default=0, help="model workloads: override the layer count (short profiling runs)")
@@ -610,6 +652,8 @@ def main():
         bench_prefill_layer(args, np, torch, wl, rx)
     elif args.workload == "ceilings":
         bench_ceilings(args, np, torch, wl, rx)
+    elif args.workload == "batch_sweep":
+        bench_batch_sweep(args, np, torch, wl, rx)
     else:
         bench_model(args, np, torch, wl, rx, big=args.workload == "batched_70b")
 

@@ -404,7 +404,8 @@ relax_status relax_dequant_matmul(const uint16_t *x, const relax_qmat *w, uint16
     if (n < 1) return RELAX_ERR_SHAPE;
     // runtime dispatch on the symbolic n (Sec. 5.1): matrix-vector kernel for one row, split-K MFMA kernel for a few
     // (when the caller brought the workspace for its partial tiles), tiled MFMA GEMM otherwise
-    if (n >= kSkinnyMinN && n <= kSkinnyMaxN && ws && gemm_skinny_eligible(*w, x, n, EPI_F16) &&
+    const bool tiled_first = gemm_prefers_tiled(w->m, n) && gemm_mfma_eligible(*w, x, EPI_F16);
+    if (!tiled_first && n >= kSkinnyMinN && n <= kSkinnyMaxN && ws && gemm_skinny_eligible(*w, x, n, EPI_F16) &&
         (reinterpret_cast<uintptr_t>(ws) & 15) == 0 && ws_bytes >= sizeof(float) * gemm_skinny_partial_floats(w->m, w->k, n))
         return hip_status(launch_gemm_skinny(x, *w, n, EPI_F16, out, nullptr, nullptr, static_cast<float *>(ws),
                                              static_cast<hipStream_t>(stream)));
@@ -534,12 +535,22 @@ relax_status layer_enqueue(const relax_layer_dims &dm, const relax_layer_weights
     auto mat_ok = [&](const relax_qmat &wq, const void *xin, int epi) {
         return (n <= kSkinnyMaxN && gemm_skinny_eligible(wq, xin, n, epi)) || (n >= kGemmMinN && gemm_mfma_eligible(wq, xin, epi));
     };
+    auto few_row = [&](const relax_qmat &wq, const void *xin, int epi) {      // the few-row kernel takes this matmul
+        if (gemm_prefers_tiled(wq.m, n) && n >= kGemmMinN && gemm_mfma_eligible(wq, xin, epi)) return false;
+        return n <= kSkinnyMaxN && gemm_skinny_eligible(wq, xin, n, epi);
+    };
     auto matmul = [&](const uint16_t *xin, const relax_qmat &wq, int epi, uint16_t *o16, float *o32, const void *resid) {
-        if (n <= kSkinnyMaxN && gemm_skinny_eligible(wq, xin, n, epi))
-            return launch_gemm_skinny(xin, wq, n, epi, o16, o32, resid, skinny_ws, st_);
+        if (few_row(wq, xin, epi)) return launch_gemm_skinny(xin, wq, n, epi, o16, o32, resid, skinny_ws, st_);
         return launch_gemm_mfma(xin, wq, n, epi, o16, o32, resid, st_);
     };
-    if (n >= kSkinnyMinN && mat_ok(wt->wqkv, x, EPI_F16) && mat_ok(wt->wo, x, EPI_RESID_F32) && mat_ok(wt->wgu, x, EPI_SWIGLU) &&
+    // Two rows of a small model stay on the matvec kernels, one pass over the weights per row: the second pass finds most of a
+    // matrix of this size in the last-level cache, and the matvec path needs no separate norm / finishing launches (measured on
+    // the 7B layer shape: 81 against 107 us at two rows, 116 against 122 at three, 147 against 144 at four; on the 70B shape,
+    // whose matrices do not fit, the matrix path is 3 to 5 times faster from two rows on).
+    const size_t largest = std::max(std::max((size_t)wt->wqkv.m * wt->wqkv.k, (size_t)wt->wo.m * wt->wo.k),
+                                    std::max((size_t)wt->wgu.m * wt->wgu.k, (size_t)wt->wdown.m * wt->wdown.k)) / 2;
+    const bool rows_as_matvecs = n == 2 && largest <= ((size_t)64 << 20);
+    if (n >= kSkinnyMinN && !rows_as_matvecs && mat_ok(wt->wqkv, x, EPI_F16) && mat_ok(wt->wo, x, EPI_RESID_F32) && mat_ok(wt->wgu, x, EPI_SWIGLU) &&
         mat_ok(wt->wdown, x, EPI_RESID_F16)) {
         uint16_t *xn = reinterpret_cast<uint16_t *>(base + pl.xn), *qkv = reinterpret_cast<uint16_t *>(base + pl.qkv);
         uint16_t *attn_o = reinterpret_cast<uint16_t *>(base + pl.attn), *act_o = reinterpret_cast<uint16_t *>(base + pl.act);
@@ -547,7 +558,7 @@ relax_status layer_enqueue(const relax_layer_dims &dm, const relax_layer_weights
         // few rows: the finishing pass of a split-K matmul also does the light step that follows it (rotary + append, RMSNorm)
         hipError_t fuse_err = hipSuccess;
         auto fused = [&](const uint16_t *xin, const relax_qmat &wq, int epi, uint16_t *o16, float *o32, const void *resid, const SkinnyFuse &f) {
-            if (!g_opt_fuse_finish || n > kSkinnyMaxN || !gemm_skinny_eligible(wq, xin, n, epi) || !gemm_skinny_fuse_ok(wq, epi, f)) return false;
+            if (!g_opt_fuse_finish || !few_row(wq, xin, epi) || !gemm_skinny_fuse_ok(wq, epi, f)) return false;
             fuse_err = launch_gemm_skinny(xin, wq, n, epi, o16, o32, resid, skinny_ws, st_, &f);
             return true;
         };

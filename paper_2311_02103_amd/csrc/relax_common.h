@@ -161,6 +161,11 @@ hipError_t launch_gemm_mfma(const uint16_t *x, const relax_qmat &w, int n, int e
 constexpr int kSkinnyMinN = 2;       // rows from which the layer takes the matrix path (norm, matmuls, rope as separate launches)
 constexpr int kSkinnyMaxN = 128;     // rows up to which the few-row kernel replaces the tiled GEMM
 bool gemm_skinny_eligible(const relax_qmat &w, const void *x, int n, int epi);
+// Which of the two MFMA kernels takes n rows (Sec. 5.1: the dispatch follows the runtime value of the symbolic dim).  The
+// few-row kernel streams the weights once and is the faster one up to 128 rows on matrices of up to ~12k rows; on taller
+// matrices the tiled GEMM fills the CUs with tiles of its own and wins earlier (measured, 16-row steps: 22016 x 4096 from 80
+// rows, 47 against 63 us; 57344 x 8192 from 48 rows, 146 against 158 us; 12288 x 4096 and smaller: never up to 128 rows).
+inline bool gemm_prefers_tiled(int m, int n) { return (n > 64 && m >= 16384) || (n >= 48 && m >= 49152); }
 size_t gemm_skinny_partial_floats(int m, int k, int n);
 // Optional light step folded into the finishing pass of the few-row matmul (one launch less):
 //   residual epilogues: also xn = RMSNorm(result) * norm_w (what the next matmul of the layer, or of the next layer, reads);

@@ -481,6 +481,21 @@ def test_llama7b_layer_prefill_128(rx):
     assert_close(*outs[0], "7B prefill n=128")
 
 
+def test_llama7b_layer_row_counts_around_the_dispatch_boundaries(rx):
+    """The same binary picks the kernels from n: two rows of a small model stay on the matvec kernels, three take the
+    few-row path; at 64 rows every matmul is the few-row kernel, at 65 and 96 the tall gate/up matrix goes to the tiled
+    GEMM while the other three stay (their finishing passes still fold the light steps)."""
+    calls = [([40, 25], [40, 25], [0, 1]),            # 65 rows, two prefills
+             ([1, 1], [41, 26], [0, 1]),              # two decode rows
+             ([1, 1, 1], [42, 27, 1], [0, 1, 2]),     # three
+             ([64], [64], [3]), ([96], [96], [2])]
+    outs, (Kg, Vg), (Ko, Vo) = run_schedule(rx, wl.LLAMA7B, 5, 100, calls, slots=4, n_max=96)
+    for ci, (g, r) in enumerate(outs):
+        assert_close(g, r, "7B dispatch boundaries, call %d" % ci)
+    assert_close(Kg, Ko, "K cache", atol=5e-3, rtol=5e-3)
+    assert_close(Vg, Vo, "V cache", atol=5e-3, rtol=5e-3)
+
+
 @pytest.mark.parametrize("n", [511, 2048])
 def test_llama7b_layer_prefill_full_sizes(rx, n):
     """The remaining row counts of the symbolic-n configuration, every row and the whole appended cache against the
