@@ -85,6 +85,7 @@ void plan_memory(MemPlan &mp, int n_ops)
 // pure function of (dims, n, L, B); a call sized by upper bounds covers every smaller call.
 struct WsPlan {
     size_t sync, f_q, f_knew, f_vnew, f_attn, f_x1, f_act, f_part, f_end, table, partials, partials_end, qbuf, attn, x1, act, xn, qkv, skinny, total;
+    size_t mm_floats;                // fp32 elements of the matmul workspace (at `skinny`)
     MemPlan mem;
 };
 
@@ -118,7 +119,13 @@ WsPlan plan_ws(const relax_layer_dims &dm, int32_t n, int32_t L, int32_t B)
     const size_t f2 = gemm_skinny_partial_floats(dm.hidden, (int)hd, ns), f3 = gemm_skinny_partial_floats(2 * dm.ffn, dm.hidden, ns),
                  f4 = gemm_skinny_partial_floats(dm.hidden, dm.ffn, ns);
     fl = fl > f2 ? fl : f2, fl = fl > f3 ? fl : f3, fl = fl > f4 ? fl : f4;
+    // ... or the partial tiles of the k-split form of the tiled GEMM (a few hundred rows on a matrix with few tiles)
+    fl = std::max(std::max(fl, gemm_splitk_partial_floats((int)qkvw, dm.hidden, n, EPI_F16)),
+                  std::max(gemm_splitk_partial_floats(dm.hidden, (int)hd, n, EPI_RESID_F32),
+                           std::max(gemm_splitk_partial_floats(2 * dm.ffn, dm.hidden, n, EPI_SWIGLU),
+                                    gemm_splitk_partial_floats(dm.hidden, dm.ffn, n, EPI_RESID_F16))));
     const SymBytes mmws = {0, 1, sizeof(float) * fl};
+    p.mm_floats = fl;
     auto rows = [&](size_t per_row) { return SymBytes{per_row, 0, per_row * (size_t)n}; };
     MemPlan &mp = p.mem;
     const int kNever = 1 << 20;
@@ -392,7 +399,7 @@ size_t relax_matmul_workspace_bytes(const relax_qmat *w, int32_t n_max)
 {
     if (check_qmat(w) != RELAX_OK || n_max < 1) return 0;
     const int ns = n_max < kSkinnyMaxN ? n_max : kSkinnyMaxN;
-    return align256(sizeof(float) * gemm_skinny_partial_floats(w->m, w->k, ns));
+    return align256(sizeof(float) * std::max(gemm_skinny_partial_floats(w->m, w->k, ns), gemm_splitk_partial_floats(w->m, w->k, n_max, EPI_F16)));
 }
 
 relax_status relax_dequant_matmul(const uint16_t *x, const relax_qmat *w, uint16_t *out, int32_t n, void *ws, size_t ws_bytes,
@@ -410,7 +417,8 @@ relax_status relax_dequant_matmul(const uint16_t *x, const relax_qmat *w, uint16
         return hip_status(launch_gemm_skinny(x, *w, n, EPI_F16, out, nullptr, nullptr, static_cast<float *>(ws),
                                              static_cast<hipStream_t>(stream)));
     if (n >= kGemmMinN && gemm_mfma_eligible(*w, x, EPI_F16))
-        return hip_status(launch_gemm_mfma(x, *w, n, EPI_F16, out, nullptr, nullptr, static_cast<hipStream_t>(stream)));
+        return hip_status(launch_gemm_mfma(x, *w, n, EPI_F16, out, nullptr, nullptr, static_cast<hipStream_t>(stream), static_cast<float *>(ws),
+                                           ws ? ws_bytes / sizeof(float) : 0));
     GemvArgs a = {};
     a.x = x, a.q = w->q, a.s = w->s, a.m = w->m, a.k = w->k, a.n = n, a.out_f16 = out;
     a.trace = g_trace;
@@ -541,7 +549,7 @@ relax_status layer_enqueue(const relax_layer_dims &dm, const relax_layer_weights
     };
     auto matmul = [&](const uint16_t *xin, const relax_qmat &wq, int epi, uint16_t *o16, float *o32, const void *resid) {
         if (few_row(wq, xin, epi)) return launch_gemm_skinny(xin, wq, n, epi, o16, o32, resid, skinny_ws, st_);
-        return launch_gemm_mfma(xin, wq, n, epi, o16, o32, resid, st_);
+        return launch_gemm_mfma(xin, wq, n, epi, o16, o32, resid, st_, skinny_ws, pl.mm_floats);
     };
     // Two rows of a small model stay on the matvec kernels, one pass over the weights per row: the second pass finds most of a
     // matrix of this size in the last-level cache, and the matvec path needs no separate norm / finishing launches (measured on

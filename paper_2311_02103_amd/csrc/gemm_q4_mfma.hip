@@ -82,7 +82,10 @@ struct GemmArgs {
     const uint16_t *s;       // [m,k/32]
     int32_t n, m, k;
     int32_t epi;
-    int32_t tiles_m;         // weight-row tiles of the launch (the grid is one-dimensional: tiles_m * x-row tiles)
+    int32_t tiles_m;         // weight-row tiles of the launch (the grid is one-dimensional: tiles_m * x-row tiles * k splits)
+    int32_t tiles_n;         // x-row tiles
+    int32_t kb_per_split;    // k blocks (of BK columns) per k split, even; one split: all of them
+    float *partial;          // more than one k split: [split][n][m] fp32 partial tiles, finished by the few-row kernel's finishing pass
     uint16_t *out_f16;       // EPI_F16: [n,m]; EPI_RESID_F16: [n,m]; EPI_SWIGLU: [n,m/2]
     float *out_f32;          // EPI_RESID_F32: [n,m]
     const void *resid;       // EPI_RESID_F32: fp16 [n,m]; EPI_RESID_F16: fp32 [n,m]
@@ -111,7 +114,7 @@ __global__ __launch_bounds__(kThreadsG) void gemm_q4_mfma_kernel(GemmArgs a)
     // workgroup streams is then fetched into one L2 instead of eight.
     const int nb = gridDim.x, xcd = blockIdx.x & 7, idx = blockIdx.x >> 3;
     const int tile = xcd * (nb >> 3) + min(xcd, nb & 7) + idx;
-    const int tile_m = tile % a.tiles_m, tile_n = tile / a.tiles_m;
+    const int tile_m = tile % a.tiles_m, tile_n = (tile / a.tiles_m) % a.tiles_n, split = tile / (a.tiles_m * a.tiles_n);
     const int n0 = tile_n * BN;
     const int kw = a.k >> 3, G = a.k >> 5;
     const int F = a.m >> 1;
@@ -140,9 +143,10 @@ __global__ __launch_bounds__(kThreadsG) void gemm_q4_mfma_kernel(GemmArgs a)
         uint32_t wsc;
         uint4 xr[XP];
     };
-    const int nkb = a.k / BK;
+    const int kb0 = split * a.kb_per_split;               // this workgroup's k range: blocks kb0 .. kb0 + nkb - 1
+    const int nkb = min(a.kb_per_split, a.k / BK - kb0);
     auto stage_load = [&](Stage &S, int kb) {             // kb is clamped: the tail re-reads the last block (never consumed)
-        kb = min(kb, nkb - 1);
+        kb = kb0 + min(kb, nkb - 1);
 #pragma unroll
         for (int i = 0; i < W / 4; ++i) S.wq[i] = *(const uint4 *)(qsrc + kb * (BK / 8) + i * 4);
         if (W == 8) S.wsc = *(const uint32_t *)(ssrc + kb * (BK / 32));
@@ -249,6 +253,33 @@ __global__ __launch_bounds__(kThreadsG) void gemm_q4_mfma_kernel(GemmArgs a)
     }
 
     // ---- epilogue.  acc[f][j][v]: tile row of fragment f + 8 (v/4) + 4 (lane/32) + v%4, x row n0 + 32 (NF wn + j) + lane%32 ----
+    if (a.partial) {
+        // k split: the raw fp32 tile goes to partial[split][x row][weight row] (gate rows first, up rows from F on, as in the
+        // matrix), and the finishing pass adds the splits in order and applies the epilogue
+#pragma unroll
+        for (int j = 0; j < NF; ++j) {
+            const int xrow = n0 + (wn * NF + j) * 32 + row32;
+            if (xrow >= a.n) continue;
+            float *dst = a.partial + ((size_t)split * a.n + xrow) * a.m;
+#pragma unroll
+            for (int f = 0; f < MF; ++f)
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    const int off = b * 8 + hf * 4;
+                    int row;                                     // matrix row of this granule of four
+                    bool ok;
+                    if (EPI == EPI_SWIGLU) {
+                        const int g = tile_m * (BM / 2) + (wm * (MF / 2) + f % (MF / 2)) * 32 + off;
+                        row = (f / (MF / 2)) * F + g, ok = g < F;
+                    } else {
+                        row = tile_m * BM + (wm * MF + f) * 32 + off, ok = row < a.m;
+                    }
+                    if (ok)
+                        *(float4 *)(dst + row) = make_float4(acc[f][j][b * 4], acc[f][j][b * 4 + 1], acc[f][j][b * 4 + 2], acc[f][j][b * 4 + 3]);
+                }
+        }
+        return;
+    }
 #pragma unroll
     for (int j = 0; j < NF; ++j) {
         const int xrow = n0 + (wn * NF + j) * 32 + row32;
@@ -301,13 +332,16 @@ __global__ __launch_bounds__(kThreadsG) void gemm_q4_mfma_kernel(GemmArgs a)
 }
 
 template <int MF, int NF>
-hipError_t launch_tile(const GemmArgs &a_in, hipStream_t stream)
+hipError_t launch_tile(const GemmArgs &a_in, hipStream_t stream, int splits)
 {
     constexpr int BM = 64 * MF, BN = 64 * NF;
     const int rows = a_in.epi == EPI_SWIGLU ? a_in.m / 2 : a_in.m, per_block = a_in.epi == EPI_SWIGLU ? BM / 2 : BM;
     GemmArgs a = a_in;
     a.tiles_m = (rows + per_block - 1) / per_block;
-    dim3 grid(a.tiles_m * ((a.n + BN - 1) / BN));
+    a.tiles_n = (a.n + BN - 1) / BN;
+    const int nkb = a.k / BK, tiles = a.tiles_m * a.tiles_n;
+    if (splits < 2) a.partial = nullptr, a.kb_per_split = nkb, splits = 1;
+    dim3 grid(tiles * splits);
     const size_t lds = 2 * (size_t)(BM + BN) * kPitch * sizeof(uint16_t);    // up to 147456 bytes: one workgroup per CU
     static bool attr_done = false;
     if (!attr_done) {
@@ -341,17 +375,21 @@ bool gemm_mfma_eligible(const relax_qmat &w, const void *x, int epi)
 
 // Tile choice for n > 128: 256 x 256, 128 x 256 or 128 x 128 (weight rows x x-rows), whichever leaves the largest
 // useful share of the rounds of workgroups over the 256 CUs (one workgroup per CU); ties go to the wider tile.
-// Small n takes narrower x tiles.
-hipError_t launch_gemm_mfma(const uint16_t *x, const relax_qmat &w, int n, int epi, uint16_t *out_f16, float *out_f32, const void *resid,
-                            hipStream_t stream)
+// Small n takes narrower x tiles.  A launch whose tiles would leave more than half of the CUs idle (few weight rows, few
+// x rows: the output and down projections of a prefill chunk of a few hundred rows) is cut along k as well, into about one
+// workgroup per CU with at least 8 k blocks each; the fp32 partial tiles go to the caller's workspace and the finishing pass
+// of the few-row kernel adds them in order and applies the epilogue.
+namespace {
+struct TilePlan {
+    int mf, nf, splits, kb_per_split;
+};
+TilePlan tile_plan(int m, int k, int n, int epi)
 {
-    GemmArgs a;
-    a.x = x, a.q = w.q, a.s = w.s, a.n = n, a.m = w.m, a.k = w.k, a.epi = epi;
-    a.out_f16 = out_f16, a.out_f32 = out_f32, a.resid = resid;
-    const long rows = epi == EPI_SWIGLU ? w.m / 2 : w.m;
+    const long rows = epi == EPI_SWIGLU ? m / 2 : m;
     const long rdiv = epi == EPI_SWIGLU ? 2 : 1;
     auto blocks = [&](int mf, int nf) { return ((rows + 64 * mf / rdiv - 1) / (64 * mf / rdiv)) * (long)((n + 64 * nf - 1) / (64 * nf)); };
     const long kCUs = 256;
+    TilePlan p = {2, 1, 1, k / BK};
     if (n > 128) {
         // useful share of the workgroup rounds: padding rows of ragged tiles and idle CUs of the last round both count as waste;
         // the 128 x 128 tile pays about a fifth more LDS traffic per MFMA than the two wide ones
@@ -361,12 +399,57 @@ hipError_t launch_gemm_mfma(const uint16_t *x, const relax_qmat &w, int n, int e
             return tile_eff * (double)rows * (double)n / (rounds * kCUs * (64.0 * mf / rdiv) * (64.0 * nf));
         };
         const double s44 = score(4, 4, 1.0), s24 = score(2, 4, 1.0), s22 = score(2, 2, 0.8);
-        if (s44 >= s24 && s44 >= s22) return launch_tile<4, 4>(a, stream);
-        if (s24 >= s22) return launch_tile<2, 4>(a, stream);
-        return launch_tile<2, 2>(a, stream);
+        if (s44 >= s24 && s44 >= s22) p.mf = 4, p.nf = 4;
+        else if (s24 >= s22) p.mf = 2, p.nf = 4;
+        else p.mf = 2, p.nf = 2;
+        const long tiles = blocks(p.mf, p.nf);
+        const int nkb = k / BK;
+        if (n <= kSplitKMaxN && tiles <= kCUs / 2) {
+            int splits = std::max(1, std::min(std::min(kSplitKMax, (int)(kCUs / tiles)), nkb / 8));
+            p.kb_per_split = ((nkb + splits - 1) / splits + 1) & ~1;
+            p.splits = (nkb + p.kb_per_split - 1) / p.kb_per_split;
+            if (p.splits < 2) p.splits = 1, p.kb_per_split = nkb;
+        }
+    } else if (n > 64) {
+        p.mf = 2, p.nf = 2;
     }
-    if (n > 64) return launch_tile<2, 2>(a, stream);
-    return launch_tile<2, 1>(a, stream);
+    return p;
+}
+}  // namespace
+
+// fp32 elements of workspace the k-split form may need for any row count up to n (0: it never splits this matrix)
+size_t gemm_splitk_partial_floats(int m, int k, int n, int epi)
+{
+    if (k % (2 * BK) != 0) return 0;
+    size_t worst = 0;
+    const int top = n < kSplitKMaxN ? n : kSplitKMaxN;
+    for (int nn = 256; nn <= top + 127; nn += 128) {               // splits change with the tile counts only: the top of each bracket
+        const int r = nn < top ? nn : top;
+        if (r <= 128) continue;
+        const TilePlan p = tile_plan(m, k, r, epi);
+        if (p.splits > 1) worst = std::max(worst, (size_t)p.splits * (size_t)r * (size_t)m);
+    }
+    return worst;
+}
+
+hipError_t launch_gemm_mfma(const uint16_t *x, const relax_qmat &w, int n, int epi, uint16_t *out_f16, float *out_f32, const void *resid,
+                            hipStream_t stream, float *partial, size_t partial_floats)
+{
+    GemmArgs a;
+    a.x = x, a.q = w.q, a.s = w.s, a.n = n, a.m = w.m, a.k = w.k, a.epi = epi;
+    a.out_f16 = out_f16, a.out_f32 = out_f32, a.resid = resid;
+    TilePlan p = tile_plan(w.m, w.k, n, epi);
+    if (p.splits > 1 && (!partial || (reinterpret_cast<uintptr_t>(partial) & 15) != 0 || partial_floats < (size_t)p.splits * n * w.m))
+        p.splits = 1, p.kb_per_split = w.k / BK;                  // no workspace for the partial tiles: one pass over k
+    a.partial = p.splits > 1 ? partial : nullptr;
+    a.kb_per_split = p.kb_per_split;
+    hipError_t e;
+    if (p.mf == 4) e = launch_tile<4, 4>(a, stream, p.splits);
+    else if (p.nf == 4) e = launch_tile<2, 4>(a, stream, p.splits);
+    else if (p.nf == 2) e = launch_tile<2, 2>(a, stream, p.splits);
+    else e = launch_tile<2, 1>(a, stream, p.splits);
+    if (e != hipSuccess || p.splits < 2) return e;
+    return launch_skinny_finish(partial, p.splits, n, w.m, epi, out_f16, out_f32, resid, stream, nullptr);
 }
 
 }  // namespace relax

@@ -487,6 +487,15 @@ hipError_t launch_gemm_skinny(const uint16_t *x, const relax_qmat &w, int n, int
     else if (n <= 64) e = launch_skinny<2, 64, 256>(a, grid, stream);
     else e = launch_skinny<4, 128, 128>(a, grid, stream);
     if (e != hipSuccess) return e;
+    return launch_skinny_finish(partial, splits, n, w.m, epi, out_f16, out_f32, resid, stream, fuse);
+}
+
+// The finishing pass alone: out = epilogue(sum over splits, in order, of partial[s][i][r]) (+ the folded light step).  Also serves the
+// k-split form of the tiled GEMM, whose partial tiles have the same layout.
+hipError_t launch_skinny_finish(const float *partial, int splits, int n, int m, int epi, uint16_t *out_f16, float *out_f32, const void *resid,
+                                hipStream_t stream, const SkinnyFuse *fuse)
+{
+    struct { int m; } w = {m};
     if (fuse) {                                           // the caller checked gemm_skinny_fuse_ok
         if (epi == EPI_RESID_F32)
             hipLaunchKernelGGL(skinny_finish_norm_kernel<EPI_RESID_F32>, dim3(n), dim3(norm_block_threads(w.m, n)), 0, stream, partial, splits, n, w.m, out_f16, out_f32, resid,

@@ -155,8 +155,12 @@ hipError_t launch_rmsnorm_f32(const float *x, const uint16_t *w, uint16_t *y, in
 // MFMA GEMM for large n (gemm_q4_mfma.hip)
 constexpr int kGemmMinN = 16;        // rows from which the MFMA GEMM replaces one matvec pass per row
 bool gemm_mfma_eligible(const relax_qmat &w, const void *x, int epi);
+constexpr int kSplitKMax = 8;         // k splits of the tiled GEMM at most, when its tiles alone leave more than half of the CUs idle
+constexpr int kSplitKMaxN = 512;      // ... and only up to this many rows (the partial tiles are splits * n * m floats)
+size_t gemm_splitk_partial_floats(int m, int k, int n, int epi);
+// partial: optional workspace of partial_floats fp32 for the k-split form (without it the launch makes one pass over k)
 hipError_t launch_gemm_mfma(const uint16_t *x, const relax_qmat &w, int n, int epi, uint16_t *out_f16, float *out_f32, const void *resid,
-                            hipStream_t stream);
+                            hipStream_t stream, float *partial = nullptr, size_t partial_floats = 0);
 // MFMA matmul for a few rows, split-K with partial tiles in the workspace (gemm_q4_skinny.hip)
 constexpr int kSkinnyMinN = 2;       // rows from which the layer takes the matrix path (norm, matmuls, rope as separate launches)
 constexpr int kSkinnyMaxN = 128;     // rows up to which the few-row kernel replaces the tiled GEMM
@@ -179,6 +183,8 @@ struct SkinnyFuse {
     const SeqTable *st;
 };
 bool gemm_skinny_fuse_ok(const relax_qmat &w, int epi, const SkinnyFuse &f);
+hipError_t launch_skinny_finish(const float *partial, int splits, int n, int m, int epi, uint16_t *out_f16, float *out_f32, const void *resid,
+                                hipStream_t stream, const SkinnyFuse *fuse);
 hipError_t launch_gemm_skinny(const uint16_t *x, const relax_qmat &w, int n, int epi, uint16_t *out_f16, float *out_f32, const void *resid,
                               float *partial, hipStream_t stream, const SkinnyFuse *fuse = nullptr);
 hipError_t launch_rope_append(uint16_t *qkv, const relax_layer_dims &dm, const relax_kv_cache &cache,

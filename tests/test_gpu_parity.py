@@ -423,7 +423,9 @@ def test_gemm_random_against_oracle_and_matvec_path(rx, m, k, n):
 
 # ------------------------------------------------------------------------- few-row split-K MFMA kernel (2 <= n <= 64, k % 256 == 0)
 @pytest.mark.parametrize("m,k,n", [(128, 256, 2), (100, 512, 5), (260, 1024, 16), (512, 4096, 32), (132, 11008, 33), (1024, 2048, 64),
-                                   (260, 512, 65), (512, 4096, 128), (132, 11008, 100)])
+                                   (260, 512, 65), (512, 4096, 128), (132, 11008, 100),
+                                   # above 128 rows with a workspace: the tiled GEMM, cut along k where its tiles are few
+                                   (516, 4096, 129), (1000, 11008, 300), (260, 2048, 512)])
 def test_skinny_integer_valued_bitwise(rx, m, k, n):
     r = np.random.RandomState(m + k + n)
     codes = r.randint(0, 16, size=(m, k)).astype(np.uint8)
@@ -440,7 +442,8 @@ def test_skinny_integer_valued_bitwise(rx, m, k, n):
 
 
 @pytest.mark.parametrize("m,k,n", [(768, 256, 3), (4096, 4096, 16), (8192, 8192, 16), (512, 28672, 7), (12288, 4096, 40), (1000, 1024, 64),
-                                   (4096, 4096, 128), (1000, 11008, 97), (768, 256, 65)])
+                                   (4096, 4096, 128), (1000, 11008, 97), (768, 256, 65),
+                                   (4096, 4096, 200), (4096, 11008, 130), (8192, 1024, 511)])     # k-split tiled GEMM (8, 8 and 2 splits)
 def test_skinny_random_against_oracle_and_reproducible(rx, m, k, n):
     q, s = wl.qmat(8, m * 7 + k, m, k)
     x = wl.normal_f16_bits(8, n, (n, k))
@@ -496,10 +499,11 @@ def test_llama7b_layer_row_counts_around_the_dispatch_boundaries(rx):
     assert_close(Vg, Vo, "V cache", atol=5e-3, rtol=5e-3)
 
 
-@pytest.mark.parametrize("n", [511, 2048])
+@pytest.mark.parametrize("n", [200, 511, 2048])
 def test_llama7b_layer_prefill_full_sizes(rx, n):
     """The remaining row counts of the symbolic-n configuration, every row and the whole appended cache against the
-    oracle (511: ragged tiles everywhere; 2048: the size the prefill figures are quoted on)."""
+    oracle (200: the tiled GEMM of the output and down projections is cut along k into 4 splits, finished by the few-row
+    kernel's finishing pass; 511: ragged tiles everywhere, 2 splits; 2048: the size the prefill figures are quoted on)."""
     outs, (Kg, Vg), (Ko, Vo) = run_schedule(rx, wl.LLAMA7B, 2, n, [([n], [n], None)])
     assert_close(*outs[0], "7B prefill n=%d" % n)
     assert_close(Kg[0, :n], Ko[0, :n], "appended K", atol=5e-3, rtol=5e-3)
