@@ -12,6 +12,9 @@ Other workloads (--workload), same JSON schema, for the other configurations:
                  a step is one relax_model_step call = one generated token.
   batched_70b    configs[4]: Llama-2-70B-shaped GQA model, 80 layers, 16 sequences with L_b ~ U{100..8000};
                  a step is one relax_model_step call = 16 generated tokens.
+  ceilings       what this device reaches on a plain streaming read, a chain of streaming launches and a bare MFMA loop.
+  batch_sweep    one 7B-shaped layer call on n decode rows against n (where the dispatch on n changes kernels).
+  memory_plan    host-only: planned against unplanned bytes of the layer's intermediates (Alg. 3 of the paper).
 All inputs are seeded and synthetic and resident in HBM before the timed region.
 """
 import argparse
