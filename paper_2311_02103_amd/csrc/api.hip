@@ -566,9 +566,16 @@ relax_status layer_enqueue(const relax_layer_dims &dm, const relax_layer_weights
         // few rows: the finishing pass of a split-K matmul also does the light step that follows it (rotary + append, RMSNorm)
         hipError_t fuse_err = hipSuccess;
         auto fused = [&](const uint16_t *xin, const relax_qmat &wq, int epi, uint16_t *o16, float *o32, const void *resid, const SkinnyFuse &f) {
-            if (!g_opt_fuse_finish || !few_row(wq, xin, epi) || !gemm_skinny_fuse_ok(wq, epi, f)) return false;
-            fuse_err = launch_gemm_skinny(xin, wq, n, epi, o16, o32, resid, skinny_ws, st_, &f);
-            return true;
+            if (!g_opt_fuse_finish || !gemm_skinny_fuse_ok(wq, epi, f)) return false;
+            if (few_row(wq, xin, epi)) {
+                fuse_err = launch_gemm_skinny(xin, wq, n, epi, o16, o32, resid, skinny_ws, st_, &f);
+                return true;
+            }
+            if (n >= kGemmMinN && gemm_mfma_eligible(wq, xin, epi) && gemm_mfma_splits(wq, n, epi, skinny_ws, pl.mm_floats) > 1) {
+                fuse_err = launch_gemm_mfma(xin, wq, n, epi, o16, o32, resid, st_, skinny_ws, pl.mm_floats, &f);    // k-split tiled GEMM
+                return true;
+            }
+            return false;
         };
         timer.before(0);
         if (!xn_ready && launch_rmsnorm(x, wt->norm_attn, xn, n, dm.hidden, dm.rms_eps, st_) != hipSuccess) return RELAX_ERR_HIP;

@@ -432,15 +432,24 @@ size_t gemm_splitk_partial_floats(int m, int k, int n, int epi)
     return worst;
 }
 
+// k splits the launch would make for n rows with this much workspace (1: one pass over k, no finishing pass)
+int gemm_mfma_splits(const relax_qmat &w, int n, int epi, const float *partial, size_t partial_floats)
+{
+    const TilePlan p = tile_plan(w.m, w.k, n, epi);
+    if (p.splits > 1 && (!partial || (reinterpret_cast<uintptr_t>(partial) & 15) != 0 || partial_floats < (size_t)p.splits * n * w.m)) return 1;
+    return p.splits;
+}
+
 hipError_t launch_gemm_mfma(const uint16_t *x, const relax_qmat &w, int n, int epi, uint16_t *out_f16, float *out_f32, const void *resid,
-                            hipStream_t stream, float *partial, size_t partial_floats)
+                            hipStream_t stream, float *partial, size_t partial_floats, const SkinnyFuse *fuse)
 {
     GemmArgs a;
     a.x = x, a.q = w.q, a.s = w.s, a.n = n, a.m = w.m, a.k = w.k, a.epi = epi;
     a.out_f16 = out_f16, a.out_f32 = out_f32, a.resid = resid;
     TilePlan p = tile_plan(w.m, w.k, n, epi);
-    if (p.splits > 1 && (!partial || (reinterpret_cast<uintptr_t>(partial) & 15) != 0 || partial_floats < (size_t)p.splits * n * w.m))
+    if (p.splits > 1 && gemm_mfma_splits(w, n, epi, partial, partial_floats) == 1)
         p.splits = 1, p.kb_per_split = w.k / BK;                  // no workspace for the partial tiles: one pass over k
+    if (fuse && p.splits < 2) return hipErrorInvalidValue;        // a folded light step needs the finishing pass
     a.partial = p.splits > 1 ? partial : nullptr;
     a.kb_per_split = p.kb_per_split;
     hipError_t e;
@@ -449,7 +458,7 @@ hipError_t launch_gemm_mfma(const uint16_t *x, const relax_qmat &w, int n, int e
     else if (p.nf == 2) e = launch_tile<2, 2>(a, stream, p.splits);
     else e = launch_tile<2, 1>(a, stream, p.splits);
     if (e != hipSuccess || p.splits < 2) return e;
-    return launch_skinny_finish(partial, p.splits, n, w.m, epi, out_f16, out_f32, resid, stream, nullptr);
+    return launch_skinny_finish(partial, p.splits, n, w.m, epi, out_f16, out_f32, resid, stream, fuse);
 }
 
 }  // namespace relax

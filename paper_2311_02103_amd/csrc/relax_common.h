@@ -159,8 +159,11 @@ constexpr int kSplitKMax = 8;         // k splits of the tiled GEMM at most, whe
 constexpr int kSplitKMaxN = 512;      // ... and only up to this many rows (the partial tiles are splits * n * m floats)
 size_t gemm_splitk_partial_floats(int m, int k, int n, int epi);
 // partial: optional workspace of partial_floats fp32 for the k-split form (without it the launch makes one pass over k)
+struct SkinnyFuse;
+int gemm_mfma_splits(const relax_qmat &w, int n, int epi, const float *partial, size_t partial_floats);
+// fuse: only for a launch that splits (gemm_mfma_splits > 1): the light step folded into its finishing pass
 hipError_t launch_gemm_mfma(const uint16_t *x, const relax_qmat &w, int n, int epi, uint16_t *out_f16, float *out_f32, const void *resid,
-                            hipStream_t stream, float *partial = nullptr, size_t partial_floats = 0);
+                            hipStream_t stream, float *partial = nullptr, size_t partial_floats = 0, const SkinnyFuse *fuse = nullptr);
 // MFMA matmul for a few rows, split-K with partial tiles in the workspace (gemm_q4_skinny.hip)
 constexpr int kSkinnyMinN = 2;       // rows from which the layer takes the matrix path (norm, matmuls, rope as separate launches)
 constexpr int kSkinnyMaxN = 128;     // rows up to which the few-row kernel replaces the tiled GEMM

@@ -135,13 +135,18 @@ def test_70b_shape_batched_decode_one_layer(rx):
     check_step(dev, od, ol, mt, wl.token_ids(17, B, V), [1] * B, kv, list(range(B)), Ko, Vo, "70B-shape batched decode")
 
 
-def test_few_row_path_with_and_without_folded_finishing_steps(rx):
+@pytest.mark.parametrize("q", [None, [150, 50]])
+def test_few_row_path_with_and_without_folded_finishing_steps(rx, q):
     """The few-row matrix path folds rotary + append and the RMSNorms into the finishing pass of its split-K matmuls
     (and the first RMSNorm of a layer into the last finishing pass of the layer before).  The folded kernels repeat the
     arithmetic of the separate ones element by element, so logits, picks and caches must be identical bit for bit."""
-    shape, V, nl, B, cap = wl.LLAMA7B, 3000, 3, 5, 64
-    dev, od, ol, mt = build_models(shape, nl, V, seed=21, cap=cap, slots=B, n_max=32, B_max=B, distinct_layers=2)
-    q = [int(v) for v in wl.uniform_lengths(21, B, 1, 6)]
+    shape, V, nl = wl.LLAMA7B, 3000, 3
+    if q is None:                                          # five short prompts: every matmul is the few-row kernel
+        B, cap = 5, 64
+        q = [int(v) for v in wl.uniform_lengths(21, B, 1, 6)]
+    else:                                                  # 200 rows: the tiled GEMM, cut along k for the output and down projections
+        B, cap = len(q), 256
+    dev, od, ol, mt = build_models(shape, nl, V, seed=21, cap=cap, slots=B, n_max=max(32, sum(q)), B_max=B, distinct_layers=2)
     ids = torch.from_numpy(wl.token_ids(21, sum(q), V)).cuda()
     results = []
     try:
