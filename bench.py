@@ -509,7 +509,7 @@ def bench_batch_sweep(args, np, torch, wl, rx):
     best = max(rows, key=lambda r: r["layer_tokens_per_s"])
     emit(args, "layer-tokens/s of one 7B-shaped int4 layer call against the number of decode rows (best point)", "tokens/s",
          best["layer_tokens_per_s"], best["us_per_call"] / 1e3, "f16 (int4 weights, f32 accumulate)",
-         {"workload": "batch sweep (§8(f) item 3, int4 part): n decode rows, one per sequence, L = 256, %d rotating weight sets" % sets,
+         {"workload": "batch sweep on the int4 path (the paper sweeps batch sizes in Sec. 5.1): n decode rows, one per sequence, L = 256, %d rotating weight sets" % sets,
           "build_id": rx.relax_build_id()}, None, None, {"batch_sweep": rows})
 
 
@@ -533,7 +533,7 @@ def bench_memory_plan(args, wl, rx):
         table[shape.name] = rows
     head = table[wl.LLAMA7B.name][3]
     emit(args, "planned / unplanned activation bytes of one layer call (7B shape, prefill of 1024 tokens)", "ratio", head["ratio"], 0.0,
-         "bytes", {"workload": "§8(f) item 2: dynamic shape-aware memory planning (Alg. 3) of the layer workspace; host-only, nothing is timed",
+         "bytes", {"workload": "dynamic shape-aware memory planning (Sec. 4.3, Alg. 3) of the layer workspace, in the shape of the paper's activation-memory experiment; host-only, nothing is timed",
                    "build_id": rx.relax_build_id()}, None, None, {"higher_is_better": False, "memory_plan": table})
 
 

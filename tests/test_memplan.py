@@ -103,7 +103,8 @@ def test_chains_against_the_fewest_storages_any_assignment_can_reach(sizes, opti
 
 # ------------------------------------------------------------------------------------------------ the library's plan
 def layer_program(hidden, n_heads, n_kv_heads, head_dim, ffn):
-    """The layer as the sequence of destination-passing operations the design doc lists (steps 1-5 of the path; the second norm
+    """The layer as its sequence of destination-passing operations (norm + QKV + rotary + append, attention, output
+    projection + residual, gate/up + SwiGLU, down + residual; the second norm
     is an operation of its own), with the sizes of its intermediates in bytes per row, written out independently of
     the library: xn fp16 [n,H]; qkv fp16 [n,(h+2g)d]; attention output fp16 [n,hd]; x1 fp32 [n,H]; act fp16 [n,F]; the
     lifted workspaces of the few-row matmul (one expression, requested around each matmul) and of split-L attention."""
