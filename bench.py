@@ -15,6 +15,7 @@ Other workloads (--workload), same JSON schema, for the other configurations:
   ceilings       what this device reaches on a plain streaming read, a chain of streaming launches and a bare MFMA loop.
   batch_sweep    one 7B-shaped layer call on n decode rows against n (where the dispatch on n changes kernels).
   memory_plan    host-only: planned against unplanned bytes of the layer's intermediates (Alg. 3 of the paper).
+  half_sweep     relax_half_matmul (plain fp16 weights) against n, matvec passes and tiled GEMM forced in turn: the crossover.
 All inputs are seeded and synthetic and resident in HBM before the timed region.
 """
 import argparse
@@ -513,6 +514,57 @@ def bench_batch_sweep(args, np, torch, wl, rx):
           "build_id": rx.relax_build_id()}, None, None, {"batch_sweep": rows})
 
 
+# ------------------------------------------------------------------------------------------------ fp16-weight sweep
+def bench_half_sweep(args, np, torch, wl, rx):
+    """relax_half_matmul (plain fp16 weights) against the row count n on two 7B-shaped matrices, with the matvec passes and the
+    tiled GEMM forced in turn: where the matrix-vector form stops paying (Sec. 5.1 of the paper: its LLM charts sweep the batch
+    size on fp16 weights).  Weight copies are rotated so that each launch streams its matrix from HBM."""
+    steps = args.steps = args.steps or 30
+    warmup = args.warmup = 5 if args.warmup is None else args.warmup
+    ns = [1, 2, 4, 8, 9, 10, 12, 16, 24, 32, 64, 128, 256, 512, 1024, 2048]
+    stream = torch.cuda.Stream()
+    table = {}
+    try:
+        for name, (m, k) in (("o_proj 4096x4096", (4096, 4096)), ("gate_up 22016x4096", (22016, 4096))):
+            copies = max(3, int(600e6 // (m * k * 2)))
+            ws_ = [(torch.randn((m, k), device="cuda", dtype=torch.float32) * 0.02).to(torch.float16) for _ in range(copies)]
+            rows = []
+            x = torch.randn((8, k), device="cuda", dtype=torch.float16)
+            out = torch.empty((8, m), dtype=torch.float16, device="cuda")
+            for i in range(4 * copies):                   # first touches of the fresh copies (address translation) stay out of the sweep
+                rx.check(rx.relax_half_matmul(x, ws_[i % copies], out, 8, m, k, stream))
+            stream.synchronize()
+            for n in ns:
+                x = torch.randn((n, k), device="cuda", dtype=torch.float16)
+                out = torch.empty((n, m), dtype=torch.float16, device="cuda")
+                res = {"n": n}
+                for label, gemm_rows in (("matvec_us", 10 ** 6), ("gemm_us", 1)):
+                    if label == "matvec_us" and n > 64:
+                        continue                        # n / 8 passes over the matrix: far off by then
+                    rx.check(rx.relax_set_option("half_matmul_gemm_rows", gemm_rows))
+                    for i in range(warmup):
+                        rx.check(rx.relax_half_matmul(x, ws_[i % copies], out, n, m, k, stream))
+                    stream.synchronize()
+                    t0 = time.perf_counter()
+                    for i in range(steps):
+                        rx.relax_half_matmul(x, ws_[i % copies], out, n, m, k, stream)
+                    stream.synchronize()
+                    res[label] = round((time.perf_counter() - t0) * 1e6 / steps, 1)
+                rows.append(res)
+            both = [r for r in rows if "matvec_us" in r]
+            cross = next((r["n"] for r in both if r["gemm_us"] < r["matvec_us"]), None)
+            table[name] = {"rows": rows, "gemm_faster_from_n": cross, "weight_MB": round(m * k * 2 / 1e6, 1)}
+            del ws_
+    finally:
+        rx.check(rx.relax_set_option("half_matmul_gemm_rows", 0))     # back to the default: by estimate
+    big = table["gate_up 22016x4096"]["rows"][-1]
+    tflops = 2.0 * 2048 * 22016 * 4096 / (big["gemm_us"] * 1e-6) / 1e12
+    emit(args, "fp16-weight GEMM rate at n = 2048 on the gate/up shape (22016 x 4096)", "TFLOP/s", tflops, big["gemm_us"] / 1e3, "f16 MFMA, f32 accumulate",
+         {"workload": "fp16-weight matmul against the row count, matvec passes and tiled GEMM forced in turn", "build_id": rx.relax_build_id()},
+         {"bound": "mfma", "kernel": "gemm_q4_mfma_kernel<EPI_F16, 4, 4, fp16 weights>", "achieved": round(tflops, 1), "peak": PEAK_MFMA_TFLOPS,
+          "unit": "TFLOP/s", "frac": round(tflops / PEAK_MFMA_TFLOPS, 4), "traffic": None}, None, {"half_sweep": table})
+
+
 # ------------------------------------------------------------------------------------------------ memory plan
 def bench_memory_plan(args, wl, rx):
     """The shape of the paper's activation-memory experiment (Sec. 5: prefill of 128..1024 tokens, decode at batch 1..64,
@@ -608,7 +660,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=0, help="timed steps (default: 1280 decode_layer, 50 prefill_layer, 256 model_7b, 8 batched_70b)")
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", choices=["decode_layer", "prefill_layer", "model_7b", "batched_70b", "ceilings", "memory_plan", "batch_sweep"],
+    ap.add_argument("--workload", choices=["decode_layer", "prefill_layer", "model_7b", "batched_70b", "ceilings", "memory_plan", "batch_sweep", "half_sweep"],
                     default="decode_layer")
     ap.add_argument("--n", type=int, default=2048, help="rows of the prefill_layer workload")
     ap.add_argument("--layers", type=int, default=0, help="model workloads: override the layer count (short profiling runs)")
@@ -657,6 +709,8 @@ def main():
         bench_ceilings(args, np, torch, wl, rx)
     elif args.workload == "batch_sweep":
         bench_batch_sweep(args, np, torch, wl, rx)
+    elif args.workload == "half_sweep":
+        bench_half_sweep(args, np, torch, wl, rx)
     else:
         bench_model(args, np, torch, wl, rx, big=args.workload == "batched_70b")
 

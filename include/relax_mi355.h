@@ -195,6 +195,18 @@ size_t       relax_matmul_workspace_bytes(const relax_qmat *w, int32_t n_max);
 relax_status relax_dequant_matmul(const uint16_t *x, const relax_qmat *w, uint16_t *out, int32_t n,
                                   void *ws, size_t ws_bytes, relax_stream stream);
 
+/* The same matmul with plain fp16 weights (the fp16-weight configurations of the paper's LLM evaluation,
+ * Sec. 5.1): out[i,r] = sum_c x[i,c] * w[r,c], x [n,k] fp16, w [m,k] fp16 row-major, out [n,m] fp16, fp32
+ * accumulation, dispatched on the runtime n like the int4 call: passes of up to 8 rows through the fp16
+ * matrix-vector kernel (the one the LM head uses) for a few rows, the tiled MFMA GEMM without its decode
+ * step (k % 128 == 0, m % 4 == 0) from the row count on at which its estimated time falls below that of the
+ * passes -- 24 rows on a 4096 x 4096 matrix, 8 on 22016 x 4096 (measured: bench.py --workload half_sweep).
+ * relax_set_option("half_matmul_gemm_rows", r) with r > 0 fixes the crossover at r rows instead (0, the
+ * default: by estimate).  Device pointers, x and w 16-byte aligned.  Errors: NULL, SHAPE (n<1, m<1, k<8,
+ * k%8, alignment), UNSUPPORTED (k > 73728).                                                                */
+relax_status relax_half_matmul(const uint16_t *x, const uint16_t *w, uint16_t *out, int32_t n, int32_t m,
+                               int32_t k, relax_stream stream);
+
 /* Two optional parts (the norm and the rotary step are separated by the QKV matmul, so
  * they cannot be one pass; either part is skipped when its first pointer is NULL):
  *  part 1  y[i,:] = x[i,:] * rsqrt(mean(x[i,:]^2) + eps) * w      x,y [n,H] fp16, w [H]

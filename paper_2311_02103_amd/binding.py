@@ -84,6 +84,7 @@ _SIGNATURES = {
     "relax_matmul_workspace_bytes": (C.c_size_t, [C.POINTER(QMatC), C.c_int32]),
     "relax_dequant_matmul": (C.c_int32, [C.c_void_p, C.POINTER(QMatC), C.c_void_p, C.c_int32, C.c_void_p, C.c_size_t,
                                          C.c_void_p]),
+    "relax_half_matmul": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p]),
     "relax_rmsnorm_rope": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_void_p,
                                        C.POINTER(LayerDims), C.POINTER(KVCacheC), C.POINTER(SeqsC), C.c_void_p]),
     "relax_attention": (C.c_int32, [C.c_void_p, C.POINTER(KVCacheC), C.POINTER(SeqsC), C.POINTER(LayerDims), C.c_void_p,
@@ -248,6 +249,10 @@ def relax_rmsnorm_rope(x: Ptr, w: Ptr, y: Ptr, n: int, H: int, eps: float, qkv: 
     sc = None if seqs is None else seqs.c()
     return lib().relax_rmsnorm_rope(_ptr(x), _ptr(w), _ptr(y), n, H, eps, _ptr(qkv), _ref(dims), _ref(cc), _ref(sc),
                                     _stream(stream))
+
+
+def relax_half_matmul(x: Ptr, w: Ptr, out: Ptr, n: int, m: int, k: int, stream=None) -> int:
+    return lib().relax_half_matmul(_ptr(x), _ptr(w), _ptr(out), n, m, k, _stream(stream))
 
 
 def relax_attention(q: Ptr, cache: Optional[KVCache], seqs: Optional[Seqs], dims: Optional[LayerDims], out: Ptr, n: int,

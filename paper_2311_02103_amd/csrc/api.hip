@@ -254,6 +254,7 @@ struct StepTimer {
 // Tuning / test switches (relax_set_option).
 int g_opt_fused_decode = 0;
 int g_opt_fuse_finish = 1;                   // few-row path: light steps folded into the finishing pass of the split-K matmuls
+int g_opt_half_gemm_rows = 0;                // relax_half_matmul: rows from which the tiled GEMM replaces the matvec passes; 0: by estimate
 const uint32_t *g_prof_alt_q = nullptr;      // relax_profile_alt_gate_up: another matrix of the gate/up shape
 const uint16_t *g_prof_alt_s = nullptr;
 unsigned long long *g_trace = nullptr;      // relax_profile_trace_buffer
@@ -293,6 +294,11 @@ relax_status relax_set_option(const char *name, int32_t value)
     }
     if (std::strcmp(name, "fuse_finish") == 0) {
         g_opt_fuse_finish = value;
+        return RELAX_OK;
+    }
+    if (std::strcmp(name, "half_matmul_gemm_rows") == 0) {
+        if (value < 0) return RELAX_ERR_SHAPE;
+        g_opt_half_gemm_rows = value;
         return RELAX_OK;
     }
     return RELAX_ERR_UNSUPPORTED;
@@ -793,6 +799,40 @@ relax_status relax_model_step(const relax_model *model, const int32_t *ids, cons
     if (launch_lm_head(xn, model->lm_head, lg, seqs->B, dm.hidden, model->vocab, device_cus(), st_) != hipSuccess) return RELAX_ERR_HIP;
     if (next_ids && launch_argmax(lg, next_ids, seqs->B, model->vocab, st_) != hipSuccess) return RELAX_ERR_HIP;
     return RELAX_OK;
+}
+
+relax_status relax_half_matmul(const uint16_t *x, const uint16_t *w, uint16_t *out, int32_t n, int32_t m, int32_t k, relax_stream stream)
+{
+    if (!x || !w || !out) return RELAX_ERR_NULL;
+    if (n < 1 || m < 1 || k < 8 || k % 8 != 0) return RELAX_ERR_SHAPE;
+    if (((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(w)) & 15) != 0) return RELAX_ERR_SHAPE;
+    if (2 * (size_t)k > 144 * 1024) return RELAX_ERR_UNSUPPORTED;       // one x row has to fit the matvec kernel's LDS
+    hipStream_t st_ = static_cast<hipStream_t>(stream);
+    // The same runtime dispatch on the symbolic n as the int4 path (Sec. 5.1): matvec passes for a few rows, tiled MFMA GEMM from
+    // there on.  Where "there" is depends on the matrix: a pass streams the whole matrix (5.5 TB/s; passes of 8 rows are
+    // bound by their dot products and take 1.8 times as long), a GEMM launch with few rows costs its k loop whatever n is
+    // (0.5 us per 64 columns, more when its tiles fill the device); wider passes also cost more when only one block's x rows fit
+    // a CU.  Measured on 4096 x 4096: matvec up to 16 rows (33 against 36 us), GEMM from 24 (36 against 47); on 22016 x 4096:
+    // matvec up to 4 rows (35 against 46 us), GEMM from 6 (44 against 62); on 4096 x 11008: GEMM from 16 (94 against 120).
+    bool use_gemm;
+    if (g_opt_half_gemm_rows > 0) {
+        use_gemm = n >= g_opt_half_gemm_rows;
+    } else {
+        const double pass_us = (double)m * k * 2.0 / 5.5e6;
+        const int per = lm_head_rows_per_pass(k);                 // rows of x the matvec kernel holds in LDS
+        double mv_us = 0.0;
+        for (int left = n; left > 0;) {
+            const int nb = left >= 8 && per >= 8 ? 8 : left >= 4 && per >= 4 ? 4 : left >= 2 && per >= 2 ? 2 : 1;
+            const bool one_block_per_cu = (size_t)2 * nb * k * 2 > 150 * 1024;      // the x rows of two blocks no longer fit a CU
+            mv_us += pass_us * (nb == 8 ? 2.0 : nb == 4 ? 1.15 : 1.0) * (one_block_per_cu ? 1.35 : 1.0) + 3.0;
+            left -= nb;
+        }
+        const double tiles = (double)((m + 127) / 128) * ((n + 63) / 64);
+        const double gemm_us = (k / 64.0) * (0.5 + 0.15 * std::min(tiles / 256.0, 1.0)) * std::max(1.0, tiles / 256.0) + 4.0;
+        use_gemm = n > 64 || gemm_us < mv_us;
+    }
+    if (use_gemm && gemm_f16_eligible(x, w, out, m, k)) return hip_status(launch_gemm_f16(x, w, n, m, k, out, st_));
+    return hip_status(launch_lm_head(x, w, out, n, k, m, device_cus(), st_));
 }
 
 relax_status relax_unpack_int4(const relax_qmat *w, int8_t *out, relax_stream stream)

@@ -80,6 +80,7 @@ struct GemmArgs {
     const uint16_t *x;       // [n,k] fp16
     const uint32_t *q;       // [m,k/8]
     const uint16_t *s;       // [m,k/32]
+    const uint16_t *wh;      // FP16W kernels: plain fp16 weights [m,k] instead of q, s
     int32_t n, m, k;
     int32_t epi;
     int32_t tiles_m;         // weight-row tiles of the launch (the grid is one-dimensional: tiles_m * x-row tiles * k splits)
@@ -95,7 +96,9 @@ struct GemmArgs {
 // and NF fragments of 32 x-rows (w >> 1 picks which) of the workgroup tile of 64 MF weight rows x 64 NF x-rows.
 // LDS row r of the weight tile is weight row m0 + r, except for EPI_SWIGLU: rows [0, 32 MF) are gate rows
 // g0 + r and rows [32 MF, 64 MF) the up rows F + g0 + (r - 32 MF).
-template <int EPI, int MF, int NF>
+// FP16W: the weights are plain fp16 (the fp16-weight configurations of the paper's LLM charts, Sec. 5.1): the staging copies
+// 16-byte packets instead of decoding words, everything else is the same kernel.
+template <int EPI, int MF, int NF, bool FP16W = false>
 __global__ __launch_bounds__(kThreadsG) void gemm_q4_mfma_kernel(GemmArgs a)
 {
     constexpr int BM = 64 * MF, BN = 64 * NF;
@@ -128,8 +131,9 @@ __global__ __launch_bounds__(kThreadsG) void gemm_q4_mfma_kernel(GemmArgs a)
     } else {
         grow = min(tile_m * BM + arow, a.m - 1);
     }
-    const uint32_t *qsrc = a.q + (size_t)grow * kw + aword0;
-    const uint16_t *ssrc = a.s + (size_t)grow * G + (aword0 >> 2);
+    const uint32_t *qsrc = FP16W ? nullptr : a.q + (size_t)grow * kw + aword0;
+    const uint16_t *ssrc = FP16W ? nullptr : a.s + (size_t)grow * G + (aword0 >> 2);
+    const uint16_t *hsrc = FP16W ? a.wh + (size_t)grow * a.k + aword0 * 8 : nullptr;
     const uint16_t *xsrc[XP];
 #pragma unroll
     for (int p = 0; p < XP; ++p) {
@@ -139,7 +143,7 @@ __global__ __launch_bounds__(kThreadsG) void gemm_q4_mfma_kernel(GemmArgs a)
 
     // Staged registers of one k block: packed codes + scales of this thread's weight row part, and its x packets.
     struct Stage {
-        uint4 wq[W / 4];
+        uint4 wq[FP16W ? W : W / 4];                      // packed words, or one 16-byte packet of fp16 weights per word
         uint32_t wsc;
         uint4 xr[XP];
     };
@@ -147,10 +151,15 @@ __global__ __launch_bounds__(kThreadsG) void gemm_q4_mfma_kernel(GemmArgs a)
     const int nkb = min(a.kb_per_split, a.k / BK - kb0);
     auto stage_load = [&](Stage &S, int kb) {             // kb is clamped: the tail re-reads the last block (never consumed)
         kb = kb0 + min(kb, nkb - 1);
+        if (FP16W) {
 #pragma unroll
-        for (int i = 0; i < W / 4; ++i) S.wq[i] = *(const uint4 *)(qsrc + kb * (BK / 8) + i * 4);
-        if (W == 8) S.wsc = *(const uint32_t *)(ssrc + kb * (BK / 32));
-        else S.wsc = ssrc[kb * (BK / 32)];
+            for (int i = 0; i < W; ++i) S.wq[i] = *(const uint4 *)(hsrc + kb * BK + i * 8);
+        } else {
+#pragma unroll
+            for (int i = 0; i < W / 4; ++i) S.wq[i] = *(const uint4 *)(qsrc + kb * (BK / 8) + i * 4);
+            if (W == 8) S.wsc = *(const uint32_t *)(ssrc + kb * (BK / 32));
+            else S.wsc = ssrc[kb * (BK / 32)];
+        }
 #pragma unroll
         for (int p = 0; p < XP; ++p) S.xr[p] = *(const uint4 *)(xsrc[p] + kb * BK);
     };
@@ -160,6 +169,16 @@ __global__ __launch_bounds__(kThreadsG) void gemm_q4_mfma_kernel(GemmArgs a)
 #pragma unroll
         for (int i = 0; i < W; ++i) {
             if (i * 4 / W != part) continue;
+            if (FP16W) {                                  // same packet order as the decode and the x tile
+                const uint4 &h = S.wq[FP16W ? i : 0];
+                uint4 o;
+                o.x = __builtin_amdgcn_perm(h.z, h.x, 0x05040100u);
+                o.y = __builtin_amdgcn_perm(h.z, h.x, 0x07060302u);
+                o.z = __builtin_amdgcn_perm(h.w, h.y, 0x05040100u);
+                o.w = __builtin_amdgcn_perm(h.w, h.y, 0x07060302u);
+                *(uint4 *)(ad + i * 8) = o;
+                continue;
+            }
             const uint4 &wv = S.wq[i >> 2];
             const uint32_t word = (i & 3) == 0 ? wv.x : (i & 3) == 1 ? wv.y : (i & 3) == 2 ? wv.z : wv.w;
             const uint32_t sc = (W == 8 && i >= 4) ? (S.wsc >> 16) : (S.wsc & 0xFFFFu);
@@ -331,7 +350,7 @@ __global__ __launch_bounds__(kThreadsG) void gemm_q4_mfma_kernel(GemmArgs a)
     }
 }
 
-template <int MF, int NF>
+template <int MF, int NF, bool FP16W = false>
 hipError_t launch_tile(const GemmArgs &a_in, hipStream_t stream, int splits)
 {
     constexpr int BM = 64 * MF, BN = 64 * NF;
@@ -344,6 +363,16 @@ hipError_t launch_tile(const GemmArgs &a_in, hipStream_t stream, int splits)
     dim3 grid(tiles * splits);
     const size_t lds = 2 * (size_t)(BM + BN) * kPitch * sizeof(uint16_t);    // up to 147456 bytes: one workgroup per CU
     static bool attr_done = false;
+    if constexpr (FP16W) {
+        if (a.epi != EPI_F16 || splits != 1) return hipErrorInvalidValue;
+        if (!attr_done) {
+            if (hipFuncSetAttribute((const void *)gemm_q4_mfma_kernel<EPI_F16, MF, NF, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+                return hipErrorInvalidValue;
+            attr_done = true;
+        }
+        hipLaunchKernelGGL((gemm_q4_mfma_kernel<EPI_F16, MF, NF, true>), grid, dim3(kThreadsG), lds, stream, a);
+        return hipGetLastError();
+    }
     if (!attr_done) {
         const void *ks[4] = {(const void *)gemm_q4_mfma_kernel<EPI_F16, MF, NF>, (const void *)gemm_q4_mfma_kernel<EPI_RESID_F32, MF, NF>,
                              (const void *)gemm_q4_mfma_kernel<EPI_RESID_F16, MF, NF>, (const void *)gemm_q4_mfma_kernel<EPI_SWIGLU, MF, NF>};
@@ -440,10 +469,30 @@ int gemm_mfma_splits(const relax_qmat &w, int n, int epi, const float *partial, 
     return p.splits;
 }
 
+// out[n,m] = x[n,k] . w[m,k]^T with plain fp16 weights: the same tiles, no decode, one pass over k
+bool gemm_f16_eligible(const void *x, const void *w, const void *out, int m, int k)
+{
+    return k % (2 * BK) == 0 && m % 4 == 0 && ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(w)) & 15) == 0 &&
+           (reinterpret_cast<uintptr_t>(out) & 7) == 0;
+}
+
+hipError_t launch_gemm_f16(const uint16_t *x, const uint16_t *w, int n, int m, int k, uint16_t *out, hipStream_t stream)
+{
+    GemmArgs a = {};
+    a.x = x, a.wh = w, a.n = n, a.m = m, a.k = k, a.epi = EPI_F16, a.out_f16 = out;
+    const TilePlan p = tile_plan(m, k, n, EPI_F16);
+    a.kb_per_split = k / BK;
+    if (p.mf == 4) return launch_tile<4, 4, true>(a, stream, 1);
+    if (p.nf == 4) return launch_tile<2, 4, true>(a, stream, 1);
+    if (p.nf == 2) return launch_tile<2, 2, true>(a, stream, 1);
+    return launch_tile<2, 1, true>(a, stream, 1);
+}
+
 hipError_t launch_gemm_mfma(const uint16_t *x, const relax_qmat &w, int n, int epi, uint16_t *out_f16, float *out_f32, const void *resid,
                             hipStream_t stream, float *partial, size_t partial_floats, const SkinnyFuse *fuse)
 {
     GemmArgs a;
+    a.wh = nullptr;
     a.x = x, a.q = w.q, a.s = w.s, a.n = n, a.m = w.m, a.k = w.k, a.epi = epi;
     a.out_f16 = out_f16, a.out_f32 = out_f32, a.resid = resid;
     TilePlan p = tile_plan(w.m, w.k, n, epi);

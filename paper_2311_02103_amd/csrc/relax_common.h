@@ -159,6 +159,9 @@ constexpr int kSplitKMax = 8;         // k splits of the tiled GEMM at most, whe
 constexpr int kSplitKMaxN = 512;      // ... and only up to this many rows (the partial tiles are splits * n * m floats)
 size_t gemm_splitk_partial_floats(int m, int k, int n, int epi);
 // partial: optional workspace of partial_floats fp32 for the k-split form (without it the launch makes one pass over k)
+// the same tiled kernel on plain fp16 weights [m,k] (no decode)
+bool gemm_f16_eligible(const void *x, const void *w, const void *out, int m, int k);
+hipError_t launch_gemm_f16(const uint16_t *x, const uint16_t *w, int n, int m, int k, uint16_t *out, hipStream_t stream);
 struct SkinnyFuse;
 int gemm_mfma_splits(const relax_qmat &w, int n, int epi, const float *partial, size_t partial_floats);
 // fuse: only for a launch that splits (gemm_mfma_splits > 1): the light step folded into its finishing pass
@@ -223,6 +226,7 @@ hipError_t launch_attention_prefill(const uint16_t *q, int32_t q_stride, const r
 // Model wrapper steps (model_head.hip)
 hipError_t launch_embed(const int32_t *ids, const uint16_t *E, uint16_t *x, int n, int H, int V, uint32_t *err, hipStream_t stream);
 hipError_t launch_final_norm(const uint16_t *x, const uint16_t *w, uint16_t *y, const SeqTable &st, int H, float eps, hipStream_t stream);
+int lm_head_rows_per_pass(int H);    // rows of x one pass of the fp16 matvec kernel holds in LDS (at most 8)
 hipError_t launch_lm_head(const uint16_t *xn, const uint16_t *W, uint16_t *logits, int B, int H, int V, int n_cus, hipStream_t stream);
 hipError_t launch_argmax(const uint16_t *logits, int32_t *ids, int B, int V, hipStream_t stream);
 

@@ -156,6 +156,18 @@ def test_model_step_and_matmul_workspace_checks():
     assert rx.relax_probe_mfma(None, 10, False)[0] == rx.ERR_NULL
 
 
+def test_half_matmul_checks():
+    assert rx.relax_half_matmul(None, P, P, 1, 8, 64) == rx.ERR_NULL
+    assert rx.relax_half_matmul(P, None, P, 1, 8, 64) == rx.ERR_NULL
+    assert rx.relax_half_matmul(P, P, None, 1, 8, 64) == rx.ERR_NULL
+    assert rx.relax_half_matmul(P, P, P, 0, 8, 64) == rx.ERR_SHAPE
+    assert rx.relax_half_matmul(P, P, P, 1, 0, 64) == rx.ERR_SHAPE
+    assert rx.relax_half_matmul(P, P, P, 1, 8, 60) == rx.ERR_SHAPE          # k % 8
+    assert rx.relax_half_matmul(P + 2, P, P, 1, 8, 64) == rx.ERR_SHAPE      # x not 16-byte aligned
+    assert rx.relax_half_matmul(P, P, P, 1, 8, 80000) == rx.ERR_UNSUPPORTED  # a row of x beyond the matvec kernel's LDS
+    assert rx.relax_set_option("half_matmul_gemm_rows", -1) == rx.ERR_SHAPE
+
+
 def test_no_product_module_touches_the_oracle():
     pkg = os.path.join(ROOT, "paper_2311_02103_amd")
     for dirpath, _, files in os.walk(pkg):

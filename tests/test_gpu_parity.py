@@ -508,3 +508,45 @@ def test_llama7b_layer_prefill_full_sizes(rx, n):
     assert_close(*outs[0], "7B prefill n=%d" % n)
     assert_close(Kg[0, :n], Ko[0, :n], "appended K", atol=5e-3, rtol=5e-3)
     assert_close(Vg[0, :n], Vo[0, :n], "appended V", atol=5e-3, rtol=5e-3)
+
+
+# ------------------------------------------------------------------------- fp16-weight matmul (matvec passes / tiled GEMM without decode)
+def gpu_half_matmul(rx, x_bits, w_bits):
+    n, k = x_bits.shape
+    m = w_bits.shape[0]
+    out = torch.empty((n, m), dtype=torch.float16, device="cuda")
+    rx.check(rx.relax_half_matmul(dev(x_bits), dev(w_bits), out, n, m, k), "relax_half_matmul")
+    torch.cuda.synchronize()
+    return host_bits(out).view(np.float16).astype(np.float32)
+
+
+@pytest.mark.parametrize("m,k,n", [(512, 1024, 1), (1000, 4096, 3), (516, 4096, 8), (516, 4096, 9), (1000, 4096, 11), (1000, 4096, 12),
+                                   (4096, 4096, 17), (300, 1024, 64), (260, 2048, 65), (1028, 11008, 130), (4096, 4096, 300),
+                                   (700, 1024, 513), (250, 1000, 40), (1000, 4096 + 64, 40)])      # the last two: shapes the GEMM cannot take
+def test_half_matmul_against_oracle(rx, m, k, n):
+    """Plain fp16 weights through the same dispatch on n: passes of up to 8 rows through the matvec kernel below the
+    crossover, the tiled MFMA GEMM without its decode step from there on (every tile shape, ragged edges), and the
+    matvec passes again for matrices the GEMM cannot take (m % 4 != 0, k % 128 != 0)."""
+    w = wl.normal_f16_bits(9, m * 3 + k, (m, k))
+    w = (wl.f16_bits_to_f32(w) * 0.02).astype(np.float16).view(np.uint16)          # weight scale of the int4 workloads
+    x = wl.normal_f16_bits(9, n + k, (n, k))
+    ref = oracle.half_matmul(wl.f16_bits_to_f32(x), w)
+    got = gpu_half_matmul(rx, x, w)
+    assert_close(got, ref, "half_matmul m=%d k=%d n=%d" % (m, k, n))
+    assert np.abs(got - ref).max() <= 2e-3 * max(1.0, np.abs(ref).max())
+
+
+def test_half_matmul_both_kernels_on_the_same_rows(rx):
+    """The crossover is a tuning value: forcing the GEMM down to one row, or the matvec passes up to 40 rows, changes the
+    kernel, not the result beyond the fp16 bar."""
+    m, k, n = 2048, 4096, 40
+    w = (wl.f16_bits_to_f32(wl.normal_f16_bits(10, 1, (m, k))) * 0.02).astype(np.float16).view(np.uint16)
+    x = wl.normal_f16_bits(10, 2, (n, k))
+    ref = oracle.half_matmul(wl.f16_bits_to_f32(x), w)
+    try:
+        for rows in (1, 10 ** 6):
+            rx.check(rx.relax_set_option("half_matmul_gemm_rows", rows))
+            for nn in (1, 5, 40):
+                assert_close(gpu_half_matmul(rx, x[:nn], w), ref[:nn], "half_matmul, GEMM from %d rows, n=%d" % (rows, nn))
+    finally:
+        rx.check(rx.relax_set_option("half_matmul_gemm_rows", 0))         # back to the default: by estimate
