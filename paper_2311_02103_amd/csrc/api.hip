@@ -273,6 +273,36 @@ int device_cus()
     return cus[dev];
 }
 
+// out[n,m] = x[n,k] . w[m,k]^T on plain fp16 weights (relax_half_matmul, and the LM head of relax_model_step).
+// The same runtime dispatch on the symbolic n as the int4 path (Sec. 5.1): matvec passes for a few rows, tiled MFMA GEMM from
+// there on.  Where "there" is depends on the matrix: a pass streams the whole matrix (5.5 TB/s; passes of 8 rows are
+// bound by their dot products and take twice as long), a GEMM launch with few rows costs its k loop whatever n is
+// (0.5 us per 64 columns, more when its tiles fill the device); wider passes also cost more when only one block's x rows fit
+// a CU.  Measured on 4096 x 4096: matvec up to 16 rows (33 against 36 us), GEMM from 24 (36 against 47); on 22016 x 4096:
+// matvec up to 4 rows (35 against 46 us), GEMM from 6 (44 against 62); on 4096 x 11008: GEMM from 16 (94 against 120).
+hipError_t half_matmul_enqueue(const uint16_t *x, const uint16_t *w, uint16_t *out, int n, int m, int k, hipStream_t st_)
+{
+    bool use_gemm;
+    if (g_opt_half_gemm_rows > 0) {
+        use_gemm = n >= g_opt_half_gemm_rows;
+    } else {
+        const double pass_us = (double)m * k * 2.0 / 5.5e6;
+        const int per = lm_head_rows_per_pass(k);                 // rows of x the matvec kernel holds in LDS
+        double mv_us = 0.0;
+        for (int left = n; left > 0;) {
+            const int nb = left >= 8 && per >= 8 ? 8 : left >= 4 && per >= 4 ? 4 : left >= 2 && per >= 2 ? 2 : 1;
+            const bool one_block_per_cu = (size_t)2 * nb * k * 2 > 150 * 1024;      // the x rows of two blocks no longer fit a CU
+            mv_us += pass_us * (nb == 8 ? 2.0 : nb == 4 ? 1.15 : 1.0) * (one_block_per_cu ? 1.35 : 1.0) + 3.0;
+            left -= nb;
+        }
+        const double tiles = (double)((m + 127) / 128) * ((n + 63) / 64);
+        const double gemm_us = (k / 64.0) * (0.5 + 0.15 * std::min(tiles / 256.0, 1.0)) * std::max(1.0, tiles / 256.0) + 4.0;
+        use_gemm = n > 64 || gemm_us < mv_us;
+    }
+    if (use_gemm && gemm_f16_eligible(x, w, out, m, k)) return launch_gemm_f16(x, w, n, m, k, out, st_);
+    return launch_lm_head(x, w, out, n, k, m, device_cus(), st_);
+}
+
 }  // namespace
 
 extern "C" {
@@ -796,7 +826,7 @@ relax_status relax_model_step(const relax_model *model, const int32_t *ids, cons
     uint16_t *xn = reinterpret_cast<uint16_t *>(base + mp.xn);
     uint16_t *lg = logits ? logits : reinterpret_cast<uint16_t *>(base + mp.logits);
     if (launch_final_norm(cur, model->norm_final, xn, st, dm.hidden, dm.rms_eps, st_) != hipSuccess) return RELAX_ERR_HIP;
-    if (launch_lm_head(xn, model->lm_head, lg, seqs->B, dm.hidden, model->vocab, device_cus(), st_) != hipSuccess) return RELAX_ERR_HIP;
+    if (half_matmul_enqueue(xn, model->lm_head, lg, seqs->B, model->vocab, dm.hidden, st_) != hipSuccess) return RELAX_ERR_HIP;
     if (next_ids && launch_argmax(lg, next_ids, seqs->B, model->vocab, st_) != hipSuccess) return RELAX_ERR_HIP;
     return RELAX_OK;
 }
@@ -807,32 +837,7 @@ relax_status relax_half_matmul(const uint16_t *x, const uint16_t *w, uint16_t *o
     if (n < 1 || m < 1 || k < 8 || k % 8 != 0) return RELAX_ERR_SHAPE;
     if (((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(w)) & 15) != 0) return RELAX_ERR_SHAPE;
     if (2 * (size_t)k > 144 * 1024) return RELAX_ERR_UNSUPPORTED;       // one x row has to fit the matvec kernel's LDS
-    hipStream_t st_ = static_cast<hipStream_t>(stream);
-    // The same runtime dispatch on the symbolic n as the int4 path (Sec. 5.1): matvec passes for a few rows, tiled MFMA GEMM from
-    // there on.  Where "there" is depends on the matrix: a pass streams the whole matrix (5.5 TB/s; passes of 8 rows are
-    // bound by their dot products and take 1.8 times as long), a GEMM launch with few rows costs its k loop whatever n is
-    // (0.5 us per 64 columns, more when its tiles fill the device); wider passes also cost more when only one block's x rows fit
-    // a CU.  Measured on 4096 x 4096: matvec up to 16 rows (33 against 36 us), GEMM from 24 (36 against 47); on 22016 x 4096:
-    // matvec up to 4 rows (35 against 46 us), GEMM from 6 (44 against 62); on 4096 x 11008: GEMM from 16 (94 against 120).
-    bool use_gemm;
-    if (g_opt_half_gemm_rows > 0) {
-        use_gemm = n >= g_opt_half_gemm_rows;
-    } else {
-        const double pass_us = (double)m * k * 2.0 / 5.5e6;
-        const int per = lm_head_rows_per_pass(k);                 // rows of x the matvec kernel holds in LDS
-        double mv_us = 0.0;
-        for (int left = n; left > 0;) {
-            const int nb = left >= 8 && per >= 8 ? 8 : left >= 4 && per >= 4 ? 4 : left >= 2 && per >= 2 ? 2 : 1;
-            const bool one_block_per_cu = (size_t)2 * nb * k * 2 > 150 * 1024;      // the x rows of two blocks no longer fit a CU
-            mv_us += pass_us * (nb == 8 ? 2.0 : nb == 4 ? 1.15 : 1.0) * (one_block_per_cu ? 1.35 : 1.0) + 3.0;
-            left -= nb;
-        }
-        const double tiles = (double)((m + 127) / 128) * ((n + 63) / 64);
-        const double gemm_us = (k / 64.0) * (0.5 + 0.15 * std::min(tiles / 256.0, 1.0)) * std::max(1.0, tiles / 256.0) + 4.0;
-        use_gemm = n > 64 || gemm_us < mv_us;
-    }
-    if (use_gemm && gemm_f16_eligible(x, w, out, m, k)) return hip_status(launch_gemm_f16(x, w, n, m, k, out, st_));
-    return hip_status(launch_lm_head(x, w, out, n, k, m, device_cus(), st_));
+    return hip_status(half_matmul_enqueue(x, w, out, n, m, k, static_cast<hipStream_t>(stream)));
 }
 
 relax_status relax_unpack_int4(const relax_qmat *w, int8_t *out, relax_stream stream)
