@@ -110,3 +110,59 @@ def test_70b_shape_ragged_calls_against_the_oracle(rx):
         assert err_rms <= 2.5e-3 * ref_rms, "%s: error RMS %.3e against output RMS %.3f" % (what, err_rms, ref_rms)
         assert_close(layer.k.float().cpu().numpy(), Ko, what + ": K cache", atol=5e-3, rtol=5e-3)
         assert_close(layer.v.float().cpu().numpy(), Vo, what + ": V cache", atol=5e-3, rtol=5e-3)
+
+
+def test_random_matmul_shapes_against_the_oracle(rx):
+    """Seeded random (m, k, n) through relax_dequant_matmul (without and with the split-K workspace) and
+    relax_half_matmul: any k that is a multiple of 8, any m, row counts on both sides of every dispatch boundary."""
+    from test_gpu_parity import gpu_matmul, gpu_half_matmul
+    rng = np.random.default_rng(77)
+    for it in range(60):
+        kind = it % 3
+        n = int(rng.choice([1, 2, 3, 7, 16, 33, 64, 65, 100, 128, 129, 200, 300, 512, 513, 700]))
+        if rng.random() < 0.4:
+            n = int(rng.integers(1, 700))
+        k = 8 * int(rng.integers(1, 1500)) if rng.random() < 0.5 else int(rng.choice([64, 128, 256, 1024, 2048, 4096, 8192, 11008]))
+        m = int(rng.integers(1, 6000)) if rng.random() < 0.6 else int(rng.choice([64, 128, 256, 4096, 12288, 22016]))
+        while m * k * n > 2e9:                              # keeps the oracle's share of the test to seconds
+            if n > 16:
+                n //= 2
+            else:
+                m //= 2
+        what = "case %d (%s) m=%d k=%d n=%d" % (it, ["int4", "int4 + workspace", "fp16"][kind], m, k, n)
+        x = wl.normal_f16_bits(400 + it, 1, (n, k))
+        if kind < 2:
+            q, s = wl.qmat(400 + it, 2, m, k)
+            ref = oracle.dequant_matmul(wl.f16_bits_to_f32(x), q, s, m, k)
+            got = gpu_matmul(rx, x, q, s, m, k, with_ws=bool(kind)).view(np.float16).astype(np.float32)
+        else:
+            w = (wl.f16_bits_to_f32(wl.normal_f16_bits(400 + it, 3, (m, k))) * 0.02).astype(np.float16).view(np.uint16)
+            ref = oracle.half_matmul(wl.f16_bits_to_f32(x), w)
+            got = gpu_half_matmul(rx, x, w)
+        assert_close(got, ref, what)
+        assert np.abs(got - ref).max() <= 2e-3 * max(1.0, np.abs(ref).max()), what
+
+
+def test_random_attention_calls_against_the_oracle(rx):
+    """Seeded random head layouts (1 to 8 KV heads, 1 to 8 query heads each, head dim 64 or 128), capacities, batch sizes
+    and length mixes through relax_attention: decode batches, ragged prefills with and without a cached prefix, mixtures.
+    The cache above every sequence's length holds NaNs, so a read past a row's position shows."""
+    from test_gpu_parity import run_attention
+    rng = np.random.default_rng(78)
+    for it in range(45):
+        d, g, group = int(rng.choice([64, 128])), int(rng.integers(1, 9)), int(rng.choice([1, 2, 4, 8]))
+        cap, B = int(rng.choice([64, 130, 600, 1500])), int(rng.integers(1, 21))
+        if it % 3 == 0:
+            q = [1] * B
+        elif it % 3 == 1:
+            q = [int(rng.integers(1, min(cap, 200) + 1)) for _ in range(B)]
+        else:
+            q = [int(rng.choice([1, 1, int(rng.integers(2, min(cap, 50) + 1))])) for _ in range(B)]
+        while sum(q) > 800:
+            q[int(np.argmax(q))] //= 2
+        q = [max(1, v) for v in q]
+        kv = list(q) if it % 5 == 0 else [int(rng.integers(v, cap + 1)) for v in q]
+        slots = [int(v) for v in rng.permutation(B + 3)[:B]]
+        what = "case %d h=%d g=%d d=%d cap=%d q=%s kv=%s slots=%s" % (it, g * group, g, d, cap, q, kv, slots)
+        got, ref = run_attention(rx, g * group, g, d, cap, B + 3, q, kv, slots, seed=600 + it)
+        assert_close(got, ref, what, atol=2e-3, rtol=1e-2)
