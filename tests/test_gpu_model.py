@@ -169,3 +169,48 @@ def test_few_row_path_with_and_without_folded_finishing_steps(rx, q):
         assert torch.equal(a[4][l].view(torch.int16), b[4][l].view(torch.int16)), "K cache layer %d" % l
         assert torch.equal(a[5][l].view(torch.int16), b[5][l].view(torch.int16)), "V cache layer %d" % l
     assert float(a[0].float().abs().max()) > 0 and torch.isfinite(a[2].float()).all()
+
+
+SCHEDULE_SHAPES = [(wl.TINY, 1003, 3, 12, 96),
+                   (wl.LayerShape("mid-gqa", hidden=1024, n_heads=16, n_kv_heads=4, head_dim=64, ffn=2816), 5000, 2, 8, 300),
+                   (wl.LayerShape("mid-mha", hidden=2048, n_heads=16, n_kv_heads=16, head_dim=128, ffn=5632), 32000, 2, 20, 160)]
+
+
+@pytest.mark.parametrize("si", range(len(SCHEDULE_SHAPES)))
+def test_serving_like_schedule_against_the_oracle(rx, si):
+    """A seeded continuous-batching schedule through relax_model_step: every step retires some sequences, admits new
+    prompts into free cache slots and decodes the rest, in shuffled order, so calls mix prefill and decode rows, the
+    slots in use and the batch size change from call to call, and each sequence's cache is what earlier calls left."""
+    shape, V, nl, slots, cap = SCHEDULE_SHAPES[si]
+    n_max = 400
+    rng = np.random.default_rng(900 + si)
+    dev, od, ol, mt = build_models(shape, nl, V, seed=90 + si, cap=cap, slots=slots, n_max=n_max, B_max=slots)
+    Ko, Vo = zero_caches(od, nl, slots)
+    length, last = {}, {}                                  # per live slot: cached length, the oracle's last pick
+    for step in range(12):
+        for s in list(length):
+            if length[s] + 1 >= cap or rng.random() < 0.15:
+                del length[s], last[s]
+        free = [s for s in range(slots) if s not in length]
+        rng.shuffle(free)
+        admit = free[:int(rng.integers(0, min(len(free), 4) + 1))]
+        if not length and not admit:
+            admit = free[:1]
+        order = list(length) + admit
+        rng.shuffle(order)
+        sl, q, kv, ids = [], [], [], []
+        for s in order:
+            sl.append(s)
+            if s in length:
+                q.append(1), kv.append(length[s] + 1), ids.append([last[s]])
+            else:
+                p = int(rng.integers(1, min(cap - 2, 70)))
+                q.append(p), kv.append(p), ids.append(list(wl.token_ids(1000 * si + step, p, V)))
+        while sum(q) > n_max:
+            j = int(np.argmax(q))
+            q[j] //= 2
+            kv[j], ids[j] = q[j], ids[j][:q[j]]
+        flat = np.asarray([t for row in ids for t in row], np.int32)
+        nxt = check_step(dev, od, ol, mt, flat, q, kv, sl, Ko, Vo, "%s step %d q=%s kv=%s slots=%s" % (shape.name, step, q, kv, sl))
+        for b, s in enumerate(sl):
+            length[s], last[s] = kv[b], int(nxt[b])
