@@ -189,3 +189,30 @@ def model_tensors(shape: LayerShape, seed: int, vocab: int) -> Dict[str, np.ndar
 def token_ids(seed: int, count: int, vocab: int, stream: int = 0) -> np.ndarray:
     """count token ids uniform in [0, vocab)."""
     return rng(seed, TID_IDS + 16 * stream).integers(0, vocab, size=count, dtype=np.int32)
+
+
+# ---- 3-bit weights (same group of 32 columns, 96 bits = three words per group) --------------------------------------
+def pack_codes3(codes: np.ndarray) -> np.ndarray:
+    """codes uint8 [m,k] in 0..7, k % 32 == 0 -> uint32 [m, 3k/32]: the codes of a row laid end to end as one
+    little-endian bit string, 3 bits each (code c of a group starts at bit 3c of the group's three words)."""
+    m, k = codes.shape
+    assert k % GROUP == 0 and codes.max(initial=0) <= 7
+    bits = ((codes[:, :, None] >> np.arange(3, dtype=np.uint8)) & 1).astype(np.uint8).reshape(m, 3 * k)
+    return np.packbits(bits, axis=1, bitorder="little").view("<u4").reshape(m, 3 * k // 32)
+
+
+def quantize_q3(w: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+    """Symmetric 3-bit, group 32 along k: scale = fp16(max|w| / 3) per group, codes = clamp(rint(w / scale), -3, 3) + 4.
+    Returns (uint32 [m, 3k/32], fp16 bits [m, k/32])."""
+    m, k = w.shape
+    g = w.reshape(m, k // GROUP, GROUP).astype(np.float32)
+    scale = (np.abs(g).max(axis=2) / 3.0).astype(np.float16)
+    scale = np.where(scale == 0, np.float16(1.0), scale)
+    codes = np.clip(np.rint(g / scale.astype(np.float32)[:, :, None]), -3, 3).astype(np.int8) + 4
+    return pack_codes3(codes.reshape(m, k).astype(np.uint8)), scale.view(np.uint16)
+
+
+def qmat3(seed: int, tensor_id: int, m: int, k: int, std: float = 0.02) -> Tuple[np.ndarray, np.ndarray]:
+    """One random 3-bit matrix from N(0, std^2) weights."""
+    w = rng(seed, tensor_id).standard_normal((m, k), dtype=np.float32) * np.float32(std)
+    return quantize_q3(w)
