@@ -293,6 +293,21 @@ relax_status relax_probe_mfma(float *sink, int32_t iters, int32_t random_data, i
 relax_status relax_unpack_int4(const relax_qmat *w, int8_t *out, relax_stream stream);
 relax_status relax_dequantize(const relax_qmat *w, float *out, relax_stream stream);
 
+/* 3-bit weights (Sec. 5.3: 3-bit quantised models are what fits the smaller devices; the
+ * paper prints no bit layout, this one mirrors the 4-bit format).  A relax_qmat whose q is
+ * uint32 [m][3k/32] and whose s is fp16 [m][k/32], both device memory, row-major: a group
+ * of 32 columns shares one scale, its 32 codes u in 0..7 lie end to end, 3 bits each, in
+ * three little-endian words (code c at bits 3c..3c+2 of the 96-bit string), and the weight
+ * is (u - 4) * scale.  k % 32 == 0.
+ * relax_unpack_q3: out int8 [m,k] in -4..3 (device), bit-exact decode export.
+ * relax_dequant_matmul_q3: out[n,m] fp16 = x[n,k] fp16 (device, 16-byte aligned) times the
+ * decoded matrix, fp32 accumulation; a matrix-vector kernel run once per row of x (meant for
+ * decode-sized n; every row of x streams the matrix again), k <= 12288 (longer rows:
+ * RELAX_ERR_UNSUPPORTED), n <= 65535.  Asynchronous on `stream`; nothing is allocated and
+ * nothing is owned.  NULL pointers: RELAX_ERR_NULL; bad sizes or alignment: RELAX_ERR_SHAPE. */
+relax_status relax_unpack_q3(const relax_qmat *w, int8_t *out, relax_stream stream);
+relax_status relax_dequant_matmul_q3(const uint16_t *x, const relax_qmat *w, uint16_t *out, int32_t n, relax_stream stream);
+
 /* Measurement aid: the next relax_decoder_layer call on this host thread records `start`
  * before and `stop` after the launch of one of its steps (0 QKV matvec/GEMM, 1 attention,
  * 2 output projection, 3 gate/up, 4 down projection, 5 the fused single-launch decode

@@ -98,6 +98,8 @@ _SIGNATURES = {
     "relax_probe_mfma": (C.c_int32, [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_int64), C.c_void_p]),
     "relax_unpack_int4": (C.c_int32, [C.POINTER(QMatC), C.c_void_p, C.c_void_p]),
     "relax_dequantize": (C.c_int32, [C.POINTER(QMatC), C.c_void_p, C.c_void_p]),
+    "relax_unpack_q3": (C.c_int32, [C.POINTER(QMatC), C.c_void_p, C.c_void_p]),
+    "relax_dequant_matmul_q3": (C.c_int32, [C.c_void_p, C.POINTER(QMatC), C.c_void_p, C.c_int32, C.c_void_p]),
 }
 EXPORTS = tuple(_SIGNATURES)
 
@@ -106,6 +108,10 @@ def lib():
     """Loads the HIP library; raises (never falls back) when it has not been built."""
     global _lib
     if _lib is None:
+        try:                       # torch ships its own HIP runtime: it must be in the process first so that this library binds
+            import torch  # noqa: F401  to the same one (a second runtime loaded beside it reports "no device" at the first launch)
+        except ImportError:
+            pass
         if not os.path.exists(LIB_PATH):
             raise ImportError("librelax_mi355.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
                               "(or python paper_2311_02103_amd/build.py) first")
@@ -319,6 +325,16 @@ def relax_unpack_int4(w: Optional[QMat], out: Ptr, stream=None) -> int:
 def relax_dequantize(w: Optional[QMat], out: Ptr, stream=None) -> int:
     wc = None if w is None else w.c()
     return lib().relax_dequantize(_ref(wc), _ptr(out), _stream(stream))
+
+
+def relax_unpack_q3(w: Optional[QMat], out: Ptr, stream=None) -> int:
+    wc = None if w is None else w.c()
+    return lib().relax_unpack_q3(_ref(wc), _ptr(out), _stream(stream))
+
+
+def relax_dequant_matmul_q3(x: Ptr, w: Optional[QMat], out: Ptr, n: int, stream=None) -> int:
+    wc = None if w is None else w.c()
+    return lib().relax_dequant_matmul_q3(_ptr(x), _ref(wc), _ptr(out), n, _stream(stream))
 
 
 def relax_profile_step_events(start: Optional[int], stop: Optional[int], step: int) -> None:

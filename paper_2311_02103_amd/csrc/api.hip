@@ -232,7 +232,14 @@ relax_status upload_table(SeqTable &st, const std::vector<int32_t> &host_table, 
     return RELAX_OK;
 }
 
-inline relax_status hip_status(hipError_t e) { return e == hipSuccess ? RELAX_OK : RELAX_ERR_HIP; }
+// RELAX_LOG_ERRORS in the environment: the HIP error behind a RELAX_ERR_HIP goes to stderr
+inline relax_status hip_status(hipError_t e)
+{
+    if (e == hipSuccess) return RELAX_OK;
+    static const bool log = getenv("RELAX_LOG_ERRORS") != nullptr;
+    if (log) fprintf(stderr, "relax_mi355: HIP error %d (%s)\n", (int)e, hipGetErrorString(e));
+    return RELAX_ERR_HIP;
+}
 
 // One-shot measurement hook (relax_profile_step_events): events around one step of the next layer call.
 thread_local hipEvent_t g_prof_start = nullptr, g_prof_stop = nullptr;
@@ -852,6 +859,23 @@ relax_status relax_dequantize(const relax_qmat *w, float *out, relax_stream stre
     if (!w || !w->q || !w->s || !out) return RELAX_ERR_NULL;
     if (w->m < 1 || w->k < 8 || w->k % 8 != 0) return RELAX_ERR_SHAPE;
     return hip_status(launch_dequantize(*w, out, static_cast<hipStream_t>(stream)));
+}
+
+relax_status relax_unpack_q3(const relax_qmat *w, int8_t *out, relax_stream stream)
+{
+    if (!w || !w->q || !out) return RELAX_ERR_NULL;
+    if (w->m < 1 || w->k < 32 || w->k % 32 != 0) return RELAX_ERR_SHAPE;
+    return hip_status(launch_unpack_q3(*w, out, static_cast<hipStream_t>(stream)));
+}
+
+relax_status relax_dequant_matmul_q3(const uint16_t *x, const relax_qmat *w, uint16_t *out, int32_t n, relax_stream stream)
+{
+    if (!x || !out || !w || !w->q || !w->s) return RELAX_ERR_NULL;
+    if (n < 1 || n > 65535 || w->m < 1 || w->k < 32 || w->k % 32 != 0) return RELAX_ERR_SHAPE;
+    if (!gemv_q3_supported(w->m, w->k)) return RELAX_ERR_UNSUPPORTED;
+    if ((reinterpret_cast<uintptr_t>(x) & 15) != 0 || (reinterpret_cast<uintptr_t>(w->q) & 3) != 0 || (reinterpret_cast<uintptr_t>(w->s) & 1) != 0)
+        return RELAX_ERR_SHAPE;
+    return hip_status(launch_gemv_q3(x, *w, n, out, static_cast<hipStream_t>(stream)));
 }
 
 }  // extern "C"

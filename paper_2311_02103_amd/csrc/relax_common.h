@@ -197,6 +197,10 @@ hipError_t launch_rope_append(uint16_t *qkv, const relax_layer_dims &dm, const r
                               const SeqTable &st, hipStream_t stream);
 hipError_t launch_rope_table(const relax_layer_dims &dm, float *table, hipStream_t stream);
 hipError_t launch_unpack(const relax_qmat &w, int8_t *out, hipStream_t stream);
+// 3-bit weights: matrix-vector kernel (k a multiple of 32, at most 12288) and the dense decode export
+bool gemv_q3_supported(int m, int k);
+hipError_t launch_gemv_q3(const uint16_t *x, const relax_qmat &w, int n, uint16_t *out, hipStream_t stream);
+hipError_t launch_unpack_q3(const relax_qmat &w, int8_t *out, hipStream_t stream);
 hipError_t launch_dequantize(const relax_qmat &w, float *out, hipStream_t stream);
 
 // Split-L attention: chunk length and split count are pure functions of the runtime shape.

@@ -67,3 +67,82 @@ def test_quantiser_stays_in_range_and_close():
     assert codes.min() >= -3 and codes.max() <= 3
     step = np.repeat(s.view(np.float16).astype(np.float64), 32, axis=1)
     assert np.all(np.abs(q3.dequantize_q3(q, s, 5, 64) - w) <= 0.5 * step + 1e-6)
+
+
+# ------------------------------------------------------------------------------------------------ GPU parity
+@pytest.fixture(scope="module")
+def rx():
+    from paper_2311_02103_amd import binding
+    binding.lib()
+    return binding
+
+
+def gpu_q3_matmul(rx, x_bits, q, s, m, k):
+    import torch
+    n = x_bits.shape[0]
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a).view(np.int32 if a.dtype == np.uint32 else np.int16)).cuda()
+    out = torch.empty((n, m), dtype=torch.float16, device="cuda")
+    rx.check(rx.relax_dequant_matmul_q3(dev(x_bits), rx.QMat(dev(q), dev(s), m, k), out, n), "relax_dequant_matmul_q3")
+    torch.cuda.synchronize()
+    return out.cpu().numpy().astype(np.float32)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("m,k", [(1, 32), (5, 96), (33, 704), (64, 4096), (3, 11008)])
+def test_gpu_unpack_bit_exact(rx, m, k):
+    import torch
+    r = np.random.RandomState(m * 7 + k)
+    q = r.randint(0, 2 ** 32, size=(m, 3 * k // 32), dtype=np.uint64).astype(np.uint32)
+    qd = torch.from_numpy(q.view(np.int32)).cuda()
+    out = torch.empty((m, k), dtype=torch.int8, device="cuda")
+    rx.check(rx.relax_unpack_q3(rx.QMat(qd, qd, m, k), out), "relax_unpack_q3")
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy(), q3.unpack_q3(q, m, k))
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("m,k,n", [(40, 256, 2), (65, 704, 3), (130, 4096, 1), (37, 11008, 2)])
+def test_gpu_integer_valued_matmul_bitwise(rx, m, k, n):
+    """Random codes, scales 1 and 2, sparse small-integer x: every partial sum is an integer below 2^24 and the result is at
+    most 2048 in magnitude, so the fp16 output must equal the reference exactly — any slip in word, bit offset, straddling
+    code or scale group shows as a wrong integer."""
+    r = np.random.RandomState(k + m)
+    codes = r.randint(0, 8, size=(m, k)).astype(np.uint8)
+    s = r.choice([1.0, 2.0], size=(m, k // 32)).astype(np.float16).view(np.uint16)
+    x = np.zeros((n, k), dtype=np.float32)
+    hot = r.choice(k, size=40, replace=False)
+    x[:, hot] = r.randint(-3, 4, size=(n, 40))
+    q = wl.pack_codes3(codes)
+    ref = q3.dequant_matmul_q3(x, q, s, m, k)
+    assert np.abs(ref).max() <= 2048
+    got = gpu_q3_matmul(rx, x.astype(np.float16).view(np.uint16), q, s, m, k)
+    assert np.array_equal(got.astype(np.float64), ref)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("m,k,n", [(1, 32, 1), (7, 64, 3), (257, 704, 1), (1000, 2048 + 32, 5), (4099, 4096, 1), (22016, 4096, 1),
+                                   (4096, 11008, 2), (300, 12288, 1), (515, 4096, 17)])
+def test_gpu_matmul_random(rx, m, k, n):
+    """Quantised N(0, 0.02^2) weights, N(0,1) x: ragged m, every groups-per-lane variant of the kernel (k from 32 to
+    12288), several rows of x."""
+    q, s = wl.qmat3(8, m * 131 + k, m, k)
+    x = wl.normal_f16_bits(8, m + k + n, (n, k))
+    ref = q3.dequant_matmul_q3(wl.f16_bits_to_f32(x), q, s, m, k)
+    got = gpu_q3_matmul(rx, x, q, s, m, k)
+    err = np.abs(got - ref)
+    assert np.all(err <= 1e-2 + 2e-2 * np.abs(ref)), "m=%d k=%d n=%d: max err %g" % (m, k, n, err.max())
+    assert err.max() <= 2e-3 * max(1.0, np.abs(ref).max())
+
+
+def test_host_checks_of_the_q3_entry_points():
+    from paper_2311_02103_amd import binding as rx
+    if not os.path.exists(rx.LIB_PATH):
+        pytest.skip("library not built")
+    w = rx.QMatC(64, 64, 8, 64)                    # non-NULL fake pointers: every case below is rejected before any launch
+    assert rx.lib().relax_dequant_matmul_q3(None, w, 64, 1, None) == rx.ERR_NULL
+    assert rx.lib().relax_dequant_matmul_q3(64, w, 64, 0, None) == rx.ERR_SHAPE
+    assert rx.lib().relax_dequant_matmul_q3(64, rx.QMatC(64, 64, 8, 40), 64, 1, None) == rx.ERR_SHAPE          # k % 32
+    assert rx.lib().relax_dequant_matmul_q3(64, rx.QMatC(64, 64, 8, 12288 + 32), 64, 1, None) == rx.ERR_UNSUPPORTED
+    assert rx.lib().relax_dequant_matmul_q3(72, w, 64, 1, None) == rx.ERR_SHAPE                                 # x not 16-byte aligned
+    assert rx.lib().relax_unpack_q3(None, 64, None) == rx.ERR_NULL
+    assert rx.lib().relax_unpack_q3(rx.QMatC(64, 64, 8, 48), 64, None) == rx.ERR_SHAPE
