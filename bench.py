@@ -16,6 +16,7 @@ Other workloads (--workload), same JSON schema, for the other configurations:
   batch_sweep    one 7B-shaped layer call on n decode rows against n (where the dispatch on n changes kernels).
   memory_plan    host-only: planned against unplanned bytes of the layer's intermediates (Alg. 3 of the paper).
   half_sweep     relax_half_matmul (plain fp16 weights) against n, matvec passes and tiled GEMM forced in turn: the crossover.
+  q3_matvec      relax_dequant_matmul_q3 (3-bit weights) at n = 1 on the four matrix shapes of the 7B layer.
 All inputs are seeded and synthetic and resident in HBM before the timed region.
 """
 import argparse
@@ -565,6 +566,67 @@ def bench_half_sweep(args, np, torch, wl, rx):
           "unit": "TFLOP/s", "frac": round(tflops / PEAK_MFMA_TFLOPS, 4), "traffic": None}, None, {"half_sweep": table})
 
 
+# ------------------------------------------------------------------------------------------------ 3-bit matvec
+def bench_q3_matvec(args, np, torch, wl, rx):
+    """relax_dequant_matmul_q3 at n = 1 on the four matrix shapes of the 7B layer (Sec. 5.3 of the paper deploys 3-bit models):
+    HIP-event time per launch on the launch stream over rotating weight copies (each launch streams its matrix from HBM),
+    algorithmic bytes = 3-bit codes + fp16 scales + x + out.  The CPU leg times the numpy reference on a row sample of the
+    gate/up matrix and checks the GPU's outputs for those rows against it."""
+    steps = args.steps = args.steps or 400
+    warmup = args.warmup = 40 if args.warmup is None else args.warmup
+    stream = torch.cuda.Stream()
+    table, keep = {}, None
+    for name, (m, k) in (("gate_up 22016x4096", (22016, 4096)), ("qkv 12288x4096", (12288, 4096)), ("down 4096x11008", (4096, 11008)),
+                         ("o_proj 4096x4096", (4096, 4096))):
+        wbytes = m * k * 3 // 8 + m * (k // 32) * 2
+        copies = max(3, int(600e6 // wbytes))
+        qs = [torch.randint(-2 ** 31, 2 ** 31 - 1, (m, 3 * k // 32), dtype=torch.int32, device="cuda") for _ in range(copies)]
+        ss = [(torch.rand((m, k // 32), device="cuda") * 0.01 + 0.002).to(torch.float16) for _ in range(copies)]
+        mats = [rx.QMat(q, s, m, k) for q, s in zip(qs, ss)]
+        x = torch.randn((1, k), device="cuda", dtype=torch.float16)
+        out = torch.empty((1, m), dtype=torch.float16, device="cuda")
+        for i in range(warmup + 2 * copies):
+            rx.check(rx.relax_dequant_matmul_q3(x, mats[i % copies], out, 1, stream))
+        start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        stream.synchronize()
+        start.record(stream)
+        for i in range(steps):
+            rx.relax_dequant_matmul_q3(x, mats[i % copies], out, 1, stream)
+        stop.record(stream)
+        stream.synchronize()
+        us = start.elapsed_time(stop) * 1e3 / steps
+        alg = wbytes + k * 2 + m * 2
+        table[name] = {"us_per_launch": round(us, 2), "algorithmic_MB": round(alg / 1e6, 2), "GBps": round(alg / us / 1e3, 1),
+                       "frac_of_peak": round(alg / us / 1e3 / PEAK_HBM_GBS, 4), "weight_copies": copies}
+        if keep is None:
+            rx.check(rx.relax_dequant_matmul_q3(x, mats[0], out, 1, stream))
+            stream.synchronize()
+            keep = (m, k, qs[0][:2048].cpu().numpy().view(np.uint32), ss[0][:2048].cpu().numpy().view(np.uint16),
+                    x.cpu().numpy().astype(np.float32), out[0, :2048].float().cpu().numpy())
+        del qs, ss, mats
+    cpu = None
+    if args.cpu_seconds > 0:
+        from oracle import q3                               # the CPU reference: baseline and check only
+        m, k, qh, sh, xh, got = keep
+        reps, t0 = 0, time.perf_counter()
+        while reps < 1 or time.perf_counter() - t0 < min(args.cpu_seconds, 10.0):
+            ref = q3.dequant_matmul_q3(xh, qh, sh, 2048, k)[0]
+            reps += 1
+        sec = (time.perf_counter() - t0) / reps
+        err = np.abs(got - ref)
+        assert np.all(err <= 1e-2 + 2e-2 * np.abs(ref)), "3-bit matvec differs from the reference: max err %g" % err.max()
+        sample_bytes = 2048 * (k * 3 // 8 + (k // 32) * 2)
+        cpu = {"value": round(sample_bytes / sec / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
+               "sample": "rows 0..2047 of the gate/up matrix, %d repetitions of the numpy reference (%.2f s each); the GPU's outputs for those rows checked against it" % (reps, sec)}
+    g = table["gate_up 22016x4096"]
+    emit(args, "3-bit matvec, algorithmic GB/s on the 7B gate/up shape (22016 x 4096, n = 1)", "GB/s", g["GBps"], g["us_per_launch"] / 1e3,
+         "f16 (3-bit weights, f32 accumulate)",
+         {"workload": "3-bit group-32 weights, n = 1, the four matrix shapes of the 7B layer, rotating weight copies", "build_id": rx.relax_build_id()},
+         {"bound": "hbm", "kernel": "gemv_q3_kernel<2> (22016 x 4096)", "achieved": g["GBps"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
+          "frac": g["frac_of_peak"], "traffic": None, "algorithmic_bytes_per_launch": int(g["algorithmic_MB"] * 1e6), "avg_launch_ms": g["us_per_launch"] / 1e3},
+         cpu, {"q3_matvec": table})
+
+
 # ------------------------------------------------------------------------------------------------ memory plan
 def bench_memory_plan(args, wl, rx):
     """The shape of the paper's activation-memory experiment (Sec. 5: prefill of 128..1024 tokens, decode at batch 1..64,
@@ -660,7 +722,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=0, help="timed steps (default: 1280 decode_layer, 50 prefill_layer, 256 model_7b, 8 batched_70b)")
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", choices=["decode_layer", "prefill_layer", "model_7b", "batched_70b", "ceilings", "memory_plan", "batch_sweep", "half_sweep"],
+    ap.add_argument("--workload", choices=["decode_layer", "prefill_layer", "model_7b", "batched_70b", "ceilings", "memory_plan", "batch_sweep", "half_sweep", "q3_matvec"],
                     default="decode_layer")
     ap.add_argument("--n", type=int, default=2048, help="rows of the prefill_layer workload")
     ap.add_argument("--layers", type=int, default=0, help="model workloads: override the layer count (short profiling runs)")
@@ -711,6 +773,8 @@ def main():
         bench_batch_sweep(args, np, torch, wl, rx)
     elif args.workload == "half_sweep":
         bench_half_sweep(args, np, torch, wl, rx)
+    elif args.workload == "q3_matvec":
+        bench_q3_matvec(args, np, torch, wl, rx)
     else:
         bench_model(args, np, torch, wl, rx, big=args.workload == "batched_70b")
 
