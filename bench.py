@@ -69,6 +69,68 @@ def emit(args, metric, unit, value, ms_per_step, dtype, config, roofline, cpu, e
     print(json.dumps(line))
 
 
+# ------------------------------------------------------------------------------------------------ the other two parts of the metric
+def measure_prefill(np, torch, wl, rx, host_w, n=2048, calls=10):
+    """configs[2] at n rows, short: ms per layer call and the MFMA rate of its GEMMs (HIP events around each step)."""
+    from paper_2311_02103_amd.runtime import DeviceLayer, to_device
+    shape = wl.LLAMA7B
+    layer = DeviceLayer(host_w, hidden=shape.hidden, n_heads=shape.n_heads, n_kv_heads=shape.n_kv_heads, head_dim=shape.head_dim,
+                        ffn=shape.ffn, kv_capacity=n, n_max=n)
+    x = to_device(wl.activations(shape, 2, 0, n))
+    out = torch.empty_like(x)
+    stream = torch.cuda.Stream()
+    call = layer.prepare(x, [n], [n], out=out)
+    for _ in range(3):
+        call(stream.cuda_stream)
+    stream.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for _ in range(calls):
+        call(stream.cuda_stream)
+    e1.record(stream)
+    stream.synchronize()
+    ms = e0.elapsed_time(e1) / calls
+    kms = time_steps(torch, rx, stream, lambda i: call(stream.cuda_stream), [0, 1, 2, 3, 4], calls)
+    P = sum(m * k for m, k in shape.matrices().values())
+    m, k = shape.matrices()["wgu"]
+    gemm_ms = kms["qkv"] + kms["o_proj"] + kms["gate_up"] + kms["down"]
+    gu = 2.0 * n * m * k / kms["gate_up"] / 1e9
+    allg = 2.0 * n * P / gemm_ms / 1e9
+    return {"workload": "configs[2]: the same 7B-shaped layer, prefill of n=%d rows, L=n (same binary)" % n, "ms_per_call": round(ms, 4),
+            "tokens_per_s": round(n / ms * 1e3, 1), "gate_up_gemm_TFLOPs": round(gu, 1), "gate_up_frac_of_mfma_peak": round(gu / PEAK_MFMA_TFLOPS, 4),
+            "four_gemm_steps_TFLOPs": round(allg, 1), "frac_of_mfma_peak": round(allg / PEAK_MFMA_TFLOPS, 4),
+            "attention_ms": round(kms["attention"], 4), "note": "the qkv step includes the RMSNorm and rotary/append launches"}
+
+
+def measure_model_7b(np, torch, wl, rx, host_sets, steps=64):
+    """configs[3], short: 32 layers (the weight sets cycled) + fp16 embedding and LM head, 128-token prompt, then greedy decode."""
+    from paper_2311_02103_amd.runtime import DeviceModel
+    shape, nl, V, cap, seed = wl.LLAMA7B, 32, 32000, 512, 3
+    mt = wl.model_tensors(shape, seed, V)
+    dev = DeviceModel([host_sets[l % len(host_sets)] for l in range(nl)], mt["embedding"], mt["norm_final"], mt["lm_head"], hidden=shape.hidden,
+                      n_heads=shape.n_heads, n_kv_heads=shape.n_kv_heads, head_dim=shape.head_dim, ffn=shape.ffn, kv_capacity=cap,
+                      kv_slots=1, n_max=128, B_max=1)
+    logits = torch.empty((1, V), dtype=torch.float16, device="cuda")
+    nxt = torch.empty((1,), dtype=torch.int32, device="cuda")
+    dev.step(torch.from_numpy(wl.token_ids(seed, 128, V)).cuda(), [128], [128], logits=logits, next_ids=nxt)
+    for s in range(8):
+        dev.step(nxt, [1], [129 + s], logits=logits, next_ids=nxt)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(8, 8 + steps):
+        dev.step(nxt, [1], [129 + s], logits=logits, next_ids=nxt)
+    torch.cuda.synchronize()
+    el = time.perf_counter() - t0
+    P = sum(m * k for m, k in shape.matrices().values())
+    step_bytes = nl * P * 0.5625 + V * shape.hidden * 2 + shape.kv_bytes_per_token() * (137 + steps / 2.0) * nl
+    tps = steps / el
+    return {"workload": "configs[3]: 32-layer 7B-shaped model (%d weight sets cycled), vocab 32000, 128-token prompt, then %d greedy decode "
+                        "steps at batch 1, one C call per token" % (len(host_sets), steps),
+            "tokens_per_s": round(tps, 1), "ms_per_token": round(el * 1e3 / steps, 4), "bytes_per_token": int(step_bytes),
+            "achieved_GBps": round(step_bytes * tps / 1e9, 1), "frac_of_hbm_peak": round(step_bytes * tps / 1e9 / PEAK_HBM_GBS, 4),
+            "hbm_ceiling_tokens_per_s": round(PEAK_HBM_GBS * 1e9 / step_bytes, 1)}
+
+
 # ------------------------------------------------------------------------------------------------ configs[1]
 def bench_decode_layer(args, np, torch, wl, rx):
     from paper_2311_02103_amd.runtime import DeviceLayer, f16_bits, to_device
@@ -82,9 +144,10 @@ def bench_decode_layer(args, np, torch, wl, rx):
     t_setup = time.time()
     Ls = [int(v) for v in wl.uniform_lengths(seed, ncalls, 1, cap)]
     kv_k, kv_v = wl.kv_prefill(shape, seed, 1, cap)
-    host_w0, layers = None, []
+    host_w0, layers, host_sets = None, [], []
     for s in range(args.sets):
         w = wl.layer_weights(shape, seed, layer=s)
+        host_sets.append(w)
         if s == 0:
             host_w0 = w
         lay = DeviceLayer(w, hidden=shape.hidden, n_heads=shape.n_heads, n_kv_heads=shape.n_kv_heads, head_dim=shape.head_dim,
@@ -105,24 +168,37 @@ def bench_decode_layer(args, np, torch, wl, rx):
         for i in range(first, first + nsteps):
             calls[i % ncalls](sh)
 
-    graph = None
+    # The timed region is `steps` consecutive calls of the 64-call schedule, repeated `reps` times so that it lasts at least
+    # 0.2 s whatever --steps is (a handful of 45 us steps would time the clock, not the GPU); ms_per_step is the mean over all
+    # of them.  Graph mode (Sec. 4.5 of the paper): the calls are captured once -- the whole schedule in one graph, what is
+    # left of `steps` after whole schedules in a second one -- and replayed; eager mode issues one C call per step.
+    def capture(first, count):
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=stream):
+            run_eager(count, first)
+        return g
+
+    full, rest = divmod(steps, ncalls)
+    graph = graph_rest = None
     if args.mode == "graph":
         with torch.cuda.stream(stream):
             run_eager(ncalls)                       # everything touched once before capture
         stream.synchronize()
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph, stream=stream):
-            run_eager(ncalls)
+        graph = capture(0, ncalls)
+        graph_rest = capture(0, rest) if rest else None
 
     def run(nsteps):
+        f, r = divmod(nsteps, ncalls)
         if graph is None:
             run_eager(nsteps)
-        else:
-            full, rest = divmod(nsteps, ncalls)
-            with torch.cuda.stream(stream):
-                for _ in range(full):
-                    graph.replay()
-            run_eager(rest)
+            return
+        with torch.cuda.stream(stream):
+            for _ in range(f):
+                graph.replay()
+            if r == rest and graph_rest is not None:
+                graph_rest.replay()
+        if r != rest:
+            run_eager(r)
 
     run(warmup)
     stream.synchronize()
@@ -130,8 +206,16 @@ def bench_decode_layer(args, np, torch, wl, rx):
     t0 = time.perf_counter()
     run(steps)
     stream.synchronize()
+    first_pass = time.perf_counter() - t0
+    passes = max(1, min(10000, int(0.25 / max(first_pass, 1e-6)) + 1))
+    stream.synchronize()
     torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    for _ in range(passes):
+        run(steps)
+    stream.synchronize()
+    torch.cuda.synchronize()
+    elapsed = (time.perf_counter() - t0) / passes     # per pass of `steps` steps
     ms_per_step = elapsed * 1e3 / steps
 
     mean_L = float(np.mean([Ls[i % ncalls] for i in range(steps)]))
@@ -187,8 +271,10 @@ def bench_decode_layer(args, np, torch, wl, rx):
         roofline = {"bound": "hbm", "kernel": "gemv_q4_reg_kernel<X_F32_NORM, EPI_SWIGLU, 2> (gate/up matvec, m=22016, k=4096: "
                                                 "RMSNorm prologue, SwiGLU epilogue)",
                     "achieved": round(ach, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(ach / PEAK_HBM_GBS, 4),
-                    "traffic": traffic_from_profile("traffic_gate_up_matvec_7b.json"), "algorithmic_bytes_per_launch": gu_bytes,
-                    "avg_launch_ms": round(kernel_ms["gate_up"], 5)}
+                    "traffic": traffic_from_profile("traffic_gate_up_matvec_7b.json"),
+                    "traffic_source": "stored value, not measured in this run: profiles/traffic_gate_up_matvec_7b.json (rocprofv3 --pmc "
+                                      "FETCH_SIZE and WRITE_SIZE of this kernel, scaled by a copy kernel of known size)",
+                    "algorithmic_bytes_per_launch": gu_bytes, "avg_launch_ms": round(kernel_ms["gate_up"], 5)}
 
     # CPU baseline: the oracle as it stands on the calls of weight set 0, cycled until the time budget is used; the first
     # pass doubles as a parity check of the very calls that were timed.
@@ -224,16 +310,28 @@ def bench_decode_layer(args, np, torch, wl, rx):
                "sample": "%d layer calls (the %d calls of the schedule that use weight set 0, cycled), %.1f s of oracle time; GPU "
                          "outputs of those calls checked against it, max abs err %.2e" % (done, len(sample), t_cpu, worst)}
 
+    # the other two parts of the benchmark's metric, from short runs in this process: prefill MFMA utilisation, model-level rate
+    extra_parts = {}
+    if not args.no_extras:
+        del calls, xs, outs
+        for lay in layers:
+            lay.t.clear()
+        layers.clear()
+        torch.cuda.empty_cache()
+        extra_parts["prefill"] = measure_prefill(np, torch, wl, rx, host_w0)
+        torch.cuda.empty_cache()
+        extra_parts["model_7b"] = measure_model_7b(np, torch, wl, rx, host_sets)
+
     emit(args, "decode tokens/s (7B-shaped int4, batch 1)", "tokens/s", steps / elapsed, ms_per_step,
          "f16 (int4 weights, f32 accumulate)",
          {"workload": "configs[1]: one Llama-2-7B-shaped int4-g32 decoder layer, decode only, batch 1, n=1, L~U{1..4096} over 64 "
                       "seeded calls; 1 step = 1 token through 1 layer (a 32-layer model does 32 such steps per token); %d rotating "
                       "weight sets" % args.sets,
-          "mode": args.mode, "path": args.path, "mean_L": round(mean_L, 1), "build_id": rx.relax_build_id(), "setup_s": round(setup_s, 1)},
+          "mode": args.mode, "timed_passes": passes, "path": args.path, "mean_L": round(mean_L, 1), "build_id": rx.relax_build_id(), "setup_s": round(setup_s, 1)},
          roofline, cpu,
          {"layer_hbm": {"algorithmic_bytes_per_step": int(layer_bytes), "achieved_GBps": round(layer_gbs, 1),
                         "frac_of_peak": round(layer_gbs / PEAK_HBM_GBS, 4)},
-          "kernel_ms": {k_: round(v, 5) for k_, v in kernel_ms.items()}})
+          "kernel_ms": {k_: round(v, 5) for k_, v in kernel_ms.items()}, **extra_parts})
 
 
 # ------------------------------------------------------------------------------------------------ configs[2]
@@ -642,12 +740,19 @@ def bench_memory_plan(args, wl, rx):
             for n, L, B in cases:
                 rc, entries, planned, unplanned = rx.relax_workspace_plan(dims, n, L, B)
                 rx.check(rc, "relax_workspace_plan")
-                rows.append({"case": "%s n=%d L=%d B=%d" % (kind, n, L, B), "unplanned_bytes": unplanned, "planned_bytes": planned,
-                             "ratio": round(planned / unplanned, 4), "storages": len({e["storage"] for e in entries}), "tensors": len(entries)})
+                rc, entries_eq, planned_eq, _ = rx.relax_workspace_plan(dims, n, L, B, rule=1)
+                rx.check(rc, "relax_workspace_plan_rule")
+                rows.append({"case": "%s n=%d L=%d B=%d" % (kind, n, L, B), "unplanned_bytes": unplanned,
+                             "planned_bytes_equal_rule": planned_eq, "ratio_equal_rule": round(planned_eq / unplanned, 4),
+                             "storages_equal_rule": len({e["storage"] for e in entries_eq}),
+                             "planned_bytes": planned, "ratio": round(planned / unplanned, 4),
+                             "storages": len({e["storage"] for e in entries}), "tensors": len(entries)})
         table[shape.name] = rows
     head = table[wl.LLAMA7B.name][3]
     emit(args, "planned / unplanned activation bytes of one layer call (7B shape, prefill of 1024 tokens)", "ratio", head["ratio"], 0.0,
-         "bytes", {"workload": "dynamic shape-aware memory planning (Sec. 4.3, Alg. 3) of the layer workspace, in the shape of the paper's activation-memory experiment; host-only, nothing is timed",
+         "bytes", {"workload": "dynamic shape-aware memory planning (Sec. 4.3, Alg. 3) of the layer workspace, in the shape of the paper's activation-memory experiment "
+                               "(Sec. 5.2: prefill 128..1024, decode batch 1..64); *_equal_rule = the paper's rule (reuse on proven-equal symbolic sizes), "
+                               "the unsuffixed columns = the library's layout rule (reuse when the request provably fits); host-only, nothing is timed",
                    "build_id": rx.relax_build_id()}, None, None, {"higher_is_better": False, "memory_plan": table})
 
 
@@ -734,6 +839,8 @@ def main():
     ap.add_argument("--graph-steps", type=int, default=8, help="model_7b, graph mode: decode steps captured in the one graph that is replayed")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the CPU-oracle baseline leg (0 = skip)")
     ap.add_argument("--no-kernel-timing", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="decode_layer: skip the short prefill (n = 2048) and 32-layer model runs behind the "
+                                                             "`prefill` and `model_7b` keys of the line")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="before the workload, copy a 512 MiB buffer four times with a plain device copy kernel: a dispatch of known "
                          "traffic (512 MiB read, 512 MiB written) that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters")

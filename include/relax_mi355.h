@@ -152,6 +152,14 @@ typedef struct {
 } relax_plan_entry;
 relax_status relax_workspace_plan(const relax_layer_dims *dims, int32_t n, int32_t L, int32_t B, relax_plan_entry *entries,
                                   int32_t capacity, int32_t *count, size_t *planned_bytes, size_t *unplanned_bytes);
+/* The same query under a chosen reuse rule.  rule 1 is Alg. 3 as Sec. 4.3 states it: a free storage is reused only when
+ * the symbolic size of the request is proven EQUAL to the storage's (the same multiple of n, or the same opaque
+ * expression).  rule 0 is the extension the calls of this library lay their workspace out with (and what
+ * relax_workspace_plan reports): the request only has to fit provably, c1*n bytes into c2*n bytes when c1 <= c2.
+ * Offsets of rule 1 describe the layout that rule would give; no call uses it.  Other rules: RELAX_ERR_UNSUPPORTED. */
+relax_status relax_workspace_plan_rule(const relax_layer_dims *dims, int32_t n, int32_t L, int32_t B, int32_t rule,
+                                       relax_plan_entry *entries, int32_t capacity, int32_t *count, size_t *planned_bytes,
+                                       size_t *unplanned_bytes);
 
 /* The front of the workspace holds the state of the persistent fused decode kernel: an epoch counter and
  * the exchange buffers whose 8-byte words carry {value, epoch}.  It must be zeroed once before the first

@@ -13,14 +13,20 @@ expression the planner cannot decompose.  The steps are those of the algorithm, 
 
   1. liveness analysis: the last operation that uses each tensor;
   2. a storage pool with symbolic-shape awareness, empty at first;
-  3. walk the operations: an allocation asks the pool for a reusable storage (``request_reuse``: a free storage whose
-     size provably holds the request whatever the symbols are -- equal expressions, or c1 * n into c2 * n with
-     c1 <= c2 -- the smallest such), and opens a new storage when there is none; any other operation gives back the
-     storage of every tensor it uses that is dead after it.
+  3. walk the operations: an allocation asks the pool for a reusable storage and opens a new one when there is none;
+     any other operation gives back the storage of every tensor it uses that is dead after it.
+
+Two reuse rules:
+  rule="equal"  the algorithm as Sec. 4.3 states it: a free storage is reused when the request's symbolic size is
+                proven EQUAL to the storage's (the same multiple of n, the same opaque expression);
+  rule="fits"   the extension the library lays its workspace out with (default here, because that is what the
+                library's plan is compared with): the request only has to fit provably whatever the symbols are --
+                equal expressions, or c1 * n into c2 * n with c1 <= c2 -- and the smallest such storage is taken.
 
 The result maps every tensor to a storage index and every storage to the size expression it was opened with.
-Pinned by tests/test_oracle_pins.py (the four-tensors-into-two-chunks example of the paper's figure, chains, a brute
-force over all assignments on small programs, and the no-overlap invariant).
+Pinned by tests/test_memplan.py (the four-tensors-into-two-chunks example of the paper's figure under both rules, cases
+on which the rules differ, best fit, a brute force over all assignments on small programs, the no-overlap invariant,
+and closed forms of the byte count).
 """
 from __future__ import annotations
 
@@ -38,6 +44,11 @@ def provably_fits(want: Size, have: Size) -> bool:
     return False
 
 
+def provably_equal(want: Size, have: Size) -> bool:
+    """True when the two symbolic sizes are the same expression (the reuse condition of Sec. 4.3)."""
+    return want[0] == have[0] and want[1] == have[1]
+
+
 def liveness(program: Sequence[tuple], outputs: Sequence[str] = ()) -> Dict[str, int]:
     """Index of the last operation that uses each tensor (len(program) for the function's outputs)."""
     last: Dict[str, int] = {}
@@ -52,8 +63,10 @@ def liveness(program: Sequence[tuple], outputs: Sequence[str] = ()) -> Dict[str,
     return last
 
 
-def plan(program: Sequence[tuple], outputs: Sequence[str] = ()):
+def plan(program: Sequence[tuple], outputs: Sequence[str] = (), rule: str = "fits"):
     """Returns (storage_of_tensor: dict name -> storage index, storage_sizes: list of Size)."""
+    assert rule in ("fits", "equal")
+    reusable = provably_fits if rule == "fits" else provably_equal
     last = liveness(program, outputs)
     storage_sizes: List[Size] = []
     free: List[int] = []
@@ -61,7 +74,7 @@ def plan(program: Sequence[tuple], outputs: Sequence[str] = ()):
     for idx, op in enumerate(program):
         if op[0] == "alloc":
             _, name, size = op
-            candidates = [s for s in free if provably_fits(size, storage_sizes[s])]
+            candidates = [s for s in free if reusable(size, storage_sizes[s])]
             if candidates:
                 # smallest storage that holds the request; sizes of one kind compare by their coefficient, and storages
                 # of the other kind never are candidates

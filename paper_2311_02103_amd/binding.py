@@ -79,6 +79,8 @@ _SIGNATURES = {
     "relax_workspace_bytes": (C.c_size_t, [C.POINTER(LayerDims), C.c_int32, C.c_int32, C.c_int32]),
     "relax_workspace_plan": (C.c_int32, [C.POINTER(LayerDims), C.c_int32, C.c_int32, C.c_int32, C.POINTER(PlanEntryC), C.c_int32,
                                          C.POINTER(C.c_int32), C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]),
+    "relax_workspace_plan_rule": (C.c_int32, [C.POINTER(LayerDims), C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.POINTER(PlanEntryC), C.c_int32,
+                                              C.POINTER(C.c_int32), C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]),
     "relax_rope_table_bytes": (C.c_size_t, [C.POINTER(LayerDims)]),
     "relax_rope_table_init": (C.c_int32, [C.POINTER(LayerDims), C.c_void_p, C.c_void_p]),
     "relax_matmul_workspace_bytes": (C.c_size_t, [C.POINTER(QMatC), C.c_int32]),
@@ -217,11 +219,15 @@ def relax_workspace_bytes(dims: Optional[LayerDims], n_max: int, L_max: int, B_m
     return int(lib().relax_workspace_bytes(_ref(dims), n_max, L_max, B_max))
 
 
-def relax_workspace_plan(dims: Optional[LayerDims], n: int, L: int, B: int, capacity: int = 32):
-    """(status, entries, planned_bytes, unplanned_bytes); entries are dicts of the C struct's fields."""
+def relax_workspace_plan(dims: Optional[LayerDims], n: int, L: int, B: int, capacity: int = 32, rule: Optional[int] = None):
+    """(status, entries, planned_bytes, unplanned_bytes); entries are dicts of the C struct's fields.  rule: None calls
+    relax_workspace_plan, an integer calls relax_workspace_plan_rule with it (0: provably fits, 1: equal expressions)."""
     arr = (PlanEntryC * capacity)()
     count, planned, unplanned = C.c_int32(0), C.c_size_t(0), C.c_size_t(0)
-    rc = lib().relax_workspace_plan(_ref(dims), n, L, B, arr, capacity, C.byref(count), C.byref(planned), C.byref(unplanned))
+    if rule is None:
+        rc = lib().relax_workspace_plan(_ref(dims), n, L, B, arr, capacity, C.byref(count), C.byref(planned), C.byref(unplanned))
+    else:
+        rc = lib().relax_workspace_plan_rule(_ref(dims), n, L, B, rule, arr, capacity, C.byref(count), C.byref(planned), C.byref(unplanned))
     entries = []
     if rc == 0:
         for e in arr[:count.value]:

@@ -49,7 +49,16 @@ inline bool provably_fits(const SymBytes &want, const SymBytes &have)
     return false;
 }
 
-void plan_memory(MemPlan &mp, int n_ops)
+// The reuse rule as Sec. 4.3 states it: a storage is reused only by a tensor whose symbolic size is the SAME expression.
+inline bool provably_equal(const SymBytes &want, const SymBytes &have)
+{
+    if (want.per_row > 0 && have.per_row > 0) return want.per_row == have.per_row;
+    if (want.per_row == 0 && have.per_row == 0) return want.opaque == have.opaque;
+    return false;
+}
+
+// equal_only: the paper's rule (equal expressions); otherwise the extension the workspace layout uses (provably fits)
+void plan_memory(MemPlan &mp, int n_ops, bool equal_only = false)
 {
     bool is_free[T_COUNT] = {};
     mp.n_storages = 0;
@@ -61,7 +70,7 @@ void plan_memory(MemPlan &mp, int n_ops)
             mp.unplanned += align256(t.size.value);
             int best = -1;
             for (int s = 0; s < mp.n_storages; ++s) {
-                if (!is_free[s] || !provably_fits(t.size, mp.storage_size[s])) continue;
+                if (!is_free[s] || !(equal_only ? provably_equal(t.size, mp.storage_size[s]) : provably_fits(t.size, mp.storage_size[s]))) continue;
                 if (best < 0 || mp.storage_size[s].value < mp.storage_size[best].value) best = s;
             }
             if (best < 0) {
@@ -89,7 +98,7 @@ struct WsPlan {
     MemPlan mem;
 };
 
-WsPlan plan_ws(const relax_layer_dims &dm, int32_t n, int32_t L, int32_t B)
+WsPlan plan_ws(const relax_layer_dims &dm, int32_t n, int32_t L, int32_t B, bool equal_only = false)
 {
     WsPlan p;
     size_t off = 0;
@@ -139,7 +148,7 @@ WsPlan plan_ws(const relax_layer_dims &dm, int32_t n, int32_t L, int32_t B)
     mp.t[T_ACT] = {rows(2 * (size_t)dm.ffn), 5, 6, -1};
     mp.t[T_MMWS5] = {mmws, 5, 5, -1};
     mp.t[T_MMWS6] = {mmws, 6, 6, -1};
-    plan_memory(mp, 6);
+    plan_memory(mp, 6, equal_only);
     auto at = [&](int id) { return off + mp.storage_off[mp.t[id].storage]; };
     p.xn = at(T_XN), p.qkv = at(T_QKV), p.qbuf = p.qkv, p.partials = at(T_PART), p.attn = at(T_ATTN), p.x1 = at(T_X1), p.act = at(T_ACT);
     p.skinny = at(T_MMWS1);                                        // the four requests are the same expression: same storage every time
@@ -398,10 +407,17 @@ size_t relax_workspace_bytes(const relax_layer_dims *dims, int32_t n_max, int32_
 relax_status relax_workspace_plan(const relax_layer_dims *dims, int32_t n, int32_t L, int32_t B, relax_plan_entry *entries, int32_t capacity,
                                   int32_t *count, size_t *planned_bytes, size_t *unplanned_bytes)
 {
+    return relax_workspace_plan_rule(dims, n, L, B, 0, entries, capacity, count, planned_bytes, unplanned_bytes);
+}
+
+relax_status relax_workspace_plan_rule(const relax_layer_dims *dims, int32_t n, int32_t L, int32_t B, int32_t rule, relax_plan_entry *entries,
+                                       int32_t capacity, int32_t *count, size_t *planned_bytes, size_t *unplanned_bytes)
+{
     const relax_status rc = check_dims(dims);
     if (rc != RELAX_OK) return rc;
     if (n < 1 || L < 1 || B < 1) return RELAX_ERR_SHAPE;
-    const WsPlan pl = plan_ws(*dims, n, L, B);
+    if (rule != 0 && rule != 1) return RELAX_ERR_UNSUPPORTED;
+    const WsPlan pl = plan_ws(*dims, n, L, B, rule == 1);
     const size_t base = pl.total - pl.mem.planned;               // the planned region follows the fixed front part
     if (count) *count = T_COUNT;
     if (planned_bytes) *planned_bytes = pl.mem.planned;

@@ -22,9 +22,48 @@ def test_four_intermediates_of_equal_symbolic_shape_share_two_storages():
     """The example of the paper's memory-planning figure: four intermediate tensors, individually allocated before
     planning, live in two storage chunks afterwards."""
     prog = chain([("rows", 16)] * 4)
-    storage_of, sizes = memplan.plan(prog, outputs=["t3"])
-    assert len(sizes) == 2
-    assert [storage_of["t%d" % i] for i in range(4)] == [0, 1, 0, 1]
+    for rule in ("equal", "fits"):                                 # the paper's rule, and the extension: the example needs only equality
+        storage_of, sizes = memplan.plan(prog, outputs=["t3"], rule=rule)
+        assert len(sizes) == 2
+        assert [storage_of["t%d" % i] for i in range(4)] == [0, 1, 0, 1]
+        assert sizes == [("rows", 16), ("rows", 16)]
+
+
+def test_equality_rule_reuses_only_the_same_expression():
+    """Sec. 4.3 reuses a storage when the two symbolic sizes are proven equal: n*8 and n*4 are different expressions, so the
+    paper's rule opens a new storage where the "provably fits" extension parks the smaller tensor in the larger one."""
+    prog = chain([("rows", 8), ("rows", 8), ("rows", 4), ("rows", 8)])
+    eq_of, eq_sizes = memplan.plan(prog, outputs=["t3"], rule="equal")
+    assert eq_sizes == [("rows", 8), ("rows", 8), ("rows", 4)]
+    assert eq_of == {"t0": 0, "t1": 1, "t2": 2, "t3": 0}           # t2 (4n) gets its own storage; t3 (8n) reuses t0's, free since t1
+    fit_of, fit_sizes = memplan.plan(prog, outputs=["t3"], rule="fits")
+    assert fit_sizes == [("rows", 8), ("rows", 8)] and fit_of == {"t0": 0, "t1": 1, "t2": 0, "t3": 1}
+    # opaque expressions: only the same expression, under both rules
+    prog = chain([("opaque", 1), ("opaque", 2), ("opaque", 1), ("opaque", 2)])
+    for rule in ("equal", "fits"):
+        of, sizes = memplan.plan(prog, outputs=["t3"], rule=rule)
+        assert sizes == [("opaque", 1), ("opaque", 2)] and of == {"t0": 0, "t1": 1, "t2": 0, "t3": 1}
+    # neither rule dominates the other in bytes: the walk is greedy, and parking a small tensor in a big free storage (which
+    # only the extension may do) can force a new big storage later
+    sizes_ = [("rows", 9), ("rows", 3), ("rows", 3), ("rows", 9), ("rows", 1)]
+    pe = memplan.planned_bytes(memplan.plan(chain(sizes_), ["t4"], rule="equal")[1], 1000, {})
+    pf = memplan.planned_bytes(memplan.plan(chain(sizes_), ["t4"], rule="fits")[1], 1000, {})
+    assert (pe, pf) == (9216 + 3072 + 3072 + 1024, 9216 + 3072 + 9216)      # storages {9n, 3n, 3n, 1n} against {9n, 3n, 9n} at n = 1000
+
+
+def test_planned_bytes_closed_forms():
+    """The byte count of a plan is the sum of its storages, each evaluated at the symbols' values and rounded up to the
+    alignment: written out by hand here."""
+    assert memplan.evaluate(("rows", 100), 3, {}) == 300
+    assert memplan.evaluate(("opaque", 7), 3, {7: 1000}) == 1000
+    assert memplan.planned_bytes([("rows", 100), ("opaque", 1)], 3, {1: 1000}) == 512 + 1024            # 300 -> 512, 1000 -> 1024
+    assert memplan.planned_bytes([("rows", 256)], 1, {}) == 256                                          # exact multiples stay
+    assert memplan.planned_bytes([("rows", 256)], 2, {}) == 512
+    assert memplan.planned_bytes([("rows", 1)], 257, {}) == 512
+    assert memplan.planned_bytes([("rows", 1), ("rows", 1)], 1, {}, align=64) == 128
+    assert memplan.planned_bytes([], 5, {}) == 0
+    # the four equal intermediates of the figure at n = 10 rows of 16 bytes: two storages of 160 -> 256 bytes each
+    assert memplan.planned_bytes(memplan.plan(chain([("rows", 16)] * 4), ["t3"], rule="equal")[1], 10, {}) == 512
 
 
 def test_symbolically_different_sizes_are_not_reused_unless_they_provably_fit():
@@ -132,17 +171,22 @@ SHAPES = {"7B": dict(hidden=4096, n_heads=32, n_kv_heads=32, head_dim=128, ffn=1
           "tiny": dict(hidden=256, n_heads=4, n_kv_heads=4, head_dim=64, ffn=688)}
 
 
+@pytest.mark.parametrize("rule", ["fits", "equal"])
 @pytest.mark.parametrize("shape", list(SHAPES))
 @pytest.mark.parametrize("n,L,B", [(1, 1, 1), (1, 4096, 1), (16, 8000, 16), (64, 300, 64), (128, 128, 1), (512, 512, 2), (2048, 2048, 1)])
-def test_library_plan_equals_the_reference_plan(shape, n, L, B):
+def test_library_plan_equals_the_reference_plan(shape, n, L, B, rule):
     sh = SHAPES[shape]
     cap = 8192
     dims = rx.make_dims(sh["hidden"], sh["n_heads"], sh["n_kv_heads"], sh["head_dim"], sh["ffn"], cap, max(B, 1))
-    rc, entries, planned, unplanned = rx.relax_workspace_plan(dims, n, L, B)
+    if rule == "fits":                                            # the rule the workspace is laid out with: the plain query reports it
+        rc, entries, planned, unplanned = rx.relax_workspace_plan(dims, n, L, B)
+        assert (rc, entries, planned, unplanned) == rx.relax_workspace_plan(dims, n, L, B, rule=0)
+    else:                                                         # the paper's rule: equal expressions only
+        rc, entries, planned, unplanned = rx.relax_workspace_plan(dims, n, L, B, rule=1)
     assert rc == 0
     by_name = {e["name"]: e for e in entries}
     prog, outputs = layer_program(**sh)
-    storage_of, storage_sizes = memplan.plan(prog, outputs)
+    storage_of, storage_sizes = memplan.plan(prog, outputs, rule=rule)
     assert set(by_name) == set(storage_of)
     # same sharing structure (storage numbers are arbitrary labels on both sides: compare the partition of the tensors)
     part_lib, part_ref = {}, {}
@@ -170,7 +214,8 @@ def test_library_plan_equals_the_reference_plan(shape, n, L, B):
             assert ea["offset"] + ea["bytes"] <= eb["offset"] or eb["offset"] + eb["bytes"] <= ea["offset"], (a, b)
     for e in entries:
         assert e["offset"] % 256 == 0 and e["bytes"] <= e["storage_bytes"]
-    assert rx.relax_workspace_bytes(dims, n, L, B) == max(e["offset"] + (e["storage_bytes"] + 255) // 256 * 256 for e in entries)
+    if rule == "fits":
+        assert rx.relax_workspace_bytes(dims, n, L, B) == max(e["offset"] + (e["storage_bytes"] + 255) // 256 * 256 for e in entries)
 
 
 def test_plan_at_upper_bounds_covers_every_smaller_call():
@@ -191,3 +236,5 @@ def test_plan_query_errors():
     assert rx.relax_workspace_plan(None, 1, 1, 1)[0] == rx.ERR_NULL
     assert rx.relax_workspace_plan(dims, 0, 1, 1)[0] == rx.ERR_SHAPE
     assert rx.relax_workspace_plan(dims, 1, 1, 1, capacity=3)[0] == rx.ERR_WORKSPACE
+    assert rx.relax_workspace_plan(dims, 1, 1, 1, rule=2)[0] == rx.ERR_UNSUPPORTED
+    assert rx.relax_workspace_plan(dims, 1, 1, 1, rule=1)[0] == 0
