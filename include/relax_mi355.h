@@ -236,6 +236,22 @@ relax_status relax_attention(const uint16_t *q, const relax_kv_cache *cache, con
                              const relax_layer_dims *dims, uint16_t *out, int32_t n,
                              void *ws, size_t ws_bytes, relax_stream stream);
 
+/* relax_attention for callers that cannot allocate or bring a workspace: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments, checks, kernels and results as relax_attention, without
+ * ws / ws_bytes: the split-L partials live in a device array that is part of the library image (a file-scope
+ * __device__ array of relax_attention_static_max_bytes() = 16 MiB; every GPU the library runs on holds its copy until
+ * the process ends).  The call allocates nothing and frees nothing; its first call on a device looks the array's
+ * address up once.  Limits: the partials of the call -- relax_workspace_plan's "attn_partials" entry for (n, max L_b),
+ * e.g. 0.55 MB for one 7B-shaped decode row, 8.5 MB for 16 rows of the 70B shape at L = 8192 -- must fit the array
+ * (RELAX_ERR_WORKSPACE otherwise), and a descriptor without device_table may hold at most 16 sequences
+ * (RELAX_ERR_UNSUPPORTED: copying a longer one to the device needs a workspace).  All calls on one GPU share the array,
+ * which keeps the previous call's contents (every partial a call reads it has written itself, nothing needs clearing):
+ * calls that overlap on one GPU -- different streams, or graphs replayed concurrently -- race; calls on one stream
+ * are ordered and safe.                                                                                          */
+size_t       relax_attention_static_max_bytes(void);
+relax_status relax_attention_static(const uint16_t *q, const relax_kv_cache *cache, const relax_seqs *seqs,
+                                    const relax_layer_dims *dims, uint16_t *out, int32_t n, relax_stream stream);
+
 /* The whole layer on n rows:
  *   xn = RMSNorm(x; norm_attn); qkv = xn Wqkv^T; rotary(q,k); append k,v;
  *   a = attention(q); x1 = x + a Wo^T;

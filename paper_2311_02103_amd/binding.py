@@ -91,6 +91,9 @@ _SIGNATURES = {
                                        C.POINTER(LayerDims), C.POINTER(KVCacheC), C.POINTER(SeqsC), C.c_void_p]),
     "relax_attention": (C.c_int32, [C.c_void_p, C.POINTER(KVCacheC), C.POINTER(SeqsC), C.POINTER(LayerDims), C.c_void_p,
                                     C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "relax_attention_static_max_bytes": (C.c_size_t, []),
+    "relax_attention_static": (C.c_int32, [C.c_void_p, C.POINTER(KVCacheC), C.POINTER(SeqsC), C.POINTER(LayerDims), C.c_void_p,
+                                           C.c_int32, C.c_void_p]),
     "relax_decoder_layer": (C.c_int32, [C.POINTER(LayerDims), C.POINTER(LayerWeightsC), C.c_void_p, C.POINTER(KVCacheC),
                                         C.POINTER(SeqsC), C.c_void_p, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]),
     "relax_model_workspace_bytes": (C.c_size_t, [C.POINTER(ModelC), C.c_int32, C.c_int32, C.c_int32]),
@@ -272,6 +275,17 @@ def relax_attention(q: Ptr, cache: Optional[KVCache], seqs: Optional[Seqs], dims
     cc = None if cache is None else cache.c()
     sc = None if seqs is None else seqs.c()
     return lib().relax_attention(_ptr(q), _ref(cc), _ref(sc), _ref(dims), _ptr(out), n, _ptr(ws), ws_bytes, _stream(stream))
+
+
+def relax_attention_static_max_bytes() -> int:
+    return int(lib().relax_attention_static_max_bytes())
+
+
+def relax_attention_static(q: Ptr, cache: Optional[KVCache], seqs: Optional[Seqs], dims: Optional[LayerDims], out: Ptr, n: int,
+                           stream=None) -> int:
+    cc = None if cache is None else cache.c()
+    sc = None if seqs is None else seqs.c()
+    return lib().relax_attention_static(_ptr(q), _ref(cc), _ref(sc), _ref(dims), _ptr(out), n, _stream(stream))
 
 
 def relax_decoder_layer(dims: Optional[LayerDims], weights: Optional[LayerWeights], x: Ptr, cache: Optional[KVCache],

@@ -2,6 +2,7 @@
 // the workspace plan, and the launch sequence of each exported call.  See include/relax_mi355.h
 // for the contract and for the passages of the paper each rule comes from.
 #include <cstring>
+#include <mutex>
 #include <vector>
 
 #include "relax_common.h"
@@ -319,6 +320,32 @@ hipError_t half_matmul_enqueue(const uint16_t *x, const uint16_t *w, uint16_t *o
     return launch_lm_head(x, w, out, n, k, m, device_cus(), st_);
 }
 
+// Scratch of relax_attention_static: the split-L partials of one call live in this file-scope device array instead of a
+// caller workspace.  Every GPU holds its own copy at its own address; the name is a host-side stand-in, so the address is
+// asked for once per device (with that device current) and only that pointer is ever handed to kernels.
+constexpr size_t kStaticScratchBytes = (size_t)16 << 20;
+__device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mutex;
+
+relax_status static_scratch(void **out)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return RELAX_ERR_HIP;
+    if (dev < 0 || dev >= kMaxDevices) return RELAX_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        const relax_status rc = hip_status(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (rc != RELAX_OK) return rc;
+        if (!p) return RELAX_ERR_HIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return RELAX_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -532,6 +559,29 @@ relax_status relax_attention(const uint16_t *q, const relax_kv_cache *cache, con
     if (rc != RELAX_OK) return rc;
     float *partials = reinterpret_cast<float *>(static_cast<char *>(ws) + pl.partials);
     return hip_status(launch_attention(q, dims->n_heads * dims->head_dim, *cache, *dims, st, L_max, out, partials, st_));
+}
+
+size_t relax_attention_static_max_bytes(void) { return kStaticScratchBytes; }
+
+relax_status relax_attention_static(const uint16_t *q, const relax_kv_cache *cache, const relax_seqs *seqs, const relax_layer_dims *dims,
+                                    uint16_t *out, int32_t n, relax_stream stream)
+{
+    hipStream_t st_ = static_cast<hipStream_t>(stream);
+    relax_status rc = check_dims(dims);
+    if (rc != RELAX_OK) return rc;
+    if (!q || !out || !cache || !cache->k || !cache->v) return RELAX_ERR_NULL;
+    SeqTable st = {};
+    std::vector<int32_t> host_table;                             // stays empty (no heap use) unless B > kInlineSeqs, which is refused below
+    int32_t L_max = 0;
+    if (seqs && !seqs->device_table && seqs->B > kInlineSeqs) return RELAX_ERR_UNSUPPORTED;   // the copy of a long descriptor needs a workspace
+    rc = build_seqs(seqs, *dims, n, st, L_max, host_table);
+    if (rc != RELAX_OK) return rc;
+    const size_t need = sizeof(float) * attn_partial_floats(*dims, n, L_max);
+    if (need > kStaticScratchBytes) return RELAX_ERR_WORKSPACE;
+    void *base = nullptr;
+    rc = static_scratch(&base);
+    if (rc != RELAX_OK) return rc;
+    return hip_status(launch_attention(q, dims->n_heads * dims->head_dim, *cache, *dims, st, L_max, out, static_cast<float *>(base), st_));
 }
 
 }  // extern "C"

@@ -114,6 +114,23 @@ def test_attention_and_norm_rope_checks():
     assert rx.relax_rope_table_init(d, None) == rx.ERR_NULL
 
 
+def test_static_attention_checks():
+    """The entry point without a workspace refuses, on the host, what its fixed device array cannot hold."""
+    d = dims()
+    c = rx.KVCache(P, P, P)
+    s = rx.Seqs([2], [5])
+    assert rx.relax_attention_static_max_bytes() == 16 << 20
+    assert rx.relax_attention_static(None, c, s, d, P, 2) == rx.ERR_NULL
+    assert rx.relax_attention_static(P, c, None, d, P, 2) == rx.ERR_NULL
+    assert rx.relax_attention_static(P, c, s, d, P, 3) == rx.ERR_SHAPE
+    assert rx.relax_attention_static(P, c, rx.Seqs([2], [70]), d, P, 2) == rx.ERR_CAPACITY
+    big = dims(hidden=8192, n_heads=64, n_kv_heads=8, head_dim=128, ffn=28672, kv_capacity=8192, kv_slots=64)
+    # 17 sequences without a device table: the copy of the descriptor would need a workspace
+    assert rx.relax_attention_static(P, c, rx.Seqs([1] * 17, [100] * 17), big, P, 17) == rx.ERR_UNSUPPORTED
+    # 64 rows x 64 heads x 16 splits x 130 floats = 34 MB of partials: beyond the 16 MiB array
+    assert rx.relax_attention_static(P, c, rx.Seqs([1] * 64, [8192] * 64, device_table=P), big, P, 64) == rx.ERR_WORKSPACE
+
+
 def test_model_step_and_matmul_workspace_checks():
     d = dims()
     w = weights(d)
