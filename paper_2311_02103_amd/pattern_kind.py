@@ -59,11 +59,11 @@ class Program:
     tensors: Set[str]
 
     @property
-    def w_indices(self) -> List[Tuple[str, ...]]:
+    def write_tuples(self) -> List[Tuple[str, ...]]:
         return [s.write.indices for s in self.statements]
 
     @property
-    def r_indices(self) -> List[Tuple[str, ...]]:
+    def read_tuples(self) -> List[Tuple[str, ...]]:
         return [r.indices for s in self.statements for r in s.reads]
 
 
@@ -153,19 +153,19 @@ def _plain(indices: Tuple[str, ...]) -> bool:
     return all(_IDENT.fullmatch(i) for i in indices)
 
 
-def is_element_wise(r_idx, w_idx) -> bool:
-    return tuple(r_idx) == tuple(w_idx)
+def is_element_wise(read, write) -> bool:
+    return tuple(read) == tuple(write)
 
 
-def is_broadcast(r_idx, w_idx) -> bool:
-    if not (_plain(r_idx) and _plain(w_idx)) or len(r_idx) >= len(w_idx) or len(set(r_idx)) != len(r_idx):
+def is_broadcast(read, write) -> bool:
+    if not (_plain(read) and _plain(write)) or len(read) >= len(write) or len(set(read)) != len(read):
         return False
-    it = iter(w_idx)
-    return all(any(v == w for w in it) for v in r_idx)             # order-preserving sub-sequence
+    it = iter(write)
+    return all(any(v == w for w in it) for v in read)             # order-preserving sub-sequence
 
 
-def is_injective(r_idx, w_idx, tensors: Set[str]) -> bool:
-    return _variables(r_idx, tensors) <= _variables(w_idx, tensors)
+def is_injective(read, write, tensors: Set[str]) -> bool:
+    return _variables(read, tensors) <= _variables(write, tensors)
 
 
 def _top_level_product(rhs: str) -> bool:
@@ -195,34 +195,46 @@ def is_fuse_multiply_add(prog: Program) -> bool:
     return has_reduction_loop(prog) and any(s.op == "+=" and _top_level_product(s.rhs) for s in prog.statements)
 
 
+# Generality of one read relative to the write's index tuple: a read is rated by the most specific of the three index
+# predicates it satisfies, and anything else is unrated.  Ratings are totally ordered, so a whole program is rated by the
+# most general read it contains.
+_IDENTITY, _SUBSEQUENCE, _ONE_TO_ONE, _UNRATED = range(4)
+_KIND_OF_RATING = (ELEMENT_WISE, BROADCAST, INJECTIVE, OPAQUE)
+
+
+def _rate_read(read_indices, write_indices, tensors: Set[str]) -> int:
+    if is_element_wise(read_indices, write_indices):
+        return _IDENTITY
+    if is_broadcast(read_indices, write_indices):
+        return _SUBSEQUENCE
+    if is_injective(read_indices, write_indices, tensors):
+        return _ONE_TO_ONE
+    return _UNRATED
+
+
 def pattern_kind(source) -> str:
-    """Alg. 1 on a program given as text or as a parsed Program."""
+    """Pattern kind of a program given as text or as a parsed Program (Sec. 4.2, Alg. 1).
+
+    Formulation: (1) a program whose statements write through different index tuples is Opaque; (2) every read is rated on
+    the lattice identity < sub-sequence < one-to-one < unrated against the write's indices, and the program takes the
+    highest rating among its reads (a program without reads is unrated); (3) the rating maps to a kind, with two
+    refinements: a sub-sequence program that also holds an identity read computes one output element per input element
+    and counts as ElementWise, and an unrated program is still fusible when it is a multiply-add over a reduction loop
+    (OutputEwiseFusible) or any other reduction (Reduction)."""
     prog = source if isinstance(source, Program) else parse(source)
-    w_all = prog.w_indices
-    if any(w != w_all[0] for w in w_all):
+    writes = prog.write_tuples
+    if len(set(writes)) > 1:
         return OPAQUE
-    w_idx = w_all[0]
-    order = {ELEMENT_WISE: 0, BROADCAST: 1, INJECTIVE: 2, OPAQUE: 3}
-    kind, has_elem_wise, seen = OPAQUE, False, None
-    for r_idx in prog.r_indices:
-        if is_element_wise(r_idx, w_idx):
-            this, has_elem_wise = ELEMENT_WISE, True
-        elif is_broadcast(r_idx, w_idx):
-            this = BROADCAST
-        elif is_injective(r_idx, w_idx, prog.tensors):
-            this = INJECTIVE
-        else:
-            this = OPAQUE
-        seen = this if seen is None or order[this] > order[seen] else seen
-    if seen is not None:
-        kind = seen
-    if kind == BROADCAST and has_elem_wise:
-        kind = ELEMENT_WISE
-    elif kind == OPAQUE and is_fuse_multiply_add(prog):
-        kind = OUT_EWISE_FUSIBLE
-    elif kind == OPAQUE and has_reduction_loop(prog):
-        kind = REDUCTION
-    return kind
+    ratings = [_rate_read(r, writes[0], prog.tensors) for r in prog.read_tuples]
+    rating = max(ratings, default=_UNRATED)
+    if rating == _SUBSEQUENCE and _IDENTITY in ratings:
+        return ELEMENT_WISE
+    if rating == _UNRATED:
+        if is_fuse_multiply_add(prog):
+            return OUT_EWISE_FUSIBLE
+        if has_reduction_loop(prog):
+            return REDUCTION
+    return _KIND_OF_RATING[rating]
 
 
 # The steps of the decoder layer (Sec. 5.1's LLM workload) as index expressions, with the kind Alg. 1 gives each; i = row,

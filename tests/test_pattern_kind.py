@@ -24,8 +24,8 @@ def test_examples_named_by_the_listing(program, kind):
 
 def test_read_and_write_indices_of_the_listing_example():
     prog = pk.parse("C[i,j] = A[i,j] + B[j]")
-    assert prog.r_indices == [("i", "j"), ("j",)]
-    assert prog.w_indices == [("i", "j")]
+    assert prog.read_tuples == [("i", "j"), ("j",)]
+    assert prog.write_tuples == [("i", "j")]
 
 
 def test_index_predicates():
