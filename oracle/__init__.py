@@ -45,7 +45,7 @@ class _Dims(C.Structure):
 
 
 class _QMat(C.Structure):
-    _fields_ = [("q", C.c_void_p), ("s", C.c_void_p), ("m", C.c_int32), ("k", C.c_int32)]
+    _fields_ = [("q", C.c_void_p), ("s", C.c_void_p), ("m", C.c_int32), ("k", C.c_int32), ("group", C.c_int32)]
 
 
 class _LayerWeights(C.Structure):
@@ -133,23 +133,29 @@ def unpack_int4(qweight: np.ndarray, m: int, k: int) -> np.ndarray:
     return out
 
 
-def dequantize(qweight: np.ndarray, scales: np.ndarray, m: int, k: int) -> np.ndarray:
+def dequantize(qweight: np.ndarray, scales: np.ndarray, m: int, k: int, group: int = 32) -> np.ndarray:
     qweight = _chk(qweight, np.uint32, (m, k // 8))
-    scales = _chk(scales, np.uint16, (m, (k + 31) // 32))
+    scales = _chk(scales, np.uint16, (m, (k + group - 1) // group))
     out = np.empty((m, k), dtype=np.float32)
-    lib().oracle_dequantize(_p(qweight), _p(scales), C.c_int32(m), C.c_int32(k), _p(out))
+    if group == 32:
+        lib().oracle_dequantize(_p(qweight), _p(scales), C.c_int32(m), C.c_int32(k), _p(out))
+    else:
+        lib().oracle_dequantize_g(_p(qweight), _p(scales), C.c_int32(m), C.c_int32(k), C.c_int32(group), _p(out))
     return out
 
 
-def dequant_matmul(x: np.ndarray, qweight: np.ndarray, scales: np.ndarray, m: int, k: int) -> np.ndarray:
+def dequant_matmul(x: np.ndarray, qweight: np.ndarray, scales: np.ndarray, m: int, k: int, group: int = 32) -> np.ndarray:
     x = _chk(x, np.float32)
     n = x.shape[0]
     assert x.shape == (n, k)
     qweight = _chk(qweight, np.uint32, (m, k // 8))
-    scales = _chk(scales, np.uint16, (m, (k + 31) // 32))
+    scales = _chk(scales, np.uint16, (m, (k + group - 1) // group))
     out = np.empty((n, m), dtype=np.float32)
-    lib().oracle_dequant_matmul(_p(x), _p(qweight), _p(scales), C.c_int32(m), C.c_int32(k),
-                                _p(out), C.c_int32(n))
+    if group == 32:
+        lib().oracle_dequant_matmul(_p(x), _p(qweight), _p(scales), C.c_int32(m), C.c_int32(k), _p(out), C.c_int32(n))
+    else:
+        lib().oracle_dequant_matmul_g(_p(x), _p(qweight), _p(scales), C.c_int32(m), C.c_int32(k), C.c_int32(group),
+                                      _p(out), C.c_int32(n))
     return out
 
 
@@ -229,14 +235,15 @@ def argmax(logits: np.ndarray) -> np.ndarray:
 @dataclass
 class QMat:
     q: np.ndarray  # uint32 [m, k/8]
-    s: np.ndarray  # uint16 [m, ceil(k/32)]
+    s: np.ndarray  # uint16 [m, ceil(k/group)]
     m: int
     k: int
+    group: int = 32
 
     def c(self) -> _QMat:
         self.q = _chk(self.q, np.uint32, (self.m, self.k // 8))
-        self.s = _chk(self.s, np.uint16, (self.m, (self.k + 31) // 32))
-        return _QMat(self.q.ctypes.data, self.s.ctypes.data, self.m, self.k)
+        self.s = _chk(self.s, np.uint16, (self.m, (self.k + self.group - 1) // self.group))
+        return _QMat(self.q.ctypes.data, self.s.ctypes.data, self.m, self.k, self.group)
 
 
 @dataclass

@@ -41,7 +41,9 @@ float oracle_half_to_float(uint16_t bits)
     return sign ? -mag : mag;
 }
 
-static int32_t groups_per_row(int32_t k) { return (k + 31) / 32; }
+/* scales per row: one per `group` consecutive columns, the last group short when group does not divide k */
+static int32_t groups_per_row(int32_t k, int32_t group) { return (k + group - 1) / group; }
+static int32_t group_of(int32_t group) { return group > 0 ? group : 32; }     /* 0 in a descriptor reads as 32 */
 
 /* code of element (r,c): word r*(k/8)+c/8, bits 4*(c%8)..4*(c%8)+3          */
 static int nibble_code(const uint32_t *qweight, int32_t k, int32_t r, int32_t c)
@@ -58,33 +60,47 @@ void oracle_unpack_int4(const uint32_t *qweight, int32_t m, int32_t k, int8_t *o
 }
 
 static void dequant_row(const uint32_t *qweight, const uint16_t *scales,
-                        int32_t k, int32_t r, float *row)
+                        int32_t k, int32_t group, int32_t r, float *row)
 {
-    int32_t G = groups_per_row(k);
+    int32_t G = groups_per_row(k, group);
     for (int32_t c = 0; c < k; ++c) {
         int q = nibble_code(qweight, k, r, c) - 8;
-        float s = oracle_half_to_float(scales[(size_t)r * G + c / 32]);
+        float s = oracle_half_to_float(scales[(size_t)r * G + c / group]);
         row[c] = (float)q * s;
     }
+}
+
+void oracle_dequantize_g(const uint32_t *qweight, const uint16_t *scales,
+                         int32_t m, int32_t k, int32_t group, float *out)
+{
+    group = group_of(group);
+#pragma omp parallel for schedule(static)
+    for (int32_t r = 0; r < m; ++r)
+        dequant_row(qweight, scales, k, group, r, out + (size_t)r * k);
 }
 
 void oracle_dequantize(const uint32_t *qweight, const uint16_t *scales,
                        int32_t m, int32_t k, float *out)
 {
-#pragma omp parallel for schedule(static)
-    for (int32_t r = 0; r < m; ++r)
-        dequant_row(qweight, scales, k, r, out + (size_t)r * k);
+    oracle_dequantize_g(qweight, scales, m, k, 32, out);
 }
 
 void oracle_dequant_matmul(const float *x, const uint32_t *qweight, const uint16_t *scales,
                            int32_t m, int32_t k, float *out, int32_t n)
 {
+    oracle_dequant_matmul_g(x, qweight, scales, m, k, 32, out, n);
+}
+
+void oracle_dequant_matmul_g(const float *x, const uint32_t *qweight, const uint16_t *scales,
+                             int32_t m, int32_t k, int32_t group, float *out, int32_t n)
+{
+    group = group_of(group);
 #pragma omp parallel
     {
         float *row = (float *)malloc(sizeof(float) * (size_t)(k > 0 ? k : 1));
 #pragma omp for schedule(static)
         for (int32_t r = 0; r < m; ++r) {
-            dequant_row(qweight, scales, k, r, row);        /* W[r, :]        */
+            dequant_row(qweight, scales, k, group, r, row); /* W[r, :]        */
             for (int32_t i = 0; i < n; ++i) {
                 const float *xi = x + (size_t)i * k;
                 float acc = 0.0f;
@@ -283,21 +299,21 @@ int32_t oracle_decoder_layer_f32(const oracle_dims *dm, const oracle_layer_weigh
 
     /* attention block */
     oracle_rmsnorm(x, w->norm_attn, xn, n, H, dm->rms_eps);
-    oracle_dequant_matmul(xn, w->wqkv.q, w->wqkv.s, w->wqkv.m, w->wqkv.k, qkv, n);
+    oracle_dequant_matmul_g(xn, w->wqkv.q, w->wqkv.s, w->wqkv.m, w->wqkv.k, w->wqkv.group, qkv, n);
     oracle_rope_append(qkv, dm, kcache, vcache, sq, n);
     for (int32_t i = 0; i < n; ++i)
         memcpy(qbuf + (size_t)i * h * d, qkv + (size_t)i * qkvw, sizeof(float) * (size_t)(h * d));
     oracle_attention(qbuf, kcache, vcache, dm, sq, attn, n, NULL);
-    oracle_dequant_matmul(attn, w->wo.q, w->wo.s, w->wo.m, w->wo.k, proj, n);
+    oracle_dequant_matmul_g(attn, w->wo.q, w->wo.s, w->wo.m, w->wo.k, w->wo.group, proj, n);
     for (size_t e = 0; e < (size_t)n * H; ++e)
         x1[e] = x[e] + proj[e];
 
     /* feed-forward block */
     if (taps && taps->xn) memcpy(taps->xn, xn, sizeof(float) * (size_t)n * H);
     oracle_rmsnorm(x1, w->norm_ffn, xn, n, H, dm->rms_eps);
-    oracle_dequant_matmul(xn, w->wgu.q, w->wgu.s, w->wgu.m, w->wgu.k, gu, n);
+    oracle_dequant_matmul_g(xn, w->wgu.q, w->wgu.s, w->wgu.m, w->wgu.k, w->wgu.group, gu, n);
     oracle_swiglu(gu, act, n, F);
-    oracle_dequant_matmul(act, w->wdown.q, w->wdown.s, w->wdown.m, w->wdown.k, proj, n);
+    oracle_dequant_matmul_g(act, w->wdown.q, w->wdown.s, w->wdown.m, w->wdown.k, w->wdown.group, proj, n);
     for (size_t e = 0; e < (size_t)n * H; ++e)
         out[e] = x1[e] + proj[e];
 

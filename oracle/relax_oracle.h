@@ -57,6 +57,17 @@ void oracle_dequant_matmul(const float *x /* [n,k] */, const uint32_t *qweight,
                            const uint16_t *scales, int32_t m, int32_t k,
                            float *out /* [n,m] */, int32_t n);
 
+/* Steps 2 and 3 for any quantisation group along k (the workload description
+ * fixes 32; deployments of the paper's 4-bit models also use wider groups):
+ * W[r,c] = (float)(u-8) * (float)scales[r*ceil(k/group) + c/group], the last
+ * group of a row short when group does not divide k.  group <= 0 reads as 32;
+ * the two functions above are these with group = 32.                        */
+void oracle_dequantize_g(const uint32_t *qweight, const uint16_t *scales,
+                         int32_t m, int32_t k, int32_t group, float *out /* [m,k] */);
+void oracle_dequant_matmul_g(const float *x /* [n,k] */, const uint32_t *qweight,
+                             const uint16_t *scales, int32_t m, int32_t k, int32_t group,
+                             float *out /* [n,m] */, int32_t n);
+
 /* Dense fp16 weight matmul (LM head): out[i,r] = sum_c x[i,c]*(float)w[r,c]. */
 void oracle_half_matmul(const float *x /* [n,k] */, const uint16_t *w /* [m,k] */,
                         int32_t m, int32_t k, float *out /* [n,m] */, int32_t n);
@@ -102,9 +113,10 @@ void oracle_attention(const float *q, const float *kcache, const float *vcache,
 void oracle_swiglu(const float *gu /* [n,2F] */, float *a /* [n,F] */, int32_t n, int32_t F);
 
 typedef struct {
-    const uint32_t *q;   /* [m, k/8]        */
-    const uint16_t *s;   /* [m, ceil(k/32)] */
+    const uint32_t *q;   /* [m, k/8]           */
+    const uint16_t *s;   /* [m, ceil(k/group)] */
     int32_t m, k;
+    int32_t group;       /* columns per scale; <= 0 reads as 32 */
 } oracle_qmat;
 
 typedef struct {

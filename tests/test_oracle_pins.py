@@ -109,6 +109,104 @@ def test_dequant_is_exact_product_for_all_codes_and_odd_scales():
     assert np.array_equal(W.astype(np.float64), want)      # 4-bit x 11-bit product is exact in fp32
 
 
+# ----------------------------------------------------------------------------- other quantisation groups (64, 128 columns per scale)
+def _golden_group_cases():
+    cases = []
+    for line in open(os.path.join(GOLD, "group_scales.txt")):
+        line = line.split("#")[0].strip()
+        if not line:
+            continue
+        head, rest = line.split(":")
+        per_row, pairs = rest.split("|")
+        group, k = (int(v) for v in head.split())
+        cases.append((group, k, int(per_row), [tuple(int(v) for v in pr.split("->")) for pr in pairs.split()]))
+    assert len(cases) >= 6
+    return cases
+
+
+def test_group_scale_indexing_against_hand_worked_table():
+    """Scale number g of a row holds 2^(g - 8) and every code is +1: the decoded element IS its scale, so the element at
+    column c names the scale it read.  Columns and expected scale numbers come from the hand-written table."""
+    for group, k, per_row, pairs in _golden_group_cases():
+        m = 3
+        assert (k + group - 1) // group == per_row
+        expo = np.arange(per_row)[None, :] - 8 + np.arange(m)[:, None] * 0          # same powers in every row ...
+        scales = np.ldexp(np.float32(1), expo).astype(np.float16)
+        scales[1] *= np.float16(4.0)                                                 # ... except row 1: rows must not mix
+        W = oracle.dequantize(wl.pack_codes(np.full((m, k), 9, np.uint8)), scales.view(np.uint16), m, k, group)
+        for c, g in pairs:
+            assert W[0, c] == 2.0 ** (g - 8) and W[2, c] == 2.0 ** (g - 8), (group, k, c, g)
+            assert W[1, c] == 4.0 * 2.0 ** (g - 8), (group, k, c, g)
+
+
+@pytest.mark.parametrize("group", [64, 128])
+@pytest.mark.parametrize("k", [256, 688])
+def test_wider_group_equals_group_32_with_repeated_scales(group, k):
+    """A matrix with one scale per `group` columns is the group-32 matrix whose neighbouring scales are equal: decode and
+    matmul through the wider-group entry points must equal, bit for bit, the (separately pinned) group-32 ones on scales
+    repeated group/32 times -- including the short last group of k = 688."""
+    m, n = 9, 3
+    q, s = wl.qmat(21, group, m, k, group=group)
+    assert s.shape == (m, (k + group - 1) // group)
+    s32 = np.repeat(s, group // 32, axis=1)[:, :(k + 31) // 32].copy()
+    assert np.array_equal(oracle.dequantize(q, s, m, k, group).view(np.uint32), oracle.dequantize(q, s32, m, k).view(np.uint32))
+    x = RS(22).randn(n, k).astype(np.float32)
+    assert np.array_equal(oracle.dequant_matmul(x, q, s, m, k, group).view(np.uint32), oracle.dequant_matmul(x, q, s32, m, k).view(np.uint32))
+
+
+@pytest.mark.parametrize("group", [64, 128])
+def test_wider_group_matmul_integer_case_and_float64(group):
+    m, k, n = 17, 688, 4
+    r = RS(23 + group)
+    codes = r.randint(0, 16, size=(m, k)).astype(np.uint8)
+    sc = r.choice([1.0, 2.0], size=(m, (k + group - 1) // group)).astype(np.float32)
+    x = r.randint(-3, 4, size=(n, k)).astype(np.float32)
+    out = oracle.dequant_matmul(x, wl.pack_codes(codes), f16(sc), m, k, group)
+    W = (codes.astype(np.int64) - 8) * np.repeat(sc.astype(np.int64), group, axis=1)[:, :k]
+    assert np.array_equal(out.astype(np.int64), x.astype(np.int64) @ W.T)
+    q, s = wl.qmat(24, group, m, k, group=group)
+    xr = r.randn(n, k).astype(np.float32)
+    dense = (oracle.unpack_int4(q, m, k).astype(np.float64) * np.repeat(s.view(np.float16).astype(np.float64), group, axis=1)[:, :k])
+    want = xr.astype(np.float64) @ dense.T
+    got = oracle.dequant_matmul(xr, q, s, m, k, group)
+    assert np.max(np.abs(got - want)) < 2e-5 * max(1.0, np.max(np.abs(want)))
+
+
+@pytest.mark.parametrize("group", [64, 128])
+def test_quantizer_with_wider_groups(group):
+    m, k = 6, 688
+    w = wl.normal_f32(25, group, (m, k), std=0.02)
+    q, s = wl.quantize_q4(w, group)
+    G = (k + group - 1) // group
+    assert s.shape == (m, G)
+    W = oracle.dequantize(q, s, m, k, group)
+    sc = np.repeat(s.view(np.float16).astype(np.float32), group, axis=1)[:, :k]
+    assert np.all(np.abs(w - W) <= 0.5 * sc * (1 + 2e-3) + 1e-12)
+    codes = np.abs(oracle.unpack_int4(q, m, k).astype(np.int32))
+    for g in range(G):
+        assert np.all(codes[:, g * group:min(k, (g + 1) * group)].max(axis=1) == 7)
+    amax = np.abs(np.pad(w, ((0, 0), (0, G * group - k))).reshape(m, G, group)).max(axis=2)
+    assert np.array_equal(s, (amax / np.float32(7.0)).astype(np.float16).view(np.uint16))
+
+
+def test_layer_with_group_64_equals_layer_with_repeated_group_32_scales():
+    shape, cap, group = wl.TINY, 16, 64
+    w = wl.layer_weights(shape, 26, group=group)
+    mats = shape.matrices()
+    wide = oracle.LayerWeights(*(oracle.QMat(w[n + ".q"], w[n + ".s"], *mats[n], group) for n in ("wqkv", "wo", "wgu", "wdown")),
+                               w["norm_attn"], w["norm_ffn"])
+    rep = lambda nme: np.repeat(w[nme + ".s"], 2, axis=1)[:, :(mats[nme][1] + 31) // 32].copy()
+    narrow = oracle.LayerWeights(*(oracle.QMat(w[n + ".q"], rep(n), *mats[n]) for n in ("wqkv", "wo", "wgu", "wdown")),
+                                 w["norm_attn"], w["norm_ffn"])
+    dims = oracle.Dims(shape.hidden, shape.n_heads, shape.n_kv_heads, shape.head_dim, shape.ffn, shape.rms_eps, shape.rope_base, cap)
+    x = wl.activations(shape, 26, 0, 5)
+    outs = []
+    for lw in (wide, narrow):
+        K, V = np.zeros((1, cap, shape.n_kv_heads, shape.head_dim), np.float32), np.zeros((1, cap, shape.n_kv_heads, shape.head_dim), np.float32)
+        outs.append(oracle.decoder_layer(dims, lw, x, K, V, oracle.Seqs([5], [5])))
+    assert np.array_equal(outs[0].view(np.uint32), outs[1].view(np.uint32)) and np.abs(outs[0]).max() > 0.1
+
+
 # ----------------------------------------------------------------------------- matmul
 def test_matmul_all_ones_closed_form():
     m, k, n = 6, 688, 2

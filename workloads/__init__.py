@@ -108,19 +108,19 @@ def pack_codes(codes: np.ndarray) -> np.ndarray:
     return word
 
 
-def quantize_q4(w: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
-    """Symmetric int4, group 32 along k (last group short if k % 32 != 0).
+def quantize_q4(w: np.ndarray, group: int = GROUP) -> Tuple[np.ndarray, np.ndarray]:
+    """Symmetric int4, `group` columns per scale along k (32 unless stated; last group short if it does not divide k).
 
     Per group: scale = fp16(max|w| / 7); codes = clamp(rint(w / scale), -7, 7) + 8,
     an all-zero group (scale 0) gets code 8 everywhere.  Returns
-    (qweight uint32 [m,k/8], scales uint16 bits [m,ceil(k/32)])."""
+    (qweight uint32 [m,k/8], scales uint16 bits [m,ceil(k/group)])."""
     w = np.ascontiguousarray(w, dtype=np.float32)
     m, k = w.shape
     assert k % NIBBLES == 0
-    G = (k + GROUP - 1) // GROUP
-    pad = G * GROUP - k
+    G = (k + group - 1) // group
+    pad = G * group - k
     wp = np.pad(w, ((0, 0), (0, pad))) if pad else w
-    grp = wp.reshape(m, G, GROUP)
+    grp = wp.reshape(m, G, group)
     amax = np.abs(grp).max(axis=2)
     s16 = (amax / np.float32(7.0)).astype(np.float16)
     s32 = s16.astype(np.float32)
@@ -128,21 +128,21 @@ def quantize_q4(w: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
     q = np.rint(grp / safe[:, :, None])
     q = np.clip(q, -7, 7)
     q = np.where((s32 > 0)[:, :, None], q, 0.0)
-    codes = (q + 8).astype(np.uint8).reshape(m, G * GROUP)[:, :k]
+    codes = (q + 8).astype(np.uint8).reshape(m, G * group)[:, :k]
     return pack_codes(np.ascontiguousarray(codes)), s16.view(np.uint16)
 
 
-def _qmat_slab(seed: int, tensor_id: int, slab: int, rows: int, k: int, std: float):
+def _qmat_slab(seed: int, tensor_id: int, slab: int, rows: int, k: int, std: float, group: int = GROUP):
     # every slab has its own Philox counter block, so the result does not depend on how slabs are scheduled
     g = np.random.Generator(np.random.Philox(key=[int(seed), int(tensor_id)], counter=[0, 0, int(slab) + 1, 0]))
     w = g.standard_normal(size=(rows, k), dtype=np.float32) * np.float32(std)
-    return quantize_q4(w)
+    return quantize_q4(w, group)
 
 
-def qmat(seed: int, tensor_id: int, m: int, k: int, std: float = 0.02) -> Tuple[np.ndarray, np.ndarray]:
+def qmat(seed: int, tensor_id: int, m: int, k: int, std: float = 0.02, group: int = GROUP) -> Tuple[np.ndarray, np.ndarray]:
     """One random quantised matrix N(0, std^2); generated in row slabs (bounded host memory, threads)."""
     slab_rows = max(1, (1 << 22) // k)
-    jobs = [(seed, tensor_id, i, min(slab_rows, m - r0), k, std) for i, r0 in enumerate(range(0, m, slab_rows))]
+    jobs = [(seed, tensor_id, i, min(slab_rows, m - r0), k, std, group) for i, r0 in enumerate(range(0, m, slab_rows))]
     if len(jobs) == 1:
         parts = [_qmat_slab(*jobs[0])]
     else:
@@ -151,11 +151,11 @@ def qmat(seed: int, tensor_id: int, m: int, k: int, std: float = 0.02) -> Tuple[
     return np.concatenate([p[0] for p in parts], axis=0), np.concatenate([p[1] for p in parts], axis=0)
 
 
-def layer_weights(shape: LayerShape, seed: int, layer: int = 0) -> Dict[str, np.ndarray]:
+def layer_weights(shape: LayerShape, seed: int, layer: int = 0, group: int = GROUP) -> Dict[str, np.ndarray]:
     """Host arrays of one layer: '<mat>.q' uint32, '<mat>.s' uint16, 'norm_attn'/'norm_ffn' uint16."""
     out: Dict[str, np.ndarray] = {}
     for name, (m, k) in shape.matrices().items():
-        q, s = qmat(seed, layer * 16 + _SLOT[name], m, k)
+        q, s = qmat(seed, layer * 16 + _SLOT[name], m, k, group=group)
         out[name + ".q"], out[name + ".s"] = q, s
     for name in ("norm_attn", "norm_ffn"):
         out[name] = normal_f16_bits(seed, layer * 16 + _SLOT[name], (shape.hidden,), std=0.1, mean=1.0)
