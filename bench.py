@@ -30,7 +30,7 @@ sys.path.insert(0, ROOT)
 
 PEAK_HBM_GBS = 8000.0           # MI355X published HBM3E bandwidth
 PEAK_MFMA_TFLOPS = 2500.0       # MI355X published dense fp16 MFMA rate
-STEP_NAMES = ["qkv", "attention", "o_proj", "gate_up", "down", "fused_decode_layer"]
+STEP_NAMES = ["qkv", "attention", "o_proj", "gate_up", "down"]
 
 
 def traffic_from_profile(name):
@@ -134,7 +134,6 @@ def measure_model_7b(np, torch, wl, rx, host_sets, steps=64):
 # ------------------------------------------------------------------------------------------------ configs[1]
 def bench_decode_layer(args, np, torch, wl, rx):
     from paper_2311_02103_amd.runtime import DeviceLayer, f16_bits, to_device
-    rx.check(rx.relax_set_option("fused_decode", 1 if args.path == "fused" else 0))
     args.mode = args.mode or "graph"
     dev = "cuda:0"
     shape, cap, seed, ncalls = wl.LLAMA7B, 4096, 1, 64
@@ -225,9 +224,9 @@ def bench_decode_layer(args, np, torch, wl, rx):
 
     kernel_ms, roofline = {}, None
     if not args.no_kernel_timing:
-        ids = [5] if args.path == "fused" else [0, 1, 2, 3, 4]
+        ids = [0, 1, 2, 3, 4]
         kernel_ms = time_steps(torch, rx, stream, lambda i: calls[i % ncalls](sh), ids, min(steps, 256))
-        if graph is not None and args.path != "fused":
+        if graph is not None:
             # The event pair around one eager launch also sees the gap before it.  Inside the captured schedule the
             # kernels run back to back, so the duration of the gate/up launch there is what one more launch of it per
             # call adds: the same schedule captured with that (idempotent) launch doubled, both timed with HIP events
@@ -260,13 +259,7 @@ def bench_decode_layer(args, np, torch, wl, rx):
             kernel_ms["step_in_graph_events"] = base
     m, k = shape.matrices()["wgu"]
     gu_bytes = m * (k // 2) + m * (k // 32) * 2 + shape.hidden * 4 + shape.hidden * 2 + shape.ffn * 2
-    if args.path == "fused" and "fused_decode_layer" in kernel_ms:
-        ms = kernel_ms["fused_decode_layer"]
-        ach = layer_bytes / (ms * 1e-3) / 1e9
-        roofline = {"bound": "hbm", "kernel": "decode_layer_kernel (whole layer in one launch)", "achieved": round(ach, 1),
-                    "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(ach / PEAK_HBM_GBS, 4), "traffic": None,
-                    "algorithmic_bytes_per_launch": int(layer_bytes), "avg_launch_ms": round(ms, 5)}
-    elif "gate_up" in kernel_ms:
+    if "gate_up" in kernel_ms:
         ach = gu_bytes / (kernel_ms["gate_up"] * 1e-3) / 1e9
         roofline = {"bound": "hbm", "kernel": "gemv_q4_reg_kernel<X_F32_NORM, EPI_SWIGLU, 2> (gate/up matvec, m=22016, k=4096: "
                                                 "RMSNorm prologue, SwiGLU epilogue)",
@@ -327,7 +320,7 @@ def bench_decode_layer(args, np, torch, wl, rx):
          {"workload": "configs[1]: one Llama-2-7B-shaped int4-g32 decoder layer, decode only, batch 1, n=1, L~U{1..4096} over 64 "
                       "seeded calls; 1 step = 1 token through 1 layer (a 32-layer model does 32 such steps per token); %d rotating "
                       "weight sets" % args.sets,
-          "mode": args.mode, "timed_passes": passes, "path": args.path, "mean_L": round(mean_L, 1), "build_id": rx.relax_build_id(), "setup_s": round(setup_s, 1)},
+          "mode": args.mode, "timed_passes": passes, "mean_L": round(mean_L, 1), "build_id": rx.relax_build_id(), "setup_s": round(setup_s, 1)},
          roofline, cpu,
          {"layer_hbm": {"algorithmic_bytes_per_step": int(layer_bytes), "achieved_GBps": round(layer_gbs, 1),
                         "frac_of_peak": round(layer_gbs / PEAK_HBM_GBS, 4)},
@@ -844,8 +837,6 @@ def main():
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="before the workload, copy a 512 MiB buffer four times with a plain device copy kernel: a dispatch of known "
                          "traffic (512 MiB read, 512 MiB written) that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
-    ap.add_argument("--path", choices=["fused", "stepwise"], default="stepwise",
-                    help="decode_layer: stepwise = one kernel per step (default); fused = the experimental single persistent kernel")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus %d is not supported" % args.gpus, file=sys.stderr)

@@ -34,13 +34,14 @@
  * enqueued on `stream` (a hipStream_t passed as void*; NULL = default stream)
  * and is asynchronous; the return value reports validation / launch errors.
  *
- * Storage format of a quantised matrix W[m,k] (k % 8 == 0):
+ * Storage format of a quantised matrix W[m,k] (k % 8 == 0) with quantisation group G
+ * (32 unless the descriptor says 64 or 128):
  *   q : uint32 [m, k/8]        element c of row r is nibble c%8 (bits
  *                              4*(c%8)..+3) of word q[r*(k/8) + c/8];
  *                              code u in 0..15 stands for the integer u-8
- *   s : fp16   [m, ceil(k/32)] one scale per 32 consecutive c (last group
- *                              short when k % 32 != 0)
- *   W[r,c] = (u - 8) * s[r, c/32]
+ *   s : fp16   [m, ceil(k/G)]  one scale per G consecutive c (last group
+ *                              short when k % G != 0)
+ *   W[r,c] = (u - 8) * s[r, c/G]
  */
 #ifndef RELAX_MI355_H
 #define RELAX_MI355_H
@@ -58,8 +59,8 @@ enum {
     RELAX_ERR_NULL        = -1,   /* a required pointer is NULL                          */
     RELAX_ERR_SHAPE       = -2,   /* n<1, k%8!=0, sum(q_lens)!=n, L_b<q_len_b, h%g!=0... */
     RELAX_ERR_CAPACITY    = -3,   /* L_b > kv_capacity, slot out of range                */
-    RELAX_ERR_WORKSPACE   = -4,   /* ws_bytes below relax_workspace_bytes(...)           */
-    RELAX_ERR_UNSUPPORTED = -5,   /* head_dim not in {64,128}, group != 32, k too large  */
+    RELAX_ERR_WORKSPACE   = -4,   /* ws_bytes below relax_workspace_bytes(...), ws not 256-byte aligned */
+    RELAX_ERR_UNSUPPORTED = -5,   /* head_dim not in {64,128}, group not in {32,64,128}, k too large */
     RELAX_ERR_HIP         = -6    /* the HIP runtime reported a launch error             */
 };
 
@@ -72,7 +73,7 @@ typedef struct {
     int32_t n_kv_heads;           /* g  KV heads, h % g == 0                             */
     int32_t head_dim;             /* d  in {64, 128}                                     */
     int32_t ffn;                  /* F                                                   */
-    int32_t group;                /* quantisation group, must be 32                      */
+    int32_t group;                /* quantisation group of the four matrices: 32, 64 or 128 */
     float   rms_eps;
     float   rope_base;
     int32_t kv_capacity;          /* L_cap: positions per cache slot                     */
@@ -82,8 +83,12 @@ typedef struct {
 /* A quantised matrix in the storage format described at the top.                        */
 typedef struct {
     const uint32_t *q;            /* [m, k/8]                                            */
-    const uint16_t *s;            /* [m, ceil(k/32)] fp16                                */
+    const uint16_t *s;            /* [m, ceil(k/group)] fp16                             */
     int32_t m, k;
+    int32_t group;                /* columns per scale: 32, 64 or 128 (0 reads as 32; the 4-bit deployments of
+                                     Sec. 5.3 come in several group sizes).  Inside a layer every matrix must carry
+                                     the group of relax_layer_dims.  Other values: RELAX_ERR_UNSUPPORTED.  The 3-bit
+                                     calls ignore the field (their group is 32).                                 */
 } relax_qmat;
 
 typedef struct {
@@ -105,7 +110,10 @@ typedef struct {
 
 /* The ragged batch of one call.  Rows of a sequence are contiguous and in order; row i
  * of sequence b sits at position kv_lens[b] - q_lens[b] + i.  A prefill of one sequence
- * is (B=1, {n}, {L}); a batched decode step is (B=n, {1,...}, {L_b}).                   */
+ * is (B=1, {n}, {L}); a batched decode step is (B=n, {1,...}, {L_b}).  Up to 16 sequences ride in kernel arguments;
+ * a longer descriptor without device_table is written to a table at the front of the workspace by small kernels on
+ * the call's stream (32 sequences per launch, carried in their arguments): the host arrays are not needed after the
+ * call returns, the host never waits, and the call can be captured in a graph.                                  */
 typedef struct {
     int32_t B;
     const int32_t *q_lens;        /* host [B], each >= 1, sum == n                       */
@@ -161,29 +169,14 @@ relax_status relax_workspace_plan_rule(const relax_layer_dims *dims, int32_t n, 
                                        relax_plan_entry *entries, int32_t capacity, int32_t *count, size_t *planned_bytes,
                                        size_t *unplanned_bytes);
 
-/* The front of the workspace holds the state of the persistent fused decode kernel: an epoch counter and
- * the exchange buffers whose 8-byte words carry {value, epoch}.  It must be zeroed once before the first
- * call that uses the workspace -- relax_workspace_init does that (one small kernel on `stream`) -- and is
- * then maintained by the calls themselves (every call bumps the epoch).  Call it again after
- * relax_workspace_error reported a failure.
- * relax_workspace_error copies the sticky failure flag of the fused kernel to the host (synchronous): it
- * is set when a bounded wait for another workgroup's data ran out (the kernel then finishes without
- * hanging and its output is invalid), which means the GPU could not keep one workgroup per CU resident
- * -- e.g. another kernel was occupying CUs.                                                          */
+/* The first 256 bytes of a layer or model workspace are a line of flags that kernels raise for conditions the host
+ * cannot check because they are device data: bit 1 of word 0 = relax_model_step met a token id outside [0, vocab) and
+ * read it as id 0.  relax_workspace_init clears the line (one small kernel on `stream`); a workspace whose flags are
+ * never read needs no initialisation.  relax_workspace_error copies word 0 to the host (synchronous).
+ * Every workspace pointer passed to this library must be 256-byte aligned (RELAX_ERR_WORKSPACE otherwise): the
+ * intermediates inside it are read with 16-byte accesses and as MFMA operand tiles.                               */
 relax_status relax_workspace_init(const relax_layer_dims *dims, void *ws, size_t ws_bytes, relax_stream stream);
 relax_status relax_workspace_error(const relax_layer_dims *dims, const void *ws, int32_t *flag_host);
-
-/* Tuning / test switch.  "fused_decode" (default 0): when 1, a call with n == 1 and B == 1 whose matrices
- * allow it (k % 32 == 0, 16-byte aligned, everything fits LDS) runs as ONE persistent kernel whose steps are
- * chained by published {value, epoch} words instead of kernel boundaries; 0 uses the step-by-step kernels
- * that serve every shape (the fused kernel is correct but currently slower: each step transition costs a
- * memory round trip under full HBM load).
- * "fuse_finish" (default 1): in the few-row path (2 <= n <= 128: batched decode, short prefills) the finishing
- * pass of a split-K matmul also does the light step that follows it (rotary embedding + KV append after QKV,
- * the RMSNorm after the output projection, and in relax_model_step the first RMSNorm of the next layer after
- * the down projection: Sec. 4.2 operator fusion); 0 runs them as launches of their own.  Results are identical
- * bit for bit either way.  Unknown name: RELAX_ERR_UNSUPPORTED.                                          */
-relax_status relax_set_option(const char *name, int32_t value);
 
 /* Bytes of the rotary table for these dims, and the call that fills it on the device
  * (angles, cos and sin evaluated in fp64, stored as fp32).  Pairing is half-split:
@@ -209,7 +202,7 @@ relax_status relax_dequant_matmul(const uint16_t *x, const relax_qmat *w, uint16
  * matrix-vector kernel (the one the LM head uses) for a few rows, the tiled MFMA GEMM without its decode
  * step (k % 128 == 0, m % 4 == 0) from the row count on at which its estimated time falls below that of the
  * passes -- 24 rows on a 4096 x 4096 matrix, 8 on 22016 x 4096 (measured: bench.py --workload half_sweep).
- * relax_set_option("half_matmul_gemm_rows", r) with r > 0 fixes the crossover at r rows instead (0, the
+ * the test switch "half_matmul_gemm_rows" (relax_mi355_bench.h) with r > 0 fixes the crossover at r rows instead (0, the
  * default: by estimate).  Device pointers, x and w 16-byte aligned.  Errors: NULL, SHAPE (n<1, m<1, k<8,
  * k%8, alignment), UNSUPPORTED (k > 73728).                                                                */
 relax_status relax_half_matmul(const uint16_t *x, const uint16_t *w, uint16_t *out, int32_t n, int32_t m,
@@ -279,8 +272,8 @@ typedef struct {
 /* Bytes of workspace for relax_model_step over every call with n <= n_max rows,
  * B <= B_max sequences, kv_lens <= L_max: the layer workspace (shared by all layers,
  * which run one after another), two [n_max, hidden] fp16 activation buffers, the
- * normalised last rows and [B_max, vocab] fp16 logits.  The front of it is the same
- * sync area as in relax_workspace_bytes: call relax_workspace_init on it once.
+ * normalised last rows and [B_max, vocab] fp16 logits.  Its first 256 bytes are the flag
+ * line described at relax_workspace_init (clear it once if the flags are read).
  * Returns 0 for invalid arguments.                                                      */
 size_t relax_model_workspace_bytes(const relax_model *model, int32_t n_max, int32_t L_max, int32_t B_max);
 
@@ -297,19 +290,6 @@ size_t relax_model_workspace_bytes(const relax_model *model, int32_t n_max, int3
 relax_status relax_model_step(const relax_model *model, const int32_t *ids, const relax_kv_cache *caches,
                               const relax_seqs *seqs, uint16_t *logits, int32_t *next_ids, int32_t n,
                               void *ws, size_t ws_bytes, relax_stream stream);
-
-/* Measurement aids for the roofline figures: what the device at hand reaches on a plain
- * streaming read and on a bare loop of fp16 matrix-core instructions (the published
- * peaks, 8 TB/s and 2.5 PFLOP/s, are upper bounds of these).  Time them with events.
- * relax_probe_stream_read: every byte of buf (16-byte aligned, bytes >= 16) is loaded
- * once with 16-byte loads; sink: one device word.
- * relax_probe_mfma: one workgroup of four wavefronts per CU, each issuing 16 independent
- * 32x32x16 fp16 MFMAs per iteration on register operands (random_data != 0: operands
- * drawn from a hash, which costs clock under the power limit; 0: near-constant
- * operands); sink: device fp32 [CUs * 256]; *flops receives the operation count of the
- * launch.                                                                               */
-relax_status relax_probe_stream_read(const void *buf, size_t bytes, uint32_t *sink, relax_stream stream);
-relax_status relax_probe_mfma(float *sink, int32_t iters, int32_t random_data, int64_t *flops, relax_stream stream);
 
 /* Test exports for the bit-exactness requirement on decoding and indexing: the device
  * decode of (word, nibble, scale group) written out densely, one element per thread.
@@ -331,28 +311,6 @@ relax_status relax_dequantize(const relax_qmat *w, float *out, relax_stream stre
  * nothing is owned.  NULL pointers: RELAX_ERR_NULL; bad sizes or alignment: RELAX_ERR_SHAPE. */
 relax_status relax_unpack_q3(const relax_qmat *w, int8_t *out, relax_stream stream);
 relax_status relax_dequant_matmul_q3(const uint16_t *x, const relax_qmat *w, uint16_t *out, int32_t n, relax_stream stream);
-
-/* Measurement aid: the next relax_decoder_layer call on this host thread records `start`
- * before and `stop` after the launch of one of its steps (0 QKV matvec/GEMM, 1 attention,
- * 2 output projection, 3 gate/up, 4 down projection, 5 the fused single-launch decode
- * layer) on the call's stream; the setting is
- * consumed by that one call.  start/stop are hipEvent_t handles owned by the caller;
- * step < 0 or NULL events clear the setting.  Lets a benchmark time one kernel of the
- * fused layer with HIP events on the stream the kernel really runs on.                  */
-void relax_profile_step_events(void *start, void *stop, int32_t step);
-
-/* Measurement aid: when set to a device buffer of 16 uint64 per CU, every workgroup of the fused decode kernel
- * stamps the 100 MHz wall clock into its 16 slots at each step boundary (kernel start, then the end of: staging A, step A, attention items, merge,
- * staging C, step C, staging D, step D, staging E, step E).  NULL switches it off (default).                                                          */
-void relax_profile_trace_buffer(void *dev_u64x16);
-
-/* Measurement aid: while q_alt / s_alt (device pointers to another packed matrix and its scales, of the shape of
- * the layer's gate/up matrix) are set, every relax_decoder_layer call with n == 1 launches its gate/up matvec
- * once more, on those weights, ahead of the real launch (whose result then overwrites it).  Inside a captured
- * schedule the kernels run back to back, so the duration of that launch there is the difference between the
- * schedule timed with and without the extra launch -- on weights that are cold like the real ones.  NULL, NULL
- * switches it off (default).  The caller owns the memory and keeps it alive while set.                         */
-void relax_profile_alt_gate_up(const void *q_alt, const void *s_alt);
 
 /* Build identity of the loaded binary (one binary serves every shape).                  */
 const char *relax_build_id(void);

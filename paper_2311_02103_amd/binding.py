@@ -1,7 +1,7 @@
 """ctypes binding of librelax_mi355.so: argument marshalling only.
 
 Every function has the name and argument order of its C declaration in
-include/relax_mi355.h and returns the C status code.  Tensors are torch CUDA
+include/relax_mi355.h (measurement and test aids: include/relax_mi355_bench.h) and returns the C status code.  Tensors are torch CUDA
 tensors (PyTorch is used for device memory and streams, nothing else) or raw
 integer device addresses; fp16 buffers may be torch.float16 or torch.uint16/int16.
 There is no fallback: if the HIP library is missing, loading raises.
@@ -39,7 +39,7 @@ class LayerDims(C.Structure):
 
 
 class QMatC(C.Structure):
-    _fields_ = [("q", C.c_void_p), ("s", C.c_void_p), ("m", C.c_int32), ("k", C.c_int32)]
+    _fields_ = [("q", C.c_void_p), ("s", C.c_void_p), ("m", C.c_int32), ("k", C.c_int32), ("group", C.c_int32)]
 
 
 class LayerWeightsC(C.Structure):
@@ -71,7 +71,6 @@ _lib = None
 _SIGNATURES = {
     "relax_build_id": (C.c_char_p, []),
     "relax_set_option": (C.c_int32, [C.c_char_p, C.c_int32]),
-    "relax_profile_trace_buffer": (None, [C.c_void_p]),
     "relax_profile_alt_gate_up": (None, [C.c_void_p, C.c_void_p]),
     "relax_workspace_init": (C.c_int32, [C.POINTER(LayerDims), C.c_void_p, C.c_size_t, C.c_void_p]),
     "relax_workspace_error": (C.c_int32, [C.POINTER(LayerDims), C.c_void_p, C.POINTER(C.c_int32)]),
@@ -158,14 +157,15 @@ def _ref(obj):
 
 @dataclass
 class QMat:
-    """A quantised matrix on the device: q int32/uint32 [m,k/8], s fp16 [m,ceil(k/32)]."""
+    """A quantised matrix on the device: q int32/uint32 [m,k/8], s fp16 [m,ceil(k/group)]."""
     q: Ptr
     s: Ptr
     m: int
     k: int
+    group: int = 32
 
     def c(self) -> QMatC:
-        return QMatC(_ptr(self.q), _ptr(self.s), self.m, self.k)
+        return QMatC(_ptr(self.q), _ptr(self.s), self.m, self.k, self.group)
 
 
 @dataclass
@@ -371,14 +371,10 @@ def relax_workspace_init(dims: Optional[LayerDims], ws: Ptr, ws_bytes: int, stre
 
 
 def relax_workspace_error(dims: Optional[LayerDims], ws: Ptr) -> int:
-    """Returns the sticky failure flag of the fused kernel (0 = fine); raises on a call error."""
+    """Returns word 0 of the workspace's flag line (0 = fine; bit 1: a token id was out of range); raises on a call error."""
     flag = C.c_int32(0)
     check(lib().relax_workspace_error(_ref(dims), _ptr(ws), C.byref(flag)), "relax_workspace_error")
     return flag.value
-
-
-def relax_profile_trace_buffer(buf: Ptr) -> None:
-    lib().relax_profile_trace_buffer(_ptr(buf))
 
 
 def relax_profile_alt_gate_up(q_alt: Ptr, s_alt: Ptr) -> None:

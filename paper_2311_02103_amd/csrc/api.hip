@@ -1,9 +1,9 @@
 // C ABI of librelax_mi355.so: argument checks (all on the host, before anything is enqueued),
 // the workspace plan, and the launch sequence of each exported call.  See include/relax_mi355.h
 // for the contract and for the passages of the paper each rule comes from.
+#include <atomic>
 #include <cstring>
 #include <mutex>
-#include <vector>
 
 #include "relax_common.h"
 
@@ -94,7 +94,7 @@ void plan_memory(MemPlan &mp, int n_ops, bool equal_only = false)
 // Static plan of the lifted workspace (Sec. 4.3 upper bounds, Sec. 4.4 lifting).  Offsets are a
 // pure function of (dims, n, L, B); a call sized by upper bounds covers every smaller call.
 struct WsPlan {
-    size_t sync, f_q, f_knew, f_vnew, f_attn, f_x1, f_act, f_part, f_end, table, partials, partials_end, qbuf, attn, x1, act, xn, qkv, skinny, total;
+    size_t flags, table, partials, partials_end, qbuf, attn, x1, act, xn, qkv, skinny, total;
     size_t mm_floats;                // fp32 elements of the matmul workspace (at `skinny`)
     MemPlan mem;
 };
@@ -105,19 +105,8 @@ WsPlan plan_ws(const relax_layer_dims &dm, int32_t n, int32_t L, int32_t B, bool
     size_t off = 0;
     const size_t hd = (size_t)dm.n_heads * dm.head_dim;
     const size_t qkvw = (size_t)(dm.n_heads + 2 * dm.n_kv_heads) * dm.head_dim;
-    // the sync area sits at offset 0 and depends on the static dims only: it has to stay zero from call to call
-    p.sync = off;     off += align256(decode_layer_sync_bytes(dm));
-    // exchange buffers of the fused decode kernel (n = 1): 8-byte {value, epoch} words for q, the new k/v row,
-    // attention output, x1, SwiGLU output and the split-L partials; they depend on the static dims only as well
-    const size_t gd = (size_t)dm.n_kv_heads * dm.head_dim;
-    p.f_q = off;      off += align256(8 * hd);
-    p.f_knew = off;   off += align256(8 * gd);
-    p.f_vnew = off;   off += align256(8 * gd);
-    p.f_attn = off;   off += align256(8 * hd);
-    p.f_x1 = off;     off += align256(8 * (size_t)dm.hidden);
-    p.f_act = off;    off += align256(8 * (size_t)dm.ffn);
-    p.f_part = off;   off += align256(8 * (size_t)dm.n_heads * kFusedMaxSplits * (size_t)(dm.head_dim + 2));
-    p.f_end = off;
+    // one line of flags at offset 0 (relax_workspace_init / relax_workspace_error), then the descriptor table of large batches
+    p.flags = off;    off += kWsFlagBytes;
     p.table = off;    off += align256(sizeof(int32_t) * 4 * (size_t)(B > 1 ? B : 1));
 
     // The intermediates of the layer, their sizes and live ranges.  xn is pinned for the whole call (allocated in front of
@@ -165,7 +154,7 @@ relax_status check_dims(const relax_layer_dims *dm)
         return RELAX_ERR_SHAPE;
     if (dm->n_heads % dm->n_kv_heads != 0 || dm->head_dim % 2 != 0) return RELAX_ERR_SHAPE;
     if (dm->head_dim != 64 && dm->head_dim != 128) return RELAX_ERR_UNSUPPORTED;
-    if (dm->group != kGroup) return RELAX_ERR_UNSUPPORTED;
+    if (dm->group != 32 && dm->group != 64 && dm->group != 128) return RELAX_ERR_UNSUPPORTED;
     return RELAX_OK;
 }
 
@@ -173,15 +162,15 @@ relax_status check_qmat(const relax_qmat *w)
 {
     if (!w || !w->q || !w->s) return RELAX_ERR_NULL;
     if (w->m < 1 || w->k < 8 || w->k % 8 != 0) return RELAX_ERR_SHAPE;
-    if (w->k > kMaxK) return RELAX_ERR_UNSUPPORTED;
+    if (w->k > kMaxK || gshift_of(w->group) < 0) return RELAX_ERR_UNSUPPORTED;
     return RELAX_OK;
 }
 
 // Validates the ragged descriptor against n and the cache, and builds the kernel-side table.
-// host_table receives the [4][B] image for batches that do not fit the inline arrays.
-relax_status build_seqs(const relax_seqs *sq, const relax_layer_dims &dm, int32_t n, SeqTable &st, int32_t &L_max,
-                        std::vector<int32_t> &host_table)
+// need_table: the batch does not fit the inline arrays and the caller keeps no device table: upload_table has to write one.
+relax_status build_seqs(const relax_seqs *sq, const relax_layer_dims &dm, int32_t n, SeqTable &st, int32_t &L_max, bool &need_table)
 {
+    need_table = false;
     if (!sq || !sq->q_lens || !sq->kv_lens) return RELAX_ERR_NULL;
     if (n < 1 || sq->B < 1) return RELAX_ERR_SHAPE;
     long long total = 0;
@@ -209,35 +198,39 @@ relax_status build_seqs(const relax_seqs *sq, const relax_layer_dims &dm, int32_
         for (int b = 0; b < kInlineSeqs; ++b) st.q_start[b] = st.q_len[b] = st.kv_len[b] = st.slot[b] = 0;
         return RELAX_OK;
     }
-    const bool inl = sq->B <= kInlineSeqs;
-    if (!inl) host_table.assign(4 * (size_t)sq->B, 0);
+    for (int b = 0; b < kInlineSeqs; ++b) st.q_start[b] = st.q_len[b] = st.kv_len[b] = st.slot[b] = 0;
+    if (sq->B > kInlineSeqs) {
+        need_table = true;
+        return RELAX_OK;
+    }
     int32_t start = 0;
     for (int b = 0; b < sq->B; ++b) {
-        const int32_t slot = sq->slots ? sq->slots[b] : b;
-        if (inl) {
-            st.q_start[b] = start, st.q_len[b] = sq->q_lens[b], st.kv_len[b] = sq->kv_lens[b], st.slot[b] = slot;
-        } else {
-            host_table[b] = start;
-            host_table[sq->B + b] = sq->q_lens[b];
-            host_table[2 * (size_t)sq->B + b] = sq->kv_lens[b];
-            host_table[3 * (size_t)sq->B + b] = slot;
-        }
+        st.q_start[b] = start, st.q_len[b] = sq->q_lens[b], st.kv_len[b] = sq->kv_lens[b], st.slot[b] = sq->slots ? sq->slots[b] : b;
         start += sq->q_lens[b];
     }
-    if (inl)
-        for (int b = sq->B; b < kInlineSeqs; ++b) st.q_start[b] = st.q_len[b] = st.kv_len[b] = st.slot[b] = 0;
     return RELAX_OK;
 }
 
-// Large batches: the descriptor goes to the device table at the front of the workspace.  The
-// host image is pageable, so wait for the copy before it goes out of scope.
-relax_status upload_table(SeqTable &st, const std::vector<int32_t> &host_table, void *ws, const WsPlan &pl, hipStream_t stream)
+// Large batches: the descriptor goes to the device table at the front of the workspace, 32 sequences per launch of a small
+// kernel that carries them in its arguments (the extra symbolic arguments of Sec. 3.3): no host buffer has to outlive the
+// call, nothing is copied from pageable memory, the host never waits, and the launches can be captured in a graph.
+relax_status upload_table(SeqTable &st, const relax_seqs *sq, bool need_table, void *ws, const WsPlan &pl, hipStream_t stream)
 {
-    if (host_table.empty()) return RELAX_OK;
+    if (!need_table) return RELAX_OK;
     int32_t *dev = reinterpret_cast<int32_t *>(static_cast<char *>(ws) + pl.table);
-    if (hipMemcpyAsync(dev, host_table.data(), host_table.size() * sizeof(int32_t), hipMemcpyHostToDevice, stream) != hipSuccess)
-        return RELAX_ERR_HIP;
-    if (hipStreamSynchronize(stream) != hipSuccess) return RELAX_ERR_HIP;
+    TableChunk c = {};
+    c.B = sq->B;
+    int32_t start = 0;
+    for (int first = 0; first < sq->B; first += kTableChunk) {
+        c.first = first;
+        c.count = sq->B - first < kTableChunk ? sq->B - first : kTableChunk;
+        for (int j = 0; j < c.count; ++j) {
+            const int b = first + j;
+            c.q_start[j] = start, c.q_len[j] = sq->q_lens[b], c.kv_len[j] = sq->kv_lens[b], c.slot[j] = sq->slots ? sq->slots[b] : b;
+            start += sq->q_lens[b];
+        }
+        if (launch_table_write(dev, c, stream) != hipSuccess) return RELAX_ERR_HIP;
+    }
     st.dev = dev;
     return RELAX_OK;
 }
@@ -268,13 +261,13 @@ struct StepTimer {
     void after(int s) const { if (s == step && stop) (void)hipEventRecord(stop, stream); }
 };
 
-// Tuning / test switches (relax_set_option).
-int g_opt_fused_decode = 0;
-int g_opt_fuse_finish = 1;                   // few-row path: light steps folded into the finishing pass of the split-K matmuls
-int g_opt_half_gemm_rows = 0;                // relax_half_matmul: rows from which the tiled GEMM replaces the matvec passes; 0: by estimate
-const uint32_t *g_prof_alt_q = nullptr;      // relax_profile_alt_gate_up: another matrix of the gate/up shape
-const uint16_t *g_prof_alt_s = nullptr;
-unsigned long long *g_trace = nullptr;      // relax_profile_trace_buffer
+// Test / measurement switches (relax_set_option, relax_profile_alt_gate_up; declared in relax_mi355_bench.h).  Process-wide by
+// design -- they exist for A/B tests of one process -- and atomic, so setting one while another thread is inside a call is
+// defined: that call sees the old or the new value.  Neither changes a result.
+std::atomic<int> g_opt_fuse_finish{1};       // few-row path: light steps folded into the finishing pass of the split-K matmuls
+std::atomic<int> g_opt_half_gemm_rows{0};    // relax_half_matmul: rows from which the tiled GEMM replaces the matvec passes; 0: by estimate
+std::atomic<const uint32_t *> g_prof_alt_q{nullptr};      // relax_profile_alt_gate_up: another matrix of the gate/up shape
+std::atomic<const uint16_t *> g_prof_alt_s{nullptr};
 
 // CU count of the current device (the fused kernel launches exactly one workgroup per CU).
 int device_cus()
@@ -300,8 +293,9 @@ int device_cus()
 hipError_t half_matmul_enqueue(const uint16_t *x, const uint16_t *w, uint16_t *out, int n, int m, int k, hipStream_t st_)
 {
     bool use_gemm;
-    if (g_opt_half_gemm_rows > 0) {
-        use_gemm = n >= g_opt_half_gemm_rows;
+    const int gemm_rows = g_opt_half_gemm_rows.load();
+    if (gemm_rows > 0) {
+        use_gemm = n >= gemm_rows;
     } else {
         const double pass_us = (double)m * k * 2.0 / 5.5e6;
         const int per = lm_head_rows_per_pass(k);                 // rows of x the matvec kernel holds in LDS
@@ -350,28 +344,22 @@ relax_status static_scratch(void **out)
 
 extern "C" {
 
-void relax_profile_trace_buffer(void *dev_u64x16) { g_trace = static_cast<unsigned long long *>(dev_u64x16); }
-
 void relax_profile_alt_gate_up(const void *q_alt, const void *s_alt)
 {
-    g_prof_alt_q = static_cast<const uint32_t *>(q_alt);
-    g_prof_alt_s = static_cast<const uint16_t *>(s_alt);
+    g_prof_alt_q.store(static_cast<const uint32_t *>(q_alt));
+    g_prof_alt_s.store(static_cast<const uint16_t *>(s_alt));
 }
 
 relax_status relax_set_option(const char *name, int32_t value)
 {
     if (!name) return RELAX_ERR_NULL;
-    if (std::strcmp(name, "fused_decode") == 0) {
-        g_opt_fused_decode = value;
-        return RELAX_OK;
-    }
     if (std::strcmp(name, "fuse_finish") == 0) {
-        g_opt_fuse_finish = value;
+        g_opt_fuse_finish.store(value);
         return RELAX_OK;
     }
     if (std::strcmp(name, "half_matmul_gemm_rows") == 0) {
         if (value < 0) return RELAX_ERR_SHAPE;
-        g_opt_half_gemm_rows = value;
+        g_opt_half_gemm_rows.store(value);
         return RELAX_OK;
     }
     return RELAX_ERR_UNSUPPORTED;
@@ -382,9 +370,9 @@ relax_status relax_workspace_init(const relax_layer_dims *dims, void *ws, size_t
     relax_status rc = check_dims(dims);
     if (rc != RELAX_OK) return rc;
     if (!ws) return RELAX_ERR_NULL;
-    const size_t span = plan_ws(*dims, 1, 1, 1).f_end;        // sync area + exchange buffers
-    if (ws_bytes < span) return RELAX_ERR_WORKSPACE;
-    return hip_status(launch_sync_clear(ws, span, static_cast<hipStream_t>(stream)));
+    if (ws_bytes < kWsFlagBytes) return RELAX_ERR_WORKSPACE;
+    if ((reinterpret_cast<uintptr_t>(ws) & 255) != 0) return RELAX_ERR_WORKSPACE;
+    return hip_status(launch_ws_clear(ws, kWsFlagBytes, static_cast<hipStream_t>(stream)));
 }
 
 relax_status relax_workspace_error(const relax_layer_dims *dims, const void *ws, int32_t *flag_host)
@@ -393,7 +381,7 @@ relax_status relax_workspace_error(const relax_layer_dims *dims, const void *ws,
     if (rc != RELAX_OK) return rc;
     if (!ws || !flag_host) return RELAX_ERR_NULL;
     uint32_t v = 0;
-    if (hipMemcpy(&v, static_cast<const char *>(ws) + decode_layer_error_offset(), sizeof(v), hipMemcpyDeviceToHost) != hipSuccess)
+    if (hipMemcpy(&v, ws, sizeof(v), hipMemcpyDeviceToHost) != hipSuccess)
         return RELAX_ERR_HIP;
     *flag_host = (int32_t)v;
     return RELAX_OK;
@@ -506,8 +494,7 @@ relax_status relax_dequant_matmul(const uint16_t *x, const relax_qmat *w, uint16
         return hip_status(launch_gemm_mfma(x, *w, n, EPI_F16, out, nullptr, nullptr, static_cast<hipStream_t>(stream), static_cast<float *>(ws),
                                            ws ? ws_bytes / sizeof(float) : 0));
     GemvArgs a = {};
-    a.x = x, a.q = w->q, a.s = w->s, a.m = w->m, a.k = w->k, a.n = n, a.out_f16 = out;
-    a.trace = g_trace;
+    a.x = x, a.q = w->q, a.s = w->s, a.m = w->m, a.k = w->k, a.n = n, a.out_f16 = out, a.gshift = gshift_of(w->group);
     return hip_status(launch_gemv(a, X_F16, EPI_F16, static_cast<hipStream_t>(stream)));
 }
 
@@ -519,7 +506,7 @@ relax_status relax_rmsnorm_rope(const uint16_t *x, const uint16_t *w, uint16_t *
     if (!x && !qkv) return RELAX_ERR_NULL;
     if (n < 1) return RELAX_ERR_SHAPE;
     SeqTable st = {};
-    std::vector<int32_t> host_table;
+    bool need_table = false;
     if (x) {
         if (!w || !y) return RELAX_ERR_NULL;
         if (H < 1) return RELAX_ERR_SHAPE;
@@ -529,9 +516,9 @@ relax_status relax_rmsnorm_rope(const uint16_t *x, const uint16_t *w, uint16_t *
         if (rc != RELAX_OK) return rc;
         if (!cache || !cache->k || !cache->v || !cache->rope) return RELAX_ERR_NULL;
         int32_t L_max = 0;
-        rc = build_seqs(seqs, *dims, n, st, L_max, host_table);
+        rc = build_seqs(seqs, *dims, n, st, L_max, need_table);
         if (rc != RELAX_OK) return rc;
-        if (!host_table.empty()) return RELAX_ERR_UNSUPPORTED;   // this call takes no workspace: B <= 16 only
+        if (need_table) return RELAX_ERR_UNSUPPORTED;            // this call takes no workspace: B <= 16, or a device table
     }
     if (x) {
         relax_status rc = hip_status(launch_rmsnorm(x, w, y, n, H, eps, st_));
@@ -549,13 +536,13 @@ relax_status relax_attention(const uint16_t *q, const relax_kv_cache *cache, con
     if (rc != RELAX_OK) return rc;
     if (!q || !out || !cache || !cache->k || !cache->v || !ws) return RELAX_ERR_NULL;
     SeqTable st = {};
-    std::vector<int32_t> host_table;
+    bool need_table = false;
     int32_t L_max = 0;
-    rc = build_seqs(seqs, *dims, n, st, L_max, host_table);
+    rc = build_seqs(seqs, *dims, n, st, L_max, need_table);
     if (rc != RELAX_OK) return rc;
     const WsPlan pl = plan_ws(*dims, n, L_max, seqs->B);
-    if (ws_bytes < pl.partials_end) return RELAX_ERR_WORKSPACE;   // table + partials
-    rc = upload_table(st, host_table, ws, pl, st_);
+    if (ws_bytes < pl.partials_end || (reinterpret_cast<uintptr_t>(ws) & 255) != 0) return RELAX_ERR_WORKSPACE;   // table + partials
+    rc = upload_table(st, seqs, need_table, ws, pl, st_);
     if (rc != RELAX_OK) return rc;
     float *partials = reinterpret_cast<float *>(static_cast<char *>(ws) + pl.partials);
     return hip_status(launch_attention(q, dims->n_heads * dims->head_dim, *cache, *dims, st, L_max, out, partials, st_));
@@ -571,10 +558,10 @@ relax_status relax_attention_static(const uint16_t *q, const relax_kv_cache *cac
     if (rc != RELAX_OK) return rc;
     if (!q || !out || !cache || !cache->k || !cache->v) return RELAX_ERR_NULL;
     SeqTable st = {};
-    std::vector<int32_t> host_table;                             // stays empty (no heap use) unless B > kInlineSeqs, which is refused below
+    bool need_table = false;
     int32_t L_max = 0;
     if (seqs && !seqs->device_table && seqs->B > kInlineSeqs) return RELAX_ERR_UNSUPPORTED;   // the copy of a long descriptor needs a workspace
-    rc = build_seqs(seqs, *dims, n, st, L_max, host_table);
+    rc = build_seqs(seqs, *dims, n, st, L_max, need_table);
     if (rc != RELAX_OK) return rc;
     const size_t need = sizeof(float) * attn_partial_floats(*dims, n, L_max);
     if (need > kStaticScratchBytes) return RELAX_ERR_WORKSPACE;
@@ -601,6 +588,8 @@ relax_status check_layer(const relax_layer_dims &dm, const relax_layer_weights *
     if (wt->wqkv.m != qkvw || wt->wqkv.k != dm.hidden || wt->wo.m != dm.hidden || wt->wo.k != hd ||
         wt->wgu.m != 2 * dm.ffn || wt->wgu.k != dm.hidden || wt->wdown.m != dm.hidden || wt->wdown.k != dm.ffn)
         return RELAX_ERR_SHAPE;
+    for (const relax_qmat *mq : mats)
+        if ((kGroup << gshift_of(mq->group)) != dm.group) return RELAX_ERR_SHAPE;   // one quantisation group per layer
     return RELAX_OK;
 }
 
@@ -615,34 +604,6 @@ relax_status layer_enqueue(const relax_layer_dims &dm, const relax_layer_weights
     if (xn_done) *xn_done = false;
     const int32_t hd = dm.n_heads * dm.head_dim, qkvw = (dm.n_heads + 2 * dm.n_kv_heads) * dm.head_dim;
     const StepTimer timer(st_);
-
-    // Runtime dispatch on the symbolic shape (Sec. 5.1): a single decode row takes the persistent fused kernel.
-    if (g_opt_fused_decode && n == 1 && st.B == 1) {
-        const int cus = device_cus();
-        if (decode_layer_eligible(dm, *wt, n, st.B, cus)) {
-            DecodeLayerArgs fa = {};
-            fa.wqkv = {wt->wqkv.q, wt->wqkv.s, wt->wqkv.m, wt->wqkv.k};
-            fa.wo = {wt->wo.q, wt->wo.s, wt->wo.m, wt->wo.k};
-            fa.wgu = {wt->wgu.q, wt->wgu.s, wt->wgu.m, wt->wgu.k};
-            fa.wdown = {wt->wdown.q, wt->wdown.s, wt->wdown.m, wt->wdown.k};
-            fa.norm_attn = wt->norm_attn, fa.norm_ffn = wt->norm_ffn, fa.x = x, fa.out = out;
-            fa.kcache = cache->k, fa.vcache = cache->v, fa.rope = cache->rope;
-            fa.H = dm.hidden, fa.h = dm.n_heads, fa.g = dm.n_kv_heads, fa.d = dm.head_dim, fa.F = dm.ffn, fa.cap = dm.kv_capacity;
-            fa.eps = dm.rms_eps;
-            fa.pos = st.kv_len[0] - 1, fa.slot = st.slot[0];
-            fa.sync = reinterpret_cast<uint32_t *>(base + pl.sync);
-            typedef unsigned long long u64;
-            fa.q_ll = reinterpret_cast<u64 *>(base + pl.f_q), fa.knew_ll = reinterpret_cast<u64 *>(base + pl.f_knew);
-            fa.vnew_ll = reinterpret_cast<u64 *>(base + pl.f_vnew), fa.attn_ll = reinterpret_cast<u64 *>(base + pl.f_attn);
-            fa.x1_ll = reinterpret_cast<u64 *>(base + pl.f_x1), fa.act_ll = reinterpret_cast<u64 *>(base + pl.f_act);
-            fa.part_ll = reinterpret_cast<u64 *>(base + pl.f_part);
-            fa.trace = g_trace;
-            timer.before(5);
-            if (launch_decode_layer(fa, cus, st_) != hipSuccess) return RELAX_ERR_HIP;
-            timer.after(5);
-            return RELAX_OK;
-        }
-    }
 
     float *partials = reinterpret_cast<float *>(base + pl.partials);
 
@@ -674,8 +635,9 @@ relax_status layer_enqueue(const relax_layer_dims &dm, const relax_layer_weights
         float *x1f = reinterpret_cast<float *>(base + pl.x1);
         // few rows: the finishing pass of a split-K matmul also does the light step that follows it (rotary + append, RMSNorm)
         hipError_t fuse_err = hipSuccess;
+        const bool fuse_finish = g_opt_fuse_finish.load() != 0;
         auto fused = [&](const uint16_t *xin, const relax_qmat &wq, int epi, uint16_t *o16, float *o32, const void *resid, const SkinnyFuse &f) {
-            if (!g_opt_fuse_finish || !gemm_skinny_fuse_ok(wq, epi, f)) return false;
+            if (!fuse_finish || !gemm_skinny_fuse_ok(wq, epi, f)) return false;
             if (few_row(wq, xin, epi)) {
                 fuse_err = launch_gemm_skinny(xin, wq, n, epi, o16, o32, resid, skinny_ws, st_, &f);
                 return true;
@@ -729,10 +691,9 @@ relax_status layer_enqueue(const relax_layer_dims &dm, const relax_layer_weights
     // 1. RMSNorm -> QKV matvec -> rotary embedding -> q to workspace, k/v appended to the cache
     GemvArgs a = {};
     a.x = x, a.norm_w = wt->norm_attn, a.eps = dm.rms_eps;
-    a.q = wt->wqkv.q, a.s = wt->wqkv.s, a.m = wt->wqkv.m, a.k = wt->wqkv.k, a.n = n;
+    a.q = wt->wqkv.q, a.s = wt->wqkv.s, a.m = wt->wqkv.m, a.k = wt->wqkv.k, a.n = n, a.gshift = gshift_of(wt->wqkv.group);
     a.out_f16 = qbuf, a.kcache = cache->k, a.vcache = cache->v, a.rope = cache->rope;
     a.h = dm.n_heads, a.g = dm.n_kv_heads, a.d = dm.head_dim, a.kv_capacity = dm.kv_capacity, a.seqs = st;
-    a.trace = g_trace;
     if (n == 1 && st.dev == nullptr) a.pos0 = st.kv_len[0] - st.q_len[0] - st.q_start[0], a.slot0 = st.slot[0];
     else a.pos0 = -1;                                          // rows find their position in the descriptor
     timer.before(0);
@@ -742,8 +703,8 @@ relax_status layer_enqueue(const relax_layer_dims &dm, const relax_layer_weights
     // 2. attention over the cache.  One row, one query head per KV head: the split kernel alone, with few enough
     //    splits for the output projection to fold the merge into its own prologue (one launch less per layer).
     GemvArgs o = {};
-    o.q = wt->wo.q, o.s = wt->wo.s, o.m = wt->wo.m, o.k = wt->wo.k, o.n = n;
-    o.out_f32 = x1, o.resid = x, o.trace = g_trace;
+    o.q = wt->wo.q, o.s = wt->wo.s, o.m = wt->wo.m, o.k = wt->wo.k, o.n = n, o.gshift = gshift_of(wt->wo.group);
+    o.out_f32 = x1, o.resid = x;
     bool folded = false;
     if (n == 1 && attn_mha_split_supported(dm)) {
         int splits = kAttnMergeSplits, chunk = 0, pos = -1;              // device-resident descriptor: every slice launched, plan on the device
@@ -776,12 +737,14 @@ relax_status layer_enqueue(const relax_layer_dims &dm, const relax_layer_weights
     // 4. RMSNorm -> gate/up matvec -> SwiGLU
     GemvArgs f = {};
     f.x = x1, f.norm_w = wt->norm_ffn, f.eps = dm.rms_eps;
-    f.q = wt->wgu.q, f.s = wt->wgu.s, f.m = wt->wgu.m, f.k = wt->wgu.k, f.n = n;
-    f.out_f16 = act, f.trace = g_trace;
+    f.q = wt->wgu.q, f.s = wt->wgu.s, f.m = wt->wgu.m, f.k = wt->wgu.k, f.n = n, f.gshift = gshift_of(wt->wgu.group);
+    f.out_f16 = act;
     timer.before(3);
-    if (g_prof_alt_q && g_prof_alt_s) {                        // measurement aid: one more launch of the same shape on other weights first
+    const uint32_t *alt_q = g_prof_alt_q.load();
+    const uint16_t *alt_s = g_prof_alt_s.load();
+    if (alt_q && alt_s) {                        // measurement aid: one more launch of the same shape on other weights first
         GemvArgs f2 = f;
-        f2.q = g_prof_alt_q, f2.s = g_prof_alt_s;
+        f2.q = alt_q, f2.s = alt_s;
         if (launch_gemv(f2, X_F32_NORM, EPI_SWIGLU, st_) != hipSuccess) return RELAX_ERR_HIP;
     }
     if (launch_gemv(f, X_F32_NORM, EPI_SWIGLU, st_) != hipSuccess) return RELAX_ERR_HIP;
@@ -789,8 +752,8 @@ relax_status layer_enqueue(const relax_layer_dims &dm, const relax_layer_weights
 
     // 5. down projection + residual
     GemvArgs dn = {};
-    dn.x = act, dn.q = wt->wdown.q, dn.s = wt->wdown.s, dn.m = wt->wdown.m, dn.k = wt->wdown.k, dn.n = n;
-    dn.out_f16 = out, dn.resid = x1, dn.trace = g_trace;
+    dn.x = act, dn.q = wt->wdown.q, dn.s = wt->wdown.s, dn.m = wt->wdown.m, dn.k = wt->wdown.k, dn.n = n, dn.gshift = gshift_of(wt->wdown.group);
+    dn.out_f16 = out, dn.resid = x1;
     timer.before(4);
     if (launch_gemv(dn, X_F16, EPI_RESID_F16, st_) != hipSuccess) return RELAX_ERR_HIP;
     timer.after(4);
@@ -813,13 +776,13 @@ relax_status relax_decoder_layer(const relax_layer_dims *dims, const relax_layer
     rc = check_layer(dm, wt);
     if (rc != RELAX_OK) return rc;
     SeqTable st = {};
-    std::vector<int32_t> host_table;
+    bool need_table = false;
     int32_t L_max = 0;
-    rc = build_seqs(seqs, dm, n, st, L_max, host_table);
+    rc = build_seqs(seqs, dm, n, st, L_max, need_table);
     if (rc != RELAX_OK) return rc;
     const WsPlan pl = plan_ws(dm, n, L_max, seqs->B);
-    if (ws_bytes < pl.total) return RELAX_ERR_WORKSPACE;
-    rc = upload_table(st, host_table, ws, pl, st_);
+    if (ws_bytes < pl.total || (reinterpret_cast<uintptr_t>(ws) & 255) != 0) return RELAX_ERR_WORKSPACE;
+    rc = upload_table(st, seqs, need_table, ws, pl, st_);
     if (rc != RELAX_OK) return rc;
     return layer_enqueue(dm, wt, x, cache, st, L_max, out, n, static_cast<char *>(ws), pl, st_);
 }
@@ -873,18 +836,18 @@ relax_status relax_model_step(const relax_model *model, const int32_t *ids, cons
         if (!caches[l].k || !caches[l].v || !caches[l].rope) return RELAX_ERR_NULL;
     }
     SeqTable st = {};
-    std::vector<int32_t> host_table;
+    bool need_table = false;
     int32_t L_max = 0;
-    rc = build_seqs(seqs, dm, n, st, L_max, host_table);
+    rc = build_seqs(seqs, dm, n, st, L_max, need_table);
     if (rc != RELAX_OK) return rc;
     const ModelPlan mp = plan_model(*model, n, L_max, seqs->B);
-    if (ws_bytes < mp.total) return RELAX_ERR_WORKSPACE;
-    rc = upload_table(st, host_table, ws, mp.layer, st_);
+    if (ws_bytes < mp.total || (reinterpret_cast<uintptr_t>(ws) & 255) != 0) return RELAX_ERR_WORKSPACE;
+    rc = upload_table(st, seqs, need_table, ws, mp.layer, st_);
     if (rc != RELAX_OK) return rc;
 
     char *base = static_cast<char *>(ws);
     uint16_t *cur = reinterpret_cast<uint16_t *>(base + mp.xa), *nxt = reinterpret_cast<uint16_t *>(base + mp.xb);
-    uint32_t *err = reinterpret_cast<uint32_t *>(base + decode_layer_error_offset());
+    uint32_t *err = reinterpret_cast<uint32_t *>(base);        // the flag line at the front of the workspace
     if (launch_embed(ids, model->embedding, cur, n, dm.hidden, model->vocab, err, st_) != hipSuccess) return RELAX_ERR_HIP;
     bool xn_ready = false;
     for (int l = 0; l < model->n_layers; ++l) {
@@ -924,6 +887,7 @@ relax_status relax_dequantize(const relax_qmat *w, float *out, relax_stream stre
 {
     if (!w || !w->q || !w->s || !out) return RELAX_ERR_NULL;
     if (w->m < 1 || w->k < 8 || w->k % 8 != 0) return RELAX_ERR_SHAPE;
+    if (gshift_of(w->group) < 0) return RELAX_ERR_UNSUPPORTED;
     return hip_status(launch_dequantize(*w, out, static_cast<hipStream_t>(stream)));
 }
 

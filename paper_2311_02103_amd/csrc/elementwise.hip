@@ -167,7 +167,7 @@ hipError_t launch_rope_append(uint16_t *qkv, const relax_layer_dims &dm, const r
     return hipGetLastError();
 }
 
-// Dense decode exports: element (r,c) <- word r*(k/8)+c/8, nibble c%8, scale group c/32.
+// Dense decode exports: element (r,c) <- word r*(k/8)+c/8, nibble c%8, scale c/group of the row's ceil(k/group) scales.
 __global__ void unpack_kernel(const uint32_t *q, int8_t *out, int m, int k)
 {
     const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -176,13 +176,13 @@ __global__ void unpack_kernel(const uint32_t *q, int8_t *out, int m, int k)
     out[idx] = (int8_t)decode_code(q[(size_t)r * (k >> 3) + (c >> 3)], c & 7);
 }
 
-__global__ void dequantize_kernel(const uint32_t *q, const uint16_t *s, float *out, int m, int k)
+__global__ void dequantize_kernel(const uint32_t *q, const uint16_t *s, float *out, int m, int k, int group)
 {
     const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= (size_t)m * k) return;
     const int r = (int)(idx / k), c = (int)(idx - (size_t)r * k);
-    const int G = (k + kGroup - 1) / kGroup;
-    out[idx] = (float)decode_code(q[(size_t)r * (k >> 3) + (c >> 3)], c & 7) * h2f(s[(size_t)r * G + c / kGroup]);
+    const int G = (k + group - 1) / group;
+    out[idx] = (float)decode_code(q[(size_t)r * (k >> 3) + (c >> 3)], c & 7) * h2f(s[(size_t)r * G + c / group]);
 }
 
 hipError_t launch_unpack(const relax_qmat &w, int8_t *out, hipStream_t stream)
@@ -195,7 +195,41 @@ hipError_t launch_unpack(const relax_qmat &w, int8_t *out, hipStream_t stream)
 hipError_t launch_dequantize(const relax_qmat &w, float *out, hipStream_t stream)
 {
     const size_t total = (size_t)w.m * w.k;
-    hipLaunchKernelGGL(dequantize_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, w.q, w.s, out, w.m, w.k);
+    hipLaunchKernelGGL(dequantize_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, w.q, w.s, out, w.m, w.k,
+                       kGroup << gshift_of(w.group));
+    return hipGetLastError();
+}
+
+namespace {
+
+__global__ void ws_clear_kernel(uint32_t *p, size_t count)
+{
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += (size_t)gridDim.x * blockDim.x) p[i] = 0u;
+}
+
+__global__ void table_write_kernel(int32_t *table, TableChunk c)
+{
+    const int j = threadIdx.x;
+    if (j < c.count) {
+        const int b = c.first + j;
+        table[b] = c.q_start[j];
+        table[c.B + b] = c.q_len[j];
+        table[2 * (size_t)c.B + b] = c.kv_len[j];
+        table[3 * (size_t)c.B + b] = c.slot[j];
+    }
+}
+
+}  // namespace
+
+hipError_t launch_ws_clear(void *base, size_t bytes, hipStream_t stream)
+{
+    hipLaunchKernelGGL(ws_clear_kernel, dim3(1), dim3(64), 0, stream, (uint32_t *)base, bytes / sizeof(uint32_t));
+    return hipGetLastError();
+}
+
+hipError_t launch_table_write(int32_t *table, const TableChunk &chunk, hipStream_t stream)
+{
+    hipLaunchKernelGGL(table_write_kernel, dim3(1), dim3(kTableChunk), 0, stream, table, chunk);
     return hipGetLastError();
 }
 

@@ -79,7 +79,8 @@ __device__ __forceinline__ half8_t decode_word(uint32_t w, uint32_t s2)
 struct GemmArgs {
     const uint16_t *x;       // [n,k] fp16
     const uint32_t *q;       // [m,k/8]
-    const uint16_t *s;       // [m,k/32]
+    const uint16_t *s;       // [m, k / (32 << gshift)]
+    int32_t gshift;          // 32-column sub-group index >> gshift = scale index (quantisation group 32, 64 or 128)
     const uint16_t *wh;      // FP16W kernels: plain fp16 weights [m,k] instead of q, s
     int32_t n, m, k;
     int32_t epi;
@@ -119,7 +120,7 @@ __global__ __launch_bounds__(kThreadsG) void gemm_q4_mfma_kernel(GemmArgs a)
     const int tile = xcd * (nb >> 3) + min(xcd, nb & 7) + idx;
     const int tile_m = tile % a.tiles_m, tile_n = (tile / a.tiles_m) % a.tiles_n, split = tile / (a.tiles_m * a.tiles_n);
     const int n0 = tile_n * BN;
-    const int kw = a.k >> 3, G = a.k >> 5;
+    const int kw = a.k >> 3;
     const int F = a.m >> 1;
 
     // ---- staging roles ----
@@ -132,7 +133,8 @@ __global__ __launch_bounds__(kThreadsG) void gemm_q4_mfma_kernel(GemmArgs a)
         grow = min(tile_m * BM + arow, a.m - 1);
     }
     const uint32_t *qsrc = FP16W ? nullptr : a.q + (size_t)grow * kw + aword0;
-    const uint16_t *ssrc = FP16W ? nullptr : a.s + (size_t)grow * G + (aword0 >> 2);
+    const uint16_t *ssrc = FP16W ? nullptr : a.s + (size_t)grow * scales_per_row(a.k, a.gshift);
+    const int sub0 = aword0 >> 2;                         // first 32-column sub-group of this thread's words inside a k block
     const uint16_t *hsrc = FP16W ? a.wh + (size_t)grow * a.k + aword0 * 8 : nullptr;
     const uint16_t *xsrc[XP];
 #pragma unroll
@@ -157,8 +159,10 @@ __global__ __launch_bounds__(kThreadsG) void gemm_q4_mfma_kernel(GemmArgs a)
         } else {
 #pragma unroll
             for (int i = 0; i < W / 4; ++i) S.wq[i] = *(const uint4 *)(qsrc + kb * (BK / 8) + i * 4);
-            if (W == 8) S.wsc = *(const uint32_t *)(ssrc + kb * (BK / 32));
-            else S.wsc = ssrc[kb * (BK / 32)];
+            // scale of sub-group g: ssrc[g >> gshift] (neighbouring sub-groups share it when the group is wider than 32)
+            const int g = kb * (BK / 32) + sub0;
+            if (W == 8) S.wsc = (uint32_t)ssrc[g >> a.gshift] | ((uint32_t)ssrc[(g + 1) >> a.gshift] << 16);
+            else S.wsc = ssrc[g >> a.gshift];
         }
 #pragma unroll
         for (int p = 0; p < XP; ++p) S.xr[p] = *(const uint4 *)(xsrc[p] + kb * BK);
@@ -395,8 +399,8 @@ hipError_t launch_tile(const GemmArgs &a_in, hipStream_t stream, int splits)
 // Whether the MFMA path can serve this matrix (k in whole 128-blocks, 16-byte aligned rows, 4-row store granules).
 bool gemm_mfma_eligible(const relax_qmat &w, const void *x, int epi)
 {
-    if (w.k % (2 * BK) != 0) return false;
-    if ((reinterpret_cast<uintptr_t>(w.q) & 15) != 0 || (reinterpret_cast<uintptr_t>(w.s) & 3) != 0) return false;
+    if (w.k % (2 * BK) != 0 || gshift_of(w.group) < 0) return false;
+    if ((reinterpret_cast<uintptr_t>(w.q) & 15) != 0 || (reinterpret_cast<uintptr_t>(w.s) & 1) != 0) return false;
     if ((reinterpret_cast<uintptr_t>(x) & 15) != 0) return false;
     if (epi == EPI_SWIGLU) return w.m % 8 == 0;
     return w.m % 4 == 0;
@@ -493,7 +497,7 @@ hipError_t launch_gemm_mfma(const uint16_t *x, const relax_qmat &w, int n, int e
 {
     GemmArgs a;
     a.wh = nullptr;
-    a.x = x, a.q = w.q, a.s = w.s, a.n = n, a.m = w.m, a.k = w.k, a.epi = epi;
+    a.x = x, a.q = w.q, a.s = w.s, a.gshift = gshift_of(w.group), a.n = n, a.m = w.m, a.k = w.k, a.epi = epi;
     a.out_f16 = out_f16, a.out_f32 = out_f32, a.resid = resid;
     TilePlan p = tile_plan(w.m, w.k, n, epi);
     if (p.splits > 1 && gemm_mfma_splits(w, n, epi, partial, partial_floats) == 1)

@@ -445,6 +445,7 @@ bool gemm_skinny_eligible(const relax_qmat &w, const void *x, int n, int epi)
 {
     if (n < 1 || n > kSkinnyMaxN) return false;
     if (w.k % kRound != 0) return false;
+    if (gshift_of(w.group) != 0) return false;            // its scale tile holds one scale per 32 columns: wider groups take the other two kernels
     if ((reinterpret_cast<uintptr_t>(w.q) & 15) != 0 || (reinterpret_cast<uintptr_t>(w.s) & 15) != 0) return false;
     if ((reinterpret_cast<uintptr_t>(x) & 15) != 0) return false;
     return epi == EPI_SWIGLU ? w.m % 8 == 0 : w.m % 4 == 0;

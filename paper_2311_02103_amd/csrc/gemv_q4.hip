@@ -109,7 +109,7 @@ __global__ __launch_bounds__(512) void gemv_q4_kernel(GemvArgs a)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     __shared__ float red[8];
-    const int k = a.k, G = (k + kGroup - 1) / kGroup, kw = k >> 3;
+    const int k = a.k, G = (k + kGroup - 1) / kGroup, kw = k >> 3, SG = scales_per_row(k, a.gshift);
     const int kpad = FAST ? ((k + 2047) >> 11) << 11 : k;
     uint16_t *xs = (uint16_t *)smem;
     float *corr = (float *)(smem + (size_t)kpad * 2);
@@ -173,7 +173,7 @@ __global__ __launch_bounds__(512) void gemv_q4_kernel(GemvArgs a)
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         wv[r] = *(const uint4 *)(a.q + (size_t)rows[r] * kw + (size_t)gi * 4);
-                        sc[r] = h2f(a.s[(size_t)rows[r] * G + gi]);
+                        sc[r] = h2f(a.s[(size_t)rows[r] * SG + (gi >> a.gshift)]);
                     }
 #pragma unroll
                     for (int r = 0; r < 4; ++r) tot[r] += sc[r] * group_dot(wv[r], xv, cr);
@@ -188,7 +188,7 @@ __global__ __launch_bounds__(512) void gemv_q4_kernel(GemvArgs a)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     const uint32_t word = a.q[(size_t)rows[r] * kw + widx];
-                    const float sc = h2f(a.s[(size_t)rows[r] * G + (widx >> 2)]);
+                    const float sc = h2f(a.s[(size_t)rows[r] * SG + ((widx >> 2) >> a.gshift)]);
 #pragma unroll
                     for (int e = 0; e < 8; ++e) tot[r] += xv[e] * ((float)decode_code(word, e) * sc);
                 }
@@ -285,16 +285,12 @@ __global__ __launch_bounds__(kSThreads) void gemv_q4_stream_kernel(GemvArgs a)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     float *res = corr + ((G + 63) & ~63) + wave * (kSMaxTiles * 4);
     const int i = blockIdx.y;
-    const DLMat M = {a.q, a.s, a.m, a.k};
+    const DLMat M = {a.q, a.s, a.m, a.k, a.gshift};
     const int ntiles = (EPI == EPI_ROPE_KV || EPI == EPI_SWIGLU) ? (a.m >> 2) : ((a.m + 3) >> 2);
     const int nsub = (nchunks + 1) >> 1;
     const int W = gridDim.x * kSWaves, wave_global = blockIdx.x * kSWaves + wave;
     const int mine = wave_global < ntiles ? (ntiles - wave_global + W - 1) / W : 0;
     const int nsu = mine * nsub;
-    auto stamp = [&](int s) {
-        if (a.trace && tid == 0 && blockIdx.y == 0) a.trace[blockIdx.x * 8 + s] = wall_clock64();
-    };
-    stamp(0);
 
     auto target = [&](int su, int *rows, int &chunk0) {
         const bool live = su < nsu;
@@ -341,7 +337,6 @@ __global__ __launch_bounds__(kSThreads) void gemv_q4_stream_kernel(GemvArgs a)
         slot_load(s1, M, rows, chunk0, 0, lane);
     }
 
-    stamp(1);
     // ---- stage the (optionally RMS-normalised) x row in LDS as fp16 in the packet order [x0 x4 x1 x5 x2 x6 x3 x7] ----
     auto put8 = [&](int c8, const float *y) {
         const uint32_t o0 = (uint32_t)f2h(y[0]) | ((uint32_t)f2h(y[4]) << 16), o1 = (uint32_t)f2h(y[1]) | ((uint32_t)f2h(y[5]) << 16);
@@ -397,7 +392,6 @@ __global__ __launch_bounds__(kSThreads) void gemv_q4_stream_kernel(GemvArgs a)
     for (int gi = tid; gi < G; gi += kSThreads) corr[gi] = group_corr(xs, gi);
     wg_barrier();
 
-    stamp(2);
     RowInfo ri = {0, 0, 0};
     if (EPI == EPI_ROPE_KV) ri = row_info(a.seqs, i);
 
@@ -436,21 +430,18 @@ __global__ __launch_bounds__(kSThreads) void gemv_q4_stream_kernel(GemvArgs a)
     }
     trip(s0, su, false);
     trip(s1, su + 1, false);
-    stamp(3);
     if (lane < mine) {
         float v[4];
 #pragma unroll
         for (int r = 0; r < 4; ++r) v[r] = res[lane * 4 + r];
         stream_epilogue<EPI>(a, i, ri, wave_global + lane * W, v);
     }
-    stamp(4);
 }
 
 template <int XMODE, int EPI>
 static hipError_t launch_t(const GemvArgs &a, hipStream_t stream)
 {
-    static const bool use_reg = getenv("RELAX_GEMV_OLD") == nullptr;     // tuning aid: the LDS-resident variants below
-    if (use_reg && gemv_reg_eligible(a)) return launch_gemv_reg(a, XMODE, EPI, stream);
+    if (gemv_reg_eligible(a)) return launch_gemv_reg(a, XMODE, EPI, stream);
     const int k = a.k, G = groups_of(k);
     const bool fast = (k % kGroup == 0) && ((k / 8) % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.q) & 15) == 0) &&
                       ((reinterpret_cast<uintptr_t>(a.x) & 15) == 0) && ((reinterpret_cast<uintptr_t>(a.norm_w) & 15) == 0);
@@ -472,9 +463,7 @@ static hipError_t launch_t(const GemvArgs &a, hipStream_t stream)
             int dev = 0, cus = 0, occ = 0;
             if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) cus = 256;
             if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, kern, kSThreads, 40 * 1024) != hipSuccess || occ < 1) occ = 1;
-            const char *env = getenv("RELAX_GEMV_BPC");            // tuning aid: workgroups per CU
-            const int want = env ? atoi(env) : 1;
-            resident[small_k] = cus * std::max(1, std::min(occ, want));
+            resident[small_k] = cus * std::max(1, std::min(occ, 1));       // one workgroup per CU (two measured slower)
         }
         int sgx = std::max(1, resident[small_k] / std::min(a.n, 8));
         sgx = std::min(sgx, (ntiles + kSWaves - 1) / kSWaves);

@@ -207,21 +207,11 @@ __global__ __launch_bounds__(kRThreads) void gemv_q4_reg_kernel(GemvArgs a)
     __shared__ float res_all[kRWaves][kRMaxUnits * 2 + 4];     // one sum per row of the wavefront (+ the dead rows of a last slot)
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int i = blockIdx.y;
-    const int k = a.k, G = k >> 5, kw = k >> 3;
+    const int k = a.k, G = k >> 5, kw = k >> 3, SG = scales_per_row(k, a.gshift);
     const int U = unit_count_r<EPI>(a);
     const int W = gridDim.x * kRWaves, wg = blockIdx.x * kRWaves + wave;
     const int mine = wg < U ? (U - wg + W - 1) / W : 0;        // <= kRMaxUnits: the launcher sizes the grid for it
     float *res = res_all[wave];
-    // Measurement aid, compiled in only on request: wall-clock stamps of a workgroup.  A store under a condition
-    // between the requests and their waits makes every later wait a wait for all requests in flight.
-    auto stamp = [&](int st) {
-#ifdef RELAX_GEMV_TRACE
-        if (a.trace && tid == 0 && blockIdx.y == 0) a.trace[(EPI * 1024 + blockIdx.x) * 8 + st] = wall_clock64();
-#else
-        (void)st;
-#endif
-    };
-    stamp(0);
 
     // ---- what the epilogue reads, then the x row, then the first slots: requested in the order they are needed ----
     RowInfo ri = {0, 0, 0};
@@ -296,13 +286,13 @@ __global__ __launch_bounds__(kRThreads) void gemv_q4_reg_kernel(GemvArgs a)
             unit_rows_r<EPI>(a, u, rows[0], rows[1]);
             const int row = __builtin_amdgcn_readfirstlane((t & 1) ? rows[1] : rows[0]);     // uniform: row bases in scalar registers
             const uint32_t *qrow = a.q + (size_t)row * kw;
-            const uint16_t *srow = a.s + (size_t)row * G;
+            const uint16_t *srow = a.s + (size_t)row * SG;
 #pragma unroll
             for (int c = 0; c < NG; ++c) {
                 // chunks that can reach past the row (NG = 4, 6 also serve rows one chunk shorter) are clamped
                 const int gi = (c >= kFirstRagged) ? min(c * 64 + lane, G - 1) : c * 64 + lane;
                 s.w[rr * NG + c] = *(const u32x4_t *)(qrow + gi * 4);
-                s.sc[rr * NG + c] = srow[gi];
+                s.sc[rr * NG + c] = srow[gi >> a.gshift];     // 1, 2 or 4 neighbouring lanes read the same scale
             }
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -314,7 +304,6 @@ __global__ __launch_bounds__(kRThreads) void gemv_q4_reg_kernel(GemvArgs a)
     // behind the first slots in program order: its address arithmetic runs while they are in flight
     const float2 pre = epi_fetch<EPI>(a, i, ri, lane < mine ? wg + lane * W : min(wg, U - 1));
     __builtin_amdgcn_sched_barrier(0);
-    stamp(1);
 
     // ---- stage the (optionally RMS-normalised) x row in LDS as fp16, packet order [x0 x4 x1 x5 x2 x6 x3 x7] ----
     float inv = 1.0f;
@@ -409,7 +398,6 @@ __global__ __launch_bounds__(kRThreads) void gemv_q4_reg_kernel(GemvArgs a)
     bool chunk_on[NG];                                             // lanes past the last group of the row contribute nothing
 #pragma unroll
     for (int c = 0; c < NG; ++c) chunk_on[c] = c * 64 + lane < G;
-    stamp(2);
 
     // ---- the stream ------------------------------------------------------------------------------------------
     auto consume = [&](const Slot &s, int j0) {
@@ -477,10 +465,8 @@ __global__ __launch_bounds__(kRThreads) void gemv_q4_reg_kernel(GemvArgs a)
             if (t < left) consume(sl[t], t);
     }
 
-    stamp(3);
     // ---- epilogue: lane jj finishes the wavefront's unit jj ----------------------------------------------------
     if (lane < mine) epi_store<EPI>(a, i, ri, wg + lane * W, res[lane * 2], res[lane * 2 + 1], pre);
-    stamp(4);
 }
 
 template <int XMODE, int EPI, int NG>
@@ -490,8 +476,7 @@ hipError_t launch_ng(const GemvArgs &a, hipStream_t stream)
     if (cus == 0) {
         int dev = 0, v = 0;
         if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v < 1) v = 256;
-        const char *env = getenv("RELAX_GEMV_WGS_PER_CU");         // tuning aid
-        cus = v * std::max(1, env ? atoi(env) : 1);
+        cus = v;                                                   // one workgroup per CU (two per CU measured 1 us per layer slower)
     }
     const int U = (EPI == EPI_SWIGLU || EPI == EPI_ROPE_KV) ? a.m / 2 : (a.m + 1) / 2;
     // one workgroup per CU, shared between the rows of x; never fewer than what keeps a wavefront within kRMaxUnits

@@ -79,13 +79,13 @@ struct Slot {
 // trip requested after it.
 __device__ __forceinline__ void slot_load(Slot &s, const DLMat &M, const int *rows, int chunk0, int mode, int lane)
 {
-    const int G = M.k >> 5, kw = M.k >> 3;
+    const int G = M.k >> 5, kw = M.k >> 3, SG = scales_per_row(M.k, M.gshift);
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
         const int row = mode ? rows[e & 1] : rows[e & 3], c = mode ? (e >> 1) : (e >> 2);    // static indices only
         const int gi = min(((chunk0 + c) << 6) + lane, G - 1);
         s.w[e] = *(const uint4 *)(M.q + (size_t)row * kw + (size_t)gi * 4);
-        s.sc[e] = M.s[(size_t)row * G + gi];
+        s.sc[e] = M.s[(size_t)row * SG + (gi >> M.gshift)];
     }
 }
 

@@ -11,7 +11,8 @@
 namespace relax {
 
 constexpr int kWave = 64;            // CDNA wavefront
-constexpr int kGroup = 32;           // quantisation group along k
+constexpr int kGroup = 32;           // sub-group the kernels walk in: 32 columns = four packed words.  The quantisation group of a matrix
+                                     // is 32, 64 or 128 columns: 1, 2 or 4 neighbouring sub-groups share one scale (gshift = 0, 1, 2)
 constexpr int kMaxK = 28672;         // x row (fp16) + per-group terms must fit 64 KB of LDS
 constexpr int kInlineSeqs = 16;      // ragged descriptors up to this many sequences ride in kernel arguments
 
@@ -90,6 +91,10 @@ __device__ inline uint16_t f2h(float v) { return __half_as_ushort(__float2half_r
 __device__ inline int decode_code(uint32_t word, int e) { return (int)((word >> (4 * e)) & 0xFu) - 8; }
 
 inline int groups_of(int k) { return (k + kGroup - 1) / kGroup; }
+// quantisation group of a matrix descriptor (0 reads as 32) -> shift from sub-group index to scale index; -1: unsupported
+inline int gshift_of(int group) { return (group == 0 || group == 32) ? 0 : group == 64 ? 1 : group == 128 ? 2 : -1; }
+// scales per row: one per (32 << gshift) columns, the last group short when that does not divide k
+__host__ __device__ inline int scales_per_row(int k, int gshift) { return (k + (kGroup << gshift) - 1) / (kGroup << gshift); }
 
 // ---- launchers (defined in the .hip files), all asynchronous on `stream` --------------------------------------
 
@@ -120,6 +125,7 @@ struct GemvArgs {
     const uint32_t *q;
     const uint16_t *s;
     int32_t m, k, n;
+    int32_t gshift;                  // sub-group (32 columns) index >> gshift = scale index of the row (0: group 32, 1: 64, 2: 128)
     // epilogue
     uint16_t *out_f16;               // EPI_F16: [n,m]; EPI_ROPE_KV: q buffer [n,h*d]; EPI_RESID_F16: out [n,m]; EPI_SWIGLU: act [n,F]
     float *out_f32;                  // EPI_RESID_F32: x1 [n,m]
@@ -130,7 +136,6 @@ struct GemvArgs {
     int32_t h, g, d, kv_capacity;
     SeqTable seqs;
     int32_t pos0, slot0;             // position and cache slot of row 0, resolved on the host (what a one-row call needs of seqs)
-    unsigned long long *trace;       // optional measurement aid: [workgroup][8] wall-clock stamps
 };
 
 hipError_t launch_gemv(const GemvArgs &a, int xmode, int epi, hipStream_t stream);
@@ -238,37 +243,25 @@ hipError_t launch_argmax(const uint16_t *logits, int32_t *ids, int B, int V, hip
 hipError_t launch_probe_stream_read(const void *buf, size_t bytes, uint32_t *sink, int n_cus, hipStream_t stream);
 hipError_t launch_probe_mfma(float *sink, int iters, int random_data, int n_cus, hipStream_t stream);
 
-// ---- persistent fused decode layer (decode_layer.hip) -----------------------------------------------------------
+// ---- front of every layer / model workspace --------------------------------------------------------------------
+// One 256-byte line of flags the kernels may raise (word 0 bit 1: a token id outside the vocabulary was read as id 0);
+// relax_workspace_init clears it, relax_workspace_error reads it.
+constexpr size_t kWsFlagBytes = 256;
+hipError_t launch_ws_clear(void *base, size_t bytes, hipStream_t stream);
+// Writes a chunk of the ragged descriptor into the device table [4][B] (batches that do not ride in kernel arguments).
+constexpr int kTableChunk = 32;
+struct TableChunk {
+    int32_t first, count, B;
+    int32_t q_start[kTableChunk], q_len[kTableChunk], kv_len[kTableChunk], slot[kTableChunk];
+};
+hipError_t launch_table_write(int32_t *table, const TableChunk &chunk, hipStream_t stream);
+
+// A quantised matrix as the streaming kernels pass it around
 struct DLMat {
     const uint32_t *q;
     const uint16_t *s;
     int32_t m, k;
+    int32_t gshift;
 };
-
-struct DecodeLayerArgs {
-    DLMat wqkv, wo, wgu, wdown;
-    const uint16_t *norm_attn, *norm_ffn;
-    const uint16_t *x;
-    uint16_t *out;
-    uint16_t *kcache, *vcache;
-    const float *rope;
-    int32_t H, h, g, d, F, cap;
-    float eps;
-    int32_t pos, slot;                 // the single row of the call: its position and cache slot
-    uint32_t *sync;                    // epoch counter, exit counter, error flag
-    // exchange buffers in the workspace: one 8-byte word {fp32 value, epoch tag} per element
-    unsigned long long *q_ll, *knew_ll, *vnew_ll, *part_ll, *attn_ll, *x1_ll, *act_ll;
-    int32_t splits, chunk;             // attention plan (pure function of L and the CU count)
-    int32_t nblocks;
-    int32_t lds_corr, lds_raw, lds_wn, lds_attn, lds_res;
-    unsigned long long *trace;         // optional: [workgroup][16] stamps of the 100 MHz wall clock at step boundaries
-};
-
-constexpr int kFusedMaxSplits = 64;
-size_t decode_layer_sync_bytes(const relax_layer_dims &dm);
-size_t decode_layer_error_offset();
-hipError_t launch_sync_clear(void *base, size_t bytes, hipStream_t stream);
-bool decode_layer_eligible(const relax_layer_dims &dm, const relax_layer_weights &w, int n, int B, int n_cus);
-hipError_t launch_decode_layer(DecodeLayerArgs &a, int n_cus, hipStream_t stream);
 
 }  // namespace relax

@@ -30,13 +30,13 @@ class DeviceLayer:
 
     def __init__(self, host_weights: Dict[str, np.ndarray], *, hidden: int, n_heads: int, n_kv_heads: int, head_dim: int,
                  ffn: int, kv_capacity: int, kv_slots: int = 1, n_max: int = 1, B_max: Optional[int] = None,
-                 rms_eps: float = 1e-5, rope_base: float = 10000.0, device="cuda", share_from: "DeviceLayer" = None):
+                 rms_eps: float = 1e-5, rope_base: float = 10000.0, device="cuda", share_from: "DeviceLayer" = None, group: int = 32):
         self.device = device
-        self.dims = rx.make_dims(hidden, n_heads, n_kv_heads, head_dim, ffn, kv_capacity, kv_slots, rms_eps, rope_base)
+        self.dims = rx.make_dims(hidden, n_heads, n_kv_heads, head_dim, ffn, kv_capacity, kv_slots, rms_eps, rope_base, group)
         mats = {"wqkv": ((n_heads + 2 * n_kv_heads) * head_dim, hidden), "wo": (hidden, n_heads * head_dim),
                 "wgu": (2 * ffn, hidden), "wdown": (hidden, ffn)}
         self.t = {k: to_device(v, device) for k, v in host_weights.items()}
-        self.weights = rx.LayerWeights(*(rx.QMat(self.t[n + ".q"], self.t[n + ".s"], *mats[n]) for n in mats),
+        self.weights = rx.LayerWeights(*(rx.QMat(self.t[n + ".q"], self.t[n + ".s"], *mats[n], group) for n in mats),
                                        self.t["norm_attn"], self.t["norm_ffn"])
         self.n_max, self.B_max = n_max, (B_max if B_max is not None else max(kv_slots, 1))
         if share_from is not None:          # layers of one model share cache geometry, rope table and workspace
@@ -99,9 +99,9 @@ class DeviceModel:
     def __init__(self, layer_weights: Sequence[Dict[str, np.ndarray]], embedding_bits: np.ndarray, norm_final_bits: np.ndarray,
                  lm_head_bits: np.ndarray, *, hidden: int, n_heads: int, n_kv_heads: int, head_dim: int, ffn: int,
                  kv_capacity: int, kv_slots: int = 1, n_max: int = 1, B_max: Optional[int] = None, rms_eps: float = 1e-5,
-                 rope_base: float = 10000.0, device="cuda"):
+                 rope_base: float = 10000.0, device="cuda", group: int = 32):
         self.device = device
-        self.dims = rx.make_dims(hidden, n_heads, n_kv_heads, head_dim, ffn, kv_capacity, kv_slots, rms_eps, rope_base)
+        self.dims = rx.make_dims(hidden, n_heads, n_kv_heads, head_dim, ffn, kv_capacity, kv_slots, rms_eps, rope_base, group)
         self.vocab = int(embedding_bits.shape[0])
         mats = {"wqkv": ((n_heads + 2 * n_kv_heads) * head_dim, hidden), "wo": (hidden, n_heads * head_dim),
                 "wgu": (2 * ffn, hidden), "wdown": (hidden, ffn)}
@@ -110,7 +110,7 @@ class DeviceModel:
         for hw in layer_weights:
             if id(hw) not in uploaded:
                 t = {k: to_device(v, device) for k, v in hw.items()}
-                uploaded[id(hw)] = (t, rx.LayerWeights(*(rx.QMat(t[n + ".q"], t[n + ".s"], *mats[n]) for n in mats),
+                uploaded[id(hw)] = (t, rx.LayerWeights(*(rx.QMat(t[n + ".q"], t[n + ".s"], *mats[n], group) for n in mats),
                                                        t["norm_attn"], t["norm_ffn"]))
             self.layers.append(uploaded[id(hw)][1])
         self._tensors = uploaded

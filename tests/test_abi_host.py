@@ -13,7 +13,8 @@ P = 0x10000   # a non-null fake device address: every call below must fail valid
 
 
 def test_library_exports_every_declared_symbol():
-    header = open(os.path.join(ROOT, "include", "relax_mi355.h")).read()
+    header = "".join(open(os.path.join(ROOT, "include", h)).read() for h in sorted(os.listdir(os.path.join(ROOT, "include"))) if h.endswith(".h"))
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)       # declarations only: comments also name calls
     declared = set(re.findall(r"\b(relax_[a-z0-9_]+)\s*\(", header))
     declared -= {"relax_status", "relax_stream"}
     assert declared == set(rx.EXPORTS), declared ^ set(rx.EXPORTS)
@@ -88,7 +89,8 @@ def test_decoder_layer_checks():
     assert call(d, w, rx.Seqs([3], [3], slots=[-1]), 3) == rx.ERR_CAPACITY
     assert call(dims(n_kv_heads=3), w, ok_seq, 3) == rx.ERR_SHAPE        # h % g
     assert call(dims(head_dim=96), w, ok_seq, 3) == rx.ERR_UNSUPPORTED
-    assert call(dims(group=64), w, ok_seq, 3) == rx.ERR_UNSUPPORTED
+    assert call(dims(group=64), w, ok_seq, 3) == rx.ERR_SHAPE             # matrices of group 32 in a layer of group 64
+    assert call(dims(group=48), w, ok_seq, 3) == rx.ERR_UNSUPPORTED
     assert call(d, weights(d, wo=rx.QMat(P, P, 256, 128)), ok_seq, 3) == rx.ERR_SHAPE    # matrix does not fit dims
     assert call(d, weights(d, wdown=rx.QMat(P, P, 256, 684)), ok_seq, 3) == rx.ERR_SHAPE  # k % 8
     assert call(d, w, rx.Seqs([8], [64]), 8, wsb=ws_bytes - 1) == rx.ERR_WORKSPACE
@@ -112,6 +114,19 @@ def test_attention_and_norm_rope_checks():
     assert rx.relax_unpack_int4(rx.QMat(P, P, 4, 12), P) == rx.ERR_SHAPE
     assert rx.relax_dequantize(rx.QMat(P, None, 4, 16), P) == rx.ERR_NULL
     assert rx.relax_rope_table_init(d, None) == rx.ERR_NULL
+
+
+def test_workspace_pointers_must_be_256_byte_aligned():
+    d = dims()
+    w = weights(d)
+    c = rx.KVCache(P, P, P)
+    s = rx.Seqs([2], [5])
+    big = 1 << 24
+    assert rx.relax_decoder_layer(d, w, P, c, s, P, 2, P + 16, big) == rx.ERR_WORKSPACE
+    assert rx.relax_attention(P, c, s, d, P, 2, P + 128, big) == rx.ERR_WORKSPACE
+    assert rx.relax_workspace_init(d, P + 8, big) == rx.ERR_WORKSPACE
+    m = rx.Model(d, [w], 100, P, P, P)
+    assert rx.relax_model_step(m, P, [c], s, P, P, 2, P + 64, big) == rx.ERR_WORKSPACE
 
 
 def test_static_attention_checks():
@@ -192,3 +207,16 @@ def test_no_product_module_touches_the_oracle():
             if f.endswith((".py", ".hip", ".h", ".cpp")):
                 text = open(os.path.join(dirpath, f)).read()
                 assert "oracle" not in text.lower(), os.path.join(dirpath, f)
+
+
+def test_unsupported_group_is_refused():
+    assert rx.relax_dequant_matmul(P, rx.QMat(P, P, 8, 64, 48), P, 1) == rx.ERR_UNSUPPORTED
+    assert rx.relax_dequantize(rx.QMat(P, P, 8, 64, 16), P) == rx.ERR_UNSUPPORTED
+    assert rx.relax_workspace_bytes(rx.make_dims(256, 4, 4, 64, 688, 64, 1, group=96), 1, 1, 1) == 0
+
+
+def test_layer_rejects_a_matrix_whose_group_differs_from_the_dims():
+    d = rx.make_dims(256, 4, 4, 64, 688, 64, 2, group=64)
+    good = lambda m, k: rx.QMat(P, P, m, k, 64)
+    w = rx.LayerWeights(good(768, 256), good(256, 256), rx.QMat(P, P, 1376, 256, 32), good(256, 688), P, P)
+    assert rx.relax_decoder_layer(d, w, P, rx.KVCache(P, P, P), rx.Seqs([1], [1]), P, 1, P, 1 << 24) == rx.ERR_SHAPE
