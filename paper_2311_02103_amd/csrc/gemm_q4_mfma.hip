@@ -21,11 +21,15 @@
 //     every n: 17, 511, 2048 ...).  k must be a multiple of 128 (else the matvec path serves the call).
 //     Narrower tiles (64 weight rows per wavefront; 32 or 64 x-rows per wavefront) are picked by the launcher
 //     when the wide one would leave CUs idle.
+#include <atomic>
+
 #include "relax_common.h"
 
 namespace relax {
 
 namespace {
+
+std::atomic<int> g_waves_per_simd{2};
 
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
@@ -33,7 +37,6 @@ typedef float float16_t __attribute__((ext_vector_type(16)));
 
 constexpr int BK = 64;                  // k per main-loop step
 constexpr int kPitch = BK + 8;          // LDS row pitch in halfs (144 bytes)
-constexpr int kThreadsG = 256;
 
 __device__ __forceinline__ uint32_t pk_add(uint32_t a, uint32_t b)
 {
@@ -99,20 +102,29 @@ struct GemmArgs {
 // g0 + r and rows [32 MF, 64 MF) the up rows F + g0 + (r - 32 MF).
 // FP16W: the weights are plain fp16 (the fp16-weight configurations of the paper's LLM charts, Sec. 5.1): the staging copies
 // 16-byte packets instead of decoding words, everything else is the same kernel.
-template <int EPI, int MF, int NF, bool FP16W = false>
-__global__ __launch_bounds__(kThreadsG) void gemm_q4_mfma_kernel(GemmArgs a)
+// WM x WN: wavefronts along the weight rows and along the x rows.  2 x 2: four wavefronts, one per SIMD, each with up to 512
+// registers.  4 x 2 and 2 x 4: eight wavefronts, two per SIMD with up to 256 registers each, so that one wavefront's decode, LDS
+// traffic and waits run under the other's MFMAs (with one wavefront per SIMD the matrix pipe was busy 37 % of the time:
+// counters in profiles/).
+template <int EPI, int MF, int NF, bool FP16W = false, int WM = 2, int WN = 2>
+__global__ __launch_bounds__(WM * WN * 64) void gemm_q4_mfma_kernel(GemmArgs a)
 {
-    constexpr int BM = 64 * MF, BN = 64 * NF;
-    constexpr int W = 2 * MF;                             // packed words a thread decodes per k block (8 or 4)
+    constexpr int kThreadsG = WM * WN * 64;
+    constexpr int BM = 32 * MF * WM, BN = 32 * NF * WN;
+    // packed words a thread decodes per k block: its share of the BM x 8 words of the weight tile, but never fewer than one
+    // 16-byte load's worth -- with a narrow weight tile only the first kAThreads threads (whole wavefronts) stage weights
+    constexpr int W = (BM * 8 / kThreadsG) < 4 ? 4 : BM * 8 / kThreadsG;
+    constexpr int kAThreads = BM * 8 / W;
     constexpr int TPR = 8 / W;                            // threads per weight row
-    constexpr int XP = 2 * NF;                            // 16-byte x packets a thread stages per k block
+    constexpr int XP = BN * 8 / kThreadsG;                // 16-byte x packets a thread stages per k block
+    static_assert(kAThreads % 64 == 0 && kAThreads <= kThreadsG && XP >= 1, "staging roles");
     constexpr int kABuf = BM * kPitch, kBBuf = BN * kPitch;
     extern __shared__ __align__(16) uint16_t lds[];       // A[2][BM][kPitch], B[2][BN][kPitch]
     uint16_t *const As = lds, *const Bs = lds + 2 * kABuf;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int row32 = lane & 31, hf = lane >> 5;
-    const int wm = wave & 1, wn = wave >> 1;
+    const int wm = wave % WM, wn = wave / WM;
     // Workgroups are handed to the 8 XCDs round-robin by linear id, and each XCD has its own L2.  Renumber them so
     // that an XCD owns a contiguous run of tiles (consecutive weight-row tiles of one x-row tile): the x tile a
     // workgroup streams is then fetched into one L2 instead of eight.
@@ -124,7 +136,8 @@ __global__ __launch_bounds__(kThreadsG) void gemm_q4_mfma_kernel(GemmArgs a)
     const int F = a.m >> 1;
 
     // ---- staging roles ----
-    const int arow = tid / TPR, aword0 = (tid % TPR) * W;
+    const bool a_on = tid < kAThreads;                    // wave-uniform
+    const int arow = (tid % kAThreads) / TPR, aword0 = (tid % TPR) * W;
     int grow;
     if (EPI == EPI_SWIGLU) {
         const int g0 = tile_m * (BM / 2);
@@ -172,7 +185,7 @@ __global__ __launch_bounds__(kThreadsG) void gemm_q4_mfma_kernel(GemmArgs a)
         uint16_t *ad = As + buf * kABuf + arow * kPitch + aword0 * 8;
 #pragma unroll
         for (int i = 0; i < W; ++i) {
-            if (i * 4 / W != part) continue;
+            if (i * 4 / W != part || !a_on) continue;
             if (FP16W) {                                  // same packet order as the decode and the x tile
                 const uint4 &h = S.wq[FP16W ? i : 0];
                 uint4 o;
@@ -248,11 +261,13 @@ __global__ __launch_bounds__(kThreadsG) void gemm_q4_mfma_kernel(GemmArgs a)
                 for (int j = 0; j < NF; ++j) bf[nxt][j] = *(const half8_t *)(bb + j * 32 * kPitch + (ks + 1) * 16);
             }
             __builtin_amdgcn_sched_barrier(0);
+            if (WM * WN > 4) __builtin_amdgcn_s_setprio(1);      // two wavefronts per SIMD: the one that has its fragments issues its MFMAs first
 #pragma unroll
             for (int j = 0; j < NF; ++j)
 #pragma unroll
                 for (int f = 0; f < MF; ++f)
                     acc[f][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[cur][f], bf[cur][j], acc[f][j], 0, 0, 0);
+            if (WM * WN > 4) __builtin_amdgcn_s_setprio(0);
             stage_store(S, buf ^ 1, ks);
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -354,10 +369,10 @@ __global__ __launch_bounds__(kThreadsG) void gemm_q4_mfma_kernel(GemmArgs a)
     }
 }
 
-template <int MF, int NF, bool FP16W = false>
+template <int MF, int NF, bool FP16W = false, int WM = 2, int WN = 2>
 hipError_t launch_tile(const GemmArgs &a_in, hipStream_t stream, int splits)
 {
-    constexpr int BM = 64 * MF, BN = 64 * NF;
+    constexpr int BM = 32 * MF * WM, BN = 32 * NF * WN, kThreadsG = WM * WN * 64;
     const int rows = a_in.epi == EPI_SWIGLU ? a_in.m / 2 : a_in.m, per_block = a_in.epi == EPI_SWIGLU ? BM / 2 : BM;
     GemmArgs a = a_in;
     a.tiles_m = (rows + per_block - 1) / per_block;
@@ -370,31 +385,35 @@ hipError_t launch_tile(const GemmArgs &a_in, hipStream_t stream, int splits)
     if constexpr (FP16W) {
         if (a.epi != EPI_F16 || splits != 1) return hipErrorInvalidValue;
         if (!attr_done) {
-            if (hipFuncSetAttribute((const void *)gemm_q4_mfma_kernel<EPI_F16, MF, NF, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+            if (hipFuncSetAttribute((const void *)gemm_q4_mfma_kernel<EPI_F16, MF, NF, true, WM, WN>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
                 return hipErrorInvalidValue;
             attr_done = true;
         }
-        hipLaunchKernelGGL((gemm_q4_mfma_kernel<EPI_F16, MF, NF, true>), grid, dim3(kThreadsG), lds, stream, a);
+        hipLaunchKernelGGL((gemm_q4_mfma_kernel<EPI_F16, MF, NF, true, WM, WN>), grid, dim3(kThreadsG), lds, stream, a);
         return hipGetLastError();
     }
     if (!attr_done) {
-        const void *ks[4] = {(const void *)gemm_q4_mfma_kernel<EPI_F16, MF, NF>, (const void *)gemm_q4_mfma_kernel<EPI_RESID_F32, MF, NF>,
-                             (const void *)gemm_q4_mfma_kernel<EPI_RESID_F16, MF, NF>, (const void *)gemm_q4_mfma_kernel<EPI_SWIGLU, MF, NF>};
+        const void *ks[4] = {(const void *)gemm_q4_mfma_kernel<EPI_F16, MF, NF, false, WM, WN>, (const void *)gemm_q4_mfma_kernel<EPI_RESID_F32, MF, NF, false, WM, WN>,
+                             (const void *)gemm_q4_mfma_kernel<EPI_RESID_F16, MF, NF, false, WM, WN>, (const void *)gemm_q4_mfma_kernel<EPI_SWIGLU, MF, NF, false, WM, WN>};
         for (const void *kf : ks)
             if (hipFuncSetAttribute(kf, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) return hipErrorInvalidValue;
         attr_done = true;
     }
     switch (a.epi) {
-    case EPI_F16: hipLaunchKernelGGL((gemm_q4_mfma_kernel<EPI_F16, MF, NF>), grid, dim3(kThreadsG), lds, stream, a); break;
-    case EPI_RESID_F32: hipLaunchKernelGGL((gemm_q4_mfma_kernel<EPI_RESID_F32, MF, NF>), grid, dim3(kThreadsG), lds, stream, a); break;
-    case EPI_RESID_F16: hipLaunchKernelGGL((gemm_q4_mfma_kernel<EPI_RESID_F16, MF, NF>), grid, dim3(kThreadsG), lds, stream, a); break;
-    case EPI_SWIGLU: hipLaunchKernelGGL((gemm_q4_mfma_kernel<EPI_SWIGLU, MF, NF>), grid, dim3(kThreadsG), lds, stream, a); break;
+    case EPI_F16: hipLaunchKernelGGL((gemm_q4_mfma_kernel<EPI_F16, MF, NF, false, WM, WN>), grid, dim3(kThreadsG), lds, stream, a); break;
+    case EPI_RESID_F32: hipLaunchKernelGGL((gemm_q4_mfma_kernel<EPI_RESID_F32, MF, NF, false, WM, WN>), grid, dim3(kThreadsG), lds, stream, a); break;
+    case EPI_RESID_F16: hipLaunchKernelGGL((gemm_q4_mfma_kernel<EPI_RESID_F16, MF, NF, false, WM, WN>), grid, dim3(kThreadsG), lds, stream, a); break;
+    case EPI_SWIGLU: hipLaunchKernelGGL((gemm_q4_mfma_kernel<EPI_SWIGLU, MF, NF, false, WM, WN>), grid, dim3(kThreadsG), lds, stream, a); break;
     default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
 }
 
 }  // namespace
+
+// Test switch ("gemm_waves_per_simd"): the 256 x 256 tile runs as eight wavefronts of 64 x 128 (2, the default) or as four of
+// 128 x 128 (1).  Same arithmetic per output element in the same order either way: results are identical.
+void gemm_set_waves_per_simd(int v) { g_waves_per_simd.store(v == 1 ? 1 : 2); }
 
 // Whether the MFMA path can serve this matrix (k in whole 128-blocks, 16-byte aligned rows, 4-row store granules).
 bool gemm_mfma_eligible(const relax_qmat &w, const void *x, int epi)
@@ -486,7 +505,7 @@ hipError_t launch_gemm_f16(const uint16_t *x, const uint16_t *w, int n, int m, i
     a.x = x, a.wh = w, a.n = n, a.m = m, a.k = k, a.epi = EPI_F16, a.out_f16 = out;
     const TilePlan p = tile_plan(m, k, n, EPI_F16);
     a.kb_per_split = k / BK;
-    if (p.mf == 4) return launch_tile<4, 4, true>(a, stream, 1);
+    if (p.mf == 4) return launch_tile<4, 4, true>(a, stream, 1);    // the fp16-weight staging needs more registers than two wavefronts per SIMD leave
     if (p.nf == 4) return launch_tile<2, 4, true>(a, stream, 1);
     if (p.nf == 2) return launch_tile<2, 2, true>(a, stream, 1);
     return launch_tile<2, 1, true>(a, stream, 1);
@@ -506,8 +525,9 @@ hipError_t launch_gemm_mfma(const uint16_t *x, const relax_qmat &w, int n, int e
     a.partial = p.splits > 1 ? partial : nullptr;
     a.kb_per_split = p.kb_per_split;
     hipError_t e;
-    if (p.mf == 4) e = launch_tile<4, 4>(a, stream, p.splits);
-    else if (p.nf == 4) e = launch_tile<2, 4>(a, stream, p.splits);
+    const bool eight = g_waves_per_simd.load() == 2;
+    if (p.mf == 4) e = eight ? launch_tile<2, 4, false, 4, 2>(a, stream, p.splits) : launch_tile<4, 4>(a, stream, p.splits);
+    else if (p.nf == 4) e = eight ? launch_tile<2, 2, false, 2, 4>(a, stream, p.splits) : launch_tile<2, 4>(a, stream, p.splits);
     else if (p.nf == 2) e = launch_tile<2, 2>(a, stream, p.splits);
     else e = launch_tile<2, 1>(a, stream, p.splits);
     if (e != hipSuccess || p.splits < 2) return e;
