@@ -312,6 +312,21 @@ relax_status relax_dequantize(const relax_qmat *w, float *out, relax_stream stre
 relax_status relax_unpack_q3(const relax_qmat *w, int8_t *out, relax_stream stream);
 relax_status relax_dequant_matmul_q3(const uint16_t *x, const relax_qmat *w, uint16_t *out, int32_t n, relax_stream stream);
 
+/* The GPU-native 3-bit layout: the same bits per group in an order the kernels decode at a third of the cost (one
+ * vector operation yields a ready fp16 pair), so that 3-bit weights stream FASTER than 4-bit ones, as their size
+ * promises.  Per group of 32 columns (codes u_0..u_31) and its three words: position j (0..4) of word w holds
+ * u_{2(5w+j)} in bits 3j..3j+2 and u_{2(5w+j)+1} in bits 16+3j..16+3j+2; bit i of u_30 is bit 15 of word i, bit i of
+ * u_31 is bit 31 of word i.  Scales are unchanged.
+ * relax_repack_q3: canonical q (as above) -> native_q, device uint32 [m][3k/32] owned by the caller, not in place; a
+ * one-time step at load time (Sec. 4.6: weights are prepared once for the kernels that serve them).
+ * relax_unpack_q3_native: out int8 [m,k] in -4..3 from a native matrix -- equals relax_unpack_q3 of the canonical one.
+ * relax_dequant_matmul_q3_native: out[n,m] fp16 = x[n,k] times the decoded native matrix, fp32 accumulation.  Rows of
+ * x are taken 4, 2 or 1 per pass over the matrix (k <= 4096: 4; k <= 8192: 2), the decode of a weight shared by the
+ * rows of a pass, so a few rows cost little more than one.  k <= 12288, x 16-byte aligned; errors as the canonical call. */
+relax_status relax_repack_q3(const relax_qmat *canonical, uint32_t *native_q, relax_stream stream);
+relax_status relax_unpack_q3_native(const relax_qmat *w, int8_t *out, relax_stream stream);
+relax_status relax_dequant_matmul_q3_native(const uint16_t *x, const relax_qmat *w, uint16_t *out, int32_t n, relax_stream stream);
+
 /* Build identity of the loaded binary (one binary serves every shape).                  */
 const char *relax_build_id(void);
 

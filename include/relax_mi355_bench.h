@@ -19,6 +19,8 @@ extern "C" {
  * split-K matmul also does the light step that follows it (rotary embedding + KV append after QKV, the RMSNorm after
  * the output projection, and in relax_model_step the first RMSNorm of the next layer after the down projection:
  * Sec. 4.2 operator fusion); 0 runs them as launches of their own.  Results are identical bit for bit either way.
+ * "gemm_waves_per_simd" (default 2): the 256 x 256 tile of the tiled GEMM runs as eight wavefronts (two per SIMD) or, with 1,
+ * as four (one per SIMD); identical results.
  * "half_matmul_gemm_rows" (default 0): relax_half_matmul takes the tiled GEMM from this many rows on; 0: by estimate.
  * Unknown name: RELAX_ERR_UNSUPPORTED.                                                                           */
 relax_status relax_set_option(const char *name, int32_t value);

@@ -104,6 +104,9 @@ _SIGNATURES = {
     "relax_dequantize": (C.c_int32, [C.POINTER(QMatC), C.c_void_p, C.c_void_p]),
     "relax_unpack_q3": (C.c_int32, [C.POINTER(QMatC), C.c_void_p, C.c_void_p]),
     "relax_dequant_matmul_q3": (C.c_int32, [C.c_void_p, C.POINTER(QMatC), C.c_void_p, C.c_int32, C.c_void_p]),
+    "relax_repack_q3": (C.c_int32, [C.POINTER(QMatC), C.c_void_p, C.c_void_p]),
+    "relax_unpack_q3_native": (C.c_int32, [C.POINTER(QMatC), C.c_void_p, C.c_void_p]),
+    "relax_dequant_matmul_q3_native": (C.c_int32, [C.c_void_p, C.POINTER(QMatC), C.c_void_p, C.c_int32, C.c_void_p]),
 }
 EXPORTS = tuple(_SIGNATURES)
 
@@ -355,6 +358,21 @@ def relax_unpack_q3(w: Optional[QMat], out: Ptr, stream=None) -> int:
 def relax_dequant_matmul_q3(x: Ptr, w: Optional[QMat], out: Ptr, n: int, stream=None) -> int:
     wc = None if w is None else w.c()
     return lib().relax_dequant_matmul_q3(_ptr(x), _ref(wc), _ptr(out), n, _stream(stream))
+
+
+def relax_repack_q3(canonical: Optional[QMat], native_q: Ptr, stream=None) -> int:
+    wc = None if canonical is None else canonical.c()
+    return lib().relax_repack_q3(_ref(wc), _ptr(native_q), _stream(stream))
+
+
+def relax_unpack_q3_native(w: Optional[QMat], out: Ptr, stream=None) -> int:
+    wc = None if w is None else w.c()
+    return lib().relax_unpack_q3_native(_ref(wc), _ptr(out), _stream(stream))
+
+
+def relax_dequant_matmul_q3_native(x: Ptr, w: Optional[QMat], out: Ptr, n: int, stream=None) -> int:
+    wc = None if w is None else w.c()
+    return lib().relax_dequant_matmul_q3_native(_ptr(x), _ref(wc), _ptr(out), n, _stream(stream))
 
 
 def relax_profile_step_events(start: Optional[int], stop: Optional[int], step: int) -> None:

@@ -357,6 +357,11 @@ relax_status relax_set_option(const char *name, int32_t value)
         g_opt_fuse_finish.store(value);
         return RELAX_OK;
     }
+    if (std::strcmp(name, "gemm_waves_per_simd") == 0) {
+        if (value != 1 && value != 2) return RELAX_ERR_SHAPE;
+        gemm_set_waves_per_simd(value);
+        return RELAX_OK;
+    }
     if (std::strcmp(name, "half_matmul_gemm_rows") == 0) {
         if (value < 0) return RELAX_ERR_SHAPE;
         g_opt_half_gemm_rows.store(value);
@@ -906,6 +911,32 @@ relax_status relax_dequant_matmul_q3(const uint16_t *x, const relax_qmat *w, uin
     if ((reinterpret_cast<uintptr_t>(x) & 15) != 0 || (reinterpret_cast<uintptr_t>(w->q) & 3) != 0 || (reinterpret_cast<uintptr_t>(w->s) & 1) != 0)
         return RELAX_ERR_SHAPE;
     return hip_status(launch_gemv_q3(x, *w, n, out, static_cast<hipStream_t>(stream)));
+}
+
+relax_status relax_repack_q3(const relax_qmat *canonical, uint32_t *native_q, relax_stream stream)
+{
+    if (!canonical || !canonical->q || !native_q) return RELAX_ERR_NULL;
+    if (canonical->m < 1 || canonical->k < 32 || canonical->k % 32 != 0) return RELAX_ERR_SHAPE;
+    if ((reinterpret_cast<uintptr_t>(canonical->q) & 3) != 0 || (reinterpret_cast<uintptr_t>(native_q) & 3) != 0) return RELAX_ERR_SHAPE;
+    if (static_cast<const void *>(canonical->q) == static_cast<const void *>(native_q)) return RELAX_ERR_SHAPE;   // not in place
+    return hip_status(launch_repack_q3(*canonical, native_q, static_cast<hipStream_t>(stream)));
+}
+
+relax_status relax_unpack_q3_native(const relax_qmat *w, int8_t *out, relax_stream stream)
+{
+    if (!w || !w->q || !out) return RELAX_ERR_NULL;
+    if (w->m < 1 || w->k < 32 || w->k % 32 != 0) return RELAX_ERR_SHAPE;
+    return hip_status(launch_unpack_q3_native(*w, out, static_cast<hipStream_t>(stream)));
+}
+
+relax_status relax_dequant_matmul_q3_native(const uint16_t *x, const relax_qmat *w, uint16_t *out, int32_t n, relax_stream stream)
+{
+    if (!x || !out || !w || !w->q || !w->s) return RELAX_ERR_NULL;
+    if (n < 1 || n > 4 * 65535 || w->m < 1 || w->k < 32 || w->k % 32 != 0) return RELAX_ERR_SHAPE;
+    if (!gemv_q3_supported(w->m, w->k)) return RELAX_ERR_UNSUPPORTED;
+    if ((reinterpret_cast<uintptr_t>(x) & 15) != 0 || (reinterpret_cast<uintptr_t>(w->q) & 3) != 0 || (reinterpret_cast<uintptr_t>(w->s) & 1) != 0)
+        return RELAX_ERR_SHAPE;
+    return hip_status(launch_gemv_q3_native(x, *w, n, out, static_cast<hipStream_t>(stream)));
 }
 
 }  // extern "C"

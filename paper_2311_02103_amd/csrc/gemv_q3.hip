@@ -129,6 +129,204 @@ __global__ void unpack_q3_kernel(const uint32_t *q, int8_t *out, int m, int k)
     out[e] = (int8_t)((int)(v & 7u) - 4);
 }
 
+// ---- native 3-bit layout: the same 96 bits per group, placed so that one v_and_or_b32 yields a ready fp16 pair ----------
+// Canonical codes lie end to end; a 6-bit window has to be shifted into place for every pair (about five vector ops per
+// two weights, which made the 3-bit matvec slower than the 4-bit one although it reads fewer bytes).  relax_repack_q3
+// rewrites a matrix once into this layout of a group's three words (columns c = 0..31 of the group, code u_c):
+//   word w (0..2), position j (0..4): u_{2(5w+j)} in bits 3j..3j+2, u_{2(5w+j)+1} in bits 16+3j..16+3j+2
+//   (the 15 pairs of columns 0..29: pair p = 5w + j, its even column in the low half-word, its odd column in the high one);
+//   bit i (0..2) of u_30 is bit 15 of word i, bit i of u_31 is bit 31 of word i.
+// (v & 0x00070007) | 0x64006400 is then the fp16 pair (1024 + u_even, 1024 + u_odd) of position 0, the masks 0x00380038 and
+// 0x01C001C0 give (1024 + 8u, ...) and (1024 + 64u, ...) of positions 1 and 2 without a shift -- all inside the ten mantissa
+// bits -- and positions 3, 4 are positions 0, 1 of v >> 9.  Pairs of the three scale classes go to three accumulators;
+// sum x (u - 4) = A + B / 8 + C / 64 - (1028 sum_A x + 132 sum_B x + 20 sum_C x), the bracket precomputed per group of x.
+// 24 decode ops per group, shared by every row of x in the pass, plus 16 dot products per row of x.
+
+__device__ __forceinline__ uint32_t and_or3(uint32_t w, uint32_t mask, uint32_t bits)
+{
+    uint32_t r;
+    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(w), "s"(mask), "v"(bits));
+    return r;
+}
+
+// class of pair p (0: plain, 1: times 8, 2: times 64); pair 15 (columns 30, 31) is plain
+__host__ __device__ constexpr int q3n_class(int p) { return p == 15 ? 0 : (p % 5 == 2 ? 2 : (p % 5) % 3 == 1 ? 1 : 0); }
+
+// the 16 fp16 pairs of a group in pair order, each (1024 + f u_even, 1024 + f u_odd) with f = 1, 8 or 64 by class
+__device__ __forceinline__ void q3n_decode(uint32_t w0, uint32_t w1, uint32_t w2, uint32_t *pk)
+{
+    const uint32_t base = 0x64006400u;
+    const uint32_t w[3] = {w0, w1, w2};
+#pragma unroll
+    for (int i = 0; i < 3; ++i) {
+        const uint32_t v = w[i], v9 = v >> 9;
+        pk[5 * i + 0] = and_or3(v, 0x00070007u, base);
+        pk[5 * i + 1] = and_or3(v, 0x00380038u, base);
+        pk[5 * i + 2] = and_or3(v, 0x01C001C0u, base);
+        pk[5 * i + 3] = and_or3(v9, 0x00070007u, base);
+        pk[5 * i + 4] = and_or3(v9, 0x00380038u, base);
+    }
+    uint32_t t = and_or3(w0 >> 15, 0x00010001u, base);
+    t = and_or3(w1 >> 14, 0x00020002u, t);
+    pk[15] = and_or3(w2 >> 13, 0x00040004u, t);
+}
+
+// one group: canonical words -> native words
+__global__ void repack_q3_kernel(const uint32_t *src, uint32_t *dst, size_t groups)
+{
+    const size_t g = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (g >= groups) return;
+    const uint32_t a = src[3 * g], b = src[3 * g + 1], c = src[3 * g + 2];
+    uint32_t u[32];
+#pragma unroll
+    for (int col = 0; col < 32; ++col) {
+        const int bit = 3 * col, word = bit >> 5, sh = bit & 31;
+        const uint32_t lo = word == 0 ? a : word == 1 ? b : c, hi = word == 0 ? b : c;
+        uint32_t v = lo >> sh;
+        if (sh > 29) v |= hi << (32 - sh);
+        u[col] = v & 7u;
+    }
+    uint32_t o[3] = {0u, 0u, 0u};
+#pragma unroll
+    for (int p = 0; p < 15; ++p) o[p / 5] |= (u[2 * p] << (3 * (p % 5))) | (u[2 * p + 1] << (16 + 3 * (p % 5)));
+#pragma unroll
+    for (int i = 0; i < 3; ++i) o[i] |= (((u[30] >> i) & 1u) << 15) | (((u[31] >> i) & 1u) << 31);
+    dst[3 * g] = o[0], dst[3 * g + 1] = o[1], dst[3 * g + 2] = o[2];
+}
+
+__global__ void unpack_q3n_kernel(const uint32_t *q, int8_t *out, int m, int k)
+{
+    const size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= (size_t)m * k) return;
+    const size_t row = e / k;
+    const int c = (int)(e - row * k), g = c >> 5, col = c & 31;
+    const uint32_t *p = q + (row * (k >> 5) + g) * 3;
+    uint32_t u;
+    if (col < 30) {
+        const int pr = col >> 1;
+        u = (p[pr / 5] >> (3 * (pr % 5) + 16 * (col & 1))) & 7u;
+    } else {
+        const int sh = col == 30 ? 15 : 31;
+        u = ((p[0] >> sh) & 1u) | (((p[1] >> sh) & 1u) << 1) | (((p[2] >> sh) & 1u) << 2);
+    }
+    out[e] = (int8_t)((int)u - 4);
+}
+
+// V partial sums per lane -> lane l holds the total of value l % V (a transposing reduction: the number of live values
+// halves with every exchange)
+template <int V>
+__device__ __forceinline__ float reduce_many(float *v, int lane)
+{
+    static_assert(V == 1 || V == 2 || V == 4 || V == 8, "1, 2, 4 or 8 values");
+    int n = V;
+#pragma unroll
+    for (int bit = 1; bit < V; bit <<= 1) {
+        const bool up = lane & bit;
+#pragma unroll
+        for (int i = 0; i < V / 2; ++i) {
+            if (2 * i + 1 < n) {
+                const float keep = up ? v[2 * i + 1] : v[2 * i], give = up ? v[2 * i] : v[2 * i + 1];
+                v[i] = keep + __shfl_xor(give, bit, kWave);
+            }
+        }
+        n >>= 1;
+    }
+    float r = v[0];
+#pragma unroll
+    for (int off = V; off < kWave; off <<= 1) r += __shfl_xor(r, off, kWave);
+    return r;
+}
+
+constexpr int kQ3nRows = 2;                                  // matrix rows per slot; two slots in flight per wavefront
+
+// out[i0 + xr, r] for NR rows of x per pass: grid = (workgroups, passes).  A wavefront owns the row pairs wg, wg + W, ...
+template <int J, int NR>
+__global__ __launch_bounds__(kQ3Threads) void gemv_q3n_kernel(const uint16_t *__restrict__ x, const uint32_t *__restrict__ q,
+                                                              const uint16_t *__restrict__ s, uint16_t *__restrict__ out, int m, int k, int n)
+{
+    const int G = k >> 5, lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    const int i0 = blockIdx.y * NR;
+    // the lane's x values of every row of the pass, as fp16 pairs in column order, and the offset term of each group
+    uint32_t xp[NR][J][16];
+    float corr[NR][J];
+#pragma unroll
+    for (int xr = 0; xr < NR; ++xr) {
+        const int i = min(i0 + xr, n - 1);                   // a ragged last pass re-reads the last row (never stored)
+#pragma unroll
+        for (int j = 0; j < J; ++j) {
+            const int g = min(lane + kWave * j, G - 1);
+#pragma unroll
+            for (int v4 = 0; v4 < 4; ++v4) {
+                const uint4 raw = *(const uint4 *)(x + (size_t)i * k + (size_t)g * 32 + v4 * 8);
+                xp[xr][j][4 * v4] = raw.x, xp[xr][j][4 * v4 + 1] = raw.y, xp[xr][j][4 * v4 + 2] = raw.z, xp[xr][j][4 * v4 + 3] = raw.w;
+            }
+            float sc[3] = {0.0f, 0.0f, 0.0f};
+#pragma unroll
+            for (int p = 0; p < 16; ++p) sc[q3n_class(p)] = dot2(0x3C003C00u, xp[xr][j][p], sc[q3n_class(p)]);
+            corr[xr][j] = 1028.0f * sc[0] + 132.0f * sc[1] + 20.0f * sc[2];
+        }
+    }
+    bool on[J];
+#pragma unroll
+    for (int j = 0; j < J; ++j) on[j] = lane + kWave * j < G;
+
+    struct Slot {
+        uint32_t w[kQ3nRows][J][3];
+        uint16_t sc[kQ3nRows][J];
+    };
+    const int U = (m + kQ3nRows - 1) / kQ3nRows;             // row pairs
+    const int W = gridDim.x * kQ3Waves, wg = blockIdx.x * kQ3Waves + wave;
+    auto slot_load = [&](Slot &sl, int u) {                  // unit u; past the end: the last unit again (dropped)
+        u = min(u, U - 1);
+#pragma unroll
+        for (int rr = 0; rr < kQ3nRows; ++rr) {
+            const size_t row = (size_t)min(u * kQ3nRows + rr, m - 1);
+#pragma unroll
+            for (int j = 0; j < J; ++j) {
+                const int g = min(lane + kWave * j, G - 1);
+                const uint32_t *p = q + (row * G + g) * 3;
+                sl.w[rr][j][0] = p[0], sl.w[rr][j][1] = p[1], sl.w[rr][j][2] = p[2];
+                sl.sc[rr][j] = s[row * G + g];
+            }
+        }
+    };
+    auto consume = [&](const Slot &sl, int u) {
+        float tot[kQ3nRows * NR];
+#pragma unroll
+        for (int rr = 0; rr < kQ3nRows; ++rr) {
+#pragma unroll
+            for (int xr = 0; xr < NR; ++xr) tot[rr * NR + xr] = 0.0f;
+#pragma unroll
+            for (int j = 0; j < J; ++j) {
+                uint32_t pk[16];
+                q3n_decode(sl.w[rr][j][0], sl.w[rr][j][1], sl.w[rr][j][2], pk);
+                const float scale = on[j] ? h2f(sl.sc[rr][j]) : 0.0f;
+#pragma unroll
+                for (int xr = 0; xr < NR; ++xr) {
+                    float acc[3] = {0.0f, 0.0f, 0.0f};
+#pragma unroll
+                    for (int p = 0; p < 16; ++p) acc[q3n_class(p)] = dot2(pk[p], xp[xr][j][p], acc[q3n_class(p)]);
+                    tot[rr * NR + xr] += scale * (acc[0] + acc[1] * 0.125f + acc[2] * 0.015625f - corr[xr][j]);
+                }
+            }
+        }
+        const float r = reduce_many<kQ3nRows * NR>(tot, lane);
+        if (u < U && lane < kQ3nRows * NR) {                 // lane l: row l / NR of the unit, x row l % NR of the pass
+            const int row = u * kQ3nRows + lane / NR, i = i0 + lane % NR;
+            if (row < m && i < n) out[(size_t)i * m + row] = f2h(r);
+        }
+    };
+    Slot a, b;
+    slot_load(a, wg);
+    slot_load(b, wg + W);
+    for (int u = wg; u < U; u += 2 * W) {
+        consume(a, u);
+        slot_load(a, u + 2 * W);
+        consume(b, u + W);
+        slot_load(b, u + 3 * W);
+    }
+}
+
 }  // namespace
 
 bool gemv_q3_supported(int m, int k) { return m >= 1 && k >= 32 && k % 32 == 0 && k <= kQ3MaxGroupsPerLane * kWave * 32; }
@@ -164,6 +362,71 @@ hipError_t launch_unpack_q3(const relax_qmat &w, int8_t *out, hipStream_t stream
     const size_t total = (size_t)w.m * w.k;
     (void)hipGetLastError();
     hipLaunchKernelGGL(unpack_q3_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, static_cast<const uint32_t *>(w.q), out, w.m, w.k);
+    return hipGetLastError();
+}
+
+// x rows per pass of the native-layout kernel: as many as the registers of a lane hold next to the slots
+int gemv_q3n_rows_per_pass(int k, int n)
+{
+    const int J = (k / 32 + kWave - 1) / kWave;
+    const int cap = J <= 2 ? 4 : J <= 4 ? 2 : 1;
+    return n >= 4 && cap >= 4 ? 4 : n >= 2 && cap >= 2 ? 2 : 1;
+}
+
+template <int J, int NR>
+static void launch_q3n(const uint16_t *x, const uint32_t *q, const uint16_t *s, uint16_t *out, int m, int k, int n, int blocks, hipStream_t stream)
+{
+    hipLaunchKernelGGL((gemv_q3n_kernel<J, NR>), dim3(blocks, (n + NR - 1) / NR), dim3(kQ3Threads), 0, stream, x, q, s, out, m, k, n);
+}
+
+hipError_t launch_gemv_q3_native(const uint16_t *x, const relax_qmat &w, int n, uint16_t *out, hipStream_t stream)
+{
+    const int G = w.k / 32, J = (G + kWave - 1) / kWave, NR = gemv_q3n_rows_per_pass(w.k, n);
+    (void)hipGetLastError();
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
+    }
+    const int units = (w.m + kQ3nRows - 1) / kQ3nRows;
+    // two workgroups per CU, one for the two variants whose registers leave room for a single one
+    const int per_cu = (J == 6 || (J == 4 && NR == 2)) ? 1 : 2;
+    const int blocks = std::max(1, std::min((units + kQ3Waves - 1) / kQ3Waves, per_cu * cus));
+    const uint32_t *q = static_cast<const uint32_t *>(w.q);
+    const uint16_t *s = static_cast<const uint16_t *>(w.s);
+#define RELAX_Q3N(JJ, RR) launch_q3n<JJ, RR>(x, q, s, out, w.m, w.k, n, blocks, stream)
+    switch (J * 8 + NR) {
+    case 1 * 8 + 1: RELAX_Q3N(1, 1); break;
+    case 1 * 8 + 2: RELAX_Q3N(1, 2); break;
+    case 1 * 8 + 4: RELAX_Q3N(1, 4); break;
+    case 2 * 8 + 1: RELAX_Q3N(2, 1); break;
+    case 2 * 8 + 2: RELAX_Q3N(2, 2); break;
+    case 2 * 8 + 4: RELAX_Q3N(2, 4); break;
+    case 3 * 8 + 1: RELAX_Q3N(3, 1); break;
+    case 3 * 8 + 2: RELAX_Q3N(3, 2); break;
+    case 4 * 8 + 1: RELAX_Q3N(4, 1); break;
+    case 4 * 8 + 2: RELAX_Q3N(4, 2); break;
+    case 5 * 8 + 1: RELAX_Q3N(5, 1); break;
+    case 6 * 8 + 1: RELAX_Q3N(6, 1); break;
+    default: return hipErrorInvalidValue;
+    }
+#undef RELAX_Q3N
+    return hipGetLastError();
+}
+
+hipError_t launch_repack_q3(const relax_qmat &w, uint32_t *dst, hipStream_t stream)
+{
+    const size_t groups = (size_t)w.m * (w.k / 32);
+    (void)hipGetLastError();
+    hipLaunchKernelGGL(repack_q3_kernel, dim3((unsigned)((groups + 255) / 256)), dim3(256), 0, stream, static_cast<const uint32_t *>(w.q), dst, groups);
+    return hipGetLastError();
+}
+
+hipError_t launch_unpack_q3_native(const relax_qmat &w, int8_t *out, hipStream_t stream)
+{
+    const size_t total = (size_t)w.m * w.k;
+    (void)hipGetLastError();
+    hipLaunchKernelGGL(unpack_q3n_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, static_cast<const uint32_t *>(w.q), out, w.m, w.k);
     return hipGetLastError();
 }
 

@@ -160,6 +160,7 @@ hipError_t launch_rmsnorm_f32(const float *x, const uint16_t *w, uint16_t *y, in
 // MFMA GEMM for large n (gemm_q4_mfma.hip)
 constexpr int kGemmMinN = 16;        // rows from which the MFMA GEMM replaces one matvec pass per row
 bool gemm_mfma_eligible(const relax_qmat &w, const void *x, int epi);
+void gemm_set_waves_per_simd(int v);     // test switch: 2 (default) = eight wavefronts per 256 x 256 tile, 1 = four
 constexpr int kSplitKMax = 8;         // k splits of the tiled GEMM at most, when its tiles alone leave more than half of the CUs idle
 constexpr int kSplitKMaxN = 512;      // ... and only up to this many rows (the partial tiles are splits * n * m floats)
 size_t gemm_splitk_partial_floats(int m, int k, int n, int epi);
@@ -206,6 +207,10 @@ hipError_t launch_unpack(const relax_qmat &w, int8_t *out, hipStream_t stream);
 bool gemv_q3_supported(int m, int k);
 hipError_t launch_gemv_q3(const uint16_t *x, const relax_qmat &w, int n, uint16_t *out, hipStream_t stream);
 hipError_t launch_unpack_q3(const relax_qmat &w, int8_t *out, hipStream_t stream);
+// native 3-bit layout (gemv_q3.hip): one-time repack, its dense decode export, the streaming matvec for 1..n rows of x
+hipError_t launch_repack_q3(const relax_qmat &canonical, uint32_t *dst, hipStream_t stream);
+hipError_t launch_unpack_q3_native(const relax_qmat &w, int8_t *out, hipStream_t stream);
+hipError_t launch_gemv_q3_native(const uint16_t *x, const relax_qmat &w, int n, uint16_t *out, hipStream_t stream);
 hipError_t launch_dequantize(const relax_qmat &w, float *out, hipStream_t stream);
 
 // Split-L attention: chunk length and split count are pure functions of the runtime shape.

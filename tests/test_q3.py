@@ -134,11 +134,88 @@ def test_gpu_matmul_random(rx, m, k, n):
     assert err.max() <= 2e-3 * max(1.0, np.abs(ref).max())
 
 
+# ------------------------------------------------------------------------------------------------ GPU-native layout
+def gpu_q3_native(rx, q):
+    """canonical words on the host -> native words on the device (relax_repack_q3)"""
+    import torch
+    m, w = q.shape
+    qd = torch.from_numpy(q.view(np.int32)).cuda()
+    nat = torch.empty_like(qd)
+    rx.check(rx.relax_repack_q3(rx.QMat(qd, qd, m, w * 32 // 3), nat), "relax_repack_q3")
+    return nat
+
+
+def gpu_q3_native_matmul(rx, x_bits, q, s, m, k):
+    import torch
+    n = x_bits.shape[0]
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a).view(np.int32 if a.dtype == np.uint32 else np.int16)).cuda()
+    out = torch.full((n, m), float("nan"), dtype=torch.float16, device="cuda")
+    rx.check(rx.relax_dequant_matmul_q3_native(dev(x_bits), rx.QMat(gpu_q3_native(rx, q), dev(s), m, k), out, n), "relax_dequant_matmul_q3_native")
+    torch.cuda.synchronize()
+    return out.cpu().numpy().astype(np.float32)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("m,k", [(1, 32), (5, 96), (33, 704), (64, 4096), (3, 11008)])
+def test_gpu_repack_then_native_unpack_bit_exact(rx, m, k):
+    """Random words (every code at every position, both straddling codes): the native layout decodes to what the canonical
+    one decodes to, element by element."""
+    import torch
+    r = np.random.RandomState(m * 11 + k)
+    q = r.randint(0, 2 ** 32, size=(m, 3 * k // 32), dtype=np.uint64).astype(np.uint32)
+    nat = gpu_q3_native(rx, q)
+    out = torch.empty((m, k), dtype=torch.int8, device="cuda")
+    rx.check(rx.relax_unpack_q3_native(rx.QMat(nat, nat, m, k), out), "relax_unpack_q3_native")
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy(), q3.unpack_q3(q, m, k))
+    # one code set at a time: the native word image is what the layout's definition says (column -> word, bit)
+    codes = np.zeros((32, 32), dtype=np.uint8)
+    codes[np.arange(32), np.arange(32)] = 5                       # row c: u_c = 5 (binary 101), all other codes 0
+    nat = gpu_q3_native(rx, wl.pack_codes3(codes)).cpu().numpy().view(np.uint32)
+    want = np.zeros((32, 3), dtype=np.uint32)
+    for c in range(30):
+        p = c // 2
+        want[c, p // 5] = 5 << (3 * (p % 5) + 16 * (c % 2))
+    for c in (30, 31):
+        want[c, 0] = want[c, 2] = 1 << (15 if c == 30 else 31)    # bits 0 and 2 of the code go to words 0 and 2
+    assert np.array_equal(nat, want)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("m,k,n", [(40, 256, 2), (65, 704, 3), (130, 4096, 1), (131, 4096, 4), (37, 11008, 2), (64, 8192, 5)])
+def test_gpu_native_integer_valued_matmul_bitwise(rx, m, k, n):
+    r = np.random.RandomState(k + m + n)
+    codes = r.randint(0, 8, size=(m, k)).astype(np.uint8)
+    s = r.choice([1.0, 2.0], size=(m, k // 32)).astype(np.float16).view(np.uint16)
+    x = np.zeros((n, k), dtype=np.float32)
+    hot = r.choice(k, size=40, replace=False)
+    x[:, hot] = r.randint(-3, 4, size=(n, 40))
+    q = wl.pack_codes3(codes)
+    ref = q3.dequant_matmul_q3(x, q, s, m, k)
+    assert np.abs(ref).max() <= 2048
+    got = gpu_q3_native_matmul(rx, x.astype(np.float16).view(np.uint16), q, s, m, k)
+    assert np.array_equal(got.astype(np.float64), ref)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("m,k,n", [(1, 32, 1), (7, 64, 3), (257, 704, 1), (1000, 2048 + 32, 5), (4099, 4096, 1), (22016, 4096, 1),
+                                   (4096, 11008, 2), (300, 12288, 1), (515, 4096, 17), (1001, 8192, 7), (333, 6144, 4)])
+def test_gpu_native_matmul_random(rx, m, k, n):
+    """Every (groups per lane, rows per pass) variant of the native-layout kernel, odd m, ragged last passes."""
+    q, s = wl.qmat3(9, m * 131 + k, m, k)
+    x = wl.normal_f16_bits(9, m + k + n, (n, k))
+    ref = q3.dequant_matmul_q3(wl.f16_bits_to_f32(x), q, s, m, k)
+    got = gpu_q3_native_matmul(rx, x, q, s, m, k)
+    err = np.abs(got - ref)
+    assert np.all(err <= 1e-2 + 2e-2 * np.abs(ref)), "m=%d k=%d n=%d: max err %g" % (m, k, n, err.max())
+    assert err.max() <= 2e-3 * max(1.0, np.abs(ref).max())
+
+
 def test_host_checks_of_the_q3_entry_points():
     from paper_2311_02103_amd import binding as rx
     if not os.path.exists(rx.LIB_PATH):
         pytest.skip("library not built")
-    w = rx.QMatC(64, 64, 8, 64)                    # non-NULL fake pointers: every case below is rejected before any launch
+    w = rx.QMatC(64, 64, 8, 64, 32)                # non-NULL fake pointers: every case below is rejected before any launch
     assert rx.lib().relax_dequant_matmul_q3(None, w, 64, 1, None) == rx.ERR_NULL
     assert rx.lib().relax_dequant_matmul_q3(64, w, 64, 0, None) == rx.ERR_SHAPE
     assert rx.lib().relax_dequant_matmul_q3(64, rx.QMatC(64, 64, 8, 40), 64, 1, None) == rx.ERR_SHAPE          # k % 32
@@ -146,3 +223,10 @@ def test_host_checks_of_the_q3_entry_points():
     assert rx.lib().relax_dequant_matmul_q3(72, w, 64, 1, None) == rx.ERR_SHAPE                                 # x not 16-byte aligned
     assert rx.lib().relax_unpack_q3(None, 64, None) == rx.ERR_NULL
     assert rx.lib().relax_unpack_q3(rx.QMatC(64, 64, 8, 48), 64, None) == rx.ERR_SHAPE
+    assert rx.lib().relax_repack_q3(None, 64, None) == rx.ERR_NULL
+    assert rx.lib().relax_repack_q3(w, 64, None) == rx.ERR_SHAPE                                               # in place
+    assert rx.lib().relax_repack_q3(rx.QMatC(64, 64, 8, 40), 128, None) == rx.ERR_SHAPE
+    assert rx.lib().relax_unpack_q3_native(rx.QMatC(64, 64, 8, 48), 64, None) == rx.ERR_SHAPE
+    assert rx.lib().relax_dequant_matmul_q3_native(64, w, 64, 0, None) == rx.ERR_SHAPE
+    assert rx.lib().relax_dequant_matmul_q3_native(64, rx.QMatC(64, 64, 8, 12288 + 32), 64, 1, None) == rx.ERR_UNSUPPORTED
+    assert rx.lib().relax_dequant_matmul_q3_native(None, w, 64, 1, None) == rx.ERR_NULL
