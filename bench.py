@@ -16,7 +16,7 @@ Other workloads (--workload), same JSON schema, for the other configurations:
   batch_sweep    one 7B-shaped layer call on n decode rows against n (where the dispatch on n changes kernels).
   memory_plan    host-only: planned against unplanned bytes of the layer's intermediates (Alg. 3 of the paper).
   half_sweep     relax_half_matmul (plain fp16 weights) against n, matvec passes and tiled GEMM forced in turn: the crossover.
-  q3_matvec      relax_dequant_matmul_q3 (3-bit weights) at n = 1 on the four matrix shapes of the 7B layer.
+  q3_matvec      relax_dequant_matmul_q3_native / relax_dequant_matmul_q3 (3-bit weights) at n = 1 on the four matrix shapes of the 7B layer.
 All inputs are seeded and synthetic and resident in HBM before the timed region.
 """
 import argparse
@@ -659,7 +659,7 @@ def bench_half_sweep(args, np, torch, wl, rx):
 
 # ------------------------------------------------------------------------------------------------ 3-bit matvec
 def bench_q3_matvec(args, np, torch, wl, rx):
-    """relax_dequant_matmul_q3 at n = 1 on the four matrix shapes of the 7B layer (Sec. 5.3 of the paper deploys 3-bit models):
+    """relax_dequant_matmul_q3_native (and, beside it, relax_dequant_matmul_q3 on the canonical stream) at n = 1 on the four matrix shapes of the 7B layer (Sec. 5.3 of the paper deploys 3-bit models):
     HIP-event time per launch on the launch stream over rotating weight copies (each launch streams its matrix from HBM),
     algorithmic bytes = 3-bit codes + fp16 scales + x + out.  The CPU leg times the numpy reference on a row sample of the
     gate/up matrix and checks the GPU's outputs for those rows against it."""
@@ -674,27 +674,36 @@ def bench_q3_matvec(args, np, torch, wl, rx):
         qs = [torch.randint(-2 ** 31, 2 ** 31 - 1, (m, 3 * k // 32), dtype=torch.int32, device="cuda") for _ in range(copies)]
         ss = [(torch.rand((m, k // 32), device="cuda") * 0.01 + 0.002).to(torch.float16) for _ in range(copies)]
         mats = [rx.QMat(q, s, m, k) for q, s in zip(qs, ss)]
+        nqs = [torch.empty_like(q) for q in qs]
+        for mat, nq in zip(mats, nqs):
+            rx.check(rx.relax_repack_q3(mat, nq, stream), "relax_repack_q3")
+        nmats = [rx.QMat(nq, s, m, k) for nq, s in zip(nqs, ss)]
         x = torch.randn((1, k), device="cuda", dtype=torch.float16)
         out = torch.empty((1, m), dtype=torch.float16, device="cuda")
-        for i in range(warmup + 2 * copies):
-            rx.check(rx.relax_dequant_matmul_q3(x, mats[i % copies], out, 1, stream))
-        start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        stream.synchronize()
-        start.record(stream)
-        for i in range(steps):
-            rx.relax_dequant_matmul_q3(x, mats[i % copies], out, 1, stream)
-        stop.record(stream)
-        stream.synchronize()
-        us = start.elapsed_time(stop) * 1e3 / steps
         alg = wbytes + k * 2 + m * 2
-        table[name] = {"us_per_launch": round(us, 2), "algorithmic_MB": round(alg / 1e6, 2), "GBps": round(alg / us / 1e3, 1),
-                       "frac_of_peak": round(alg / us / 1e3 / PEAK_HBM_GBS, 4), "weight_copies": copies}
-        if keep is None:
-            rx.check(rx.relax_dequant_matmul_q3(x, mats[0], out, 1, stream))
+        row = {"algorithmic_MB": round(alg / 1e6, 2), "weight_copies": copies}
+        for layout, fn, ms_ in (("native", rx.relax_dequant_matmul_q3_native, nmats), ("canonical", rx.relax_dequant_matmul_q3, mats)):
+            for i in range(warmup + 2 * copies):
+                rx.check(fn(x, ms_[i % copies], out, 1, stream))
+            start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             stream.synchronize()
+            start.record(stream)
+            for i in range(steps):
+                fn(x, ms_[i % copies], out, 1, stream)
+            stop.record(stream)
+            stream.synchronize()
+            us = start.elapsed_time(stop) * 1e3 / steps
+            row[layout] = {"us_per_launch": round(us, 2), "GBps": round(alg / us / 1e3, 1), "frac_of_peak": round(alg / us / 1e3 / PEAK_HBM_GBS, 4)}
+        table[name] = row
+        if keep is None:
+            outs = []
+            for fn, mat in ((rx.relax_dequant_matmul_q3_native, nmats[0]), (rx.relax_dequant_matmul_q3, mats[0])):
+                rx.check(fn(x, mat, out, 1, stream))
+                stream.synchronize()
+                outs.append(out[0, :2048].float().cpu().numpy())
             keep = (m, k, qs[0][:2048].cpu().numpy().view(np.uint32), ss[0][:2048].cpu().numpy().view(np.uint16),
-                    x.cpu().numpy().astype(np.float32), out[0, :2048].float().cpu().numpy())
-        del qs, ss, mats
+                    x.cpu().numpy().astype(np.float32), outs)
+        del qs, ss, mats, nqs, nmats
     cpu = None
     if args.cpu_seconds > 0:
         from oracle import q3                               # the CPU reference: baseline and check only
@@ -704,16 +713,17 @@ def bench_q3_matvec(args, np, torch, wl, rx):
             ref = q3.dequant_matmul_q3(xh, qh, sh, 2048, k)[0]
             reps += 1
         sec = (time.perf_counter() - t0) / reps
-        err = np.abs(got - ref)
-        assert np.all(err <= 1e-2 + 2e-2 * np.abs(ref)), "3-bit matvec differs from the reference: max err %g" % err.max()
+        for one in got:                                     # native layout (repacked from the same codes), then canonical
+            err = np.abs(one - ref)
+            assert np.all(err <= 1e-2 + 2e-2 * np.abs(ref)), "3-bit matvec differs from the reference: max err %g" % err.max()
         sample_bytes = 2048 * (k * 3 // 8 + (k // 32) * 2)
         cpu = {"value": round(sample_bytes / sec / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
                "sample": "rows 0..2047 of the gate/up matrix, %d repetitions of the numpy reference (%.2f s each); the GPU's outputs for those rows checked against it" % (reps, sec)}
-    g = table["gate_up 22016x4096"]
+    g = dict(table["gate_up 22016x4096"]["native"], algorithmic_MB=table["gate_up 22016x4096"]["algorithmic_MB"])
     emit(args, "3-bit matvec, algorithmic GB/s on the 7B gate/up shape (22016 x 4096, n = 1)", "GB/s", g["GBps"], g["us_per_launch"] / 1e3,
          "f16 (3-bit weights, f32 accumulate)",
-         {"workload": "3-bit group-32 weights, n = 1, the four matrix shapes of the 7B layer, rotating weight copies", "build_id": rx.relax_build_id()},
-         {"bound": "hbm", "kernel": "gemv_q3_kernel<2> (22016 x 4096)", "achieved": g["GBps"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
+         {"workload": "3-bit group-32 weights in the native word layout (repacked once from the canonical stream), n = 1, the four matrix shapes of the 7B layer, rotating weight copies; the canonical-layout kernel timed beside it", "build_id": rx.relax_build_id()},
+         {"bound": "hbm", "kernel": "gemv_q3n_kernel (22016 x 4096)", "achieved": g["GBps"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
           "frac": g["frac_of_peak"], "traffic": None, "algorithmic_bytes_per_launch": int(g["algorithmic_MB"] * 1e6), "avg_launch_ms": g["us_per_launch"] / 1e3},
          cpu, {"q3_matvec": table})
 

@@ -2,15 +2,20 @@
 //
 // At large n the contraction is dense and MFMA-bound (Relax, Sec. 5.1: library-grade GEMM for batch sizes
 // other than 1; Sec. 4.2: the 4-bit decode stays fused into the matmul).  Mapping for gfx950:
-//   - v_mfma_f32_32x32x16_f16, fp32 accumulate.  A workgroup is four wavefronts (2 x 2), one per SIMD, so a
-//     wavefront may use all 512 registers of its lane: its tile is 128 weight rows x 128 x-rows = 16 MFMA tiles
-//     = 256 accumulator registers, and every 16-byte LDS fragment read feeds four MFMAs.
+//   - v_mfma_f32_32x32x16_f16, fp32 accumulate.  The wide tiles (256 x 256 and 128 x 256, weight rows x x-rows) run as
+//     eight wavefronts, two per SIMD with up to 256 registers each (64 x 128 or 64 x 64 outputs per wavefront), so that
+//     one wavefront's decode, LDS traffic and waits run under the other's MFMAs; the narrow tiles and the fp16-weight
+//     variant run as four wavefronts (2 x 2), one per SIMD.
 //   - Both operands go through LDS in 64-wide k blocks, double buffered with ONE LDS-only barrier per block
 //     (global loads of the next block stay in flight across it).  The packed weights are decoded on the way in,
-//     once per workgroup: a thread loads 32 bytes of codes and the two group scales of one weight row, turns
-//     them into 64 fp16 values and writes them to LDS.  Decode = merge the nibbles into the mantissa of fp16
+//     once per workgroup: every thread loads its share of the codes and the group scale of one weight row, turns
+//     them into fp16 values and writes them to LDS.  Decode = merge the nibbles into the mantissa of fp16
 //     1024.0, remove the offset exactly (1024+u-1032, (1024+16u)/16-72), multiply by the group scale: 13
-//     packed-fp16 VALU ops per 8 weights, which the scheduler places between the MFMAs of the current block.
+//     packed-fp16 VALU ops per 8 weights.  A quarter of a block's loads, decode and LDS writes is placed next to the
+//     MFMAs of each of its four k steps.
+//   - What bounds it: with realistic operand values the matrix pipes of this chip run well below the rate they reach on
+//     all-zero operands (the vendor's fp16 GEMM: 1.5 against 2.3 PFLOP/s at 8192^3; 0.86 to 1.19 PFLOP/s on the four
+//     shapes of the 7B layer at n = 2048), so timing a variant on dummy LDS contents says nothing about its staging cost.
 //   - Each 8-wide k packet is kept in LDS in the order [e0 e4 e1 e5 e2 e6 e3 e7] -- the nibble pairs the decode
 //     produces; the x tile is permuted the same way when it is staged.  The order of k inside an MFMA is free
 //     as long as A and B agree.  Rows are padded to 144 bytes: 16-byte reads and writes of consecutive rows hit
@@ -109,15 +114,16 @@ struct GemmArgs {
 template <int EPI, int MF, int NF, bool FP16W = false, int WM = 2, int WN = 2>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_q4_mfma_kernel(GemmArgs a)
 {
+    constexpr int ST = 2;                                 // register stages; four were measured and gained nothing
     constexpr int kThreadsG = WM * WN * 64;
     constexpr int BM = 32 * MF * WM, BN = 32 * NF * WN;
-    // packed words a thread decodes per k block: its share of the BM x 8 words of the weight tile, but never fewer than one
-    // 16-byte load's worth -- with a narrow weight tile only the first kAThreads threads (whole wavefronts) stage weights
-    constexpr int W = (BM * 8 / kThreadsG) < 4 ? 4 : BM * 8 / kThreadsG;
-    constexpr int kAThreads = BM * 8 / W;
+    // packed words a thread decodes per k block: its share of the BM x 8 words of the weight tile (2, 4 or 8: every thread
+    // stages weights, so the staging has no branch for the compiler's wait-count pass to merge across)
+    constexpr int W = BM * 8 / kThreadsG;
     constexpr int TPR = 8 / W;                            // threads per weight row
     constexpr int XP = BN * 8 / kThreadsG;                // 16-byte x packets a thread stages per k block
-    static_assert(kAThreads % 64 == 0 && kAThreads <= kThreadsG && XP >= 1, "staging roles");
+    static_assert((W == 2 || W == 4 || W == 8) && XP >= 1, "staging roles");
+    constexpr int WV = W < 4 ? 1 : W / 4;                 // 16-byte (W = 2: 8-byte) loads of packed words per thread and k block
     constexpr int kABuf = BM * kPitch, kBBuf = BN * kPitch;
     extern __shared__ __align__(16) uint16_t lds[];       // A[2][BM][kPitch], B[2][BN][kPitch]
     uint16_t *const As = lds, *const Bs = lds + 2 * kABuf;
@@ -136,8 +142,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_q4_mfma_kernel(GemmArgs a)
     const int F = a.m >> 1;
 
     // ---- staging roles ----
-    const bool a_on = tid < kAThreads;                    // wave-uniform
-    const int arow = (tid % kAThreads) / TPR, aword0 = (tid % TPR) * W;
+    const int arow = tid / TPR, aword0 = (tid % TPR) * W;
     int grow;
     if (EPI == EPI_SWIGLU) {
         const int g0 = tile_m * (BM / 2);
@@ -158,34 +163,59 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_q4_mfma_kernel(GemmArgs a)
 
     // Staged registers of one k block: packed codes + scales of this thread's weight row part, and its x packets.
     struct Stage {
-        uint4 wq[FP16W ? W : W / 4];                      // packed words, or one 16-byte packet of fp16 weights per word
+        uint4 wq[FP16W ? W : WV];                         // packed words (W = 2: in .x, .y), or one 16-byte packet of fp16 weights per word
         uint32_t wsc;
         uint4 xr[XP];
     };
     const int kb0 = split * a.kb_per_split;               // this workgroup's k range: blocks kb0 .. kb0 + nkb - 1
     const int nkb = min(a.kb_per_split, a.k / BK - kb0);
-    auto stage_load = [&](Stage &S, int kb) {             // kb is clamped: the tail re-reads the last block (never consumed)
+    // The loads of k block kb, in four shares: share `part` is issued next to k step `part` of the running block -- a
+    // workgroup that issued all its loads in one burst at the top of a block filled the address queue of the texture unit and
+    // stalled in front of its own MFMAs.  Loads return in order, so the order of issue is what the wait counts stand on:
+    // weights first (the decode of share 0 needs them first), then per share the x packets.
+    auto stage_load = [&](Stage &S, int kb, int part) {   // kb is clamped: the tail re-reads the last block (never consumed)
         kb = kb0 + min(kb, nkb - 1);
         if (FP16W) {
 #pragma unroll
-            for (int i = 0; i < W; ++i) S.wq[i] = *(const uint4 *)(hsrc + kb * BK + i * 8);
+            for (int i = 0; i < W; ++i)
+                if (i * 4 / W == part) S.wq[i] = *(const uint4 *)(hsrc + kb * BK + i * 8);
         } else {
 #pragma unroll
-            for (int i = 0; i < W / 4; ++i) S.wq[i] = *(const uint4 *)(qsrc + kb * (BK / 8) + i * 4);
-            // scale of sub-group g: ssrc[g >> gshift] (neighbouring sub-groups share it when the group is wider than 32)
-            const int g = kb * (BK / 32) + sub0;
-            if (W == 8) S.wsc = (uint32_t)ssrc[g >> a.gshift] | ((uint32_t)ssrc[(g + 1) >> a.gshift] << 16);
-            else S.wsc = ssrc[g >> a.gshift];
+            for (int i = 0; i < WV; ++i) {
+                if (i * 2 != part) continue;
+                if (W == 2) {
+                    const uint2 two = *(const uint2 *)(qsrc + kb * (BK / 8));
+                    S.wq[0].x = two.x, S.wq[0].y = two.y;
+                } else {
+                    S.wq[i] = *(const uint4 *)(qsrc + kb * (BK / 8) + i * 4);
+                }
+            }
+            if (part == 1) {
+                // scale of sub-group g: ssrc[g >> gshift] (neighbouring sub-groups share it when the group is wider than 32)
+                const int g = kb * (BK / 32) + sub0;
+                if (W == 8) S.wsc = (uint32_t)ssrc[g >> a.gshift] | ((uint32_t)ssrc[(g + 1) >> a.gshift] << 16);
+                else S.wsc = ssrc[g >> a.gshift];
+            }
         }
 #pragma unroll
-        for (int p = 0; p < XP; ++p) S.xr[p] = *(const uint4 *)(xsrc[p] + kb * BK);
+        for (int p = 0; p < XP; ++p)
+            if (p * 4 / XP == part) S.xr[p] = *(const uint4 *)(xsrc[p] + kb * BK);
+    };
+    // a whole block's loads in the order the running loop issues them (prologue): the compiler's wait counts at the loop
+    // head are the merge of this order and the loop's own, so the two must agree or every wait in the loop is pessimistic
+    auto stage_load_all = [&](Stage &S, int kb) {
+#pragma unroll
+        for (int part = 0; part < 4; ++part) {
+            stage_load(S, kb, part);
+            __builtin_amdgcn_sched_barrier(0);
+        }
     };
     // quarter `part` (0..3) of the decode + LDS write of a staged block
     auto stage_store = [&](const Stage &S, int buf, int part) {
         uint16_t *ad = As + buf * kABuf + arow * kPitch + aword0 * 8;
 #pragma unroll
         for (int i = 0; i < W; ++i) {
-            if (i * 4 / W != part || !a_on) continue;
+            if (i * 4 / W != part) continue;
             if (FP16W) {                                  // same packet order as the decode and the x tile
                 const uint4 &h = S.wq[FP16W ? i : 0];
                 uint4 o;
@@ -244,7 +274,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_q4_mfma_kernel(GemmArgs a)
     // One k block: MFMAs on LDS buffer `buf` while the staged block S is decoded into the other buffer.  The
     // fragments of k step ks+1 are requested before the MFMAs of step ks are issued, and a quarter of the decode
     // is placed next to each step's MFMAs; the scheduling fences keep the compiler from undoing either.
-    auto block = [&](int buf, const Stage &S) {
+    auto block = [&](int buf, const Stage &S, Stage &L, int kb_load) {
         const uint16_t *ab = As + buf * kABuf, *bb = Bs + buf * kBBuf + bfrag_off;
         half8_t af[2][MF], bf[2][NF];
 #pragma unroll
@@ -268,26 +298,29 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_q4_mfma_kernel(GemmArgs a)
                 for (int f = 0; f < MF; ++f)
                     acc[f][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[cur][f], bf[cur][j], acc[f][j], 0, 0, 0);
             if (WM * WN > 4) __builtin_amdgcn_s_setprio(0);
+            stage_load(L, kb_load, ks);
             stage_store(S, buf ^ 1, ks);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
 
-    // Software pipeline over k blocks, two register stages deep: the global loads of block kb+2 are issued at the
-    // top of block kb and consumed (decoded into LDS) during block kb+1, a full block of MFMAs later.
-    Stage S0, S1;
-    stage_load(S0, 0);
+    // Software pipeline over k blocks, ST register stages deep: the global loads of block kb+ST are issued during block kb
+    // (a share next to each k step) into the stage whose block was decoded during block kb-1, and are consumed (decoded
+    // into LDS) during block kb+ST-1, ST-1 blocks of MFMAs later (the k blocks of a workgroup are a multiple of ST).
+    Stage S[ST];
+    stage_load_all(S[0], 0);
 #pragma unroll
-    for (int part = 0; part < 4; ++part) stage_store(S0, 0, part);
+    for (int part = 0; part < 4; ++part) stage_store(S[0], 0, part);
     lds_barrier();
-    stage_load(S1, 1);
-    for (int kb = 0; kb < nkb; kb += 2) {                 // nkb is even (k % 128 == 0)
-        stage_load(S0, kb + 2);
-        block(0, S1);                                     // MFMAs on buffer 0 (block kb), block kb+1 -> buffer 1
-        lds_barrier();
-        stage_load(S1, kb + 3);
-        block(1, S0);                                     // MFMAs on buffer 1 (block kb+1), block kb+2 -> buffer 0
-        lds_barrier();
+#pragma unroll
+    for (int d = 1; d < ST; ++d) stage_load_all(S[d], d);
+    for (int kb = 0; kb < nkb; kb += ST) {
+#pragma unroll
+        for (int b = 0; b < ST; ++b) {
+            // MFMAs on buffer b & 1 (block kb+b), block kb+b+1 decoded into the other buffer, loads of block kb+b+ST
+            block(b & 1, S[(b + 1) % ST], S[b], kb + b + ST);
+            lds_barrier();
+        }
     }
 
     // ---- epilogue.  acc[f][j][v]: tile row of fragment f + 8 (v/4) + 4 (lane/32) + v%4, x row n0 + 32 (NF wn + j) + lane%32 ----
@@ -443,14 +476,15 @@ TilePlan tile_plan(int m, int k, int n, int epi)
     const long kCUs = 256;
     TilePlan p = {2, 1, 1, k / BK};
     if (n > 128) {
-        // useful share of the workgroup rounds: padding rows of ragged tiles and idle CUs of the last round both count as waste;
-        // the 128 x 128 tile pays about a fifth more LDS traffic per MFMA than the two wide ones
+        // useful share of the workgroup rounds: padding rows of ragged tiles and idle CUs of the last round both count as waste,
+        // weighted by what a tile shape reaches per MFMA when the CUs are full (measured on the 7B shapes at n = 2048: the
+        // 128 x 256 tile stages the same x tile and pays the same barrier per k block for half the MFMAs of the 256 x 256 one)
         auto score = [&](int mf, int nf, double tile_eff) {
             const long b = blocks(mf, nf);
             const double rounds = (double)((b + kCUs - 1) / kCUs);
             return tile_eff * (double)rows * (double)n / (rounds * kCUs * (64.0 * mf / rdiv) * (64.0 * nf));
         };
-        const double s44 = score(4, 4, 1.0), s24 = score(2, 4, 1.0), s22 = score(2, 2, 0.8);
+        const double s44 = score(4, 4, 1.0), s24 = score(2, 4, 0.65), s22 = score(2, 2, 0.5);
         if (s44 >= s24 && s44 >= s22) p.mf = 4, p.nf = 4;
         else if (s24 >= s22) p.mf = 2, p.nf = 4;
         else p.mf = 2, p.nf = 2;
