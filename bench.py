@@ -817,12 +817,32 @@ def bench_ceilings(args, np, torch, wl, rx):
         chain["%d MB" % mb] = round(a.elapsed_time(b) * 1e3 / (10 * nl), 2)
     slope = (96 - 48) * (1 << 20) / ((chain["96 MB"] - chain["48 MB"]) * 1e-6) / 1e9
     chain_out = {"us_per_dependent_launch": chain, "fixed_us": chain["0 MB"], "slope_GBps": round(slope, 1)}
+    # The vendor's fp16 GEMM (torch.matmul, i.e. hipBLASLt / rocBLAS: fp16 weights, no decode) on the four matrix shapes of the
+    # 7B layer at n = 2048 and on 8192^3, with normally distributed and with all-zero operands: the matrix pipes of this
+    # chip clock down with the bit activity of their operands, so the second figure is not reachable on real data.  Context
+    # for the tiled int4 GEMM only; nothing of the product calls it.
+    del bufs
+    torch.manual_seed(0)
+    vendor = {}
+    for name, (n, m, k) in (("gate_up 22016x4096", (2048, 22016, 4096)), ("qkv 12288x4096", (2048, 12288, 4096)), ("down 4096x11008", (2048, 4096, 11008)),
+                            ("o_proj 4096x4096", (2048, 4096, 4096)), ("square 8192", (8192, 8192, 8192))):
+        row = {}
+        for kind in ("normal", "zeros"):
+            if kind == "normal":
+                xa = torch.randn(n, k, device="cuda", dtype=torch.float16)
+                wa = (torch.randn(m, k, device="cuda") * 0.02).to(torch.float16)
+            else:
+                xa, wa = torch.zeros(n, k, device="cuda", dtype=torch.float16), torch.zeros(m, k, device="cuda", dtype=torch.float16)
+            ms = timed(lambda i: torch.matmul(xa, wa.t()), 20)
+            row[kind] = {"us": round(ms * 1e3, 1), "TFLOPs": round(2.0 * n * m * k / ms / 1e9, 1)}
+        vendor[name] = row
     emit(args, "device ceilings: streaming read GB/s, MFMA loop TFLOP/s", "GB/s", ach, ms_read, "u32x4 loads / f16 MFMA",
          {"workload": "ceilings: relax_probe_stream_read over 1 GiB (two buffers alternated) and relax_probe_mfma (16 independent "
                       "32x32x16 f16 MFMAs per wavefront and iteration, 4 wavefronts per CU, 4000 iterations)", "build_id": rx.relax_build_id()},
          {"bound": "hbm", "kernel": "stream_read_kernel", "achieved": round(ach, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
           "frac": round(ach / PEAK_HBM_GBS, 4), "traffic": None},
-         None, {"mfma_loop_TFLOPs": out, "mfma_published_peak_TFLOPs": PEAK_MFMA_TFLOPS, "stream_chain": chain_out})
+         None, {"mfma_loop_TFLOPs": out, "mfma_published_peak_TFLOPs": PEAK_MFMA_TFLOPS, "stream_chain": chain_out,
+                "vendor_fp16_gemm_n2048": vendor})
 
 
 def main():
