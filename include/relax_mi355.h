@@ -148,7 +148,7 @@ size_t relax_workspace_bytes(const relax_layer_dims *dims, int32_t n_max, int32_
  * relax_workspace_plan reports that plan for one (n, L, B): one entry per tensor (operations of the layer:
  * 1 QKV + rotary + append, 2 attention, 3 output projection, 4 second norm, 5 gate/up, 6 down), `offset` in bytes
  * from the start of the workspace, and the bytes of the planned region with and without reuse (every storage,
- * resp. tensor, rounded up to 256 bytes; the fixed front part of the workspace -- fused-kernel state and the
+ * resp. tensor, rounded up to 256 bytes; the fixed front part of the workspace -- the flag line and the
  * descriptor table -- is in neither).  entries may be NULL (sizes only); capacity < *count: RELAX_ERR_WORKSPACE.
  * Host-only: nothing is enqueued.                                                                                */
 typedef struct {
