@@ -2,10 +2,11 @@
 //
 // At large n the contraction is dense and MFMA-bound (Relax, Sec. 5.1: library-grade GEMM for batch sizes
 // other than 1; Sec. 4.2: the 4-bit decode stays fused into the matmul).  Mapping for gfx950:
-//   - v_mfma_f32_32x32x16_f16, fp32 accumulate.  The wide tiles (256 x 256 and 128 x 256, weight rows x x-rows) run as
-//     eight wavefronts, two per SIMD with up to 256 registers each (64 x 128 or 64 x 64 outputs per wavefront), so that
-//     one wavefront's decode, LDS traffic and waits run under the other's MFMAs; the narrow tiles and the fp16-weight
-//     variant run as four wavefronts (2 x 2), one per SIMD.
+//   - v_mfma_f32_32x32x16_f16, fp32 accumulate.  The 256 x 256 tile (weight rows x x-rows) runs as eight wavefronts,
+//     two per SIMD with up to 256 registers each (64 x 128 outputs per wavefront), so that one wavefront's decode, LDS
+//     traffic and waits run under the other's MFMAs; the narrower tiles and the fp16-weight variant run as four
+//     wavefronts (2 x 2), one per SIMD (128 x 256 as eight wavefronts of 64 x 64 was measured 4 to 11 % slower than as
+//     four of 64 x 128: twice the fragment reads per MFMA).
 //   - Both operands go through LDS in 64-wide k blocks, double buffered with ONE LDS-only barrier per block
 //     (global loads of the next block stay in flight across it).  The packed weights are decoded on the way in,
 //     once per workgroup: every thread loads its share of the codes and the group scale of one weight row, turns
@@ -108,7 +109,7 @@ struct GemmArgs {
 // FP16W: the weights are plain fp16 (the fp16-weight configurations of the paper's LLM charts, Sec. 5.1): the staging copies
 // 16-byte packets instead of decoding words, everything else is the same kernel.
 // WM x WN: wavefronts along the weight rows and along the x rows.  2 x 2: four wavefronts, one per SIMD, each with up to 512
-// registers.  4 x 2 and 2 x 4: eight wavefronts, two per SIMD with up to 256 registers each, so that one wavefront's decode, LDS
+// registers.  4 x 2: eight wavefronts, two per SIMD with up to 256 registers each, so that one wavefront's decode, LDS
 // traffic and waits run under the other's MFMAs (with one wavefront per SIMD the matrix pipe was busy 37 % of the time:
 // counters in profiles/).
 template <int EPI, int MF, int NF, bool FP16W = false, int WM = 2, int WN = 2>
@@ -478,13 +479,13 @@ TilePlan tile_plan(int m, int k, int n, int epi)
     if (n > 128) {
         // useful share of the workgroup rounds: padding rows of ragged tiles and idle CUs of the last round both count as waste,
         // weighted by what a tile shape reaches per MFMA when the CUs are full (measured on the 7B shapes at n = 2048: the
-        // 128 x 256 tile stages the same x tile and pays the same barrier per k block for half the MFMAs of the 256 x 256 one)
+        // 128 x 256 tile as four wavefronts reaches about nine tenths of the 256 x 256 tile as eight)
         auto score = [&](int mf, int nf, double tile_eff) {
             const long b = blocks(mf, nf);
             const double rounds = (double)((b + kCUs - 1) / kCUs);
             return tile_eff * (double)rows * (double)n / (rounds * kCUs * (64.0 * mf / rdiv) * (64.0 * nf));
         };
-        const double s44 = score(4, 4, 1.0), s24 = score(2, 4, 0.65), s22 = score(2, 2, 0.5);
+        const double s44 = score(4, 4, 1.0), s24 = score(2, 4, 0.9), s22 = score(2, 2, 0.6);
         if (s44 >= s24 && s44 >= s22) p.mf = 4, p.nf = 4;
         else if (s24 >= s22) p.mf = 2, p.nf = 4;
         else p.mf = 2, p.nf = 2;
@@ -561,7 +562,7 @@ hipError_t launch_gemm_mfma(const uint16_t *x, const relax_qmat &w, int n, int e
     hipError_t e;
     const bool eight = g_waves_per_simd.load() == 2;
     if (p.mf == 4) e = eight ? launch_tile<2, 4, false, 4, 2>(a, stream, p.splits) : launch_tile<4, 4>(a, stream, p.splits);
-    else if (p.nf == 4) e = eight ? launch_tile<2, 2, false, 2, 4>(a, stream, p.splits) : launch_tile<2, 4>(a, stream, p.splits);
+    else if (p.nf == 4) e = launch_tile<2, 4>(a, stream, p.splits);        // 128 x 256: four wavefronts of 64 x 128 beat eight of 64 x 64 by 4 to 11 %
     else if (p.nf == 2) e = launch_tile<2, 2>(a, stream, p.splits);
     else e = launch_tile<2, 1>(a, stream, p.splits);
     if (e != hipSuccess || p.splits < 2) return e;
