@@ -415,23 +415,23 @@ hipError_t launch_tile(const GemmArgs &a_in, hipStream_t stream, int splits)
     if (splits < 2) a.partial = nullptr, a.kb_per_split = nkb, splits = 1;
     dim3 grid(tiles * splits);
     const size_t lds = 2 * (size_t)(BM + BN) * kPitch * sizeof(uint16_t);    // up to 147456 bytes: one workgroup per CU
-    static bool attr_done = false;
+    static std::atomic<bool> attr_done{false};   // setting the attribute twice is harmless; the flag only has to be a defined read
     if constexpr (FP16W) {
         if (a.epi != EPI_F16 || splits != 1) return hipErrorInvalidValue;
-        if (!attr_done) {
+        if (!attr_done.load()) {
             if (hipFuncSetAttribute((const void *)gemm_q4_mfma_kernel<EPI_F16, MF, NF, true, WM, WN>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
                 return hipErrorInvalidValue;
-            attr_done = true;
+            attr_done.store(true);
         }
         hipLaunchKernelGGL((gemm_q4_mfma_kernel<EPI_F16, MF, NF, true, WM, WN>), grid, dim3(kThreadsG), lds, stream, a);
         return hipGetLastError();
     }
-    if (!attr_done) {
+    if (!attr_done.load()) {
         const void *ks[4] = {(const void *)gemm_q4_mfma_kernel<EPI_F16, MF, NF, false, WM, WN>, (const void *)gemm_q4_mfma_kernel<EPI_RESID_F32, MF, NF, false, WM, WN>,
                              (const void *)gemm_q4_mfma_kernel<EPI_RESID_F16, MF, NF, false, WM, WN>, (const void *)gemm_q4_mfma_kernel<EPI_SWIGLU, MF, NF, false, WM, WN>};
         for (const void *kf : ks)
             if (hipFuncSetAttribute(kf, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) return hipErrorInvalidValue;
-        attr_done = true;
+        attr_done.store(true);
     }
     switch (a.epi) {
     case EPI_F16: hipLaunchKernelGGL((gemm_q4_mfma_kernel<EPI_F16, MF, NF, false, WM, WN>), grid, dim3(kThreadsG), lds, stream, a); break;

@@ -17,6 +17,8 @@
 //     several times over even when m is small; every task writes its fp32 partial tile to the workspace and a small
 //     finishing kernel adds the partials IN A FIXED ORDER and applies the epilogue (plain fp16, residual adds,
 //     SwiGLU).  No atomics: results are reproducible run to run.
+#include <atomic>
+
 #include "relax_common.h"
 
 namespace relax {
@@ -429,11 +431,11 @@ template <int NF, int XR, int KR>
 hipError_t launch_skinny(const SkinnyArgs &a, dim3 grid, hipStream_t stream)
 {
     const size_t lds = (size_t)2 * XR * (KR + 8) * sizeof(uint16_t) + (size_t)kRowsPerBlock * (a.rounds_per_split * KR / 256 * 8 + 8) * sizeof(uint16_t);
-    static bool attr_done = false;
-    if (!attr_done) {
+    static std::atomic<bool> attr_done{false};   // setting the attribute twice is harmless; the flag only has to be a defined read
+    if (!attr_done.load()) {
         if (hipFuncSetAttribute((const void *)skinny_q4_kernel<NF, XR, KR>, hipFuncAttributeMaxDynamicSharedMemorySize, 112 * 1024) != hipSuccess)
             return hipErrorInvalidValue;
-        attr_done = true;
+        attr_done.store(true);
     }
     hipLaunchKernelGGL((skinny_q4_kernel<NF, XR, KR>), grid, dim3(256), lds, stream, a);
     return hipGetLastError();

@@ -2,6 +2,8 @@
 // sequence, fp16 LM head, greedy pick).  At decode the LM head is one more HBM stream per token (vocab x hidden
 // fp16, 262 MB for the 7B shape): the same batch-1 matrix-vector special case the paper singles out (Relax,
 // Sec. 5.1), here with unquantised weights.
+#include <atomic>
+
 #include "relax_common.h"
 
 namespace relax {
@@ -208,11 +210,11 @@ template <int NB>
 hipError_t launch_lm_pass(const uint16_t *xn, const uint16_t *W, uint16_t *logits, int b0, int H, int V, int blocks, hipStream_t stream)
 {
     const size_t lds = (size_t)NB * H * sizeof(uint16_t);
-    static bool attr_done = false;
-    if (!attr_done) {
+    static std::atomic<bool> attr_done{false};   // setting the attribute twice is harmless; the flag only has to be a defined read
+    if (!attr_done.load()) {
         if (hipFuncSetAttribute((const void *)lm_head_kernel<NB>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
             return hipErrorInvalidValue;
-        attr_done = true;
+        attr_done.store(true);
     }
     hipLaunchKernelGGL(lm_head_kernel<NB>, dim3(blocks), dim3(256), lds, stream, xn, W, logits, b0, H, V);
     return hipGetLastError();
