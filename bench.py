@@ -704,6 +704,28 @@ def bench_q3_matvec(args, np, torch, wl, rx):
             keep = (m, k, qs[0][:2048].cpu().numpy().view(np.uint32), ss[0][:2048].cpu().numpy().view(np.uint16),
                     x.cpu().numpy().astype(np.float32), outs)
         del qs, ss, mats, nqs, nmats
+    # the same format at n = 2048: from 16 rows on the native-layout call goes through the tiled MFMA GEMM
+    gemm = {}
+    for name, (m, k) in (("gate_up 22016x4096", (22016, 4096)), ("qkv 12288x4096", (12288, 4096)), ("down 4096x11008", (4096, 11008)),
+                         ("o_proj 4096x4096", (4096, 4096))):
+        n = 2048
+        nq = torch.randint(-2 ** 31, 2 ** 31 - 1, (m, 3 * k // 32), dtype=torch.int32, device="cuda")
+        sc = (torch.rand((m, k // 32), device="cuda") * 0.01 + 0.002).to(torch.float16)
+        xb = torch.randn((n, k), device="cuda", dtype=torch.float16)
+        ob = torch.empty((n, m), dtype=torch.float16, device="cuda")
+        mat = rx.QMat(nq, sc, m, k)
+        for _ in range(3):
+            rx.check(rx.relax_dequant_matmul_q3_native(xb, mat, ob, n, stream))
+        start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        stream.synchronize()
+        start.record(stream)
+        for _ in range(20):
+            rx.relax_dequant_matmul_q3_native(xb, mat, ob, n, stream)
+        stop.record(stream)
+        stream.synchronize()
+        us = start.elapsed_time(stop) * 1e3 / 20
+        gemm[name] = {"us_per_launch": round(us, 1), "TFLOPs": round(2.0 * n * m * k / us / 1e6, 1), "frac_of_mfma_peak": round(2.0 * n * m * k / us / 1e6 / PEAK_MFMA_TFLOPS, 4)}
+        del nq, sc, xb, ob, mat
     cpu = None
     if args.cpu_seconds > 0:
         from oracle import q3                               # the CPU reference: baseline and check only
@@ -725,7 +747,7 @@ def bench_q3_matvec(args, np, torch, wl, rx):
          {"workload": "3-bit group-32 weights in the native word layout (repacked once from the canonical stream), n = 1, the four matrix shapes of the 7B layer, rotating weight copies; the canonical-layout kernel timed beside it", "build_id": rx.relax_build_id()},
          {"bound": "hbm", "kernel": "gemv_q3n_kernel (22016 x 4096)", "achieved": g["GBps"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
           "frac": g["frac_of_peak"], "traffic": None, "algorithmic_bytes_per_launch": int(g["algorithmic_MB"] * 1e6), "avg_launch_ms": g["us_per_launch"] / 1e3},
-         cpu, {"q3_matvec": table})
+         cpu, {"q3_matvec": table, "q3_gemm_n2048": gemm})
 
 
 # ------------------------------------------------------------------------------------------------ memory plan

@@ -320,9 +320,12 @@ relax_status relax_dequant_matmul_q3(const uint16_t *x, const relax_qmat *w, uin
  * relax_repack_q3: canonical q (as above) -> native_q, device uint32 [m][3k/32] owned by the caller, not in place; a
  * one-time step at load time (Sec. 4.6: weights are prepared once for the kernels that serve them).
  * relax_unpack_q3_native: out int8 [m,k] in -4..3 from a native matrix -- equals relax_unpack_q3 of the canonical one.
- * relax_dequant_matmul_q3_native: out[n,m] fp16 = x[n,k] times the decoded native matrix, fp32 accumulation.  Rows of
- * x are taken 4, 2 or 1 per pass over the matrix (k <= 4096: 4; k <= 8192: 2), the decode of a weight shared by the
- * rows of a pass, so a few rows cost little more than one.  k <= 12288, x 16-byte aligned; errors as the canonical call. */
+ * relax_dequant_matmul_q3_native: out[n,m] fp16 = x[n,k] times the decoded native matrix, fp32 accumulation.  Up to 15
+ * rows of x are taken 4, 2 or 1 per pass over the matrix (k <= 4096: 4; k <= 8192: 2), the decode of a weight shared
+ * by the rows of a pass, so a few rows cost little more than one (k <= 12288).  From 16 rows on, a matrix with
+ * k % 128 == 0 and m % 4 == 0 (out 8-byte aligned) goes through the tiled MFMA GEMM that serves the 4-bit format at
+ * large n, its decode step replaced by the 3-bit one: the matrix is read once whatever n is, and k is not limited.
+ * x 16-byte aligned; errors as the canonical call. */
 relax_status relax_repack_q3(const relax_qmat *canonical, uint32_t *native_q, relax_stream stream);
 relax_status relax_unpack_q3_native(const relax_qmat *w, int8_t *out, relax_stream stream);
 relax_status relax_dequant_matmul_q3_native(const uint16_t *x, const relax_qmat *w, uint16_t *out, int32_t n, relax_stream stream);

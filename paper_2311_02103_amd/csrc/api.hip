@@ -933,9 +933,13 @@ relax_status relax_dequant_matmul_q3_native(const uint16_t *x, const relax_qmat 
 {
     if (!x || !out || !w || !w->q || !w->s) return RELAX_ERR_NULL;
     if (n < 1 || n > 4 * 65535 || w->m < 1 || w->k < 32 || w->k % 32 != 0) return RELAX_ERR_SHAPE;
-    if (!gemv_q3_supported(w->m, w->k)) return RELAX_ERR_UNSUPPORTED;
     if ((reinterpret_cast<uintptr_t>(x) & 15) != 0 || (reinterpret_cast<uintptr_t>(w->q) & 3) != 0 || (reinterpret_cast<uintptr_t>(w->s) & 1) != 0)
         return RELAX_ERR_SHAPE;
+    // From kQ3GemmRows rows on the matrix is read once by the tiled MFMA GEMM (decode on the way into LDS); below that, or
+    // for a shape the GEMM does not take, it is streamed once per pass of up to four rows of x.
+    if (n >= kQ3GemmRows && gemm_q3_eligible(x, *w, out))
+        return hip_status(launch_gemm_q3(x, *w, n, out, static_cast<hipStream_t>(stream)));
+    if (!gemv_q3_supported(w->m, w->k)) return RELAX_ERR_UNSUPPORTED;
     return hip_status(launch_gemv_q3_native(x, *w, n, out, static_cast<hipStream_t>(stream)));
 }
 

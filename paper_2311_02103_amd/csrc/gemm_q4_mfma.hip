@@ -85,9 +85,43 @@ __device__ __forceinline__ half8_t decode_word(uint32_t w, uint32_t s2)
     return __builtin_bit_cast(half8_t, r);
 }
 
+// 3-bit weights in the native word layout (three words per group of 32 columns: word w, position j holds column 2(5w+j)
+// in bits 3j.. and column 2(5w+j)+1 in bits 16+3j..; bit i of columns 30 / 31 is bit 15 / 31 of word i): the four fp16 pairs
+// of packet t (columns 8t .. 8t+7 of the group, NATURAL order) times the group scale.  v_and_or_b32 merges a pair of codes
+// into the mantissas of fp16 (1024, 1024) at weight 1, 8 or 64; one packed fma removes offset and weight exactly
+// ((1024 + f u) / f - (1024 / f + 4) = u - 4), one packed multiply applies the scale.
+__device__ __forceinline__ half8_t decode_q3_packet(uint32_t w0, uint32_t w1, uint32_t w2, int t, uint32_t s2)
+{
+    const uint32_t base = 0x64006400u;
+    const uint32_t kOne = 0x3C003C00u, kEighth = 0x30003000u, k64th = 0x24002400u;          // 1, 1/8, 1/64
+    const uint32_t kNeg1028 = 0xE404E404u, kNeg132 = 0xD820D820u, kNeg20 = 0xCD00CD00u;     // -(1024 / f + 4)
+    uint32_t r[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int p = 4 * t + q;                              // pair p = columns 2p, 2p + 1
+        uint32_t pair;
+        int cls;                                              // 0: weight 1, 1: weight 8, 2: weight 64
+        if (p == 15) {
+            uint32_t g = and_or(w0 >> 15, 0x00010001u, base);
+            g = and_or(w1 >> 14, 0x00020002u, g);
+            pair = and_or(w2 >> 13, 0x00040004u, g), cls = 0;
+        } else {
+            const uint32_t w = p / 5 == 0 ? w0 : p / 5 == 1 ? w1 : w2;
+            const int j = p % 5;
+            const uint32_t v = j >= 3 ? w >> 9 : w;
+            cls = j >= 3 ? j - 3 : j;
+            pair = and_or(v, cls == 0 ? 0x00070007u : cls == 1 ? 0x00380038u : 0x01C001C0u, base);
+        }
+        const uint32_t scaled = cls == 0 ? pk_fma(pair, kOne, kNeg1028) : cls == 1 ? pk_fma(pair, kEighth, kNeg132) : pk_fma(pair, k64th, kNeg20);
+        r[q] = pk_mul(scaled, s2);
+    }
+    uint4 o = {r[0], r[1], r[2], r[3]};
+    return __builtin_bit_cast(half8_t, o);
+}
+
 struct GemmArgs {
     const uint16_t *x;       // [n,k] fp16
-    const uint32_t *q;       // [m,k/8]
+    const uint32_t *q;       // [m,k/8]; Q3 kernels: [m, 3 k / 32] words of the native 3-bit layout
     const uint16_t *s;       // [m, k / (32 << gshift)]
     int32_t gshift;          // 32-column sub-group index >> gshift = scale index (quantisation group 32, 64 or 128)
     const uint16_t *wh;      // FP16W kernels: plain fp16 weights [m,k] instead of q, s
@@ -112,9 +146,12 @@ struct GemmArgs {
 // registers.  4 x 2: eight wavefronts, two per SIMD with up to 256 registers each, so that one wavefront's decode, LDS
 // traffic and waits run under the other's MFMAs (with one wavefront per SIMD the matrix pipe was busy 37 % of the time:
 // counters in profiles/).
-template <int EPI, int MF, int NF, bool FP16W = false, int WM = 2, int WN = 2>
+// Q3: 3-bit weights in the native word layout (Sec. 5.3 of the paper deploys 3-bit models): a thread stages whole groups of 32
+// columns (three words), the decode yields the columns in natural order, so the x tile is staged unpermuted.
+template <int EPI, int MF, int NF, bool FP16W = false, int WM = 2, int WN = 2, bool Q3 = false>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_q4_mfma_kernel(GemmArgs a)
 {
+    static_assert(!(FP16W && Q3), "one weight format per kernel");
     constexpr int ST = 2;                                 // register stages; four were measured and gained nothing
     constexpr int kThreadsG = WM * WN * 64;
     constexpr int BM = 32 * MF * WM, BN = 32 * NF * WN;
@@ -124,6 +161,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_q4_mfma_kernel(GemmArgs a)
     constexpr int TPR = 8 / W;                            // threads per weight row
     constexpr int XP = BN * 8 / kThreadsG;                // 16-byte x packets a thread stages per k block
     static_assert((W == 2 || W == 4 || W == 8) && XP >= 1, "staging roles");
+    static_assert(!Q3 || W >= 4, "a thread stages whole 3-bit groups");
     constexpr int WV = W < 4 ? 1 : W / 4;                 // 16-byte (W = 2: 8-byte) loads of packed words per thread and k block
     constexpr int kABuf = BM * kPitch, kBBuf = BN * kPitch;
     extern __shared__ __align__(16) uint16_t lds[];       // A[2][BM][kPitch], B[2][BN][kPitch]
@@ -151,7 +189,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_q4_mfma_kernel(GemmArgs a)
     } else {
         grow = min(tile_m * BM + arow, a.m - 1);
     }
-    const uint32_t *qsrc = FP16W ? nullptr : a.q + (size_t)grow * kw + aword0;
+    const uint32_t *qsrc = FP16W ? nullptr : Q3 ? a.q + ((size_t)grow * (a.k >> 5) + (aword0 >> 2)) * 3 : a.q + (size_t)grow * kw + aword0;
     const uint16_t *ssrc = FP16W ? nullptr : a.s + (size_t)grow * scales_per_row(a.k, a.gshift);
     const int sub0 = aword0 >> 2;                         // first 32-column sub-group of this thread's words inside a k block
     const uint16_t *hsrc = FP16W ? a.wh + (size_t)grow * a.k + aword0 * 8 : nullptr;
@@ -184,7 +222,10 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_q4_mfma_kernel(GemmArgs a)
 #pragma unroll
             for (int i = 0; i < WV; ++i) {
                 if (i * 2 != part) continue;
-                if (W == 2) {
+                if (Q3) {                                 // group i of this thread: three words, 4-byte aligned
+                    const uint32_t *g3 = qsrc + (kb * (BK / 32) + i) * 3;
+                    S.wq[i].x = g3[0], S.wq[i].y = g3[1], S.wq[i].z = g3[2];
+                } else if (W == 2) {
                     const uint2 two = *(const uint2 *)(qsrc + kb * (BK / 8));
                     S.wq[0].x = two.x, S.wq[0].y = two.y;
                 } else {
@@ -230,7 +271,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_q4_mfma_kernel(GemmArgs a)
             const uint4 &wv = S.wq[i >> 2];
             const uint32_t word = (i & 3) == 0 ? wv.x : (i & 3) == 1 ? wv.y : (i & 3) == 2 ? wv.z : wv.w;
             const uint32_t sc = (W == 8 && i >= 4) ? (S.wsc >> 16) : (S.wsc & 0xFFFFu);
-            *(half8_t *)(ad + i * 8) = decode_word(word, sc | (sc << 16));
+            if (Q3) *(half8_t *)(ad + i * 8) = decode_q3_packet(wv.x, wv.y, wv.z, i & 3, sc | (sc << 16));
+            else *(half8_t *)(ad + i * 8) = decode_word(word, sc | (sc << 16));
         }
         uint16_t *bd = Bs + buf * kBBuf;
 #pragma unroll
@@ -238,11 +280,13 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_q4_mfma_kernel(GemmArgs a)
             if (p * 4 / XP != part) continue;
             const int pk = tid + p * kThreadsG;
             // [x0 x1 | x2 x3 | x4 x5 | x6 x7] -> [x0 x4 | x1 x5 | x2 x6 | x3 x7]
-            uint4 o;
-            o.x = __builtin_amdgcn_perm(S.xr[p].z, S.xr[p].x, 0x05040100u);
-            o.y = __builtin_amdgcn_perm(S.xr[p].z, S.xr[p].x, 0x07060302u);
-            o.z = __builtin_amdgcn_perm(S.xr[p].w, S.xr[p].y, 0x05040100u);
-            o.w = __builtin_amdgcn_perm(S.xr[p].w, S.xr[p].y, 0x07060302u);
+            uint4 o = S.xr[p];                            // Q3: the decode yields natural order
+            if (!Q3) {
+                o.x = __builtin_amdgcn_perm(S.xr[p].z, S.xr[p].x, 0x05040100u);
+                o.y = __builtin_amdgcn_perm(S.xr[p].z, S.xr[p].x, 0x07060302u);
+                o.z = __builtin_amdgcn_perm(S.xr[p].w, S.xr[p].y, 0x05040100u);
+                o.w = __builtin_amdgcn_perm(S.xr[p].w, S.xr[p].y, 0x07060302u);
+            }
             *(uint4 *)(bd + (pk >> 3) * kPitch + (pk & 7) * 8) = o;
         }
     };
@@ -403,7 +447,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_q4_mfma_kernel(GemmArgs a)
     }
 }
 
-template <int MF, int NF, bool FP16W = false, int WM = 2, int WN = 2>
+template <int MF, int NF, bool FP16W = false, int WM = 2, int WN = 2, bool Q3 = false>
 hipError_t launch_tile(const GemmArgs &a_in, hipStream_t stream, int splits)
 {
     constexpr int BM = 32 * MF * WM, BN = 32 * NF * WN, kThreadsG = WM * WN * 64;
@@ -416,14 +460,14 @@ hipError_t launch_tile(const GemmArgs &a_in, hipStream_t stream, int splits)
     dim3 grid(tiles * splits);
     const size_t lds = 2 * (size_t)(BM + BN) * kPitch * sizeof(uint16_t);    // up to 147456 bytes: one workgroup per CU
     static std::atomic<bool> attr_done{false};   // setting the attribute twice is harmless; the flag only has to be a defined read
-    if constexpr (FP16W) {
+    if constexpr (FP16W || Q3) {                          // plain matmuls only: one epilogue, one pass over k
         if (a.epi != EPI_F16 || splits != 1) return hipErrorInvalidValue;
         if (!attr_done.load()) {
-            if (hipFuncSetAttribute((const void *)gemm_q4_mfma_kernel<EPI_F16, MF, NF, true, WM, WN>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+            if (hipFuncSetAttribute((const void *)gemm_q4_mfma_kernel<EPI_F16, MF, NF, FP16W, WM, WN, Q3>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
                 return hipErrorInvalidValue;
             attr_done.store(true);
         }
-        hipLaunchKernelGGL((gemm_q4_mfma_kernel<EPI_F16, MF, NF, true, WM, WN>), grid, dim3(kThreadsG), lds, stream, a);
+        hipLaunchKernelGGL((gemm_q4_mfma_kernel<EPI_F16, MF, NF, FP16W, WM, WN, Q3>), grid, dim3(kThreadsG), lds, stream, a);
         return hipGetLastError();
     }
     if (!attr_done.load()) {
@@ -544,6 +588,25 @@ hipError_t launch_gemm_f16(const uint16_t *x, const uint16_t *w, int n, int m, i
     if (p.nf == 4) return launch_tile<2, 4, true>(a, stream, 1);
     if (p.nf == 2) return launch_tile<2, 2, true>(a, stream, 1);
     return launch_tile<2, 1, true>(a, stream, 1);
+}
+
+// out[n,m] = x[n,k] . w[m,k]^T with 3-bit weights in the native word layout (group 32): the same tiles, one pass over k
+bool gemm_q3_eligible(const void *x, const relax_qmat &w, const void *out)
+{
+    return w.k % (2 * BK) == 0 && w.m % 4 == 0 && (w.group == 0 || w.group == 32) && (reinterpret_cast<uintptr_t>(x) & 15) == 0 &&
+           (reinterpret_cast<uintptr_t>(w.q) & 3) == 0 && (reinterpret_cast<uintptr_t>(w.s) & 1) == 0 && (reinterpret_cast<uintptr_t>(out) & 7) == 0;
+}
+
+hipError_t launch_gemm_q3(const uint16_t *x, const relax_qmat &w, int n, uint16_t *out, hipStream_t stream)
+{
+    GemmArgs a = {};
+    a.x = x, a.q = w.q, a.s = w.s, a.gshift = 0, a.n = n, a.m = w.m, a.k = w.k, a.epi = EPI_F16, a.out_f16 = out;
+    const TilePlan p = tile_plan(w.m, w.k, n, EPI_F16);
+    a.kb_per_split = w.k / BK;
+    if (p.mf == 4) return launch_tile<2, 4, false, 4, 2, true>(a, stream, 1);
+    if (p.nf == 4) return launch_tile<2, 4, false, 2, 2, true>(a, stream, 1);
+    if (p.nf == 2) return launch_tile<2, 2, false, 2, 2, true>(a, stream, 1);
+    return launch_tile<2, 1, false, 2, 2, true>(a, stream, 1);
 }
 
 hipError_t launch_gemm_mfma(const uint16_t *x, const relax_qmat &w, int n, int epi, uint16_t *out_f16, float *out_f32, const void *resid,

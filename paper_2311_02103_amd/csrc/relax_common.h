@@ -211,6 +211,10 @@ hipError_t launch_unpack_q3(const relax_qmat &w, int8_t *out, hipStream_t stream
 hipError_t launch_repack_q3(const relax_qmat &canonical, uint32_t *dst, hipStream_t stream);
 hipError_t launch_unpack_q3_native(const relax_qmat &w, int8_t *out, hipStream_t stream);
 hipError_t launch_gemv_q3_native(const uint16_t *x, const relax_qmat &w, int n, uint16_t *out, hipStream_t stream);
+// the tiled MFMA GEMM on native 3-bit weights (gemm_q4_mfma.hip), taken from kQ3GemmRows rows of x on
+constexpr int kQ3GemmRows = 16;
+bool gemm_q3_eligible(const void *x, const relax_qmat &w, const void *out);
+hipError_t launch_gemm_q3(const uint16_t *x, const relax_qmat &w, int n, uint16_t *out, hipStream_t stream);
 hipError_t launch_dequantize(const relax_qmat &w, float *out, hipStream_t stream);
 
 // Split-L attention: chunk length and split count are pure functions of the runtime shape.

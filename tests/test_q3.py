@@ -211,6 +211,46 @@ def test_gpu_native_matmul_random(rx, m, k, n):
     assert err.max() <= 2e-3 * max(1.0, np.abs(ref).max())
 
 
+# From 16 rows of x on, a matrix with k % 128 == 0 and m % 4 == 0 goes through the tiled MFMA GEMM (3-bit decode on the way
+# into LDS); every tile shape of it is met below (n <= 64: 128 x 64; <= 128: 128 x 128; above: 128 x 256 and 256 x 256).
+@pytest.mark.gpu
+@pytest.mark.parametrize("m,k,n", [(128, 256, 16), (64, 4096, 40), (260, 1024, 100), (512, 2048, 200), (1024, 1024, 300), (96, 16384, 17)])
+def test_gpu_native_gemm_integer_valued_bitwise(rx, m, k, n):
+    r = np.random.RandomState(k + m + n)
+    codes = r.randint(0, 8, size=(m, k)).astype(np.uint8)
+    s = r.choice([1.0, 2.0], size=(m, k // 32)).astype(np.float16).view(np.uint16)
+    x = np.zeros((n, k), dtype=np.float32)
+    hot = r.choice(k, size=40, replace=False)
+    x[:, hot] = r.randint(-3, 4, size=(n, 40))
+    q = wl.pack_codes3(codes)
+    ref = q3.dequant_matmul_q3(x, q, s, m, k)
+    assert np.abs(ref).max() <= 2048 and np.abs(ref).max() > 0
+    got = gpu_q3_native_matmul(rx, x.astype(np.float16).view(np.uint16), q, s, m, k)
+    assert np.array_equal(got.astype(np.float64), ref)
+    # a selector matrix (one code 5 = +1 per row, all others 4 = 0, scale 1) picks integer-valued x exactly: a wrong column
+    # order inside a group, or between the weight tile and the x tile, picks the wrong element
+    codes = np.full((m, k), 4, dtype=np.uint8)
+    cols = (7 * np.arange(m) + 3) % k
+    codes[np.arange(m), cols] = 5
+    xi = ((np.arange(n)[:, None] * 5 + np.arange(k)[None, :] * 37) % 15 - 7).astype(np.float32)
+    ones = np.full((m, k // 32), np.float16(1.0)).view(np.uint16)
+    got = gpu_q3_native_matmul(rx, xi.astype(np.float16).view(np.uint16), wl.pack_codes3(codes), ones, m, k)
+    assert np.array_equal(got, xi[:, cols])
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("m,k,n", [(512, 4096, 16), (1000, 2048, 300), (4096, 4096, 128), (22016, 4096, 64), (4096, 11008, 130), (256, 16384, 33),
+                                   (12288, 4096, 511)])
+def test_gpu_native_gemm_random(rx, m, k, n):
+    q, s = wl.qmat3(9, m * 131 + k, m, k)
+    x = wl.normal_f16_bits(9, m + k + n, (n, k))
+    ref = q3.dequant_matmul_q3(wl.f16_bits_to_f32(x), q, s, m, k)
+    got = gpu_q3_native_matmul(rx, x, q, s, m, k)
+    err = np.abs(got - ref)
+    assert np.all(err <= 1e-2 + 2e-2 * np.abs(ref)), "m=%d k=%d n=%d: max err %g" % (m, k, n, err.max())
+    assert err.max() <= 3e-3 * max(1.0, np.abs(ref).max())
+
+
 def test_host_checks_of_the_q3_entry_points():
     from paper_2311_02103_amd import binding as rx
     if not os.path.exists(rx.LIB_PATH):
@@ -228,5 +268,5 @@ def test_host_checks_of_the_q3_entry_points():
     assert rx.lib().relax_repack_q3(rx.QMatC(64, 64, 8, 40), 128, None) == rx.ERR_SHAPE
     assert rx.lib().relax_unpack_q3_native(rx.QMatC(64, 64, 8, 48), 64, None) == rx.ERR_SHAPE
     assert rx.lib().relax_dequant_matmul_q3_native(64, w, 64, 0, None) == rx.ERR_SHAPE
-    assert rx.lib().relax_dequant_matmul_q3_native(64, rx.QMatC(64, 64, 8, 12288 + 32), 64, 1, None) == rx.ERR_UNSUPPORTED
+    assert rx.lib().relax_dequant_matmul_q3_native(64, rx.QMatC(64, 64, 8, 12288 + 32), 64, 1, None) == rx.ERR_UNSUPPORTED    # one row: matvec only
     assert rx.lib().relax_dequant_matmul_q3_native(None, w, 64, 1, None) == rx.ERR_NULL
