@@ -75,7 +75,8 @@ __device__ __forceinline__ half8_t decode_word(uint32_t w, uint32_t s2)
 struct SkinnyArgs {
     const uint16_t *x;       // [n,k] fp16
     const uint32_t *q;       // [m,k/8]
-    const uint16_t *s;       // [m,k/32]
+    const uint16_t *s;       // [m, k / (32 << gshift)]
+    int32_t gshift;          // quantisation group = 32 << gshift columns
     float *partial;          // [splits][n][m] fp32
     int32_t n, m, k;
     int32_t rounds_per_split;
@@ -95,7 +96,7 @@ __global__ __launch_bounds__(256) void skinny_q4_kernel(SkinnyArgs a)
     uint16_t *const xs = lds, *const scs = lds + 2 * kXBuf;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int row32 = lane & 31, hf = lane >> 5;
-    const int kw = a.k >> 3, G = a.k >> 5;
+    const int kw = a.k >> 3, SG = a.k >> (5 + a.gshift);   // packed words and scales per weight row
     const int total_rounds = a.k / KR;
     const int r_begin = blockIdx.y * a.rounds_per_split, r_end = min(total_rounds, r_begin + a.rounds_per_split);
     const int nr = r_end - r_begin;                       // >= 1 by construction of the grid
@@ -104,12 +105,26 @@ __global__ __launch_bounds__(256) void skinny_q4_kernel(SkinnyArgs a)
 
     // ---- group scales of the whole task, once: 128 rows x (8 nr) fp16, 16-byte packets, coalesced along each row ----
     // (per-round 8-byte loads would touch every 128-byte line of the scale rows eight rounds in a row)
+    // The tile always holds one entry per 32 columns; with a wider quantisation group a packet's 8 entries are 4 or 2
+    // scales of the matrix, each written twice or four times (8- or 4-byte loads: k % 256 == 0 keeps them aligned).
     u32x4_t screg[kMaxRounds / 2];
 #pragma unroll
     for (int i = 0; i < kMaxRounds / 2; ++i) {
         const int pk = tid + i * 256, row = pk / spr, pp = pk - row * spr;
         const int grow = min(blockIdx.x * kRowsPerBlock + min(row, kRowsPerBlock - 1), a.m - 1);
-        screg[i] = *(const u32x4_t *)(a.s + (size_t)grow * G + (size_t)r_begin * (KR / 32) + (size_t)min(pp, nr * KR / 256 - 1) * 8);
+        const size_t sub = (size_t)r_begin * (KR / 32) + (size_t)min(pp, nr * KR / 256 - 1) * 8;      // first 32-column sub-group of the packet
+        const uint16_t *src = a.s + (size_t)grow * SG + (sub >> a.gshift);
+        if (a.gshift == 0) {
+            screg[i] = *(const u32x4_t *)src;
+        } else if (a.gshift == 1) {
+            const u32x2_t four = *(const u32x2_t *)src;                                                // s0 s1 | s2 s3
+            screg[i] = u32x4_t{__builtin_amdgcn_perm(four.x, four.x, 0x01000100u), __builtin_amdgcn_perm(four.x, four.x, 0x03020302u),
+                               __builtin_amdgcn_perm(four.y, four.y, 0x01000100u), __builtin_amdgcn_perm(four.y, four.y, 0x03020302u)};
+        } else {
+            const uint32_t two = *(const uint32_t *)src;                                               // s0 s1
+            const uint32_t lo = __builtin_amdgcn_perm(two, two, 0x01000100u), hi = __builtin_amdgcn_perm(two, two, 0x03020302u);
+            screg[i] = u32x4_t{lo, lo, hi, hi};
+        }
     }
 
     const int wrow = min(blockIdx.x * kRowsPerBlock + wave * 32 + row32, a.m - 1);
@@ -447,7 +462,7 @@ bool gemm_skinny_eligible(const relax_qmat &w, const void *x, int n, int epi)
 {
     if (n < 1 || n > kSkinnyMaxN) return false;
     if (w.k % kRound != 0) return false;
-    if (gshift_of(w.group) != 0) return false;            // its scale tile holds one scale per 32 columns: wider groups take the other two kernels
+    if (gshift_of(w.group) < 0) return false;
     if ((reinterpret_cast<uintptr_t>(w.q) & 15) != 0 || (reinterpret_cast<uintptr_t>(w.s) & 15) != 0) return false;
     if ((reinterpret_cast<uintptr_t>(x) & 15) != 0) return false;
     return epi == EPI_SWIGLU ? w.m % 8 == 0 : w.m % 4 == 0;
@@ -481,7 +496,7 @@ hipError_t launch_gemm_skinny(const uint16_t *x, const relax_qmat &w, int n, int
 {
     const SkinnyPlan pl = skinny_plan(w.m, w.k, skinny_round(n));
     SkinnyArgs a;
-    a.x = x, a.q = w.q, a.s = w.s, a.partial = partial, a.n = n, a.m = w.m, a.k = w.k, a.rounds_per_split = pl.rounds_per_split;
+    a.x = x, a.q = w.q, a.s = w.s, a.gshift = gshift_of(w.group), a.partial = partial, a.n = n, a.m = w.m, a.k = w.k, a.rounds_per_split = pl.rounds_per_split;
     dim3 grid(pl.tiles_m, pl.splits);
     hipError_t e;
     const int splits = pl.splits;

@@ -1,8 +1,7 @@
 """Quantisation groups of 64 and 128 columns through the C ABI, against the oracle (whose group generalisation is pinned
 on the CPU in test_oracle_pins.py): decode exports bit-exact, exact matmul cases bitwise on every kernel that takes such a
-matrix (the x-in-registers matvec, the LDS-resident matvec for long rows, the word-by-word matvec for k % 32 != 0, the tiled
-MFMA GEMM), random matmuls and whole layers within the fp16 bar.  The few-row split-K kernel serves group 32 only, so
-2..15 rows of a wider-group matrix run as matvec passes and 16 rows or more as the tiled GEMM."""
+matrix (the x-in-registers matvec, the LDS-resident matvec for long rows, the word-by-word matvec for k % 32 != 0, the
+few-row split-K kernel, the tiled MFMA GEMM), random matmuls and whole layers within the fp16 bar."""
 import numpy as np
 import pytest
 
@@ -38,10 +37,10 @@ def test_dequantize_bit_exact(rx, m, k, group):
     assert np.array_equal(dense.cpu().numpy().view(np.uint32), oracle.dequantize(q, s, m, k, group).view(np.uint32))
 
 
-# n: 1 = matvec kernels; 3 = matvec passes (no few-row kernel for these groups); 16, 200 = tiled MFMA GEMM
+# n: 1 = matvec kernels; 3 = few-row kernel (k % 256 == 0, with a workspace) or matvec passes; 16.. = few-row kernel or tiled MFMA GEMM
 @pytest.mark.parametrize("group", GROUPS)
 @pytest.mark.parametrize("m,k,n", [(130, 4096, 1), (37, 11008, 1), (65, 688, 1), (12, 16384, 1), (40, 256, 3), (64, 4096, 3),
-                                   (128, 4096, 16), (256, 1024, 200), (96, 11008, 64)])
+                                   (128, 4096, 16), (256, 1024, 200), (96, 11008, 64), (132, 2048, 7), (260, 8192, 33), (128, 1024, 100)])
 def test_exact_cases_bitwise(rx, m, k, n, group):
     """Per-group scales are distinct powers of two and codes random, x sparse small integers: every output is an integer
     that fp16 holds exactly, so a wrong scale index (sub-group -> scale, row stride ceil(k / group)) shows as a wrong
@@ -56,8 +55,9 @@ def test_exact_cases_bitwise(rx, m, k, n, group):
     q, s = wl.pack_codes(codes), sc.view(np.uint16)
     ref = oracle.dequant_matmul(x, q, s, m, k, group)
     assert np.abs(ref).max() <= 2048 and np.abs(ref).max() > 0
-    got = gpu_matmul(rx, x.astype(np.float16).view(np.uint16), q, s, m, k, group=group).view(np.float16).astype(np.float32)
-    assert np.array_equal(got, ref)
+    for with_ws in (False, True):               # with a workspace 2..128 rows take the few-row split-K kernel
+        got = gpu_matmul(rx, x.astype(np.float16).view(np.uint16), q, s, m, k, with_ws=with_ws, group=group).view(np.float16).astype(np.float32)
+        assert np.array_equal(got, ref), with_ws
     codes = np.full((m, k), 8, dtype=np.uint8)
     cols = (7 * np.arange(m) + 3) % k
     codes[np.arange(m), cols] = 9
@@ -87,7 +87,7 @@ MID_GQA = wl.LayerShape("mid-gqa", hidden=1024, n_heads=16, n_kv_heads=4, head_d
 @pytest.mark.parametrize("group", GROUPS)
 @pytest.mark.parametrize("shape,calls", [
     (wl.TINY, [([9], [9], None), ([1], [10], None)]),                               # k = 688: short last group (48 of 64, 48 of 128)
-    (MID, [([40], [40], None), ([1], [41], None), ([3], [44], None), ([200], [244], None)]),   # GEMM, matvec, matvec passes, GEMM
+    (MID, [([40], [40], None), ([1], [41], None), ([3], [44], None), ([200], [244], None)]),   # few-row kernel, matvec, few-row kernel, GEMM
     (MID_GQA, [([5, 1, 20], [5, 1, 20], [2, 0, 1]), ([1, 1, 1], [6, 2, 21], [2, 0, 1])]),
 ])
 def test_layer_with_wider_groups(rx, shape, calls, group):
