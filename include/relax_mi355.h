@@ -313,8 +313,8 @@ relax_status relax_unpack_q3(const relax_qmat *w, int8_t *out, relax_stream stre
 relax_status relax_dequant_matmul_q3(const uint16_t *x, const relax_qmat *w, uint16_t *out, int32_t n, relax_stream stream);
 
 /* The GPU-native 3-bit layout: the same bits per group in an order the kernels decode at a third of the cost (one
- * vector operation yields a ready fp16 pair), so that 3-bit weights stream FASTER than 4-bit ones, as their size
- * promises.  Per group of 32 columns (codes u_0..u_31) and its three words: position j (0..4) of word w holds
+ * vector operation yields a ready fp16 pair); with it a 3-bit matrix-vector product takes the time of the 4-bit one
+ * on the same shape (from the canonical stream it was a third slower).  Per group of 32 columns (codes u_0..u_31) and its three words: position j (0..4) of word w holds
  * u_{2(5w+j)} in bits 3j..3j+2 and u_{2(5w+j)+1} in bits 16+3j..16+3j+2; bit i of u_30 is bit 15 of word i, bit i of
  * u_31 is bit 31 of word i.  Scales are unchanged.
  * relax_repack_q3: canonical q (as above) -> native_q, device uint32 [m][3k/32] owned by the caller, not in place; a
