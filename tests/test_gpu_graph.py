@@ -147,3 +147,38 @@ def test_one_captured_decode_step_replays_through_the_positions(rx):
         assert int(tab[2].item()) == P + 1 + s
         assert torch.equal(bits(logits), bits(eager[s][0])), "logits of replay %d" % s
         assert torch.equal(ids, eager[s][1]), "token of replay %d" % s
+
+
+def test_capture_of_a_call_with_more_than_sixteen_sequences_and_host_descriptors(rx):
+    """21 sequences with host arrays: the descriptor does not fit kernel arguments, so the call writes a device table at the
+    front of the workspace -- with small kernels that carry the values, no copy and no synchronisation, hence capturable.
+    The captured call, replayed three times with eager work in between, gives the bits of the eager call every time."""
+    from paper_2311_02103_amd.runtime import DeviceLayer
+    shape, cap, B = wl.TINY, 64, 21
+    layer = DeviceLayer(wl.layer_weights(shape, 41), hidden=shape.hidden, n_heads=shape.n_heads, n_kv_heads=shape.n_kv_heads,
+                        head_dim=shape.head_dim, ffn=shape.ffn, kv_capacity=cap, kv_slots=B, n_max=B, B_max=B)
+    kb, vb = wl.kv_prefill(shape, 41, B, cap)
+    kv = [int(v) for v in wl.uniform_lengths(41, B, 2, 60)]
+    slots = list(reversed(range(B)))
+    x = torch.from_numpy(wl.activations(shape, 41, 0, B).view(np.int16)).view(torch.float16).cuda()
+    layer.load_cache(kb, vb)
+    want = layer.forward(x, [1] * B, kv, slots).clone()
+    want_k = layer.k.clone()
+    torch.cuda.synchronize()
+
+    stream = torch.cuda.Stream()
+    out = torch.empty_like(x)
+    call = layer.prepare(x, [1] * B, kv, slots, out=out)
+    layer.load_cache(kb, vb)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=stream):
+        call(stream.cuda_stream)
+    for rep in range(3):
+        layer.load_cache(kb, vb)                       # eager work between the replays; the appended rows are written again
+        out.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(bits(out), bits(want)), "replay %d: output differs from the eager call" % rep
+        assert torch.equal(bits(layer.k), bits(want_k)), "replay %d: K cache differs" % rep
