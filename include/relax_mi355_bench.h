@@ -43,7 +43,7 @@ relax_status relax_probe_mfma(float *sink, int32_t iters, int32_t random_data, i
  * 2 output projection, 3 gate/up, 4 down projection) on the call's stream; the setting is
  * consumed by that one call.  start/stop are hipEvent_t handles owned by the caller;
  * step < 0 or NULL events clear the setting.  Lets a benchmark time one kernel of the
- * fused layer with HIP events on the stream the kernel really runs on.                  */
+ * layer with HIP events on the stream the kernel really runs on.                        */
 void relax_profile_step_events(void *start, void *stop, int32_t step);
 
 /* Measurement aid: while q_alt / s_alt (device pointers to another packed matrix and its scales, of the shape of
