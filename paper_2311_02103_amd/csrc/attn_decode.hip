@@ -95,8 +95,8 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const uint16_t *__restr
     for (int t = t_begin + wave * TPW + sub; t < t_end; t += 4 * TPW) {
         const size_t at = ((slot_base + t) * g + kvh) * D + e0;
         float kf[8], vf[8];
-        unpack8(*(const uint4 *)(kc + at), kf);
-        unpack8(*(const uint4 *)(vc + at), vf);
+        unpack8(stream_load((const uint4 *)(kc + at)), kf);
+        unpack8(stream_load((const uint4 *)(vc + at)), vf);
 #pragma unroll
         for (int r = 0; r < REP; ++r) {
             float dot = 0.0f;
@@ -216,8 +216,8 @@ __global__ __launch_bounds__(256) void attn_mha_split_kernel(const uint16_t *__r
 #pragma unroll
         for (int j = 0; j < NL; ++j) {
             const size_t at = (size_t)min(t0 + j * TPW, t_end - 1) * row_stride;    // tokens past the end re-read the last one, masked below
-            sp.k[j] = *(const u32x4a_t *)(kbase + at);
-            sp.v[j] = *(const u32x4a_t *)(vbase + at);
+            sp.k[j] = stream_load((const u32x4a_t *)(kbase + at));
+            sp.v[j] = stream_load((const u32x4a_t *)(vbase + at));
         }
         __builtin_amdgcn_sched_barrier(0);
     };

@@ -82,7 +82,7 @@ __global__ __launch_bounds__(256, 2) void attn_gqa_kernel(const uint16_t *__rest
 #pragma unroll
         for (int p = 0; p < VPK; ++p) {
             const int pk = lane + p * 64, r = pk / (D / 8), c = pk % (D / 8);
-            vreg[p] = *(const u32x4_t *)(vc + ((slot_base + min(t0 + r, t_end - 1)) * g + kvh) * D + c * 8);
+            vreg[p] = stream_load((const u32x4_t *)(vc + ((slot_base + min(t0 + r, t_end - 1)) * g + kvh) * D + c * 8));
         }
     };
 

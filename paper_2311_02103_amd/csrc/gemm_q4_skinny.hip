@@ -150,6 +150,7 @@ __global__ __launch_bounds__(256) void skinny_q4_kernel(SkinnyArgs a)
 #pragma unroll
         for (int p = 0; p < XP; ++p) S.x[p] = *(const u32x4_t *)(xsrc[p] + (size_t)r * KR);
 #pragma unroll
+        // (plain loads: the four 16-byte pieces of a lane's 64 bytes and its neighbour's share 128-byte lines, which have to stay cached between them)
         for (int i = 0; i < W / 4; ++i) S.w[i] = *(const u32x4_t *)(qsrc + (size_t)r * (KR / 8) + i * 4);
     };
     auto x_store = [&](const Stage &S, int buf) {

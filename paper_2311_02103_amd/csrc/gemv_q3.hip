@@ -285,7 +285,7 @@ __global__ __launch_bounds__(kQ3Threads) void gemv_q3n_kernel(const uint16_t *__
             for (int j = 0; j < J; ++j) {
                 const int g = min(lane + kWave * j, G - 1);
                 const uint32_t *p = q + (row * G + g) * 3;
-                sl.w[rr][j][0] = p[0], sl.w[rr][j][1] = p[1], sl.w[rr][j][2] = p[2];
+                sl.w[rr][j][0] = stream_load(p), sl.w[rr][j][1] = stream_load(p + 1), sl.w[rr][j][2] = stream_load(p + 2);
                 sl.sc[rr][j] = s[row * G + g];
             }
         }

@@ -172,7 +172,7 @@ __global__ __launch_bounds__(512) void gemv_q4_kernel(GemvArgs a)
                     float sc[4];
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
-                        wv[r] = *(const uint4 *)(a.q + (size_t)rows[r] * kw + (size_t)gi * 4);
+                        wv[r] = stream_load((const uint4 *)(a.q + (size_t)rows[r] * kw + (size_t)gi * 4));
                         sc[r] = h2f(a.s[(size_t)rows[r] * SG + (gi >> a.gshift)]);
                     }
 #pragma unroll

@@ -291,7 +291,7 @@ __global__ __launch_bounds__(kRThreads) void gemv_q4_reg_kernel(GemvArgs a)
             for (int c = 0; c < NG; ++c) {
                 // chunks that can reach past the row (NG = 4, 6 also serve rows one chunk shorter) are clamped
                 const int gi = (c >= kFirstRagged) ? min(c * 64 + lane, G - 1) : c * 64 + lane;
-                s.w[rr * NG + c] = *(const u32x4_t *)(qrow + gi * 4);
+                s.w[rr * NG + c] = stream_load((const u32x4_t *)(qrow + gi * 4));
                 s.sc[rr * NG + c] = srow[gi >> a.gshift];     // 1, 2 or 4 neighbouring lanes read the same scale
             }
         }

@@ -173,7 +173,7 @@ __global__ __launch_bounds__(1024) void argmax_kernel(const uint16_t *__restrict
         for (int p0 = threadIdx.x; p0 < packets; p0 += 4 * 1024) {
             uint4 raw[4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) raw[j] = *(const uint4 *)(row + (size_t)min(p0 + j * 1024, packets - 1) * 8);
+            for (int j = 0; j < 4; ++j) raw[j] = stream_load((const uint4 *)(row + (size_t)min(p0 + j * 1024, packets - 1) * 8));
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int pk = p0 + j * 1024;
