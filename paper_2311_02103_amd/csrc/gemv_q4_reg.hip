@@ -235,7 +235,7 @@ __global__ __launch_bounds__(kRThreads) void gemv_q4_reg_kernel(GemvArgs a)
         const int pos = row_info(a.seqs, 0).pos;
         used = pos / attn_fold_chunk(pos + 1, a.part_splits) + 1;
     } else if (kMerge) {
-        used = (a.pos0 + a.part_chunk) / a.part_chunk;
+        used = a.part_used;                                        // the host knew the position: no division up front
     }
     auto x_loads = [&]() {
 #pragma unroll
@@ -259,9 +259,11 @@ __global__ __launch_bounds__(kRThreads) void gemv_q4_reg_kernel(GemvArgs a)
         if (kNorm) wnr[p] = *(const u32x4_t *)(a.norm_w + (size_t)c8 * 8);
     }
     };
-    // The x row goes out ahead of the weights (it is needed first and is small).  The partials of X_ATTN_MERGE are
-    // many requests served by the L2: behind the first slots, so that the weight stream from HBM starts at once.
-    if (!kMerge) x_loads();
+    // The x row goes out ahead of the weights: it is needed first and is small.  That holds for the partials of
+    // X_ATTN_MERGE too, although they are 24 requests per thread: returns are counted in order, so behind the slots the
+    // merge arithmetic could only start once the weights were there; ahead of them it runs while they are on their way
+    // (0.4 us per call at the 7B shape).
+    x_loads();
 
     struct Slot {
         u32x4_t w[E];
@@ -300,7 +302,6 @@ __global__ __launch_bounds__(kRThreads) void gemv_q4_reg_kernel(GemvArgs a)
     Slot sl[NSLOT];
 #pragma unroll
     for (int t = 0; t < NSLOT; ++t) slot_load(sl[t], t);
-    if (kMerge) x_loads();
     // behind the first slots in program order: its address arithmetic runs while they are in flight
     const float2 pre = epi_fetch<EPI>(a, i, ri, lane < mine ? wg + lane * W : min(wg, U - 1));
     __builtin_amdgcn_sched_barrier(0);
@@ -366,9 +367,12 @@ __global__ __launch_bounds__(kRThreads) void gemv_q4_reg_kernel(GemvArgs a)
                     num[2 * j] += w * h2f((uint16_t)(ow & 0xFFFFu)), num[2 * j + 1] += w * h2f((uint16_t)(ow >> 16));
                 }
             }
+            // one division per head instead of one per element (a dozen instructions each, ahead of the whole stream);
+            // den > 0: the first split holds a token
+            const float rden = on ? 1.0f / den : 0.0f;
             uint16_t y[8];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) y[e] = on ? f2h(num[e] / den) : (uint16_t)0;
+            for (int e = 0; e < 8; ++e) y[e] = f2h(num[e] * rden);
             o.x = (uint32_t)y[0] | ((uint32_t)y[4] << 16), o.y = (uint32_t)y[1] | ((uint32_t)y[5] << 16);
             o.z = (uint32_t)y[2] | ((uint32_t)y[6] << 16), o.w = (uint32_t)y[3] | ((uint32_t)y[7] << 16);
         } else {
@@ -537,8 +541,10 @@ hipError_t launch_gemv_reg(const GemvArgs &a, int xmode, int epi, hipStream_t st
     if (xmode == X_F16_NORM && epi == EPI_ROPE_KV) return launch_xe<X_F16_NORM, EPI_ROPE_KV>(a, stream);
     if (xmode == X_F16 && epi == EPI_RESID_F32) return launch_xe<X_F16, EPI_RESID_F32>(a, stream);
     if (xmode == X_ATTN_MERGE && epi == EPI_RESID_F32 && gemv_merge_eligible(a)) {
-        if (a.k <= 2048) return launch_ng<X_ATTN_MERGE, EPI_RESID_F32, 1>(a, stream);
-        return launch_ng<X_ATTN_MERGE, EPI_RESID_F32, 2>(a, stream);
+        GemvArgs b = a;
+        b.part_used = a.pos0 >= 0 ? a.pos0 / a.part_chunk + 1 : 0;     // splits that hold tokens (read from the descriptor when pos0 < 0)
+        if (a.k <= 2048) return launch_ng<X_ATTN_MERGE, EPI_RESID_F32, 1>(b, stream);
+        return launch_ng<X_ATTN_MERGE, EPI_RESID_F32, 2>(b, stream);
     }
     if (xmode == X_F32_NORM && epi == EPI_SWIGLU) return launch_xe<X_F32_NORM, EPI_SWIGLU>(a, stream);
     if (xmode == X_F16 && epi == EPI_RESID_F16) return launch_xe<X_F16, EPI_RESID_F16>(a, stream);

@@ -137,6 +137,7 @@ struct GemvArgs {
     // as fp16, then (max, sum) as fp32 at float index d / 2
     const float *part;
     int32_t part_splits, part_stride, part_chunk;
+    int32_t part_used;               // filled in by launch_gemv_reg: splits that hold tokens when the host knows the position
     const uint16_t *norm_w;          // [k] fp16, norm modes only
     float eps;
     // matrix
