@@ -75,8 +75,8 @@ __device__ __forceinline__ float reduce1(float v)
     r += dpp<kQuadXor2>(r);
     r += dpp<kRowRor4>(r);
     r += dpp<kRowRor8>(r);
-    r += __shfl_xor(r, 16, kWave);
-    r += __shfl_xor(r, 32, kWave);
+    r = xor16_sum(r);
+    r = xor32_sum(r);
     return r;
 }
 // two partial sums -> lane l holds the total of row l & 1
@@ -87,8 +87,8 @@ __device__ __forceinline__ float reduce2(float v0, float v1, int lane)
     r += dpp<kQuadXor2>(r);
     r += dpp<kRowRor4>(r);
     r += dpp<kRowRor8>(r);
-    r += __shfl_xor(r, 16, kWave);
-    r += __shfl_xor(r, 32, kWave);
+    r = xor16_sum(r);
+    r = xor32_sum(r);
     return r;
 }
 
@@ -210,7 +210,7 @@ __global__ __launch_bounds__(kRThreads) void gemv_q4_reg_kernel(GemvArgs a)
     const int k = a.k, G = k >> 5, kw = k >> 3, SG = scales_per_row(k, a.gshift);
     const int U = unit_count_r<EPI>(a);
     const int W = gridDim.x * kRWaves, wg = blockIdx.x * kRWaves + wave;
-    const int mine = wg < U ? (U - wg + W - 1) / W : 0;        // <= kRMaxUnits: the launcher sizes the grid for it
+    const int mine = a.units_div + (wg < a.units_mod ? 1 : 0); // units wg, wg + W, .. below U, the division done by the host; <= kRMaxUnits
     float *res = res_all[wave];
 
     // ---- what the epilogue reads, then the x row, then the first slots: requested in the order they are needed ----
@@ -474,8 +474,9 @@ __global__ __launch_bounds__(kRThreads) void gemv_q4_reg_kernel(GemvArgs a)
 }
 
 template <int XMODE, int EPI, int NG>
-hipError_t launch_ng(const GemvArgs &a, hipStream_t stream)
+hipError_t launch_ng(const GemvArgs &a_in, hipStream_t stream)
 {
+    GemvArgs a = a_in;
     static int cus = 0;
     if (cus == 0) {
         int dev = 0, v = 0;
@@ -490,6 +491,7 @@ hipError_t launch_ng(const GemvArgs &a, hipStream_t stream)
     const bool few_rows = 2 * ((U + gx * kRWaves - 1) / (gx * kRWaves)) <= 4;      // rows a wavefront owns
     constexpr bool kHasPos = EPI == EPI_ROPE_KV || XMODE == X_ATTN_MERGE;
     const bool one = rows_per_slot<NG>(few_rows) == 1;
+    a.units_div = U / (gx * kRWaves), a.units_mod = U % (gx * kRWaves);
     if constexpr (kHasPos) {
         if (a.n == 1 && a.pos0 < 0) {                              // position from the device-resident descriptor
             if (a.seqs.dev == nullptr) return hipErrorInvalidValue;

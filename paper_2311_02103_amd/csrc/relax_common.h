@@ -88,17 +88,59 @@ __device__ inline RowInfo row_info(const SeqTable &st, int32_t row)
     return r;
 }
 
+// ---- wavefront reductions without the LDS crossbar ------------------------------------------------------------------
+// The exchange with lane ^ 32 and lane ^ 16 is one v_permlane32_swap / v_permlane16_swap (two copies of v in, the lower /
+// even and the upper / odd quarter-rows out), the one with lane ^ 8 .. lane ^ 1 a DPP row rotation or quad permutation:
+// register-to-register moves of a few cycles each, where a ds_bpermute costs a trip through the LDS and a wait.  The
+// partners are those of a butterfly over lane ^ 32, 16, 8, 4, 2, 1 in this order (after the step for ^ 8 the lanes i and
+// i ^ 8 hold the same value, so the rotation by 4 hands lane i what lane i ^ 4 holds), hence every lane ends with the
+// same bits as that butterfly gives.
+typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+template <int CTRL>
+__device__ __forceinline__ float lane_dpp(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
+}
+// (v[lane & 31], v[lane | 32]): both halves of the pair (lane, lane ^ 32), the same in both lanes of the pair
+__device__ __forceinline__ float2 pair_xor32(float v)
+{
+    const unsigned int u = __builtin_bit_cast(unsigned int, v);
+    const u32x2_t r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    const unsigned int lo = r.x, hi = r.y;    // element copies: a bit_cast applied to the subscript itself reads word 0
+    return make_float2(__builtin_bit_cast(float, lo), __builtin_bit_cast(float, hi));
+}
+// the same for the pair (lane, lane ^ 16)
+__device__ __forceinline__ float2 pair_xor16(float v)
+{
+    const unsigned int u = __builtin_bit_cast(unsigned int, v);
+    const u32x2_t r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+    const unsigned int lo = r.x, hi = r.y;    // element copies: a bit_cast applied to the subscript itself reads word 0
+    return make_float2(__builtin_bit_cast(float, lo), __builtin_bit_cast(float, hi));
+}
+__device__ __forceinline__ float xor32_sum(float v) { const float2 p = pair_xor32(v); return p.x + p.y; }
+__device__ __forceinline__ float xor16_sum(float v) { const float2 p = pair_xor16(v); return p.x + p.y; }
+
 __device__ inline float wave_sum(float v)
 {
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, kWave);
+    v = xor32_sum(v);
+    v = xor16_sum(v);
+    v += lane_dpp<0x128>(v);                  // row_ror:8 = lane ^ 8
+    v += lane_dpp<0x124>(v);                  // row_ror:4: the value lane ^ 4 holds
+    v += lane_dpp<0x4E>(v);                   // quad_perm [2,3,0,1] = lane ^ 2
+    v += lane_dpp<0xB1>(v);                   // quad_perm [1,0,3,2] = lane ^ 1
     return v;
 }
 
 __device__ inline float wave_max(float v)
 {
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, kWave));
+    float2 p = pair_xor32(v);
+    v = fmaxf(p.x, p.y);
+    p = pair_xor16(v);
+    v = fmaxf(p.x, p.y);
+    v = fmaxf(v, lane_dpp<0x128>(v));
+    v = fmaxf(v, lane_dpp<0x124>(v));
+    v = fmaxf(v, lane_dpp<0x4E>(v));
+    v = fmaxf(v, lane_dpp<0xB1>(v));
     return v;
 }
 
@@ -112,7 +154,7 @@ inline int groups_of(int k) { return (k + kGroup - 1) / kGroup; }
 // quantisation group of a matrix descriptor (0 reads as 32) -> shift from sub-group index to scale index; -1: unsupported
 inline int gshift_of(int group) { return (group == 0 || group == 32) ? 0 : group == 64 ? 1 : group == 128 ? 2 : -1; }
 // scales per row: one per (32 << gshift) columns, the last group short when that does not divide k
-__host__ __device__ inline int scales_per_row(int k, int gshift) { return (k + (kGroup << gshift) - 1) / (kGroup << gshift); }
+__host__ __device__ inline int scales_per_row(int k, int gshift) { return (k + (kGroup << gshift) - 1) >> (5 + gshift); }   // kGroup = 32: a shift, not a division (these run ahead of a kernel's first load)
 
 // ---- launchers (defined in the .hip files), all asynchronous on `stream` --------------------------------------
 
@@ -138,6 +180,7 @@ struct GemvArgs {
     const float *part;
     int32_t part_splits, part_stride, part_chunk;
     int32_t part_used;               // filled in by launch_gemv_reg: splits that hold tokens when the host knows the position
+    int32_t units_div, units_mod;    // filled in by launch_gemv_reg: units of a row / wavefronts of the grid, and the remainder
     const uint16_t *norm_w;          // [k] fp16, norm modes only
     float eps;
     // matrix
