@@ -181,16 +181,22 @@ __device__ __forceinline__ float dpp_f(float v)
 template <int D, bool HALF>
 __global__ __launch_bounds__(256) void attn_mha_split_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict__ kc,
                                                              const uint16_t *__restrict__ vc, float *__restrict__ part, SeqTable st,
-                                                             int h, int cap, int chunk, int splits, int q_stride, int ps)
+                                                             int h, int cap, int chunk, int splits, int q_stride, int ps, int pos0,
+                                                             int slot0)
 {
     constexpr int LPT = D / 8;        // lanes that share one token (each owns 8 of its d elements)
     constexpr int TPW = kWave / LPT;  // tokens per load instruction of a wavefront
     constexpr int NL = 4;             // K (and V) loads per step
     constexpr int TS = NL * TPW;      // tokens per wavefront step
     __shared__ float sm[4 * (D + 2)];
+    // every kernel argument in scalar registers here: one round of scalar loads and one wait ahead of the first K / V
+    // request, instead of a round per group of arguments at the place of its first use
+    asm volatile("" ::"s"(q), "s"(kc), "s"(vc), "s"(part), "s"(h), "s"(cap), "s"(chunk), "s"(splits), "s"(q_stride), "s"(ps), "s"(pos0),
+                 "s"(slot0));
 
     const int i = blockIdx.z, split = blockIdx.y, head = blockIdx.x;
-    const RowInfo ri = row_info(st, i);
+    RowInfo ri = {0, pos0, slot0};                             // pos0 >= 0: the only row of the call, resolved by the host
+    if (pos0 < 0) ri = row_info(st, i);
     const int L = ri.pos + 1;
     if (chunk <= 0) chunk = attn_fold_chunk(L, splits);        // device-resident descriptor: the plan follows the L read here
     const int t_begin = split * chunk;
@@ -203,21 +209,31 @@ __global__ __launch_bounds__(256) void attn_mha_split_kernel(const uint16_t *__r
     // step s of this wavefront covers tokens t_begin + (4 s + wave) TS .. + TS - 1
     const int first = t_begin + wave * TS;
     const int ns = first < t_end ? (t_end - first + 4 * TS - 1) / (4 * TS) : 0;
-    const size_t row_stride = (size_t)h * D;                   // one token of the cache, all heads
-    const uint16_t *kbase = kc + ((size_t)ri.slot * cap) * row_stride + (size_t)head * D + e0;
-    const uint16_t *vbase = vc + ((size_t)ri.slot * cap) * row_stride + (size_t)head * D + e0;
+    // Addresses: a uniform base per (slot, head) plus a 32-bit byte offset per lane that K and V share (the launcher
+    // checks that a slot of the cache stays under 2 GiB).  The offsets of a step are those of the step before plus a
+    // constant, clamped to the last token of the split: two vector instructions per K / V pair instead of a 64-bit
+    // multiply-add each, ahead of the first request as well as in the stream.
+    const uint32_t row_bytes = (uint32_t)h * D * 2;            // one token of the cache, all heads
+    const size_t slot_base = ((size_t)ri.slot * cap) * ((size_t)h * D) + (size_t)head * D;
+    const char *kslot = (const char *)(kc + slot_base), *vslot = (const char *)(vc + slot_base);
+    const uint32_t last_off = (uint32_t)(t_end - 1) * row_bytes + (uint32_t)e0 * 2;
+    const uint32_t step_bytes = 4 * TS * row_bytes;
+    uint32_t run[NL];                                          // offsets of the next step to request, not clamped
+#pragma unroll
+    for (int j = 0; j < NL; ++j) run[j] = (uint32_t)(first + sub + j * TPW) * row_bytes + (uint32_t)e0 * 2;
 
     struct Step {
         u32x4a_t k[NL], v[NL];
     };
-    auto step_load = [&](Step &sp, int s) {
+    // requests step s; the calls come in the order s = 0, 1, 2, ..
+    auto step_load = [&](Step &sp, int) {
         __builtin_amdgcn_sched_barrier(0);
-        const int t0 = first + s * 4 * TS + sub;
 #pragma unroll
         for (int j = 0; j < NL; ++j) {
-            const size_t at = (size_t)min(t0 + j * TPW, t_end - 1) * row_stride;    // tokens past the end re-read the last one, masked below
-            sp.k[j] = stream_load((const u32x4a_t *)(kbase + at));
-            sp.v[j] = stream_load((const u32x4a_t *)(vbase + at));
+            const uint32_t at = min(run[j], last_off);         // tokens past the end re-read the last one, masked below
+            sp.k[j] = stream_load((const u32x4a_t *)(kslot + at));
+            sp.v[j] = stream_load((const u32x4a_t *)(vslot + at));
+            run[j] += step_bytes;
         }
         __builtin_amdgcn_sched_barrier(0);
     };
@@ -395,9 +411,10 @@ static hipError_t launch_d(const uint16_t *q, int q_stride, const relax_kv_cache
     const int rep = dm.n_heads / dm.n_kv_heads;
     hipError_t e;
     if (attn_gqa_supported(dm)) e = launch_attention_gqa_split(q, q_stride, cache, dm, st, pl, partials, stream);   // MFMA kernel for grouped heads
-    else if (rep == 1) {
+    else if (rep == 1 && attn_mha_split_supported(dm)) {
+        const HostRow hr = host_row(st);
         hipLaunchKernelGGL((attn_mha_split_kernel<D, false>), dim3(dm.n_heads, pl.splits, st.n), dim3(256), 0, stream, q, cache.k, cache.v, partials, st,
-                           dm.n_heads, dm.kv_capacity, pl.chunk, pl.splits, q_stride, D + 2);
+                           dm.n_heads, dm.kv_capacity, pl.chunk, pl.splits, q_stride, D + 2, hr.pos, hr.slot);
         e = hipGetLastError();
     }
     else if (rep % 8 == 0) e = launch_split<D, 8>(q, q_stride, cache, dm, st, pl, partials, stream);
@@ -415,19 +432,22 @@ static hipError_t launch_d(const uint16_t *q, int q_stride, const relax_kv_cache
 // format: head_dim normalised outputs acc / l as fp16, then (max, sum) as fp32 at float index head_dim / 2; part_stride >= head_dim / 2 + 2
 bool attn_mha_split_supported(const relax_layer_dims &dm)
 {
-    return dm.n_heads == dm.n_kv_heads && (dm.head_dim == 128 || dm.head_dim == 64);
+    // 32-bit byte offsets inside a slot of the cache (plus the two steps a wavefront requests past its split)
+    const size_t slot_bytes = ((size_t)dm.kv_capacity + 256) * dm.n_kv_heads * dm.head_dim * 2;
+    return dm.n_heads == dm.n_kv_heads && (dm.head_dim == 128 || dm.head_dim == 64) && slot_bytes < ((size_t)1 << 31);
 }
 
 hipError_t launch_attention_mha_split(const uint16_t *q, int32_t q_stride, const relax_kv_cache &cache, const relax_layer_dims &dm,
                                       const SeqTable &st, int32_t chunk, int32_t splits, int32_t part_stride, float *partials, hipStream_t stream)
 {
     const dim3 grid(dm.n_heads, splits, st.n);
+    const HostRow hr = host_row(st);
     if (dm.head_dim == 128)
         hipLaunchKernelGGL((attn_mha_split_kernel<128, true>), grid, dim3(256), 0, stream, q, cache.k, cache.v, partials, st, dm.n_heads,
-                           dm.kv_capacity, chunk, splits, q_stride, part_stride);
+                           dm.kv_capacity, chunk, splits, q_stride, part_stride, hr.pos, hr.slot);
     else
         hipLaunchKernelGGL((attn_mha_split_kernel<64, true>), grid, dim3(256), 0, stream, q, cache.k, cache.v, partials, st, dm.n_heads,
-                           dm.kv_capacity, chunk, splits, q_stride, part_stride);
+                           dm.kv_capacity, chunk, splits, q_stride, part_stride, hr.pos, hr.slot);
     return hipGetLastError();
 }
 

@@ -58,7 +58,7 @@ __global__ __launch_bounds__(1024) void rmsnorm_kernel(const T *x, const uint16_
     ss = wave_sum(ss);
     if (lane == 0) red[wave] = ss;
     __syncthreads();
-    const float inv = 1.0f / sqrtf(block_total(red, NT >> 6) / (float)H + eps);
+    const float inv = rms_scale(block_total(red, NT >> 6), 1.0f / (float)H, eps);
     if (vec) {
 #pragma unroll
         for (int p = 0; p < kNormPasses; ++p) {

@@ -362,7 +362,7 @@ __global__ __launch_bounds__(1024) void skinny_finish_norm_kernel(const float *_
     ss = wave_sum(ss);
     if (lane == 0) red[wave] = ss;
     __syncthreads();
-    const float inv = 1.0f / sqrtf(block_total(red, T >> 6) / (float)m + eps);
+    const float inv = rms_scale(block_total(red, T >> 6), 1.0f / (float)m, eps);
 #pragma unroll
     for (int p = 0; p < kFuseNormPasses; ++p) {
         const int c = (p * T + tid) * 8;

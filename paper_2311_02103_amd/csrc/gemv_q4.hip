@@ -130,7 +130,7 @@ __global__ __launch_bounds__(512) void gemv_q4_kernel(GemvArgs a)
         __syncthreads();
         float tot = 0.0f;
         for (int w = 0; w < nwaves; ++w) tot += red[w];
-        inv = 1.0f / sqrtf(tot / (float)k + a.eps);
+        inv = rms_scale(tot, 1.0f / (float)k, a.eps);
     }
     for (int c = tid; c < kpad; c += blockDim.x) {
         float v = 0.0f;
@@ -357,7 +357,7 @@ __global__ __launch_bounds__(kSThreads) void gemv_q4_stream_kernel(GemvArgs a)
         float tot = 0.0f;
 #pragma unroll
         for (int w = 0; w < kSWaves; ++w) tot += red[w];
-        const float inv = 1.0f / sqrtf(tot / (float)k + a.eps);
+        const float inv = rms_scale(tot, 1.0f / (float)k, a.eps);
 #pragma unroll
         for (int p = 0; p < PN; ++p) {
             const int c8 = tid + p * kSThreads;

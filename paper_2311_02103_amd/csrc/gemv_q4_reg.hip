@@ -205,6 +205,17 @@ __global__ __launch_bounds__(kRThreads) void gemv_q4_reg_kernel(GemvArgs a)
     __shared__ __align__(16) uint16_t xs[NG * 2048];
     __shared__ float red[kRWaves];
     __shared__ float res_all[kRWaves][kRMaxUnits * 2 + 4];     // one sum per row of the wavefront (+ the dead rows of a last slot)
+    // The arguments this variant uses, in scalar registers from here on: one round of scalar loads and one wait ahead of
+    // the first request, none at the place of a first use further down (where the stream or the epilogue would wait).
+    asm volatile("" ::"s"(a.x), "s"(a.q), "s"(a.s), "s"(a.m), "s"(a.k), "s"(a.gshift), "s"(a.units_div), "s"(a.units_mod));
+    if (XMODE == X_F16_NORM || XMODE == X_F32_NORM) asm volatile("" ::"s"(a.norm_w), "s"(a.eps));
+    if (XMODE == X_ATTN_MERGE) asm volatile("" ::"s"(a.part), "s"(a.part_splits), "s"(a.part_stride), "s"(a.part_used), "s"(a.h), "s"(a.d));
+    if (EPI == EPI_RESID_F32) asm volatile("" ::"s"(a.out_f32), "s"(a.resid));
+    if (EPI == EPI_RESID_F16) asm volatile("" ::"s"(a.out_f16), "s"(a.resid));
+    if (EPI == EPI_F16 || EPI == EPI_SWIGLU) asm volatile("" ::"s"(a.out_f16));
+    if (EPI == EPI_ROPE_KV)
+        asm volatile("" ::"s"(a.out_f16), "s"(a.rope), "s"(a.kcache), "s"(a.vcache), "s"(a.h), "s"(a.g), "s"(a.d), "s"(a.kv_capacity), "s"(a.pos0),
+                     "s"(a.slot0));
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int i = blockIdx.y;
     const int k = a.k, G = k >> 5, kw = k >> 3, SG = scales_per_row(k, a.gshift);
@@ -308,6 +319,7 @@ __global__ __launch_bounds__(kRThreads) void gemv_q4_reg_kernel(GemvArgs a)
 
     // ---- stage the (optionally RMS-normalised) x row in LDS as fp16, packet order [x0 x4 x1 x5 x2 x6 x3 x7] ----
     float inv = 1.0f;
+    const float inv_k = 1.0f / (float)k;                           // ahead of the reduction it is used with
     float xf[kNorm ? NG : 1][8];
     if (kNorm) {
         float ss = 0.0f;
@@ -333,7 +345,7 @@ __global__ __launch_bounds__(kRThreads) void gemv_q4_reg_kernel(GemvArgs a)
         float tot = 0.0f;
 #pragma unroll
         for (int w = 0; w < kRWaves; ++w) tot += red[w];
-        inv = 1.0f / sqrtf(tot / (float)k + a.eps);
+        inv = rms_scale(tot, inv_k, a.eps);
     }
 #pragma unroll
     for (int p = 0; p < NG; ++p) {

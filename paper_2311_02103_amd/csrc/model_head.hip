@@ -77,7 +77,7 @@ __global__ __launch_bounds__(256) void final_norm_kernel(const uint16_t *__restr
         ss = wave_sum(ss);
         if (lane == 0) red[wave] = ss;
         __syncthreads();
-        const float inv = 1.0f / sqrtf((red[0] + red[1] + red[2] + red[3]) / (float)H + eps);
+        const float inv = rms_scale((red[0] + red[1] + red[2] + red[3]), 1.0f / (float)H, eps);
 #pragma unroll
         for (int p = 0; p < kNormPasses; ++p) {
             const int c8 = tid + p * 256;
@@ -103,7 +103,7 @@ __global__ __launch_bounds__(256) void final_norm_kernel(const uint16_t *__restr
     ss = wave_sum(ss);
     if (lane == 0) red[wave] = ss;
     __syncthreads();
-    const float inv = 1.0f / sqrtf((red[0] + red[1] + red[2] + red[3]) / (float)H + eps);
+    const float inv = rms_scale((red[0] + red[1] + red[2] + red[3]), 1.0f / (float)H, eps);
     for (int c = tid; c < H; c += 256) y[(size_t)b * H + c] = f2h(h2f(x[base + c]) * inv * h2f(w[c]));
 }
 

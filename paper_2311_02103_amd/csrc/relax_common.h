@@ -53,6 +53,17 @@ struct RowInfo {
     int32_t seq, pos, slot;
 };
 
+// The only row of a call whose descriptor the host holds: its position and slot travel as two scalars, and the kernel
+// has them with its first round of argument loads instead of reading the table.  pos < 0: resolve on the device.
+struct HostRow {
+    int32_t pos, slot;
+};
+inline HostRow host_row(const SeqTable &st)
+{
+    if (st.n == 1 && st.B == 1 && st.dev == nullptr) return {st.kv_len[0] - st.q_len[0] - st.q_start[0], st.slot[0]};
+    return {-1, 0};
+}
+
 // row of the call -> (sequence, position in its cache slot, slot)
 __device__ inline RowInfo row_info(const SeqTable &st, int32_t row)
 {
@@ -143,6 +154,12 @@ __device__ inline float wave_max(float v)
     v = fmaxf(v, lane_dpp<0xB1>(v));
     return v;
 }
+
+// 1 / sqrt(mean square + eps) of an RMSNorm from the sum of squares: one multiply-add and v_rsq_f32 (1 ulp) behind the
+// reduction instead of two IEEE divisions and a square root (some forty dependent instructions that every fused
+// prologue waits for); 1 / k does not depend on the data and can be ready before the sum is.  Every kernel that
+// normalises uses this, so the fused and the stand-alone forms still agree bit for bit.
+__device__ __forceinline__ float rms_scale(float sum_sq, float inv_k, float eps) { return __builtin_amdgcn_rsqf(fmaf(sum_sq, inv_k, eps)); }
 
 __device__ inline float h2f(uint16_t bits) { return __half2float(__ushort_as_half(bits)); }
 __device__ inline uint16_t f2h(float v) { return __half_as_ushort(__float2half_rn(v)); }
