@@ -214,27 +214,32 @@ __global__ void unpack_q3n_kernel(const uint32_t *q, int8_t *out, int m, int k)
 
 // V partial sums per lane -> lane l holds the total of value l % V (a transposing reduction: the number of live values
 // halves with every exchange)
+template <int V, int BIT = 1>
+__device__ __forceinline__ void fold_values(float *v, int lane)
+{
+    if constexpr (BIT < V) {
+        const bool up = lane & BIT;
+#pragma unroll
+        for (int i = 0; i < V / (2 * BIT); ++i) {
+            const float keep = up ? v[2 * i + 1] : v[2 * i], give = up ? v[2 * i] : v[2 * i + 1];
+            v[i] = keep + lane_xor<BIT>(give);
+        }
+        fold_values<V, 2 * BIT>(v, lane);
+    }
+}
+template <int OFF>
+__device__ __forceinline__ float sum_from(float r)
+{
+    if constexpr (OFF < kWave) return sum_from<2 * OFF>(lane_xor_sum<OFF>(r));
+    else return r;
+}
+// register-to-register exchanges only (DPP, permlane swaps): the partners and the order of a butterfly over lane ^ 1, 2, ..
 template <int V>
 __device__ __forceinline__ float reduce_many(float *v, int lane)
 {
     static_assert(V == 1 || V == 2 || V == 4 || V == 8, "1, 2, 4 or 8 values");
-    int n = V;
-#pragma unroll
-    for (int bit = 1; bit < V; bit <<= 1) {
-        const bool up = lane & bit;
-#pragma unroll
-        for (int i = 0; i < V / 2; ++i) {
-            if (2 * i + 1 < n) {
-                const float keep = up ? v[2 * i + 1] : v[2 * i], give = up ? v[2 * i] : v[2 * i + 1];
-                v[i] = keep + __shfl_xor(give, bit, kWave);
-            }
-        }
-        n >>= 1;
-    }
-    float r = v[0];
-#pragma unroll
-    for (int off = V; off < kWave; off <<= 1) r += __shfl_xor(r, off, kWave);
-    return r;
+    fold_values<V>(v, lane);
+    return sum_from<V>(v[0]);
 }
 
 constexpr int kQ3nRows = 2;                                  // matrix rows per slot; two slots in flight per wavefront
@@ -260,10 +265,6 @@ __global__ __launch_bounds__(kQ3Threads) void gemv_q3n_kernel(const uint16_t *__
                 const uint4 raw = *(const uint4 *)(x + (size_t)i * k + (size_t)g * 32 + v4 * 8);
                 xp[xr][j][4 * v4] = raw.x, xp[xr][j][4 * v4 + 1] = raw.y, xp[xr][j][4 * v4 + 2] = raw.z, xp[xr][j][4 * v4 + 3] = raw.w;
             }
-            float sc[3] = {0.0f, 0.0f, 0.0f};
-#pragma unroll
-            for (int p = 0; p < 16; ++p) sc[q3n_class(p)] = dot2(0x3C003C00u, xp[xr][j][p], sc[q3n_class(p)]);
-            corr[xr][j] = 1028.0f * sc[0] + 132.0f * sc[1] + 20.0f * sc[2];
         }
     }
     bool on[J];
@@ -277,6 +278,7 @@ __global__ __launch_bounds__(kQ3Threads) void gemv_q3n_kernel(const uint16_t *__
     const int U = (m + kQ3nRows - 1) / kQ3nRows;             // row pairs
     const int W = gridDim.x * kQ3Waves, wg = blockIdx.x * kQ3Waves + wave;
     auto slot_load = [&](Slot &sl, int u) {                  // unit u; past the end: the last unit again (dropped)
+        __builtin_amdgcn_sched_barrier(0);                   // the requests of a slot stay together, where they are written
         u = min(u, U - 1);
 #pragma unroll
         for (int rr = 0; rr < kQ3nRows; ++rr) {
@@ -289,9 +291,23 @@ __global__ __launch_bounds__(kQ3Threads) void gemv_q3n_kernel(const uint16_t *__
                 sl.sc[rr][j] = s[row * G + g];
             }
         }
+        __builtin_amdgcn_sched_barrier(0);
     };
-    auto consume = [&](const Slot &sl, int u) {
-        float tot[kQ3nRows * NR];
+    // both slots are requested before anything waits for x
+    Slot a, b;
+    slot_load(a, wg);
+    slot_load(b, wg + W);
+#pragma unroll
+    for (int xr = 0; xr < NR; ++xr)
+#pragma unroll
+        for (int j = 0; j < J; ++j) {
+            float sc[3] = {0.0f, 0.0f, 0.0f};
+#pragma unroll
+            for (int p = 0; p < 16; ++p) sc[q3n_class(p)] = dot2(0x3C003C00u, xp[xr][j][p], sc[q3n_class(p)]);
+            corr[xr][j] = 1028.0f * sc[0] + 132.0f * sc[1] + 20.0f * sc[2];
+        }
+    // the dot products of a slot; its registers are free afterwards, so the next request goes out before the reduction
+    auto dots = [&](const Slot &sl, float *tot) {
 #pragma unroll
         for (int rr = 0; rr < kQ3nRows; ++rr) {
 #pragma unroll
@@ -310,20 +326,22 @@ __global__ __launch_bounds__(kQ3Threads) void gemv_q3n_kernel(const uint16_t *__
                 }
             }
         }
+    };
+    auto finish = [&](float *tot, int u) {
         const float r = reduce_many<kQ3nRows * NR>(tot, lane);
         if (u < U && lane < kQ3nRows * NR) {                 // lane l: row l / NR of the unit, x row l % NR of the pass
             const int row = u * kQ3nRows + lane / NR, i = i0 + lane % NR;
             if (row < m && i < n) out[(size_t)i * m + row] = f2h(r);
         }
     };
-    Slot a, b;
-    slot_load(a, wg);
-    slot_load(b, wg + W);
     for (int u = wg; u < U; u += 2 * W) {
-        consume(a, u);
+        float ta[kQ3nRows * NR], tb[kQ3nRows * NR];
+        dots(a, ta);
         slot_load(a, u + 2 * W);
-        consume(b, u + W);
+        finish(ta, u);
+        dots(b, tb);
         slot_load(b, u + 3 * W);
+        finish(tb, u + W);
     }
 }
 

@@ -131,6 +131,25 @@ __device__ __forceinline__ float2 pair_xor16(float v)
 __device__ __forceinline__ float xor32_sum(float v) { const float2 p = pair_xor32(v); return p.x + p.y; }
 __device__ __forceinline__ float xor16_sum(float v) { const float2 p = pair_xor16(v); return p.x + p.y; }
 
+// the value lane ^ OFF holds, for OFF < 16 (DPP only; lane ^ 4 = mirror of the half row of eight, then of the quad)
+template <int OFF>
+__device__ __forceinline__ float lane_xor(float v)
+{
+    static_assert(OFF == 1 || OFF == 2 || OFF == 4 || OFF == 8, "within a row of 16 lanes");
+    if (OFF == 1) return lane_dpp<0xB1>(v);
+    if (OFF == 2) return lane_dpp<0x4E>(v);
+    if (OFF == 4) return lane_dpp<0x1B>(lane_dpp<0x141>(v));
+    return lane_dpp<0x128>(v);
+}
+// v + (the value lane ^ OFF holds), any OFF of a wavefront
+template <int OFF>
+__device__ __forceinline__ float lane_xor_sum(float v)
+{
+    if constexpr (OFF == 32) return xor32_sum(v);
+    else if constexpr (OFF == 16) return xor16_sum(v);
+    else return v + lane_xor<OFF>(v);
+}
+
 __device__ inline float wave_sum(float v)
 {
     v = xor32_sum(v);
