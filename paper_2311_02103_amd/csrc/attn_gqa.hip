@@ -50,6 +50,27 @@ __global__ __launch_bounds__(256, 2) void attn_gqa_kernel(const uint16_t *__rest
     const int col = lane & 31, hf = lane >> 5;
     const float scale = 1.0f / sqrtf((float)D);
 
+    uint16_t *vs = vs_all + wave * 32 * VP;
+    const size_t slot_base = (size_t)ri.slot * cap;
+    const int tr_row = hf * 4 + ((lane & 15) >> 2), tr_col = ((lane >> 4) & 1) * 16 + (lane & 3) * 4;
+
+    // registers of one tile in flight: the lane's run of its K row (KS packets) and its share of the V tile
+    u32x4_t kreg[KS], vreg[VPK];
+    auto tile_load = [&](int t0) {                             // rows are clamped to the split: masked later
+        const size_t krow = ((slot_base + min(t0 + col, t_end - 1)) * g + kvh) * D + hf * 8;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) kreg[ks] = *(const u32x4_t *)(kc + krow + ks * 16);
+#pragma unroll
+        for (int p = 0; p < VPK; ++p) {
+            const int pk = lane + p * 64, r = pk / (D / 8), c = pk % (D / 8);
+            vreg[p] = stream_load((const u32x4_t *)(vc + ((slot_base + min(t0 + r, t_end - 1)) * g + kvh) * D + c * 8));
+        }
+    };
+
+    // the first K / V tile is requested before the Q fragments are staged: it does not depend on them, and a workgroup
+    // lives for a few tiles only
+    const int t_first = t_begin + wave * 32;
+    if (t_first < t_end) tile_load(t_first);
     // ---- Q fragments: lane owns head (col) of the group; k step ks pairs d = 16 ks + 8 hf .. + 8 of K and Q.
     // The same for every wavefront and every tile: kept in LDS (KS x 64 lanes x 16 bytes), not in registers, so that
     // two workgroups fit a CU ----
@@ -69,25 +90,6 @@ __global__ __launch_bounds__(256, 2) void attn_gqa_kernel(const uint16_t *__rest
         for (int v = 0; v < 16; ++v) O[db][v] = 0.0f;
     float m_run = -INFINITY, l_run = 0.0f;
 
-    uint16_t *vs = vs_all + wave * 32 * VP;
-    const size_t slot_base = (size_t)ri.slot * cap;
-    const int tr_row = hf * 4 + ((lane & 15) >> 2), tr_col = ((lane >> 4) & 1) * 16 + (lane & 3) * 4;
-
-    // registers of one tile in flight: the lane's run of its K row (KS packets) and its share of the V tile
-    u32x4_t kreg[KS], vreg[VPK];
-    auto tile_load = [&](int t0) {                             // rows are clamped to the split: masked later
-        const size_t krow = ((slot_base + min(t0 + col, t_end - 1)) * g + kvh) * D + hf * 8;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) kreg[ks] = *(const u32x4_t *)(kc + krow + ks * 16);
-#pragma unroll
-        for (int p = 0; p < VPK; ++p) {
-            const int pk = lane + p * 64, r = pk / (D / 8), c = pk % (D / 8);
-            vreg[p] = stream_load((const u32x4_t *)(vc + ((slot_base + min(t0 + r, t_end - 1)) * g + kvh) * D + c * 8));
-        }
-    };
-
-    const int t_first = t_begin + wave * 32;
-    if (t_first < t_end) tile_load(t_first);
     for (int t0 = t_first; t0 < t_end; t0 += 128) {
         // ---- S^T = K Q^T on the tile in registers; V tile to the wavefront's LDS region ----
         float16_t S;

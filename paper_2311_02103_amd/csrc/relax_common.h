@@ -72,6 +72,23 @@ __device__ inline RowInfo row_info(const SeqTable &st, int32_t row)
         r.seq = 0;
         r.pos = st.kv_len[0] - st.q_len[0] + (row - st.q_start[0]);
         r.slot = st.slot[0];
+    } else if (st.q_max == 1 && st.n == st.B) {
+        // a decode batch (every sequence brings one row, so row b is sequence b): no walk over the starts -- one read of
+        // the device table, or one pass of compares over the inline one instead of the cumulative search below
+        r.seq = row;
+        if (st.dev) {
+            r.pos = st.dev[2 * st.B + row] - 1;
+            r.slot = st.dev[3 * st.B + row];
+        } else {
+            int kl = st.kv_len[0], sl = st.slot[0];
+#pragma unroll
+            for (int j = 1; j < kInlineSeqs; ++j) {
+                kl = row == j ? st.kv_len[j] : kl;
+                sl = row == j ? st.slot[j] : sl;
+            }
+            r.pos = kl - 1;
+            r.slot = sl;
+        }
     } else if (st.dev) {
         const int32_t *qs = st.dev, *ql = st.dev + st.B, *kl = st.dev + 2 * st.B, *sl = st.dev + 3 * st.B;
         int b = 0;
