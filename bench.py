@@ -571,7 +571,7 @@ def bench_batch_sweep(args, np, torch, wl, rx):
     model this small), the few-row MFMA kernel up to 128 rows (64 for the tall gate/up matrix), the tiled GEMM above."""
     from paper_2311_02103_amd.runtime import DeviceLayer, to_device
     shape, seed, cap, L = wl.LLAMA7B, 6, 320, 256
-    ns = [1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64, 65, 96, 128, 129, 192, 256]
+    ns = [int(v) for v in args.sweep_rows.split(",")] if args.sweep_rows else [1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64, 65, 96, 128, 129, 192, 256]
     steps = args.steps = args.steps or 60
     warmup = args.warmup = 10 if args.warmup is None else args.warmup
     sets = max(1, min(args.sets, 3))                # three sets = 342 MB of weights: more than the last-level cache
@@ -875,6 +875,7 @@ def main():
     ap.add_argument("--workload", choices=["decode_layer", "prefill_layer", "model_7b", "batched_70b", "ceilings", "memory_plan", "batch_sweep", "half_sweep", "q3_matvec"],
                     default="decode_layer")
     ap.add_argument("--n", type=int, default=2048, help="rows of the prefill_layer workload")
+    ap.add_argument("--sweep-rows", default="", help="batch_sweep: comma-separated row counts instead of the default list (short profiling runs)")
     ap.add_argument("--layers", type=int, default=0, help="model workloads: override the layer count (short profiling runs)")
     ap.add_argument("--sets", type=int, default=8, help="distinct weight sets rotated through")
     ap.add_argument("--mode", choices=["graph", "eager"], default=None,

@@ -212,36 +212,6 @@ __global__ void unpack_q3n_kernel(const uint32_t *q, int8_t *out, int m, int k)
     out[e] = (int8_t)((int)u - 4);
 }
 
-// V partial sums per lane -> lane l holds the total of value l % V (a transposing reduction: the number of live values
-// halves with every exchange)
-template <int V, int BIT = 1>
-__device__ __forceinline__ void fold_values(float *v, int lane)
-{
-    if constexpr (BIT < V) {
-        const bool up = lane & BIT;
-#pragma unroll
-        for (int i = 0; i < V / (2 * BIT); ++i) {
-            const float keep = up ? v[2 * i + 1] : v[2 * i], give = up ? v[2 * i] : v[2 * i + 1];
-            v[i] = keep + lane_xor<BIT>(give);
-        }
-        fold_values<V, 2 * BIT>(v, lane);
-    }
-}
-template <int OFF>
-__device__ __forceinline__ float sum_from(float r)
-{
-    if constexpr (OFF < kWave) return sum_from<2 * OFF>(lane_xor_sum<OFF>(r));
-    else return r;
-}
-// register-to-register exchanges only (DPP, permlane swaps): the partners and the order of a butterfly over lane ^ 1, 2, ..
-template <int V>
-__device__ __forceinline__ float reduce_many(float *v, int lane)
-{
-    static_assert(V == 1 || V == 2 || V == 4 || V == 8, "1, 2, 4 or 8 values");
-    fold_values<V>(v, lane);
-    return sum_from<V>(v[0]);
-}
-
 constexpr int kQ3nRows = 2;                                  // matrix rows per slot; two slots in flight per wavefront
 
 // out[i0 + xr, r] for NR rows of x per pass: grid = (workgroups, passes).  A wavefront owns the row pairs wg, wg + W, ...

@@ -194,17 +194,23 @@ constexpr int rows_per_slot(bool few_rows)
     return NG > 4 ? 1 : (NG <= 2 && few_rows ? 1 : 2);
 }
 
-// grid: x = workgroups (at most one per CU and row), y = row of x
+// grid: x = workgroups (at most one per CU and pass), y = pass: NR rows of x that share one pass over the weights (a
+// batch of two to four decode rows: the stream is the same, the dot products of a group are taken once per row on the
+// words decoded once; a ragged last pass re-reads the last row and stores nothing for it)
 // DEV: the position of the (single) row comes from the device-resident descriptor a.seqs.dev instead of a.pos0 / a.slot0
 // (a captured launch is then valid for later positions too); only the two variants that need a position have it.
-template <int XMODE, int EPI, int NG, int R, bool DEV = false>
-__global__ __launch_bounds__(kRThreads) void gemv_q4_reg_kernel(GemvArgs a)
+// Several rows per pass keep NR times the x registers: those variants are compiled for one wavefront per SIMD (which is
+// how every variant runs: one workgroup per CU), so that the allocator may use the whole register file instead of spilling.
+template <int XMODE, int EPI, int NG, int R, bool DEV = false, int NR = 1>
+__global__ __launch_bounds__(kRThreads) __attribute__((amdgpu_waves_per_eu(1, 1))) void gemv_q4_reg_kernel(GemvArgs a)
 {
+    static_assert(NR == 1 || (XMODE != X_ATTN_MERGE && !DEV), "several rows per pass: plain and normalising prologues, host descriptor");
     constexpr int NSLOT = kRSlots, E = R * NG;
+    constexpr int kResPitch = NR * (kRMaxUnits * 2 + 4);
     constexpr int kFirstRagged = NG >= 4 ? NG - 2 : NG - 1;        // first chunk of 2048 columns that a row may end in
-    __shared__ __align__(16) uint16_t xs[NG * 2048];
-    __shared__ float red[kRWaves];
-    __shared__ float res_all[kRWaves][kRMaxUnits * 2 + 4];     // one sum per row of the wavefront (+ the dead rows of a last slot)
+    __shared__ __align__(16) uint16_t xs[NR * NG * 2048];
+    __shared__ float red[NR * kRWaves];
+    __shared__ float res_all[kRWaves][kResPitch];              // one sum per matrix row of the wavefront and row of x (+ the dead rows of a last slot)
     // The arguments this variant uses, in scalar registers from here on: one round of scalar loads and one wait ahead of
     // the first request, none at the place of a first use further down (where the stream or the epilogue would wait).
     asm volatile("" ::"s"(a.x), "s"(a.q), "s"(a.s), "s"(a.m), "s"(a.k), "s"(a.gshift), "s"(a.units_div), "s"(a.units_mod));
@@ -213,11 +219,13 @@ __global__ __launch_bounds__(kRThreads) void gemv_q4_reg_kernel(GemvArgs a)
     if (EPI == EPI_RESID_F32) asm volatile("" ::"s"(a.out_f32), "s"(a.resid));
     if (EPI == EPI_RESID_F16) asm volatile("" ::"s"(a.out_f16), "s"(a.resid));
     if (EPI == EPI_F16 || EPI == EPI_SWIGLU) asm volatile("" ::"s"(a.out_f16));
-    if (EPI == EPI_ROPE_KV)
-        asm volatile("" ::"s"(a.out_f16), "s"(a.rope), "s"(a.kcache), "s"(a.vcache), "s"(a.h), "s"(a.g), "s"(a.d), "s"(a.kv_capacity), "s"(a.pos0),
-                     "s"(a.slot0));
+    if (EPI == EPI_ROPE_KV) asm volatile("" ::"s"(a.out_f16), "s"(a.rope), "s"(a.h), "s"(a.g), "s"(a.d), "s"(a.pos0), "s"(a.slot0));
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int i = blockIdx.y;
+    const int i0 = blockIdx.y * NR;
+    const int i = i0;                                          // NR == 1: the row
+    int irow[NR];                                              // a ragged last pass re-reads the last row (never stored)
+#pragma unroll
+    for (int xr = 0; xr < NR; ++xr) irow[xr] = min(i0 + xr, a.n - 1);
     const int k = a.k, G = k >> 5, kw = k >> 3, SG = scales_per_row(k, a.gshift);
     const int U = unit_count_r<EPI>(a);
     const int W = gridDim.x * kRWaves, wg = blockIdx.x * kRWaves + wave;
@@ -225,18 +233,24 @@ __global__ __launch_bounds__(kRThreads) void gemv_q4_reg_kernel(GemvArgs a)
     float *res = res_all[wave];
 
     // ---- what the epilogue reads, then the x row, then the first slots: requested in the order they are needed ----
-    RowInfo ri = {0, 0, 0};
-    if (EPI == EPI_ROPE_KV) {
-        if (DEV) ri = row_info(a.seqs, i);                         // scalar loads of the descriptor
-        else if (a.n == 1) ri.pos = a.pos0, ri.slot = a.slot0;     // the host resolved the only row: no table walk up front
-        else ri = row_info(a.seqs, i);
+    int rpos[NR], rslot[NR];                                   // position and cache slot of every row (rotary + append epilogue)
+#pragma unroll
+    for (int xr = 0; xr < NR; ++xr) {
+        rpos[xr] = rslot[xr] = 0;
+        if (EPI == EPI_ROPE_KV) {
+            if (!DEV && a.n == 1) {
+                rpos[xr] = a.pos0, rslot[xr] = a.slot0;            // the host resolved the only row: no table walk up front
+            } else {
+                const RowInfo t = row_info(a.seqs, irow[xr]);      // DEV: scalar loads of the descriptor
+                rpos[xr] = t.pos, rslot[xr] = t.slot;
+            }
+        }
     }
 
     // pass p of the staging covers chunk p of 2048 columns: thread t holds word t & 3 of group 64 p + (t >> 2)
     constexpr bool kNorm = (XMODE == X_F16_NORM || XMODE == X_F32_NORM), kMerge = (XMODE == X_ATTN_MERGE);
     constexpr int MS = kAttnMergeSplits;
-    const size_t xbase = (size_t)i * k;
-    u32x4_t xraw[NG], xraw2[XMODE == X_F32_NORM ? NG : 1], wnr[kNorm ? NG : 1];
+    u32x4_t xraw[NR][NG], xraw2[NR][XMODE == X_F32_NORM ? NG : 1], wnr[kNorm ? NG : 1];
     // X_ATTN_MERGE: x is the attention output, still in split form.  The thread's 8 elements belong to one head; it
     // reads their accumulators and the (max, sum) pair of every split (splits past the used ones re-read the last)
     u32x4_t pacc[kMerge ? NG : 1][kMerge ? MS : 1];            // 8 normalised outputs of the split, fp16
@@ -262,10 +276,14 @@ __global__ __launch_bounds__(kRThreads) void gemv_q4_reg_kernel(GemvArgs a)
                 pml[p][s] = *(const float2 *)(ps + (a.d >> 1));
             }
         } else if (XMODE == X_F32_NORM) {
-            xraw[p] = *(const u32x4_t *)((const float *)a.x + xbase + (size_t)c8 * 8);
-            xraw2[p] = *(const u32x4_t *)((const float *)a.x + xbase + (size_t)c8 * 8 + 4);
+#pragma unroll
+            for (int xr = 0; xr < NR; ++xr) {
+                xraw[xr][p] = *(const u32x4_t *)((const float *)a.x + (size_t)irow[xr] * k + (size_t)c8 * 8);
+                xraw2[xr][p] = *(const u32x4_t *)((const float *)a.x + (size_t)irow[xr] * k + (size_t)c8 * 8 + 4);
+            }
         } else {
-            xraw[p] = *(const u32x4_t *)((const uint16_t *)a.x + xbase + (size_t)c8 * 8);
+#pragma unroll
+            for (int xr = 0; xr < NR; ++xr) xraw[xr][p] = *(const u32x4_t *)((const uint16_t *)a.x + (size_t)irow[xr] * k + (size_t)c8 * 8);
         }
         if (kNorm) wnr[p] = *(const u32x4_t *)(a.norm_w + (size_t)c8 * 8);
     }
@@ -314,39 +332,52 @@ __global__ __launch_bounds__(kRThreads) void gemv_q4_reg_kernel(GemvArgs a)
 #pragma unroll
     for (int t = 0; t < NSLOT; ++t) slot_load(sl[t], t);
     // behind the first slots in program order: its address arithmetic runs while they are in flight
-    const float2 pre = epi_fetch<EPI>(a, i, ri, lane < mine ? wg + lane * W : min(wg, U - 1));
+    float2 pre[NR];
+#pragma unroll
+    for (int xr = 0; xr < NR; ++xr) pre[xr] = epi_fetch<EPI>(a, irow[xr], RowInfo{0, rpos[xr], rslot[xr]}, lane < mine ? wg + lane * W : min(wg, U - 1));
     __builtin_amdgcn_sched_barrier(0);
 
     // ---- stage the (optionally RMS-normalised) x row in LDS as fp16, packet order [x0 x4 x1 x5 x2 x6 x3 x7] ----
-    float inv = 1.0f;
     const float inv_k = 1.0f / (float)k;                           // ahead of the reduction it is used with
-    float xf[kNorm ? NG : 1][8];
+    float inv[NR];
+    float xf[NR][kNorm ? NG : 1][8];
+#pragma unroll
+    for (int xr = 0; xr < NR; ++xr) inv[xr] = 1.0f;
     if (kNorm) {
-        float ss = 0.0f;
 #pragma unroll
-        for (int p = 0; p < NG; ++p) {
-            const bool on = (p * kRThreads + tid) < kw;
-            if (XMODE == X_F32_NORM) {
+        for (int xr = 0; xr < NR; ++xr) {
+            float ss = 0.0f;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) xf[p][e] = __uint_as_float(xraw[p][e]), xf[p][4 + e] = __uint_as_float(xraw2[p][e]);
-            } else {
+            for (int p = 0; p < NG; ++p) {
+                const bool on = (p * kRThreads + tid) < kw;
+                if (XMODE == X_F32_NORM) {
 #pragma unroll
-                for (int e = 0; e < 4; ++e) xf[p][2 * e] = h2f((uint16_t)(xraw[p][e] & 0xFFFFu)), xf[p][2 * e + 1] = h2f((uint16_t)(xraw[p][e] >> 16));
+                    for (int e = 0; e < 4; ++e) xf[xr][p][e] = __uint_as_float(xraw[xr][p][e]), xf[xr][p][4 + e] = __uint_as_float(xraw2[xr][p][e]);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        xf[xr][p][2 * e] = h2f((uint16_t)(xraw[xr][p][e] & 0xFFFFu)), xf[xr][p][2 * e + 1] = h2f((uint16_t)(xraw[xr][p][e] >> 16));
+                }
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    xf[xr][p][e] = on ? xf[xr][p][e] : 0.0f;
+                    ss += xf[xr][p][e] * xf[xr][p][e];
+                }
             }
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                xf[p][e] = on ? xf[p][e] : 0.0f;
-                ss += xf[p][e] * xf[p][e];
-            }
+            ss = wave_sum(ss);
+            if (lane == 0) red[xr * kRWaves + wave] = ss;
         }
-        ss = wave_sum(ss);
-        if (lane == 0) red[wave] = ss;
         wg_barrier();
-        float tot = 0.0f;
 #pragma unroll
-        for (int w = 0; w < kRWaves; ++w) tot += red[w];
-        inv = rms_scale(tot, inv_k, a.eps);
+        for (int xr = 0; xr < NR; ++xr) {
+            float tot = 0.0f;
+#pragma unroll
+            for (int w = 0; w < kRWaves; ++w) tot += red[xr * kRWaves + w];
+            inv[xr] = rms_scale(tot, inv_k, a.eps);
+        }
     }
+#pragma unroll
+    for (int xr = 0; xr < NR; ++xr)
 #pragma unroll
     for (int p = 0; p < NG; ++p) {
         u32x4_t o;
@@ -355,7 +386,7 @@ __global__ __launch_bounds__(kRThreads) void gemv_q4_reg_kernel(GemvArgs a)
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const uint32_t ww = wnr[p][e >> 1];
-                y[e] = f2h(xf[p][e] * inv * h2f((uint16_t)((e & 1) ? (ww >> 16) : (ww & 0xFFFFu))));
+                y[e] = f2h(xf[xr][p][e] * inv[xr] * h2f((uint16_t)((e & 1) ? (ww >> 16) : (ww & 0xFFFFu))));
             }
             o.x = (uint32_t)y[0] | ((uint32_t)y[4] << 16), o.y = (uint32_t)y[1] | ((uint32_t)y[5] << 16);
             o.z = (uint32_t)y[2] | ((uint32_t)y[6] << 16), o.w = (uint32_t)y[3] | ((uint32_t)y[7] << 16);
@@ -389,27 +420,29 @@ __global__ __launch_bounds__(kRThreads) void gemv_q4_reg_kernel(GemvArgs a)
             o.z = (uint32_t)y[2] | ((uint32_t)y[6] << 16), o.w = (uint32_t)y[3] | ((uint32_t)y[7] << 16);
         } else {
             const bool on = (p * kRThreads + tid) < kw;
-            const u32x4_t r = xraw[p];
+            const u32x4_t r = xraw[xr][p];
             o.x = __builtin_amdgcn_perm(r.z, r.x, 0x05040100u), o.y = __builtin_amdgcn_perm(r.z, r.x, 0x07060302u);
             o.z = __builtin_amdgcn_perm(r.w, r.y, 0x05040100u), o.w = __builtin_amdgcn_perm(r.w, r.y, 0x07060302u);
             if (!on) o = u32x4_t{0u, 0u, 0u, 0u};
         }
-        *(u32x4_t *)(xs + (((p * 4 + (tid & 3)) << 6) + (tid >> 2)) * 8) = o;
+        *(u32x4_t *)(xs + xr * (NG * 2048) + (((p * 4 + (tid & 3)) << 6) + (tid >> 2)) * 8) = o;
     }
     wg_barrier();
     // the lane's share of x: group c * 64 + lane of every chunk, and the offset term of each group
-    u32x4_t xv[NG][4];
-    float cr[NG];
+    u32x4_t xv[NR][NG][4];
+    float cr[NR][NG];
+#pragma unroll
+    for (int xr = 0; xr < NR; ++xr)
 #pragma unroll
     for (int c = 0; c < NG; ++c) {
         float sa = 0.0f, sb = 0.0f;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            xv[c][j] = *(const u32x4_t *)(xs + (((c * 4 + j) << 6) + lane) * 8);
-            sa = dot2(xv[c][j].x, 0x3C003C00u, sa), sb = dot2(xv[c][j].y, 0x3C003C00u, sb);
-            sa = dot2(xv[c][j].z, 0x3C003C00u, sa), sb = dot2(xv[c][j].w, 0x3C003C00u, sb);
+            xv[xr][c][j] = *(const u32x4_t *)(xs + xr * (NG * 2048) + (((c * 4 + j) << 6) + lane) * 8);
+            sa = dot2(xv[xr][c][j].x, 0x3C003C00u, sa), sb = dot2(xv[xr][c][j].y, 0x3C003C00u, sb);
+            sa = dot2(xv[xr][c][j].z, 0x3C003C00u, sa), sb = dot2(xv[xr][c][j].w, 0x3C003C00u, sb);
         }
-        cr[c] = 1032.0f * sa + 72.0f * sb;
+        cr[xr][c] = 1032.0f * sa + 72.0f * sb;
     }
     bool chunk_on[NG];                                             // lanes past the last group of the row contribute nothing
 #pragma unroll
@@ -417,9 +450,9 @@ __global__ __launch_bounds__(kRThreads) void gemv_q4_reg_kernel(GemvArgs a)
 
     // ---- the stream ------------------------------------------------------------------------------------------
     auto consume = [&](const Slot &s, int j0) {
-        float acc[R];
+        float acc[R * NR];                                         // value rr * NR + xr: row rr of the slot, row xr of x
 #pragma unroll
-        for (int rr = 0; rr < R; ++rr) acc[rr] = 0.0f;
+        for (int v = 0; v < R * NR; ++v) acc[v] = 0.0f;
         // in the order the requests went out (row by row): every group is used as soon as it has arrived
 #pragma unroll
         for (int rr = 0; rr < R; ++rr)
@@ -427,11 +460,36 @@ __global__ __launch_bounds__(kRThreads) void gemv_q4_reg_kernel(GemvArgs a)
             for (int c = 0; c < NG; ++c) {
                 float scv = h2f(s.sc[rr * NG + c]);
                 if (c >= kFirstRagged) scv = chunk_on[c] ? scv : 0.0f;
-                acc[rr] += scv * group_dot_r(s.w[rr * NG + c], xv[c], cr[c]);
+                if constexpr (NR == 1) {
+                    acc[rr] += scv * group_dot_r(s.w[rr * NG + c], xv[0][c], cr[0][c]);
+                } else {
+                    // the sixteen decoded pairs of the group once, a dot product per row of x
+                    const u32x4_t wq = s.w[rr * NG + c];
+                    uint32_t dq[16];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const uint32_t w = wq[j], w8 = w >> 8;
+                        dq[4 * j] = and_or(w, 0x000F000Fu, 0x64006400u), dq[4 * j + 1] = and_or(w, 0x00F000F0u, 0x64006400u);
+                        dq[4 * j + 2] = and_or(w8, 0x000F000Fu, 0x64006400u), dq[4 * j + 3] = and_or(w8, 0x00F000F0u, 0x64006400u);
+                    }
+#pragma unroll
+                    for (int xr = 0; xr < NR; ++xr) {
+                        float accA = 0.0f, accB = 0.0f;
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            accA = dot2(dq[4 * j], xv[xr][c][j].x, accA), accB = dot2(dq[4 * j + 1], xv[xr][c][j].y, accB);
+                            accA = dot2(dq[4 * j + 2], xv[xr][c][j].z, accA), accB = dot2(dq[4 * j + 3], xv[xr][c][j].w, accB);
+                        }
+                        acc[rr * NR + xr] += scv * (accA + accB * 0.0625f - cr[xr][c]);
+                    }
+                }
             }
-        // res[t] = sum of the wavefront's row t
+        // res[t * NR + xr] = sum of the wavefront's row t against row xr of x
         static_assert(R == 1 || R == 2, "slots of one or two rows");
-        if (R == 2) {
+        if constexpr (NR > 1) {
+            const float r = reduce_many<R * NR>(acc, lane);            // lane l: the total of value l % (R NR)
+            if (lane < R * NR) res[j0 * (R * NR) + lane] = r;
+        } else if (R == 2) {
             const float r = reduce2(acc[0], acc[R > 1 ? 1 : 0], lane);
             if (lane < 2) res[j0 * 2 + lane] = r;
         } else {
@@ -482,7 +540,12 @@ __global__ __launch_bounds__(kRThreads) void gemv_q4_reg_kernel(GemvArgs a)
     }
 
     // ---- epilogue: lane jj finishes the wavefront's unit jj ----------------------------------------------------
-    if (lane < mine) epi_store<EPI>(a, i, ri, wg + lane * W, res[lane * 2], res[lane * 2 + 1], pre);
+    if (lane < mine) {
+#pragma unroll
+        for (int xr = 0; xr < NR; ++xr)
+            if (i0 + xr < a.n)
+                epi_store<EPI>(a, i0 + xr, RowInfo{0, rpos[xr], rslot[xr]}, wg + lane * W, res[(lane * 2) * NR + xr], res[(lane * 2 + 1) * NR + xr], pre[xr]);
+    }
 }
 
 template <int XMODE, int EPI, int NG>
@@ -496,24 +559,46 @@ hipError_t launch_ng(const GemvArgs &a_in, hipStream_t stream)
         cus = v;                                                   // one workgroup per CU (two per CU measured 1 us per layer slower)
     }
     const int U = (EPI == EPI_SWIGLU || EPI == EPI_ROPE_KV) ? a.m / 2 : (a.m + 1) / 2;
-    // one workgroup per CU, shared between the rows of x; never fewer than what keeps a wavefront within kRMaxUnits
-    int gx = std::max(1, cus / std::min(a.n, 8));
+    // rows of x that share a pass over the weights: four where a lane's x is 32 registers per row (k <= 4096), two up to
+    // k = 8192, one beyond (the variants that would not fit 256 vector registers are not built)
+    const int nr = (XMODE == X_ATTN_MERGE || a.n < 2 || NG > 4) ? 1 : (a.n >= 3 && NG <= 2 ? 4 : 2);
+    const int passes = (a.n + nr - 1) / nr;
+    // one workgroup per CU, shared between the passes; never fewer than what keeps a wavefront within kRMaxUnits
+    int gx = std::max(1, cus / std::min(passes, 8));
     gx = std::min(gx, (U + kRWaves - 1) / kRWaves);
     gx = std::max(gx, (U + kRWaves * kRMaxUnits - 1) / (kRWaves * kRMaxUnits));
     const bool few_rows = 2 * ((U + gx * kRWaves - 1) / (gx * kRWaves)) <= 4;      // rows a wavefront owns
     constexpr bool kHasPos = EPI == EPI_ROPE_KV || XMODE == X_ATTN_MERGE;
     const bool one = rows_per_slot<NG>(few_rows) == 1;
     a.units_div = U / (gx * kRWaves), a.units_mod = U % (gx * kRWaves);
+    const dim3 grid(gx, passes);
     if constexpr (kHasPos) {
         if (a.n == 1 && a.pos0 < 0) {                              // position from the device-resident descriptor
             if (a.seqs.dev == nullptr) return hipErrorInvalidValue;
-            if (one) hipLaunchKernelGGL((gemv_q4_reg_kernel<XMODE, EPI, NG, 1, true>), dim3(gx, a.n), dim3(kRThreads), 0, stream, a);
-            else hipLaunchKernelGGL((gemv_q4_reg_kernel<XMODE, EPI, NG, 2, true>), dim3(gx, a.n), dim3(kRThreads), 0, stream, a);
+            if (one) hipLaunchKernelGGL((gemv_q4_reg_kernel<XMODE, EPI, NG, 1, true>), grid, dim3(kRThreads), 0, stream, a);
+            else hipLaunchKernelGGL((gemv_q4_reg_kernel<XMODE, EPI, NG, 2, true>), grid, dim3(kRThreads), 0, stream, a);
             return hipGetLastError();
         }
     }
-    if (one) hipLaunchKernelGGL((gemv_q4_reg_kernel<XMODE, EPI, NG, 1>), dim3(gx, a.n), dim3(kRThreads), 0, stream, a);
-    else hipLaunchKernelGGL((gemv_q4_reg_kernel<XMODE, EPI, NG, 2>), dim3(gx, a.n), dim3(kRThreads), 0, stream, a);
+    if constexpr (XMODE != X_ATTN_MERGE && NG <= 2) {
+        if (nr == 4) {                                             // one-row slots: 8 sums per slot would not fit
+            hipLaunchKernelGGL((gemv_q4_reg_kernel<XMODE, EPI, NG, 1, false, 4>), grid, dim3(kRThreads), 0, stream, a);
+            return hipGetLastError();
+        }
+        if (nr == 2) {
+            if (one) hipLaunchKernelGGL((gemv_q4_reg_kernel<XMODE, EPI, NG, 1, false, 2>), grid, dim3(kRThreads), 0, stream, a);
+            else hipLaunchKernelGGL((gemv_q4_reg_kernel<XMODE, EPI, NG, 2, false, 2>), grid, dim3(kRThreads), 0, stream, a);
+            return hipGetLastError();
+        }
+    }
+    if constexpr (XMODE != X_ATTN_MERGE && NG == 4) {
+        if (nr == 2) {
+            hipLaunchKernelGGL((gemv_q4_reg_kernel<XMODE, EPI, NG, 1, false, 2>), grid, dim3(kRThreads), 0, stream, a);
+            return hipGetLastError();
+        }
+    }
+    if (one) hipLaunchKernelGGL((gemv_q4_reg_kernel<XMODE, EPI, NG, 1>), grid, dim3(kRThreads), 0, stream, a);
+    else hipLaunchKernelGGL((gemv_q4_reg_kernel<XMODE, EPI, NG, 2>), grid, dim3(kRThreads), 0, stream, a);
     return hipGetLastError();
 }
 

@@ -167,6 +167,41 @@ __device__ __forceinline__ float lane_xor_sum(float v)
     else return v + lane_xor<OFF>(v);
 }
 
+// V partial sums per lane -> lane l holds the total of value l % V (a transposing reduction: the number of live values
+// halves with every exchange)
+template <int V, int BIT = 1>
+__device__ __forceinline__ void fold_values(float *v, int lane)
+{
+    if constexpr (BIT < V) {
+        const bool up = lane & BIT;
+#pragma unroll
+        for (int i = 0; i < V / (2 * BIT); ++i) {
+            const float keep = up ? v[2 * i + 1] : v[2 * i], give = up ? v[2 * i] : v[2 * i + 1];
+            v[i] = keep + lane_xor<BIT>(give);
+        }
+        fold_values<V, 2 * BIT>(v, lane);
+    }
+}
+// the rest of the sum over the wavefront once the values are folded.  The step over the quads of a row is a rotation by
+// four lanes, not lane ^ 4 (the rotation by eight that follows completes the row either way): the same instructions, in
+// the same order, as the one- and two-value reductions of the matvec kernels, so a row's sum has the same bits whether
+// it was reduced alone or next to the sums of other rows.
+template <int OFF>
+__device__ __forceinline__ float sum_from(float r)
+{
+    if constexpr (OFF == 4) return sum_from<8>(r + lane_dpp<0x124>(r));
+    else if constexpr (OFF < kWave) return sum_from<2 * OFF>(lane_xor_sum<OFF>(r));
+    else return r;
+}
+// register-to-register exchanges only (DPP, permlane swaps)
+template <int V>
+__device__ __forceinline__ float reduce_many(float *v, int lane)
+{
+    static_assert(V == 1 || V == 2 || V == 4 || V == 8, "1, 2, 4 or 8 values");
+    fold_values<V>(v, lane);
+    return sum_from<V>(v[0]);
+}
+
 __device__ inline float wave_sum(float v)
 {
     v = xor32_sum(v);

@@ -465,10 +465,32 @@ def test_llama7b_layer_prefill_128(rx):
     assert_close(*outs[0], "7B prefill n=128")
 
 
+@pytest.mark.parametrize("matvec_rows", [1, 4])
+def test_llama7b_layer_two_to_five_decode_rows_on_both_paths(rx, matvec_rows):
+    """Batches of two to five decode rows of the 7B-shaped layer through the matvec kernels with several rows per pass
+    (the default up to four rows) and, with the switch at 1, through the few-row matrix path: both against the oracle."""
+    rx.check(rx.relax_set_option("layer_matvec_rows", matvec_rows))
+    try:
+        past = [int(v) for v in wl.uniform_lengths(41, 5, 1, 60)]
+        kb, vb = wl.kv_prefill(wl.LLAMA7B, 41, 5, 64)
+        calls = [([1, 1], [past[0] + 1, past[1] + 1], [0, 1]),
+                 ([1, 1, 1], [past[2] + 1, past[0] + 2, past[4] + 1], [2, 0, 4]),
+                 ([1, 1, 1, 1], [past[1] + 2, past[3] + 1, past[2] + 2, past[4] + 2], [1, 3, 2, 4]),
+                 ([1] * 5, [past[0] + 3, past[1] + 3, past[2] + 3, past[3] + 2, past[4] + 3], [0, 1, 2, 3, 4])]
+        outs, (Kg, Vg), (Ko, Vo) = run_schedule(rx, wl.LLAMA7B, 41, 64, calls, slots=5, prefill_bits=(kb, vb))
+        for ci, (g, r) in enumerate(outs):
+            assert_close(g, r, "7B layer, %d decode rows, layer_matvec_rows = %d" % (ci + 2, matvec_rows))
+        assert_close(Kg, Ko, "K cache", atol=5e-3, rtol=5e-3)
+        assert_close(Vg, Vo, "V cache", atol=5e-3, rtol=5e-3)
+    finally:
+        rx.check(rx.relax_set_option("layer_matvec_rows", 4))
+
+
 def test_llama7b_layer_row_counts_around_the_dispatch_boundaries(rx):
-    """The same binary picks the kernels from n: two rows of a small model stay on the matvec kernels, three take the
-    few-row path; at 64 rows every matmul is the few-row kernel, at 65 and 96 the tall gate/up matrix goes to the tiled
-    GEMM while the other three stay (their finishing passes still fold the light steps)."""
+    """The same binary picks the kernels from n: up to four rows of a small model stay on the matvec kernels (two or
+    four rows of x share one pass over the weights), five take the few-row path; at 64 rows every matmul is the few-row
+    kernel, at 65 and 96 the tall gate/up matrix goes to the tiled GEMM while the other three stay (their finishing
+    passes still fold the light steps)."""
     calls = [([40, 25], [40, 25], [0, 1]),            # 65 rows, two prefills
              ([1, 1], [41, 26], [0, 1]),              # two decode rows
              ([1, 1, 1], [42, 27, 1], [0, 1, 2]),     # three
