@@ -308,7 +308,10 @@ hipError_t half_matmul_enqueue(const uint16_t *x, const uint16_t *w, uint16_t *o
             left -= nb;
         }
         const double tiles = (double)((m + 127) / 128) * ((n + 63) / 64);
-        const double gemm_us = (k / 64.0) * (0.5 + 0.15 * std::min(tiles / 256.0, 1.0)) * std::max(1.0, tiles / 256.0) + 4.0;
+        // ... and never less than its own pass over the matrix (the GEMM streams a tall matrix at about 4.3 TB/s: 262 MB in 61.6 us
+        // at one row, where the estimate of the k loop alone said 45 and the matvec pass takes 45.4)
+        const double gemm_us = std::max((k / 64.0) * (0.5 + 0.15 * std::min(tiles / 256.0, 1.0)) * std::max(1.0, tiles / 256.0),
+                                        (double)m * k * 2.0 / 4.3e6) + 4.0;
         use_gemm = n > 64 || gemm_us < mv_us;
     }
     if (use_gemm && gemm_f16_eligible(x, w, out, m, k)) return launch_gemm_f16(x, w, n, m, k, out, st_);

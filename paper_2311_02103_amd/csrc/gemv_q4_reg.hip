@@ -258,7 +258,7 @@ __global__ __launch_bounds__(kRThreads) __attribute__((amdgpu_waves_per_eu(1, 1)
     int used = 0;                                              // splits that hold tokens: ceil((pos + 1) / chunk)
     if (kMerge && DEV) {
         const int pos = row_info(a.seqs, 0).pos;
-        used = pos / attn_fold_chunk(pos + 1, a.part_splits) + 1;
+        used = attn_fold_used(pos, attn_fold_chunk(pos + 1, a.part_splits));
     } else if (kMerge) {
         used = a.part_used;                                        // the host knew the position: no division up front
     }

@@ -251,12 +251,35 @@ constexpr int kAttnMergeSplits = 8;  // splits along L that the matvec prologue 
 // Split plan of the folded form for one decode row with L cached tokens: at most max_splits chunks of whole wavefront steps
 // (32 tokens), none shorter than 64 tokens unless L is.  The host evaluates it when it knows L; with a device-resident
 // descriptor both kernels evaluate it from the L they read (the launch then always has max_splits slices).
+// x / d for the few divisors a split count takes: constant divisors (a multiply and a shift each) behind a uniform
+// branch instead of the forty-instruction general division -- on the device this runs ahead of a kernel's first request
+__host__ __device__ inline int div_by_splits(int x, int d)
+{
+    switch (d) {
+    case 1: return x;
+    case 2: return x >> 1;
+    case 3: return x / 3;
+    case 4: return x >> 2;
+    case 5: return x / 5;
+    case 6: return x / 6;
+    case 7: return x / 7;
+    case 8: return x >> 3;
+    default: return x / d;
+    }
+}
 __host__ __device__ inline int attn_fold_chunk(int L, int max_splits)
 {
-    int sp = (L + 63) / 64;
+    int sp = (L + 63) >> 6;
     sp = sp > max_splits ? max_splits : sp;
     sp = sp < 1 ? 1 : sp;
-    return ((L + sp - 1) / sp + 31) / 32 * 32;
+    return (div_by_splits(L + sp - 1, sp) + 31) >> 5 << 5;       // L >= 1
+}
+// splits of `chunk` tokens that hold at least one of the pos + 1 tokens (at most max_splits: no division either)
+__host__ __device__ inline int attn_fold_used(int pos, int chunk)
+{
+    int used = 1;
+    while (used * chunk <= pos) ++used;
+    return used;
 }
 enum Epilogue { EPI_F16 = 0, EPI_ROPE_KV = 1, EPI_RESID_F32 = 2, EPI_RESID_F16 = 3, EPI_SWIGLU = 4 };
 
