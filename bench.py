@@ -567,8 +567,9 @@ def bench_model(args, np, torch, wl, rx, big):
 # ------------------------------------------------------------------------------------------------ batch sweep
 def bench_batch_sweep(args, np, torch, wl, rx):
     """One 7B-shaped layer call on n decode rows (n sequences, one row each, 256 cached tokens each) against n: where the
-    runtime dispatch on the symbolic row count (Sec. 5.1) changes kernels -- matvec kernels for one row (and two rows of a
-    model this small), the few-row MFMA kernel up to 128 rows (64 for the tall gate/up matrix), the tiled GEMM above."""
+    runtime dispatch on the symbolic row count (Sec. 5.1) changes kernels -- matvec kernels for one row (and up to four rows
+    of a model this small, two or four rows of x per pass over the weights), the few-row MFMA kernel up to 128 rows (64 for the
+    tall gate/up matrix), the tiled GEMM above."""
     from paper_2311_02103_amd.runtime import DeviceLayer, to_device
     shape, seed, cap, L = wl.LLAMA7B, 6, 320, 256
     ns = [int(v) for v in args.sweep_rows.split(",")] if args.sweep_rows else [1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64, 65, 96, 128, 129, 192, 256]
@@ -596,7 +597,7 @@ def bench_batch_sweep(args, np, torch, wl, rx):
             calls[i % sets](stream.cuda_stream)
         stream.synchronize()
         us = (time.perf_counter() - t0) * 1e6 / steps
-        matmuls = ("matvec per row" if n <= 2 else "few-row MFMA" if n <= 64 else
+        matmuls = ("matvec" if n == 1 else "matvec, 2 or 4 rows per pass" if n <= 4 else "few-row MFMA" if n <= 64 else
                    "few-row MFMA, tiled GEMM for gate/up" if n <= 128 else "tiled GEMM")
         rows.append({"n": n, "us_per_call": round(us, 1), "layer_tokens_per_s": round(n / us * 1e6, 0), "matmul_kernels": matmuls})
     best = max(rows, key=lambda r: r["layer_tokens_per_s"])
