@@ -126,6 +126,7 @@ struct GemmArgs {
     int32_t gshift;          // 32-column sub-group index >> gshift = scale index (quantisation group 32, 64 or 128)
     const uint16_t *wh;      // FP16W kernels: plain fp16 weights [m,k] instead of q, s
     int32_t n, m, k;
+    int32_t ldm;             // row pitch of out / resid in elements; 0: m (a launch on a range of the weight rows brings the matrix's m here)
     int32_t epi;
     int32_t tiles_m;         // weight-row tiles of the launch (the grid is one-dimensional: tiles_m * x-row tiles * k splits)
     int32_t tiles_n;         // x-row tiles
@@ -184,6 +185,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_q4_mfma_kernel(GemmArgs a)
     const int n0 = tile_n * BN;
     const int kw = a.k >> 3;
     const int F = a.m >> 1;
+    const int ldm = a.ldm > 0 ? a.ldm : a.m;
 
     // ---- staging roles ----
     const int arow = tid / TPR, aword0 = (tid % TPR) * W;
@@ -427,7 +429,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_q4_mfma_kernel(GemmArgs a)
                 for (int f = 0; f < MF; ++f) {
                     const int r0 = tile_m * BM + (wm * MF + f) * 32 + off;
                     if (r0 < a.m) {                              // m % 4 == 0 is checked by the launcher
-                        const size_t at = (size_t)xrow * a.m + r0;
+                        const size_t at = (size_t)xrow * ldm + r0;
                         float v[4];
 #pragma unroll
                         for (int r = 0; r < 4; ++r) v[r] = acc[f][j][b * 4 + r];
@@ -517,6 +519,7 @@ bool gemm_mfma_eligible(const relax_qmat &w, const void *x, int epi)
 namespace {
 struct TilePlan {
     int mf, nf, splits, kb_per_split;
+    int m_big;               // > 0: the first m_big weight rows go through a launch of 256 x 256 tiles of their own (whole rounds of them)
 };
 TilePlan tile_plan(int m, int k, int n, int epi)
 {
@@ -524,7 +527,7 @@ TilePlan tile_plan(int m, int k, int n, int epi)
     const long rdiv = epi == EPI_SWIGLU ? 2 : 1;
     auto blocks = [&](int mf, int nf) { return ((rows + 64 * mf / rdiv - 1) / (64 * mf / rdiv)) * (long)((n + 64 * nf - 1) / (64 * nf)); };
     const long kCUs = 256;
-    TilePlan p = {2, 1, 1, k / BK};
+    TilePlan p = {2, 1, 1, k / BK, 0};
     if (n > 128) {
         // useful share of the workgroup rounds: padding rows of ragged tiles and idle CUs of the last round both count as waste,
         // weighted by what a tile shape reaches per MFMA when the CUs are full (measured on the 7B shapes at n = 2048: the
@@ -538,6 +541,24 @@ TilePlan tile_plan(int m, int k, int n, int epi)
         if (s44 >= s24 && s44 >= s22) p.mf = 4, p.nf = 4;
         else if (s24 >= s22) p.mf = 2, p.nf = 4;
         else p.mf = 2, p.nf = 2;
+        // Two launches instead of one when the 128 x 256 tile was chosen only for its rounds: whole rounds of 256 x 256
+        // tiles on the first rows (the tile that reaches more per MFMA), the narrower tile on the rest.  A round of the
+        // wide tile is taken as 1.6 rounds of the narrow one (129 against 80 us per round at k = 4096, n = 2048); the
+        // split is made when the estimate gains a tenth (QKV of the 7B layer at n = 2048: 1.6 + 1 against 3 rounds).
+        if (p.mf == 2 && p.nf == 4 && epi != EPI_SWIGLU) {
+            const long tn = (n + 255) / 256;
+            if (tn <= kCUs) {
+                const long rows_round = (kCUs / tn) * 256;                       // weight rows of one full round of wide tiles
+                const double all_small = (double)((blocks(2, 4) + kCUs - 1) / kCUs);
+                double best = all_small;
+                for (long r = 1; r * rows_round < rows; ++r) {
+                    const long rem = rows - r * rows_round;
+                    const double t = 1.6 * (double)r + (double)((((rem + 127) / 128) * tn + kCUs - 1) / kCUs);
+                    if (t < best) best = t, p.m_big = (int)(r * rows_round);
+                }
+                if (best > 0.9 * all_small) p.m_big = 0;
+            }
+        }
         const long tiles = blocks(p.mf, p.nf);
         const int nkb = k / BK;
         if (n <= kSplitKMaxN && tiles <= kCUs / 2) {
@@ -545,6 +566,7 @@ TilePlan tile_plan(int m, int k, int n, int epi)
             p.kb_per_split = ((nkb + splits - 1) / splits + 1) & ~1;
             p.splits = (nkb + p.kb_per_split - 1) / p.kb_per_split;
             if (p.splits < 2) p.splits = 1, p.kb_per_split = nkb;
+            if (p.splits > 1) p.m_big = 0;
         }
     } else if (n > 64) {
         p.mf = 2, p.nf = 2;
@@ -617,7 +639,7 @@ hipError_t launch_gemm_q3(const uint16_t *x, const relax_qmat &w, int n, uint16_
 hipError_t launch_gemm_mfma(const uint16_t *x, const relax_qmat &w, int n, int epi, uint16_t *out_f16, float *out_f32, const void *resid,
                             hipStream_t stream, float *partial, size_t partial_floats, const SkinnyFuse *fuse)
 {
-    GemmArgs a;
+    GemmArgs a = {};
     a.wh = nullptr;
     a.x = x, a.q = w.q, a.s = w.s, a.gshift = gshift_of(w.group), a.n = n, a.m = w.m, a.k = w.k, a.epi = epi;
     a.out_f16 = out_f16, a.out_f32 = out_f32, a.resid = resid;
@@ -629,6 +651,21 @@ hipError_t launch_gemm_mfma(const uint16_t *x, const relax_qmat &w, int n, int e
     a.kb_per_split = p.kb_per_split;
     hipError_t e;
     const bool eight = g_waves_per_simd.load() == 2;
+    if (p.m_big > 0 && p.splits == 1 && epi != EPI_SWIGLU) {
+        // rows [0, m_big) on wide tiles, rows [m_big, m) on the narrow ones: two launches on the same stream
+        GemmArgs b = a;
+        b.m = p.m_big, b.ldm = w.m;
+        e = eight ? launch_tile<2, 4, false, 4, 2>(b, stream, 1) : launch_tile<4, 4>(b, stream, 1);
+        if (e != hipSuccess) return e;
+        GemmArgs c = a;
+        const size_t skip = (size_t)p.m_big;
+        c.q = a.q + skip * (size_t)(w.k / 8), c.s = a.s + skip * (size_t)scales_per_row(w.k, a.gshift);
+        c.m = w.m - p.m_big, c.ldm = w.m;
+        if (c.out_f16) c.out_f16 = a.out_f16 + skip;
+        if (c.out_f32) c.out_f32 = a.out_f32 + skip;
+        if (c.resid) c.resid = (epi == EPI_RESID_F32) ? (const void *)((const uint16_t *)a.resid + skip) : (const void *)((const float *)a.resid + skip);
+        return launch_tile<2, 4>(c, stream, 1);
+    }
     if (p.mf == 4) e = eight ? launch_tile<2, 4, false, 4, 2>(a, stream, p.splits) : launch_tile<4, 4>(a, stream, p.splits);
     else if (p.nf == 4) e = launch_tile<2, 4>(a, stream, p.splits);        // 128 x 256: four wavefronts of 64 x 128 beat eight of 64 x 64 by 4 to 11 %
     else if (p.nf == 2) e = launch_tile<2, 2>(a, stream, p.splits);

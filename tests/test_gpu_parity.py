@@ -373,7 +373,10 @@ def test_repeated_decode_call_is_reproducible_and_raises_no_flag(rx):
 
 
 # ------------------------------------------------------------------------- MFMA GEMM path (n >= 16, k % 128 == 0)
-@pytest.mark.parametrize("m,k,n", [(64, 128, 16), (260, 256, 33), (512, 4096, 128), (256, 11008, 17), (1024, 1024, 511)])
+@pytest.mark.parametrize("m,k,n", [(64, 128, 16), (260, 256, 33), (512, 4096, 128), (256, 11008, 17), (1024, 1024, 511),
+                                   # two launches: the first 8192 weight rows on 256 x 256 tiles (one full round of them at 2048
+                                   # rows of x), the last 256 on 128 x 256 tiles
+                                   (8448, 256, 2048)])
 def test_gemm_integer_valued_bitwise(rx, m, k, n):
     r = np.random.RandomState(m + k + n)
     codes = r.randint(0, 16, size=(m, k)).astype(np.uint8)
