@@ -727,6 +727,41 @@ def bench_q3_matvec(args, np, torch, wl, rx):
         us = start.elapsed_time(stop) * 1e3 / 20
         gemm[name] = {"us_per_launch": round(us, 1), "TFLOPs": round(2.0 * n * m * k / us / 1e6, 1), "frac_of_mfma_peak": round(2.0 * n * m * k / us / 1e6 / PEAK_MFMA_TFLOPS, 4)}
         del nq, sc, xb, ob, mat
+    # the whole 7B-shaped layer on 3-bit weights (relax_decoder_layer_q3: eleven launches, nothing fused), three rotating weight sets
+    layer3 = {}
+    shape7 = wl.LLAMA7B
+    dims = rx.make_dims(shape7.hidden, shape7.n_heads, shape7.n_kv_heads, shape7.head_dim, shape7.ffn, 2304, 1, shape7.rms_eps, shape7.rope_base, 32)
+    sets3 = []
+    for _ in range(3):
+        qm = []
+        for m, k in ((12288, 4096), (4096, 4096), (22016, 4096), (4096, 11008)):
+            nq = torch.randint(-2 ** 31, 2 ** 31 - 1, (m, 3 * k // 32), dtype=torch.int32, device="cuda")
+            sc = (torch.rand((m, k // 32), device="cuda") * 0.01 + 0.002).to(torch.float16)
+            qm.append(rx.QMat(nq, sc, m, k, 32))
+        nw = (torch.randn(4096, device="cuda") * 0.1 + 1.0).to(torch.float16)
+        sets3.append(rx.LayerWeights(*qm, nw, nw))
+    rope = torch.empty(rx.relax_rope_table_bytes(dims) // 4, dtype=torch.float32, device="cuda")
+    rx.check(rx.relax_rope_table_init(dims, rope, stream), "relax_rope_table_init")
+    kc = torch.randn((1, 2304, shape7.n_kv_heads, shape7.head_dim), device="cuda", dtype=torch.float16)
+    cache = rx.KVCache(kc, kc.clone(), rope)
+    for n, L, reps in ((1, 2231, 120), (2048, 2048, 6)):
+        wsb = rx.relax_layer_q3_workspace_bytes(dims, n, 2304, 1)
+        ws3 = torch.empty(wsb, dtype=torch.uint8, device="cuda")
+        x3 = torch.randn((n, 4096), device="cuda", dtype=torch.float16)
+        o3 = torch.empty_like(x3)
+        seqs = rx.Seqs([n], [L], None, None)
+        for i in range(6):
+            rx.check(rx.relax_decoder_layer_q3(dims, sets3[i % 3], x3, cache, seqs, o3, n, ws3, wsb, stream), "relax_decoder_layer_q3")
+        start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        stream.synchronize()
+        start.record(stream)
+        for i in range(reps):
+            rx.relax_decoder_layer_q3(dims, sets3[i % 3], x3, cache, seqs, o3, n, ws3, wsb, stream)
+        stop.record(stream)
+        stream.synchronize()
+        layer3["n=%d L=%d" % (n, L)] = {"us_per_call": round(start.elapsed_time(stop) * 1e3 / reps, 1)}
+        del ws3, x3, o3
+    del sets3, kc, cache
     cpu = None
     if args.cpu_seconds > 0:
         from oracle import q3                               # the CPU reference: baseline and check only
@@ -748,7 +783,7 @@ def bench_q3_matvec(args, np, torch, wl, rx):
          {"workload": "3-bit group-32 weights in the native word layout (repacked once from the canonical stream), n = 1, the four matrix shapes of the 7B layer, rotating weight copies; the canonical-layout kernel timed beside it", "build_id": rx.relax_build_id()},
          {"bound": "hbm", "kernel": "gemv_q3n_kernel (22016 x 4096)", "achieved": g["GBps"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
           "frac": g["frac_of_peak"], "traffic": None, "algorithmic_bytes_per_launch": int(g["algorithmic_MB"] * 1e6), "avg_launch_ms": g["us_per_launch"] / 1e3},
-         cpu, {"q3_matvec": table, "q3_gemm_n2048": gemm})
+         cpu, {"q3_matvec": table, "q3_gemm_n2048": gemm, "q3_layer_7b": layer3})
 
 
 # ------------------------------------------------------------------------------------------------ memory plan

@@ -330,6 +330,22 @@ relax_status relax_repack_q3(const relax_qmat *canonical, uint32_t *native_q, re
 relax_status relax_unpack_q3_native(const relax_qmat *w, int8_t *out, relax_stream stream);
 relax_status relax_dequant_matmul_q3_native(const uint16_t *x, const relax_qmat *w, uint16_t *out, int32_t n, relax_stream stream);
 
+/* The whole layer on 3-bit weights (Sec. 5.3: the 3-bit models are what the paper deploys where memory is short): the
+ * same computation as relax_decoder_layer, same dims, cache, descriptor and x / out conventions, with the four matrices of
+ * `weights` in the GPU-native 3-bit layout above (group 0 or 32; their rows within what the 3-bit matmul takes: k % 32 == 0,
+ * k <= 12288).  The 3-bit matmuls have the plain fp16 epilogue only, so this layer is a sequence of launches of their own
+ * -- RMSNorm, matmul, rotary + append, attention, matmul, residual add, RMSNorm, matmul, SwiGLU, matmul, residual add --
+ * with the dispatch on n of relax_dequant_matmul_q3_native inside (matrix-vector passes below 16 rows, tiled MFMA GEMM from
+ * there on); nothing is fused, a 3-bit matmul output is rounded to fp16 before the residual is added, the residual stream
+ * x1 stays fp32 between the two halves of the layer.  Its workspace is its own: relax_layer_q3_workspace_bytes(dims, n_max,
+ * L_max, B_max) bytes, 256-byte aligned (0 for invalid arguments); the first 256 bytes are the flag line of
+ * relax_workspace_init, which this call neither reads nor writes.  hidden % 8 == 0, ffn % 8 == 0, x and out 16-byte
+ * aligned.  Asynchronous on `stream`; allocates nothing; errors as relax_decoder_layer, checked before anything is enqueued. */
+size_t       relax_layer_q3_workspace_bytes(const relax_layer_dims *dims, int32_t n_max, int32_t L_max, int32_t B_max);
+relax_status relax_decoder_layer_q3(const relax_layer_dims *dims, const relax_layer_weights *weights, const uint16_t *x,
+                                    const relax_kv_cache *cache, const relax_seqs *seqs, uint16_t *out, int32_t n, void *ws,
+                                    size_t ws_bytes, relax_stream stream);
+
 /* Build identity of the loaded binary (one binary serves every shape).                  */
 const char *relax_build_id(void);
 

@@ -35,3 +35,30 @@ def dequant_matmul_q3(x: np.ndarray, qweight: np.ndarray, scales: np.ndarray, m:
     """x float [n,k] -> float64 [n,m] = x W^T."""
     assert x.shape[1] == k
     return x.astype(np.float64) @ dequantize_q3(qweight, scales, m, k).T
+
+
+def decoder_layer_q3(dims, w, x, kcache: np.ndarray, vcache: np.ndarray, seqs) -> np.ndarray:
+    """One decoder layer whose four matrices are 3-bit (canonical layout): the layer of Sec. 5.1's Llama-style models with the
+    3-bit weights of Sec. 5.3, written as the sequence of its steps -- RMSNorm, QKV matmul, rotary embedding + KV append,
+    causal attention over the cache, output projection + residual, RMSNorm, gate/up matmul, SwiGLU, down projection +
+    residual -- each step being the package's own reference for it (the matmuls the definition above, in float64).
+    w: mapping with '<mat>.q' uint32 [m, 3k/32], '<mat>.s' fp16 bits [m, k/32] for wqkv, wo, wgu, wdown and 'norm_attn',
+    'norm_ffn' fp16 bits [H].  x: fp16 bits or float32 [n,H].  kcache / vcache float32, updated in place.  Returns float32 [n,H]."""
+    from . import attention, rmsnorm, rope_append, swiglu
+    x = np.ascontiguousarray(x)
+    xf = x.view(np.float16).astype(np.float32) if x.dtype == np.uint16 else x.astype(np.float32)
+    n, H = xf.shape
+    h, g, d, F = dims.n_heads, dims.n_kv_heads, dims.head_dim, dims.ffn
+    assert H == dims.hidden
+
+    def mm(v, name, m, k):
+        return dequant_matmul_q3(v, w[name + ".q"], w[name + ".s"], m, k)
+
+    xn = rmsnorm(xf, w["norm_attn"], dims.rms_eps)
+    qkv = mm(xn, "wqkv", (h + 2 * g) * d, H).astype(np.float32)
+    qkv = rope_append(qkv, dims, kcache, vcache, seqs)
+    a = attention(np.ascontiguousarray(qkv[:, :h * d]), kcache, vcache, dims, seqs).reshape(n, h * d)
+    x1 = xf.astype(np.float64) + mm(a, "wo", H, h * d)
+    xn2 = rmsnorm(x1.astype(np.float32), w["norm_ffn"], dims.rms_eps)
+    act = swiglu(mm(xn2, "wgu", 2 * F, H).astype(np.float32))
+    return (x1 + mm(act, "wdown", H, F)).astype(np.float32)

@@ -95,6 +95,9 @@ _SIGNATURES = {
                                            C.c_int32, C.c_void_p]),
     "relax_decoder_layer": (C.c_int32, [C.POINTER(LayerDims), C.POINTER(LayerWeightsC), C.c_void_p, C.POINTER(KVCacheC),
                                         C.POINTER(SeqsC), C.c_void_p, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "relax_layer_q3_workspace_bytes": (C.c_size_t, [C.POINTER(LayerDims), C.c_int32, C.c_int32, C.c_int32]),
+    "relax_decoder_layer_q3": (C.c_int32, [C.POINTER(LayerDims), C.POINTER(LayerWeightsC), C.c_void_p, C.POINTER(KVCacheC),
+                                           C.POINTER(SeqsC), C.c_void_p, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]),
     "relax_model_workspace_bytes": (C.c_size_t, [C.POINTER(ModelC), C.c_int32, C.c_int32, C.c_int32]),
     "relax_model_step": (C.c_int32, [C.POINTER(ModelC), C.c_void_p, C.POINTER(KVCacheC), C.POINTER(SeqsC), C.c_void_p,
                                      C.c_void_p, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]),
@@ -298,6 +301,19 @@ def relax_decoder_layer(dims: Optional[LayerDims], weights: Optional[LayerWeight
     sc = None if seqs is None else seqs.c()
     return lib().relax_decoder_layer(_ref(dims), _ref(wc), _ptr(x), _ref(cc), _ref(sc), _ptr(out), n, _ptr(ws), ws_bytes,
                                      _stream(stream))
+
+
+def relax_layer_q3_workspace_bytes(dims: Optional[LayerDims], n_max: int, L_max: int, B_max: int) -> int:
+    return int(lib().relax_layer_q3_workspace_bytes(_ref(dims), n_max, L_max, B_max))
+
+
+def relax_decoder_layer_q3(dims: Optional[LayerDims], weights: Optional[LayerWeights], x: Ptr, cache: Optional[KVCache],
+                           seqs: Optional[Seqs], out: Ptr, n: int, ws: Ptr, ws_bytes: int, stream=None) -> int:
+    wc = None if weights is None else weights.c()
+    cc = None if cache is None else cache.c()
+    sc = None if seqs is None else seqs.c()
+    return lib().relax_decoder_layer_q3(_ref(dims), _ref(wc), _ptr(x), _ref(cc), _ref(sc), _ptr(out), n, _ptr(ws), ws_bytes,
+                                        _stream(stream))
 
 
 class Model:

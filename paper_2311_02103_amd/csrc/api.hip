@@ -802,6 +802,110 @@ relax_status relax_decoder_layer(const relax_layer_dims *dims, const relax_layer
     return layer_enqueue(dm, wt, x, cache, st, L_max, out, n, static_cast<char *>(ws), pl, st_);
 }
 
+}  // extern "C"
+
+// ---- one decoder layer on 3-bit weights (native layout) ---------------------------------------------------------------
+// The same layer, composed of launches of their own: the 3-bit matmuls have the plain fp16 epilogue only, so the light
+// steps run between them (RMSNorm, rotary + append, attention, residual adds, SwiGLU).  Its workspace is laid out one
+// intermediate after the other (nothing is shared: the schedule differs from the one the planner of the 4-bit layer walks).
+namespace {
+struct Q3Plan {
+    WsPlan ws;                       // flags, table and partials at their usual places (upload_table and the attention launch read them)
+    size_t gu, tmp, total;
+};
+Q3Plan plan_q3(const relax_layer_dims &dm, int32_t n, int32_t L, int32_t B)
+{
+    Q3Plan p = {};
+    const size_t hd = (size_t)dm.n_heads * dm.head_dim, qkvw = (size_t)(dm.n_heads + 2 * dm.n_kv_heads) * dm.head_dim;
+    size_t off = 0;
+    p.ws.flags = off;    off += kWsFlagBytes;
+    p.ws.table = off;    off += align256(sizeof(int32_t) * 4 * (size_t)(B > 1 ? B : 1));
+    p.ws.partials = off; off += align256(sizeof(float) * attn_partial_floats(dm, n, L));
+    p.ws.partials_end = off;
+    p.ws.xn = off;       off += align256(2 * (size_t)n * std::max((size_t)dm.hidden, hd));
+    p.ws.qkv = off;      off += align256(2 * (size_t)n * qkvw);
+    p.ws.attn = off;     off += align256(2 * (size_t)n * hd);
+    p.ws.x1 = off;       off += align256(4 * (size_t)n * dm.hidden);
+    p.ws.act = off;      off += align256(2 * (size_t)n * dm.ffn);
+    p.gu = off;          off += align256(2 * (size_t)n * 2 * dm.ffn);
+    p.tmp = off;         off += align256(2 * (size_t)n * dm.hidden);
+    p.total = p.ws.total = off;
+    return p;
+}
+// a relax_qmat of the native 3-bit layout that the matmul dispatch below can take for any n
+relax_status check_q3mat(const relax_qmat &w, int32_t m, int32_t k)
+{
+    if (!w.q || !w.s) return RELAX_ERR_NULL;
+    if (w.m != m || w.k != k || k % 32 != 0) return RELAX_ERR_SHAPE;
+    if (w.group != 0 && w.group != 32) return RELAX_ERR_UNSUPPORTED;
+    if ((reinterpret_cast<uintptr_t>(w.q) & 3) != 0 || (reinterpret_cast<uintptr_t>(w.s) & 1) != 0) return RELAX_ERR_SHAPE;
+    if (!gemv_q3_supported(m, k)) return RELAX_ERR_UNSUPPORTED;   // rows longer than the matvec kernel keeps in registers
+    return RELAX_OK;
+}
+hipError_t q3_matmul(const uint16_t *x, const relax_qmat &w, int32_t n, uint16_t *out, hipStream_t st_)
+{
+    if (n >= kQ3GemmRows && gemm_q3_eligible(x, w, out)) return launch_gemm_q3(x, w, n, out, st_);
+    return launch_gemv_q3_native(x, w, n, out, st_);
+}
+}  // namespace
+
+extern "C" {
+
+size_t relax_layer_q3_workspace_bytes(const relax_layer_dims *dims, int32_t n_max, int32_t L_max, int32_t B_max)
+{
+    if (check_dims(dims) != RELAX_OK || n_max < 1 || L_max < 1 || B_max < 1) return 0;
+    return plan_q3(*dims, n_max, L_max, B_max).total;
+}
+
+relax_status relax_decoder_layer_q3(const relax_layer_dims *dims, const relax_layer_weights *wt, const uint16_t *x,
+                                    const relax_kv_cache *cache, const relax_seqs *seqs, uint16_t *out, int32_t n, void *ws,
+                                    size_t ws_bytes, relax_stream stream)
+{
+    hipStream_t st_ = static_cast<hipStream_t>(stream);
+    relax_status rc = check_dims(dims);
+    if (rc != RELAX_OK) return rc;
+    if (!wt || !x || !out || !ws || !cache || !cache->k || !cache->v || !cache->rope || !wt->norm_attn || !wt->norm_ffn) return RELAX_ERR_NULL;
+    const relax_layer_dims &dm = *dims;
+    const int32_t hd = dm.n_heads * dm.head_dim, qkvw = (dm.n_heads + 2 * dm.n_kv_heads) * dm.head_dim;
+    if (dm.hidden % 8 != 0 || dm.ffn % 8 != 0) return RELAX_ERR_SHAPE;
+    if ((rc = check_q3mat(wt->wqkv, qkvw, dm.hidden)) != RELAX_OK || (rc = check_q3mat(wt->wo, dm.hidden, hd)) != RELAX_OK ||
+        (rc = check_q3mat(wt->wgu, 2 * dm.ffn, dm.hidden)) != RELAX_OK || (rc = check_q3mat(wt->wdown, dm.hidden, dm.ffn)) != RELAX_OK)
+        return rc;
+    if (((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(out)) & 15) != 0) return RELAX_ERR_SHAPE;
+    SeqTable st = {};
+    bool need_table = false;
+    int32_t L_max = 0;
+    rc = build_seqs(seqs, dm, n, st, L_max, need_table);
+    if (rc != RELAX_OK) return rc;
+    const Q3Plan pl = plan_q3(dm, n, L_max, seqs->B);
+    if (ws_bytes < pl.total || (reinterpret_cast<uintptr_t>(ws) & 255) != 0) return RELAX_ERR_WORKSPACE;
+    rc = upload_table(st, seqs, need_table, ws, pl.ws, st_);
+    if (rc != RELAX_OK) return rc;
+
+    char *base = static_cast<char *>(ws);
+    uint16_t *xn = reinterpret_cast<uint16_t *>(base + pl.ws.xn), *qkv = reinterpret_cast<uint16_t *>(base + pl.ws.qkv);
+    uint16_t *attn = reinterpret_cast<uint16_t *>(base + pl.ws.attn), *act = reinterpret_cast<uint16_t *>(base + pl.ws.act);
+    uint16_t *gu = reinterpret_cast<uint16_t *>(base + pl.gu), *tmp = reinterpret_cast<uint16_t *>(base + pl.tmp);
+    float *x1 = reinterpret_cast<float *>(base + pl.ws.x1), *partials = reinterpret_cast<float *>(base + pl.ws.partials);
+    const size_t nh = (size_t)n * dm.hidden;
+    if (launch_rmsnorm(x, wt->norm_attn, xn, n, dm.hidden, dm.rms_eps, st_) != hipSuccess) return RELAX_ERR_HIP;
+    if (q3_matmul(xn, wt->wqkv, n, qkv, st_) != hipSuccess) return RELAX_ERR_HIP;
+    if (launch_rope_append(qkv, dm, *cache, st, st_) != hipSuccess) return RELAX_ERR_HIP;
+    if (launch_attention(qkv, qkvw, *cache, dm, st, L_max, attn, partials, st_) != hipSuccess) return RELAX_ERR_HIP;
+    if (q3_matmul(attn, wt->wo, n, tmp, st_) != hipSuccess) return RELAX_ERR_HIP;
+    if (launch_add_rows(x, tmp, x1, nh, st_) != hipSuccess) return RELAX_ERR_HIP;
+    if (launch_rmsnorm_f32(x1, wt->norm_ffn, xn, n, dm.hidden, dm.rms_eps, st_) != hipSuccess) return RELAX_ERR_HIP;
+    if (q3_matmul(xn, wt->wgu, n, gu, st_) != hipSuccess) return RELAX_ERR_HIP;
+    if (launch_swiglu_rows(gu, act, n, dm.ffn, st_) != hipSuccess) return RELAX_ERR_HIP;
+    if (q3_matmul(act, wt->wdown, n, tmp, st_) != hipSuccess) return RELAX_ERR_HIP;
+    if (launch_add_out(x1, tmp, out, nh, st_) != hipSuccess) return RELAX_ERR_HIP;
+    return RELAX_OK;
+}
+
+}  // extern "C"
+
+extern "C" {
+
 // Workspace of a model step: [layer workspace][xa][xb][normalised last rows][logits]
 struct ModelPlan {
     WsPlan layer;

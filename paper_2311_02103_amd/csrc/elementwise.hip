@@ -95,6 +95,66 @@ hipError_t launch_rmsnorm_f32(const float *x, const uint16_t *w, uint16_t *y, in
     return hipGetLastError();
 }
 
+// ---- the element-wise steps of a layer as launches of their own ------------------------------------------------------
+// For the layer on 3-bit weights (Sec. 5.3 of the paper deploys 3-bit models), whose matmuls have the plain fp16
+// epilogue only: residual adds and SwiGLU run between them.  Eight elements per thread, 16-byte accesses; the counts
+// are multiples of 8 (hidden and ffn are).
+//   x1[i] = x[i] + o[i]                      fp16, fp16 -> fp32   (the residual stream stays fp32 inside a layer)
+__global__ __launch_bounds__(256) void add_rows_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ o, float *__restrict__ x1, size_t count8)
+{
+    const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (t >= count8) return;
+    float a[8], b[8];
+    load8(x + t * 8, a), load8(o + t * 8, b);
+    *(float4_t *)(x1 + t * 8) = float4_t{a[0] + b[0], a[1] + b[1], a[2] + b[2], a[3] + b[3]};
+    *(float4_t *)(x1 + t * 8 + 4) = float4_t{a[4] + b[4], a[5] + b[5], a[6] + b[6], a[7] + b[7]};
+}
+//   out[i] = fp16(x1[i] + d[i])              fp32, fp16 -> fp16
+__global__ __launch_bounds__(256) void add_out_kernel(const float *__restrict__ x1, const uint16_t *__restrict__ d, uint16_t *__restrict__ out, size_t count8)
+{
+    const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (t >= count8) return;
+    float a[8], b[8];
+    load8(x1 + t * 8, a), load8(d + t * 8, b);
+    uint32_t w[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) w[j] = (uint32_t)f2h(a[2 * j] + b[2 * j]) | ((uint32_t)f2h(a[2 * j + 1] + b[2 * j + 1]) << 16);
+    *(u32x4_t *)(out + t * 8) = u32x4_t{w[0], w[1], w[2], w[3]};
+}
+//   act[i,f] = fp16(silu(gu[i,f]) * gu[i,F+f])    gu [n,2F] fp16 -> act [n,F] fp16
+__global__ __launch_bounds__(256) void swiglu_rows_kernel(const uint16_t *__restrict__ gu, uint16_t *__restrict__ act, int F)
+{
+    const int i = blockIdx.y, f = (blockIdx.x * 256 + threadIdx.x) * 8;
+    if (f >= F) return;
+    float g[8], u[8];
+    load8(gu + (size_t)i * 2 * F + f, g), load8(gu + (size_t)i * 2 * F + F + f, u);
+    uint32_t w[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const float a = g[2 * j] / (1.0f + expf(-g[2 * j])) * u[2 * j], b = g[2 * j + 1] / (1.0f + expf(-g[2 * j + 1])) * u[2 * j + 1];
+        w[j] = (uint32_t)f2h(a) | ((uint32_t)f2h(b) << 16);
+    }
+    *(u32x4_t *)(act + (size_t)i * F + f) = u32x4_t{w[0], w[1], w[2], w[3]};
+}
+
+hipError_t launch_add_rows(const uint16_t *x, const uint16_t *o, float *x1, size_t count, hipStream_t stream)
+{
+    const size_t c8 = count / 8;
+    hipLaunchKernelGGL(add_rows_kernel, dim3((unsigned)((c8 + 255) / 256)), dim3(256), 0, stream, x, o, x1, c8);
+    return hipGetLastError();
+}
+hipError_t launch_add_out(const float *x1, const uint16_t *d, uint16_t *out, size_t count, hipStream_t stream)
+{
+    const size_t c8 = count / 8;
+    hipLaunchKernelGGL(add_out_kernel, dim3((unsigned)((c8 + 255) / 256)), dim3(256), 0, stream, x1, d, out, c8);
+    return hipGetLastError();
+}
+hipError_t launch_swiglu_rows(const uint16_t *gu, uint16_t *act, int n, int F, hipStream_t stream)
+{
+    hipLaunchKernelGGL(swiglu_rows_kernel, dim3((unsigned)((F / 8 + 255) / 256), (unsigned)n), dim3(256), 0, stream, gu, act, F);
+    return hipGetLastError();
+}
+
 // table[pos][t] = (cos, sin)(pos * base^(-2t/d)), everything in fp64 until the final rounding.
 __global__ void rope_table_kernel(float *table, int cap, int hd2, int d, double base)
 {

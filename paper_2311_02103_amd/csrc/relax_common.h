@@ -329,6 +329,10 @@ __device__ inline float block_total(const float *red, int waves)
 }
 hipError_t launch_rmsnorm(const uint16_t *x, const uint16_t *w, uint16_t *y, int n, int H, float eps, hipStream_t stream);
 hipError_t launch_rmsnorm_f32(const float *x, const uint16_t *w, uint16_t *y, int n, int H, float eps, hipStream_t stream);
+// element-wise steps as launches of their own (the layer on 3-bit weights): counts are multiples of 8, pointers 16-byte aligned
+hipError_t launch_add_rows(const uint16_t *x, const uint16_t *o, float *x1, size_t count, hipStream_t stream);      // x1 = x + o (fp32)
+hipError_t launch_add_out(const float *x1, const uint16_t *d, uint16_t *out, size_t count, hipStream_t stream);     // out = fp16(x1 + d)
+hipError_t launch_swiglu_rows(const uint16_t *gu, uint16_t *act, int n, int F, hipStream_t stream);                 // act = silu(gate) * up
 
 // MFMA GEMM for large n (gemm_q4_mfma.hip)
 constexpr int kGemmMinN = 16;        // rows from which the MFMA GEMM replaces one matvec pass per row

@@ -142,3 +142,46 @@ class DeviceModel:
         rx.check(rx.relax_model_step(self.model, ids, self.caches, rx.Seqs(q_lens, kv_lens, slots, device_table), logits, next_ids,
                                      int(ids.shape[0]), self.ws, self.ws_bytes, stream), "relax_model_step")
         return logits, next_ids
+
+
+class DeviceLayerQ3:
+    """One decoder layer on 3-bit weights resident on the GPU: the canonical matrices are uploaded, repacked once into the
+    GPU-native layout (relax_repack_q3) and dropped; cache, rotary table and workspace as in DeviceLayer."""
+
+    def __init__(self, host_weights: Dict[str, np.ndarray], *, hidden: int, n_heads: int, n_kv_heads: int, head_dim: int,
+                 ffn: int, kv_capacity: int, kv_slots: int = 1, n_max: int = 1, B_max: Optional[int] = None,
+                 rms_eps: float = 1e-5, rope_base: float = 10000.0, device="cuda"):
+        self.device = device
+        self.dims = rx.make_dims(hidden, n_heads, n_kv_heads, head_dim, ffn, kv_capacity, kv_slots, rms_eps, rope_base, 32)
+        mats = {"wqkv": ((n_heads + 2 * n_kv_heads) * head_dim, hidden), "wo": (hidden, n_heads * head_dim),
+                "wgu": (2 * ffn, hidden), "wdown": (hidden, ffn)}
+        self.t = {}
+        qm = []
+        for name, (m, k) in mats.items():
+            canon, sc = to_device(host_weights[name + ".q"], device), to_device(host_weights[name + ".s"], device)
+            native = torch.empty_like(canon)
+            rx.check(rx.relax_repack_q3(rx.QMat(canon, sc, m, k, 32), native), "relax_repack_q3")
+            torch.cuda.synchronize()
+            self.t[name + ".q"], self.t[name + ".s"] = native, sc
+            qm.append(rx.QMat(native, sc, m, k, 32))
+        self.t["norm_attn"], self.t["norm_ffn"] = to_device(host_weights["norm_attn"], device), to_device(host_weights["norm_ffn"], device)
+        self.weights = rx.LayerWeights(*qm, self.t["norm_attn"], self.t["norm_ffn"])
+        self.n_max, self.B_max = n_max, (B_max if B_max is not None else max(kv_slots, 1))
+        self.rope = torch.empty(rx.relax_rope_table_bytes(self.dims) // 4, dtype=torch.float32, device=device)
+        rx.check(rx.relax_rope_table_init(self.dims, self.rope), "relax_rope_table_init")
+        self.ws_bytes = rx.relax_layer_q3_workspace_bytes(self.dims, n_max, kv_capacity, self.B_max)
+        self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device=device)
+        shape = (kv_slots, kv_capacity, n_kv_heads, head_dim)
+        self.k = torch.zeros(shape, dtype=torch.float16, device=device)
+        self.v = torch.zeros(shape, dtype=torch.float16, device=device)
+        self.cache = rx.KVCache(self.k, self.v, self.rope)
+
+    def forward(self, x: torch.Tensor, q_lens: Sequence[int], kv_lens: Sequence[int], slots=None,
+                out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+        n = x.shape[0]
+        if out is None:
+            out = torch.empty_like(x)
+        seqs = rx.Seqs(q_lens, kv_lens, slots, None)
+        rx.check(rx.relax_decoder_layer_q3(self.dims, self.weights, x, self.cache, seqs, out, n, self.ws, self.ws_bytes, stream),
+                 "relax_decoder_layer_q3")
+        return out

@@ -69,6 +69,33 @@ def test_quantiser_stays_in_range_and_close():
     assert np.all(np.abs(q3.dequantize_q3(q, s, 5, 64) - w) <= 0.5 * step + 1e-6)
 
 
+def test_layer_equals_the_4bit_reference_layer_on_embedded_codes():
+    """The composed 3-bit layer reference against the C reference of the 4-bit layer on the same real matrices
+    (u3 - 4 == (u3 + 4) - 8, same scales): a prefill of 5 rows and two decode steps, caches included."""
+    from helpers import oracle_dims
+    shape = wl.LayerShape("q3-pin", hidden=64, n_heads=2, n_kv_heads=1, head_dim=32, ffn=96)
+    r = np.random.RandomState(11)
+    w3, w4 = {}, {}
+    for name, (m, k) in shape.matrices().items():
+        codes = r.randint(0, 8, size=(m, k)).astype(np.uint8)
+        sc = (r.rand(m, k // 32) * 0.05 + 0.01).astype(np.float16).view(np.uint16)
+        w3[name + ".q"], w3[name + ".s"] = wl.pack_codes3(codes), sc
+        w4[name + ".q"], w4[name + ".s"] = wl.pack_codes(codes + 4), sc
+    for name in ("norm_attn", "norm_ffn"):
+        w3[name] = w4[name] = wl.normal_f16_bits(11, 7 if name == "norm_attn" else 8, (shape.hidden,), std=0.1, mean=1.0)
+    od = oracle_dims(shape, 16)
+    ow4 = oracle.LayerWeights(*(oracle.QMat(w4[n_ + ".q"], w4[n_ + ".s"], *shape.matrices()[n_]) for n_ in ("wqkv", "wo", "wgu", "wdown")),
+                              w4["norm_attn"], w4["norm_ffn"])
+    cs = (1, 16, shape.n_kv_heads, shape.head_dim)
+    K3, V3, K4, V4 = (np.zeros(cs, np.float32) for _ in range(4))
+    for ci, (ql, kl) in enumerate([([5], [5]), ([1], [6]), ([1], [7])]):
+        x = wl.activations(shape, 11, ci, ql[0])
+        ref = oracle.decoder_layer(od, ow4, x, K4, V4, oracle.Seqs(ql, kl, None))
+        got = q3.decoder_layer_q3(od, w3, x, K3, V3, oracle.Seqs(ql, kl, None))
+        assert np.abs(got - ref).max() <= 2e-5 * max(1.0, np.abs(ref).max()), ci
+    assert np.abs(K3 - K4).max() <= 1e-5 and np.abs(V3 - V4).max() <= 1e-5
+
+
 # ------------------------------------------------------------------------------------------------ GPU parity
 @pytest.fixture(scope="module")
 def rx():
@@ -270,3 +297,59 @@ def test_host_checks_of_the_q3_entry_points():
     assert rx.lib().relax_dequant_matmul_q3_native(64, w, 64, 0, None) == rx.ERR_SHAPE
     assert rx.lib().relax_dequant_matmul_q3_native(64, rx.QMatC(64, 64, 8, 12288 + 32), 64, 1, None) == rx.ERR_UNSUPPORTED    # one row: matvec only
     assert rx.lib().relax_dequant_matmul_q3_native(None, w, 64, 1, None) == rx.ERR_NULL
+
+
+# ------------------------------------------------------------------------------------------------ the layer on 3-bit weights
+Q3_SMALL = wl.LayerShape("q3-small", hidden=256, n_heads=4, n_kv_heads=2, head_dim=64, ffn=704)
+Q3_MID = wl.LayerShape("q3-mid", hidden=2048, n_heads=16, n_kv_heads=16, head_dim=128, ffn=5632)
+
+
+def run_q3_schedule(rx, shape, seed, cap, calls, slots=1):
+    import torch
+    from helpers import assert_close, oracle_dims
+    from paper_2311_02103_amd.runtime import DeviceLayerQ3, f16_bits, to_device
+    w = wl.layer_weights3(shape, seed)
+    n_max = max(int(np.sum(c[0])) for c in calls)
+    layer = DeviceLayerQ3(w, hidden=shape.hidden, n_heads=shape.n_heads, n_kv_heads=shape.n_kv_heads, head_dim=shape.head_dim,
+                          ffn=shape.ffn, kv_capacity=cap, kv_slots=slots, n_max=n_max, B_max=max(len(c[0]) for c in calls),
+                          rms_eps=shape.rms_eps, rope_base=shape.rope_base)
+    od = oracle_dims(shape, cap)
+    cshape = (slots, cap, shape.n_kv_heads, shape.head_dim)
+    Ko, Vo = np.zeros(cshape, np.float32), np.zeros(cshape, np.float32)
+    for ci, (ql, kl, sl) in enumerate(calls):
+        n = int(np.sum(ql))
+        x = wl.activations(shape, seed, ci, n)
+        y = layer.forward(to_device(x), ql, kl, sl)
+        torch.cuda.synchronize()
+        ref = q3.decoder_layer_q3(od, w, x, Ko, Vo, oracle.Seqs(ql, kl, sl))
+        assert_close(f16_bits(y).view(np.float16).astype(np.float32), ref, "%s 3-bit layer, call %d (n = %d)" % (shape.name, ci, n))
+    Kg, Vg = f16_bits(layer.k).view(np.float16).astype(np.float32), f16_bits(layer.v).view(np.float16).astype(np.float32)
+    assert_close(Kg.reshape(cshape), Ko, "K cache", atol=5e-3, rtol=5e-3)
+    assert_close(Vg.reshape(cshape), Vo, "V cache", atol=5e-3, rtol=5e-3)
+
+
+@pytest.mark.gpu
+def test_gpu_q3_layer_small_prefill_decode_and_ragged_batch(rx):
+    """Grouped heads, k = 256 and 704: a prefill (rows through the matvec passes: 704 is not a multiple of 128), decode steps,
+    a ragged batch over three slots."""
+    calls = [([21], [21], [0]), ([1], [22], [0]), ([1], [23], [0]), ([3, 1, 5], [3, 24, 5], [1, 0, 2]), ([1, 1, 1], [4, 25, 6], [1, 0, 2])]
+    run_q3_schedule(rx, Q3_SMALL, 13, 40, calls, slots=3)
+
+
+@pytest.mark.gpu
+def test_gpu_q3_layer_mid_through_matvec_and_gemm(rx):
+    """k = 2048 and 5632: one decode row and a few rows through the matvec passes, 40 and 130 rows through the tiled GEMM."""
+    calls = [([40], [40], None), ([1], [41], None), ([3], [44], None), ([130], [174], None), ([1], [175], None)]
+    run_q3_schedule(rx, Q3_MID, 17, 192, calls)
+
+
+def test_host_checks_of_the_q3_layer():
+    from paper_2311_02103_amd import binding as rx
+    if not os.path.exists(rx.LIB_PATH):
+        pytest.skip("library not built")
+    dims = rx.make_dims(256, 4, 2, 64, 704, 32, 1, 1e-5, 10000.0, 32)
+    assert rx.relax_layer_q3_workspace_bytes(dims, 8, 32, 2) > 0
+    assert rx.relax_layer_q3_workspace_bytes(None, 8, 32, 2) == 0
+    assert rx.relax_layer_q3_workspace_bytes(dims, 0, 32, 2) == 0
+    assert rx.relax_layer_q3_workspace_bytes(dims, 16, 32, 2) > rx.relax_layer_q3_workspace_bytes(dims, 8, 32, 2)
+    assert rx.relax_decoder_layer_q3(dims, None, 64, None, None, 64, 1, 256, 1 << 20) == rx.ERR_NULL

@@ -216,3 +216,14 @@ def qmat3(seed: int, tensor_id: int, m: int, k: int, std: float = 0.02) -> Tuple
     """One random 3-bit matrix from N(0, std^2) weights."""
     w = rng(seed, tensor_id).standard_normal((m, k), dtype=np.float32) * np.float32(std)
     return quantize_q3(w)
+
+
+def layer_weights3(shape: LayerShape, seed: int, layer: int = 0) -> Dict[str, np.ndarray]:
+    """Host arrays of one layer on 3-bit weights (canonical layout): '<mat>.q' uint32 [m, 3k/32], '<mat>.s' uint16, and
+    the two norm vectors, from the same weight distributions as layer_weights."""
+    out: Dict[str, np.ndarray] = {}
+    for name, (m, k) in shape.matrices().items():
+        out[name + ".q"], out[name + ".s"] = qmat3(seed, layer * 16 + _SLOT[name], m, k)
+    for name in ("norm_attn", "norm_ffn"):
+        out[name] = normal_f16_bits(seed, layer * 16 + _SLOT[name], (shape.hidden,), std=0.1, mean=1.0)
+    return out
