@@ -346,6 +346,24 @@ relax_status relax_decoder_layer_q3(const relax_layer_dims *dims, const relax_la
                                     const relax_kv_cache *cache, const relax_seqs *seqs, uint16_t *out, int32_t n, void *ws,
                                     size_t ws_bytes, relax_stream stream);
 
+/* The whole layer on plain fp16 weights (the fp16 models of the paper's LLM evaluation, Sec. 5.1): the same computation,
+ * dims, cache, descriptor and x / out conventions as relax_decoder_layer, the four matrices row-major fp16 -- wqkv
+ * [(h + 2g) d, H], wo [H, h d], wgu [2F, H] (gate rows, then up rows), wdown [H, F] -- and the two norm vectors, all device
+ * memory, 16-byte aligned, owned by the caller.  Like the 3-bit layer it is a sequence of launches of their own around
+ * relax_half_matmul's dispatch on n (matrix-vector passes for a few rows, tiled MFMA GEMM from the row count on at which
+ * its estimate is lower); nothing is fused, a matmul output is rounded to fp16 before the residual is added, x1 stays fp32.
+ * Workspace: relax_layer_f16_workspace_bytes(dims, n_max, L_max, B_max) bytes, 256-byte aligned (0 for invalid arguments).
+ * hidden % 8 == 0, ffn % 8 == 0, rows of at most 73728 columns.  Asynchronous on `stream`; allocates nothing; errors as
+ * relax_decoder_layer, checked before anything is enqueued.                                                         */
+typedef struct {
+    const uint16_t *wqkv, *wo, *wgu, *wdown;
+    const uint16_t *norm_attn, *norm_ffn;
+} relax_layer_f16_weights;
+size_t       relax_layer_f16_workspace_bytes(const relax_layer_dims *dims, int32_t n_max, int32_t L_max, int32_t B_max);
+relax_status relax_decoder_layer_f16(const relax_layer_dims *dims, const relax_layer_f16_weights *weights, const uint16_t *x,
+                                     const relax_kv_cache *cache, const relax_seqs *seqs, uint16_t *out, int32_t n, void *ws,
+                                     size_t ws_bytes, relax_stream stream);
+
 /* Build identity of the loaded binary (one binary serves every shape).                  */
 const char *relax_build_id(void);
 

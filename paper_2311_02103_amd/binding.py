@@ -47,6 +47,11 @@ class LayerWeightsC(C.Structure):
                 ("norm_attn", C.c_void_p), ("norm_ffn", C.c_void_p)]
 
 
+class LayerF16WeightsC(C.Structure):
+    _fields_ = [("wqkv", C.c_void_p), ("wo", C.c_void_p), ("wgu", C.c_void_p), ("wdown", C.c_void_p),
+                ("norm_attn", C.c_void_p), ("norm_ffn", C.c_void_p)]
+
+
 class KVCacheC(C.Structure):
     _fields_ = [("k", C.c_void_p), ("v", C.c_void_p), ("rope", C.c_void_p)]
 
@@ -98,6 +103,9 @@ _SIGNATURES = {
     "relax_layer_q3_workspace_bytes": (C.c_size_t, [C.POINTER(LayerDims), C.c_int32, C.c_int32, C.c_int32]),
     "relax_decoder_layer_q3": (C.c_int32, [C.POINTER(LayerDims), C.POINTER(LayerWeightsC), C.c_void_p, C.POINTER(KVCacheC),
                                            C.POINTER(SeqsC), C.c_void_p, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "relax_layer_f16_workspace_bytes": (C.c_size_t, [C.POINTER(LayerDims), C.c_int32, C.c_int32, C.c_int32]),
+    "relax_decoder_layer_f16": (C.c_int32, [C.POINTER(LayerDims), C.POINTER(LayerF16WeightsC), C.c_void_p, C.POINTER(KVCacheC),
+                                            C.POINTER(SeqsC), C.c_void_p, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]),
     "relax_model_workspace_bytes": (C.c_size_t, [C.POINTER(ModelC), C.c_int32, C.c_int32, C.c_int32]),
     "relax_model_step": (C.c_int32, [C.POINTER(ModelC), C.c_void_p, C.POINTER(KVCacheC), C.POINTER(SeqsC), C.c_void_p,
                                      C.c_void_p, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]),
@@ -314,6 +322,20 @@ def relax_decoder_layer_q3(dims: Optional[LayerDims], weights: Optional[LayerWei
     sc = None if seqs is None else seqs.c()
     return lib().relax_decoder_layer_q3(_ref(dims), _ref(wc), _ptr(x), _ref(cc), _ref(sc), _ptr(out), n, _ptr(ws), ws_bytes,
                                         _stream(stream))
+
+
+def relax_layer_f16_workspace_bytes(dims: Optional[LayerDims], n_max: int, L_max: int, B_max: int) -> int:
+    return int(lib().relax_layer_f16_workspace_bytes(_ref(dims), n_max, L_max, B_max))
+
+
+def relax_decoder_layer_f16(dims: Optional[LayerDims], weights, x: Ptr, cache: Optional[KVCache], seqs: Optional[Seqs], out: Ptr,
+                            n: int, ws: Ptr, ws_bytes: int, stream=None) -> int:
+    """weights: sequence of six device pointers (wqkv, wo, wgu, wdown, norm_attn, norm_ffn) or None."""
+    wc = None if weights is None else LayerF16WeightsC(*[_ptr(w) for w in weights])
+    cc = None if cache is None else cache.c()
+    sc = None if seqs is None else seqs.c()
+    return lib().relax_decoder_layer_f16(_ref(dims), _ref(wc), _ptr(x), _ref(cc), _ref(sc), _ptr(out), n, _ptr(ws), ws_bytes,
+                                         _stream(stream))
 
 
 class Model:

@@ -808,6 +808,7 @@ relax_status relax_decoder_layer(const relax_layer_dims *dims, const relax_layer
 // The same layer, composed of launches of their own: the 3-bit matmuls have the plain fp16 epilogue only, so the light
 // steps run between them (RMSNorm, rotary + append, attention, residual adds, SwiGLU).  Its workspace is laid out one
 // intermediate after the other (nothing is shared: the schedule differs from the one the planner of the 4-bit layer walks).
+// The layer on plain fp16 weights further down is the same sequence around relax_half_matmul's dispatch and shares the layout.
 namespace {
 struct Q3Plan {
     WsPlan ws;                       // flags, table and partials at their usual places (upload_table and the attention launch read them)
@@ -898,6 +899,59 @@ relax_status relax_decoder_layer_q3(const relax_layer_dims *dims, const relax_la
     if (q3_matmul(xn, wt->wgu, n, gu, st_) != hipSuccess) return RELAX_ERR_HIP;
     if (launch_swiglu_rows(gu, act, n, dm.ffn, st_) != hipSuccess) return RELAX_ERR_HIP;
     if (q3_matmul(act, wt->wdown, n, tmp, st_) != hipSuccess) return RELAX_ERR_HIP;
+    if (launch_add_out(x1, tmp, out, nh, st_) != hipSuccess) return RELAX_ERR_HIP;
+    return RELAX_OK;
+}
+
+// ---- the same sequence on plain fp16 weights (the fp16 models of the paper's LLM evaluation, Sec. 5.1) -----------------
+size_t relax_layer_f16_workspace_bytes(const relax_layer_dims *dims, int32_t n_max, int32_t L_max, int32_t B_max)
+{
+    if (check_dims(dims) != RELAX_OK || n_max < 1 || L_max < 1 || B_max < 1) return 0;
+    return plan_q3(*dims, n_max, L_max, B_max).total;
+}
+
+relax_status relax_decoder_layer_f16(const relax_layer_dims *dims, const relax_layer_f16_weights *wt, const uint16_t *x,
+                                     const relax_kv_cache *cache, const relax_seqs *seqs, uint16_t *out, int32_t n, void *ws,
+                                     size_t ws_bytes, relax_stream stream)
+{
+    hipStream_t st_ = static_cast<hipStream_t>(stream);
+    relax_status rc = check_dims(dims);
+    if (rc != RELAX_OK) return rc;
+    if (!wt || !x || !out || !ws || !cache || !cache->k || !cache->v || !cache->rope) return RELAX_ERR_NULL;
+    if (!wt->wqkv || !wt->wo || !wt->wgu || !wt->wdown || !wt->norm_attn || !wt->norm_ffn) return RELAX_ERR_NULL;
+    const relax_layer_dims &dm = *dims;
+    const int32_t hd = dm.n_heads * dm.head_dim, qkvw = (dm.n_heads + 2 * dm.n_kv_heads) * dm.head_dim;
+    if (dm.hidden % 8 != 0 || dm.ffn % 8 != 0) return RELAX_ERR_SHAPE;
+    const uintptr_t ptrs = reinterpret_cast<uintptr_t>(wt->wqkv) | reinterpret_cast<uintptr_t>(wt->wo) | reinterpret_cast<uintptr_t>(wt->wgu) |
+                           reinterpret_cast<uintptr_t>(wt->wdown) | reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(out);
+    if ((ptrs & 15) != 0) return RELAX_ERR_SHAPE;
+    if (2 * (size_t)std::max(std::max(dm.hidden, hd), dm.ffn) > 144 * 1024) return RELAX_ERR_UNSUPPORTED;     // one x row has to fit the matvec kernel's LDS
+    SeqTable st = {};
+    bool need_table = false;
+    int32_t L_max = 0;
+    rc = build_seqs(seqs, dm, n, st, L_max, need_table);
+    if (rc != RELAX_OK) return rc;
+    const Q3Plan pl = plan_q3(dm, n, L_max, seqs->B);
+    if (ws_bytes < pl.total || (reinterpret_cast<uintptr_t>(ws) & 255) != 0) return RELAX_ERR_WORKSPACE;
+    rc = upload_table(st, seqs, need_table, ws, pl.ws, st_);
+    if (rc != RELAX_OK) return rc;
+
+    char *base = static_cast<char *>(ws);
+    uint16_t *xn = reinterpret_cast<uint16_t *>(base + pl.ws.xn), *qkv = reinterpret_cast<uint16_t *>(base + pl.ws.qkv);
+    uint16_t *attn = reinterpret_cast<uint16_t *>(base + pl.ws.attn), *act = reinterpret_cast<uint16_t *>(base + pl.ws.act);
+    uint16_t *gu = reinterpret_cast<uint16_t *>(base + pl.gu), *tmp = reinterpret_cast<uint16_t *>(base + pl.tmp);
+    float *x1 = reinterpret_cast<float *>(base + pl.ws.x1), *partials = reinterpret_cast<float *>(base + pl.ws.partials);
+    const size_t nh = (size_t)n * dm.hidden;
+    if (launch_rmsnorm(x, wt->norm_attn, xn, n, dm.hidden, dm.rms_eps, st_) != hipSuccess) return RELAX_ERR_HIP;
+    if (half_matmul_enqueue(xn, wt->wqkv, qkv, n, qkvw, dm.hidden, st_) != hipSuccess) return RELAX_ERR_HIP;
+    if (launch_rope_append(qkv, dm, *cache, st, st_) != hipSuccess) return RELAX_ERR_HIP;
+    if (launch_attention(qkv, qkvw, *cache, dm, st, L_max, attn, partials, st_) != hipSuccess) return RELAX_ERR_HIP;
+    if (half_matmul_enqueue(attn, wt->wo, tmp, n, dm.hidden, hd, st_) != hipSuccess) return RELAX_ERR_HIP;
+    if (launch_add_rows(x, tmp, x1, nh, st_) != hipSuccess) return RELAX_ERR_HIP;
+    if (launch_rmsnorm_f32(x1, wt->norm_ffn, xn, n, dm.hidden, dm.rms_eps, st_) != hipSuccess) return RELAX_ERR_HIP;
+    if (half_matmul_enqueue(xn, wt->wgu, gu, n, 2 * dm.ffn, dm.hidden, st_) != hipSuccess) return RELAX_ERR_HIP;
+    if (launch_swiglu_rows(gu, act, n, dm.ffn, st_) != hipSuccess) return RELAX_ERR_HIP;
+    if (half_matmul_enqueue(act, wt->wdown, tmp, n, dm.hidden, dm.ffn, st_) != hipSuccess) return RELAX_ERR_HIP;
     if (launch_add_out(x1, tmp, out, nh, st_) != hipSuccess) return RELAX_ERR_HIP;
     return RELAX_OK;
 }

@@ -185,3 +185,36 @@ class DeviceLayerQ3:
         rx.check(rx.relax_decoder_layer_q3(self.dims, self.weights, x, self.cache, seqs, out, n, self.ws, self.ws_bytes, stream),
                  "relax_decoder_layer_q3")
         return out
+
+
+class DeviceLayerF16:
+    """One decoder layer on plain fp16 weights resident on the GPU.  host_weights: 'wqkv', 'wo', 'wgu', 'wdown' as fp16 bit
+    patterns [m,k] and the two norm vectors."""
+
+    def __init__(self, host_weights: Dict[str, np.ndarray], *, hidden: int, n_heads: int, n_kv_heads: int, head_dim: int,
+                 ffn: int, kv_capacity: int, kv_slots: int = 1, n_max: int = 1, B_max: Optional[int] = None,
+                 rms_eps: float = 1e-5, rope_base: float = 10000.0, device="cuda"):
+        self.device = device
+        self.dims = rx.make_dims(hidden, n_heads, n_kv_heads, head_dim, ffn, kv_capacity, kv_slots, rms_eps, rope_base, 32)
+        names = ("wqkv", "wo", "wgu", "wdown", "norm_attn", "norm_ffn")
+        self.t = {k: to_device(host_weights[k], device) for k in names}
+        self.weights = [self.t[k] for k in names]
+        self.n_max, self.B_max = n_max, (B_max if B_max is not None else max(kv_slots, 1))
+        self.rope = torch.empty(rx.relax_rope_table_bytes(self.dims) // 4, dtype=torch.float32, device=device)
+        rx.check(rx.relax_rope_table_init(self.dims, self.rope), "relax_rope_table_init")
+        self.ws_bytes = rx.relax_layer_f16_workspace_bytes(self.dims, n_max, kv_capacity, self.B_max)
+        self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device=device)
+        shape = (kv_slots, kv_capacity, n_kv_heads, head_dim)
+        self.k = torch.zeros(shape, dtype=torch.float16, device=device)
+        self.v = torch.zeros(shape, dtype=torch.float16, device=device)
+        self.cache = rx.KVCache(self.k, self.v, self.rope)
+
+    def forward(self, x: torch.Tensor, q_lens: Sequence[int], kv_lens: Sequence[int], slots=None,
+                out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+        n = x.shape[0]
+        if out is None:
+            out = torch.empty_like(x)
+        seqs = rx.Seqs(q_lens, kv_lens, slots, None)
+        rx.check(rx.relax_decoder_layer_f16(self.dims, self.weights, x, self.cache, seqs, out, n, self.ws, self.ws_bytes, stream),
+                 "relax_decoder_layer_f16")
+        return out

@@ -1,0 +1,112 @@
+"""The decoder layer on plain fp16 weights: the composed CPU reference is pinned against the C reference of the 4-bit
+layer on matrices both can hold exactly; on the GPU, relax_decoder_layer_f16 against that reference."""
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from oracle import half_layer
+import workloads as wl
+from helpers import assert_close, oracle_dims
+
+MATS = ("wqkv", "wo", "wgu", "wdown")
+
+
+def half_weights(shape, seed):
+    """fp16 matrices with the weight scale of the int4 workloads (N(0, 0.02^2)) and the norm vectors."""
+    w = {}
+    for j, (name, (m, k)) in enumerate(shape.matrices().items()):
+        w[name] = (wl.normal_f32(seed, 40 + j, (m, k)) * np.float32(0.02)).astype(np.float16).view(np.uint16)
+    for j, name in enumerate(("norm_attn", "norm_ffn")):
+        w[name] = wl.normal_f16_bits(seed, 50 + j, (shape.hidden,), std=0.1, mean=1.0)
+    return w
+
+
+def test_reference_equals_the_4bit_reference_layer_on_exactly_representable_weights():
+    """4-bit codes with power-of-two scales dequantise to values fp16 holds exactly: the composed fp16 reference on those
+    values against the C reference of the 4-bit layer -- a prefill of 5 rows and two decode steps, caches included."""
+    shape = wl.LayerShape("f16-pin", hidden=64, n_heads=2, n_kv_heads=1, head_dim=32, ffn=96)
+    r = np.random.RandomState(21)
+    w4, wh = {}, {}
+    for name, (m, k) in shape.matrices().items():
+        codes = r.randint(0, 16, size=(m, k)).astype(np.uint8)
+        sc = r.choice([1.0 / 64, 1.0 / 32, 1.0 / 16], size=(m, k // 32)).astype(np.float16)
+        w4[name + ".q"], w4[name + ".s"] = wl.pack_codes(codes), sc.view(np.uint16)
+        dense = (codes.astype(np.float32) - 8.0) * np.repeat(sc.astype(np.float32), 32, axis=1)
+        assert np.array_equal(dense.astype(np.float16).astype(np.float32), dense)
+        wh[name] = dense.astype(np.float16).view(np.uint16)
+    for name in ("norm_attn", "norm_ffn"):
+        w4[name] = wh[name] = wl.normal_f16_bits(21, 7 if name == "norm_attn" else 8, (shape.hidden,), std=0.1, mean=1.0)
+    od = oracle_dims(shape, 16)
+    ow4 = oracle.LayerWeights(*(oracle.QMat(w4[n_ + ".q"], w4[n_ + ".s"], *shape.matrices()[n_]) for n_ in MATS), w4["norm_attn"], w4["norm_ffn"])
+    cs = (1, 16, shape.n_kv_heads, shape.head_dim)
+    Kh, Vh, K4, V4 = (np.zeros(cs, np.float32) for _ in range(4))
+    for ci, (ql, kl) in enumerate([([5], [5]), ([1], [6]), ([1], [7])]):
+        x = wl.activations(shape, 21, ci, ql[0])
+        ref = oracle.decoder_layer(od, ow4, x, K4, V4, oracle.Seqs(ql, kl, None))
+        got = half_layer.decoder_layer_f16(od, wh, x, Kh, Vh, oracle.Seqs(ql, kl, None))
+        assert np.abs(got - ref).max() <= 2e-5 * max(1.0, np.abs(ref).max()), ci
+    assert np.abs(Kh - K4).max() <= 1e-5 and np.abs(Vh - V4).max() <= 1e-5
+
+
+def test_host_checks():
+    from paper_2311_02103_amd import binding as rx
+    if not os.path.exists(rx.LIB_PATH):
+        pytest.skip("library not built")
+    dims = rx.make_dims(256, 4, 2, 64, 704, 32, 1, 1e-5, 10000.0, 32)
+    assert rx.relax_layer_f16_workspace_bytes(dims, 8, 32, 2) > 0
+    assert rx.relax_layer_f16_workspace_bytes(None, 8, 32, 2) == 0
+    assert rx.relax_layer_f16_workspace_bytes(dims, 8, 0, 2) == 0
+    assert rx.relax_decoder_layer_f16(dims, None, 64, None, None, 64, 1, 256, 1 << 20) == rx.ERR_NULL
+
+
+@pytest.fixture(scope="module")
+def rx():
+    import torch
+    from paper_2311_02103_amd import binding
+    assert torch.cuda.is_available()
+    binding.lib()
+    return binding
+
+
+F16_SMALL = wl.LayerShape("f16-small", hidden=256, n_heads=4, n_kv_heads=2, head_dim=64, ffn=704)
+F16_MID = wl.LayerShape("f16-mid", hidden=2048, n_heads=16, n_kv_heads=16, head_dim=128, ffn=5632)
+
+
+def run_schedule(rx, shape, seed, cap, calls, slots=1):
+    import torch
+    from paper_2311_02103_amd.runtime import DeviceLayerF16, f16_bits, to_device
+    w = half_weights(shape, seed)
+    n_max = max(int(np.sum(c[0])) for c in calls)
+    layer = DeviceLayerF16(w, hidden=shape.hidden, n_heads=shape.n_heads, n_kv_heads=shape.n_kv_heads, head_dim=shape.head_dim,
+                           ffn=shape.ffn, kv_capacity=cap, kv_slots=slots, n_max=n_max, B_max=max(len(c[0]) for c in calls),
+                           rms_eps=shape.rms_eps, rope_base=shape.rope_base)
+    od = oracle_dims(shape, cap)
+    cshape = (slots, cap, shape.n_kv_heads, shape.head_dim)
+    Ko, Vo = np.zeros(cshape, np.float32), np.zeros(cshape, np.float32)
+    for ci, (ql, kl, sl) in enumerate(calls):
+        n = int(np.sum(ql))
+        x = wl.activations(shape, seed, ci, n)
+        y = layer.forward(to_device(x), ql, kl, sl)
+        torch.cuda.synchronize()
+        ref = half_layer.decoder_layer_f16(od, w, x, Ko, Vo, oracle.Seqs(ql, kl, sl))
+        assert_close(f16_bits(y).view(np.float16).astype(np.float32), ref, "%s fp16-weight layer, call %d (n = %d)" % (shape.name, ci, n))
+    Kg, Vg = f16_bits(layer.k).view(np.float16).astype(np.float32), f16_bits(layer.v).view(np.float16).astype(np.float32)
+    assert_close(Kg.reshape(cshape), Ko, "K cache", atol=5e-3, rtol=5e-3)
+    assert_close(Vg.reshape(cshape), Vo, "V cache", atol=5e-3, rtol=5e-3)
+
+
+@pytest.mark.gpu
+def test_gpu_layer_small_prefill_decode_and_ragged_batch(rx):
+    """Grouped heads, k = 256 and 704 (matvec passes only: 704 is not a multiple of 128): a prefill, decode steps, a ragged
+    batch over three slots."""
+    calls = [([21], [21], [0]), ([1], [22], [0]), ([1], [23], [0]), ([3, 1, 5], [3, 24, 5], [1, 0, 2]), ([1, 1, 1], [4, 25, 6], [1, 0, 2])]
+    run_schedule(rx, F16_SMALL, 13, 40, calls, slots=3)
+
+
+@pytest.mark.gpu
+def test_gpu_layer_mid_through_matvec_and_gemm(rx):
+    """k = 2048 and 5632: one decode row and a few rows through the matvec passes, 40 and 130 rows through the tiled GEMM."""
+    calls = [([40], [40], None), ([1], [41], None), ([3], [44], None), ([130], [174], None), ([1], [175], None)]
+    run_schedule(rx, F16_MID, 17, 192, calls)
