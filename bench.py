@@ -650,12 +650,50 @@ def bench_half_sweep(args, np, torch, wl, rx):
             del ws_
     finally:
         rx.check(rx.relax_set_option("half_matmul_gemm_rows", 0))     # back to the default: by estimate
+    # the whole 7B-shaped layer on fp16 weights (relax_decoder_layer_f16: eleven launches), three rotating weight sets of 405 MB
+    layer16 = {}
+    shape7 = wl.LLAMA7B
+    dims = rx.make_dims(shape7.hidden, shape7.n_heads, shape7.n_kv_heads, shape7.head_dim, shape7.ffn, 2304, 1, shape7.rms_eps, shape7.rope_base, 32)
+    sets16 = []
+    for _ in range(3):
+        mats = [(torch.randn((m, k), device="cuda", dtype=torch.float32) * 0.02).to(torch.float16)
+                for m, k in ((12288, 4096), (4096, 4096), (22016, 4096), (4096, 11008))]
+        nw = (torch.randn(4096, device="cuda") * 0.1 + 1.0).to(torch.float16)
+        sets16.append(mats + [nw, nw])
+    rope = torch.empty(rx.relax_rope_table_bytes(dims) // 4, dtype=torch.float32, device="cuda")
+    rx.check(rx.relax_rope_table_init(dims, rope, stream), "relax_rope_table_init")
+    kc = torch.randn((1, 2304, shape7.n_kv_heads, shape7.head_dim), device="cuda", dtype=torch.float16)
+    cache = rx.KVCache(kc, kc.clone(), rope)
+    wbytes = 2 * (12288 * 4096 + 4096 * 4096 + 22016 * 4096 + 4096 * 11008)
+    for n, L, reps in ((1, 2231, 120), (2048, 2048, 6)):
+        wsb = rx.relax_layer_f16_workspace_bytes(dims, n, 2304, 1)
+        ws16 = torch.empty(wsb, dtype=torch.uint8, device="cuda")
+        x16 = torch.randn((n, 4096), device="cuda", dtype=torch.float16)
+        o16 = torch.empty_like(x16)
+        seqs = rx.Seqs([n], [L], None, None)
+        for i in range(6):
+            rx.check(rx.relax_decoder_layer_f16(dims, sets16[i % 3], x16, cache, seqs, o16, n, ws16, wsb, stream), "relax_decoder_layer_f16")
+        start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        stream.synchronize()
+        start.record(stream)
+        for i in range(reps):
+            rx.relax_decoder_layer_f16(dims, sets16[i % 3], x16, cache, seqs, o16, n, ws16, wsb, stream)
+        stop.record(stream)
+        stream.synchronize()
+        us = start.elapsed_time(stop) * 1e3 / reps
+        row = {"us_per_call": round(us, 1)}
+        if n == 1:
+            alg = wbytes + 2 * L * shape7.n_kv_heads * shape7.head_dim * 2
+            row.update(algorithmic_MB=round(alg / 1e6, 1), GBps=round(alg / us / 1e3, 1), frac_of_hbm_peak=round(alg / us / 1e3 / PEAK_HBM_GBS, 4))
+        layer16["n=%d L=%d" % (n, L)] = row
+        del ws16, x16, o16
+    del sets16, kc, cache
     big = table["gate_up 22016x4096"]["rows"][-1]
     tflops = 2.0 * 2048 * 22016 * 4096 / (big["gemm_us"] * 1e-6) / 1e12
     emit(args, "fp16-weight GEMM rate at n = 2048 on the gate/up shape (22016 x 4096)", "TFLOP/s", tflops, big["gemm_us"] / 1e3, "f16 MFMA, f32 accumulate",
          {"workload": "fp16-weight matmul against the row count, matvec passes and tiled GEMM forced in turn", "build_id": rx.relax_build_id()},
          {"bound": "mfma", "kernel": "gemm_q4_mfma_kernel<EPI_F16, 4, 4, fp16 weights>", "achieved": round(tflops, 1), "peak": PEAK_MFMA_TFLOPS,
-          "unit": "TFLOP/s", "frac": round(tflops / PEAK_MFMA_TFLOPS, 4), "traffic": None}, None, {"half_sweep": table})
+          "unit": "TFLOP/s", "frac": round(tflops / PEAK_MFMA_TFLOPS, 4), "traffic": None}, None, {"half_sweep": table, "f16_layer_7b": layer16})
 
 
 # ------------------------------------------------------------------------------------------------ 3-bit matvec
