@@ -349,9 +349,12 @@ relax_status relax_decoder_layer_q3(const relax_layer_dims *dims, const relax_la
 /* The whole layer on plain fp16 weights (the fp16 models of the paper's LLM evaluation, Sec. 5.1): the same computation,
  * dims, cache, descriptor and x / out conventions as relax_decoder_layer, the four matrices row-major fp16 -- wqkv
  * [(h + 2g) d, H], wo [H, h d], wgu [2F, H] (gate rows, then up rows), wdown [H, F] -- and the two norm vectors, all device
- * memory, 16-byte aligned, owned by the caller.  Like the 3-bit layer it is a sequence of launches of their own around
- * relax_half_matmul's dispatch on n (matrix-vector passes for a few rows, tiled MFMA GEMM from the row count on at which
- * its estimate is lower); nothing is fused, a matmul output is rounded to fp16 before the residual is added, x1 stays fp32.
+ * memory, 16-byte aligned, owned by the caller.  From two rows on it is, like the 3-bit layer, a sequence of launches of
+ * their own around relax_half_matmul's dispatch on n (matrix-vector passes for a few rows, tiled MFMA GEMM from the row
+ * count on at which its estimate is lower): nothing is fused, a matmul output is rounded to fp16 before the residual is
+ * added, x1 stays fp32.  One row (n == 1, rows of at most 12288 columns) runs the five fused launches of the 4-bit decode
+ * layer on the fp16 stream of the same matrix-vector kernel: the norms, rotary + append, the attention merge, the
+ * residuals and SwiGLU happen inside the four matrix-vector launches, on fp32 sums that are not rounded in between.
  * Workspace: relax_layer_f16_workspace_bytes(dims, n_max, L_max, B_max) bytes, 256-byte aligned (0 for invalid arguments).
  * hidden % 8 == 0, ffn % 8 == 0, rows of at most 73728 columns.  Asynchronous on `stream`; allocates nothing; errors as
  * relax_decoder_layer, checked before anything is enqueued.                                                         */

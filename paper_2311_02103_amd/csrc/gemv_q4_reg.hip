@@ -201,10 +201,16 @@ constexpr int rows_per_slot(bool few_rows)
 // (a captured launch is then valid for later positions too); only the two variants that need a position have it.
 // Several rows per pass keep NR times the x registers: those variants are compiled for one wavefront per SIMD (which is
 // how every variant runs: one workgroup per CU), so that the allocator may use the whole register file instead of spilling.
-template <int XMODE, int EPI, int NG, int R, bool DEV = false, int NR = 1>
+// FP16W: the matrix is plain fp16, a.wh [m,k] (the fp16 models of Sec. 5.1): the same stream with four 16-byte loads per lane,
+// row and chunk instead of one load and a scale -- load j of chunk c brings columns 2048 c + 512 j + 8 lane .. + 7, a contiguous
+// kilobyte per instruction -- and nothing to decode: x is staged in plain column order and a load meets its eight x values
+// in four v_dot2_f32_f16.  Columns past the end of a row meet x = 0 (the staging zero-fills), so no lane is masked.
+template <int XMODE, int EPI, int NG, int R, bool DEV = false, int NR = 1, bool FP16W = false>
 __global__ __launch_bounds__(kRThreads) __attribute__((amdgpu_waves_per_eu(1, 1))) void gemv_q4_reg_kernel(GemvArgs a)
 {
     static_assert(NR == 1 || (XMODE != X_ATTN_MERGE && !DEV), "several rows per pass: plain and normalising prologues, host descriptor");
+    static_assert(!FP16W || NR == 1, "fp16 weights: one row of x per pass");
+    constexpr int LW = FP16W ? 4 : 1;                              // 16-byte loads per lane, row and chunk
     constexpr int NSLOT = kRSlots, E = R * NG;
     constexpr int kResPitch = NR * (kRMaxUnits * 2 + 4);
     constexpr int kFirstRagged = NG >= 4 ? NG - 2 : NG - 1;        // first chunk of 2048 columns that a row may end in
@@ -213,7 +219,8 @@ __global__ __launch_bounds__(kRThreads) __attribute__((amdgpu_waves_per_eu(1, 1)
     __shared__ float res_all[kRWaves][kResPitch];              // one sum per matrix row of the wavefront and row of x (+ the dead rows of a last slot)
     // The arguments this variant uses, in scalar registers from here on: one round of scalar loads and one wait ahead of
     // the first request, none at the place of a first use further down (where the stream or the epilogue would wait).
-    asm volatile("" ::"s"(a.x), "s"(a.q), "s"(a.s), "s"(a.m), "s"(a.k), "s"(a.gshift), "s"(a.units_div), "s"(a.units_mod));
+    if (FP16W) asm volatile("" ::"s"(a.x), "s"(a.wh), "s"(a.m), "s"(a.k), "s"(a.units_div), "s"(a.units_mod));
+    else asm volatile("" ::"s"(a.x), "s"(a.q), "s"(a.s), "s"(a.m), "s"(a.k), "s"(a.gshift), "s"(a.units_div), "s"(a.units_mod));
     if (XMODE == X_F16_NORM || XMODE == X_F32_NORM) asm volatile("" ::"s"(a.norm_w), "s"(a.eps));
     if (XMODE == X_ATTN_MERGE) asm volatile("" ::"s"(a.part), "s"(a.part_splits), "s"(a.part_stride), "s"(a.part_used), "s"(a.h), "s"(a.d));
     if (EPI == EPI_RESID_F32) asm volatile("" ::"s"(a.out_f32), "s"(a.resid));
@@ -295,8 +302,8 @@ __global__ __launch_bounds__(kRThreads) __attribute__((amdgpu_waves_per_eu(1, 1)
     x_loads();
 
     struct Slot {
-        u32x4_t w[E];
-        uint16_t sc[E];
+        u32x4_t w[E * LW];
+        uint16_t sc[FP16W ? 1 : E];
     };
     // entry e = rr * NG + c: row rr of the slot (unit j0 + rr / 2, its first or second row), chunk c
     // The requests of a slot stay together in program order (scheduling barriers on both sides): the wait before a
@@ -316,6 +323,17 @@ __global__ __launch_bounds__(kRThreads) __attribute__((amdgpu_waves_per_eu(1, 1)
             int rows[2];
             unit_rows_r<EPI>(a, u, rows[0], rows[1]);
             const int row = __builtin_amdgcn_readfirstlane((t & 1) ? rows[1] : rows[0]);     // uniform: row bases in scalar registers
+            if constexpr (FP16W) {
+                const uint16_t *wrow = a.wh + (size_t)row * k;
+#pragma unroll
+                for (int c = 0; c < NG; ++c)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const int pk = c * 256 + j * 64 + lane;    // 16-byte packet of the row; past the end: the last one (it meets x = 0)
+                        const int pc = (c >= kFirstRagged) ? min(pk, kw - 1) : pk;
+                        s.w[(rr * NG + c) * 4 + j] = stream_load((const u32x4_t *)(wrow + (size_t)pc * 8));
+                    }
+            } else {
             const uint32_t *qrow = a.q + (size_t)row * kw;
             const uint16_t *srow = a.s + (size_t)row * SG;
 #pragma unroll
@@ -324,6 +342,7 @@ __global__ __launch_bounds__(kRThreads) __attribute__((amdgpu_waves_per_eu(1, 1)
                 const int gi = (c >= kFirstRagged) ? min(c * 64 + lane, G - 1) : c * 64 + lane;
                 s.w[rr * NG + c] = stream_load((const u32x4_t *)(qrow + gi * 4));
                 s.sc[rr * NG + c] = srow[gi >> a.gshift];     // 1, 2 or 4 neighbouring lanes read the same scale
+            }
             }
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -388,8 +407,13 @@ __global__ __launch_bounds__(kRThreads) __attribute__((amdgpu_waves_per_eu(1, 1)
                 const uint32_t ww = wnr[p][e >> 1];
                 y[e] = f2h(xf[xr][p][e] * inv[xr] * h2f((uint16_t)((e & 1) ? (ww >> 16) : (ww & 0xFFFFu))));
             }
-            o.x = (uint32_t)y[0] | ((uint32_t)y[4] << 16), o.y = (uint32_t)y[1] | ((uint32_t)y[5] << 16);
-            o.z = (uint32_t)y[2] | ((uint32_t)y[6] << 16), o.w = (uint32_t)y[3] | ((uint32_t)y[7] << 16);
+            if (FP16W) {
+                o.x = (uint32_t)y[0] | ((uint32_t)y[1] << 16), o.y = (uint32_t)y[2] | ((uint32_t)y[3] << 16);
+                o.z = (uint32_t)y[4] | ((uint32_t)y[5] << 16), o.w = (uint32_t)y[6] | ((uint32_t)y[7] << 16);
+            } else {
+                o.x = (uint32_t)y[0] | ((uint32_t)y[4] << 16), o.y = (uint32_t)y[1] | ((uint32_t)y[5] << 16);
+                o.z = (uint32_t)y[2] | ((uint32_t)y[6] << 16), o.w = (uint32_t)y[3] | ((uint32_t)y[7] << 16);
+            }
         } else if (kMerge) {
             // out = sum_s acc_s e^(m_s - M) / sum_s l_s e^(m_s - M), rounded to fp16 like the stand-alone merge
             const bool on = (p * kRThreads + tid) < kw;
@@ -416,16 +440,28 @@ __global__ __launch_bounds__(kRThreads) __attribute__((amdgpu_waves_per_eu(1, 1)
             uint16_t y[8];
 #pragma unroll
             for (int e = 0; e < 8; ++e) y[e] = f2h(num[e] * rden);
-            o.x = (uint32_t)y[0] | ((uint32_t)y[4] << 16), o.y = (uint32_t)y[1] | ((uint32_t)y[5] << 16);
-            o.z = (uint32_t)y[2] | ((uint32_t)y[6] << 16), o.w = (uint32_t)y[3] | ((uint32_t)y[7] << 16);
+            if (FP16W) {
+                o.x = (uint32_t)y[0] | ((uint32_t)y[1] << 16), o.y = (uint32_t)y[2] | ((uint32_t)y[3] << 16);
+                o.z = (uint32_t)y[4] | ((uint32_t)y[5] << 16), o.w = (uint32_t)y[6] | ((uint32_t)y[7] << 16);
+            } else {
+                o.x = (uint32_t)y[0] | ((uint32_t)y[4] << 16), o.y = (uint32_t)y[1] | ((uint32_t)y[5] << 16);
+                o.z = (uint32_t)y[2] | ((uint32_t)y[6] << 16), o.w = (uint32_t)y[3] | ((uint32_t)y[7] << 16);
+            }
         } else {
             const bool on = (p * kRThreads + tid) < kw;
             const u32x4_t r = xraw[xr][p];
-            o.x = __builtin_amdgcn_perm(r.z, r.x, 0x05040100u), o.y = __builtin_amdgcn_perm(r.z, r.x, 0x07060302u);
-            o.z = __builtin_amdgcn_perm(r.w, r.y, 0x05040100u), o.w = __builtin_amdgcn_perm(r.w, r.y, 0x07060302u);
+            if (FP16W) {
+                o = r;
+            } else {
+                o.x = __builtin_amdgcn_perm(r.z, r.x, 0x05040100u), o.y = __builtin_amdgcn_perm(r.z, r.x, 0x07060302u);
+                o.z = __builtin_amdgcn_perm(r.w, r.y, 0x05040100u), o.w = __builtin_amdgcn_perm(r.w, r.y, 0x07060302u);
+            }
             if (!on) o = u32x4_t{0u, 0u, 0u, 0u};
         }
-        *(u32x4_t *)(xs + xr * (NG * 2048) + (((p * 4 + (tid & 3)) << 6) + (tid >> 2)) * 8) = o;
+        // the thread holds columns 2048 p + 8 tid .. + 7: word tid & 3 of group 64 p + (tid >> 2), or (fp16 weights) the packet that
+        // load tid >> 6 of lane tid & 63 meets
+        if (FP16W) *(u32x4_t *)(xs + xr * (NG * 2048) + (((p * 4 + (tid >> 6)) << 6) + (tid & 63)) * 8) = o;
+        else *(u32x4_t *)(xs + xr * (NG * 2048) + (((p * 4 + (tid & 3)) << 6) + (tid >> 2)) * 8) = o;
     }
     wg_barrier();
     // the lane's share of x: group c * 64 + lane of every chunk, and the offset term of each group
@@ -442,7 +478,7 @@ __global__ __launch_bounds__(kRThreads) __attribute__((amdgpu_waves_per_eu(1, 1)
             sa = dot2(xv[xr][c][j].x, 0x3C003C00u, sa), sb = dot2(xv[xr][c][j].y, 0x3C003C00u, sb);
             sa = dot2(xv[xr][c][j].z, 0x3C003C00u, sa), sb = dot2(xv[xr][c][j].w, 0x3C003C00u, sb);
         }
-        cr[xr][c] = 1032.0f * sa + 72.0f * sb;
+        cr[xr][c] = FP16W ? 0.0f : 1032.0f * sa + 72.0f * sb;
     }
     bool chunk_on[NG];                                             // lanes past the last group of the row contribute nothing
 #pragma unroll
@@ -458,7 +494,18 @@ __global__ __launch_bounds__(kRThreads) __attribute__((amdgpu_waves_per_eu(1, 1)
         for (int rr = 0; rr < R; ++rr)
 #pragma unroll
             for (int c = 0; c < NG; ++c) {
-                float scv = h2f(s.sc[rr * NG + c]);
+                if constexpr (FP16W) {
+                    float dsum = 0.0f;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const u32x4_t wv = s.w[(rr * NG + c) * 4 + j];
+                        dsum = dot2(wv.x, xv[0][c][j].x, dsum), dsum = dot2(wv.y, xv[0][c][j].y, dsum);
+                        dsum = dot2(wv.z, xv[0][c][j].z, dsum), dsum = dot2(wv.w, xv[0][c][j].w, dsum);
+                    }
+                    acc[rr] += dsum;
+                    continue;
+                }
+                float scv = h2f(s.sc[FP16W ? 0 : rr * NG + c]);
                 if (c >= kFirstRagged) scv = chunk_on[c] ? scv : 0.0f;
                 if constexpr (NR == 1) {
                     acc[rr] += scv * group_dot_r(s.w[rr * NG + c], xv[0][c], cr[0][c]);
@@ -548,7 +595,7 @@ __global__ __launch_bounds__(kRThreads) __attribute__((amdgpu_waves_per_eu(1, 1)
     }
 }
 
-template <int XMODE, int EPI, int NG>
+template <int XMODE, int EPI, int NG, bool FP16W = false>
 hipError_t launch_ng(const GemvArgs &a_in, hipStream_t stream)
 {
     GemvArgs a = a_in;
@@ -561,7 +608,7 @@ hipError_t launch_ng(const GemvArgs &a_in, hipStream_t stream)
     const int U = (EPI == EPI_SWIGLU || EPI == EPI_ROPE_KV) ? a.m / 2 : (a.m + 1) / 2;
     // rows of x that share a pass over the weights: four where a lane's x is 32 registers per row (k <= 4096), two up to
     // k = 8192, one beyond (the variants that would not fit 256 vector registers are not built)
-    const int nr = (XMODE == X_ATTN_MERGE || a.n < 2 || NG > 4) ? 1 : (a.n >= 3 && NG <= 2 ? 4 : 2);
+    const int nr = (FP16W || XMODE == X_ATTN_MERGE || a.n < 2 || NG > 4) ? 1 : (a.n >= 3 && NG <= 2 ? 4 : 2);
     const int passes = (a.n + nr - 1) / nr;
     // one workgroup per CU, shared between the passes; never fewer than what keeps a wavefront within kRMaxUnits
     int gx = std::max(1, cus / std::min(passes, 8));
@@ -572,6 +619,17 @@ hipError_t launch_ng(const GemvArgs &a_in, hipStream_t stream)
     const bool one = rows_per_slot<NG>(few_rows) == 1;
     a.units_div = U / (gx * kRWaves), a.units_mod = U % (gx * kRWaves);
     const dim3 grid(gx, passes);
+    if constexpr (FP16W) {                                         // a row is four times the bytes: one row per slot throughout
+        if constexpr (kHasPos) {
+            if (a.n == 1 && a.pos0 < 0) {
+                if (a.seqs.dev == nullptr) return hipErrorInvalidValue;
+                hipLaunchKernelGGL((gemv_q4_reg_kernel<XMODE, EPI, NG, 1, true, 1, true>), grid, dim3(kRThreads), 0, stream, a);
+                return hipGetLastError();
+            }
+        }
+        hipLaunchKernelGGL((gemv_q4_reg_kernel<XMODE, EPI, NG, 1, false, 1, true>), grid, dim3(kRThreads), 0, stream, a);
+        return hipGetLastError();
+    }
     if constexpr (kHasPos) {
         if (a.n == 1 && a.pos0 < 0) {                              // position from the device-resident descriptor
             if (a.seqs.dev == nullptr) return hipErrorInvalidValue;
@@ -602,14 +660,14 @@ hipError_t launch_ng(const GemvArgs &a_in, hipStream_t stream)
     return hipGetLastError();
 }
 
-template <int XMODE, int EPI>
+template <int XMODE, int EPI, bool FP16W = false>
 hipError_t launch_xe(const GemvArgs &a, hipStream_t stream)
 {
     const int ng = (a.k + 2047) / 2048;
-    if (ng <= 1) return launch_ng<XMODE, EPI, 1>(a, stream);
-    if (ng == 2) return launch_ng<XMODE, EPI, 2>(a, stream);
-    if (ng <= 4) return launch_ng<XMODE, EPI, 4>(a, stream);
-    return launch_ng<XMODE, EPI, 6>(a, stream);
+    if (ng <= 1) return launch_ng<XMODE, EPI, 1, FP16W>(a, stream);
+    if (ng == 2) return launch_ng<XMODE, EPI, 2, FP16W>(a, stream);
+    if (ng <= 4) return launch_ng<XMODE, EPI, 4, FP16W>(a, stream);
+    return launch_ng<XMODE, EPI, 6, FP16W>(a, stream);
 }
 
 }  // namespace
@@ -647,6 +705,38 @@ hipError_t launch_gemv_reg(const GemvArgs &a, int xmode, int epi, hipStream_t st
     }
     if (xmode == X_F32_NORM && epi == EPI_SWIGLU) return launch_xe<X_F32_NORM, EPI_SWIGLU>(a, stream);
     if (xmode == X_F16 && epi == EPI_RESID_F16) return launch_xe<X_F16, EPI_RESID_F16>(a, stream);
+    return hipErrorInvalidValue;
+}
+
+// fp16 weights (a.wh): the four fused one-row matvecs of the decoder layer
+bool gemv_f16w_eligible(const GemvArgs &a)
+{
+    const int k = a.k;
+    return a.n == 1 && k >= 32 && k <= 6 * 2048 && (k % 8 == 0) && ((reinterpret_cast<uintptr_t>(a.wh) & 15) == 0) &&
+           ((reinterpret_cast<uintptr_t>(a.x) & 15) == 0) && ((reinterpret_cast<uintptr_t>(a.norm_w) & 15) == 0) && a.m >= 2;
+}
+
+bool gemv_f16w_merge_eligible(const GemvArgs &a)
+{
+    return a.n == 1 && a.k <= 2 * 2048 && a.k >= 32 && (a.k % 8 == 0) && a.k == a.h * a.d && (a.d % 8 == 0) && a.part != nullptr &&
+           ((reinterpret_cast<uintptr_t>(a.part) & 15) == 0) && (a.part_stride % 4 == 0) && a.part_stride >= a.d / 2 + 2 &&
+           a.part_splits >= 1 && a.part_splits <= kAttnMergeSplits &&
+           (a.pos0 < 0 ? a.seqs.dev != nullptr : a.part_chunk > 0 && a.pos0 / a.part_chunk < a.part_splits) &&
+           ((reinterpret_cast<uintptr_t>(a.wh) & 15) == 0) && a.m >= 2;
+}
+
+hipError_t launch_gemv_f16w(const GemvArgs &a, int xmode, int epi, hipStream_t stream)
+{
+    if (xmode == X_F16_NORM && epi == EPI_ROPE_KV) return launch_xe<X_F16_NORM, EPI_ROPE_KV, true>(a, stream);
+    if (xmode == X_ATTN_MERGE && epi == EPI_RESID_F32 && gemv_f16w_merge_eligible(a)) {
+        GemvArgs b = a;
+        b.part_used = a.pos0 >= 0 ? a.pos0 / a.part_chunk + 1 : 0;
+        if (a.k <= 2048) return launch_ng<X_ATTN_MERGE, EPI_RESID_F32, 1, true>(b, stream);
+        return launch_ng<X_ATTN_MERGE, EPI_RESID_F32, 2, true>(b, stream);
+    }
+    if (xmode == X_F16 && epi == EPI_RESID_F32) return launch_xe<X_F16, EPI_RESID_F32, true>(a, stream);
+    if (xmode == X_F32_NORM && epi == EPI_SWIGLU) return launch_xe<X_F32_NORM, EPI_SWIGLU, true>(a, stream);
+    if (xmode == X_F16 && epi == EPI_RESID_F16) return launch_xe<X_F16, EPI_RESID_F16, true>(a, stream);
     return hipErrorInvalidValue;
 }
 

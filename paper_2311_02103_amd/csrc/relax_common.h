@@ -297,6 +297,7 @@ struct GemvArgs {
     // matrix
     const uint32_t *q;
     const uint16_t *s;
+    const uint16_t *wh;              // plain fp16 matrix [m,k] instead of (q, s): launch_gemv_f16w only
     int32_t m, k, n;
     int32_t gshift;                  // sub-group (32 columns) index >> gshift = scale index of the row (0: group 32, 1: 64, 2: 128)
     // epilogue
@@ -316,6 +317,10 @@ hipError_t launch_gemv(const GemvArgs &a, int xmode, int epi, hipStream_t stream
 bool gemv_reg_eligible(const GemvArgs &a);
 bool gemv_merge_eligible(const GemvArgs &a);
 hipError_t launch_gemv_reg(const GemvArgs &a, int xmode, int epi, hipStream_t stream);
+// the same kernel on a plain fp16 matrix (a.wh), one row of x: the fused matvecs of the decode layer of an fp16 model
+bool gemv_f16w_eligible(const GemvArgs &a);
+bool gemv_f16w_merge_eligible(const GemvArgs &a);
+hipError_t launch_gemv_f16w(const GemvArgs &a, int xmode, int epi, hipStream_t stream);
 
 // Workgroup size of the row-norm kernels (one workgroup per row, eight elements per thread and pass) and the order in which the
 // per-wavefront sums of squares are added: shared by the stand-alone kernels and the finishing pass that folds the norm in.

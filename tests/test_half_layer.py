@@ -110,3 +110,11 @@ def test_gpu_layer_mid_through_matvec_and_gemm(rx):
     """k = 2048 and 5632: one decode row and a few rows through the matvec passes, 40 and 130 rows through the tiled GEMM."""
     calls = [([40], [40], None), ([1], [41], None), ([3], [44], None), ([130], [174], None), ([1], [175], None)]
     run_schedule(rx, F16_MID, 17, 192, calls)
+
+
+@pytest.mark.gpu
+def test_gpu_layer_7b_shape_decode_rows(rx):
+    """The 7B layer shape (k = 4096 and 11008: the two- and six-chunk variants of the one-row path, attention merge folded
+    into the output projection): a short prefill, then two decode rows."""
+    calls = [([6], [6], None), ([1], [7], None), ([1], [8], None)]
+    run_schedule(rx, wl.LLAMA7B, 19, 64, calls)
