@@ -333,7 +333,9 @@ relax_status relax_dequant_matmul_q3_native(const uint16_t *x, const relax_qmat 
 /* The whole layer on 3-bit weights (Sec. 5.3: the 3-bit models are what the paper deploys where memory is short): the
  * same computation as relax_decoder_layer, same dims, cache, descriptor and x / out conventions, with the four matrices of
  * `weights` in the GPU-native 3-bit layout above (group 0 or 32; their rows within what the 3-bit matmul takes: k % 32 == 0,
- * k <= 12288).  The 3-bit matmuls have the plain fp16 epilogue only, so this layer is a sequence of launches of their own
+ * k <= 12288).  One row (n == 1) runs the five fused launches of the 4-bit decode layer on the 3-bit stream of the same
+ * matrix-vector kernel (norms, rotary + append, attention merge, residuals and SwiGLU inside the four launches, fp32 sums
+ * not rounded in between).  From two rows on the 3-bit matmuls have the plain fp16 epilogue only, so the layer is a sequence of launches of their own
  * -- RMSNorm, matmul, rotary + append, attention, matmul, residual add, RMSNorm, matmul, SwiGLU, matmul, residual add --
  * with the dispatch on n of relax_dequant_matmul_q3_native inside (matrix-vector passes below 16 rows, tiled MFMA GEMM from
  * there on); nothing is fused, a 3-bit matmul output is rounded to fp16 before the residual is added, the residual stream

@@ -889,6 +889,46 @@ relax_status relax_decoder_layer_q3(const relax_layer_dims *dims, const relax_la
     uint16_t *gu = reinterpret_cast<uint16_t *>(base + pl.gu), *tmp = reinterpret_cast<uint16_t *>(base + pl.tmp);
     float *x1 = reinterpret_cast<float *>(base + pl.ws.x1), *partials = reinterpret_cast<float *>(base + pl.ws.partials);
     const size_t nh = (size_t)n * dm.hidden;
+
+    // One row: the five launches of the 4-bit decode layer on the 3-bit stream of the same kernel (the norms, rotary + append,
+    // the attention merge, the residuals and SwiGLU inside the four matrix-vector launches).
+    if (n == 1) {
+        GemvArgs a = {};
+        a.x = x, a.norm_w = wt->norm_attn, a.eps = dm.rms_eps, a.q = wt->wqkv.q, a.s = wt->wqkv.s, a.m = qkvw, a.k = dm.hidden, a.n = 1;
+        a.out_f16 = qkv, a.kcache = cache->k, a.vcache = cache->v, a.rope = cache->rope;
+        a.h = dm.n_heads, a.g = dm.n_kv_heads, a.d = dm.head_dim, a.kv_capacity = dm.kv_capacity, a.seqs = st;
+        if (st.dev == nullptr) a.pos0 = st.kv_len[0] - st.q_len[0] - st.q_start[0], a.slot0 = st.slot[0];
+        else a.pos0 = -1;
+        GemvArgs o = {};
+        o.x = attn, o.q = wt->wo.q, o.s = wt->wo.s, o.m = dm.hidden, o.k = hd, o.n = 1, o.out_f32 = x1, o.resid = x;
+        GemvArgs f = {};
+        f.x = x1, f.norm_w = wt->norm_ffn, f.eps = dm.rms_eps, f.q = wt->wgu.q, f.s = wt->wgu.s, f.m = 2 * dm.ffn, f.k = dm.hidden, f.n = 1;
+        f.out_f16 = act;
+        GemvArgs dn = {};
+        dn.x = act, dn.q = wt->wdown.q, dn.s = wt->wdown.s, dn.m = dm.hidden, dn.k = dm.ffn, dn.n = 1, dn.out_f16 = out, dn.resid = x1;
+        if (gemv_q3w_eligible(a) && gemv_q3w_eligible(o) && gemv_q3w_eligible(f) && gemv_q3w_eligible(dn) && dm.head_dim % 2 == 0) {
+            if (launch_gemv_q3w(a, X_F16_NORM, EPI_ROPE_KV, st_) != hipSuccess) return RELAX_ERR_HIP;
+            bool folded = false;
+            if (attn_mha_split_supported(dm)) {
+                int splits = kAttnMergeSplits, chunk = 0, pos = -1;
+                if (st.dev == nullptr) {
+                    pos = a.pos0;
+                    chunk = attn_fold_chunk(pos + 1, kAttnMergeSplits);
+                    splits = (pos + chunk) / chunk;
+                }
+                o.h = dm.n_heads, o.d = dm.head_dim, o.pos0 = pos, o.seqs = st;
+                o.part = partials, o.part_splits = splits, o.part_stride = dm.head_dim / 2 + 4, o.part_chunk = chunk;
+                folded = (size_t)dm.n_heads * splits * o.part_stride <= attn_partial_floats(dm, 1, 1) && gemv_merge_eligible(o);
+                if (folded && launch_attention_mha_split(qkv, hd, *cache, dm, st, chunk, splits, o.part_stride, partials, st_) != hipSuccess)
+                    return RELAX_ERR_HIP;
+            }
+            if (!folded && launch_attention(qkv, hd, *cache, dm, st, L_max, attn, partials, st_) != hipSuccess) return RELAX_ERR_HIP;
+            if (launch_gemv_q3w(o, folded ? X_ATTN_MERGE : X_F16, EPI_RESID_F32, st_) != hipSuccess) return RELAX_ERR_HIP;
+            if (launch_gemv_q3w(f, X_F32_NORM, EPI_SWIGLU, st_) != hipSuccess) return RELAX_ERR_HIP;
+            if (launch_gemv_q3w(dn, X_F16, EPI_RESID_F16, st_) != hipSuccess) return RELAX_ERR_HIP;
+            return RELAX_OK;
+        }
+    }
     if (launch_rmsnorm(x, wt->norm_attn, xn, n, dm.hidden, dm.rms_eps, st_) != hipSuccess) return RELAX_ERR_HIP;
     if (q3_matmul(xn, wt->wqkv, n, qkv, st_) != hipSuccess) return RELAX_ERR_HIP;
     if (launch_rope_append(qkv, dm, *cache, st, st_) != hipSuccess) return RELAX_ERR_HIP;

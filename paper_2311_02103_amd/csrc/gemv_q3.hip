@@ -142,34 +142,8 @@ __global__ void unpack_q3_kernel(const uint32_t *q, int8_t *out, int m, int k)
 // sum x (u - 4) = A + B / 8 + C / 64 - (1028 sum_A x + 132 sum_B x + 20 sum_C x), the bracket precomputed per group of x.
 // 24 decode ops per group, shared by every row of x in the pass, plus 16 dot products per row of x.
 
-__device__ __forceinline__ uint32_t and_or3(uint32_t w, uint32_t mask, uint32_t bits)
-{
-    uint32_t r;
-    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(w), "s"(mask), "v"(bits));
-    return r;
-}
-
-// class of pair p (0: plain, 1: times 8, 2: times 64); pair 15 (columns 30, 31) is plain
-__host__ __device__ constexpr int q3n_class(int p) { return p == 15 ? 0 : (p % 5 == 2 ? 2 : (p % 5) % 3 == 1 ? 1 : 0); }
-
-// the 16 fp16 pairs of a group in pair order, each (1024 + f u_even, 1024 + f u_odd) with f = 1, 8 or 64 by class
-__device__ __forceinline__ void q3n_decode(uint32_t w0, uint32_t w1, uint32_t w2, uint32_t *pk)
-{
-    const uint32_t base = 0x64006400u;
-    const uint32_t w[3] = {w0, w1, w2};
-#pragma unroll
-    for (int i = 0; i < 3; ++i) {
-        const uint32_t v = w[i], v9 = v >> 9;
-        pk[5 * i + 0] = and_or3(v, 0x00070007u, base);
-        pk[5 * i + 1] = and_or3(v, 0x00380038u, base);
-        pk[5 * i + 2] = and_or3(v, 0x01C001C0u, base);
-        pk[5 * i + 3] = and_or3(v9, 0x00070007u, base);
-        pk[5 * i + 4] = and_or3(v9, 0x00380038u, base);
-    }
-    uint32_t t = and_or3(w0 >> 15, 0x00010001u, base);
-    t = and_or3(w1 >> 14, 0x00020002u, t);
-    pk[15] = and_or3(w2 >> 13, 0x00040004u, t);
-}
+// and_or3, q3n_class and q3n_decode (the decode of a group in this layout) live in relax_common.h: the fused one-row kernel
+// of the decoder layer uses them too.
 
 // one group: canonical words -> native words
 __global__ void repack_q3_kernel(const uint32_t *src, uint32_t *dst, size_t groups)
@@ -369,6 +343,12 @@ static void launch_q3n(const uint16_t *x, const uint32_t *q, const uint16_t *s, 
 
 hipError_t launch_gemv_q3_native(const uint16_t *x, const relax_qmat &w, int n, uint16_t *out, hipStream_t stream)
 {
+    if (n == 1) {                                // one row: the 3-bit stream of the decode layer's matvec kernel (x staged once per
+        GemvArgs a = {};                         // workgroup, one workgroup per CU) is 1 to 1.5 us faster per launch than the kernel below
+        a.x = x, a.q = static_cast<const uint32_t *>(w.q), a.s = static_cast<const uint16_t *>(w.s), a.m = w.m, a.k = w.k, a.n = 1;
+        a.out_f16 = out;
+        if (gemv_q3w_eligible(a)) return launch_gemv_q3w(a, X_F16, EPI_F16, stream);
+    }
     const int G = w.k / 32, J = (G + kWave - 1) / kWave, NR = gemv_q3n_rows_per_pass(w.k, n);
     (void)hipGetLastError();
     static int cus = 0;

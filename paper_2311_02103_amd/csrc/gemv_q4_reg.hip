@@ -186,13 +186,16 @@ constexpr int kRSlots = 2;                // slots in flight (the schedule of th
 // Rows per slot, R.  Small slots shorten what is left to compute after the last byte has arrived and let the
 // arithmetic follow the stream more closely; large ones keep more bytes in flight.  Measured on the 7B layer: two rows
 // for rows of up to 4096 columns (four rows: +3 us per layer; one row: +2.7 us), except when a wavefront owns four
-// rows or fewer (the output projection: one row per slot is 0.6 us faster); one row for long rows, whose lanes keep
-// up to 96 registers of x (with two rows the kernel needed 382 registers and spilled to AGPRs: +1.5 us).
+// rows or fewer (the output projection: one row per slot is 0.6 us faster); one row for rows beyond 4096 columns, whose
+// lanes keep 64 to 96 registers of x: with two rows the six-chunk variant needed 382 registers (+1.5 us), and the four-chunk
+// variant spilled to scratch memory (57344 x 8192 at one row: 166 us against 43.5 us with one row per slot).
 template <int NG>
 constexpr int rows_per_slot(bool few_rows)
 {
-    return NG > 4 ? 1 : (NG <= 2 && few_rows ? 1 : 2);
+    return NG >= 4 ? 1 : (few_rows ? 1 : 2);
 }
+template <int NG>
+constexpr int kMaxRowsPerSlot = NG >= 4 ? 1 : 2;          // what the launcher instantiates
 
 // grid: x = workgroups (at most one per CU and pass), y = pass: NR rows of x that share one pass over the weights (a
 // batch of two to four decode rows: the stream is the same, the dot products of a group are taken once per row on the
@@ -205,11 +208,15 @@ constexpr int rows_per_slot(bool few_rows)
 // row and chunk instead of one load and a scale -- load j of chunk c brings columns 2048 c + 512 j + 8 lane .. + 7, a contiguous
 // kilobyte per instruction -- and nothing to decode: x is staged in plain column order and a load meets its eight x values
 // in four v_dot2_f32_f16.  Columns past the end of a row meet x = 0 (the staging zero-fills), so no lane is masked.
-template <int XMODE, int EPI, int NG, int R, bool DEV = false, int NR = 1, bool FP16W = false>
+// Q3W: the matrix is 3-bit in the GPU-native word layout (Sec. 5.3; gemv_q3.hip describes it): twelve bytes and one scale per
+// lane, row and chunk, x staged in plain column order under the group mapping of the 4-bit stream, the decode of a group
+// (24 vector operations into 16 ready fp16 pairs of three scale classes) ahead of its 16 dot products.
+template <int XMODE, int EPI, int NG, int R, bool DEV = false, int NR = 1, int WM = W_Q4>
 __global__ __launch_bounds__(kRThreads) __attribute__((amdgpu_waves_per_eu(1, 1))) void gemv_q4_reg_kernel(GemvArgs a)
 {
     static_assert(NR == 1 || (XMODE != X_ATTN_MERGE && !DEV), "several rows per pass: plain and normalising prologues, host descriptor");
-    static_assert(!FP16W || NR == 1, "fp16 weights: one row of x per pass");
+    constexpr bool FP16W = WM == W_F16, Q3W = WM == W_Q3;
+    static_assert(WM == W_Q4 || NR == 1, "fp16 and 3-bit weights: one row of x per pass");
     constexpr int LW = FP16W ? 4 : 1;                              // 16-byte loads per lane, row and chunk
     constexpr int NSLOT = kRSlots, E = R * NG;
     constexpr int kResPitch = NR * (kRMaxUnits * 2 + 4);
@@ -333,6 +340,18 @@ __global__ __launch_bounds__(kRThreads) __attribute__((amdgpu_waves_per_eu(1, 1)
                         const int pc = (c >= kFirstRagged) ? min(pk, kw - 1) : pk;
                         s.w[(rr * NG + c) * 4 + j] = stream_load((const u32x4_t *)(wrow + (size_t)pc * 8));
                     }
+            } else if constexpr (Q3W) {
+                const uint32_t *qrow = a.q + (size_t)row * G * 3;
+                const uint16_t *srow = a.s + (size_t)row * G;
+#pragma unroll
+                for (int c = 0; c < NG; ++c) {
+                    const int gi = (c >= kFirstRagged) ? min(c * 64 + lane, G - 1) : c * 64 + lane;
+                    const uint32_t *p3 = qrow + gi * 3;              // consecutive lanes read consecutive 12-byte groups
+                    u32x4_t w3 = {0u, 0u, 0u, 0u};
+                    w3.x = stream_load(p3), w3.y = stream_load(p3 + 1), w3.z = stream_load(p3 + 2);
+                    s.w[rr * NG + c] = w3;
+                    s.sc[rr * NG + c] = srow[gi];
+                }
             } else {
             const uint32_t *qrow = a.q + (size_t)row * kw;
             const uint16_t *srow = a.s + (size_t)row * SG;
@@ -407,7 +426,7 @@ __global__ __launch_bounds__(kRThreads) __attribute__((amdgpu_waves_per_eu(1, 1)
                 const uint32_t ww = wnr[p][e >> 1];
                 y[e] = f2h(xf[xr][p][e] * inv[xr] * h2f((uint16_t)((e & 1) ? (ww >> 16) : (ww & 0xFFFFu))));
             }
-            if (FP16W) {
+            if (WM != W_Q4) {
                 o.x = (uint32_t)y[0] | ((uint32_t)y[1] << 16), o.y = (uint32_t)y[2] | ((uint32_t)y[3] << 16);
                 o.z = (uint32_t)y[4] | ((uint32_t)y[5] << 16), o.w = (uint32_t)y[6] | ((uint32_t)y[7] << 16);
             } else {
@@ -440,7 +459,7 @@ __global__ __launch_bounds__(kRThreads) __attribute__((amdgpu_waves_per_eu(1, 1)
             uint16_t y[8];
 #pragma unroll
             for (int e = 0; e < 8; ++e) y[e] = f2h(num[e] * rden);
-            if (FP16W) {
+            if (WM != W_Q4) {
                 o.x = (uint32_t)y[0] | ((uint32_t)y[1] << 16), o.y = (uint32_t)y[2] | ((uint32_t)y[3] << 16);
                 o.z = (uint32_t)y[4] | ((uint32_t)y[5] << 16), o.w = (uint32_t)y[6] | ((uint32_t)y[7] << 16);
             } else {
@@ -450,7 +469,7 @@ __global__ __launch_bounds__(kRThreads) __attribute__((amdgpu_waves_per_eu(1, 1)
         } else {
             const bool on = (p * kRThreads + tid) < kw;
             const u32x4_t r = xraw[xr][p];
-            if (FP16W) {
+            if (WM != W_Q4) {
                 o = r;
             } else {
                 o.x = __builtin_amdgcn_perm(r.z, r.x, 0x05040100u), o.y = __builtin_amdgcn_perm(r.z, r.x, 0x07060302u);
@@ -479,6 +498,17 @@ __global__ __launch_bounds__(kRThreads) __attribute__((amdgpu_waves_per_eu(1, 1)
             sa = dot2(xv[xr][c][j].z, 0x3C003C00u, sa), sb = dot2(xv[xr][c][j].w, 0x3C003C00u, sb);
         }
         cr[xr][c] = FP16W ? 0.0f : 1032.0f * sa + 72.0f * sb;
+        if constexpr (Q3W) {                                       // pair p = 4 j + word of the packet; its scale class as in the decode
+            float sc3[3] = {0.0f, 0.0f, 0.0f};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                sc3[q3n_class(4 * j)] = dot2(0x3C003C00u, xv[xr][c][j].x, sc3[q3n_class(4 * j)]);
+                sc3[q3n_class(4 * j + 1)] = dot2(0x3C003C00u, xv[xr][c][j].y, sc3[q3n_class(4 * j + 1)]);
+                sc3[q3n_class(4 * j + 2)] = dot2(0x3C003C00u, xv[xr][c][j].z, sc3[q3n_class(4 * j + 2)]);
+                sc3[q3n_class(4 * j + 3)] = dot2(0x3C003C00u, xv[xr][c][j].w, sc3[q3n_class(4 * j + 3)]);
+            }
+            cr[xr][c] = 1028.0f * sc3[0] + 132.0f * sc3[1] + 20.0f * sc3[2];
+        }
     }
     bool chunk_on[NG];                                             // lanes past the last group of the row contribute nothing
 #pragma unroll
@@ -507,6 +537,21 @@ __global__ __launch_bounds__(kRThreads) __attribute__((amdgpu_waves_per_eu(1, 1)
                 }
                 float scv = h2f(s.sc[FP16W ? 0 : rr * NG + c]);
                 if (c >= kFirstRagged) scv = chunk_on[c] ? scv : 0.0f;
+                if constexpr (Q3W) {
+                    uint32_t pk[16];
+                    const u32x4_t w3 = s.w[rr * NG + c];
+                    q3n_decode(w3.x, w3.y, w3.z, pk);
+                    float a3[3] = {0.0f, 0.0f, 0.0f};
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        a3[q3n_class(4 * j)] = dot2(pk[4 * j], xv[0][c][j].x, a3[q3n_class(4 * j)]);
+                        a3[q3n_class(4 * j + 1)] = dot2(pk[4 * j + 1], xv[0][c][j].y, a3[q3n_class(4 * j + 1)]);
+                        a3[q3n_class(4 * j + 2)] = dot2(pk[4 * j + 2], xv[0][c][j].z, a3[q3n_class(4 * j + 2)]);
+                        a3[q3n_class(4 * j + 3)] = dot2(pk[4 * j + 3], xv[0][c][j].w, a3[q3n_class(4 * j + 3)]);
+                    }
+                    acc[rr] += scv * (a3[0] + a3[1] * 0.125f + a3[2] * 0.015625f - cr[0][c]);
+                    continue;
+                }
                 if constexpr (NR == 1) {
                     acc[rr] += scv * group_dot_r(s.w[rr * NG + c], xv[0][c], cr[0][c]);
                 } else {
@@ -595,7 +640,7 @@ __global__ __launch_bounds__(kRThreads) __attribute__((amdgpu_waves_per_eu(1, 1)
     }
 }
 
-template <int XMODE, int EPI, int NG, bool FP16W = false>
+template <int XMODE, int EPI, int NG, int WM = W_Q4>
 hipError_t launch_ng(const GemvArgs &a_in, hipStream_t stream)
 {
     GemvArgs a = a_in;
@@ -608,7 +653,7 @@ hipError_t launch_ng(const GemvArgs &a_in, hipStream_t stream)
     const int U = (EPI == EPI_SWIGLU || EPI == EPI_ROPE_KV) ? a.m / 2 : (a.m + 1) / 2;
     // rows of x that share a pass over the weights: four where a lane's x is 32 registers per row (k <= 4096), two up to
     // k = 8192, one beyond (the variants that would not fit 256 vector registers are not built)
-    const int nr = (FP16W || XMODE == X_ATTN_MERGE || a.n < 2 || NG > 4) ? 1 : (a.n >= 3 && NG <= 2 ? 4 : 2);
+    const int nr = (WM != W_Q4 || XMODE == X_ATTN_MERGE || a.n < 2 || NG > 4) ? 1 : (a.n >= 3 && NG <= 2 ? 4 : 2);
     const int passes = (a.n + nr - 1) / nr;
     // one workgroup per CU, shared between the passes; never fewer than what keeps a wavefront within kRMaxUnits
     int gx = std::max(1, cus / std::min(passes, 8));
@@ -619,22 +664,35 @@ hipError_t launch_ng(const GemvArgs &a_in, hipStream_t stream)
     const bool one = rows_per_slot<NG>(few_rows) == 1;
     a.units_div = U / (gx * kRWaves), a.units_mod = U % (gx * kRWaves);
     const dim3 grid(gx, passes);
-    if constexpr (FP16W) {                                         // a row is four times the bytes: one row per slot throughout
+    if constexpr (WM == W_F16) {                                   // a row is four times the bytes: one row per slot throughout
         if constexpr (kHasPos) {
             if (a.n == 1 && a.pos0 < 0) {
                 if (a.seqs.dev == nullptr) return hipErrorInvalidValue;
-                hipLaunchKernelGGL((gemv_q4_reg_kernel<XMODE, EPI, NG, 1, true, 1, true>), grid, dim3(kRThreads), 0, stream, a);
+                hipLaunchKernelGGL((gemv_q4_reg_kernel<XMODE, EPI, NG, 1, true, 1, W_F16>), grid, dim3(kRThreads), 0, stream, a);
                 return hipGetLastError();
             }
         }
-        hipLaunchKernelGGL((gemv_q4_reg_kernel<XMODE, EPI, NG, 1, false, 1, true>), grid, dim3(kRThreads), 0, stream, a);
+        hipLaunchKernelGGL((gemv_q4_reg_kernel<XMODE, EPI, NG, 1, false, 1, W_F16>), grid, dim3(kRThreads), 0, stream, a);
+        return hipGetLastError();
+    }
+    if constexpr (WM == W_Q3) {                                    // rows per slot as on the 4-bit stream
+        if constexpr (kHasPos) {
+            if (a.n == 1 && a.pos0 < 0) {
+                if (a.seqs.dev == nullptr) return hipErrorInvalidValue;
+                if (one) hipLaunchKernelGGL((gemv_q4_reg_kernel<XMODE, EPI, NG, 1, true, 1, W_Q3>), grid, dim3(kRThreads), 0, stream, a);
+                else hipLaunchKernelGGL((gemv_q4_reg_kernel<XMODE, EPI, NG, kMaxRowsPerSlot<NG>, true, 1, W_Q3>), grid, dim3(kRThreads), 0, stream, a);
+                return hipGetLastError();
+            }
+        }
+        if (one) hipLaunchKernelGGL((gemv_q4_reg_kernel<XMODE, EPI, NG, 1, false, 1, W_Q3>), grid, dim3(kRThreads), 0, stream, a);
+        else hipLaunchKernelGGL((gemv_q4_reg_kernel<XMODE, EPI, NG, kMaxRowsPerSlot<NG>, false, 1, W_Q3>), grid, dim3(kRThreads), 0, stream, a);
         return hipGetLastError();
     }
     if constexpr (kHasPos) {
         if (a.n == 1 && a.pos0 < 0) {                              // position from the device-resident descriptor
             if (a.seqs.dev == nullptr) return hipErrorInvalidValue;
             if (one) hipLaunchKernelGGL((gemv_q4_reg_kernel<XMODE, EPI, NG, 1, true>), grid, dim3(kRThreads), 0, stream, a);
-            else hipLaunchKernelGGL((gemv_q4_reg_kernel<XMODE, EPI, NG, 2, true>), grid, dim3(kRThreads), 0, stream, a);
+            else hipLaunchKernelGGL((gemv_q4_reg_kernel<XMODE, EPI, NG, kMaxRowsPerSlot<NG>, true>), grid, dim3(kRThreads), 0, stream, a);
             return hipGetLastError();
         }
     }
@@ -645,7 +703,7 @@ hipError_t launch_ng(const GemvArgs &a_in, hipStream_t stream)
         }
         if (nr == 2) {
             if (one) hipLaunchKernelGGL((gemv_q4_reg_kernel<XMODE, EPI, NG, 1, false, 2>), grid, dim3(kRThreads), 0, stream, a);
-            else hipLaunchKernelGGL((gemv_q4_reg_kernel<XMODE, EPI, NG, 2, false, 2>), grid, dim3(kRThreads), 0, stream, a);
+            else hipLaunchKernelGGL((gemv_q4_reg_kernel<XMODE, EPI, NG, kMaxRowsPerSlot<NG>, false, 2>), grid, dim3(kRThreads), 0, stream, a);
             return hipGetLastError();
         }
     }
@@ -656,18 +714,18 @@ hipError_t launch_ng(const GemvArgs &a_in, hipStream_t stream)
         }
     }
     if (one) hipLaunchKernelGGL((gemv_q4_reg_kernel<XMODE, EPI, NG, 1>), grid, dim3(kRThreads), 0, stream, a);
-    else hipLaunchKernelGGL((gemv_q4_reg_kernel<XMODE, EPI, NG, 2>), grid, dim3(kRThreads), 0, stream, a);
+    else hipLaunchKernelGGL((gemv_q4_reg_kernel<XMODE, EPI, NG, kMaxRowsPerSlot<NG>>), grid, dim3(kRThreads), 0, stream, a);
     return hipGetLastError();
 }
 
-template <int XMODE, int EPI, bool FP16W = false>
+template <int XMODE, int EPI, int WM = W_Q4>
 hipError_t launch_xe(const GemvArgs &a, hipStream_t stream)
 {
     const int ng = (a.k + 2047) / 2048;
-    if (ng <= 1) return launch_ng<XMODE, EPI, 1, FP16W>(a, stream);
-    if (ng == 2) return launch_ng<XMODE, EPI, 2, FP16W>(a, stream);
-    if (ng <= 4) return launch_ng<XMODE, EPI, 4, FP16W>(a, stream);
-    return launch_ng<XMODE, EPI, 6, FP16W>(a, stream);
+    if (ng <= 1) return launch_ng<XMODE, EPI, 1, WM>(a, stream);
+    if (ng == 2) return launch_ng<XMODE, EPI, 2, WM>(a, stream);
+    if (ng <= 4) return launch_ng<XMODE, EPI, 4, WM>(a, stream);
+    return launch_ng<XMODE, EPI, 6, WM>(a, stream);
 }
 
 }  // namespace
@@ -727,16 +785,40 @@ bool gemv_f16w_merge_eligible(const GemvArgs &a)
 
 hipError_t launch_gemv_f16w(const GemvArgs &a, int xmode, int epi, hipStream_t stream)
 {
-    if (xmode == X_F16_NORM && epi == EPI_ROPE_KV) return launch_xe<X_F16_NORM, EPI_ROPE_KV, true>(a, stream);
+    if (xmode == X_F16_NORM && epi == EPI_ROPE_KV) return launch_xe<X_F16_NORM, EPI_ROPE_KV, W_F16>(a, stream);
     if (xmode == X_ATTN_MERGE && epi == EPI_RESID_F32 && gemv_f16w_merge_eligible(a)) {
         GemvArgs b = a;
         b.part_used = a.pos0 >= 0 ? a.pos0 / a.part_chunk + 1 : 0;
-        if (a.k <= 2048) return launch_ng<X_ATTN_MERGE, EPI_RESID_F32, 1, true>(b, stream);
-        return launch_ng<X_ATTN_MERGE, EPI_RESID_F32, 2, true>(b, stream);
+        if (a.k <= 2048) return launch_ng<X_ATTN_MERGE, EPI_RESID_F32, 1, W_F16>(b, stream);
+        return launch_ng<X_ATTN_MERGE, EPI_RESID_F32, 2, W_F16>(b, stream);
     }
-    if (xmode == X_F16 && epi == EPI_RESID_F32) return launch_xe<X_F16, EPI_RESID_F32, true>(a, stream);
-    if (xmode == X_F32_NORM && epi == EPI_SWIGLU) return launch_xe<X_F32_NORM, EPI_SWIGLU, true>(a, stream);
-    if (xmode == X_F16 && epi == EPI_RESID_F16) return launch_xe<X_F16, EPI_RESID_F16, true>(a, stream);
+    if (xmode == X_F16 && epi == EPI_RESID_F32) return launch_xe<X_F16, EPI_RESID_F32, W_F16>(a, stream);
+    if (xmode == X_F32_NORM && epi == EPI_SWIGLU) return launch_xe<X_F32_NORM, EPI_SWIGLU, W_F16>(a, stream);
+    if (xmode == X_F16 && epi == EPI_RESID_F16) return launch_xe<X_F16, EPI_RESID_F16, W_F16>(a, stream);
+    return hipErrorInvalidValue;
+}
+
+// 3-bit weights in the native word layout (a.q, a.s; group 32): the same four launches for one row of x
+bool gemv_q3w_eligible(const GemvArgs &a)
+{
+    const int k = a.k;
+    return a.n == 1 && k >= 32 && k <= 6 * 2048 && (k % 32 == 0) && ((reinterpret_cast<uintptr_t>(a.q) & 3) == 0) &&
+           ((reinterpret_cast<uintptr_t>(a.x) & 15) == 0) && ((reinterpret_cast<uintptr_t>(a.norm_w) & 15) == 0) && a.m >= 2;
+}
+
+hipError_t launch_gemv_q3w(const GemvArgs &a, int xmode, int epi, hipStream_t stream)
+{
+    if (xmode == X_F16 && epi == EPI_F16) return launch_xe<X_F16, EPI_F16, W_Q3>(a, stream);
+    if (xmode == X_F16_NORM && epi == EPI_ROPE_KV) return launch_xe<X_F16_NORM, EPI_ROPE_KV, W_Q3>(a, stream);
+    if (xmode == X_ATTN_MERGE && epi == EPI_RESID_F32 && gemv_merge_eligible(a)) {
+        GemvArgs b = a;
+        b.part_used = a.pos0 >= 0 ? a.pos0 / a.part_chunk + 1 : 0;
+        if (a.k <= 2048) return launch_ng<X_ATTN_MERGE, EPI_RESID_F32, 1, W_Q3>(b, stream);
+        return launch_ng<X_ATTN_MERGE, EPI_RESID_F32, 2, W_Q3>(b, stream);
+    }
+    if (xmode == X_F16 && epi == EPI_RESID_F32) return launch_xe<X_F16, EPI_RESID_F32, W_Q3>(a, stream);
+    if (xmode == X_F32_NORM && epi == EPI_SWIGLU) return launch_xe<X_F32_NORM, EPI_SWIGLU, W_Q3>(a, stream);
+    if (xmode == X_F16 && epi == EPI_RESID_F16) return launch_xe<X_F16, EPI_RESID_F16, W_Q3>(a, stream);
     return hipErrorInvalidValue;
 }
 

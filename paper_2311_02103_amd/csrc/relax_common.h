@@ -312,6 +312,39 @@ struct GemvArgs {
     int32_t pos0, slot0;             // position and cache slot of row 0, resolved on the host (what a one-row call needs of seqs)
 };
 
+// ---- native 3-bit word layout (gemv_q3.hip describes it): the decode of one group, shared by the kernels that stream it ----
+__device__ __forceinline__ uint32_t and_or3(uint32_t w, uint32_t mask, uint32_t bits)
+{
+    uint32_t r;
+    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(w), "s"(mask), "v"(bits));
+    return r;
+}
+// class of pair p (0: plain, 1: times 8, 2: times 64); pair 15 (columns 30, 31) is plain
+__host__ __device__ constexpr int q3n_class(int p) { return p == 15 ? 0 : (p % 5 == 2 ? 2 : (p % 5) % 3 == 1 ? 1 : 0); }
+
+// the 16 fp16 pairs of a group in pair order, each (1024 + f u_even, 1024 + f u_odd) with f = 1, 8 or 64 by class
+__device__ __forceinline__ void q3n_decode(uint32_t w0, uint32_t w1, uint32_t w2, uint32_t *pk)
+{
+    const uint32_t base = 0x64006400u;
+    const uint32_t w[3] = {w0, w1, w2};
+#pragma unroll
+    for (int i = 0; i < 3; ++i) {
+        const uint32_t v = w[i], v9 = v >> 9;
+        pk[5 * i + 0] = and_or3(v, 0x00070007u, base);
+        pk[5 * i + 1] = and_or3(v, 0x00380038u, base);
+        pk[5 * i + 2] = and_or3(v, 0x01C001C0u, base);
+        pk[5 * i + 3] = and_or3(v9, 0x00070007u, base);
+        pk[5 * i + 4] = and_or3(v9, 0x00380038u, base);
+    }
+    uint32_t t = and_or3(w0 >> 15, 0x00010001u, base);
+    t = and_or3(w1 >> 14, 0x00020002u, t);
+    pk[15] = and_or3(w2 >> 13, 0x00040004u, t);
+}
+
+
+// weight stream of the register-resident matvec kernel (gemv_q4_reg.hip)
+enum { W_Q4 = 0, W_F16 = 1, W_Q3 = 2 };
+
 hipError_t launch_gemv(const GemvArgs &a, int xmode, int epi, hipStream_t stream);
 // x-in-registers variant for rows of up to 6 x 2048 columns (gemv_q4_reg.hip); launch_gemv picks it when eligible
 bool gemv_reg_eligible(const GemvArgs &a);
@@ -321,6 +354,9 @@ hipError_t launch_gemv_reg(const GemvArgs &a, int xmode, int epi, hipStream_t st
 bool gemv_f16w_eligible(const GemvArgs &a);
 bool gemv_f16w_merge_eligible(const GemvArgs &a);
 hipError_t launch_gemv_f16w(const GemvArgs &a, int xmode, int epi, hipStream_t stream);
+// ... and on 3-bit weights in the native word layout (a.q, a.s with group 32)
+bool gemv_q3w_eligible(const GemvArgs &a);
+hipError_t launch_gemv_q3w(const GemvArgs &a, int xmode, int epi, hipStream_t stream);
 
 // Workgroup size of the row-norm kernels (one workgroup per row, eight elements per thread and pass) and the order in which the
 // per-wavefront sums of squares are added: shared by the stand-alone kernels and the finishing pass that folds the norm in.
