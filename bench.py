@@ -70,7 +70,7 @@ def emit(args, metric, unit, value, ms_per_step, dtype, config, roofline, cpu, e
 
 
 # ------------------------------------------------------------------------------------------------ the other two parts of the metric
-def measure_prefill(np, torch, wl, rx, host_w, n=2048, calls=10):
+def measure_prefill(np, torch, wl, rx, host_w, n=2048, calls=30):
     """configs[2] at n rows, short: ms per layer call and the MFMA rate of its GEMMs (HIP events around each step)."""
     from paper_2311_02103_amd.runtime import DeviceLayer, to_device
     shape = wl.LLAMA7B
@@ -80,7 +80,7 @@ def measure_prefill(np, torch, wl, rx, host_w, n=2048, calls=10):
     out = torch.empty_like(x)
     stream = torch.cuda.Stream()
     call = layer.prepare(x, [n], [n], out=out)
-    for _ in range(3):
+    for _ in range(10):                      # as the prefill_layer workload: ten untimed calls first
         call(stream.cuda_stream)
     stream.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)

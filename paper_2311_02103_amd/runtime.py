@@ -176,12 +176,16 @@ class DeviceLayerQ3:
         self.v = torch.zeros(shape, dtype=torch.float16, device=device)
         self.cache = rx.KVCache(self.k, self.v, self.rope)
 
+    def load_cache(self, k_bits: np.ndarray, v_bits: np.ndarray) -> None:
+        self.k.copy_(to_device(k_bits, self.device).view(self.k.shape))
+        self.v.copy_(to_device(v_bits, self.device).view(self.v.shape))
+
     def forward(self, x: torch.Tensor, q_lens: Sequence[int], kv_lens: Sequence[int], slots=None,
-                out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+                out: Optional[torch.Tensor] = None, device_table: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
         n = x.shape[0]
         if out is None:
             out = torch.empty_like(x)
-        seqs = rx.Seqs(q_lens, kv_lens, slots, None)
+        seqs = rx.Seqs(q_lens, kv_lens, slots, device_table)
         rx.check(rx.relax_decoder_layer_q3(self.dims, self.weights, x, self.cache, seqs, out, n, self.ws, self.ws_bytes, stream),
                  "relax_decoder_layer_q3")
         return out
@@ -209,12 +213,16 @@ class DeviceLayerF16:
         self.v = torch.zeros(shape, dtype=torch.float16, device=device)
         self.cache = rx.KVCache(self.k, self.v, self.rope)
 
+    def load_cache(self, k_bits: np.ndarray, v_bits: np.ndarray) -> None:
+        self.k.copy_(to_device(k_bits, self.device).view(self.k.shape))
+        self.v.copy_(to_device(v_bits, self.device).view(self.v.shape))
+
     def forward(self, x: torch.Tensor, q_lens: Sequence[int], kv_lens: Sequence[int], slots=None,
-                out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+                out: Optional[torch.Tensor] = None, device_table: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
         n = x.shape[0]
         if out is None:
             out = torch.empty_like(x)
-        seqs = rx.Seqs(q_lens, kv_lens, slots, None)
+        seqs = rx.Seqs(q_lens, kv_lens, slots, device_table)
         rx.check(rx.relax_decoder_layer_f16(self.dims, self.weights, x, self.cache, seqs, out, n, self.ws, self.ws_bytes, stream),
                  "relax_decoder_layer_f16")
         return out

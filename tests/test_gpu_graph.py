@@ -182,3 +182,41 @@ def test_capture_of_a_call_with_more_than_sixteen_sequences_and_host_descriptors
         torch.cuda.synchronize()
         assert torch.equal(bits(out), bits(want)), "replay %d: output differs from the eager call" % rep
         assert torch.equal(bits(layer.k), bits(want_k)), "replay %d: K cache differs" % rep
+
+
+MID = wl.LayerShape("table-mid", hidden=2048, n_heads=16, n_kv_heads=16, head_dim=128, ffn=5632)
+
+
+def half_weights(shape, seed):
+    w = {}
+    for j, (name, (m, k)) in enumerate(shape.matrices().items()):
+        w[name] = (wl.normal_f32(seed, 40 + j, (m, k)) * np.float32(0.02)).astype(np.float16).view(np.uint16)
+    for j, name in enumerate(("norm_attn", "norm_ffn")):
+        w[name] = wl.normal_f16_bits(seed, 50 + j, (shape.hidden,), std=0.1, mean=1.0)
+    return w
+
+
+@pytest.mark.parametrize("kind", ["q3", "f16"])
+@pytest.mark.parametrize("L", [1, 63, 300, 512])
+def test_single_row_of_the_3bit_and_fp16_layers_reads_its_position_from_the_device_table(rx, kind, L):
+    """The fused one-row path of the layers on 3-bit and on fp16 weights: with the device table the kernels read the position
+    and plan the attention splits on the device; output and appended cache rows equal the host-descriptor call bit for bit."""
+    from paper_2311_02103_amd.runtime import DeviceLayerF16, DeviceLayerQ3
+    shape, cap = MID, 512
+    kw = dict(hidden=shape.hidden, n_heads=shape.n_heads, n_kv_heads=shape.n_kv_heads, head_dim=shape.head_dim, ffn=shape.ffn,
+              kv_capacity=cap, kv_slots=1, n_max=1, B_max=1)
+    layer = DeviceLayerQ3(wl.layer_weights3(shape, 37), **kw) if kind == "q3" else DeviceLayerF16(half_weights(shape, 37), **kw)
+    kb, vb = wl.kv_prefill(shape, 37, 1, cap)
+    x = torch.from_numpy(wl.activations(shape, 37, L, 1).view(np.int16)).view(torch.float16).cuda()
+    res = []
+    for dev in (False, True):
+        layer.load_cache(kb, vb)
+        if dev:
+            out = layer.forward(x, [1], [cap], None, device_table=table([1], [L], [0]))
+        else:
+            out = layer.forward(x, [1], [L], None)
+        torch.cuda.synchronize()
+        res.append((out.clone(), layer.k[0, L - 1].clone(), layer.v[0, L - 1].clone()))
+    for name, a, b in zip(("out", "K row", "V row"), res[0], res[1]):
+        assert torch.equal(bits(a), bits(b)), "%s differs at L=%d (%s)" % (name, L, kind)
+    assert torch.isfinite(res[0][0].float()).all() and float(res[0][0].float().abs().max()) > 0

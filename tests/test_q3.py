@@ -353,3 +353,11 @@ def test_host_checks_of_the_q3_layer():
     assert rx.relax_layer_q3_workspace_bytes(dims, 0, 32, 2) == 0
     assert rx.relax_layer_q3_workspace_bytes(dims, 16, 32, 2) > rx.relax_layer_q3_workspace_bytes(dims, 8, 32, 2)
     assert rx.relax_decoder_layer_q3(dims, None, 64, None, None, 64, 1, 256, 1 << 20) == rx.ERR_NULL
+
+
+@pytest.mark.gpu
+def test_gpu_q3_layer_7b_shape_decode_rows(rx):
+    """The 7B layer shape (k = 4096 and 11008: the two- and six-chunk variants of the fused one-row path, attention merge
+    folded into the output projection): a short prefill, then two decode rows."""
+    calls = [([6], [6], None), ([1], [7], None), ([1], [8], None)]
+    run_q3_schedule(rx, wl.LLAMA7B, 19, 64, calls)
