@@ -26,7 +26,8 @@ def sources():
 # Sources whose kernels stream from HBM with their working set in registers: a variant that the register allocator
 # spills to scratch memory still computes the right values, several times slower (measured: 4 x on a one-row matvec), so
 # the build refuses it.  {source: substring of the mangled kernel names it applies to}
-NO_SCRATCH = {"gemv_q4_reg.hip": "gemv_q4_reg_kernel", "gemv_q3.hip": "gemv_q3", "attn_decode.hip": "attn_"}
+NO_SCRATCH = {"gemv_q4_reg.hip": "gemv_q4_reg_kernel", "gemv_reg_f16.hip": "gemv_q4_reg_kernel", "gemv_reg_q3.hip": "gemv_q4_reg_kernel",
+              "gemv_q3.hip": "gemv_q3", "attn_decode.hip": "attn_"}
 REMARK = "-Rpass-analysis=kernel-resource-usage"
 
 
@@ -54,7 +55,7 @@ def _compile(src: str) -> str:
         bad = scratch_users(res.stderr, NO_SCRATCH[src])
         if bad:
             raise RuntimeError("%s: kernels that spill to scratch memory: %s" % (src, ", ".join("%s (%d B/lane)" % b for b in bad)))
-        res.stderr = "\n".join(l for l in res.stderr.splitlines() if REMARK not in l and not l.lstrip().startswith(("|", "^")) and
+        res.stderr = "\n".join(l for l in res.stderr.splitlines() if REMARK not in l and not l.lstrip().startswith(("|", "^", "In file included from")) and
                                not (l.strip()[:1].isdigit() and "|" in l))
     warn = "\n".join(l for l in res.stderr.splitlines() if "packed-fp32-ops" not in l and l.strip())
     if warn:

@@ -295,9 +295,11 @@ struct GemvArgs {
     const uint16_t *norm_w;          // [k] fp16, norm modes only
     float eps;
     // matrix
-    const uint32_t *q;
+    union {                          // (the size and the offsets of this block are part of the tuning: one more pointer ahead of
+        const uint32_t *q;           // the matrix fields cost the one-row layer 0.3 us per step)
+        const uint16_t *wh;          // plain fp16 matrix [m,k] instead of (q, s): launch_gemv_f16w only
+    };
     const uint16_t *s;
-    const uint16_t *wh;              // plain fp16 matrix [m,k] instead of (q, s): launch_gemv_f16w only
     int32_t m, k, n;
     int32_t gshift;                  // sub-group (32 columns) index >> gshift = scale index of the row (0: group 32, 1: 64, 2: 128)
     // epilogue
