@@ -26,7 +26,7 @@ def sources():
 # Sources whose kernels stream from HBM with their working set in registers: a variant that the register allocator
 # spills to scratch memory still computes the right values, several times slower (measured: 4 x on a one-row matvec), so
 # the build refuses it.  {source: substring of the mangled kernel names it applies to}
-NO_SCRATCH = {"gemv_q4_reg.hip": "gemv_q4_reg_kernel", "gemv_reg_f16.hip": "gemv_q4_reg_kernel", "gemv_reg_q3.hip": "gemv_q4_reg_kernel",
+NO_SCRATCH = {"gemv_q4_reg.hip": "gemv_q4_reg_kernel", "gemv_reg_f16.hip": "gemv_q4_reg_kernel", "gemv_reg_q3.hip": "gemv_q4_reg_kernel", "gemv_q4_long.hip": "gemv_q4_long_kernel",
               "gemv_q3.hip": "gemv_q3", "attn_decode.hip": "attn_"}
 REMARK = "-Rpass-analysis=kernel-resource-usage"
 

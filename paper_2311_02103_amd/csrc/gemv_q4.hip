@@ -442,6 +442,7 @@ template <int XMODE, int EPI>
 static hipError_t launch_t(const GemvArgs &a, hipStream_t stream)
 {
     if (gemv_reg_eligible(a)) return launch_gemv_reg(a, XMODE, EPI, stream);
+    if (gemv_long_eligible(a, XMODE, EPI)) return launch_gemv_long(a, EPI, stream);     // rows of 12289 .. 32768 columns, plain prologue
     const int k = a.k, G = groups_of(k);
     const bool fast = (k % kGroup == 0) && ((k / 8) % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.q) & 15) == 0) &&
                       ((reinterpret_cast<uintptr_t>(a.x) & 15) == 0) && ((reinterpret_cast<uintptr_t>(a.norm_w) & 15) == 0);

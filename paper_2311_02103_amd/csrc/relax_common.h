@@ -352,6 +352,9 @@ hipError_t launch_gemv(const GemvArgs &a, int xmode, int epi, hipStream_t stream
 bool gemv_reg_eligible(const GemvArgs &a);
 bool gemv_merge_eligible(const GemvArgs &a);
 hipError_t launch_gemv_reg(const GemvArgs &a, int xmode, int epi, hipStream_t stream);
+// rows of 12289 .. 32768 columns split over the four wavefronts of a workgroup (gemv_q4_long.hip): plain prologue, row-pair epilogues
+bool gemv_long_eligible(const GemvArgs &a, int xmode, int epi);
+hipError_t launch_gemv_long(const GemvArgs &a, int epi, hipStream_t stream);
 // the same kernel on a plain fp16 matrix (a.wh), one row of x: the fused matvecs of the decode layer of an fp16 model
 bool gemv_f16w_eligible(const GemvArgs &a);
 bool gemv_f16w_merge_eligible(const GemvArgs &a);

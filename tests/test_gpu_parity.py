@@ -85,7 +85,8 @@ def test_selector_matrix_bitwise(rx, m, k, n):
     assert np.abs(got - ref).max() <= 4e-3          # scale 1.0 here: ~150x the scale of real weights
 
 
-@pytest.mark.parametrize("m,k,n", [(33, 688, 5), (64, 4096, 2), (31, 2048, 1), (16, 11008, 1)])
+@pytest.mark.parametrize("m,k,n", [(33, 688, 5), (64, 4096, 2), (31, 2048, 1), (16, 11008, 1),
+                                   (70, 28672, 1), (19, 14336, 1)])       # rows split over the wavefronts of a workgroup
 def test_integer_valued_matmul_bitwise(rx, m, k, n):
     r = np.random.RandomState(k + m)
     codes = r.randint(0, 16, size=(m, k)).astype(np.uint8)
@@ -107,7 +108,10 @@ def test_integer_valued_matmul_bitwise(rx, m, k, n):
                                    (1024, 4096, 1), (515, 4096, 17), (640, 11008, 1), (96, 11008, 3), (9, 8192, 2),
                                    (2, 28672, 1), (1, 64, 1),
                                    # rows that end in the first / second-to-last chunk of 2048 columns of the register-resident matvec
-                                   (131, 2080, 1), (200, 4192, 1), (64, 8224, 1), (77, 2080, 3), (37, 10272, 1)])
+                                   (131, 2080, 1), (200, 4192, 1), (64, 8224, 1), (77, 2080, 3), (37, 10272, 1),
+                                   # rows of 12289 .. 32768 columns (split over the four wavefronts of a workgroup): 14, 7, 10, 13 and
+                                   # 6.75 chunks of 2048 columns, odd m, more pairs than workgroups, two rows of x
+                                   (300, 28672, 1), (131, 14336, 1), (64, 20480, 2), (37, 26624, 1), (1100, 13824, 1)])
 def test_dequant_matmul_random(rx, m, k, n):
     q, s = wl.qmat(3, m * 131 + k, m, k)
     x = wl.normal_f16_bits(3, m + k + n, (n, k))
