@@ -467,6 +467,19 @@ def test_mid_layer_prefill_and_decode_through_gemm_and_matvec(rx):
     assert_close(Vg[:, :184], Vo[:, :184], "V cache", atol=5e-3, rtol=5e-3)
 
 
+def test_wide_layer_decode_rows_through_the_long_row_matvec(rx):
+    """A layer whose attention width (112 heads x 128 = 14336) and FFN width (13824) exceed what one wavefront keeps of x: at
+    one row the output projection (fp32 residual epilogue) and the down projection (fp16 residual epilogue) run the matvec
+    that splits a row over the wavefronts of a workgroup; the attention merge is a launch of its own at that width."""
+    shape = wl.LayerShape("wide", hidden=512, n_heads=112, n_kv_heads=112, head_dim=128, ffn=13824)
+    calls = [([5], [5], None), ([1], [6], None), ([1], [7], None)]
+    outs, (Kg, Vg), (Ko, Vo) = run_schedule(rx, shape, 29, 16, calls)
+    for ci, (g, r) in enumerate(outs):
+        assert_close(g, r, "wide layer call %d" % ci)
+    assert_close(Kg[:, :7], Ko[:, :7], "K cache", atol=5e-3, rtol=5e-3)
+    assert_close(Vg[:, :7], Vo[:, :7], "V cache", atol=5e-3, rtol=5e-3)
+
+
 def test_llama7b_layer_prefill_128(rx):
     outs, _, _ = run_schedule(rx, wl.LLAMA7B, 2, 128, [([128], [128], None)])
     assert_close(*outs[0], "7B prefill n=128")
