@@ -16,6 +16,7 @@ Other workloads (--workload), same JSON schema, for the other configurations:
   batch_sweep    one 7B-shaped layer call on n decode rows against n (where the dispatch on n changes kernels).
   memory_plan    host-only: planned against unplanned bytes of the layer's intermediates (Alg. 3 of the paper).
   half_sweep     relax_half_matmul (plain fp16 weights) against n, matvec passes and tiled GEMM forced in turn: the crossover.
+  decode_shapes  one decode row (L = 2231) through one int4 layer of the 7B, 13B and 70B shapes: the same binary on three sizes.
   q3_matvec      relax_dequant_matmul_q3_native / relax_dequant_matmul_q3 (3-bit weights) at n = 1 on the four matrix shapes of the 7B layer.
 All inputs are seeded and synthetic and resident in HBM before the timed region.
 """
@@ -607,6 +608,69 @@ def bench_batch_sweep(args, np, torch, wl, rx):
           "build_id": rx.relax_build_id()}, None, None, {"batch_sweep": rows})
 
 
+# ------------------------------------------------------------------------------------------------ one decode row at three model shapes
+def bench_decode_shapes(args, np, torch, wl, rx):
+    """One decode row (n = 1, 2231 cached tokens) through one int4 layer of the 7B, 13B and 70B shapes of the paper's LLM
+    evaluation (Sec. 5.1): the same binary, the dispatch on k picks the chunk count of the matvec, the long-row kernel for
+    the down projections of 13B / 70B, the grouped-query attention kernel for 70B.  Weight codes and scales are random
+    bits made on the device (the time does not depend on them); graph replays over rotating weight sets."""
+    from paper_2311_02103_amd.runtime import DeviceLayer
+    L = 2231
+    steps = args.steps = args.steps or 10
+    args.warmup = 1 if args.warmup is None else args.warmup
+    shapes = [(wl.LLAMA7B, 8), (wl.LayerShape("llama2-13b", hidden=5120, n_heads=40, n_kv_heads=40, head_dim=128, ffn=13824), 6), (wl.LLAMA70B, 3)]
+    rs = np.random.RandomState(12)
+    rows = []
+    for shape, sets in shapes:
+        layers = []
+        for _ in range(sets):
+            w = {}
+            for name, (m, k) in shape.matrices().items():
+                w[name + ".q"] = rs.randint(0, 2 ** 31 - 1, size=(m, k // 8)).astype(np.int32)
+                w[name + ".s"] = (rs.rand(m, k // 32) * 0.004 + 0.002).astype(np.float16).view(np.uint16)
+            w["norm_attn"] = np.ones(shape.hidden, np.float16).view(np.uint16)
+            w["norm_ffn"] = np.ones(shape.hidden, np.float16).view(np.uint16)
+            lay = DeviceLayer(w, hidden=shape.hidden, n_heads=shape.n_heads, n_kv_heads=shape.n_kv_heads, head_dim=shape.head_dim,
+                              ffn=shape.ffn, kv_capacity=L, kv_slots=1, n_max=1, B_max=1)
+            lay.k.normal_()
+            lay.v.normal_()
+            layers.append(lay)
+        x = (torch.randn(1, shape.hidden, device="cuda") * 0.5).half()
+        calls = [lay.prepare(x, [1], [L]) for lay in layers]
+        st = torch.cuda.Stream()
+        with torch.cuda.stream(st):
+            for c in calls:
+                c(st.cuda_stream)
+            st.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=st):
+                for _ in range(4):
+                    for c in calls:
+                        c(st.cuda_stream)
+            for _ in range(args.warmup):
+                g.replay()
+            st.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(st)
+            for _ in range(steps):
+                g.replay()
+            e1.record(st)
+            st.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / (steps * 4 * sets)
+        nbytes = sum(m * k * (0.5 + 2 / 32) for m, k in shape.matrices().values()) + 2 * L * shape.n_kv_heads * shape.head_dim * 2
+        rows.append({"shape": shape.name, "us_per_call": round(us, 2), "algorithmic_MB": round(nbytes / 1e6, 1),
+                     "GBps": round(nbytes / us / 1e3, 1), "frac_of_hbm_peak": round(nbytes / us / 1e3 / PEAK_HBM_GBS, 4)})
+        del layers, calls, g
+        torch.cuda.empty_cache()
+    head = rows[0]
+    emit(args, "decode layer calls/s at one row (7B shape; 13B and 70B shapes in decode_shapes)", "calls/s", 1e6 / head["us_per_call"],
+         head["us_per_call"] / 1e3, "f16 (int4 weights, f32 accumulate)",
+         {"workload": "one decode row, L = %d, one int4-g32 layer of the 7B / 13B / 70B shapes, graph replays over rotating weight sets" % L,
+          "build_id": rx.relax_build_id()},
+         {"bound": "hbm", "kernel": "the five (13B) or six (70B: grouped-query attention + merge) launches of the one-row layer",
+          "achieved": head["GBps"], "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": head["frac_of_hbm_peak"], "traffic": None}, None, {"decode_shapes": rows})
+
+
 # ------------------------------------------------------------------------------------------------ fp16-weight sweep
 def bench_half_sweep(args, np, torch, wl, rx):
     """relax_half_matmul (plain fp16 weights) against the row count n on two 7B-shaped matrices, with the matvec passes and the
@@ -946,7 +1010,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=0, help="timed steps (default: 1280 decode_layer, 50 prefill_layer, 256 model_7b, 8 batched_70b)")
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", choices=["decode_layer", "prefill_layer", "model_7b", "batched_70b", "ceilings", "memory_plan", "batch_sweep", "half_sweep", "q3_matvec"],
+    ap.add_argument("--workload", choices=["decode_layer", "prefill_layer", "model_7b", "batched_70b", "ceilings", "memory_plan", "batch_sweep", "half_sweep", "q3_matvec", "decode_shapes"],
                     default="decode_layer")
     ap.add_argument("--n", type=int, default=2048, help="rows of the prefill_layer workload")
     ap.add_argument("--sweep-rows", default="", help="batch_sweep: comma-separated row counts instead of the default list (short profiling runs)")
@@ -1000,6 +1064,8 @@ def main():
         bench_half_sweep(args, np, torch, wl, rx)
     elif args.workload == "q3_matvec":
         bench_q3_matvec(args, np, torch, wl, rx)
+    elif args.workload == "decode_shapes":
+        bench_decode_shapes(args, np, torch, wl, rx)
     else:
         bench_model(args, np, torch, wl, rx, big=args.workload == "batched_70b")
 

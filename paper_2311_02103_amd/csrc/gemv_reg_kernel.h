@@ -712,7 +712,7 @@ hipError_t launch_ng(const GemvArgs &a_in, hipStream_t stream)
             return hipGetLastError();
         }
     }
-    if constexpr (XMODE != X_ATTN_MERGE && NG == 4) {
+    if constexpr (XMODE != X_ATTN_MERGE && (NG == 3 || NG == 4)) {
         if (nr == 2) {
             hipLaunchKernelGGL((gemv_q4_reg_kernel<XMODE, EPI, NG, 1, false, 2>), grid, dim3(kRThreads), 0, stream, a);
             return hipGetLastError();
@@ -729,6 +729,7 @@ hipError_t launch_xe(const GemvArgs &a, hipStream_t stream)
     const int ng = (a.k + 2047) / 2048;
     if (ng <= 1) return launch_ng<XMODE, EPI, 1, WM>(a, stream);
     if (ng == 2) return launch_ng<XMODE, EPI, 2, WM>(a, stream);
+    if (ng == 3) return launch_ng<XMODE, EPI, 3, WM>(a, stream);     // hidden 5120: no dead fourth chunk
     if (ng <= 4) return launch_ng<XMODE, EPI, 4, WM>(a, stream);
     return launch_ng<XMODE, EPI, 6, WM>(a, stream);
 }

@@ -20,6 +20,7 @@ hipError_t launch_gemv_q3w(const GemvArgs &a, int xmode, int epi, hipStream_t st
         GemvArgs b = a;
         b.part_used = a.pos0 >= 0 ? a.pos0 / a.part_chunk + 1 : 0;
         if (a.k <= 2048) return launch_ng<X_ATTN_MERGE, EPI_RESID_F32, 1, W_Q3>(b, stream);
+        if (a.k > 2 * 2048) return launch_ng<X_ATTN_MERGE, EPI_RESID_F32, 3, W_Q3>(b, stream);
         return launch_ng<X_ATTN_MERGE, EPI_RESID_F32, 2, W_Q3>(b, stream);
     }
     if (xmode == X_F16 && epi == EPI_RESID_F32) return launch_xe<X_F16, EPI_RESID_F32, W_Q3>(a, stream);

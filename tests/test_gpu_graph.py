@@ -220,3 +220,27 @@ def test_single_row_of_the_3bit_and_fp16_layers_reads_its_position_from_the_devi
     for name, a, b in zip(("out", "K row", "V row"), res[0], res[1]):
         assert torch.equal(bits(a), bits(b)), "%s differs at L=%d (%s)" % (name, L, kind)
     assert torch.isfinite(res[0][0].float()).all() and float(res[0][0].float().abs().max()) > 0
+
+
+@pytest.mark.parametrize("L", [1, 300, 512])
+def test_single_row_layer_at_hidden_5120_reads_its_position_from_the_device_table(rx, L):
+    """Hidden width of the 13B shape (three chunks of 2048 columns, the attention merge folded into a three-chunk output
+    projection): device-table call and host-descriptor call give the same bits."""
+    from paper_2311_02103_amd.runtime import DeviceLayer
+    shape, cap = wl.LayerShape("h5120", hidden=5120, n_heads=40, n_kv_heads=40, head_dim=128, ffn=1024), 512
+    layer = DeviceLayer(wl.layer_weights(shape, 41), hidden=shape.hidden, n_heads=shape.n_heads, n_kv_heads=shape.n_kv_heads,
+                        head_dim=shape.head_dim, ffn=shape.ffn, kv_capacity=cap, kv_slots=1, n_max=1, B_max=1)
+    kb, vb = wl.kv_prefill(shape, 41, 1, cap)
+    x = torch.from_numpy(wl.activations(shape, 41, L, 1).view(np.int16)).view(torch.float16).cuda()
+    res = []
+    for dev in (False, True):
+        layer.load_cache(kb, vb)
+        if dev:
+            out = layer.forward(x, [1], [cap], None, device_table=table([1], [L], [0]))
+        else:
+            out = layer.forward(x, [1], [L], None)
+        torch.cuda.synchronize()
+        res.append((out.clone(), layer.k[0, L - 1].clone(), layer.v[0, L - 1].clone()))
+    for name, a, b in zip(("out", "K row", "V row"), res[0], res[1]):
+        assert torch.equal(bits(a), bits(b)), "%s differs at L=%d" % (name, L)
+    assert torch.isfinite(res[0][0].float()).all() and float(res[0][0].float().abs().max()) > 0

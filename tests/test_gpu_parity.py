@@ -111,6 +111,7 @@ def test_integer_valued_matmul_bitwise(rx, m, k, n):
                                    (131, 2080, 1), (200, 4192, 1), (64, 8224, 1), (77, 2080, 3), (37, 10272, 1),
                                    # rows of 12289 .. 32768 columns (split over the four wavefronts of a workgroup): 14, 7, 10, 13 and
                                    # 6.75 chunks of 2048 columns, odd m, more pairs than workgroups, two rows of x
+                                   (300, 5120, 1), (77, 6144, 3), (41, 4128, 2),      # three chunks of 2048 columns
                                    (300, 28672, 1), (131, 14336, 1), (64, 20480, 2), (37, 26624, 1), (1100, 13824, 1)])
 def test_dequant_matmul_random(rx, m, k, n):
     q, s = wl.qmat(3, m * 131 + k, m, k)
@@ -348,10 +349,13 @@ def test_llama7b_layer_prefill_17(rx):
 # ------------------------------------------------------------------------- one decode row over a pre-filled cache, more shapes
 FAST_SMALL = wl.LayerShape("small-fast", hidden=256, n_heads=4, n_kv_heads=2, head_dim=64, ffn=704)
 FAST_MID = wl.LayerShape("mid-fast", hidden=2048, n_heads=16, n_kv_heads=16, head_dim=128, ffn=5632)
+# hidden width of the 13B shape (5120 = 2.5 chunks of 2048 columns: the three-chunk variants, attention merge folded in), small FFN
+H5120 = wl.LayerShape("h5120", hidden=5120, n_heads=40, n_kv_heads=40, head_dim=128, ffn=1024)
 
 
 @pytest.mark.parametrize("shape,cap,Ls", [(FAST_SMALL, 600, [1, 2, 63, 64, 65, 130, 600]),
                                           (FAST_MID, 2100, [1, 777, 2100]),
+                                          (H5120, 700, [1, 64, 449, 700]),
                                           (wl.LLAMA7B, 4096, [2, 2048, 4095])])
 def test_one_decode_row_over_a_prefilled_cache(rx, shape, cap, Ls):
     pre = wl.kv_prefill(shape, 11, 1, cap)
