@@ -118,3 +118,11 @@ def test_gpu_layer_7b_shape_decode_rows(rx):
     into the output projection): a short prefill, then two decode rows."""
     calls = [([6], [6], None), ([1], [7], None), ([1], [8], None)]
     run_schedule(rx, wl.LLAMA7B, 19, 64, calls)
+
+
+@pytest.mark.gpu
+def test_gpu_layer_hidden_5120_decode_rows(rx):
+    """Hidden width of the 13B shape (2.5 chunks of 2048 columns: the three-chunk variants of the fused one-row path; the
+    attention merge stays a launch of its own at that width on fp16 weights): a short prefill, then two decode rows."""
+    shape = wl.LayerShape("f16-h5120", hidden=5120, n_heads=40, n_kv_heads=40, head_dim=128, ffn=1024)
+    run_schedule(rx, shape, 23, 32, [([4], [4], None), ([1], [5], None), ([1], [6], None)])
