@@ -22,9 +22,9 @@ extern "C" {
  * "gemm_waves_per_simd" (default 2): the 256 x 256 tile of the tiled GEMM runs as eight wavefronts (two per SIMD) or, with 1,
  * as four (one per SIMD); identical results.
  * "layer_matvec_rows" (default 4, 1 .. 64): relax_decoder_layer and relax_model_step keep a call of up to this many rows on
- * the matrix-vector kernels (two or four rows of x share one pass over the weights) when every matrix of the layer is at most
- * 64 MB -- a model that mostly stays in the last-level cache; above it, and on larger models from two rows on, the few-row
- * matrix path takes the call.  1: matrix path from two rows on.
+ * the matrix-vector kernels (two or four rows of x share one pass over the weights): two rows on every model, more when
+ * every matrix of the layer is at most "layer_matvec_mb" MB of packed codes (default 64, 0 .. 4096) -- a model that mostly
+ * stays in the last-level cache; above it the few-row matrix path takes the call.  1: matrix path from two rows on.
  * "half_matmul_gemm_rows" (default 0): relax_half_matmul takes the tiled GEMM from this many rows on; 0: by estimate.
  * Unknown name: RELAX_ERR_UNSUPPORTED.                                                                           */
 relax_status relax_set_option(const char *name, int32_t value);

@@ -265,6 +265,7 @@ struct StepTimer {
 // design -- they exist for A/B tests of one process -- and atomic, so setting one while another thread is inside a call is
 // defined: that call sees the old or the new value.  Neither changes a result.
 std::atomic<int> g_opt_fuse_finish{1};       // few-row path: light steps folded into the finishing pass of the split-K matmuls
+std::atomic<int> g_opt_matvec_mb{64};        // ... and the size of the largest matrix (MB of packed codes) up to which that holds for more than two rows
 std::atomic<int> g_opt_matvec_rows{4};       // relax_decoder_layer on a model whose matrices fit the last-level cache: rows up to which the matvec kernels take the call
 std::atomic<int> g_opt_half_gemm_rows{0};    // relax_half_matmul: rows from which the tiled GEMM replaces the matvec passes; 0: by estimate
 std::atomic<const uint32_t *> g_prof_alt_q{nullptr};      // relax_profile_alt_gate_up: another matrix of the gate/up shape
@@ -369,6 +370,11 @@ relax_status relax_set_option(const char *name, int32_t value)
     if (std::strcmp(name, "layer_matvec_rows") == 0) {
         if (value < 1 || value > 64) return RELAX_ERR_SHAPE;
         g_opt_matvec_rows.store(value);
+        return RELAX_OK;
+    }
+    if (std::strcmp(name, "layer_matvec_mb") == 0) {
+        if (value < 0 || value > 4096) return RELAX_ERR_SHAPE;
+        g_opt_matvec_mb.store(value);
         return RELAX_OK;
     }
     if (std::strcmp(name, "half_matmul_gemm_rows") == 0) {
@@ -638,11 +644,13 @@ relax_status layer_enqueue(const relax_layer_dims &dm, const relax_layer_weights
     // Up to four rows of a small model stay on the matvec kernels: two or four rows of x share one pass over the weights
     // (k <= 4096: four, k <= 8192: two; taller rows go one by one and find most of a matrix of this size in the last-level
     // cache), and the matvec path needs no separate norm / finishing launches.  Measured on the 7B layer shape, 256 cached
-    // tokens: 46 against 75 us at two rows, 64 against 77 at three, 62 against 75 at four, 92 against 76 at five; on the 70B
-    // shape, whose matrices do not fit, the matrix path is 3 to 5 times faster from two rows on.
+    // tokens: 46 against 75 us at two rows, 64 against 77 at three, 62 against 75 at four, 92 against 76 at five.
     const size_t largest = std::max(std::max((size_t)wt->wqkv.m * wt->wqkv.k, (size_t)wt->wo.m * wt->wo.k),
                                     std::max((size_t)wt->wgu.m * wt->wgu.k, (size_t)wt->wdown.m * wt->wdown.k)) / 2;
-    const bool rows_as_matvecs = n >= 2 && n <= g_opt_matvec_rows.load() && largest <= ((size_t)64 << 20);
+    // Two rows share one pass over the weights on every model size (measured per layer at L = 512: 13B shape 65 against 90 us on
+    // the matrix path, 70B shape 112 against 167 us); three and four rows need a second pass where a lane cannot hold four rows
+    // of x, which pays only while the matrices mostly stay in the last-level cache (13B: 94 against 92 us, 70B: 178 against 155).
+    const bool rows_as_matvecs = n >= 2 && n <= g_opt_matvec_rows.load() && (n == 2 || largest <= ((size_t)g_opt_matvec_mb.load() << 20));
     if (n >= kSkinnyMinN && !rows_as_matvecs && mat_ok(wt->wqkv, x, EPI_F16) && mat_ok(wt->wo, x, EPI_RESID_F32) && mat_ok(wt->wgu, x, EPI_SWIGLU) &&
         mat_ok(wt->wdown, x, EPI_RESID_F16)) {
         uint16_t *xn = reinterpret_cast<uint16_t *>(base + pl.xn), *qkv = reinterpret_cast<uint16_t *>(base + pl.qkv);

@@ -86,7 +86,9 @@ def test_70b_shape_ragged_calls_against_the_oracle(rx):
              ([1, 1, 1, 1], [1789, 1383, 307, 1125], [1, 0, 2, 4]),            # few-row kernel, grouped-query decode attention
              ([1, 23, 1, 16], [563, 1005, 568, 16], [4, 0, 2, 1]),             # few-row kernel, mixed rows
              ([115, 103, 178, 102], [1604, 163, 745, 793], [4, 1, 0, 3]),      # tiled GEMM, chunked prefills
-             ([241, 199, 128], [241, 2048, 128], [3, 1, 2])]                   # tiled GEMM, fresh prefills and a full cache
+             ([241, 199, 128], [241, 2048, 128], [3, 1, 2]),                   # tiled GEMM, fresh prefills and a full cache
+             ([1, 1], [907, 1466], [2, 0]),                                    # two decode rows: matvec kernels, two rows of x per pass
+             ([1, 1], [33, 2048], [1, 4])]                                     # the same through the device table
     for it, (q, kv, sl) in enumerate(calls):
         n, B = sum(q), len(q)
         layer.load_cache(kb, vb)
