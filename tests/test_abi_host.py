@@ -200,6 +200,14 @@ def test_half_matmul_checks():
     assert rx.relax_set_option("half_matmul_gemm_rows", -1) == rx.ERR_SHAPE
 
 
+def test_dispatch_options_check_their_ranges():
+    for name, bad, good in (("layer_matvec_rows", (0, 65), 4), ("layer_matvec_mb", (-1, 4097), 64)):
+        for v in bad:
+            assert rx.relax_set_option(name, v) == rx.ERR_SHAPE
+        assert rx.relax_set_option(name, good) == rx.OK
+    assert rx.relax_set_option("no_such_option", 1) == rx.ERR_UNSUPPORTED
+
+
 def test_no_product_module_touches_the_oracle():
     pkg = os.path.join(ROOT, "paper_2311_02103_amd")
     for dirpath, _, files in os.walk(pkg):
