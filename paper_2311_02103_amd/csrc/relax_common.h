@@ -344,11 +344,11 @@ __device__ __forceinline__ void q3n_decode(uint32_t w0, uint32_t w1, uint32_t w2
 }
 
 
-// weight stream of the register-resident matvec kernel (gemv_q4_reg.hip)
+// weight stream of the register-resident matvec kernel (gemv_reg_kernel.h)
 enum { W_Q4 = 0, W_F16 = 1, W_Q3 = 2 };
 
 hipError_t launch_gemv(const GemvArgs &a, int xmode, int epi, hipStream_t stream);
-// x-in-registers variant for rows of up to 6 x 2048 columns (gemv_q4_reg.hip); launch_gemv picks it when eligible
+// x-in-registers variant for rows of up to 6 x 2048 columns (gemv_reg_kernel.h, launchers in gemv_q4_reg.hip); launch_gemv picks it when eligible
 bool gemv_reg_eligible(const GemvArgs &a);
 bool gemv_merge_eligible(const GemvArgs &a);
 hipError_t launch_gemv_reg(const GemvArgs &a, int xmode, int epi, hipStream_t stream);
