@@ -441,8 +441,9 @@ __global__ __launch_bounds__(kSThreads) void gemv_q4_stream_kernel(GemvArgs a)
 template <int XMODE, int EPI>
 static hipError_t launch_t(const GemvArgs &a, hipStream_t stream)
 {
+    // rows of 12289 .. 28672 columns behind a plain prologue, and from two rows of x on rows of 8193 columns up (several rows of x per pass)
+    if (gemv_long_eligible(a, XMODE, EPI)) return launch_gemv_long(a, EPI, stream);
     if (gemv_reg_eligible(a)) return launch_gemv_reg(a, XMODE, EPI, stream);
-    if (gemv_long_eligible(a, XMODE, EPI)) return launch_gemv_long(a, EPI, stream);     // rows of 12289 .. 32768 columns, plain prologue
     const int k = a.k, G = groups_of(k);
     const bool fast = (k % kGroup == 0) && ((k / 8) % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.q) & 15) == 0) &&
                       ((reinterpret_cast<uintptr_t>(a.x) & 15) == 0) && ((reinterpret_cast<uintptr_t>(a.norm_w) & 15) == 0);
