@@ -23,7 +23,7 @@ extern "C" {
  * as four (one per SIMD); identical results.
  * "layer_matvec_rows" (default 4, 1 .. 64): relax_decoder_layer and relax_model_step keep a call of up to this many rows on
  * the matrix-vector kernels (two or four rows of x share one pass over the weights): two rows on every model, more when
- * every matrix of the layer is at most "layer_matvec_mb" MB of packed codes (default 64, 0 .. 4096) -- a model that mostly
+ * every matrix of the layer is at most "layer_matvec_mb" MB of packed codes (default 96, 0 .. 4096) -- a model that mostly
  * stays in the last-level cache; above it the few-row matrix path takes the call.  1: matrix path from two rows on.
  * "half_matmul_gemm_rows" (default 0): relax_half_matmul takes the tiled GEMM from this many rows on; 0: by estimate.
  * Unknown name: RELAX_ERR_UNSUPPORTED.                                                                           */

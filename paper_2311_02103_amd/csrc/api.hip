@@ -265,7 +265,7 @@ struct StepTimer {
 // design -- they exist for A/B tests of one process -- and atomic, so setting one while another thread is inside a call is
 // defined: that call sees the old or the new value.  Neither changes a result.
 std::atomic<int> g_opt_fuse_finish{1};       // few-row path: light steps folded into the finishing pass of the split-K matmuls
-std::atomic<int> g_opt_matvec_mb{64};        // ... and the size of the largest matrix (MB of packed codes) up to which that holds for more than two rows
+std::atomic<int> g_opt_matvec_mb{96};        // ... and the size of the largest matrix (MB of packed codes) up to which that holds for more than two rows
 std::atomic<int> g_opt_matvec_rows{4};       // relax_decoder_layer on a model whose matrices fit the last-level cache: rows up to which the matvec kernels take the call
 std::atomic<int> g_opt_half_gemm_rows{0};    // relax_half_matmul: rows from which the tiled GEMM replaces the matvec passes; 0: by estimate
 std::atomic<const uint32_t *> g_prof_alt_q{nullptr};      // relax_profile_alt_gate_up: another matrix of the gate/up shape

@@ -201,7 +201,7 @@ def test_half_matmul_checks():
 
 
 def test_dispatch_options_check_their_ranges():
-    for name, bad, good in (("layer_matvec_rows", (0, 65), 4), ("layer_matvec_mb", (-1, 4097), 64)):
+    for name, bad, good in (("layer_matvec_rows", (0, 65), 4), ("layer_matvec_mb", (-1, 4097), 96)):
         for v in bad:
             assert rx.relax_set_option(name, v) == rx.ERR_SHAPE
         assert rx.relax_set_option(name, good) == rx.OK

@@ -489,6 +489,22 @@ def test_llama7b_layer_prefill_128(rx):
     assert_close(*outs[0], "7B prefill n=128")
 
 
+def test_13b_width_layer_two_to_four_decode_rows_on_the_matvec_kernels(rx):
+    """Hidden 5120 and FFN 13824 (the 13B widths, fewer heads' worth of rows would not change the kernels): two to four decode
+    rows through the three-chunk matvec variants (two rows of x per pass) and the long-row kernel (two and four rows per pass)."""
+    shape = wl.LayerShape("w13b", hidden=5120, n_heads=40, n_kv_heads=40, head_dim=128, ffn=13824)
+    past = [int(v) for v in wl.uniform_lengths(43, 4, 1, 40)]
+    kb, vb = wl.kv_prefill(shape, 43, 4, 48)
+    calls = [([1, 1], [past[0] + 1, past[1] + 1], [0, 1]),
+             ([1, 1, 1], [past[2] + 1, past[0] + 2, past[3] + 1], [2, 0, 3]),
+             ([1, 1, 1, 1], [past[1] + 2, past[3] + 2, past[2] + 2, past[0] + 3], [1, 3, 2, 0])]
+    outs, (Kg, Vg), (Ko, Vo) = run_schedule(rx, shape, 43, 48, calls, slots=4, prefill_bits=(kb, vb))
+    for ci, (g, r) in enumerate(outs):
+        assert_close(g, r, "13B-width layer, %d decode rows" % (ci + 2))
+    assert_close(Kg, Ko, "K cache", atol=5e-3, rtol=5e-3)
+    assert_close(Vg, Vo, "V cache", atol=5e-3, rtol=5e-3)
+
+
 @pytest.mark.parametrize("matvec_rows", [1, 4])
 def test_llama7b_layer_two_to_five_decode_rows_on_both_paths(rx, matvec_rows):
     """Batches of two to five decode rows of the 7B-shaped layer through the matvec kernels with several rows per pass
